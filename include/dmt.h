@@ -1,0 +1,223 @@
+/*
+ * dmt.h - C ABI of libdmt: one GPU's share of the tower-decomposed sparse step
+ * of Disaggregated Multi-Tower (DMT, arXiv 2403.00877), for AMD MI355X (gfx950).
+ *
+ * The library runs three operations, each as hand-written HIP kernels:
+ *   dmt_tower_lookup_fwd         tower-local sum-pooled embedding lookup whose
+ *                                store already has the layout SPTT's steps c-e
+ *                                produce (paper Sec. 2.2 step b, Sec. 3.1.1)
+ *   dmt_tower_module_fwd         the per-tower Tower Module that shrinks that
+ *                                payload (paper Sec. 3.2, Sec. 4 Listings 1-2)
+ *   dmt_tower_lookup_bwd_update  gradients to the activated rows only (paper
+ *                                Sec. 2.2): stable sort by row id, segment
+ *                                reduce, one deterministic rowwise-Adagrad
+ *                                write per row
+ *
+ * Conventions
+ *  - C linkage, no exceptions cross the boundary; every call returns dmt_status.
+ *  - "dev" pointers are device memory owned by the CALLER (e.g. PyTorch
+ *    tensors); "host" pointers are ordinary host memory, read during the call
+ *    only.  The library owns nothing but the plan object and the small device
+ *    tables dmt_plan_bind creates.
+ *  - The three dmt_tower_* calls validate on the host first (null pointers,
+ *    sizes against the plan, supported dtypes / widths) and return
+ *    DMT_EINVAL / DMT_ENOTSUP without launching anything; then they enqueue
+ *    kernels on `stream` (a hipStream_t, NULL = default stream) and return
+ *    without synchronising or allocating.  Scratch memory is the caller's
+ *    `workspace`, sized by the dmt_*_workspace_bytes functions.
+ *  - Ids out of range [0, rows_f) are never dereferenced: the kernels skip them
+ *    and record the smallest offending position; dmt_last_device_error
+ *    synchronises the stream and reports it as DMT_EBOUNDS.
+ *  - Jagged input is feature-major CSR: bag (f, b) of table f and sample b owns
+ *    indices[offsets[f*B + b] .. offsets[f*B + b + 1]); offsets has
+ *    num_tables*B + 1 entries, offsets[0] = 0, offsets[num_tables*B] = nnz.
+ *  - Tower-major pooled layout: towers one after another, each a row-major
+ *    [B][W_t] block, W_t = sum of the dims of the tower's tables; inside a row
+ *    the tables appear in ascending table id.  With equal dims N this is the
+ *    paper's `embs` of shape (B, |F|, N) per tower (Sec. 4).
+ *  - Calls that share a plan, a workspace or tables must be ordered by the
+ *    caller (same stream, or events).
+ */
+#ifndef DMT_H_
+#define DMT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DMT_OK = 0,
+  DMT_EINVAL = 1,   /* bad argument (null, negative, exceeds the plan's maxima) */
+  DMT_ENOTSUP = 2,  /* valid but not supported by these kernels                 */
+  DMT_EBOUNDS = 3,  /* an id outside its table was seen on the device           */
+  DMT_ENOMEM = 4,   /* host allocation failed / workspace too small             */
+  DMT_EHIP = 5      /* a HIP runtime call failed                                */
+} dmt_status;
+
+typedef enum { DMT_F32 = 0, DMT_F16 = 1, DMT_BF16 = 2 } dmt_dtype;
+
+typedef enum {
+  DMT_TM_LINEAR = 0,       /* y = W x + b            (Listing 1 with c = 0)                      */
+  DMT_TM_LINEAR_RELU = 1,  /* y = max(0, W x + b)                                                 */
+  DMT_TM_DOT_LINEAR = 2,   /* z = [pairwise dots (i<j) | x], y = W z + b  (Sec. 3.2, Sec. 4)      */
+  DMT_TM_CROSS_LINEAR = 3  /* x_{l+1} = x0 * (W_l x_l + b_l) + x_l, y = W x_L + b  (Listing 2)    */
+} dmt_tm_kind;
+
+#define DMT_MAX_CROSS_LAYERS 4
+#define DMT_MAX_TOWERS 64
+#define DMT_MAX_TABLES 4096
+
+typedef struct dmt_plan dmt_plan; /* opaque, library-owned */
+
+/* Human-readable name of a status code (static string). */
+const char* dmt_status_str(dmt_status s);
+
+/*
+ * Describe the model's sparse side (paper Sec. 2.1: one table per sparse
+ * feature; Sec. 3.1: features pre-partitioned into towers).  Host-only: no
+ * device is touched.
+ *   rows, dims       host [num_tables]: rows and embedding dim of each table.
+ *                    dims[f] * sizeof(element) must be a multiple of 16 bytes
+ *                    and at most 1024 bytes.
+ *   table_dtype      element type of every table.
+ *   table_to_tower   host [num_tables], values in [0, num_towers); every tower
+ *                    needs at least one table.  A table's slot inside its tower
+ *                    is its rank among the tower's tables by ascending id.
+ *   max_batch, max_nnz  upper bounds later calls are checked against.
+ * The sum of all rows must stay below 2^32 (rows are numbered globally inside
+ * the backward sort).
+ */
+dmt_status dmt_plan_create(dmt_plan** out, int32_t num_tables, const int64_t* rows,
+                           const int32_t* dims, dmt_dtype table_dtype, int32_t num_towers,
+                           const int32_t* table_to_tower, int64_t max_batch, int64_t max_nnz);
+
+void dmt_plan_destroy(dmt_plan* plan);
+
+/*
+ * Element offsets of the tower-major pooled tensor for batch size B (host-only):
+ *   tower_base  host out [num_towers + 1]: first element of each tower's block;
+ *               tower_base[num_towers] is the tensor's total element count
+ *   tower_width host out [num_towers]: W_t
+ *   col_off     host out [num_tables]: first column of each table inside its
+ *               tower's rows
+ * Any output pointer may be NULL.
+ */
+dmt_status dmt_plan_layout(const dmt_plan* plan, int64_t B, int64_t* tower_base,
+                           int32_t* tower_width, int32_t* col_off);
+
+/*
+ * Attach the tables (and optionally the optimizer state) and upload the plan's
+ * small lookup tables to the current device.  Synchronous; call once before
+ * the dmt_tower_* calls and again whenever a pointer changes.
+ *   tables  host [num_tables] of dev pointers; table f is row-major
+ *           [rows[f]][dims[f]] of table_dtype, 16-byte aligned, row stride
+ *           dims[f] elements.
+ *   adagrad_state  host [num_tables] of dev float pointers ([rows[f]] each), or
+ *           NULL when the backward is not used.
+ */
+dmt_status dmt_plan_bind(dmt_plan* plan, const void* const* tables, float* const* adagrad_state);
+
+/*
+ * Tower-local pooled lookup, forward (paper Sec. 2.2 step b with the layout of
+ * Sec. 3.1.1 steps c-e fused into the store).
+ *   pooled_out[tower_base[t] + b*W_t + col_off[f] + d]
+ *        = sum over j in bag (f, b) of table_f[indices[j]][d]
+ * accumulated in float32, rounded once to out_dtype.  An empty bag gives
+ * zeros; an id occurring twice in a bag is added twice.
+ *   indices  dev int32 [nnz]; offsets dev int64 [num_tables*B + 1]
+ *   pooled_out dev, tower_base[num_towers] elements of out_dtype, 16-byte aligned
+ */
+dmt_status dmt_tower_lookup_fwd(const dmt_plan* plan, const int32_t* indices,
+                                const int64_t* offsets, int64_t B, int64_t nnz,
+                                void* pooled_out, dmt_dtype out_dtype, void* stream);
+
+/*
+ * Per-tower Tower-Module parameters (paper Sec. 4).  All weights are dev
+ * pointers of the dtype passed to dmt_tower_module_fwd, row-major [out][in];
+ * biases are dev [out] of the same dtype.
+ *   LINEAR / LINEAR_RELU : w_proj [out_dim][W_t]
+ *   DOT_LINEAR  : the tower's tables must share one dim n; with nf tables the
+ *                 projection input is [nf(nf-1)/2 dots, (i,j) row-major, i<j |
+ *                 the W_t pooled values]; w_proj [out_dim][nf(nf-1)/2 + W_t]
+ *   CROSS_LINEAR: num_cross_layers full-rank layers w_cross[l] [W_t][W_t],
+ *                 b_cross[l] [W_t], then w_proj [out_dim][W_t]
+ */
+typedef struct {
+  int32_t kind;              /* dmt_tm_kind */
+  int32_t out_dim;           /* O_t */
+  int32_t num_cross_layers;  /* CROSS_LINEAR only, <= DMT_MAX_CROSS_LAYERS */
+  int32_t reserved;
+  const void* w_proj;
+  const void* b_proj;
+  const void* w_cross[DMT_MAX_CROSS_LAYERS];
+  const void* b_cross[DMT_MAX_CROSS_LAYERS];
+} dmt_tm_params;
+
+/* Bytes of scratch dmt_tower_module_fwd needs for these towers at batch B
+ * (0 is possible).  Host-only. */
+size_t dmt_tm_workspace_bytes(const dmt_plan* plan, const dmt_tm_params* per_tower, int64_t B);
+
+/*
+ * Tower Module forward (paper Sec. 3.2: D = TM(V) with |D| < |V|, applied to
+ * what step e leaves on the GPU).  For every tower t:
+ *   tm_out block t = TM_t(pooled block t), row-major [B][O_t], towers one after
+ *   another (block t starts at element B * sum_{t' < t} O_t').
+ * dtype is the type of pooled, weights, biases and tm_out alike: DMT_BF16 /
+ * DMT_F16 run on MFMA with float32 accumulation (cross-layer intermediates are
+ * kept in that 16-bit type); DMT_F32 runs in plain float32 arithmetic.
+ *   per_tower  host [num_towers]
+ *   workspace  dev, at least dmt_tm_workspace_bytes, 256-byte aligned (may be
+ *              NULL when that is 0)
+ */
+dmt_status dmt_tower_module_fwd(const dmt_plan* plan, const dmt_tm_params* per_tower,
+                                const void* pooled, int64_t B, void* tm_out, dmt_dtype dtype,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/* Optional outputs of the backward's integer stages, for parity checks.  Any
+ * pointer may be NULL.  All dev. */
+typedef struct {
+  int64_t* sorted_keys;  /* [nnz]  (table << 32 | row), ascending, stable           */
+  int32_t* sorted_bag;   /* [nnz]  bag id f*B + b of each sorted lookup              */
+  int64_t* unique_keys;  /* [nnz]  first num_unique entries valid                    */
+  int64_t* seg_off;      /* [nnz + 1] run starts; seg_off[num_unique] = nnz          */
+  int64_t* num_unique;   /* [1]                                                      */
+} dmt_bwd_debug;
+
+/* Bytes of scratch dmt_tower_lookup_bwd_update needs for (B, nnz).  Host-only. */
+size_t dmt_bwd_workspace_bytes(const dmt_plan* plan, int64_t B, int64_t nnz);
+
+/*
+ * Backward of the pooled lookup fused with a rowwise-Adagrad step on the
+ * activated rows (paper Sec. 2.2: only the rows a batch touched receive
+ * gradients).  For every distinct (table f, row r) among the lookups:
+ *   G      = sum over all lookups of (f, r) of grad_pooled[bag's slice]   (float32,
+ *            fixed order: ascending bag, so results repeat bit for bit)
+ *   state[f][r] += mean_d(G[d]^2)
+ *   table_f[r][d] -= lr * G[d] / (sqrt(state[f][r]) + eps)   (rounded once to the
+ *            table dtype, one writer per row, no atomics)
+ * Rows no lookup touched, and their states, are not written.
+ *   grad_pooled  dev float32, tower-major like pooled_out
+ *   workspace    dev, at least dmt_bwd_workspace_bytes(plan, B, nnz), 256-byte aligned
+ *   dbg          NULL or where to export the sorted / deduplicated keys
+ * Requires dmt_plan_bind with a non-NULL adagrad_state.
+ */
+dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const int32_t* indices,
+                                       const int64_t* offsets, int64_t B, int64_t nnz,
+                                       const float* grad_pooled, float lr, float eps,
+                                       void* workspace, size_t workspace_bytes, void* stream,
+                                       const dmt_bwd_debug* dbg);
+
+/*
+ * Synchronise `stream` and report whether any kernel since the last call saw an
+ * id outside its table: DMT_EBOUNDS with *bad_position = smallest offending
+ * position in `indices`, else DMT_OK with *bad_position = -1.  Clears the record.
+ */
+dmt_status dmt_last_device_error(const dmt_plan* plan, void* stream, int64_t* bad_position);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DMT_H_ */

@@ -1,0 +1,9 @@
+"""MI355X-native tower hot path of Disaggregated Multi-Tower (arXiv 2403.00877).
+
+`binding` mirrors the C ABI of libdmt.so (include/dmt.h) one to one.
+"""
+from .binding import (  # noqa: F401
+    DmtError, dmt_plan, dmt_plan_create, dmt_plan_layout, dmt_plan_bind,
+    dmt_tower_lookup_fwd, make_tm_params, dmt_tm_workspace_bytes, dmt_tower_module_fwd,
+    dmt_bwd_workspace_bytes, dmt_tower_lookup_bwd_update, dmt_last_device_error,
+    status_str, library_path)

@@ -1,0 +1,217 @@
+"""ctypes binding of libdmt.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (include/dmt.h)
+and does nothing but turn torch tensors into pointers and sizes.  All
+arithmetic of the path runs in the library's HIP kernels.  There is no
+fallback: if the library cannot be loaded the import of this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+from . import build as _build
+
+DMT_OK, DMT_EINVAL, DMT_ENOTSUP, DMT_EBOUNDS, DMT_ENOMEM, DMT_EHIP = range(6)
+DMT_F32, DMT_F16, DMT_BF16 = 0, 1, 2
+DMT_TM_LINEAR, DMT_TM_LINEAR_RELU, DMT_TM_DOT_LINEAR, DMT_TM_CROSS_LINEAR = 0, 1, 2, 3
+DMT_MAX_CROSS_LAYERS = 4
+
+DTYPE_CODE = {"f32": DMT_F32, "f16": DMT_F16, "bf16": DMT_BF16,
+              torch.float32: DMT_F32, torch.float16: DMT_F16, torch.bfloat16: DMT_BF16}
+TORCH_DTYPE = {DMT_F32: torch.float32, DMT_F16: torch.float16, DMT_BF16: torch.bfloat16}
+TM_KIND_CODE = {"linear": DMT_TM_LINEAR, "linear_relu": DMT_TM_LINEAR_RELU,
+                "dot_linear": DMT_TM_DOT_LINEAR, "cross_linear": DMT_TM_CROSS_LINEAR}
+
+
+class dmt_tm_params(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("out_dim", ctypes.c_int32),
+                ("num_cross_layers", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("w_proj", ctypes.c_void_p), ("b_proj", ctypes.c_void_p),
+                ("w_cross", ctypes.c_void_p * DMT_MAX_CROSS_LAYERS),
+                ("b_cross", ctypes.c_void_p * DMT_MAX_CROSS_LAYERS)]
+
+
+class dmt_bwd_debug(ctypes.Structure):
+    _fields_ = [("sorted_keys", ctypes.c_void_p), ("sorted_bag", ctypes.c_void_p),
+                ("unique_keys", ctypes.c_void_p), ("seg_off", ctypes.c_void_p),
+                ("num_unique", ctypes.c_void_p)]
+
+
+class DmtError(RuntimeError):
+    def __init__(self, where: str, code: int):
+        self.code = code
+        super().__init__("%s failed: %s" % (where, status_str(code)))
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(_build.LIB):
+        _build.build()          # raises if hipcc is missing or the build fails
+    lib = ctypes.CDLL(_build.LIB)
+    vp, i32, i64, f32, sz = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float,
+                             ctypes.c_size_t)
+    lib.dmt_status_str.restype = ctypes.c_char_p
+    lib.dmt_status_str.argtypes = [ctypes.c_int]
+    lib.dmt_plan_create.argtypes = [ctypes.POINTER(vp), i32, vp, vp, ctypes.c_int, i32, vp, i64, i64]
+    lib.dmt_plan_destroy.argtypes = [vp]
+    lib.dmt_plan_destroy.restype = None
+    lib.dmt_plan_layout.argtypes = [vp, i64, vp, vp, vp]
+    lib.dmt_plan_bind.argtypes = [vp, vp, vp]
+    lib.dmt_tower_lookup_fwd.argtypes = [vp, vp, vp, i64, i64, vp, ctypes.c_int, vp]
+    lib.dmt_tm_workspace_bytes.argtypes = [vp, vp, i64]
+    lib.dmt_tm_workspace_bytes.restype = sz
+    lib.dmt_tower_module_fwd.argtypes = [vp, vp, vp, i64, vp, ctypes.c_int, vp, sz, vp]
+    lib.dmt_bwd_workspace_bytes.argtypes = [vp, i64, i64]
+    lib.dmt_bwd_workspace_bytes.restype = sz
+    lib.dmt_tower_lookup_bwd_update.argtypes = [vp, vp, vp, i64, i64, vp, f32, f32, vp, sz, vp, vp]
+    lib.dmt_last_device_error.argtypes = [vp, vp, ctypes.POINTER(i64)]
+    return lib
+
+
+_lib = _load()
+
+EXPORTS = ["dmt_status_str", "dmt_plan_create", "dmt_plan_destroy", "dmt_plan_layout",
+           "dmt_plan_bind", "dmt_tower_lookup_fwd", "dmt_tm_workspace_bytes",
+           "dmt_tower_module_fwd", "dmt_bwd_workspace_bytes", "dmt_tower_lookup_bwd_update",
+           "dmt_last_device_error"]
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def status_str(code: int) -> str:
+    return _lib.dmt_status_str(int(code)).decode()
+
+
+def _check(where: str, code: int) -> None:
+    if code != DMT_OK:
+        raise DmtError(where, code)
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+class dmt_plan:
+    """Owner of a C `dmt_plan*`."""
+
+    def __init__(self, rows: Sequence[int], dims: Sequence[int], table_dtype, num_towers: int,
+                 table_to_tower: Sequence[int], max_batch: int, max_nnz: int):
+        self.num_tables = len(rows)
+        self.num_towers = int(num_towers)
+        self.table_dtype = DTYPE_CODE[table_dtype]
+        r = (ctypes.c_int64 * len(rows))(*rows)
+        d = (ctypes.c_int32 * len(dims))(*dims)
+        t = (ctypes.c_int32 * len(table_to_tower))(*table_to_tower)
+        h = ctypes.c_void_p()
+        self._h = None
+        _check("dmt_plan_create", _lib.dmt_plan_create(
+            ctypes.byref(h), len(rows), r, d, self.table_dtype, num_towers, t, max_batch, max_nnz))
+        self._h = h
+        self._keep = None
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            _lib.dmt_plan_destroy(self._h)
+            self._h = None
+
+    @property
+    def handle(self):
+        return self._h
+
+
+def dmt_plan_create(rows, dims, table_dtype, num_towers, table_to_tower, max_batch, max_nnz) -> dmt_plan:
+    return dmt_plan(rows, dims, table_dtype, num_towers, table_to_tower, max_batch, max_nnz)
+
+
+def dmt_plan_layout(plan: dmt_plan, B: int):
+    """(tower_base [T+1], tower_width [T], col_off [F]) as Python lists."""
+    tb = (ctypes.c_int64 * (plan.num_towers + 1))()
+    tw = (ctypes.c_int32 * plan.num_towers)()
+    co = (ctypes.c_int32 * plan.num_tables)()
+    _check("dmt_plan_layout", _lib.dmt_plan_layout(plan.handle, B, tb, tw, co))
+    return list(tb), list(tw), list(co)
+
+
+def dmt_plan_bind(plan: dmt_plan, tables: Sequence[torch.Tensor],
+                  adagrad_state: Optional[Sequence[torch.Tensor]] = None) -> None:
+    tp = (ctypes.c_void_p * len(tables))(*[t.data_ptr() for t in tables])
+    sp = None
+    if adagrad_state is not None:
+        sp = (ctypes.c_void_p * len(adagrad_state))(*[t.data_ptr() for t in adagrad_state])
+    _check("dmt_plan_bind", _lib.dmt_plan_bind(plan.handle, tp, sp))
+    plan._keep = (list(tables), None if adagrad_state is None else list(adagrad_state))
+
+
+def dmt_tower_lookup_fwd(plan: dmt_plan, indices: torch.Tensor, offsets: torch.Tensor, B: int,
+                         pooled_out: torch.Tensor, stream=None) -> None:
+    _check("dmt_tower_lookup_fwd", _lib.dmt_tower_lookup_fwd(
+        plan.handle, _ptr(indices), _ptr(offsets), B, indices.numel(), _ptr(pooled_out),
+        DTYPE_CODE[pooled_out.dtype], _stream(stream)))
+
+
+def make_tm_params(per_tower: Sequence[dict]):
+    """per_tower: dicts with kind (str), out_dim, w_proj, b_proj and optionally
+    w_cross / b_cross (lists of tensors).  Returns a ctypes array."""
+    arr = (dmt_tm_params * len(per_tower))()
+    for a, p in zip(arr, per_tower):
+        a.kind = TM_KIND_CODE[p["kind"]]
+        a.out_dim = int(p["out_dim"])
+        wc = p.get("w_cross") or []
+        a.num_cross_layers = len(wc)
+        a.w_proj = p["w_proj"].data_ptr()
+        a.b_proj = p["b_proj"].data_ptr()
+        for l, (w, b) in enumerate(zip(wc, p.get("b_cross") or [])):
+            a.w_cross[l] = w.data_ptr()
+            a.b_cross[l] = b.data_ptr()
+    return arr
+
+
+def dmt_tm_workspace_bytes(plan: dmt_plan, tm_params, B: int) -> int:
+    return int(_lib.dmt_tm_workspace_bytes(plan.handle, tm_params, B))
+
+
+def dmt_tower_module_fwd(plan: dmt_plan, tm_params, pooled: torch.Tensor, B: int,
+                         tm_out: torch.Tensor, workspace: Optional[torch.Tensor] = None,
+                         stream=None) -> None:
+    _check("dmt_tower_module_fwd", _lib.dmt_tower_module_fwd(
+        plan.handle, tm_params, _ptr(pooled), B, _ptr(tm_out), DTYPE_CODE[tm_out.dtype],
+        _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+        _stream(stream)))
+
+
+def dmt_bwd_workspace_bytes(plan: dmt_plan, B: int, nnz: int) -> int:
+    return int(_lib.dmt_bwd_workspace_bytes(plan.handle, B, nnz))
+
+
+def dmt_tower_lookup_bwd_update(plan: dmt_plan, indices: torch.Tensor, offsets: torch.Tensor,
+                                B: int, grad_pooled: torch.Tensor, lr: float, eps: float,
+                                workspace: torch.Tensor, stream=None, debug: Optional[dict] = None) -> None:
+    dbg = None
+    if debug is not None:
+        dbg = dmt_bwd_debug()
+        for k in ("sorted_keys", "sorted_bag", "unique_keys", "seg_off", "num_unique"):
+            setattr(dbg, k, debug[k].data_ptr() if debug.get(k) is not None else None)
+        dbg = ctypes.byref(dbg)
+    _check("dmt_tower_lookup_bwd_update", _lib.dmt_tower_lookup_bwd_update(
+        plan.handle, _ptr(indices), _ptr(offsets), B, indices.numel(), _ptr(grad_pooled),
+        lr, eps, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream), dbg))
+
+
+def dmt_last_device_error(plan: dmt_plan, stream=None) -> int:
+    """-1 when clean, else the smallest offending position (and the record is cleared)."""
+    pos = ctypes.c_int64(-1)
+    code = _lib.dmt_last_device_error(plan.handle, _stream(stream), ctypes.byref(pos))
+    if code not in (DMT_OK, DMT_EBOUNDS):
+        raise DmtError("dmt_last_device_error", code)
+    return int(pos.value)

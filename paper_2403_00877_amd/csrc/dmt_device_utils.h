@@ -1,0 +1,102 @@
+// Small device helpers: 16-byte chunk decode / encode for the three element
+// types, round-to-nearest-even float -> 16-bit conversions.
+#pragma once
+
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+#include "dmt.h"
+
+namespace dmt {
+
+template <int DT> struct EltBytes { static constexpr int value = (DT == DMT_F32) ? 4 : 2; };
+// elements in one 16-byte chunk
+template <int DT> struct ChunkElems { static constexpr int value = 16 / EltBytes<DT>::value; };
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float x) {
+  uint32_t u = __float_as_uint(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;   // NaN stays NaN
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;         // ties to even
+}
+
+__device__ __forceinline__ uint32_t f32_to_f16_bits(float x) {
+  return (uint32_t)__half_as_ushort(__float2half_rn(x));
+}
+
+__device__ __forceinline__ float f16_bits_to_f32(uint32_t h) {
+  return __half2float(__ushort_as_half((unsigned short)h));
+}
+
+template <int DT> __device__ __forceinline__ uint32_t pack2(float a, float b);
+template <> __device__ __forceinline__ uint32_t pack2<DMT_F16>(float a, float b) {
+  return f32_to_f16_bits(a) | (f32_to_f16_bits(b) << 16);
+}
+template <> __device__ __forceinline__ uint32_t pack2<DMT_BF16>(float a, float b) {
+  return f32_to_bf16_bits(a) | (f32_to_bf16_bits(b) << 16);
+}
+
+template <int DT> __device__ __forceinline__ void unpack2(uint32_t u, float& a, float& b);
+template <> __device__ __forceinline__ void unpack2<DMT_F16>(uint32_t u, float& a, float& b) {
+  a = f16_bits_to_f32(u & 0xffffu);
+  b = f16_bits_to_f32(u >> 16);
+}
+template <> __device__ __forceinline__ void unpack2<DMT_BF16>(uint32_t u, float& a, float& b) {
+  a = bf16_lo(u);
+  b = bf16_hi(u);
+}
+
+// acc += the elements of one 16-byte chunk, as float32.
+template <int DT>
+__device__ __forceinline__ void accumulate_chunk(float (&acc)[ChunkElems<DT>::value], uint4 v) {
+  if constexpr (DT == DMT_F32) {
+    acc[0] += __uint_as_float(v.x);
+    acc[1] += __uint_as_float(v.y);
+    acc[2] += __uint_as_float(v.z);
+    acc[3] += __uint_as_float(v.w);
+  } else {
+    float a, b;
+    unpack2<DT>(v.x, a, b); acc[0] += a; acc[1] += b;
+    unpack2<DT>(v.y, a, b); acc[2] += a; acc[3] += b;
+    unpack2<DT>(v.z, a, b); acc[4] += a; acc[5] += b;
+    unpack2<DT>(v.w, a, b); acc[6] += a; acc[7] += b;
+  }
+}
+
+template <int DT>
+__device__ __forceinline__ void decode_chunk(float (&x)[ChunkElems<DT>::value], uint4 v) {
+#pragma unroll
+  for (int q = 0; q < ChunkElems<DT>::value; ++q) x[q] = 0.f;
+  accumulate_chunk<DT>(x, v);
+}
+
+// Store N floats (N = 4 or 8) as OD elements starting at element offset `off`
+// of `base`.  `off` is a multiple of N.
+template <int OD, int N>
+__device__ __forceinline__ void store_chunk(void* base, int64_t off, const float (&a)[N]) {
+  if constexpr (OD == DMT_F32) {
+    float4* o = (float4*)((float*)base + off);
+    o[0] = make_float4(a[0], a[1], a[2], a[3]);
+    if constexpr (N == 8) o[1] = make_float4(a[4], a[5], a[6], a[7]);
+  } else {
+    uint16_t* o = (uint16_t*)base + off;
+    if constexpr (N == 8) {
+      *(uint4*)o = make_uint4(pack2<OD>(a[0], a[1]), pack2<OD>(a[2], a[3]),
+                              pack2<OD>(a[4], a[5]), pack2<OD>(a[6], a[7]));
+    } else {
+      *(uint2*)o = make_uint2(pack2<OD>(a[0], a[1]), pack2<OD>(a[2], a[3]));
+    }
+  }
+}
+
+// Development knob: integer from the environment, `dflt` when unset.
+static inline int env_int(const char* name, int dflt) {
+  const char* v = getenv(name);
+  return (v && *v) ? atoi(v) : dflt;
+}
+
+}  // namespace dmt

@@ -1,0 +1,61 @@
+// Internal declarations shared by the library's translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "dmt.h"
+
+#define DMT_HIP_TRY(expr)                     \
+  do {                                        \
+    hipError_t e_ = (expr);                   \
+    if (e_ != hipSuccess) return DMT_EHIP;    \
+  } while (0)
+
+// Per-table record the kernels read (device copy lives in the plan).
+struct DmtTableMeta {
+  const void* table;     // row-major [rows][D]
+  float* state;          // [rows] or null
+  int64_t rows;
+  int64_t row_base;      // global id of row 0 (prefix sum of rows over tables)
+  int64_t out_prefix;    // sum of W_t' over towers before this table's tower; x B = tower base
+  int32_t D;
+  int32_t tower;
+  int32_t col_off;       // first column inside the tower's rows
+  int32_t tower_width;   // W_t
+};
+
+// Tables that share one embedding dim are launched together.
+struct DmtDimClass {
+  int32_t D;
+  int32_t num_tables;
+  int32_t first;         // offset into class_tables
+};
+
+struct dmt_plan {
+  int32_t F = 0, T = 0;
+  dmt_dtype table_dtype = DMT_F32;
+  int64_t max_batch = 0, max_nnz = 0;
+  std::vector<DmtTableMeta> meta;          // host copy, pointers filled by bind
+  std::vector<int32_t> tower_width;        // [T]
+  std::vector<int64_t> width_prefix;       // [T+1]
+  std::vector<int32_t> tower_ntab;         // [T]
+  std::vector<int32_t> tower_first_table;  // [T] lowest table id in the tower
+  std::vector<int32_t> tower_uniform_dim;  // [T] common D of the tower's tables, or 0
+  std::vector<DmtDimClass> classes;
+  std::vector<int32_t> class_tables;       // table ids grouped by class
+  int64_t total_rows = 0;
+  int32_t max_dim = 0;
+  // device side (created by dmt_plan_bind)
+  bool bound = false;
+  bool has_state = false;
+  DmtTableMeta* d_meta = nullptr;          // [F]
+  int32_t* d_class_tables = nullptr;       // [F]
+  int64_t* d_row_base = nullptr;           // [F+1]
+  unsigned long long* d_error = nullptr;   // smallest bad position, ~0 = none
+};
+
+static inline int dmt_elt_bytes(dmt_dtype t) { return t == DMT_F32 ? 4 : 2; }
+static inline size_t dmt_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

@@ -1,0 +1,185 @@
+// Plan object: the static description of tables and towers (paper Sec. 2.1,
+// Sec. 3.1), the tower-major layout arithmetic, and the device-side lookup
+// tables the kernels index.
+#include <algorithm>
+#include <new>
+
+#include "dmt_internal.h"
+
+extern "C" const char* dmt_status_str(dmt_status s) {
+  switch (s) {
+    case DMT_OK: return "DMT_OK";
+    case DMT_EINVAL: return "DMT_EINVAL";
+    case DMT_ENOTSUP: return "DMT_ENOTSUP";
+    case DMT_EBOUNDS: return "DMT_EBOUNDS";
+    case DMT_ENOMEM: return "DMT_ENOMEM";
+    case DMT_EHIP: return "DMT_EHIP";
+  }
+  return "DMT_UNKNOWN";
+}
+
+extern "C" dmt_status dmt_plan_create(dmt_plan** out, int32_t num_tables, const int64_t* rows,
+                                      const int32_t* dims, dmt_dtype table_dtype,
+                                      int32_t num_towers, const int32_t* table_to_tower,
+                                      int64_t max_batch, int64_t max_nnz) {
+  if (!out) return DMT_EINVAL;
+  *out = nullptr;
+  if (!rows || !dims || !table_to_tower) return DMT_EINVAL;
+  if (num_tables <= 0 || num_tables > DMT_MAX_TABLES) return DMT_EINVAL;
+  if (num_towers <= 0 || num_towers > DMT_MAX_TOWERS || num_towers > num_tables) return DMT_EINVAL;
+  if (max_batch <= 0 || max_nnz < 0) return DMT_EINVAL;
+  if (table_dtype != DMT_F32 && table_dtype != DMT_F16 && table_dtype != DMT_BF16) return DMT_EINVAL;
+  // bag ids f*B + b and lookup positions are carried in 32 bits by the backward
+  if ((int64_t)num_tables * max_batch >= (1LL << 31) || max_nnz >= (1LL << 31)) return DMT_ENOTSUP;
+  const int eb = dmt_elt_bytes(table_dtype);
+  int64_t total_rows = 0;
+  for (int32_t f = 0; f < num_tables; ++f) {
+    if (rows[f] <= 0 || dims[f] <= 0) return DMT_EINVAL;
+    if (rows[f] >= (1LL << 31)) return DMT_ENOTSUP;
+    if (table_to_tower[f] < 0 || table_to_tower[f] >= num_towers) return DMT_EINVAL;
+    int64_t rb = (int64_t)dims[f] * eb;
+    if (rb % 16 != 0 || rb > 1024) return DMT_ENOTSUP;
+    total_rows += rows[f];
+  }
+  if (total_rows >= (1LL << 32)) return DMT_ENOTSUP;
+
+  dmt_plan* p = new (std::nothrow) dmt_plan();
+  if (!p) return DMT_ENOMEM;
+  p->F = num_tables;
+  p->T = num_towers;
+  p->table_dtype = table_dtype;
+  p->max_batch = max_batch;
+  p->max_nnz = max_nnz;
+  p->total_rows = total_rows;
+  p->meta.resize(num_tables);
+  p->tower_width.assign(num_towers, 0);
+  p->tower_ntab.assign(num_towers, 0);
+  p->tower_first_table.assign(num_towers, -1);
+  p->tower_uniform_dim.assign(num_towers, 0);
+  p->width_prefix.assign(num_towers + 1, 0);
+  int64_t rb = 0;
+  for (int32_t f = 0; f < num_tables; ++f) {
+    DmtTableMeta& m = p->meta[f];
+    const int32_t t = table_to_tower[f];
+    m.table = nullptr;
+    m.state = nullptr;
+    m.rows = rows[f];
+    m.row_base = rb;
+    rb += rows[f];
+    m.D = dims[f];
+    m.tower = t;
+    m.col_off = p->tower_width[t];       // tables visited in ascending id = slot order
+    p->tower_width[t] += dims[f];
+    if (p->tower_ntab[t] == 0) {
+      p->tower_first_table[t] = f;
+      p->tower_uniform_dim[t] = dims[f];
+    } else if (p->tower_uniform_dim[t] != dims[f]) {
+      p->tower_uniform_dim[t] = 0;
+    }
+    p->tower_ntab[t]++;
+    p->max_dim = std::max(p->max_dim, dims[f]);
+  }
+  for (int32_t t = 0; t < num_towers; ++t) {
+    if (p->tower_ntab[t] == 0) { delete p; return DMT_EINVAL; }
+    p->width_prefix[t + 1] = p->width_prefix[t] + p->tower_width[t];
+  }
+  for (int32_t f = 0; f < num_tables; ++f) {
+    p->meta[f].tower_width = p->tower_width[p->meta[f].tower];
+    p->meta[f].out_prefix = p->width_prefix[p->meta[f].tower];
+  }
+  // group tables by dim, classes in ascending dim, tables in ascending id
+  std::vector<int32_t> ds(dims, dims + num_tables);
+  std::sort(ds.begin(), ds.end());
+  ds.erase(std::unique(ds.begin(), ds.end()), ds.end());
+  for (int32_t d : ds) {
+    DmtDimClass c;
+    c.D = d;
+    c.first = (int32_t)p->class_tables.size();
+    for (int32_t f = 0; f < num_tables; ++f)
+      if (dims[f] == d) p->class_tables.push_back(f);
+    c.num_tables = (int32_t)p->class_tables.size() - c.first;
+    p->classes.push_back(c);
+  }
+  *out = p;
+  return DMT_OK;
+}
+
+static void release_device(dmt_plan* p) {
+  if (p->d_meta) (void)hipFree(p->d_meta);
+  if (p->d_class_tables) (void)hipFree(p->d_class_tables);
+  if (p->d_row_base) (void)hipFree(p->d_row_base);
+  if (p->d_error) (void)hipFree(p->d_error);
+  p->d_meta = nullptr;
+  p->d_class_tables = nullptr;
+  p->d_row_base = nullptr;
+  p->d_error = nullptr;
+  p->bound = false;
+}
+
+extern "C" void dmt_plan_destroy(dmt_plan* plan) {
+  if (!plan) return;
+  release_device(plan);
+  delete plan;
+}
+
+extern "C" dmt_status dmt_plan_layout(const dmt_plan* plan, int64_t B, int64_t* tower_base,
+                                      int32_t* tower_width, int32_t* col_off) {
+  if (!plan || B < 0) return DMT_EINVAL;
+  if (tower_base)
+    for (int32_t t = 0; t <= plan->T; ++t) tower_base[t] = B * plan->width_prefix[t];
+  if (tower_width)
+    for (int32_t t = 0; t < plan->T; ++t) tower_width[t] = plan->tower_width[t];
+  if (col_off)
+    for (int32_t f = 0; f < plan->F; ++f) col_off[f] = plan->meta[f].col_off;
+  return DMT_OK;
+}
+
+extern "C" dmt_status dmt_plan_bind(dmt_plan* plan, const void* const* tables,
+                                    float* const* adagrad_state) {
+  if (!plan || !tables) return DMT_EINVAL;
+  for (int32_t f = 0; f < plan->F; ++f) {
+    if (!tables[f] || ((uintptr_t)tables[f] & 15)) return DMT_EINVAL;
+    if (adagrad_state && (!adagrad_state[f] || ((uintptr_t)adagrad_state[f] & 3))) return DMT_EINVAL;
+  }
+  for (int32_t f = 0; f < plan->F; ++f) {
+    plan->meta[f].table = tables[f];
+    plan->meta[f].state = adagrad_state ? adagrad_state[f] : nullptr;
+  }
+  plan->has_state = adagrad_state != nullptr;
+  if (!plan->d_meta) {
+    DMT_HIP_TRY(hipMalloc((void**)&plan->d_meta, sizeof(DmtTableMeta) * plan->F));
+    DMT_HIP_TRY(hipMalloc((void**)&plan->d_class_tables, sizeof(int32_t) * plan->F));
+    DMT_HIP_TRY(hipMalloc((void**)&plan->d_row_base, sizeof(int64_t) * (plan->F + 1)));
+    DMT_HIP_TRY(hipMalloc((void**)&plan->d_error, sizeof(unsigned long long)));
+  }
+  std::vector<int64_t> row_base(plan->F + 1);
+  for (int32_t f = 0; f < plan->F; ++f) row_base[f] = plan->meta[f].row_base;
+  row_base[plan->F] = plan->total_rows;
+  const unsigned long long none = ~0ULL;
+  DMT_HIP_TRY(hipMemcpy(plan->d_meta, plan->meta.data(), sizeof(DmtTableMeta) * plan->F,
+                        hipMemcpyHostToDevice));
+  DMT_HIP_TRY(hipMemcpy(plan->d_class_tables, plan->class_tables.data(),
+                        sizeof(int32_t) * plan->F, hipMemcpyHostToDevice));
+  DMT_HIP_TRY(hipMemcpy(plan->d_row_base, row_base.data(), sizeof(int64_t) * (plan->F + 1),
+                        hipMemcpyHostToDevice));
+  DMT_HIP_TRY(hipMemcpy(plan->d_error, &none, sizeof(none), hipMemcpyHostToDevice));
+  plan->bound = true;
+  return DMT_OK;
+}
+
+extern "C" dmt_status dmt_last_device_error(const dmt_plan* plan, void* stream,
+                                            int64_t* bad_position) {
+  if (!plan || !bad_position) return DMT_EINVAL;
+  *bad_position = -1;
+  if (!plan->bound) return DMT_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  unsigned long long v = ~0ULL;
+  const unsigned long long none = ~0ULL;
+  DMT_HIP_TRY(hipMemcpyAsync(&v, plan->d_error, sizeof(v), hipMemcpyDeviceToHost, s));
+  DMT_HIP_TRY(hipStreamSynchronize(s));
+  if (v == none) return DMT_OK;
+  DMT_HIP_TRY(hipMemcpyAsync(plan->d_error, &none, sizeof(none), hipMemcpyHostToDevice, s));
+  DMT_HIP_TRY(hipStreamSynchronize(s));
+  *bad_position = (int64_t)v;
+  return DMT_EBOUNDS;
+}

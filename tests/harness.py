@@ -1,0 +1,81 @@
+"""Shared helpers for the GPU parity tests: move a workload's seeded inputs to
+the device, call the library, and compare with the oracle."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import workloads as wl
+
+TORCH_DT = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+# spec tolerances: float32 pooling 1e-5; 16-bit outputs and updated rows 2e-2
+RTOL = {"f32": 1e-5, "f16": 2e-2, "bf16": 2e-2}
+
+
+def to_device(a: np.ndarray, dtype: str = None) -> torch.Tensor:
+    """Storage array -> device tensor (bf16 bit patterns are re-viewed)."""
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype == "bf16":
+        t = t.view(torch.int16).view(torch.bfloat16)
+    return t.cuda()
+
+
+def to_f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def assert_close(got: np.ndarray, ref: np.ndarray, rtol: float, what: str = ""):
+    """|got - ref| <= rtol*|ref| + rtol*rms(ref), elementwise (pure relative error
+    means nothing for sums that land near zero)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    if ref.size == 0:
+        return
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    err = np.abs(got - ref)
+    tol = rtol * np.abs(ref) + rtol * rms
+    bad = err > tol
+    if bad.any():
+        i = int(np.argmax(err - tol))
+        raise AssertionError("%s: %d of %d outside tolerance; worst at flat %d: got %r ref %r (rms %g)"
+                             % (what, int(bad.sum()), ref.size, i, got.flat[i], ref.flat[i], rms))
+
+
+class DeviceWorkload:
+    """A workload's tables (host-generated) bound to a plan on the GPU."""
+
+    def __init__(self, w: wl.Workload, with_state: bool = False, max_nnz: int = None):
+        import paper_2403_00877_amd as dmt
+        self.dmt = dmt
+        self.w = w
+        self.host_tables = wl.tables_host(w)
+        self.tables = [to_device(t, w.table_dtype) for t in self.host_tables]
+        self.states = None
+        if with_state:
+            self.states = [torch.zeros(r, dtype=torch.float32, device="cuda") for r in w.rows]
+        if max_nnz is None:
+            max_nnz = w.num_tables * w.batch * w.len_cap
+        self.plan = dmt.dmt_plan_create(w.rows, w.dims, w.table_dtype, w.num_towers,
+                                        w.table_to_tower, w.batch, max_nnz)
+        dmt.dmt_plan_bind(self.plan, self.tables, self.states)
+        self.base, self.widths, self.col = dmt.dmt_plan_layout(self.plan, w.batch)
+
+    def lookup(self, indices: np.ndarray, offsets: np.ndarray, out_dtype: str = None) -> torch.Tensor:
+        w = self.w
+        out_dtype = out_dtype or w.pooled_dtype
+        d_idx = torch.from_numpy(indices).cuda()
+        d_off = torch.from_numpy(offsets).cuda()
+        out = torch.full((self.base[-1],), float("nan"), dtype=TORCH_DT[out_dtype], device="cuda")
+        self.dmt.dmt_tower_lookup_fwd(self.plan, d_idx, d_off, w.batch, out)
+        torch.cuda.synchronize()
+        return out
+
+    def split_towers(self, flat, widths=None, B=None):
+        widths = widths or self.widths
+        B = B or self.w.batch
+        out, base = [], 0
+        for wt in widths:
+            out.append(flat[base:base + B * wt].reshape(B, wt))
+            base += B * wt
+        return out
