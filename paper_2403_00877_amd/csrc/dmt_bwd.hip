@@ -1,3 +1,600 @@
+// dmt_tower_lookup_bwd_update: gradients to the activated rows only (paper
+// Sec. 2.2), as  key build -> stable LSD radix sort by global row id ->
+// run heads / segment offsets -> tiled segment reduce fused with the rowwise
+// Adagrad row update -> fix-up of rows whose run spans several tiles.
+//
+// Everything is deterministic: the sort is stable (equal rows keep ascending
+// bag order), every row's gradient is summed in a fixed order, and each row has
+// exactly one writer.  No floating-point atomics anywhere.
+//
+// Data in the workspace: 64-bit records (global_row << 32 | bag), where
+// global_row = (sum of rows of earlier tables) + row and bag = f*B + b.  Ids
+// outside their table get global_row = total_rows (sorts last, never touched).
 #include "dmt_internal.h"
-extern "C" size_t dmt_bwd_workspace_bytes(const dmt_plan*, int64_t, int64_t) { return 0; }
-extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan*, const int32_t*, const int64_t*, int64_t, int64_t, const float*, float, float, void*, size_t, void*, const dmt_bwd_debug*) { return DMT_ENOTSUP; }
+#include "dmt_device_utils.h"
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kSortItems = 16;
+constexpr int kSortTile = kBlock * kSortItems;   // records per sort block
+constexpr int kScanItems = 16;
+constexpr int kScanTile = kBlock * kScanItems;   // records per head-scan block
+constexpr int kReduceTile = 128;                 // sorted records per reduce tile
+constexpr int kReduceUnroll = 4;
+
+struct BwdWs {
+  uint64_t* pk_a;
+  uint64_t* pk_b;
+  uint32_t* hist;         // [256][nblk_sort]
+  uint32_t* digit_total;  // [256]
+  uint32_t* blk_heads;    // [nblk_scan]
+  uint32_t* seg_off;      // [nnz + 1]
+  uint32_t* tile_first;   // [ntiles + 1] run heads before each reduce tile
+  uint32_t* num_unique;   // [1]
+  float* partials;        // [2 * ntiles][Dmax]
+  size_t bytes;
+  int64_t nblk_sort, nblk_scan, ntiles;
+};
+
+BwdWs carve(const dmt_plan* p, int64_t nnz, void* base) {
+  BwdWs w;
+  const int64_t n = nnz > 0 ? nnz : 1;
+  w.nblk_sort = (n + kSortTile - 1) / kSortTile;
+  w.nblk_scan = (n + kScanTile - 1) / kScanTile;
+  w.ntiles = (n + kReduceTile - 1) / kReduceTile;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off = dmt_align_up(off + bytes, 256);
+    return (char*)base + o;
+  };
+  w.pk_a = (uint64_t*)take(sizeof(uint64_t) * n);
+  w.pk_b = (uint64_t*)take(sizeof(uint64_t) * n);
+  w.hist = (uint32_t*)take(sizeof(uint32_t) * 256 * w.nblk_sort);
+  w.digit_total = (uint32_t*)take(sizeof(uint32_t) * 256);
+  w.blk_heads = (uint32_t*)take(sizeof(uint32_t) * (w.nblk_scan + 1));
+  w.seg_off = (uint32_t*)take(sizeof(uint32_t) * (n + 1));
+  w.tile_first = (uint32_t*)take(sizeof(uint32_t) * (w.ntiles + 1));
+  w.num_unique = (uint32_t*)take(sizeof(uint32_t) * 64);
+  w.partials = (float*)take(sizeof(float) * 2 * w.ntiles * p->max_dim);
+  w.bytes = off;
+  return w;
+}
+
+// ------------------------------------------------------------------ key build
+
+__global__ __launch_bounds__(kBlock) void bwd_build_keys(
+    const DmtTableMeta* __restrict__ meta, const int32_t* __restrict__ indices,
+    const int64_t* __restrict__ offsets, uint32_t B, uint32_t nbags, int64_t nnz,
+    uint32_t total_rows, uint64_t* __restrict__ pk, int log2_gl,
+    unsigned long long* __restrict__ err) {
+  const int GL = 1 << log2_gl;
+  const uint32_t g = blockIdx.x * (kBlock >> log2_gl) + (threadIdx.x >> log2_gl);
+  if (g >= nbags) return;
+  const int gl = threadIdx.x & (GL - 1);
+  const uint32_t f = g / B;
+  int64_t s = offsets[g], e = offsets[g + 1];
+  s = s < 0 ? 0 : (s > nnz ? nnz : s);
+  e = e < s ? s : (e > nnz ? nnz : e);
+  const uint64_t rows = (uint64_t)meta[f].rows;
+  const uint32_t row_base = (uint32_t)meta[f].row_base;
+  for (int64_t j = s + gl; j < e; j += GL) {
+    const int32_t idx = indices[j];
+    uint32_t gid = row_base + (uint32_t)idx;
+    if ((uint64_t)(uint32_t)idx >= rows) {
+      atomicMin(err, (unsigned long long)j);
+      gid = total_rows;
+    }
+    pk[j] = ((uint64_t)gid << 32) | g;
+  }
+}
+
+// A record no bag covers (offsets that do not tile [0, nnz)) must still be inert.
+__global__ __launch_bounds__(kBlock) void bwd_fill_inert(uint64_t* __restrict__ pk, int64_t nnz,
+                                                         uint32_t total_rows) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i < nnz) pk[i] = ((uint64_t)total_rows << 32) | 0xffffffffu;
+}
+
+// ------------------------------------------------------------------ radix sort
+
+__global__ __launch_bounds__(kBlock) void radix_hist(const uint64_t* __restrict__ pk, int64_t nnz,
+                                                     int shift, int bits,
+                                                     uint32_t* __restrict__ hist, int64_t nblk) {
+  __shared__ uint32_t h[256];
+  h[threadIdx.x] = 0;
+  __syncthreads();
+  const uint32_t mask = (1u << bits) - 1;
+  const int64_t base = (int64_t)blockIdx.x * kSortTile;
+#pragma unroll
+  for (int i = 0; i < kSortItems; ++i) {
+    const int64_t pos = base + i * kBlock + threadIdx.x;
+    if (pos < nnz) atomicAdd(&h[(uint32_t)(pk[pos] >> (32 + shift)) & mask], 1u);
+  }
+  __syncthreads();
+  if (threadIdx.x < (1u << bits)) hist[(int64_t)threadIdx.x * nblk + blockIdx.x] = h[threadIdx.x];
+}
+
+// One block per digit: exclusive scan of that digit's per-block counts, in place.
+__global__ __launch_bounds__(kBlock) void radix_scan(uint32_t* __restrict__ hist, int64_t nblk,
+                                                     uint32_t* __restrict__ digit_total) {
+  __shared__ uint32_t sm[8];
+  uint32_t* row = hist + (int64_t)blockIdx.x * nblk;
+  uint32_t running = 0;
+  for (int64_t base = 0; base < nblk; base += kBlock) {
+    const int64_t i = base + threadIdx.x;
+    const uint32_t v = i < nblk ? row[i] : 0;
+    uint32_t total;
+    const uint32_t ex = dmt::block_exclusive_scan<kBlock / 64>(v, sm, total);
+    if (i < nblk) row[i] = running + ex;
+    running += total;
+  }
+  if (threadIdx.x == 0) digit_total[blockIdx.x] = running;
+}
+
+__global__ __launch_bounds__(kBlock) void radix_scatter(
+    const uint64_t* __restrict__ in, uint64_t* __restrict__ out, int64_t nnz, int shift, int bits,
+    const uint32_t* __restrict__ hist, const uint32_t* __restrict__ digit_total, int64_t nblk) {
+  __shared__ uint64_t buf[kSortTile];
+  __shared__ uint32_t cnt[kBlock / 64][256];
+  __shared__ uint32_t tile_start[256];
+  __shared__ uint32_t gbase[256];
+  __shared__ uint32_t sm[8];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const uint32_t radix = 1u << bits, mask = radix - 1;
+  for (int w = 0; w < kBlock / 64; ++w) cnt[w][tid] = 0;
+  __syncthreads();
+  const int64_t tile_base = (int64_t)blockIdx.x * kSortTile;
+  const int n_tile = (int)min((int64_t)kSortTile, nnz - tile_base);
+  volatile uint32_t* my_cnt = cnt[wave];
+
+  uint64_t rec[kSortItems];
+  uint32_t rank[kSortItems];
+#pragma unroll
+  for (int i = 0; i < kSortItems; ++i) {
+    const int q = wave * (kSortItems * 64) + i * 64 + lane;
+    const bool valid = q < n_tile;
+    rec[i] = valid ? in[tile_base + q] : ~0ULL;
+    const uint32_t d = (uint32_t)(rec[i] >> (32 + shift)) & mask;
+    // lanes of this wave holding the same digit
+    uint64_t peers = __ballot(valid);
+    for (int b = 0; b < bits; ++b) {
+      const bool bit = (d >> b) & 1;
+      const uint64_t m = __ballot(bit);
+      peers &= bit ? m : ~m;
+    }
+    uint32_t old = 0;
+    int leader = 0;
+    if (valid) {
+      leader = __ffsll((unsigned long long)peers) - 1;
+      if (lane == leader) {
+        old = my_cnt[d];
+        my_cnt[d] = old + (uint32_t)__popcll(peers);
+      }
+    }
+    old = __shfl(old, leader);
+    rank[i] = old + (uint32_t)__popcll(peers & ((1ULL << lane) - 1));
+    __builtin_amdgcn_wave_barrier();
+  }
+  __syncthreads();
+  // digit totals over the waves; cnt becomes each wave's offset inside the digit
+  uint32_t tot = 0;
+  if (tid < (int)radix) {
+    uint32_t run = 0;
+    for (int w = 0; w < kBlock / 64; ++w) {
+      const uint32_t c = cnt[w][tid];
+      cnt[w][tid] = run;
+      run += c;
+    }
+    tot = run;
+  }
+  uint32_t total;
+  const uint32_t ex = dmt::block_exclusive_scan<kBlock / 64>(tot, sm, total);
+  const uint32_t dt = tid < (int)radix ? digit_total[tid] : 0;
+  const uint32_t dex = dmt::block_exclusive_scan<kBlock / 64>(dt, sm, total);
+  if (tid < (int)radix) {
+    tile_start[tid] = ex;
+    gbase[tid] = dex + hist[(int64_t)tid * nblk + blockIdx.x] - ex;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kSortItems; ++i) {
+    const int q = wave * (kSortItems * 64) + i * 64 + lane;
+    if (q < n_tile) {
+      const uint32_t d = (uint32_t)(rec[i] >> (32 + shift)) & mask;
+      buf[tile_start[d] + cnt[wave][d] + rank[i]] = rec[i];
+    }
+  }
+  __syncthreads();
+  for (int q = tid; q < n_tile; q += kBlock) {
+    const uint64_t r = buf[q];
+    const uint32_t d = (uint32_t)(r >> (32 + shift)) & mask;
+    out[gbase[d] + (uint32_t)q] = r;
+  }
+}
+
+// ------------------------------------------------- run heads, segment offsets
+
+__device__ __forceinline__ bool is_head(const uint64_t* pk, int64_t i) {
+  return i == 0 || (uint32_t)(pk[i] >> 32) != (uint32_t)(pk[i - 1] >> 32);
+}
+
+__global__ __launch_bounds__(kBlock) void heads_count(const uint64_t* __restrict__ pk, int64_t nnz,
+                                                      uint32_t* __restrict__ blk_heads) {
+  __shared__ uint32_t sm[8];
+  const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+  uint32_t c = 0;
+  uint32_t prev = base > 0 && base <= nnz ? (uint32_t)(pk[base - 1] >> 32) : 0;
+#pragma unroll
+  for (int i = 0; i < kScanItems; ++i) {
+    const int64_t p = base + i;
+    if (p < nnz) {
+      const uint32_t k = (uint32_t)(pk[p] >> 32);
+      c += (p == 0 || k != prev) ? 1u : 0u;
+      prev = k;
+    }
+  }
+  uint32_t total;
+  (void)dmt::block_exclusive_scan<kBlock / 64>(c, sm, total);
+  if (threadIdx.x == 0) blk_heads[blockIdx.x] = total;
+}
+
+// Single block: exclusive scan of the per-block head counts; total = number of
+// distinct keys (the inert key, if present, is counted and removed by the caller
+// of num_unique through `has_inert`).
+__global__ __launch_bounds__(1024) void heads_scan(uint32_t* __restrict__ blk_heads, int64_t nblk,
+                                                   uint32_t* __restrict__ num_unique) {
+  __shared__ uint32_t sm[32];
+  uint32_t running = 0;
+  for (int64_t base = 0; base < nblk; base += 1024) {
+    const int64_t i = base + threadIdx.x;
+    const uint32_t v = i < nblk ? blk_heads[i] : 0;
+    uint32_t total;
+    const uint32_t ex = dmt::block_exclusive_scan<16>(v, sm, total);
+    if (i < nblk) blk_heads[i] = running + ex;
+    running += total;
+  }
+  if (threadIdx.x == 0) num_unique[0] = running;
+}
+
+__global__ __launch_bounds__(kBlock) void heads_write(
+    const uint64_t* __restrict__ pk, int64_t nnz, const uint32_t* __restrict__ blk_heads,
+    uint32_t* __restrict__ seg_off, uint32_t* __restrict__ tile_first) {
+  __shared__ uint32_t sm[8];
+  const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+  uint32_t flags = 0, c = 0;
+  uint32_t prev = base > 0 && base <= nnz ? (uint32_t)(pk[base - 1] >> 32) : 0;
+#pragma unroll
+  for (int i = 0; i < kScanItems; ++i) {
+    const int64_t p = base + i;
+    if (p < nnz) {
+      const uint32_t k = (uint32_t)(pk[p] >> 32);
+      if (p == 0 || k != prev) { flags |= 1u << i; ++c; }
+      prev = k;
+    }
+  }
+  uint32_t total;
+  uint32_t before = blk_heads[blockIdx.x] + dmt::block_exclusive_scan<kBlock / 64>(c, sm, total);
+#pragma unroll
+  for (int i = 0; i < kScanItems; ++i) {
+    const int64_t p = base + i;
+    if (p < nnz) {
+      if ((p & (kReduceTile - 1)) == 0) tile_first[p / kReduceTile] = before;
+      if (flags & (1u << i)) seg_off[before++] = (uint32_t)p;
+      if (p == nnz - 1) seg_off[before] = (uint32_t)nnz;
+    }
+  }
+}
+
+// ------------------------------------------- segment reduce + rowwise Adagrad
+
+// One rowwise-Adagrad step on row `row` of table f with summed gradient g (the
+// group's lanes hold 4 consecutive columns each; lanes past D hold zeros).
+template <int TD>
+__device__ __forceinline__ void apply_row_update(const DmtTableMeta* __restrict__ meta, uint32_t f,
+                                                 uint32_t row, float4 g, int gl, int GL, float lr,
+                                                 float eps) {
+  const int D = meta[f].D;
+  float ss = g.x * g.x + g.y * g.y + g.z * g.z + g.w * g.w;
+  for (int o = 1; o < GL; o <<= 1) ss += __shfl_xor(ss, o);
+  float* state = meta[f].state;
+  const float st = state[row] + ss / (float)D;
+  const float step = lr / (sqrtf(st) + eps);
+  if (gl * 4 < D) {
+    if constexpr (TD == DMT_F32) {
+      float4* w = (float4*)((float*)meta[f].table + (int64_t)row * D) + gl;
+      float4 v = *w;
+      v.x -= step * g.x; v.y -= step * g.y; v.z -= step * g.z; v.w -= step * g.w;
+      *w = v;
+    } else {
+      uint2* w = (uint2*)((uint16_t*)meta[f].table + (int64_t)row * D) + gl;
+      const uint2 u = *w;
+      float a, b, c, d;
+      dmt::unpack2<TD>(u.x, a, b);
+      dmt::unpack2<TD>(u.y, c, d);
+      a -= step * g.x; b -= step * g.y; c -= step * g.z; d -= step * g.w;
+      *w = make_uint2(dmt::pack2<TD>(a, b), dmt::pack2<TD>(c, d));
+    }
+  }
+  if (gl == 0) state[row] = st;
+}
+
+__device__ __forceinline__ void store_partial(float* __restrict__ partials, int64_t slot,
+                                              int Dmax, int gl, float4 g) {
+  if (gl * 4 < Dmax) *((float4*)(partials + slot * Dmax) + gl) = g;
+}
+
+// Each group of GL lanes walks one tile of kReduceTile sorted records, summing
+// the bags' gradient slices run by run.  A run that lies wholly inside the tile
+// is applied to its row at once; the piece of a run that continues from the
+// previous tile goes to partial slot 2t, the piece of a run that starts here
+// and continues into the next tile goes to slot 2t + 1.
+template <int TD>
+__global__ __launch_bounds__(kBlock) void bwd_reduce_update(
+    const DmtTableMeta* __restrict__ meta, const uint64_t* __restrict__ pk, int64_t nnz, uint32_t B,
+    uint32_t nbags, uint32_t total_rows, const float* __restrict__ grad,
+    float* __restrict__ partials, int Dmax, int log2_gl, int64_t ntiles, int64_t blocks_per_xcd,
+    float lr, float eps) {
+  const int GL = 1 << log2_gl;
+  const int64_t tb = (int64_t)(blockIdx.x & 7) * blocks_per_xcd + (blockIdx.x >> 3);
+  const int64_t t = tb * (kBlock >> log2_gl) + (threadIdx.x >> log2_gl);
+  if (t >= ntiles) return;
+  const int lane = threadIdx.x & 63;
+  const int gl = threadIdx.x & (GL - 1);
+  const int lane0 = lane & ~(GL - 1);
+  const int64_t p0 = t * kReduceTile;
+  const int n = (int)min((int64_t)kReduceTile, nnz - p0);
+  const uint32_t first_key = (uint32_t)(pk[p0] >> 32);
+  const bool cont_prev = p0 > 0 && (uint32_t)(pk[p0 - 1] >> 32) == first_key;
+  const bool cont_next =
+      p0 + n < nnz && (uint32_t)(pk[p0 + n - 1] >> 32) == (uint32_t)(pk[p0 + n] >> 32);
+
+  uint32_t cur_key = first_key, cur_f = 0;
+  bool first_run = true, have_f = false;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+
+  for (int sub = 0; sub < n; sub += GL) {
+    const int cnt = min(GL, n - sub);
+    uint32_t key_l = total_rows, f_l = 0;
+    int D_l = 0;
+    int64_t goff_l = 0;
+    if (gl < cnt) {
+      const uint64_t r = pk[p0 + sub + gl];
+      key_l = (uint32_t)(r >> 32);
+      const uint32_t bag = (uint32_t)r;
+      if (key_l < total_rows && bag < nbags) {
+        f_l = bag / B;
+        const uint32_t b = bag - f_l * B;
+        D_l = meta[f_l].D;
+        goff_l = (int64_t)B * meta[f_l].out_prefix + (int64_t)b * meta[f_l].tower_width +
+                 meta[f_l].col_off;
+      } else {
+        key_l = total_rows;
+      }
+    }
+    for (int i0 = 0; i0 < cnt; i0 += kReduceUnroll) {
+      float4 g[kReduceUnroll];
+#pragma unroll
+      for (int u = 0; u < kReduceUnroll; ++u) {
+        const int src = lane0 + ((i0 + u) & (GL - 1));
+        const int64_t go = __shfl(goff_l, src);
+        const int d = __shfl(D_l, src);
+        g[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (i0 + u < cnt && gl * 4 < d) g[u] = *((const float4*)(grad + go) + gl);
+      }
+#pragma unroll
+      for (int u = 0; u < kReduceUnroll; ++u) {
+        const int src = lane0 + ((i0 + u) & (GL - 1));
+        const uint32_t k = __shfl(key_l, src);
+        const uint32_t fk = __shfl(f_l, src);
+        if (i0 + u < cnt) {
+          if (k != cur_key) {
+            // the run that just ended lies inside the tile unless it came in from the left
+            if (cur_key < total_rows) {
+              if (first_run && cont_prev) store_partial(partials, 2 * t, Dmax, gl, acc);
+              else apply_row_update<TD>(meta, cur_f, cur_key - (uint32_t)meta[cur_f].row_base, acc,
+                                        gl, GL, lr, eps);
+            }
+            acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            cur_key = k;
+            first_run = false;
+            have_f = false;
+          }
+          if (!have_f) { cur_f = fk; have_f = true; }
+          acc.x += g[u].x; acc.y += g[u].y; acc.z += g[u].z; acc.w += g[u].w;
+        }
+      }
+    }
+  }
+  if (cur_key < total_rows) {
+    if (first_run && cont_prev) store_partial(partials, 2 * t, Dmax, gl, acc);
+    else if (cont_next) store_partial(partials, 2 * t + 1, Dmax, gl, acc);
+    else apply_row_update<TD>(meta, cur_f, cur_key - (uint32_t)meta[cur_f].row_base, acc, gl, GL,
+                              lr, eps);
+  }
+}
+
+// Table that owns global row id `gid` (row_base has F + 1 ascending entries).
+__device__ __forceinline__ uint32_t table_of(const int64_t* __restrict__ row_base, int F,
+                                             uint32_t gid) {
+  int lo = 0, hi = F;                      // row_base[lo] <= gid < row_base[hi]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if ((int64_t)gid >= row_base[mid]) lo = mid; else hi = mid;
+  }
+  return (uint32_t)lo;
+}
+
+// Rows whose run crosses tile boundaries: the group of the tile where the run
+// starts adds the pieces in tile order and applies the update.
+template <int TD>
+__global__ __launch_bounds__(kBlock) void bwd_fixup_update(
+    const DmtTableMeta* __restrict__ meta, const int64_t* __restrict__ row_base, int F,
+    const uint64_t* __restrict__ pk, int64_t nnz, uint32_t total_rows,
+    const uint32_t* __restrict__ seg_off, const uint32_t* __restrict__ tile_first,
+    const float* __restrict__ partials, int Dmax, int log2_gl, int64_t ntiles, float lr, float eps) {
+  const int GL = 1 << log2_gl;
+  const int64_t t0 = (int64_t)blockIdx.x * (kBlock >> log2_gl) + (threadIdx.x >> log2_gl);
+  if (t0 >= ntiles - 1) return;
+  const int gl = threadIdx.x & (GL - 1);
+  const int64_t p0 = t0 * kReduceTile, p1 = p0 + kReduceTile;    // p1 < nnz here
+  const uint32_t k_last = (uint32_t)(pk[p1 - 1] >> 32);
+  if (k_last != (uint32_t)(pk[p1] >> 32) || k_last >= total_rows) return;
+  const uint32_t k_first = (uint32_t)(pk[p0] >> 32);
+  if (k_first == k_last && p0 > 0 && (uint32_t)(pk[p0 - 1] >> 32) == k_first) return;
+  const uint32_t u = tile_first[t0 + 1] - 1;      // the run that contains p1 - 1
+  const int64_t end = seg_off[u + 1];
+  const int64_t t1 = (end - 1) / kReduceTile;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  const bool on = gl * 4 < Dmax;
+  if (on) acc = *((const float4*)(partials + (2 * t0 + 1) * Dmax) + gl);
+  for (int64_t tt = t0 + 1; tt <= t1; tt += 8) {
+    float4 g[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      g[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (on && tt + q <= t1) g[q] = *((const float4*)(partials + 2 * (tt + q) * Dmax) + gl);
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      acc.x += g[q].x; acc.y += g[q].y; acc.z += g[q].z; acc.w += g[q].w;
+    }
+  }
+  const uint32_t f = table_of(row_base, F, k_last);
+  apply_row_update<TD>(meta, f, k_last - (uint32_t)row_base[f], acc, gl, GL, lr, eps);
+}
+
+// ------------------------------------------------------------- parity exports
+
+__global__ __launch_bounds__(kBlock) void bwd_export(
+    const int64_t* __restrict__ row_base, int F, const uint64_t* __restrict__ pk, int64_t nnz,
+    uint32_t total_rows, const uint32_t* __restrict__ seg_off,
+    const uint32_t* __restrict__ num_unique_in, int64_t* __restrict__ sorted_keys,
+    int32_t* __restrict__ sorted_bag, int64_t* __restrict__ unique_keys,
+    int64_t* __restrict__ seg_off_out, int64_t* __restrict__ num_unique) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  uint32_t U = nnz > 0 ? num_unique_in[0] : 0;
+  // the inert key (ids outside their table) sorts last and is not a row
+  if (nnz > 0 && U > 0 && (uint32_t)(pk[nnz - 1] >> 32) >= total_rows) --U;
+  if (i == 0 && num_unique) num_unique[0] = U;
+  if (i < nnz) {
+    const uint32_t gid = (uint32_t)(pk[i] >> 32);
+    int64_t key = -1;
+    if (gid < total_rows) {
+      const uint32_t f = table_of(row_base, F, gid);
+      key = ((int64_t)f << 32) | (int64_t)(gid - (uint32_t)row_base[f]);
+    }
+    if (sorted_keys) sorted_keys[i] = key;
+    if (sorted_bag) sorted_bag[i] = (int32_t)(uint32_t)pk[i];
+  }
+  if (i <= U) {
+    if (seg_off_out) seg_off_out[i] = nnz > 0 ? (int64_t)seg_off[i] : 0;
+    if (i < U && unique_keys) {
+      const uint32_t gid = (uint32_t)(pk[seg_off[i]] >> 32);
+      const uint32_t f = table_of(row_base, F, gid);
+      unique_keys[i] = ((int64_t)f << 32) | (int64_t)(gid - (uint32_t)row_base[f]);
+    }
+  }
+}
+
+int ilog2_ceil(int64_t x) {
+  int l = 0;
+  while ((1LL << l) < x) ++l;
+  return l;
+}
+
+}  // namespace
+
+extern "C" size_t dmt_bwd_workspace_bytes(const dmt_plan* plan, int64_t B, int64_t nnz) {
+  if (!plan || B <= 0 || nnz < 0) return 0;
+  return carve(plan, nnz, nullptr).bytes;
+}
+
+extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const int32_t* indices,
+                                                  const int64_t* offsets, int64_t B, int64_t nnz,
+                                                  const float* grad_pooled, float lr, float eps,
+                                                  void* workspace, size_t workspace_bytes,
+                                                  void* stream, const dmt_bwd_debug* dbg) {
+  if (!plan || !offsets || !grad_pooled) return DMT_EINVAL;
+  if (B <= 0 || B > plan->max_batch || nnz < 0 || nnz > plan->max_nnz) return DMT_EINVAL;
+  if (nnz > 0 && !indices) return DMT_EINVAL;
+  if (!plan->bound || !plan->has_state) return DMT_EINVAL;
+  if (!(eps >= 0.f) || lr != lr) return DMT_EINVAL;
+  if ((uintptr_t)grad_pooled & 15) return DMT_EINVAL;
+  if (plan->max_dim > 256) return DMT_ENOTSUP;          // one float4 per lane, 64 lanes
+  const BwdWs w = carve(plan, nnz, workspace);
+  if (!workspace || ((uintptr_t)workspace & 255)) return DMT_EINVAL;
+  if (workspace_bytes < w.bytes) return DMT_ENOMEM;
+  hipStream_t s = (hipStream_t)stream;
+  const uint32_t total_rows = (uint32_t)plan->total_rows;
+  const uint32_t nbags = (uint32_t)((int64_t)plan->F * B);
+  const uint64_t* sorted = w.pk_a;
+
+  if (nnz > 0) {
+    // keys
+    hipLaunchKernelGGL(bwd_fill_inert, dim3((unsigned)((nnz + kBlock - 1) / kBlock)), dim3(kBlock),
+                       0, s, w.pk_a, nnz, total_rows);
+    const double mean_len = (double)nnz / (double)nbags;
+    int log2_gl = ilog2_ceil((int64_t)(mean_len + 0.5));
+    log2_gl = log2_gl < 2 ? 2 : (log2_gl > 6 ? 6 : log2_gl);
+    const unsigned kb_blocks = (nbags + (kBlock >> log2_gl) - 1) / (kBlock >> log2_gl);
+    hipLaunchKernelGGL(bwd_build_keys, dim3(kb_blocks), dim3(kBlock), 0, s, plan->d_meta, indices,
+                       offsets, (uint32_t)B, nbags, nnz, total_rows, w.pk_a, log2_gl,
+                       plan->d_error);
+    // stable LSD radix sort over the bits that can be set (values 0..total_rows)
+    const int key_bits = ilog2_ceil((int64_t)total_rows + 1);
+    const int passes = (key_bits + 7) / 8;
+    const int bits_per = (key_bits + passes - 1) / passes;
+    uint64_t* src = w.pk_a;
+    uint64_t* dst = w.pk_b;
+    for (int p = 0; p < passes; ++p) {
+      const int shift = p * bits_per;
+      const int bits = (key_bits - shift) < bits_per ? (key_bits - shift) : bits_per;
+      hipLaunchKernelGGL(radix_hist, dim3((unsigned)w.nblk_sort), dim3(kBlock), 0, s, src, nnz,
+                         shift, bits, w.hist, w.nblk_sort);
+      hipLaunchKernelGGL(radix_scan, dim3(1u << bits), dim3(kBlock), 0, s, w.hist, w.nblk_sort,
+                         w.digit_total);
+      hipLaunchKernelGGL(radix_scatter, dim3((unsigned)w.nblk_sort), dim3(kBlock), 0, s, src, dst,
+                         nnz, shift, bits, w.hist, w.digit_total, w.nblk_sort);
+      uint64_t* tmp = src; src = dst; dst = tmp;
+    }
+    sorted = src;
+    // run heads -> segment offsets
+    hipLaunchKernelGGL(heads_count, dim3((unsigned)w.nblk_scan), dim3(kBlock), 0, s, sorted, nnz,
+                       w.blk_heads);
+    hipLaunchKernelGGL(heads_scan, dim3(1), dim3(1024), 0, s, w.blk_heads, w.nblk_scan,
+                       w.num_unique);
+    hipLaunchKernelGGL(heads_write, dim3((unsigned)w.nblk_scan), dim3(kBlock), 0, s, sorted, nnz,
+                       w.blk_heads, w.seg_off, w.tile_first);
+    // segment reduce + update, then the rows that span tiles
+    int log2_glb = ilog2_ceil(plan->max_dim / 4);
+    if (log2_glb > 6) log2_glb = 6;
+    const int groups = kBlock >> log2_glb;
+    const int64_t rblocks = (w.ntiles + groups - 1) / groups;
+    const int64_t blocks_per_xcd = (rblocks + 7) / 8;
+    const int td = (int)plan->table_dtype;
+#define DMT_BWD_CASE(TD)                                                                          \
+  if (td == TD) {                                                                                 \
+    hipLaunchKernelGGL((bwd_reduce_update<TD>), dim3((unsigned)(blocks_per_xcd * 8)),             \
+                       dim3(kBlock), 0, s, plan->d_meta, sorted, nnz, (uint32_t)B, nbags,         \
+                       total_rows, grad_pooled, w.partials, plan->max_dim, log2_glb, w.ntiles,    \
+                       blocks_per_xcd, lr, eps);                                                  \
+    hipLaunchKernelGGL((bwd_fixup_update<TD>), dim3((unsigned)rblocks), dim3(kBlock), 0, s,       \
+                       plan->d_meta, plan->d_row_base, plan->F, sorted, nnz, total_rows,          \
+                       w.seg_off, w.tile_first, w.partials, plan->max_dim, log2_glb, w.ntiles,    \
+                       lr, eps);                                                                  \
+  }
+    DMT_BWD_CASE(DMT_F32) DMT_BWD_CASE(DMT_F16) DMT_BWD_CASE(DMT_BF16)
+#undef DMT_BWD_CASE
+  }
+  if (dbg && (dbg->sorted_keys || dbg->sorted_bag || dbg->unique_keys || dbg->seg_off ||
+              dbg->num_unique)) {
+    const int64_t n = nnz + 1;
+    hipLaunchKernelGGL(bwd_export, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+                       plan->d_row_base, plan->F, sorted, nnz, total_rows, w.seg_off, w.num_unique,
+                       dbg->sorted_keys, dbg->sorted_bag, dbg->unique_keys, dbg->seg_off,
+                       dbg->num_unique);
+  }
+  return hipGetLastError() == hipSuccess ? DMT_OK : DMT_EHIP;
+}
