@@ -1,3 +1,472 @@
+// dmt_tower_module_fwd: the per-tower Tower Module (paper Sec. 3.2, Sec. 4).
+//
+// Every form is a chain of  C = epilogue(A . W^T + b)  contractions over the
+// tower's [B][W_t] block of the pooled tensor:
+//   linear(+ReLU)  one projection                                (Listing 1, c = 0)
+//   dot + linear   pairwise feature dot products z_p, then a projection of
+//                  [z_p | x]                                      (Sec. 3.2, Sec. 4)
+//   cross + linear x_{l+1} = x0 * (W_l x_l + b_l) + x_l, then a projection
+//                                                                 (Listing 2)
+// 16-bit types run on MFMA (v_mfma_f32_32x32x16, float32 accumulate): block tile
+// 128 x 128 x 64, four waves of 64 x 64, operands staged through padded LDS, the
+// next K tile prefetched into registers while the current one is multiplied.
+// All towers of one stage go into ONE launch (a grouped GEMM: block id -> tower,
+// tile), because a single tower's grid cannot fill 256 CUs.  The pairwise dots
+// are a Gram matrix per sample: 32 consecutive (sample, feature) rows form one
+// 32 x 32 MFMA tile whose diagonal blocks hold every sample's dots, so the
+// operand is read once, straight from global memory, as both A and B.
+// float32 towers (a latency-bound toy size) use plain FMA kernels.
+#include <algorithm>
+
 #include "dmt_internal.h"
-extern "C" size_t dmt_tm_workspace_bytes(const dmt_plan*, const dmt_tm_params*, int64_t) { return 0; }
-extern "C" dmt_status dmt_tower_module_fwd(const dmt_plan*, const dmt_tm_params*, const void*, int64_t, void*, dmt_dtype, void*, size_t, void*) { return DMT_ENOTSUP; }
+#include "dmt_device_utils.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kBlock = 256;
+constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int kLdsStride = BK + 8;       // elements; 144-byte rows keep ds_read_b128 conflict-free
+constexpr int kMaxGroups = 16;
+
+enum { EPI_BIAS = 0, EPI_BIAS_RELU = 1, EPI_CROSS = 2 };
+
+// One contraction of a grouped launch.  A is given as two K segments (the dot
+// terms, then the pooled values); a plain GEMM has K0 = 0.
+struct TmGroup {
+  const void* A0;   // [M][lda0], first K0 columns of the operand
+  const void* A1;   // [M][lda1], next K1 columns
+  const void* W;    // [N][ldw], K0 + K1 columns used
+  const void* bias; // [N]
+  const void* X0;   // EPI_CROSS: [M][ldx] (x0); the x_l term is A1
+  void* C;          // [M][ldc]
+  int32_t lda0, K0, lda1, K1, ldw, ldc, ldx, M, N, epi;
+};
+
+struct TmLaunch {
+  int32_t ngroups;
+  int32_t tile_start[kMaxGroups + 1];
+  TmGroup g[kMaxGroups];
+};
+
+template <int DT>
+__device__ __forceinline__ floatx16 mfma32(uint4 a, uint4 b, floatx16 c) {
+  if constexpr (DT == DMT_BF16)
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                   __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8, a),
+                                                  __builtin_bit_cast(halfx8, b), c, 0, 0, 0);
+}
+
+template <int DT> __device__ __forceinline__ float load_elt(const void* p, int64_t i) {
+  if constexpr (DT == DMT_F32) return ((const float*)p)[i];
+  else if constexpr (DT == DMT_F16) return dmt::f16_bits_to_f32(((const uint16_t*)p)[i]);
+  else return dmt::bf16_lo(((const uint16_t*)p)[i]);
+}
+
+template <int DT> __device__ __forceinline__ void store_elt(void* p, int64_t i, float v) {
+  if constexpr (DT == DMT_F32) ((float*)p)[i] = v;
+  else if constexpr (DT == DMT_F16) ((uint16_t*)p)[i] = (uint16_t)dmt::f32_to_f16_bits(v);
+  else ((uint16_t*)p)[i] = (uint16_t)dmt::f32_to_bf16_bits(v);
+}
+
+// ------------------------------------------------------------- MFMA grouped GEMM
+
+template <int DT>
+__global__ __launch_bounds__(kBlock, 2) void tm_gemm_mfma(const TmLaunch L) {
+  __shared__ __attribute__((aligned(16))) uint16_t As[BM * kLdsStride];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[BN * kLdsStride];
+  int gi = 0;
+  while (gi + 1 < L.ngroups && (int)blockIdx.x >= L.tile_start[gi + 1]) ++gi;
+  const TmGroup& G = L.g[gi];
+  const int tile = blockIdx.x - L.tile_start[gi];
+  const int tiles_n = (G.N + BN - 1) / BN;
+  const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+  const int M = G.M, N = G.N, K0 = G.K0, K = G.K0 + G.K1;
+  const uint16_t* A0 = (const uint16_t*)G.A0;
+  const uint16_t* A1 = (const uint16_t*)G.A1;
+  const uint16_t* W = (const uint16_t*)G.W;
+  const int lda0 = G.lda0, lda1 = G.lda1, ldw = G.ldw;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  // staging: chunk c = tid + 256*i covers row c/8, 8 elements at column (c%8)*8
+  const int srow = tid >> 3, scol = (tid & 7) * 8;
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  uint4 ra[4], rb[4];
+  auto load_tile = [&](int kt) {
+    const int k = kt * BK + scol;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int m = m0 + srow + i * 32;
+      ra[i] = make_uint4(0, 0, 0, 0);
+      if (m < M && k < K)
+        ra[i] = (k < K0) ? *(const uint4*)(A0 + (int64_t)m * lda0 + k)
+                         : *(const uint4*)(A1 + (int64_t)m * lda1 + (k - K0));
+      const int n = n0 + srow + i * 32;
+      rb[i] = make_uint4(0, 0, 0, 0);
+      if (n < N && k < K) rb[i] = *(const uint4*)(W + (int64_t)n * ldw + k);
+    }
+  };
+  auto store_tile = [&]() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      *(uint4*)(As + (srow + i * 32) * kLdsStride + scol) = ra[i];
+      *(uint4*)(Bs + (srow + i * 32) * kLdsStride + scol) = rb[i];
+    }
+  };
+
+  const int nk = (K + BK - 1) / BK;
+  load_tile(0);
+  for (int kt = 0; kt < nk; ++kt) {
+    store_tile();
+    __syncthreads();
+    if (kt + 1 < nk) load_tile(kt + 1);
+    const uint16_t* ap = As + (wm * 64 + (lane & 31)) * kLdsStride + (lane >> 5) * 8;
+    const uint16_t* bp = Bs + (wn * 64 + (lane & 31)) * kLdsStride + (lane >> 5) * 8;
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      uint4 a[2], b[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        a[i] = *(const uint4*)(ap + i * 32 * kLdsStride + kk * 16);
+        b[i] = *(const uint4*)(bp + i * 32 * kLdsStride + kk * 16);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = mfma32<DT>(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+
+  // epilogue: lane holds column n = lane % 32 of rows (v/4)*8 + (lane/32)*4 + v%4
+  const int epi = G.epi;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int n = n0 + wn * 64 + j * 32 + (lane & 31);
+    if (n >= N) continue;
+    const float bias = load_elt<DT>(G.bias, n);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int m = m0 + wm * 64 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+        if (m >= M) continue;
+        float y = acc[i][j][v] + bias;
+        if (epi == EPI_BIAS_RELU) y = y > 0.f ? y : 0.f;
+        if (epi == EPI_CROSS)
+          y = load_elt<DT>(G.X0, (int64_t)m * G.ldx + n) * y + load_elt<DT>(G.A1, (int64_t)m * lda1 + n);
+        store_elt<DT>(G.C, (int64_t)m * G.ldc + n, y);
+      }
+    }
+  }
+}
+
+// --------------------------------------------------- plain FMA GEMM (float32)
+
+template <int DT>
+__global__ __launch_bounds__(kBlock) void tm_gemm_simple(const TmLaunch L) {
+  int gi = 0;
+  while (gi + 1 < L.ngroups && (int)blockIdx.x >= L.tile_start[gi + 1]) ++gi;
+  const TmGroup& G = L.g[gi];
+  const int64_t e = (int64_t)(blockIdx.x - L.tile_start[gi]) * kBlock + threadIdx.x;
+  if (e >= (int64_t)G.M * G.N) return;
+  const int m = (int)(e / G.N), n = (int)(e % G.N);
+  float s = 0.f;
+  for (int k = 0; k < G.K0; ++k)
+    s += load_elt<DT>(G.A0, (int64_t)m * G.lda0 + k) * load_elt<DT>(G.W, (int64_t)n * G.ldw + k);
+  for (int k = 0; k < G.K1; ++k)
+    s += load_elt<DT>(G.A1, (int64_t)m * G.lda1 + k) *
+         load_elt<DT>(G.W, (int64_t)n * G.ldw + G.K0 + k);
+  float y = s + load_elt<DT>(G.bias, n);
+  if (G.epi == EPI_BIAS_RELU) y = y > 0.f ? y : 0.f;
+  if (G.epi == EPI_CROSS)
+    y = load_elt<DT>(G.X0, (int64_t)m * G.ldx + n) * y + load_elt<DT>(G.A1, (int64_t)m * G.lda1 + n);
+  store_elt<DT>(G.C, (int64_t)m * G.ldc + n, y);
+}
+
+// ------------------------------------------------------------ pairwise dot terms
+
+// z[s][p(i,j)] = <x[s][i][:], x[s][j][:]>, i < j, p row-major; x is [B][nf][n]
+// contiguous.  One wave per 32 consecutive (sample, feature) rows; needs
+// 32 % nf == 0 and n % 16 == 0.  Columns np .. np_pad-1 of z are zeroed.
+template <int DT>
+__global__ __launch_bounds__(kBlock) void tm_dots_mfma(const void* __restrict__ x, int64_t B,
+                                                       int nf, int n, void* __restrict__ z,
+                                                       int np, int np_pad) {
+  const int lane = threadIdx.x & 63;
+  const int64_t rg = (int64_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
+  const int64_t row0 = rg * 32, nrows = B * nf;
+  if (row0 >= nrows) return;
+  const int64_t r = row0 + (lane & 31);
+  const uint16_t* xp = (const uint16_t*)x + r * n + (lane >> 5) * 8;
+  floatx16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  for (int k = 0; k < n; k += 16) {
+    uint4 a = make_uint4(0, 0, 0, 0);
+    if (r < nrows) a = *(const uint4*)(xp + k);
+    acc = mfma32<DT>(a, a, acc);
+  }
+  const int spg = 32 / nf;                       // samples per row group
+  const int64_t s0 = row0 / nf;
+  const int c = lane & 31, sc = c / nf, j = c % nf;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int rr = (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+    const int i = rr % nf;
+    if (rr / nf == sc && i < j && s0 + sc < B)
+      store_elt<DT>(z, (s0 + sc) * np_pad + (i * (2 * nf - i - 1) / 2 + (j - i - 1)), acc[v]);
+  }
+  const int npad = np_pad - np;
+  if (lane < spg * npad) {
+    const int s = lane / npad, q = lane % npad;
+    if (s0 + s < B) store_elt<DT>(z, (s0 + s) * np_pad + np + q, 0.f);
+  }
+}
+
+// Any nf / n, any dtype: one thread per (sample, term).
+template <int DT>
+__global__ __launch_bounds__(kBlock) void tm_dots_simple(const void* __restrict__ x, int64_t B,
+                                                         int nf, int n, void* __restrict__ z,
+                                                         int np, int np_pad) {
+  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (e >= B * np_pad) return;
+  const int64_t s = e / np_pad;
+  const int p = (int)(e % np_pad);
+  float d = 0.f;
+  if (p < np) {
+    int i = 0, rem = p;
+    while (rem >= nf - 1 - i) { rem -= nf - 1 - i; ++i; }
+    const int j = i + 1 + rem;
+    const int64_t bi = (s * nf + i) * n, bj = (s * nf + j) * n;
+    for (int k = 0; k < n; ++k) d += load_elt<DT>(x, bi + k) * load_elt<DT>(x, bj + k);
+  }
+  store_elt<DT>(z, e, d);
+}
+
+// Projection weights [O][np + Wt] -> [O][np_pad + Wt] with zero columns after the
+// dot terms, so both K segments start 16-byte aligned.
+template <int DT>
+__global__ __launch_bounds__(kBlock) void tm_pack_w(const void* __restrict__ w, int O, int np,
+                                                    int np_pad, int wt, void* __restrict__ wp) {
+  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int kp = np_pad + wt;
+  if (e >= (int64_t)O * kp) return;
+  const int o = (int)(e / kp), k = (int)(e % kp);
+  const int64_t src = (int64_t)o * (np + wt) + (k < np ? k : np + (k - np_pad));
+  if constexpr (DT == DMT_F32) {
+    ((float*)wp)[e] = (k >= np && k < np_pad) ? 0.f : ((const float*)w)[src];
+  } else {
+    ((uint16_t*)wp)[e] = (k >= np && k < np_pad) ? (uint16_t)0 : ((const uint16_t*)w)[src];
+  }
+}
+
+// ----------------------------------------------------------------- host side
+
+struct TowerWs {
+  size_t z_off = 0, wp_off = 0, x_off[2] = {0, 0};
+  int np = 0, np_pad = 0;
+};
+
+// Validates the towers' parameters and lays out the scratch.  Returns total bytes
+// through *bytes.
+dmt_status plan_tm(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, int eb,
+                   std::vector<TowerWs>* ws, size_t* bytes) {
+  size_t off = 0;
+  auto take = [&](size_t b) { size_t o = off; off = dmt_align_up(off + b, 256); return o; };
+  ws->assign(p->T, TowerWs());
+  for (int32_t t = 0; t < p->T; ++t) {
+    const dmt_tm_params& q = tp[t];
+    const int64_t wt = p->tower_width[t];
+    if (q.out_dim <= 0 || !q.w_proj || !q.b_proj) return DMT_EINVAL;
+    if (((uintptr_t)q.w_proj & 15) && q.kind != DMT_TM_DOT_LINEAR) return DMT_EINVAL;
+    TowerWs& w = (*ws)[t];
+    switch (q.kind) {
+      case DMT_TM_LINEAR:
+      case DMT_TM_LINEAR_RELU:
+        break;
+      case DMT_TM_DOT_LINEAR: {
+        const int nf = p->tower_ntab[t];
+        if (p->tower_uniform_dim[t] == 0) return DMT_ENOTSUP;   // dots need one common dim
+        w.np = nf * (nf - 1) / 2;
+        w.np_pad = (w.np + 7) / 8 * 8;
+        w.z_off = take((size_t)B * w.np_pad * eb);
+        w.wp_off = take((size_t)q.out_dim * (w.np_pad + wt) * eb);
+        break;
+      }
+      case DMT_TM_CROSS_LINEAR:
+        if (q.num_cross_layers < 1 || q.num_cross_layers > DMT_MAX_CROSS_LAYERS) return DMT_EINVAL;
+        for (int l = 0; l < q.num_cross_layers; ++l)
+          if (!q.w_cross[l] || !q.b_cross[l] || ((uintptr_t)q.w_cross[l] & 15)) return DMT_EINVAL;
+        w.x_off[0] = take((size_t)B * wt * eb);
+        if (q.num_cross_layers > 1) w.x_off[1] = take((size_t)B * wt * eb);
+        break;
+      default:
+        return DMT_EINVAL;
+    }
+  }
+  *bytes = off;
+  return DMT_OK;
+}
+
+template <int DT>
+void launch_groups(std::vector<TmGroup>& groups, hipStream_t s) {
+  for (size_t first = 0; first < groups.size(); first += kMaxGroups) {
+    TmLaunch L;
+    L.ngroups = (int32_t)std::min<size_t>(kMaxGroups, groups.size() - first);
+    int32_t tiles = 0;
+    for (int i = 0; i < L.ngroups; ++i) {
+      const TmGroup& g = groups[first + i];
+      L.g[i] = g;
+      L.tile_start[i] = tiles;
+      if constexpr (DT == DMT_F32)
+        tiles += (int32_t)(((int64_t)g.M * g.N + kBlock - 1) / kBlock);
+      else
+        tiles += ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+    }
+    L.tile_start[L.ngroups] = tiles;
+    if (tiles == 0) continue;
+    if constexpr (DT == DMT_F32)
+      hipLaunchKernelGGL((tm_gemm_simple<DT>), dim3(tiles), dim3(kBlock), 0, s, L);
+    else
+      hipLaunchKernelGGL((tm_gemm_mfma<DT>), dim3(tiles), dim3(kBlock), 0, s, L);
+  }
+  groups.clear();
+}
+
+template <int DT>
+dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<TowerWs>& ws,
+                  const void* pooled, int64_t B, void* tm_out, char* wsp, hipStream_t s) {
+  constexpr int eb = DT == DMT_F32 ? 4 : 2;
+  const char* x_all = (const char*)pooled;
+  char* y_all = (char*)tm_out;
+  std::vector<int64_t> out_prefix(p->T + 1, 0);
+  for (int32_t t = 0; t < p->T; ++t) out_prefix[t + 1] = out_prefix[t] + tp[t].out_dim;
+  int max_layers = 0;
+
+  // stage 0: dot terms and repacked projection weights
+  for (int32_t t = 0; t < p->T; ++t) {
+    const dmt_tm_params& q = tp[t];
+    if (q.kind == DMT_TM_CROSS_LINEAR) max_layers = std::max(max_layers, q.num_cross_layers);
+    if (q.kind != DMT_TM_DOT_LINEAR) continue;
+    const TowerWs& w = ws[t];
+    const int nf = p->tower_ntab[t], n = p->tower_uniform_dim[t], wt = p->tower_width[t];
+    const void* x = x_all + (size_t)B * p->width_prefix[t] * eb;
+    void* z = wsp + w.z_off;
+    bool mfma_ok = DT != DMT_F32 && 32 % nf == 0 && n % 16 == 0;
+    if (mfma_ok) {
+      if constexpr (DT != DMT_F32) {
+        const int64_t rgs = (B * nf + 31) / 32;
+        hipLaunchKernelGGL((tm_dots_mfma<DT>), dim3((unsigned)((rgs + 3) / 4)), dim3(kBlock), 0, s,
+                           x, B, nf, n, z, w.np, w.np_pad);
+      }
+    } else {
+      const int64_t e = B * w.np_pad;
+      hipLaunchKernelGGL((tm_dots_simple<DT>), dim3((unsigned)((e + kBlock - 1) / kBlock)),
+                         dim3(kBlock), 0, s, x, B, nf, n, z, w.np, w.np_pad);
+    }
+    const int64_t e = (int64_t)q.out_dim * (w.np_pad + wt);
+    hipLaunchKernelGGL((tm_pack_w<DT>), dim3((unsigned)((e + kBlock - 1) / kBlock)), dim3(kBlock),
+                       0, s, q.w_proj, q.out_dim, w.np, w.np_pad, wt, wsp + w.wp_off);
+  }
+
+  // cross layers, one grouped launch per layer index
+  std::vector<TmGroup> groups;
+  for (int l = 0; l < max_layers; ++l) {
+    for (int32_t t = 0; t < p->T; ++t) {
+      const dmt_tm_params& q = tp[t];
+      if (q.kind != DMT_TM_CROSS_LINEAR || l >= q.num_cross_layers) continue;
+      const int wt = p->tower_width[t];
+      const void* x0 = x_all + (size_t)B * p->width_prefix[t] * eb;
+      TmGroup g{};
+      g.A0 = nullptr; g.lda0 = 0; g.K0 = 0;
+      g.A1 = l == 0 ? x0 : (const void*)(wsp + ws[t].x_off[(l - 1) & 1]);
+      g.lda1 = wt; g.K1 = wt;
+      g.W = q.w_cross[l]; g.ldw = wt; g.bias = q.b_cross[l];
+      g.X0 = x0; g.ldx = wt;
+      g.C = wsp + ws[t].x_off[l & 1]; g.ldc = wt;
+      g.M = (int32_t)B; g.N = wt; g.epi = EPI_CROSS;
+      groups.push_back(g);
+    }
+    launch_groups<DT>(groups, s);
+  }
+
+  // projections of every tower
+  for (int32_t t = 0; t < p->T; ++t) {
+    const dmt_tm_params& q = tp[t];
+    const int wt = p->tower_width[t];
+    const void* x = x_all + (size_t)B * p->width_prefix[t] * eb;
+    TmGroup g{};
+    g.A0 = nullptr; g.lda0 = 0; g.K0 = 0;
+    g.A1 = x; g.lda1 = wt; g.K1 = wt;
+    g.W = q.w_proj; g.ldw = wt;
+    if (q.kind == DMT_TM_DOT_LINEAR) {
+      g.A0 = wsp + ws[t].z_off; g.lda0 = ws[t].np_pad; g.K0 = ws[t].np_pad;
+      g.W = wsp + ws[t].wp_off; g.ldw = ws[t].np_pad + wt;
+    } else if (q.kind == DMT_TM_CROSS_LINEAR) {
+      g.A1 = wsp + ws[t].x_off[(q.num_cross_layers - 1) & 1];
+    }
+    g.bias = q.b_proj;
+    g.X0 = nullptr; g.ldx = 0;
+    g.C = y_all + (size_t)B * out_prefix[t] * eb; g.ldc = q.out_dim;
+    g.M = (int32_t)B; g.N = q.out_dim;
+    g.epi = q.kind == DMT_TM_LINEAR_RELU ? EPI_BIAS_RELU : EPI_BIAS;
+    groups.push_back(g);
+  }
+  launch_groups<DT>(groups, s);
+  return hipGetLastError() == hipSuccess ? DMT_OK : DMT_EHIP;
+}
+
+}  // namespace
+
+extern "C" size_t dmt_tm_workspace_bytes(const dmt_plan* plan, const dmt_tm_params* per_tower,
+                                         int64_t B) {
+  if (!plan || !per_tower || B <= 0) return 0;
+  std::vector<TowerWs> ws;
+  size_t bytes = 0;
+  // sized for the wider element type so one figure serves every dtype
+  if (plan_tm(plan, per_tower, B, 4, &ws, &bytes) != DMT_OK) return 0;
+  return bytes;
+}
+
+extern "C" dmt_status dmt_tower_module_fwd(const dmt_plan* plan, const dmt_tm_params* per_tower,
+                                           const void* pooled, int64_t B, void* tm_out,
+                                           dmt_dtype dtype, void* workspace,
+                                           size_t workspace_bytes, void* stream) {
+  if (!plan || !per_tower || !pooled || !tm_out) return DMT_EINVAL;
+  if (B <= 0 || B > plan->max_batch || B >= (1LL << 31)) return DMT_EINVAL;
+  if (dtype != DMT_F32 && dtype != DMT_F16 && dtype != DMT_BF16) return DMT_EINVAL;
+  if (((uintptr_t)pooled & 15) || ((uintptr_t)tm_out & 15)) return DMT_EINVAL;
+  const int eb = dmt_elt_bytes(dtype);
+  for (int32_t t = 0; t < plan->T; ++t)
+    if (plan->tower_width[t] % 8 != 0 && dtype != DMT_F32) return DMT_ENOTSUP;
+  std::vector<TowerWs> ws;
+  size_t bytes = 0;
+  dmt_status st = plan_tm(plan, per_tower, B, eb, &ws, &bytes);
+  if (st != DMT_OK) return st;
+  if (bytes > 0) {
+    if (!workspace || ((uintptr_t)workspace & 255)) return DMT_EINVAL;
+    if (workspace_bytes < bytes) return DMT_ENOMEM;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  char* wsp = (char*)workspace;
+  switch (dtype) {
+    case DMT_F32: return run_tm<DMT_F32>(plan, per_tower, ws, pooled, B, tm_out, wsp, s);
+    case DMT_F16: return run_tm<DMT_F16>(plan, per_tower, ws, pooled, B, tm_out, wsp, s);
+    default: return run_tm<DMT_BF16>(plan, per_tower, ws, pooled, B, tm_out, wsp, s);
+  }
+}

@@ -79,3 +79,56 @@ class DeviceWorkload:
             out.append(flat[base:base + B * wt].reshape(B, wt))
             base += B * wt
         return out
+
+
+class TowerModules:
+    """A workload's Tower-Module weights: encoded once to w.tm_dtype, held on the
+    device for the library and decoded back to float64 for the oracle."""
+
+    def __init__(self, dw: "DeviceWorkload", dtype: str = None):
+        w = dw.w
+        self.dw = dw
+        self.dtype = dtype or w.tm_dtype
+        self.host = wl.tm_weights(w)
+        self.keep = []
+        per_tower = []
+        self.dec = []
+        for t, hw in enumerate(self.host):
+            enc = lambda a: wl.encode(a, self.dtype)
+            dev = lambda a: to_device(enc(a), self.dtype)
+            d = dict(kind=w.tm_kind, out_dim=w.tm_out[t], w_proj=dev(hw["w_proj"]), b_proj=dev(hw["b_proj"]),
+                     w_cross=[dev(a) for a in hw["w_cross"]], b_cross=[dev(a) for a in hw["b_cross"]])
+            self.keep.append(d)
+            per_tower.append(d)
+            dd = lambda a: wl.decode(enc(a), self.dtype)
+            self.dec.append(dict(w_proj=dd(hw["w_proj"]), b_proj=dd(hw["b_proj"]),
+                                 w_cross=[dd(a) for a in hw["w_cross"]], b_cross=[dd(a) for a in hw["b_cross"]]))
+        self.params = dw.dmt.make_tm_params(per_tower)
+        nbytes = dw.dmt.dmt_tm_workspace_bytes(dw.plan, self.params, w.batch)
+        self.workspace = torch.empty(max(nbytes, 256) // 8 + 32, dtype=torch.int64, device="cuda")
+        self.out_widths = list(w.tm_out)
+
+    def run(self, pooled: torch.Tensor) -> torch.Tensor:
+        w = self.dw.w
+        out = torch.full((w.batch * sum(self.out_widths),), float("nan"), dtype=TORCH_DT[self.dtype], device="cuda")
+        self.dw.dmt.dmt_tower_module_fwd(self.dw.plan, self.params, pooled, w.batch, out, self.workspace)
+        torch.cuda.synchronize()
+        return out
+
+    def oracle(self, x_towers):
+        """x_towers: float64 [B, W_t] per tower (the values the TM reads)."""
+        import oracle
+        w = self.dw.w
+        ys = []
+        for t, x in enumerate(x_towers):
+            d = self.dec[t]
+            if w.tm_kind == wl.TM_LINEAR:
+                y = oracle.tm_linear(x, d["w_proj"], d["b_proj"])
+            elif w.tm_kind == wl.TM_LINEAR_RELU:
+                y = oracle.tm_linear(x, d["w_proj"], d["b_proj"], relu=True)
+            elif w.tm_kind == wl.TM_DOT_LINEAR:
+                y = oracle.tm_dot_linear(x, len(w.tower_tables()[t]), d["w_proj"], d["b_proj"])
+            else:
+                y = oracle.tm_cross_linear(x, d["w_cross"], d["b_cross"], d["w_proj"], d["b_proj"])
+            ys.append(y)
+        return ys

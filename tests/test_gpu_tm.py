@@ -1,0 +1,76 @@
+"""GPU parity of dmt_tower_module_fwd against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+from harness import RTOL, DeviceWorkload, TowerModules, assert_close, to_device, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def check_tm(w, chained=False):
+    """TM on the oracle's pooled values (rounded to the pooled dtype), then
+    optionally also the GPU lookup -> GPU TM chain."""
+    dw = DeviceWorkload(w)
+    tm = TowerModules(dw)
+    idx, off = wl.lookup_batch(w)
+    pooled = oracle.lookup_towered(dw.host_tables, w.table_dtype, w.dims, w.table_to_tower, idx, off, w.batch)
+    enc = [oracle.round_to(p, tm.dtype) for p in pooled]
+    x_dev = torch.cat([to_device(e, tm.dtype).reshape(-1) for e in enc])
+    got = to_f64(tm.run(x_dev))
+    x64 = [wl.decode(e, tm.dtype) for e in enc]
+    ref = tm.oracle(x64)
+    rtol = RTOL[tm.dtype]
+    for t, (g, r) in enumerate(zip(dw.split_towers(got, tm.out_widths), ref)):
+        if tm.dtype != "f32":
+            r = wl.decode(oracle.round_to(r, tm.dtype), tm.dtype)
+        assert_close(g, r, rtol, "%s TM tower %d" % (w.name, t))
+    if chained:
+        pooled_gpu = dw.lookup(idx, off, tm.dtype)
+        got2 = to_f64(tm.run(pooled_gpu))
+        for t, (g, r) in enumerate(zip(dw.split_towers(got2, tm.out_widths), ref)):
+            if tm.dtype != "f32":
+                r = wl.decode(oracle.round_to(r, tm.dtype), tm.dtype)
+            assert_close(g, r, rtol if tm.dtype != "f32" else 1e-4, "%s lookup+TM tower %d" % (w.name, t))
+
+
+def test_tiny_linear_relu_f32():
+    check_tm(wl.tiny(), chained=True)
+
+
+def test_mid_scaled_dot_linear_bf16():
+    # 2 towers x 8 features x 128: 28 dots | 1024 -> 256 ; B = 301 leaves ragged M tiles
+    check_tm(wl.scaled(wl.mid(), max_rows=5000, batch=301, num_tables=16), chained=True)
+
+
+def test_large_scaled_cross_linear_bf16():
+    # 2 towers of 16 x 128 = 2048 wide: two 2048 x 2048 cross layers, then 2048 -> 512
+    w = wl.scaled(wl.large(), max_rows=3000, batch=200)
+    sel = [f for f in range(256) if w.table_to_tower[f] in (0, 1)]
+    w.rows = [w.rows[f] for f in sel]; w.dims = [128] * 32
+    w.table_to_tower = [wl.large().table_to_tower[f] for f in sel]
+    w.tm_out = [512, 512]
+    check_tm(w, chained=True)
+
+
+def test_imbalanced_scaled_linear_f16():
+    # towers of unequal width (mixed 32/64/128 dims), Linear -> 128
+    check_tm(wl.scaled(wl.imbalanced(), max_rows=2000, batch=777, num_tables=26), chained=True)
+
+
+def test_dot_linear_odd_feature_count_falls_back():
+    # 3 features per tower do not tile a 32-row MFMA block: plain-FMA dot kernel
+    w = wl.scaled(wl.mid(), max_rows=500, batch=50, num_tables=6)
+    w.table_to_tower = [0, 0, 0, 1, 1, 1]
+    w.tm_out = [40, 24]
+    check_tm(w)
+
+
+def test_dot_linear_f32_and_f16():
+    w = wl.scaled(wl.mid(), max_rows=500, batch=70, num_tables=8)
+    for dt in ("f32", "f16"):
+        w.tm_dtype = dt
+        w.pooled_dtype = dt
+        check_tm(w)
