@@ -1,0 +1,326 @@
+#!/usr/bin/env python3
+"""Benchmark of the DMT tower hot path on one MI355X.
+
+One step = one pass of the whole path over one synthetic batch:
+    dmt_tower_lookup_fwd  ->  dmt_tower_module_fwd  ->  dmt_tower_lookup_bwd_update
+on the "Mid" tables and lookups (64 fp16 tables x 1M rows x D=128, 8 towers of
+8, batch 8192, Poisson(20) bags, Zipf 1.05 ids; dot-product Tower Module to 256
+on bf16 MFMA), with the "Backward" configuration's sorted / segment-reduced
+gradient and in-place rowwise Adagrad.  Inputs are resident in HBM before the
+timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--batches N] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS_16BIT = 2500.0
+RTILE = 128          # sorted records per reduce tile in the backward kernel (for byte accounting)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--batches", type=int, default=8, help="pool of pre-generated id batches")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--workload", default="backward")
+    return ap.parse_args()
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def batch_accounting(w, idx, off):
+    """Per-batch counts the algorithmic byte figures need (numpy only)."""
+    F, B = w.num_tables, w.batch
+    nnz = len(idx)
+    tab = np.repeat(np.arange(F, dtype=np.int64), np.diff(off[::B]))
+    key = np.sort((tab << 32) | idx.astype(np.int64))
+    head = np.ones(nnz, dtype=bool)
+    head[1:] = key[1:] != key[:-1]
+    U = int(head.sum())
+    # runs that cross a reduce-tile boundary are finished by the fix-up kernel
+    edges = np.arange(RTILE, nnz, RTILE)
+    crossing = key[edges] == key[edges - 1]
+    seg_id = np.cumsum(head) - 1
+    span = int(len(np.unique(seg_id[edges[crossing]])))
+    partial_slots = int(crossing.sum()) + span
+    return dict(nnz=nnz, U=U, span=span, partial_slots=partial_slots)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+    import torch
+    import paper_2403_00877_amd as dmt
+    import workloads as wl
+
+    torch.cuda.set_device(0)
+    w = wl.by_name(args.workload)
+    F, B, T = w.num_tables, w.batch, w.num_towers
+    eb = wl.ELT_BYTES[w.table_dtype]
+    eo = wl.ELT_BYTES[w.pooled_dtype]
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+    t0 = time.time()
+    tables = wl.tables_device(w)
+    states = [torch.zeros(r, dtype=torch.float32, device="cuda") for r in w.rows]
+    log("[bench] tables on device: %.1f GB in %.1fs" %
+        (sum(t.numel() * t.element_size() for t in tables) / 1e9, time.time() - t0))
+
+    cache = {}
+    batches = []
+    t0 = time.time()
+    for i in range(args.batches):
+        idx, off = wl.lookup_batch(w, i, cache)
+        acct = batch_accounting(w, idx, off)
+        grad = wl.grad_pooled(w, i)
+        batches.append(dict(idx=torch.from_numpy(idx).cuda(), off=torch.from_numpy(off).cuda(),
+                            grad=torch.from_numpy(grad).cuda(), acct=acct,
+                            host=(idx, off, grad) if i == 0 else None))
+    log("[bench] %d batches generated in %.1fs; nnz %d, unique rows %d (%.0f%% duplicates)" %
+        (len(batches), time.time() - t0, batches[0]["acct"]["nnz"], batches[0]["acct"]["U"],
+         100 * (1 - batches[0]["acct"]["U"] / batches[0]["acct"]["nnz"])))
+    max_nnz = max(b["acct"]["nnz"] for b in batches)
+
+    plan = dmt.dmt_plan_create(w.rows, w.dims, w.table_dtype, T, w.table_to_tower, B, max_nnz)
+    dmt.dmt_plan_bind(plan, tables, states)
+    base, widths, col = dmt.dmt_plan_layout(plan, B)
+
+    def dev(a, dt):
+        t = torch.from_numpy(wl.encode(a, dt))
+        return (t.view(torch.int16).view(torch.bfloat16) if dt == "bf16" else t).cuda()
+
+    tm_host = wl.tm_weights(w)
+    tm_dev = [dict(kind=w.tm_kind, out_dim=w.tm_out[t], w_proj=dev(h["w_proj"], w.tm_dtype),
+                   b_proj=dev(h["b_proj"], w.tm_dtype),
+                   w_cross=[dev(a, w.tm_dtype) for a in h["w_cross"]],
+                   b_cross=[dev(a, w.tm_dtype) for a in h["b_cross"]]) for t, h in enumerate(tm_host)]
+    tm_params = dmt.make_tm_params(tm_dev)
+    tm_ws = torch.empty(max(dmt.dmt_tm_workspace_bytes(plan, tm_params, B), 256), dtype=torch.uint8,
+                        device="cuda")
+    bwd_ws = torch.empty(max(dmt.dmt_bwd_workspace_bytes(plan, B, max_nnz), 256), dtype=torch.uint8,
+                         device="cuda")
+    pooled = torch.empty(base[-1], dtype=tdt[w.pooled_dtype], device="cuda")
+    tm_out = torch.empty(B * sum(w.tm_out), dtype=tdt[w.tm_dtype], device="cuda")
+
+    def step(i):
+        b = batches[i % len(batches)]
+        dmt.dmt_tower_lookup_fwd(plan, b["idx"], b["off"], B, pooled)
+        dmt.dmt_tower_module_fwd(plan, tm_params, pooled, B, tm_out, tm_ws)
+        dmt.dmt_tower_lookup_bwd_update(plan, b["idx"], b["off"], B, b["grad"], w.lr, w.eps, bwd_ws)
+
+    # ---- CPU oracle leg: baseline timing + a live parity check on the same inputs
+    cpu = None
+    if not args.no_cpu:
+        cpu = cpu_leg(dmt, wl, w, plan, tables, states, tm_host, batches[0], pooled, tm_out, tm_params,
+                      tm_ws, bwd_ws, widths)
+        for s in states:                      # restart the optimizer state for the timed run
+            s.zero_()
+
+    # ---- timed region
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    timed = ["lookup_fwd", "tm_gemm", "radix_scatter", "bwd_reduce_update"]
+    name_to_id = {dmt.dmt_kernel_name(i): i for i in range(dmt.DMT_K_COUNT)}
+    dmt.dmt_profile_enable(plan, sum(1 << name_to_id[n] for n in timed))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = dmt.dmt_profile_read(plan)
+    ms_per_step = elapsed * 1e3 / args.steps
+    assert dmt.dmt_last_device_error(plan) == -1
+
+    # ---- per-kernel breakdown (outside the timed region, every family timed)
+    dmt.dmt_profile_enable(plan, (1 << dmt.DMT_K_COUNT) - 1)
+    nb = len(batches)
+    for i in range(nb):
+        step(args.warmup + args.steps + i)
+    full = dmt.dmt_profile_read(plan)
+    dmt.dmt_profile_enable(plan, 0)
+
+    # ---- algorithmic bytes per launch, averaged over the batches the timed steps used
+    used = [batches[(args.warmup + i) % nb]["acct"] for i in range(args.steps)]
+    mean = lambda k: float(np.mean([u[k] for u in used]))
+    nnz, U, span, pslots = mean("nnz"), mean("U"), mean("span"), mean("partial_slots")
+    D = w.dims[0]
+    bags = F * B
+    bytes_of = {
+        # rows + ids + offsets + pooled store
+        "lookup_fwd": nnz * (D * eb + 4) + bags * (8 + D * eo),
+        # sorted records + gradient slices + row/state read-modify-write of rows finished in-tile
+        # + partial sums of rows that span tiles
+        "bwd_reduce_update": nnz * (8 + D * 4) + (U - span) * (2 * D * eb + 8) + pslots * D * 4,
+        # one radix pass: records read and written
+        "radix_scatter": nnz * 16,
+    }
+    kin = w.tm_in_dims()
+    tm_flops = sum(2.0 * B * o * k for o, k in zip(w.tm_out, kin))
+    kernels = {}
+    for name, (ms, n) in sorted(full.items()):
+        per = ms / n
+        kernels[name] = dict(ms_per_launch=round(per, 4), launches_per_step=n // nb,
+                             ms_per_step=round(ms / nb, 4))
+    # dominant kernel by time inside the timed region
+    dom = max(prof.items(), key=lambda kv: kv[1][0])[0]
+    dom_ms = prof[dom][0] / prof[dom][1]
+    if dom in bytes_of:
+        achieved = bytes_of[dom] / (dom_ms * 1e-3) / 1e9
+        roofline = dict(kernel=dom, bound="hbm", achieved=round(achieved, 1), peak=HBM_PEAK_GBS,
+                        unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                        ms_per_launch=round(dom_ms, 4), algorithmic_bytes=int(bytes_of[dom]))
+    else:
+        achieved = tm_flops / (dom_ms * 1e-3) / 1e12
+        roofline = dict(kernel=dom, bound="mfma", achieved=round(achieved, 2),
+                        peak=MFMA_PEAK_TFLOPS_16BIT, unit="TFLOP/s",
+                        frac=round(achieved / MFMA_PEAK_TFLOPS_16BIT, 4), traffic=None,
+                        ms_per_launch=round(dom_ms, 4))
+    others = {}
+    for name in timed:
+        if name == dom or name not in prof:
+            continue
+        ms = prof[name][0] / prof[name][1]
+        if name in bytes_of:
+            g = bytes_of[name] / (ms * 1e-3) / 1e9
+            others[name] = dict(ms_per_launch=round(ms, 4), achieved_GBs=round(g, 1),
+                                frac_hbm=round(g / HBM_PEAK_GBS, 4))
+        elif name == "tm_gemm":
+            tf = tm_flops / (ms * 1e-3) / 1e12
+            tm_bytes = sum(B * (k * eo + o * eo) for o, k in zip(w.tm_out, kin))
+            others[name] = dict(ms_per_launch=round(ms, 4), achieved_TFLOPs=round(tf, 2),
+                                frac_mfma=round(tf / MFMA_PEAK_TFLOPS_16BIT, 4),
+                                achieved_GBs=round(tm_bytes / (ms * 1e-3) / 1e9, 1))
+
+    out = {
+        "metric": "tower lookup+TM samples/sec; achieved HBM GB/s and % of peak (fwd, bwd)",
+        "value": round(B / (ms_per_step * 1e-3), 1),
+        "unit": "samples/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "backward (Mid tables and lookups: lookup fwd + dot-product TM fwd "
+                               "+ sorted segment-reduce bwd + rowwise Adagrad)" if w.name == "backward"
+                   else w.name,
+                   "tables": F, "rows": w.rows[0], "dim": D, "table_dtype": w.table_dtype,
+                   "towers": T, "batch": B, "mean_nnz": int(nnz), "mean_unique_rows": int(U),
+                   "duplicate_fraction": round(1 - U / nnz, 3), "id_batches": nb},
+        "roofline": roofline,
+        "cpu_baseline": cpu["baseline"] if cpu else None,
+        "other_kernels": others,
+        "kernel_breakdown": kernels,
+        "parity_vs_oracle_on_sample": cpu["parity"] if cpu else None,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def cpu_leg(dmt, wl, w, plan, tables, states, tm_host, b0, pooled, tm_out, tm_params, tm_ws, bwd_ws,
+            widths):
+    """Time the CPU oracle on a bounded sample of the workload (the first two
+    towers = 16 of the 64 tables, all 8192 samples of batch 0) and check the GPU
+    step on the same inputs against it."""
+    import torch
+    import oracle
+
+    def assert_close(got, ref, rtol, what):
+        # |got - ref| <= rtol*|ref| + rtol*rms(ref), the tolerance the parity tests use
+        rms = float(np.sqrt(np.mean(ref * ref)))
+        bad = np.abs(got - ref) > rtol * np.abs(ref) + rtol * rms
+        if bad.any():
+            raise AssertionError("%s: %d of %d outside tolerance" % (what, int(bad.sum()), ref.size))
+
+    B = w.batch
+    n_tow = 2
+    tabs = [f for f in range(w.num_tables) if w.table_to_tower[f] < n_tow]
+    nt = len(tabs)
+    assert tabs == list(range(nt)), "sample towers must own the leading tables"
+    idx, off, grad = b0["host"]
+    s_off = off[:nt * B + 1]
+    s_idx = idx[:s_off[-1]]
+    s_dims = w.dims[:nt]
+    s_t2t = w.table_to_tower[:nt]
+    s_grad = grad[:B * sum(widths[:n_tow])]
+    host_tables = [t.cpu().numpy() for t in tables[:nt]]            # fp16 arrays
+    host_states = [np.zeros(w.rows[f], dtype=np.float32) for f in range(nt)]
+    enc = lambda a: wl.encode(a, w.tm_dtype)
+    dec = [dict(w=wl.decode(enc(h["w_proj"]), w.tm_dtype), b=wl.decode(enc(h["b_proj"]), w.tm_dtype))
+           for h in tm_host[:n_tow]]
+    oracle.lib()
+    threads = oracle.threads()
+
+    t0 = time.perf_counter()
+    o_pooled = oracle.lookup_towered(host_tables, w.table_dtype, s_dims, s_t2t, s_idx, s_off, B)
+    o_x = [wl.decode(oracle.round_to(p, w.pooled_dtype), w.pooled_dtype) for p in o_pooled]
+    t1 = time.perf_counter()
+    o_y = [oracle.tm_dot_linear(x, len(w.tower_tables()[t]), dec[t]["w"], dec[t]["b"])
+           for t, x in enumerate(o_x)]
+    t2 = time.perf_counter()
+    o_b = oracle.bwd_update(host_tables, w.table_dtype, host_states, s_dims, s_t2t, s_idx, s_off, B,
+                            s_grad, w.lr, w.eps)
+    t3 = time.perf_counter()
+    t_cpu = t3 - t0
+    frac = nt / w.num_tables
+    log("[bench] oracle on %d/%d tables, %d threads: lookup %.2fs, TM %.2fs, bwd %.2fs" %
+        (nt, w.num_tables, threads, t1 - t0, t2 - t1, t3 - t2))
+
+    # the same step on the GPU, from the same starting tables
+    dmt.dmt_tower_lookup_fwd(plan, b0["idx"], b0["off"], B, pooled)
+    dmt.dmt_tower_module_fwd(plan, tm_params, pooled, B, tm_out, tm_ws)
+    torch.cuda.synchronize()
+    parity = {}
+    try:
+        pos = 0
+        ypos = 0
+        for t in range(n_tow):
+            g = pooled[pos:pos + B * widths[t]].to(torch.float64).cpu().numpy().reshape(B, widths[t])
+            assert_close(g, o_x[t], 2e-2, "pooled tower %d" % t)
+            pos += B * widths[t]
+            gy = tm_out[ypos:ypos + B * w.tm_out[t]].to(torch.float64).cpu().numpy().reshape(B, -1)
+            assert_close(gy, wl.decode(oracle.round_to(o_y[t], w.tm_dtype), w.tm_dtype), 2e-2,
+                         "TM tower %d" % t)
+            ypos += B * w.tm_out[t]
+        parity["lookup_fwd"] = parity["tm_fwd"] = "ok"
+        dmt.dmt_tower_lookup_bwd_update(plan, b0["idx"], b0["off"], B, b0["grad"], w.lr, w.eps, bwd_ws)
+        torch.cuda.synchronize()
+        for f in range(nt):
+            m = o_b["key_table"] == f
+            rows = torch.from_numpy(o_b["key_row"][m]).cuda()
+            got = tables[f][rows].to(torch.float64).cpu().numpy()
+            want = wl.decode(oracle.round_to(o_b["new_rows"][m][:, :w.dims[f]], w.table_dtype), w.table_dtype)
+            assert_close(got, want, 2e-2, "updated rows of table %d" % f)
+            gs = states[f][rows].to(torch.float64).cpu().numpy()
+            assert_close(gs, o_b["new_state"][m], 1e-5, "state of table %d" % f)
+        parity["bwd_update"] = "ok"
+    except AssertionError as e:            # report, do not hide
+        parity["error"] = str(e)[:300]
+        log("[bench] PARITY FAILURE: %s" % e)
+    return dict(
+        baseline=dict(value=round(B / (t_cpu / frac), 1), unit="samples/s", cores=threads,
+                      kind="oracle",
+                      sample="towers 0-1 (16 of 64 tables), all 8192 samples of batch 0: lookup+TM+"
+                             "bwd took %.2f s; value = batch / (time x 64/16)" % t_cpu,
+                      seconds=round(t_cpu, 3)),
+        parity=parity)
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -217,6 +217,37 @@ dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const int32_t* indi
  */
 dmt_status dmt_last_device_error(const dmt_plan* plan, void* stream, int64_t* bad_position);
 
+/*
+ * Kernel timing for benchmarks: HIP events recorded on the caller's stream
+ * right before and after the launches of the selected kernel families.  Off by
+ * default; the events cost about a microsecond each, so select only what is
+ * being measured.
+ */
+typedef enum {
+  DMT_K_LOOKUP_FWD = 0,        /* gather + pool + tower-major store           */
+  DMT_K_TM_DOTS = 1,           /* pairwise dot terms                          */
+  DMT_K_TM_PACK = 2,           /* projection-weight repack for the dot TM     */
+  DMT_K_TM_GEMM = 3,           /* grouped contraction (cross layers, linears) */
+  DMT_K_BWD_KEYS = 4,          /* key build                                   */
+  DMT_K_BWD_SORT_HIST = 5,     /* radix pass: per-block digit histogram       */
+  DMT_K_BWD_SORT_SCAN = 6,     /* radix pass: digit offsets                   */
+  DMT_K_BWD_SORT_SCATTER = 7,  /* radix pass: stable scatter                  */
+  DMT_K_BWD_HEADS = 8,         /* run heads -> segment offsets                */
+  DMT_K_BWD_REDUCE_UPDATE = 9, /* segment reduce + rowwise Adagrad            */
+  DMT_K_BWD_FIXUP = 10,        /* rows whose run spans reduce tiles           */
+  DMT_K_COUNT = 11
+} dmt_kernel_id;
+
+const char* dmt_kernel_name(int32_t kernel_id);
+
+/* Select the kernel families to time (bit i = dmt_kernel_id i); 0 turns timing
+ * off.  Pending measurements are dropped. */
+dmt_status dmt_profile_enable(dmt_plan* plan, uint32_t kernel_mask);
+
+/* Synchronise `stream`, add up the event pairs recorded since the last read:
+ * total_ms and launches are host out [DMT_K_COUNT]; then reset. */
+dmt_status dmt_profile_read(dmt_plan* plan, void* stream, double* total_ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -68,6 +68,10 @@ def _load() -> ctypes.CDLL:
     lib.dmt_bwd_workspace_bytes.restype = sz
     lib.dmt_tower_lookup_bwd_update.argtypes = [vp, vp, vp, i64, i64, vp, f32, f32, vp, sz, vp, vp]
     lib.dmt_last_device_error.argtypes = [vp, vp, ctypes.POINTER(i64)]
+    lib.dmt_kernel_name.restype = ctypes.c_char_p
+    lib.dmt_kernel_name.argtypes = [i32]
+    lib.dmt_profile_enable.argtypes = [vp, ctypes.c_uint32]
+    lib.dmt_profile_read.argtypes = [vp, vp, vp, vp]
     return lib
 
 
@@ -76,7 +80,9 @@ _lib = _load()
 EXPORTS = ["dmt_status_str", "dmt_plan_create", "dmt_plan_destroy", "dmt_plan_layout",
            "dmt_plan_bind", "dmt_tower_lookup_fwd", "dmt_tm_workspace_bytes",
            "dmt_tower_module_fwd", "dmt_bwd_workspace_bytes", "dmt_tower_lookup_bwd_update",
-           "dmt_last_device_error"]
+           "dmt_last_device_error", "dmt_kernel_name", "dmt_profile_enable", "dmt_profile_read"]
+
+DMT_K_COUNT = 11
 
 
 def library_path() -> str:
@@ -215,3 +221,19 @@ def dmt_last_device_error(plan: dmt_plan, stream=None) -> int:
     if code not in (DMT_OK, DMT_EBOUNDS):
         raise DmtError("dmt_last_device_error", code)
     return int(pos.value)
+
+
+def dmt_kernel_name(kernel_id: int) -> str:
+    return _lib.dmt_kernel_name(int(kernel_id)).decode()
+
+
+def dmt_profile_enable(plan: dmt_plan, kernel_mask: int) -> None:
+    _check("dmt_profile_enable", _lib.dmt_profile_enable(plan.handle, kernel_mask))
+
+
+def dmt_profile_read(plan: dmt_plan, stream=None) -> dict:
+    """{kernel name: (total_ms, launches)} for the families timed since the last read."""
+    ms = (ctypes.c_double * DMT_K_COUNT)()
+    n = (ctypes.c_int64 * DMT_K_COUNT)()
+    _check("dmt_profile_read", _lib.dmt_profile_read(plan.handle, _stream(stream), ms, n))
+    return {dmt_kernel_name(i): (ms[i], n[i]) for i in range(DMT_K_COUNT) if n[i]}

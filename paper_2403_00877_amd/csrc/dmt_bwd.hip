@@ -533,15 +533,15 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
 
   if (nnz > 0) {
     // keys
-    hipLaunchKernelGGL(bwd_fill_inert, dim3((unsigned)((nnz + kBlock - 1) / kBlock)), dim3(kBlock),
-                       0, s, w.pk_a, nnz, total_rows);
+    { DmtScope sc_(plan, DMT_K_BWD_KEYS, s); hipLaunchKernelGGL(bwd_fill_inert, dim3((unsigned)((nnz + kBlock - 1) / kBlock)), dim3(kBlock),
+                       0, s, w.pk_a, nnz, total_rows); }
     const double mean_len = (double)nnz / (double)nbags;
     int log2_gl = ilog2_ceil((int64_t)(mean_len + 0.5));
     log2_gl = log2_gl < 2 ? 2 : (log2_gl > 6 ? 6 : log2_gl);
     const unsigned kb_blocks = (nbags + (kBlock >> log2_gl) - 1) / (kBlock >> log2_gl);
-    hipLaunchKernelGGL(bwd_build_keys, dim3(kb_blocks), dim3(kBlock), 0, s, plan->d_meta, indices,
+    { DmtScope sc_(plan, DMT_K_BWD_KEYS, s); hipLaunchKernelGGL(bwd_build_keys, dim3(kb_blocks), dim3(kBlock), 0, s, plan->d_meta, indices,
                        offsets, (uint32_t)B, nbags, nnz, total_rows, w.pk_a, log2_gl,
-                       plan->d_error);
+                       plan->d_error); }
     // stable LSD radix sort over the bits that can be set (values 0..total_rows)
     const int key_bits = ilog2_ceil((int64_t)total_rows + 1);
     const int passes = (key_bits + 7) / 8;
@@ -551,22 +551,22 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
     for (int p = 0; p < passes; ++p) {
       const int shift = p * bits_per;
       const int bits = (key_bits - shift) < bits_per ? (key_bits - shift) : bits_per;
-      hipLaunchKernelGGL(radix_hist, dim3((unsigned)w.nblk_sort), dim3(kBlock), 0, s, src, nnz,
-                         shift, bits, w.hist, w.nblk_sort);
-      hipLaunchKernelGGL(radix_scan, dim3(1u << bits), dim3(kBlock), 0, s, w.hist, w.nblk_sort,
-                         w.digit_total);
-      hipLaunchKernelGGL(radix_scatter, dim3((unsigned)w.nblk_sort), dim3(kBlock), 0, s, src, dst,
-                         nnz, shift, bits, w.hist, w.digit_total, w.nblk_sort);
+      { DmtScope sc_(plan, DMT_K_BWD_SORT_HIST, s); hipLaunchKernelGGL(radix_hist, dim3((unsigned)w.nblk_sort), dim3(kBlock), 0, s, src, nnz,
+                         shift, bits, w.hist, w.nblk_sort); }
+      { DmtScope sc_(plan, DMT_K_BWD_SORT_SCAN, s); hipLaunchKernelGGL(radix_scan, dim3(1u << bits), dim3(kBlock), 0, s, w.hist, w.nblk_sort,
+                         w.digit_total); }
+      { DmtScope sc_(plan, DMT_K_BWD_SORT_SCATTER, s); hipLaunchKernelGGL(radix_scatter, dim3((unsigned)w.nblk_sort), dim3(kBlock), 0, s, src, dst,
+                         nnz, shift, bits, w.hist, w.digit_total, w.nblk_sort); }
       uint64_t* tmp = src; src = dst; dst = tmp;
     }
     sorted = src;
     // run heads -> segment offsets
-    hipLaunchKernelGGL(heads_count, dim3((unsigned)w.nblk_scan), dim3(kBlock), 0, s, sorted, nnz,
-                       w.blk_heads);
-    hipLaunchKernelGGL(heads_scan, dim3(1), dim3(1024), 0, s, w.blk_heads, w.nblk_scan,
-                       w.num_unique);
-    hipLaunchKernelGGL(heads_write, dim3((unsigned)w.nblk_scan), dim3(kBlock), 0, s, sorted, nnz,
-                       w.blk_heads, w.seg_off, w.tile_first);
+    { DmtScope sc_(plan, DMT_K_BWD_HEADS, s); hipLaunchKernelGGL(heads_count, dim3((unsigned)w.nblk_scan), dim3(kBlock), 0, s, sorted, nnz,
+                       w.blk_heads); }
+    { DmtScope sc_(plan, DMT_K_BWD_HEADS, s); hipLaunchKernelGGL(heads_scan, dim3(1), dim3(1024), 0, s, w.blk_heads, w.nblk_scan,
+                       w.num_unique); }
+    { DmtScope sc_(plan, DMT_K_BWD_HEADS, s); hipLaunchKernelGGL(heads_write, dim3((unsigned)w.nblk_scan), dim3(kBlock), 0, s, sorted, nnz,
+                       w.blk_heads, w.seg_off, w.tile_first); }
     // segment reduce + update, then the rows that span tiles
     int log2_glb = ilog2_ceil(plan->max_dim / 4);
     if (log2_glb > 6) log2_glb = 6;
@@ -576,14 +576,14 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
     const int td = (int)plan->table_dtype;
 #define DMT_BWD_CASE(TD)                                                                          \
   if (td == TD) {                                                                                 \
-    hipLaunchKernelGGL((bwd_reduce_update<TD>), dim3((unsigned)(blocks_per_xcd * 8)),             \
+    { DmtScope sc_(plan, DMT_K_BWD_REDUCE_UPDATE, s); hipLaunchKernelGGL((bwd_reduce_update<TD>), dim3((unsigned)(blocks_per_xcd * 8)),             \
                        dim3(kBlock), 0, s, plan->d_meta, sorted, nnz, (uint32_t)B, nbags,         \
                        total_rows, grad_pooled, w.partials, plan->max_dim, log2_glb, w.ntiles,    \
-                       blocks_per_xcd, lr, eps);                                                  \
-    hipLaunchKernelGGL((bwd_fixup_update<TD>), dim3((unsigned)rblocks), dim3(kBlock), 0, s,       \
+                       blocks_per_xcd, lr, eps); }                                                  \
+    { DmtScope sc_(plan, DMT_K_BWD_FIXUP, s); hipLaunchKernelGGL((bwd_fixup_update<TD>), dim3((unsigned)rblocks), dim3(kBlock), 0, s,       \
                        plan->d_meta, plan->d_row_base, plan->F, sorted, nnz, total_rows,          \
                        w.seg_off, w.tile_first, w.partials, plan->max_dim, log2_glb, w.ntiles,    \
-                       lr, eps);                                                                  \
+                       lr, eps); }                                                                  \
   }
     DMT_BWD_CASE(DMT_F32) DMT_BWD_CASE(DMT_F16) DMT_BWD_CASE(DMT_BF16)
 #undef DMT_BWD_CASE

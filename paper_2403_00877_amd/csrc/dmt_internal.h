@@ -34,6 +34,14 @@ struct DmtDimClass {
   int32_t first;         // offset into class_tables
 };
 
+// Event pairs around selected launches (dmt_profile_*).
+struct DmtProfile {
+  struct Rec { hipEvent_t a, b; int id; };
+  uint32_t mask = 0;
+  std::vector<Rec> pending;
+  std::vector<hipEvent_t> pool;
+};
+
 struct dmt_plan {
   int32_t F = 0, T = 0;
   dmt_dtype table_dtype = DMT_F32;
@@ -55,6 +63,27 @@ struct dmt_plan {
   int32_t* d_class_tables = nullptr;       // [F]
   int64_t* d_row_base = nullptr;           // [F+1]
   unsigned long long* d_error = nullptr;   // smallest bad position, ~0 = none
+  mutable DmtProfile prof;
+};
+
+// Times everything launched on `s` during its lifetime when family `id` is selected.
+struct DmtScope {
+  const dmt_plan* p;
+  hipStream_t s;
+  hipEvent_t b = nullptr;
+  DmtScope(const dmt_plan* plan, int id, hipStream_t stream) : p(plan), s(stream) {
+    DmtProfile& pr = plan->prof;
+    if (!(pr.mask & (1u << id))) return;
+    hipEvent_t ev[2];
+    for (int i = 0; i < 2; ++i) {
+      if (!pr.pool.empty()) { ev[i] = pr.pool.back(); pr.pool.pop_back(); }
+      else if (hipEventCreate(&ev[i]) != hipSuccess) return;
+    }
+    (void)hipEventRecord(ev[0], s);
+    pr.pending.push_back({ev[0], ev[1], id});
+    b = ev[1];
+  }
+  ~DmtScope() { if (b) (void)hipEventRecord(b, s); }
 };
 
 static inline int dmt_elt_bytes(dmt_dtype t) { return t == DMT_F32 ? 4 : 2; }

@@ -105,6 +105,10 @@ extern "C" dmt_status dmt_plan_create(dmt_plan** out, int32_t num_tables, const 
 }
 
 static void release_device(dmt_plan* p) {
+  for (auto& r : p->prof.pending) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  for (auto& e : p->prof.pool) (void)hipEventDestroy(e);
+  p->prof.pending.clear();
+  p->prof.pool.clear();
   if (p->d_meta) (void)hipFree(p->d_meta);
   if (p->d_class_tables) (void)hipFree(p->d_class_tables);
   if (p->d_row_base) (void)hipFree(p->d_row_base);
@@ -182,4 +186,39 @@ extern "C" dmt_status dmt_last_device_error(const dmt_plan* plan, void* stream,
   DMT_HIP_TRY(hipStreamSynchronize(s));
   *bad_position = (int64_t)v;
   return DMT_EBOUNDS;
+}
+
+extern "C" const char* dmt_kernel_name(int32_t id) {
+  static const char* names[DMT_K_COUNT] = {
+      "lookup_fwd", "tm_dots", "tm_pack_w", "tm_gemm", "bwd_build_keys", "radix_hist",
+      "radix_scan", "radix_scatter", "bwd_heads", "bwd_reduce_update", "bwd_fixup_update"};
+  return (id >= 0 && id < DMT_K_COUNT) ? names[id] : "?";
+}
+
+static void drop_pending(DmtProfile& pr) {
+  for (auto& r : pr.pending) { pr.pool.push_back(r.a); pr.pool.push_back(r.b); }
+  pr.pending.clear();
+}
+
+extern "C" dmt_status dmt_profile_enable(dmt_plan* plan, uint32_t kernel_mask) {
+  if (!plan) return DMT_EINVAL;
+  (void)hipDeviceSynchronize();
+  drop_pending(plan->prof);
+  plan->prof.mask = kernel_mask;
+  return DMT_OK;
+}
+
+extern "C" dmt_status dmt_profile_read(dmt_plan* plan, void* stream, double* total_ms,
+                                       int64_t* launches) {
+  if (!plan || !total_ms || !launches) return DMT_EINVAL;
+  for (int i = 0; i < DMT_K_COUNT; ++i) { total_ms[i] = 0.0; launches[i] = 0; }
+  DMT_HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+  for (auto& r : plan->prof.pending) {
+    float ms = 0.f;
+    DMT_HIP_TRY(hipEventElapsedTime(&ms, r.a, r.b));
+    total_ms[r.id] += ms;
+    launches[r.id] += 1;
+  }
+  drop_pending(plan->prof);
+  return DMT_OK;
 }

@@ -324,7 +324,7 @@ dmt_status plan_tm(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, int eb
 }
 
 template <int DT>
-void launch_groups(std::vector<TmGroup>& groups, hipStream_t s) {
+void launch_groups(const dmt_plan* p, std::vector<TmGroup>& groups, hipStream_t s) {
   for (size_t first = 0; first < groups.size(); first += kMaxGroups) {
     TmLaunch L;
     L.ngroups = (int32_t)std::min<size_t>(kMaxGroups, groups.size() - first);
@@ -341,9 +341,9 @@ void launch_groups(std::vector<TmGroup>& groups, hipStream_t s) {
     L.tile_start[L.ngroups] = tiles;
     if (tiles == 0) continue;
     if constexpr (DT == DMT_F32)
-      hipLaunchKernelGGL((tm_gemm_simple<DT>), dim3(tiles), dim3(kBlock), 0, s, L);
+      { DmtScope sc_(p, DMT_K_TM_GEMM, s); hipLaunchKernelGGL((tm_gemm_simple<DT>), dim3(tiles), dim3(kBlock), 0, s, L); }
     else
-      hipLaunchKernelGGL((tm_gemm_mfma<DT>), dim3(tiles), dim3(kBlock), 0, s, L);
+      { DmtScope sc_(p, DMT_K_TM_GEMM, s); hipLaunchKernelGGL((tm_gemm_mfma<DT>), dim3(tiles), dim3(kBlock), 0, s, L); }
   }
   groups.clear();
 }
@@ -371,17 +371,17 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
     if (mfma_ok) {
       if constexpr (DT != DMT_F32) {
         const int64_t rgs = (B * nf + 31) / 32;
-        hipLaunchKernelGGL((tm_dots_mfma<DT>), dim3((unsigned)((rgs + 3) / 4)), dim3(kBlock), 0, s,
-                           x, B, nf, n, z, w.np, w.np_pad);
+        { DmtScope sc_(p, DMT_K_TM_DOTS, s); hipLaunchKernelGGL((tm_dots_mfma<DT>), dim3((unsigned)((rgs + 3) / 4)), dim3(kBlock), 0, s,
+                           x, B, nf, n, z, w.np, w.np_pad); }
       }
     } else {
       const int64_t e = B * w.np_pad;
-      hipLaunchKernelGGL((tm_dots_simple<DT>), dim3((unsigned)((e + kBlock - 1) / kBlock)),
-                         dim3(kBlock), 0, s, x, B, nf, n, z, w.np, w.np_pad);
+      { DmtScope sc_(p, DMT_K_TM_DOTS, s); hipLaunchKernelGGL((tm_dots_simple<DT>), dim3((unsigned)((e + kBlock - 1) / kBlock)),
+                         dim3(kBlock), 0, s, x, B, nf, n, z, w.np, w.np_pad); }
     }
     const int64_t e = (int64_t)q.out_dim * (w.np_pad + wt);
-    hipLaunchKernelGGL((tm_pack_w<DT>), dim3((unsigned)((e + kBlock - 1) / kBlock)), dim3(kBlock),
-                       0, s, q.w_proj, q.out_dim, w.np, w.np_pad, wt, wsp + w.wp_off);
+    { DmtScope sc_(p, DMT_K_TM_PACK, s); hipLaunchKernelGGL((tm_pack_w<DT>), dim3((unsigned)((e + kBlock - 1) / kBlock)), dim3(kBlock),
+                       0, s, q.w_proj, q.out_dim, w.np, w.np_pad, wt, wsp + w.wp_off); }
   }
 
   // cross layers, one grouped launch per layer index
@@ -402,7 +402,7 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
       g.M = (int32_t)B; g.N = wt; g.epi = EPI_CROSS;
       groups.push_back(g);
     }
-    launch_groups<DT>(groups, s);
+    launch_groups<DT>(p, groups, s);
   }
 
   // projections of every tower
@@ -427,7 +427,7 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
     g.epi = q.kind == DMT_TM_LINEAR_RELU ? EPI_BIAS_RELU : EPI_BIAS;
     groups.push_back(g);
   }
-  launch_groups<DT>(groups, s);
+  launch_groups<DT>(p, groups, s);
   return hipGetLastError() == hipSuccess ? DMT_OK : DMT_EHIP;
 }
 
