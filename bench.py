@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--batches", type=int, default=8, help="pool of pre-generated id batches")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--workload", default="backward")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run dmt_calibration_copy on 1 GiB three times (for rocprofv3 --pmc runs)")
     return ap.parse_args()
 
 
@@ -156,6 +158,13 @@ def main():
         step(args.warmup + args.steps + i)
     full = dmt.dmt_profile_read(plan)
     dmt.dmt_profile_enable(plan, 0)
+
+    if args.calibrate:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        c = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+        for _ in range(3):
+            dmt.dmt_calibration_copy(a, c)
+        torch.cuda.synchronize()
 
     # ---- algorithmic bytes per launch, averaged over the batches the timed steps used
     used = [batches[(args.warmup + i) % nb]["acct"] for i in range(args.steps)]

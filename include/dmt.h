@@ -248,6 +248,14 @@ dmt_status dmt_profile_enable(dmt_plan* plan, uint32_t kernel_mask);
  * total_ms and launches are host out [DMT_K_COUNT]; then reset. */
 dmt_status dmt_profile_read(dmt_plan* plan, void* stream, double* total_ms, int64_t* launches);
 
+/*
+ * Plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers
+ * 16-byte aligned) by a grid-stride kernel named dmt_copy_kernel.  It exists so
+ * that hardware byte counters can be calibrated against a kernel whose traffic
+ * is known exactly: `bytes` read and `bytes` written.
+ */
+dmt_status dmt_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

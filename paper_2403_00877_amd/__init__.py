@@ -7,4 +7,4 @@ from .binding import (  # noqa: F401
     dmt_tower_lookup_fwd, make_tm_params, dmt_tm_workspace_bytes, dmt_tower_module_fwd,
     dmt_bwd_workspace_bytes, dmt_tower_lookup_bwd_update, dmt_last_device_error,
     status_str, library_path, dmt_kernel_name, dmt_profile_enable, dmt_profile_read,
-    DMT_K_COUNT, EXPORTS)
+    DMT_K_COUNT, EXPORTS, dmt_calibration_copy)

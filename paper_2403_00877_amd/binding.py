@@ -72,6 +72,7 @@ def _load() -> ctypes.CDLL:
     lib.dmt_kernel_name.argtypes = [i32]
     lib.dmt_profile_enable.argtypes = [vp, ctypes.c_uint32]
     lib.dmt_profile_read.argtypes = [vp, vp, vp, vp]
+    lib.dmt_calibration_copy.argtypes = [vp, vp, sz, vp]
     return lib
 
 
@@ -80,7 +81,8 @@ _lib = _load()
 EXPORTS = ["dmt_status_str", "dmt_plan_create", "dmt_plan_destroy", "dmt_plan_layout",
            "dmt_plan_bind", "dmt_tower_lookup_fwd", "dmt_tm_workspace_bytes",
            "dmt_tower_module_fwd", "dmt_bwd_workspace_bytes", "dmt_tower_lookup_bwd_update",
-           "dmt_last_device_error", "dmt_kernel_name", "dmt_profile_enable", "dmt_profile_read"]
+           "dmt_last_device_error", "dmt_kernel_name", "dmt_profile_enable", "dmt_profile_read",
+           "dmt_calibration_copy"]
 
 DMT_K_COUNT = 11
 
@@ -237,3 +239,9 @@ def dmt_profile_read(plan: dmt_plan, stream=None) -> dict:
     n = (ctypes.c_int64 * DMT_K_COUNT)()
     _check("dmt_profile_read", _lib.dmt_profile_read(plan.handle, _stream(stream), ms, n))
     return {dmt_kernel_name(i): (ms[i], n[i]) for i in range(DMT_K_COUNT) if n[i]}
+
+
+def dmt_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() >= nbytes
+    _check("dmt_calibration_copy", _lib.dmt_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)))

@@ -216,28 +216,44 @@ __global__ __launch_bounds__(kBlock) void radix_scatter(
 
 // ------------------------------------------------- run heads, segment offsets
 
-__device__ __forceinline__ bool is_head(const uint64_t* pk, int64_t i) {
-  return i == 0 || (uint32_t)(pk[i] >> 32) != (uint32_t)(pk[i - 1] >> 32);
+// Run-head flags of the 1024 consecutive records a wave owns inside its block's
+// tile, as 16 ballots (iteration i covers records i*64 .. i*64+63, one per lane,
+// so every load is one coalesced 512-byte line set).  Returns the head count.
+__device__ __forceinline__ uint32_t wave_head_ballots(const uint64_t* __restrict__ pk, int64_t nnz,
+                                                      int64_t wave_base,
+                                                      uint64_t (&ballots)[kScanItems]) {
+  const int lane = threadIdx.x & 63;
+  uint32_t count = 0;
+  uint32_t carry = 0;                                  // key of the record before this iteration
+  if (wave_base > 0 && wave_base <= nnz) carry = (uint32_t)(pk[wave_base - 1] >> 32);
+#pragma unroll
+  for (int i = 0; i < kScanItems; ++i) {
+    const int64_t p = wave_base + i * 64 + lane;
+    const uint32_t k = p < nnz ? (uint32_t)(pk[p] >> 32) : 0;
+    uint32_t prev = __shfl_up(k, 1);
+    if (lane == 0) prev = carry;
+    const bool head = p < nnz && (p == 0 || k != prev);
+    ballots[i] = __ballot(head);
+    count += (uint32_t)__popcll(ballots[i]);
+    carry = __shfl(k, 63);
+  }
+  return count;
 }
 
 __global__ __launch_bounds__(kBlock) void heads_count(const uint64_t* __restrict__ pk, int64_t nnz,
                                                       uint32_t* __restrict__ blk_heads) {
-  __shared__ uint32_t sm[8];
-  const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
-  uint32_t c = 0;
-  uint32_t prev = base > 0 && base <= nnz ? (uint32_t)(pk[base - 1] >> 32) : 0;
-#pragma unroll
-  for (int i = 0; i < kScanItems; ++i) {
-    const int64_t p = base + i;
-    if (p < nnz) {
-      const uint32_t k = (uint32_t)(pk[p] >> 32);
-      c += (p == 0 || k != prev) ? 1u : 0u;
-      prev = k;
-    }
+  __shared__ uint32_t sm[kBlock / 64];
+  const int wave = threadIdx.x >> 6;
+  uint64_t ballots[kScanItems];
+  const uint32_t c = wave_head_ballots(
+      pk, nnz, (int64_t)blockIdx.x * kScanTile + (int64_t)wave * (kScanItems * 64), ballots);
+  if ((threadIdx.x & 63) == 0) sm[wave] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t t = 0;
+    for (int w = 0; w < kBlock / 64; ++w) t += sm[w];
+    blk_heads[blockIdx.x] = t;
   }
-  uint32_t total;
-  (void)dmt::block_exclusive_scan<kBlock / 64>(c, sm, total);
-  if (threadIdx.x == 0) blk_heads[blockIdx.x] = total;
 }
 
 // Single block: exclusive scan of the per-block head counts; total = number of
@@ -261,29 +277,27 @@ __global__ __launch_bounds__(1024) void heads_scan(uint32_t* __restrict__ blk_he
 __global__ __launch_bounds__(kBlock) void heads_write(
     const uint64_t* __restrict__ pk, int64_t nnz, const uint32_t* __restrict__ blk_heads,
     uint32_t* __restrict__ seg_off, uint32_t* __restrict__ tile_first) {
-  __shared__ uint32_t sm[8];
-  const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
-  uint32_t flags = 0, c = 0;
-  uint32_t prev = base > 0 && base <= nnz ? (uint32_t)(pk[base - 1] >> 32) : 0;
+  __shared__ uint32_t sm[kBlock / 64];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int64_t wave_base = (int64_t)blockIdx.x * kScanTile + (int64_t)wave * (kScanItems * 64);
+  uint64_t ballots[kScanItems];
+  const uint32_t c = wave_head_ballots(pk, nnz, wave_base, ballots);
+  if (lane == 0) sm[wave] = c;
+  __syncthreads();
+  uint32_t before = blk_heads[blockIdx.x];              // run heads before this wave's records
+  for (int w = 0; w < wave; ++w) before += sm[w];
+  const uint64_t lt = (1ULL << lane) - 1;
 #pragma unroll
   for (int i = 0; i < kScanItems; ++i) {
-    const int64_t p = base + i;
+    const int64_t p = wave_base + i * 64 + lane;
+    const uint32_t mine = before + (uint32_t)__popcll(ballots[i] & lt);   // heads before p
+    const bool head = (ballots[i] >> lane) & 1;
     if (p < nnz) {
-      const uint32_t k = (uint32_t)(pk[p] >> 32);
-      if (p == 0 || k != prev) { flags |= 1u << i; ++c; }
-      prev = k;
+      if ((p & (kReduceTile - 1)) == 0) tile_first[p / kReduceTile] = mine;
+      if (head) seg_off[mine] = (uint32_t)p;
+      if (p == nnz - 1) seg_off[mine + (head ? 1 : 0)] = (uint32_t)nnz;
     }
-  }
-  uint32_t total;
-  uint32_t before = blk_heads[blockIdx.x] + dmt::block_exclusive_scan<kBlock / 64>(c, sm, total);
-#pragma unroll
-  for (int i = 0; i < kScanItems; ++i) {
-    const int64_t p = base + i;
-    if (p < nnz) {
-      if ((p & (kReduceTile - 1)) == 0) tile_first[p / kReduceTile] = before;
-      if (flags & (1u << i)) seg_off[before++] = (uint32_t)p;
-      if (p == nnz - 1) seg_off[before] = (uint32_t)nnz;
-    }
+    before += (uint32_t)__popcll(ballots[i]);
   }
 }
 
@@ -291,7 +305,7 @@ __global__ __launch_bounds__(kBlock) void heads_write(
 
 // One rowwise-Adagrad step on row `row` of table f with summed gradient g (the
 // group's lanes hold 4 consecutive columns each; lanes past D hold zeros).
-template <int TD>
+template <int TD, bool NT = false>
 __device__ __forceinline__ void apply_row_update(const DmtTableMeta* __restrict__ meta, uint32_t f,
                                                  uint32_t row, float4 g, int gl, int GL, float lr,
                                                  float eps) {
@@ -304,17 +318,18 @@ __device__ __forceinline__ void apply_row_update(const DmtTableMeta* __restrict_
   if (gl * 4 < D) {
     if constexpr (TD == DMT_F32) {
       float4* w = (float4*)((float*)meta[f].table + (int64_t)row * D) + gl;
-      float4 v = *w;
+      float4 v = NT ? dmt::nt_load(w) : *w;
       v.x -= step * g.x; v.y -= step * g.y; v.z -= step * g.z; v.w -= step * g.w;
-      *w = v;
+      if (NT) dmt::nt_store(v, w); else *w = v;
     } else {
       uint2* w = (uint2*)((uint16_t*)meta[f].table + (int64_t)row * D) + gl;
-      const uint2 u = *w;
+      const uint2 u = NT ? dmt::nt_load(w) : *w;
       float a, b, c, d;
       dmt::unpack2<TD>(u.x, a, b);
       dmt::unpack2<TD>(u.y, c, d);
       a -= step * g.x; b -= step * g.y; c -= step * g.z; d -= step * g.w;
-      *w = make_uint2(dmt::pack2<TD>(a, b), dmt::pack2<TD>(c, d));
+      const uint2 nu = make_uint2(dmt::pack2<TD>(a, b), dmt::pack2<TD>(c, d));
+      if (NT) dmt::nt_store(nu, w); else *w = nu;
     }
   }
   if (gl == 0) state[row] = st;
@@ -330,7 +345,7 @@ __device__ __forceinline__ void store_partial(float* __restrict__ partials, int6
 // is applied to its row at once; the piece of a run that continues from the
 // previous tile goes to partial slot 2t, the piece of a run that starts here
 // and continues into the next tile goes to slot 2t + 1.
-template <int TD>
+template <int TD, bool NT>
 __global__ __launch_bounds__(kBlock) void bwd_reduce_update(
     const DmtTableMeta* __restrict__ meta, const uint64_t* __restrict__ pk, int64_t nnz, uint32_t B,
     uint32_t nbags, uint32_t total_rows, const float* __restrict__ grad,
@@ -393,8 +408,8 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update(
             // the run that just ended lies inside the tile unless it came in from the left
             if (cur_key < total_rows) {
               if (first_run && cont_prev) store_partial(partials, 2 * t, Dmax, gl, acc);
-              else apply_row_update<TD>(meta, cur_f, cur_key - (uint32_t)meta[cur_f].row_base, acc,
-                                        gl, GL, lr, eps);
+              else apply_row_update<TD, NT>(meta, cur_f, cur_key - (uint32_t)meta[cur_f].row_base,
+                                            acc, gl, GL, lr, eps);
             }
             acc = make_float4(0.f, 0.f, 0.f, 0.f);
             cur_key = k;
@@ -410,8 +425,8 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update(
   if (cur_key < total_rows) {
     if (first_run && cont_prev) store_partial(partials, 2 * t, Dmax, gl, acc);
     else if (cont_next) store_partial(partials, 2 * t + 1, Dmax, gl, acc);
-    else apply_row_update<TD>(meta, cur_f, cur_key - (uint32_t)meta[cur_f].row_base, acc, gl, GL,
-                              lr, eps);
+    else apply_row_update<TD, NT>(meta, cur_f, cur_key - (uint32_t)meta[cur_f].row_base, acc, gl,
+                                  GL, lr, eps);
   }
 }
 
@@ -462,7 +477,7 @@ __global__ __launch_bounds__(kBlock) void bwd_fixup_update(
     }
   }
   const uint32_t f = table_of(row_base, F, k_last);
-  apply_row_update<TD>(meta, f, k_last - (uint32_t)row_base[f], acc, gl, GL, lr, eps);
+  apply_row_update<TD, false>(meta, f, k_last - (uint32_t)row_base[f], acc, gl, GL, lr, eps);
 }
 
 // ------------------------------------------------------------- parity exports
@@ -574,12 +589,22 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
     const int64_t rblocks = (w.ntiles + groups - 1) / groups;
     const int64_t blocks_per_xcd = (rblocks + 7) / 8;
     const int td = (int)plan->table_dtype;
+    const bool nt = dmt::env_int("DMT_BWD_NT", 0) != 0;
 #define DMT_BWD_CASE(TD)                                                                          \
   if (td == TD) {                                                                                 \
-    { DmtScope sc_(plan, DMT_K_BWD_REDUCE_UPDATE, s); hipLaunchKernelGGL((bwd_reduce_update<TD>), dim3((unsigned)(blocks_per_xcd * 8)),             \
-                       dim3(kBlock), 0, s, plan->d_meta, sorted, nnz, (uint32_t)B, nbags,         \
-                       total_rows, grad_pooled, w.partials, plan->max_dim, log2_glb, w.ntiles,    \
-                       blocks_per_xcd, lr, eps); }                                                  \
+    {                                                                                             \
+      DmtScope sc_(plan, DMT_K_BWD_REDUCE_UPDATE, s);                                             \
+      if (nt)                                                                                     \
+        hipLaunchKernelGGL((bwd_reduce_update<TD, true>), dim3((unsigned)(blocks_per_xcd * 8)),   \
+                           dim3(kBlock), 0, s, plan->d_meta, sorted, nnz, (uint32_t)B, nbags,     \
+                           total_rows, grad_pooled, w.partials, plan->max_dim, log2_glb,          \
+                           w.ntiles, blocks_per_xcd, lr, eps);                                    \
+      else                                                                                        \
+        hipLaunchKernelGGL((bwd_reduce_update<TD, false>), dim3((unsigned)(blocks_per_xcd * 8)),  \
+                           dim3(kBlock), 0, s, plan->d_meta, sorted, nnz, (uint32_t)B, nbags,     \
+                           total_rows, grad_pooled, w.partials, plan->max_dim, log2_glb,          \
+                           w.ntiles, blocks_per_xcd, lr, eps);                                    \
+    }                                                                                             \
     { DmtScope sc_(plan, DMT_K_BWD_FIXUP, s); hipLaunchKernelGGL((bwd_fixup_update<TD>), dim3((unsigned)rblocks), dim3(kBlock), 0, s,       \
                        plan->d_meta, plan->d_row_base, plan->F, sorted, nnz, total_rows,          \
                        w.seg_off, w.tile_first, w.partials, plan->max_dim, log2_glb, w.ntiles,    \

@@ -93,6 +93,37 @@ __device__ __forceinline__ void store_chunk(void* base, int64_t off, const float
   }
 }
 
+// Loads / stores that tell the caches the line will not be reused (streaming
+// row traffic must not evict data that is gathered repeatedly).
+typedef float dmt_f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int dmt_u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int dmt_u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float4 nt_load(const float4* p) {
+  const dmt_f32x4 v = __builtin_nontemporal_load((const dmt_f32x4*)p);
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void nt_store(float4 v, float4* p) {
+  dmt_f32x4 t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, (dmt_f32x4*)p);
+}
+__device__ __forceinline__ uint2 nt_load(const uint2* p) {
+  const dmt_u32x2 v = __builtin_nontemporal_load((const dmt_u32x2*)p);
+  return make_uint2(v.x, v.y);
+}
+__device__ __forceinline__ void nt_store(uint2 v, uint2* p) {
+  dmt_u32x2 t = {v.x, v.y};
+  __builtin_nontemporal_store(t, (dmt_u32x2*)p);
+}
+__device__ __forceinline__ uint4 nt_load(const uint4* p) {
+  const dmt_u32x4 v = __builtin_nontemporal_load((const dmt_u32x4*)p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void nt_store(uint4 v, uint4* p) {
+  dmt_u32x4 t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, (dmt_u32x4*)p);
+}
+
 // Development knob: integer from the environment, `dflt` when unset.
 static inline int env_int(const char* name, int dflt) {
   const char* v = getenv(name);

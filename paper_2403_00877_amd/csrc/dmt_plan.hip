@@ -222,3 +222,18 @@ extern "C" dmt_status dmt_profile_read(dmt_plan* plan, void* stream, double* tot
   drop_pending(plan->prof);
   return DMT_OK;
 }
+
+__global__ __launch_bounds__(256) void dmt_copy_kernel(uint4* __restrict__ dst,
+                                                       const uint4* __restrict__ src, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256)
+    dst[i] = src[i];
+}
+
+extern "C" dmt_status dmt_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15))
+    return DMT_EINVAL;
+  if (bytes == 0) return DMT_OK;
+  hipLaunchKernelGGL(dmt_copy_kernel, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (uint4*)dst,
+                     (const uint4*)src, bytes / 16);
+  return hipGetLastError() == hipSuccess ? DMT_OK : DMT_EHIP;
+}

@@ -200,19 +200,43 @@ __global__ __launch_bounds__(kBlock) void tm_gemm_simple(const TmLaunch L) {
 
 // ------------------------------------------------------------ pairwise dot terms
 
+// Per-tower work of a grouped auxiliary launch (dot terms or weight repack).
+struct TmAuxItem {
+  const void* src;
+  void* dst;
+  int32_t nf, n, np, np_pad;   // dots: features, dim, real and padded term count
+  int32_t O, wt;               // pack: output rows, tower width
+};
+
+struct TmAuxLaunch {
+  int32_t ngroups;
+  int32_t block_start[kMaxGroups + 1];
+  int64_t B;
+  TmAuxItem g[kMaxGroups];
+};
+
+__device__ __forceinline__ int aux_group(const TmAuxLaunch& L) {
+  int gi = 0;
+  while (gi + 1 < L.ngroups && (int)blockIdx.x >= L.block_start[gi + 1]) ++gi;
+  return gi;
+}
+
 // z[s][p(i,j)] = <x[s][i][:], x[s][j][:]>, i < j, p row-major; x is [B][nf][n]
 // contiguous.  One wave per 32 consecutive (sample, feature) rows; needs
 // 32 % nf == 0 and n % 16 == 0.  Columns np .. np_pad-1 of z are zeroed.
 template <int DT>
-__global__ __launch_bounds__(kBlock) void tm_dots_mfma(const void* __restrict__ x, int64_t B,
-                                                       int nf, int n, void* __restrict__ z,
-                                                       int np, int np_pad) {
+__global__ __launch_bounds__(kBlock) void tm_dots_mfma(const TmAuxLaunch L) {
+  const int gi = aux_group(L);
+  const TmAuxItem& G = L.g[gi];
+  const int64_t B = L.B;
+  const int nf = G.nf, n = G.n, np = G.np, np_pad = G.np_pad;
+  void* __restrict__ z = G.dst;
   const int lane = threadIdx.x & 63;
-  const int64_t rg = (int64_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
+  const int64_t rg = (int64_t)(blockIdx.x - L.block_start[gi]) * (kBlock / 64) + (threadIdx.x >> 6);
   const int64_t row0 = rg * 32, nrows = B * nf;
   if (row0 >= nrows) return;
   const int64_t r = row0 + (lane & 31);
-  const uint16_t* xp = (const uint16_t*)x + r * n + (lane >> 5) * 8;
+  const uint16_t* xp = (const uint16_t*)G.src + r * n + (lane >> 5) * 8;
   floatx16 acc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
@@ -240,11 +264,12 @@ __global__ __launch_bounds__(kBlock) void tm_dots_mfma(const void* __restrict__ 
 
 // Any nf / n, any dtype: one thread per (sample, term).
 template <int DT>
-__global__ __launch_bounds__(kBlock) void tm_dots_simple(const void* __restrict__ x, int64_t B,
-                                                         int nf, int n, void* __restrict__ z,
-                                                         int np, int np_pad) {
-  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (e >= B * np_pad) return;
+__global__ __launch_bounds__(kBlock) void tm_dots_simple(const TmAuxLaunch L) {
+  const int gi = aux_group(L);
+  const TmAuxItem& G = L.g[gi];
+  const int nf = G.nf, n = G.n, np = G.np, np_pad = G.np_pad;
+  const int64_t e = (int64_t)(blockIdx.x - L.block_start[gi]) * kBlock + threadIdx.x;
+  if (e >= L.B * np_pad) return;
   const int64_t s = e / np_pad;
   const int p = (int)(e % np_pad);
   float d = 0.f;
@@ -253,25 +278,27 @@ __global__ __launch_bounds__(kBlock) void tm_dots_simple(const void* __restrict_
     while (rem >= nf - 1 - i) { rem -= nf - 1 - i; ++i; }
     const int j = i + 1 + rem;
     const int64_t bi = (s * nf + i) * n, bj = (s * nf + j) * n;
-    for (int k = 0; k < n; ++k) d += load_elt<DT>(x, bi + k) * load_elt<DT>(x, bj + k);
+    for (int k = 0; k < n; ++k) d += load_elt<DT>(G.src, bi + k) * load_elt<DT>(G.src, bj + k);
   }
-  store_elt<DT>(z, e, d);
+  store_elt<DT>(G.dst, e, d);
 }
 
 // Projection weights [O][np + Wt] -> [O][np_pad + Wt] with zero columns after the
 // dot terms, so both K segments start 16-byte aligned.
 template <int DT>
-__global__ __launch_bounds__(kBlock) void tm_pack_w(const void* __restrict__ w, int O, int np,
-                                                    int np_pad, int wt, void* __restrict__ wp) {
-  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+__global__ __launch_bounds__(kBlock) void tm_pack_w(const TmAuxLaunch L) {
+  const int gi = aux_group(L);
+  const TmAuxItem& G = L.g[gi];
+  const int np = G.np, np_pad = G.np_pad, wt = G.wt;
+  const int64_t e = (int64_t)(blockIdx.x - L.block_start[gi]) * kBlock + threadIdx.x;
   const int kp = np_pad + wt;
-  if (e >= (int64_t)O * kp) return;
+  if (e >= (int64_t)G.O * kp) return;
   const int o = (int)(e / kp), k = (int)(e % kp);
   const int64_t src = (int64_t)o * (np + wt) + (k < np ? k : np + (k - np_pad));
   if constexpr (DT == DMT_F32) {
-    ((float*)wp)[e] = (k >= np && k < np_pad) ? 0.f : ((const float*)w)[src];
+    ((float*)G.dst)[e] = (k >= np && k < np_pad) ? 0.f : ((const float*)G.src)[src];
   } else {
-    ((uint16_t*)wp)[e] = (k >= np && k < np_pad) ? (uint16_t)0 : ((const uint16_t*)w)[src];
+    ((uint16_t*)G.dst)[e] = (k >= np && k < np_pad) ? (uint16_t)0 : ((const uint16_t*)G.src)[src];
   }
 }
 
@@ -358,31 +385,61 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
   for (int32_t t = 0; t < p->T; ++t) out_prefix[t + 1] = out_prefix[t] + tp[t].out_dim;
   int max_layers = 0;
 
-  // stage 0: dot terms and repacked projection weights
+  // stage 0: dot terms and repacked projection weights, one grouped launch per kind
+  std::vector<TmAuxItem> dots_mfma, dots_simple, packs;
+  std::vector<int64_t> nb_mfma, nb_simple, nb_pack;
   for (int32_t t = 0; t < p->T; ++t) {
     const dmt_tm_params& q = tp[t];
     if (q.kind == DMT_TM_CROSS_LINEAR) max_layers = std::max(max_layers, q.num_cross_layers);
     if (q.kind != DMT_TM_DOT_LINEAR) continue;
     const TowerWs& w = ws[t];
-    const int nf = p->tower_ntab[t], n = p->tower_uniform_dim[t], wt = p->tower_width[t];
-    const void* x = x_all + (size_t)B * p->width_prefix[t] * eb;
-    void* z = wsp + w.z_off;
-    bool mfma_ok = DT != DMT_F32 && 32 % nf == 0 && n % 16 == 0;
-    if (mfma_ok) {
-      if constexpr (DT != DMT_F32) {
-        const int64_t rgs = (B * nf + 31) / 32;
-        { DmtScope sc_(p, DMT_K_TM_DOTS, s); hipLaunchKernelGGL((tm_dots_mfma<DT>), dim3((unsigned)((rgs + 3) / 4)), dim3(kBlock), 0, s,
-                           x, B, nf, n, z, w.np, w.np_pad); }
-      }
+    TmAuxItem it{};
+    it.nf = p->tower_ntab[t]; it.n = p->tower_uniform_dim[t]; it.np = w.np; it.np_pad = w.np_pad;
+    it.O = q.out_dim; it.wt = p->tower_width[t];
+    it.src = x_all + (size_t)B * p->width_prefix[t] * eb;
+    it.dst = wsp + w.z_off;
+    if (DT != DMT_F32 && 32 % it.nf == 0 && it.n % 16 == 0) {
+      dots_mfma.push_back(it);
+      nb_mfma.push_back(((B * it.nf + 31) / 32 + 3) / 4);
     } else {
-      const int64_t e = B * w.np_pad;
-      { DmtScope sc_(p, DMT_K_TM_DOTS, s); hipLaunchKernelGGL((tm_dots_simple<DT>), dim3((unsigned)((e + kBlock - 1) / kBlock)),
-                         dim3(kBlock), 0, s, x, B, nf, n, z, w.np, w.np_pad); }
+      dots_simple.push_back(it);
+      nb_simple.push_back((B * w.np_pad + kBlock - 1) / kBlock);
     }
-    const int64_t e = (int64_t)q.out_dim * (w.np_pad + wt);
-    { DmtScope sc_(p, DMT_K_TM_PACK, s); hipLaunchKernelGGL((tm_pack_w<DT>), dim3((unsigned)((e + kBlock - 1) / kBlock)), dim3(kBlock),
-                       0, s, q.w_proj, q.out_dim, w.np, w.np_pad, wt, wsp + w.wp_off); }
+    it.src = q.w_proj;
+    it.dst = wsp + w.wp_off;
+    packs.push_back(it);
+    nb_pack.push_back(((int64_t)q.out_dim * (w.np_pad + it.wt) + kBlock - 1) / kBlock);
   }
+  auto launch_aux = [&](std::vector<TmAuxItem>& items, std::vector<int64_t>& nblocks, int which) {
+    for (size_t first = 0; first < items.size(); first += kMaxGroups) {
+      TmAuxLaunch L;
+      L.B = B;
+      L.ngroups = (int32_t)std::min<size_t>(kMaxGroups, items.size() - first);
+      int32_t blocks = 0;
+      for (int i = 0; i < L.ngroups; ++i) {
+        L.g[i] = items[first + i];
+        L.block_start[i] = blocks;
+        blocks += (int32_t)nblocks[first + i];
+      }
+      L.block_start[L.ngroups] = blocks;
+      if (blocks == 0) continue;
+      if (which == 0) {
+        if constexpr (DT != DMT_F32) {
+          DmtScope sc_(p, DMT_K_TM_DOTS, s);
+          hipLaunchKernelGGL((tm_dots_mfma<DT>), dim3(blocks), dim3(kBlock), 0, s, L);
+        }
+      } else if (which == 1) {
+        DmtScope sc_(p, DMT_K_TM_DOTS, s);
+        hipLaunchKernelGGL((tm_dots_simple<DT>), dim3(blocks), dim3(kBlock), 0, s, L);
+      } else {
+        DmtScope sc_(p, DMT_K_TM_PACK, s);
+        hipLaunchKernelGGL((tm_pack_w<DT>), dim3(blocks), dim3(kBlock), 0, s, L);
+      }
+    }
+  };
+  launch_aux(dots_mfma, nb_mfma, 0);
+  launch_aux(dots_simple, nb_simple, 1);
+  launch_aux(packs, nb_pack, 2);
 
   // cross layers, one grouped launch per layer index
   std::vector<TmGroup> groups;
