@@ -10,6 +10,8 @@
 // Data in the workspace: 64-bit records (global_row << 32 | bag), where
 // global_row = (sum of rows of earlier tables) + row and bag = f*B + b.  Ids
 // outside their table get global_row = total_rows (sorts last, never touched).
+#include <type_traits>
+
 #include "dmt_internal.h"
 #include "dmt_device_utils.h"
 
@@ -21,7 +23,10 @@ constexpr int kSortTile = kBlock * kSortItems;   // records per sort block
 constexpr int kScanItems = 16;
 constexpr int kScanTile = kBlock * kScanItems;   // records per head-scan block
 constexpr int kReduceTile = 128;                 // sorted records per reduce tile
-constexpr int kReduceUnroll = 4;
+#ifndef DMT_RU
+#define DMT_RU 4
+#endif
+constexpr int kReduceUnroll = DMT_RU;
 
 struct BwdWs {
   uint64_t* pk_a;
@@ -340,94 +345,242 @@ __device__ __forceinline__ void store_partial(float* __restrict__ partials, int6
   if (gl * 4 < Dmax) *((float4*)(partials + slot * Dmax) + gl) = g;
 }
 
-// Each group of GL lanes walks one tile of kReduceTile sorted records, summing
-// the bags' gradient slices run by run.  A run that lies wholly inside the tile
-// is applied to its row at once; the piece of a run that continues from the
-// previous tile goes to partial slot 2t, the piece of a run that starts here
-// and continues into the next tile goes to slot 2t + 1.
-template <int TD, bool NT>
+// Sum of v over the 2^LG lanes of an aligned lane group; every lane gets the
+// total.  Data-parallel-primitive moves inside a 16-lane row, a swizzle across
+// rows, a permute across the two 32-lane halves.
+template <int LG>
+__device__ __forceinline__ float group_sum(float v) {
+  auto dpp = [](float x, auto ctrl) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), decltype(ctrl)::value,
+                                                      0xf, 0xf, true));
+  };
+  if constexpr (LG >= 1) v += dpp(v, std::integral_constant<int, 0xB1>());   // quad_perm [1,0,3,2]
+  if constexpr (LG >= 2) v += dpp(v, std::integral_constant<int, 0x4E>());   // quad_perm [2,3,0,1]
+  if constexpr (LG >= 3) v += dpp(v, std::integral_constant<int, 0x141>());  // row_half_mirror
+  if constexpr (LG >= 4) v += dpp(v, std::integral_constant<int, 0x140>());  // row_mirror
+  if constexpr (LG >= 5)
+    v += __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), 0x401F));  // lane ^ 16
+  if constexpr (LG >= 6) v += __shfl_xor(v, 32);
+  return v;
+}
+
+// A lane's four columns of a table row.
+template <int TD> struct RowChunk { using type = uint2; static constexpr int bytes = 8; };
+template <> struct RowChunk<DMT_F32> { using type = float4; static constexpr int bytes = 16; };
+
+#ifndef DMT_QS
+#define DMT_QS 5
+#endif
+constexpr int kQueueSlots = DMT_QS;   // finished runs a lane group parks before their rows are updated
+
+// Each group of GL = 2^LG lanes walks one tile of kReduceTile sorted records,
+// summing the bags' gradient slices run by run (float32, record order).  Runs
+// that lie wholly inside the tile are parked in an LDS queue (their gradient
+// sum, row and state address); the queue is drained four rows at a time, so the
+// row / state reads of four updates are in flight together instead of one
+// dependent read per run.  The piece of a run that continues from the previous
+// tile goes to partial slot 2t, the piece of a run that starts here and
+// continues into the next tile to slot 2t + 1.
+// UD: every table has dim Dmax (no per-record width to pass round).
+template <int TD, int LG, bool UD>
 __global__ __launch_bounds__(kBlock) void bwd_reduce_update(
     const DmtTableMeta* __restrict__ meta, const uint64_t* __restrict__ pk, int64_t nnz, uint32_t B,
     uint32_t nbags, uint32_t total_rows, const float* __restrict__ grad,
-    float* __restrict__ partials, int Dmax, int log2_gl, int64_t ntiles, int64_t blocks_per_xcd,
-    float lr, float eps) {
-  const int GL = 1 << log2_gl;
+    float* __restrict__ partials, int Dmax, int64_t ntiles, int64_t blocks_per_xcd, float lr,
+    float eps) {
+  constexpr int GL = 1 << LG, NG = kBlock >> LG;
+  constexpr int eb = TD == DMT_F32 ? 4 : 2;
+  using Chunk = typename RowChunk<TD>::type;
+  __shared__ float4 q_g[kQueueSlots][kBlock];
+  __shared__ unsigned long long q_rowp[NG][kQueueSlots];
+  __shared__ unsigned long long q_stp[NG][kQueueSlots];
+  __shared__ int q_D[NG][kQueueSlots];
+
+  const int group = threadIdx.x >> LG;
   const int64_t tb = (int64_t)(blockIdx.x & 7) * blocks_per_xcd + (blockIdx.x >> 3);
-  const int64_t t = tb * (kBlock >> log2_gl) + (threadIdx.x >> log2_gl);
-  if (t >= ntiles) return;
+  const int64_t t = tb * NG + group;
+  const bool live = t < ntiles;                 // dead groups still take part in wave votes
   const int lane = threadIdx.x & 63;
   const int gl = threadIdx.x & (GL - 1);
   const int lane0 = lane & ~(GL - 1);
-  const int64_t p0 = t * kReduceTile;
-  const int n = (int)min((int64_t)kReduceTile, nnz - p0);
-  const uint32_t first_key = (uint32_t)(pk[p0] >> 32);
-  const bool cont_prev = p0 > 0 && (uint32_t)(pk[p0 - 1] >> 32) == first_key;
-  const bool cont_next =
-      p0 + n < nnz && (uint32_t)(pk[p0 + n - 1] >> 32) == (uint32_t)(pk[p0 + n] >> 32);
+  const bool lane_on = gl * 4 < Dmax;
+  const float4* __restrict__ grad4 = (const float4*)grad;
 
-  uint32_t cur_key = first_key, cur_f = 0;
-  bool first_run = true, have_f = false;
+  int64_t p0 = 0;
+  int n = 0;
+  bool cont_prev = false, cont_next = false;
+  uint32_t carry = 0;
+  if (live) {
+    p0 = t * kReduceTile;
+    n = (int)min((int64_t)kReduceTile, nnz - p0);
+    const uint32_t first_key = (uint32_t)(pk[p0] >> 32);
+    if (p0 > 0) {
+      carry = (uint32_t)(pk[p0 - 1] >> 32);
+      cont_prev = carry == first_key;
+    }
+    cont_next = p0 + n < nnz && (uint32_t)(pk[p0 + n - 1] >> 32) == (uint32_t)(pk[p0 + n] >> 32);
+  }
+  bool has_prev = p0 > 0;
+  bool run_open = cont_prev, from_left = cont_prev;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  unsigned long long cur_rowp = 0, cur_stp = 0;
+  int cur_D = Dmax;
+  bool cur_ok = false;
+  int qn = 0;
 
-  for (int sub = 0; sub < n; sub += GL) {
-    const int cnt = min(GL, n - sub);
-    uint32_t key_l = total_rows, f_l = 0;
-    int D_l = 0;
-    int64_t goff_l = 0;
-    if (gl < cnt) {
-      const uint64_t r = pk[p0 + sub + gl];
-      key_l = (uint32_t)(r >> 32);
-      const uint32_t bag = (uint32_t)r;
-      if (key_l < total_rows && bag < nbags) {
-        f_l = bag / B;
-        const uint32_t b = bag - f_l * B;
-        D_l = meta[f_l].D;
-        goff_l = (int64_t)B * meta[f_l].out_prefix + (int64_t)b * meta[f_l].tower_width +
-                 meta[f_l].col_off;
-      } else {
-        key_l = total_rows;
+  auto park = [&]() {                            // the open run is complete: queue its update
+#ifdef DMT_PROBE_NOUPDATE
+    if (cur_ok && acc.x == 12345.f) {
+#else
+    if (cur_ok) {
+#endif
+      q_g[qn][threadIdx.x] = acc;
+      q_rowp[group][qn] = cur_rowp;
+      q_stp[group][qn] = cur_stp;
+      if (!UD) q_D[group][qn] = cur_D;
+      ++qn;
+    }
+  };
+  auto drain = [&]() {
+#pragma unroll
+    for (int j0 = 0; j0 < kQueueSlots; j0 += 4) {
+      if (!__any(j0 < qn)) break;
+      Chunk w[4];
+      float st[4];
+      Chunk* wp[4];
+      float* sp[4];
+      int D[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (j0 + u < qn && j0 + u < kQueueSlots) {
+          D[u] = UD ? Dmax : q_D[group][j0 + u];
+          wp[u] = (Chunk*)(q_rowp[group][j0 + u]) + gl;
+          sp[u] = (float*)(q_stp[group][j0 + u]);
+#ifdef DMT_PROBE_NOSTLOAD
+          st[u] = 0.5f;
+#else
+          st[u] = *sp[u];
+#endif
+#ifdef DMT_PROBE_NOROWLOAD
+          if (gl * 4 < D[u]) w[u] = Chunk{};
+#else
+          if (gl * 4 < D[u]) w[u] = *wp[u];
+#endif
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (j0 + u < qn && j0 + u < kQueueSlots) {
+          const float4 g = q_g[j0 + u][threadIdx.x];
+          const float ss = group_sum<LG>(g.x * g.x + g.y * g.y + g.z * g.z + g.w * g.w);
+          const float sn = st[u] + ss / (float)D[u];
+          const float step = lr * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(sn) + eps);
+          if (gl * 4 < D[u]) {
+            if constexpr (TD == DMT_F32) {
+              float4 v = w[u];
+              v.x -= step * g.x; v.y -= step * g.y; v.z -= step * g.z; v.w -= step * g.w;
+              *wp[u] = v;
+            } else {
+              float a, b, c, d;
+              dmt::unpack2<TD>(w[u].x, a, b);
+              dmt::unpack2<TD>(w[u].y, c, d);
+              a -= step * g.x; b -= step * g.y; c -= step * g.z; d -= step * g.w;
+#ifdef DMT_PROBE_NOROWSTORE
+              if (a == 12345.f)
+#endif
+              *wp[u] = make_uint2(dmt::pack2<TD>(a, b), dmt::pack2<TD>(c, d));
+            }
+          }
+#ifdef DMT_PROBE_NOSTSTORE
+          if (gl == 0 && sn == 12345.f) *sp[u] = sn;
+#else
+          if (gl == 0) *sp[u] = sn;
+#endif
+        }
       }
     }
-    for (int i0 = 0; i0 < cnt; i0 += kReduceUnroll) {
+    qn = 0;
+  };
+
+  for (int sub = 0; sub < kReduceTile; sub += GL) {
+    const int cnt = min(GL, n - sub);            // <= 0 once this group's tile is done
+    if (!__any(cnt > 0)) break;
+    // every lane prepares its own record: gradient offset, row and state address
+    uint32_t key_l = total_rows, goff4_l = 0xffffffffu;
+    unsigned long long rowp_l = 0, stp_l = 0;
+    int D_l = 0;
+    if (gl < cnt) {
+      const uint64_t r = pk[p0 + sub + gl];
+      const uint32_t k = (uint32_t)(r >> 32), bag = (uint32_t)r;
+      if (k < total_rows && bag < nbags) {
+        const uint32_t f = bag / B, b = bag - f * B;
+        const DmtTableMeta& m = meta[f];
+        key_l = k;
+        D_l = m.D;
+        goff4_l = (uint32_t)(((int64_t)B * m.out_prefix + (int64_t)b * m.tower_width + m.col_off) >> 2);
+        const int64_t row = (int64_t)k - m.row_base;
+        rowp_l = (unsigned long long)((const char*)m.table + row * D_l * eb);
+        stp_l = (unsigned long long)(m.state + row);
+      }
+    }
+    // run heads of this sub-round as a bit mask, one bit per record
+    uint32_t prev = __shfl_up(key_l, 1, GL);
+    bool head_l = gl < cnt;
+    if (gl == 0) head_l = head_l && (!has_prev || key_l != carry);
+    else head_l = head_l && key_l != prev;
+    const unsigned long long hm = __ballot(head_l);
+    const unsigned long long gm = LG == 6 ? hm : ((hm >> lane0) & ((1ULL << (GL & 63)) - 1));
+    if (cnt > 0) {
+      carry = __shfl(key_l, lane0 + cnt - 1);
+      has_prev = true;
+    }
+
+    for (int i0 = 0; i0 < GL; i0 += kReduceUnroll) {
+      if (!__any(i0 < cnt)) break;
       float4 g[kReduceUnroll];
 #pragma unroll
       for (int u = 0; u < kReduceUnroll; ++u) {
         const int src = lane0 + ((i0 + u) & (GL - 1));
-        const int64_t go = __shfl(goff_l, src);
-        const int d = __shfl(D_l, src);
+        const uint32_t go = __shfl(goff4_l, src);
+        bool on = lane_on && i0 + u < cnt && go != 0xffffffffu;
+        if (!UD) on = on && gl * 4 < __shfl(D_l, src);
         g[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (i0 + u < cnt && gl * 4 < d) g[u] = *((const float4*)(grad + go) + gl);
+#ifdef DMT_PROBE_NOGRAD
+        if (on) g[u] = make_float4(go, 1.f, 2.f, 3.f);
+#else
+        if (on) g[u] = grad4[(size_t)go + gl];
+#endif
       }
 #pragma unroll
       for (int u = 0; u < kReduceUnroll; ++u) {
-        const int src = lane0 + ((i0 + u) & (GL - 1));
-        const uint32_t k = __shfl(key_l, src);
-        const uint32_t fk = __shfl(f_l, src);
-        if (i0 + u < cnt) {
-          if (k != cur_key) {
-            // the run that just ended lies inside the tile unless it came in from the left
-            if (cur_key < total_rows) {
-              if (first_run && cont_prev) store_partial(partials, 2 * t, Dmax, gl, acc);
-              else apply_row_update<TD, NT>(meta, cur_f, cur_key - (uint32_t)meta[cur_f].row_base,
-                                            acc, gl, GL, lr, eps);
+        const int i = i0 + u;
+        const int src = lane0 + (i & (GL - 1));
+        if (i < cnt) {
+          if ((gm >> i) & 1) {                     // a run starts at this record
+            if (run_open) {
+              if (from_left) store_partial(partials, 2 * t, Dmax, gl, acc);
+              else park();
             }
+            from_left = false;
+            run_open = true;
             acc = make_float4(0.f, 0.f, 0.f, 0.f);
-            cur_key = k;
-            first_run = false;
-            have_f = false;
+            cur_rowp = __shfl(rowp_l, src);
+            cur_stp = __shfl(stp_l, src);
+            cur_ok = __shfl(key_l, src) < total_rows;
+            if (!UD) cur_D = __shfl(D_l, src);
           }
-          if (!have_f) { cur_f = fk; have_f = true; }
           acc.x += g[u].x; acc.y += g[u].y; acc.z += g[u].z; acc.w += g[u].w;
         }
       }
+      if (__any(qn > kQueueSlots - kReduceUnroll)) drain();
     }
   }
-  if (cur_key < total_rows) {
-    if (first_run && cont_prev) store_partial(partials, 2 * t, Dmax, gl, acc);
-    else if (cont_next) store_partial(partials, 2 * t + 1, Dmax, gl, acc);
-    else apply_row_update<TD, NT>(meta, cur_f, cur_key - (uint32_t)meta[cur_f].row_base, acc, gl,
-                                  GL, lr, eps);
+  if (run_open) {
+    if (from_left) store_partial(partials, 2 * t, Dmax, gl, acc);
+    else if (cont_next) { if (cur_ok) store_partial(partials, 2 * t + 1, Dmax, gl, acc); }
+    else park();
   }
+  drain();
 }
 
 // Table that owns global row id `gid` (row_base has F + 1 ascending entries).
@@ -538,6 +691,7 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
   if (!(eps >= 0.f) || lr != lr) return DMT_EINVAL;
   if ((uintptr_t)grad_pooled & 15) return DMT_EINVAL;
   if (plan->max_dim > 256) return DMT_ENOTSUP;          // one float4 per lane, 64 lanes
+  if (B * plan->width_prefix[plan->T] >= (1LL << 33)) return DMT_ENOTSUP;   // float4 index in 32 bits
   const BwdWs w = carve(plan, nnz, workspace);
   if (!workspace || ((uintptr_t)workspace & 255)) return DMT_EINVAL;
   if (workspace_bytes < w.bytes) return DMT_ENOMEM;
@@ -584,26 +738,26 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
                        w.blk_heads, w.seg_off, w.tile_first); }
     // segment reduce + update, then the rows that span tiles
     int log2_glb = ilog2_ceil(plan->max_dim / 4);
-    if (log2_glb > 6) log2_glb = 6;
+    if (log2_glb < 2) log2_glb = 2;
     const int groups = kBlock >> log2_glb;
     const int64_t rblocks = (w.ntiles + groups - 1) / groups;
     const int64_t blocks_per_xcd = (rblocks + 7) / 8;
     const int td = (int)plan->table_dtype;
-    const bool nt = dmt::env_int("DMT_BWD_NT", 0) != 0;
+    const bool ud = plan->classes.size() == 1;
+#define DMT_BWD_LAUNCH(TD, LG, UD)                                                                \
+  hipLaunchKernelGGL((bwd_reduce_update<TD, LG, UD>), dim3((unsigned)(blocks_per_xcd * 8)),       \
+                     dim3(kBlock), 0, s, plan->d_meta, sorted, nnz, (uint32_t)B, nbags,           \
+                     total_rows, grad_pooled, w.partials, plan->max_dim, w.ntiles,                \
+                     blocks_per_xcd, lr, eps)
+#define DMT_BWD_LG(TD, LG)                                                                        \
+  if (log2_glb == LG) {                                                                           \
+    if (ud) DMT_BWD_LAUNCH(TD, LG, true); else DMT_BWD_LAUNCH(TD, LG, false);                     \
+  }
 #define DMT_BWD_CASE(TD)                                                                          \
   if (td == TD) {                                                                                 \
     {                                                                                             \
       DmtScope sc_(plan, DMT_K_BWD_REDUCE_UPDATE, s);                                             \
-      if (nt)                                                                                     \
-        hipLaunchKernelGGL((bwd_reduce_update<TD, true>), dim3((unsigned)(blocks_per_xcd * 8)),   \
-                           dim3(kBlock), 0, s, plan->d_meta, sorted, nnz, (uint32_t)B, nbags,     \
-                           total_rows, grad_pooled, w.partials, plan->max_dim, log2_glb,          \
-                           w.ntiles, blocks_per_xcd, lr, eps);                                    \
-      else                                                                                        \
-        hipLaunchKernelGGL((bwd_reduce_update<TD, false>), dim3((unsigned)(blocks_per_xcd * 8)),  \
-                           dim3(kBlock), 0, s, plan->d_meta, sorted, nnz, (uint32_t)B, nbags,     \
-                           total_rows, grad_pooled, w.partials, plan->max_dim, log2_glb,          \
-                           w.ntiles, blocks_per_xcd, lr, eps);                                    \
+      DMT_BWD_LG(TD, 2) DMT_BWD_LG(TD, 3) DMT_BWD_LG(TD, 4) DMT_BWD_LG(TD, 5) DMT_BWD_LG(TD, 6)   \
     }                                                                                             \
     { DmtScope sc_(plan, DMT_K_BWD_FIXUP, s); hipLaunchKernelGGL((bwd_fixup_update<TD>), dim3((unsigned)rblocks), dim3(kBlock), 0, s,       \
                        plan->d_meta, plan->d_row_base, plan->F, sorted, nnz, total_rows,          \
@@ -612,6 +766,8 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
   }
     DMT_BWD_CASE(DMT_F32) DMT_BWD_CASE(DMT_F16) DMT_BWD_CASE(DMT_BF16)
 #undef DMT_BWD_CASE
+#undef DMT_BWD_LG
+#undef DMT_BWD_LAUNCH
   }
   if (dbg && (dbg->sorted_keys || dbg->sorted_bag || dbg->unique_keys || dbg->seg_off ||
               dbg->num_unique)) {

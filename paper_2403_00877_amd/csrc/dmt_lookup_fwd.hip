@@ -7,9 +7,8 @@
 //    two) fetch one row with one dwordx4 load each, fully coalesced;
 //  * a bag is served by a group of GL = LPR*R lanes: R rows of the bag are in
 //    flight per load instruction, and every lane unrolls 4 such loads, so a
-//    wave keeps up to 4*64/LPR rows in flight;  R is picked from the mean bag
-//    length (short bags: R = 1 and many bags per wave; long bags: a whole wave
-//    per bag);
+//    wave keeps up to 4*64/LPR rows in flight;  R is 1 (many bags per wave)
+//    unless bags are very long;
 //  * the group reads its bag's ids coalesced (one per lane) and hands them
 //    round with ds_bpermute; partial sums of the R row slots are combined by a
 //    fixed xor tree, so results repeat bit for bit;
@@ -23,7 +22,10 @@
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kUnroll = 4;
+#ifndef DMT_LOOKUP_UNROLL
+#define DMT_LOOKUP_UNROLL 4
+#endif
+constexpr int kUnroll = DMT_LOOKUP_UNROLL;
 
 template <int TD, int OD>
 __global__ __launch_bounds__(kBlock) void lookup_fwd_kernel(
@@ -141,10 +143,12 @@ extern "C" dmt_status dmt_tower_lookup_fwd(const dmt_plan* plan, const int32_t* 
 
   for (const DmtDimClass& c : plan->classes) {
     const int log2_lpr = ilog2_ceil(c.D * eb / 16);
-    // rows of one bag in flight per load instruction: about a quarter of the
-    // mean bag length, so every slot still has ~4 rows to unroll over
+    // rows of one bag in flight per load instruction.  Measured on MI355X (Mid,
+    // mean length 20): one row slot per bag and more bags per wave beats a whole
+    // wave per bag (0.24 ms against 0.30 ms), so slots are only added once a
+    // slot's serial chain would get long.
     int r = 1;
-    while (r * 2 * kUnroll <= mean_len && ((r * 2) << log2_lpr) <= 64) r *= 2;
+    while (r * 2 * 16 * kUnroll <= mean_len && ((r * 2) << log2_lpr) <= 64) r *= 2;
     if (tuned_r > 0) {
       r = 1;
       while (r * 2 <= tuned_r && ((r * 2) << log2_lpr) <= 64) r *= 2;
@@ -152,7 +156,6 @@ extern "C" dmt_status dmt_tower_lookup_fwd(const dmt_plan* plan, const int32_t* 
     const int log2_gl = log2_lpr + ilog2_ceil(r);
     const int ngroups = kBlock >> log2_gl;
     int bpg = 1;
-    while (bpg < 4 && (int64_t)c.num_tables * B / ((int64_t)ngroups * bpg * 2) >= 8192) bpg *= 2;
     if (tuned_bpg > 0) bpg = tuned_bpg;
     const int td = (int)plan->table_dtype, od = (int)out_dtype;
 #define DMT_CASE(TD, OD)                                                                      \
