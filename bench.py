@@ -43,22 +43,26 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def batch_accounting(w, idx, off):
-    """Per-batch counts the algorithmic byte figures need (numpy only)."""
+def batch_accounting(torch, w, idx, off):
+    """Per-batch counts the algorithmic byte figures need, from the device tensors
+    (torch sort / unique on the ids: bookkeeping of the benchmark, not part of the path).
+    Returns per-table nnz and distinct rows, runs that span reduce tiles, partial slots."""
     F, B = w.num_tables, w.batch
-    nnz = len(idx)
-    tab = np.repeat(np.arange(F, dtype=np.int64), np.diff(off[::B]))
-    key = np.sort((tab << 32) | idx.astype(np.int64))
-    head = np.ones(nnz, dtype=bool)
+    nnz = idx.numel()
+    bounds = off[::B]
+    nnz_f = (bounds[1:] - bounds[:-1])
+    tab = torch.repeat_interleave(torch.arange(F, device=idx.device), nnz_f)
+    key, _ = torch.sort((tab << 32) | idx.to(torch.int64))
+    head = torch.ones(nnz, dtype=torch.bool, device=idx.device)
     head[1:] = key[1:] != key[:-1]
-    U = int(head.sum())
-    # runs that cross a reduce-tile boundary are finished by the fix-up kernel
-    edges = np.arange(RTILE, nnz, RTILE)
+    U_f = torch.bincount((key[head] >> 32), minlength=F)
+    edges = torch.arange(RTILE, nnz, RTILE, device=idx.device)
     crossing = key[edges] == key[edges - 1]
-    seg_id = np.cumsum(head) - 1
-    span = int(len(np.unique(seg_id[edges[crossing]])))
-    partial_slots = int(crossing.sum()) + span
-    return dict(nnz=nnz, U=U, span=span, partial_slots=partial_slots)
+    seg_id = torch.cumsum(head.to(torch.int64), 0) - 1
+    span = int(torch.unique(seg_id[edges[crossing]]).numel())
+    return dict(nnz=nnz, nnz_f=nnz_f.cpu().numpy().astype(np.float64),
+                U_f=U_f.cpu().numpy().astype(np.float64), U=int(head.sum().item()), span=span,
+                partial_slots=int(crossing.sum().item()) + span)
 
 
 def main():
@@ -77,26 +81,44 @@ def main():
     eb = wl.ELT_BYTES[w.table_dtype]
     eo = wl.ELT_BYTES[w.pooled_dtype]
     tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+    default = w.name == "backward"
+    on_device = w.name in ("large", "imbalanced")        # id streams too large for numpy
+    nb = args.batches if default else min(args.batches, 2)
 
     t0 = time.time()
     tables = wl.tables_device(w)
-    states = [torch.zeros(r, dtype=torch.float32, device="cuda") for r in w.rows]
-    log("[bench] tables on device: %.1f GB in %.1fs" %
-        (sum(t.numel() * t.element_size() for t in tables) / 1e9, time.time() - t0))
+    states = [torch.zeros(r, dtype=torch.float32, device="cuda") for r in w.rows] if w.backward else None
+    torch.cuda.synchronize()
+    log("[bench] %s: tables on device: %.1f GB in %.1fs" %
+        (w.name, sum(t.numel() * t.element_size() for t in tables) / 1e9, time.time() - t0))
 
     cache = {}
     batches = []
     t0 = time.time()
-    for i in range(args.batches):
-        idx, off = wl.lookup_batch(w, i, cache)
-        acct = batch_accounting(w, idx, off)
-        grad = wl.grad_pooled(w, i)
-        batches.append(dict(idx=torch.from_numpy(idx).cuda(), off=torch.from_numpy(off).cuda(),
-                            grad=torch.from_numpy(grad).cuda(), acct=acct,
-                            host=(idx, off, grad) if i == 0 else None))
+    base_w, widths_w, _ = wl.pooled_layout(w)
+    for i in range(nb):
+        host = None
+        if on_device:
+            d_idx, d_off = wl.lookup_batch_device(w, i)
+        else:
+            idx, off = wl.lookup_batch(w, i, cache)
+            d_idx, d_off = torch.from_numpy(idx).cuda(), torch.from_numpy(off).cuda()
+        grad = None
+        if w.backward:
+            if on_device:
+                g = torch.Generator(device="cuda")
+                g.manual_seed(1000 * w.seed + i)
+                grad = torch.randn(base_w[-1], generator=g, device="cuda", dtype=torch.float32)
+            else:
+                hg = wl.grad_pooled(w, i)
+                grad = torch.from_numpy(hg).cuda()
+                if i == 0:
+                    host = (idx, off, hg)
+        batches.append(dict(idx=d_idx, off=d_off, grad=grad, host=host,
+                            acct=batch_accounting(torch, w, d_idx, d_off)))
+    a0 = batches[0]["acct"]
     log("[bench] %d batches generated in %.1fs; nnz %d, unique rows %d (%.0f%% duplicates)" %
-        (len(batches), time.time() - t0, batches[0]["acct"]["nnz"], batches[0]["acct"]["U"],
-         100 * (1 - batches[0]["acct"]["U"] / batches[0]["acct"]["nnz"])))
+        (len(batches), time.time() - t0, a0["nnz"], a0["U"], 100 * (1 - a0["U"] / max(a0["nnz"], 1))))
     max_nnz = max(b["acct"]["nnz"] for b in batches)
 
     plan = dmt.dmt_plan_create(w.rows, w.dims, w.table_dtype, T, w.table_to_tower, B, max_nnz)
@@ -112,11 +134,15 @@ def main():
                    b_proj=dev(h["b_proj"], w.tm_dtype),
                    w_cross=[dev(a, w.tm_dtype) for a in h["w_cross"]],
                    b_cross=[dev(a, w.tm_dtype) for a in h["b_cross"]]) for t, h in enumerate(tm_host)]
+    if not default:
+        tm_host = None
     tm_params = dmt.make_tm_params(tm_dev)
     tm_ws = torch.empty(max(dmt.dmt_tm_workspace_bytes(plan, tm_params, B), 256), dtype=torch.uint8,
                         device="cuda")
-    bwd_ws = torch.empty(max(dmt.dmt_bwd_workspace_bytes(plan, B, max_nnz), 256), dtype=torch.uint8,
-                         device="cuda")
+    bwd_ws = None
+    if w.backward:
+        bwd_ws = torch.empty(max(dmt.dmt_bwd_workspace_bytes(plan, B, max_nnz), 256), dtype=torch.uint8,
+                             device="cuda")
     pooled = torch.empty(base[-1], dtype=tdt[w.pooled_dtype], device="cuda")
     tm_out = torch.empty(B * sum(w.tm_out), dtype=tdt[w.tm_dtype], device="cuda")
 
@@ -124,11 +150,12 @@ def main():
         b = batches[i % len(batches)]
         dmt.dmt_tower_lookup_fwd(plan, b["idx"], b["off"], B, pooled)
         dmt.dmt_tower_module_fwd(plan, tm_params, pooled, B, tm_out, tm_ws)
-        dmt.dmt_tower_lookup_bwd_update(plan, b["idx"], b["off"], B, b["grad"], w.lr, w.eps, bwd_ws)
+        if w.backward:
+            dmt.dmt_tower_lookup_bwd_update(plan, b["idx"], b["off"], B, b["grad"], w.lr, w.eps, bwd_ws)
 
     # ---- CPU oracle leg: baseline timing + a live parity check on the same inputs
     cpu = None
-    if not args.no_cpu:
+    if default and not args.no_cpu:
         cpu = cpu_leg(dmt, wl, w, plan, tables, states, tm_host, batches[0], pooled, tm_out, tm_params,
                       tm_ws, bwd_ws, widths)
         for s in states:                      # restart the optimizer state for the timed run
@@ -153,7 +180,6 @@ def main():
 
     # ---- per-kernel breakdown (outside the timed region, every family timed)
     dmt.dmt_profile_enable(plan, (1 << dmt.DMT_K_COUNT) - 1)
-    nb = len(batches)
     for i in range(nb):
         step(args.warmup + args.steps + i)
     full = dmt.dmt_profile_read(plan)
@@ -166,58 +192,74 @@ def main():
             dmt.dmt_calibration_copy(a, c)
         torch.cuda.synchronize()
 
-    # ---- algorithmic bytes per launch, averaged over the batches the timed steps used
+    # ---- algorithmic bytes per step, averaged over the batches the timed steps used
     used = [batches[(args.warmup + i) % nb]["acct"] for i in range(args.steps)]
-    mean = lambda k: float(np.mean([u[k] for u in used]))
-    nnz, U, span, pslots = mean("nnz"), mean("U"), mean("span"), mean("partial_slots")
-    D = w.dims[0]
-    bags = F * B
+    mean = lambda k: np.mean([u[k] for u in used], axis=0)
+    nnz, U, span, pslots = float(mean("nnz")), float(mean("U")), float(mean("span")), float(mean("partial_slots"))
+    nnz_f, U_f = mean("nnz_f"), mean("U_f")
+    Df = np.array(w.dims, dtype=np.float64)
+    Dmax = float(Df.max())
     bytes_of = {
-        # rows + ids + offsets + pooled store
-        "lookup_fwd": nnz * (D * eb + 4) + bags * (8 + D * eo),
-        # sorted records + gradient slices + row/state read-modify-write of rows finished in-tile
-        # + partial sums of rows that span tiles
-        "bwd_reduce_update": nnz * (8 + D * 4) + (U - span) * (2 * D * eb + 8) + pslots * D * 4,
+        # per lookup: row + id; per bag: offset + pooled store
+        "lookup_fwd": float((nnz_f * (Df * eb + 4) + B * (8 + Df * eo)).sum()),
+        # per lookup: sorted record + gradient slice; per row finished in-tile: row read + write and
+        # state read + write; partial sums of rows that span tiles
+        "bwd_reduce_update": float((nnz_f * (8 + Df * 4) + U_f * (2 * Df * eb + 8)).sum()
+                                   - span * (2 * Dmax * eb + 8) + pslots * Dmax * 4),
         # one radix pass: records read and written
         "radix_scatter": nnz * 16,
     }
     kin = w.tm_in_dims()
-    tm_flops = sum(2.0 * B * o * k for o, k in zip(w.tm_out, kin))
+    tw = w.tower_widths()
+    nl = w.tm_cross_layers if w.tm_kind == wl.TM_CROSS_LINEAR else 0
+    tm_flops = sum(2.0 * B * (o * k + nl * d * d) for o, k, d in zip(w.tm_out, kin, tw))
+    tm_bytes = sum(B * (d * eo * (1 + 3 * nl) + o * eo) + (o * k + nl * d * d) * eo
+                   for o, k, d in zip(w.tm_out, kin, tw))
     kernels = {}
     for name, (ms, n) in sorted(full.items()):
-        per = ms / n
-        kernels[name] = dict(ms_per_launch=round(per, 4), launches_per_step=n // nb,
+        kernels[name] = dict(ms_per_launch=round(ms / n, 4), launches_per_step=n // nb,
                              ms_per_step=round(ms / nb, 4))
-    # dominant kernel by time inside the timed region
-    dom = max(prof.items(), key=lambda kv: kv[1][0])[0]
-    dom_ms = prof[dom][0] / prof[dom][1]
-    if dom in bytes_of:
-        achieved = bytes_of[dom] / (dom_ms * 1e-3) / 1e9
-        roofline = dict(kernel=dom, bound="hbm", achieved=round(achieved, 1), peak=HBM_PEAK_GBS,
-                        unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
-                        ms_per_launch=round(dom_ms, 4), algorithmic_bytes=int(bytes_of[dom]))
-    else:
-        achieved = tm_flops / (dom_ms * 1e-3) / 1e12
-        roofline = dict(kernel=dom, bound="mfma", achieved=round(achieved, 2),
-                        peak=MFMA_PEAK_TFLOPS_16BIT, unit="TFLOP/s",
-                        frac=round(achieved / MFMA_PEAK_TFLOPS_16BIT, 4), traffic=None,
-                        ms_per_launch=round(dom_ms, 4))
-    others = {}
-    for name in timed:
-        if name == dom or name not in prof:
-            continue
-        ms = prof[name][0] / prof[name][1]
-        if name in bytes_of:
-            g = bytes_of[name] / (ms * 1e-3) / 1e9
-            others[name] = dict(ms_per_launch=round(ms, 4), achieved_GBs=round(g, 1),
-                                frac_hbm=round(g / HBM_PEAK_GBS, 4))
-        elif name == "tm_gemm":
-            tf = tm_flops / (ms * 1e-3) / 1e12
-            tm_bytes = sum(B * (k * eo + o * eo) for o, k in zip(w.tm_out, kin))
-            others[name] = dict(ms_per_launch=round(ms, 4), achieved_TFLOPs=round(tf, 2),
-                                frac_mfma=round(tf / MFMA_PEAK_TFLOPS_16BIT, 4),
-                                achieved_GBs=round(tm_bytes / (ms * 1e-3) / 1e9, 1))
 
+    def describe(name):
+        """Roofline entry of one kernel family from the timed region (all its launches of a step
+        taken together)."""
+        ms, n = prof[name]
+        per_step = ms / args.steps
+        launches = n // args.steps
+        if name in bytes_of:
+            g = bytes_of[name] / (per_step * 1e-3) / 1e9
+            if name == "radix_scatter":
+                g *= launches                   # bytes_of is per pass
+            return dict(kernel=name, bound="hbm", achieved=round(g, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=round(g / HBM_PEAK_GBS, 4), traffic=None,
+                        ms_per_launch=round(per_step / launches, 4), launches_per_step=launches,
+                        algorithmic_bytes=int(bytes_of[name]))
+        tf = tm_flops / (per_step * 1e-3) / 1e12
+        return dict(kernel=name, bound="mfma", achieved=round(tf, 2), peak=MFMA_PEAK_TFLOPS_16BIT,
+                    unit="TFLOP/s", frac=round(tf / MFMA_PEAK_TFLOPS_16BIT, 4), traffic=None,
+                    ms_per_launch=round(per_step / launches, 4), launches_per_step=launches,
+                    algorithmic_flops=int(tm_flops),
+                    achieved_GBs=round(tm_bytes / (per_step * 1e-3) / 1e9, 1))
+
+    dom = max(prof.items(), key=lambda kv: kv[1][0])[0]
+    roofline = describe(dom)
+    # L2<->fabric bytes per launch cannot be counted in this process: they come from the separate
+    # rocprofv3 --pmc runs of this same command whose summary is committed under profiles/
+    tfile = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                         "bench_%s_hbm_traffic.json" % w.name)
+    if os.path.exists(tfile):
+        tj = json.load(open(tfile))
+        if dom in tj.get("per_launch", {}):
+            roofline["traffic"] = tj["per_launch"][dom]["bytes"]
+            roofline["traffic_source"] = tj["source"]
+    others = {n: describe(n) for n in timed if n in prof and n != dom}
+
+    names = {"backward": "backward (Mid tables and lookups: lookup fwd + dot-product TM fwd + sorted "
+                         "segment-reduce bwd + rowwise Adagrad)",
+             "mid": "mid (lookup fwd + dot-product TM fwd)",
+             "large": "large (lookup fwd + 2 cross layers + projection TM fwd)",
+             "imbalanced": "imbalanced (lookup fwd + linear TM fwd + bwd + rowwise Adagrad)",
+             "tiny": "tiny"}
     out = {
         "metric": "tower lookup+TM samples/sec; achieved HBM GB/s and % of peak (fwd, bwd)",
         "value": round(B / (ms_per_step * 1e-3), 1),
@@ -226,12 +268,10 @@ def main():
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "backward (Mid tables and lookups: lookup fwd + dot-product TM fwd "
-                               "+ sorted segment-reduce bwd + rowwise Adagrad)" if w.name == "backward"
-                   else w.name,
-                   "tables": F, "rows": w.rows[0], "dim": D, "table_dtype": w.table_dtype,
-                   "towers": T, "batch": B, "mean_nnz": int(nnz), "mean_unique_rows": int(U),
-                   "duplicate_fraction": round(1 - U / nnz, 3), "id_batches": nb},
+        "config": {"workload": names[w.name], "tables": F, "rows": [min(w.rows), max(w.rows)],
+                   "dims": sorted(set(w.dims)), "table_dtype": w.table_dtype, "towers": T, "batch": B,
+                   "mean_nnz": int(nnz), "mean_unique_rows": int(U),
+                   "duplicate_fraction": round(1 - U / max(nnz, 1.0), 3), "id_batches": nb},
         "roofline": roofline,
         "cpu_baseline": cpu["baseline"] if cpu else None,
         "other_kernels": others,

@@ -358,3 +358,51 @@ def tm_weights(w: Workload):
             b_proj=rng.uniform(-s, s, size=w.tm_out[t]).astype(np.float32),
             w_cross=wc, b_cross=bc))
     return out
+
+
+# --------------------------------------------------------------------------
+# device-side batch generation (torch), for configurations whose id streams are
+# too large to draw with numpy in reasonable time (Large: 126 M ids over tables
+# of up to 10 M rows; Imbalanced: 8.4 M bags).  Same distributions as above, a
+# different (torch) random stream.
+# --------------------------------------------------------------------------
+
+def lookup_batch_device(w: Workload, batch_id: int = 0, device="cuda"):
+    """(indices int32 [nnz], offsets int64 [F*B + 1]) as device tensors."""
+    import torch
+    g = torch.Generator(device=device)
+    B = w.batch
+    lens = []
+    for f in range(w.num_tables):
+        g.manual_seed(((w.seed * 1000 + batch_id) << 20) + (_S_LEN << 16) + f)
+        if w.len_dist == "uniform":
+            l = torch.randint(1, int(w.len_param) + 1, (B,), generator=g, device=device)
+        elif w.len_dist == "poisson":
+            rate = torch.full((B,), float(w.len_param), device=device)
+            l = torch.poisson(rate, generator=g).clamp_(max=w.len_cap).to(torch.int64)
+        else:
+            u = 1.0 - torch.rand(B, generator=g, device=device, dtype=torch.float64)
+            l = torch.floor(u ** (-1.0 / w.len_param)).clamp_(max=w.len_cap).to(torch.int64)
+        lens.append(l)
+    lens = torch.cat(lens)
+    offsets = torch.zeros(w.num_tables * B + 1, dtype=torch.int64, device=device)
+    torch.cumsum(lens, 0, out=offsets[1:])
+    bounds = offsets[::B].cpu().tolist()
+    indices = torch.empty(bounds[-1], dtype=torch.int32, device=device)
+    for f in range(w.num_tables):
+        lo, hi = bounds[f], bounds[f + 1]
+        rows = w.rows[f]
+        g.manual_seed(((w.seed * 1000 + batch_id) << 20) + (_S_RANK << 16) + f)
+        if w.zipf_alpha is None:
+            indices[lo:hi] = torch.randint(0, rows, (hi - lo,), generator=g, device=device, dtype=torch.int32)
+            continue
+        k = torch.arange(1, rows + 1, device=device, dtype=torch.float64)
+        cdf = torch.cumsum(k.pow_(-w.zipf_alpha), 0)
+        cdf /= cdf[-1].clone()
+        u = torch.rand(hi - lo, generator=g, device=device, dtype=torch.float64)
+        r = torch.searchsorted(cdf, u).clamp_(max=rows - 1)
+        g.manual_seed((w.seed << 20) + (_S_PERM << 16) + f)          # same permutation for every batch
+        perm = torch.randperm(rows, generator=g, device=device)
+        indices[lo:hi] = perm[r].to(torch.int32)
+        del k, cdf, u, r, perm
+    return indices, offsets
