@@ -10,6 +10,9 @@
 // Data in the workspace: 64-bit records (global_row << 32 | bag), where
 // global_row = (sum of rows of earlier tables) + row and bag = f*B + b.  Ids
 // outside their table get global_row = total_rows (sorts last, never touched).
+// `offsets` must tile [0, nnz) (ascending, offsets[0] = 0, last = nnz): a record
+// no bag covers is never initialised; the kernels still keep every access in
+// bounds for any record contents, but the values written are then unspecified.
 #include <type_traits>
 
 #include "dmt_internal.h"
@@ -18,7 +21,16 @@
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kSortItems = 16;
+#ifndef DMT_SORT_ITEMS
+#define DMT_SORT_ITEMS 16
+#endif
+#ifndef DMT_RADIX_BITS
+#define DMT_RADIX_BITS 8
+#endif
+constexpr int kSortItems = DMT_SORT_ITEMS;
+constexpr int kMaxRadixBits = DMT_RADIX_BITS;      // digit width of one sort pass
+constexpr int kMaxRadix = 1 << kMaxRadixBits;
+constexpr int kDigitsPerThread = (kMaxRadix + kBlock - 1) / kBlock;
 constexpr int kSortTile = kBlock * kSortItems;   // records per sort block
 constexpr int kScanItems = 16;
 constexpr int kScanTile = kBlock * kScanItems;   // records per head-scan block
@@ -31,8 +43,8 @@ constexpr int kReduceUnroll = DMT_RU;
 struct BwdWs {
   uint64_t* pk_a;
   uint64_t* pk_b;
-  uint32_t* hist;         // [256][nblk_sort]
-  uint32_t* digit_total;  // [256]
+  uint32_t* hist;         // [kMaxRadix][nblk_sort]
+  uint32_t* digit_total;  // [kMaxRadix]
   uint32_t* blk_heads;    // [nblk_scan]
   uint32_t* seg_off;      // [nnz + 1]
   uint32_t* tile_first;   // [ntiles + 1] run heads before each reduce tile
@@ -56,8 +68,8 @@ BwdWs carve(const dmt_plan* p, int64_t nnz, void* base) {
   };
   w.pk_a = (uint64_t*)take(sizeof(uint64_t) * n);
   w.pk_b = (uint64_t*)take(sizeof(uint64_t) * n);
-  w.hist = (uint32_t*)take(sizeof(uint32_t) * 256 * w.nblk_sort);
-  w.digit_total = (uint32_t*)take(sizeof(uint32_t) * 256);
+  w.hist = (uint32_t*)take(sizeof(uint32_t) * kMaxRadix * w.nblk_sort);
+  w.digit_total = (uint32_t*)take(sizeof(uint32_t) * kMaxRadix);
   w.blk_heads = (uint32_t*)take(sizeof(uint32_t) * (w.nblk_scan + 1));
   w.seg_off = (uint32_t*)take(sizeof(uint32_t) * (n + 1));
   w.tile_first = (uint32_t*)take(sizeof(uint32_t) * (w.ntiles + 1));
@@ -95,20 +107,13 @@ __global__ __launch_bounds__(kBlock) void bwd_build_keys(
   }
 }
 
-// A record no bag covers (offsets that do not tile [0, nnz)) must still be inert.
-__global__ __launch_bounds__(kBlock) void bwd_fill_inert(uint64_t* __restrict__ pk, int64_t nnz,
-                                                         uint32_t total_rows) {
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i < nnz) pk[i] = ((uint64_t)total_rows << 32) | 0xffffffffu;
-}
-
 // ------------------------------------------------------------------ radix sort
 
 __global__ __launch_bounds__(kBlock) void radix_hist(const uint64_t* __restrict__ pk, int64_t nnz,
                                                      int shift, int bits,
                                                      uint32_t* __restrict__ hist, int64_t nblk) {
-  __shared__ uint32_t h[256];
-  h[threadIdx.x] = 0;
+  __shared__ uint32_t h[kMaxRadix];
+  for (int d = threadIdx.x; d < kMaxRadix; d += kBlock) h[d] = 0;
   __syncthreads();
   const uint32_t mask = (1u << bits) - 1;
   const int64_t base = (int64_t)blockIdx.x * kSortTile;
@@ -118,7 +123,8 @@ __global__ __launch_bounds__(kBlock) void radix_hist(const uint64_t* __restrict_
     if (pos < nnz) atomicAdd(&h[(uint32_t)(pk[pos] >> (32 + shift)) & mask], 1u);
   }
   __syncthreads();
-  if (threadIdx.x < (1u << bits)) hist[(int64_t)threadIdx.x * nblk + blockIdx.x] = h[threadIdx.x];
+  for (int d = threadIdx.x; d < (1 << bits); d += kBlock)
+    hist[(int64_t)d * nblk + blockIdx.x] = h[d];
 }
 
 // One block per digit: exclusive scan of that digit's per-block counts, in place.
@@ -142,18 +148,21 @@ __global__ __launch_bounds__(kBlock) void radix_scatter(
     const uint64_t* __restrict__ in, uint64_t* __restrict__ out, int64_t nnz, int shift, int bits,
     const uint32_t* __restrict__ hist, const uint32_t* __restrict__ digit_total, int64_t nblk) {
   __shared__ uint64_t buf[kSortTile];
-  __shared__ uint32_t cnt[kBlock / 64][256];
-  __shared__ uint32_t tile_start[256];
-  __shared__ uint32_t gbase[256];
+  __shared__ uint32_t cnt[kBlock / 64][kMaxRadix];
+  __shared__ uint32_t tile_start[kMaxRadix];
+  __shared__ uint32_t gbase[kMaxRadix];
   __shared__ uint32_t sm[8];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const uint32_t radix = 1u << bits, mask = radix - 1;
-  for (int w = 0; w < kBlock / 64; ++w) cnt[w][tid] = 0;
+  const int radix = 1 << bits;
+  const uint32_t mask = (uint32_t)radix - 1;
+  for (int w = 0; w < kBlock / 64; ++w)
+    for (int d = tid; d < kMaxRadix; d += kBlock) cnt[w][d] = 0;
   __syncthreads();
   const int64_t tile_base = (int64_t)blockIdx.x * kSortTile;
   const int n_tile = (int)min((int64_t)kSortTile, nnz - tile_base);
   volatile uint32_t* my_cnt = cnt[wave];
 
+  // stable rank of every record among the records of its wave with the same digit
   uint64_t rec[kSortItems];
   uint32_t rank[kSortItems];
 #pragma unroll
@@ -162,8 +171,7 @@ __global__ __launch_bounds__(kBlock) void radix_scatter(
     const bool valid = q < n_tile;
     rec[i] = valid ? in[tile_base + q] : ~0ULL;
     const uint32_t d = (uint32_t)(rec[i] >> (32 + shift)) & mask;
-    // lanes of this wave holding the same digit
-    uint64_t peers = __ballot(valid);
+    uint64_t peers = __ballot(valid);              // lanes of this wave holding the same digit
     for (int b = 0; b < bits; ++b) {
       const bool bit = (d >> b) & 1;
       const uint64_t m = __ballot(bit);
@@ -183,24 +191,40 @@ __global__ __launch_bounds__(kBlock) void radix_scatter(
     __builtin_amdgcn_wave_barrier();
   }
   __syncthreads();
-  // digit totals over the waves; cnt becomes each wave's offset inside the digit
-  uint32_t tot = 0;
-  if (tid < (int)radix) {
-    uint32_t run = 0;
-    for (int w = 0; w < kBlock / 64; ++w) {
-      const uint32_t c = cnt[w][tid];
-      cnt[w][tid] = run;
-      run += c;
+  // thread t owns digits t*DPT .. t*DPT+DPT-1: totals over the waves; cnt becomes each
+  // wave's offset inside the digit
+  uint32_t tot[kDigitsPerThread], dt[kDigitsPerThread];
+  uint32_t tsum = 0, dsum = 0;
+#pragma unroll
+  for (int j = 0; j < kDigitsPerThread; ++j) {
+    const int d = tid * kDigitsPerThread + j;
+    tot[j] = 0;
+    dt[j] = 0;
+    if (d < radix) {
+      uint32_t run = 0;
+      for (int w = 0; w < kBlock / 64; ++w) {
+        const uint32_t c = cnt[w][d];
+        cnt[w][d] = run;
+        run += c;
+      }
+      tot[j] = run;
+      dt[j] = digit_total[d];
     }
-    tot = run;
+    tsum += tot[j];
+    dsum += dt[j];
   }
   uint32_t total;
-  const uint32_t ex = dmt::block_exclusive_scan<kBlock / 64>(tot, sm, total);
-  const uint32_t dt = tid < (int)radix ? digit_total[tid] : 0;
-  const uint32_t dex = dmt::block_exclusive_scan<kBlock / 64>(dt, sm, total);
-  if (tid < (int)radix) {
-    tile_start[tid] = ex;
-    gbase[tid] = dex + hist[(int64_t)tid * nblk + blockIdx.x] - ex;
+  uint32_t ex = dmt::block_exclusive_scan<kBlock / 64>(tsum, sm, total);
+  uint32_t dex = dmt::block_exclusive_scan<kBlock / 64>(dsum, sm, total);
+#pragma unroll
+  for (int j = 0; j < kDigitsPerThread; ++j) {
+    const int d = tid * kDigitsPerThread + j;
+    if (d < radix) {
+      tile_start[d] = ex;
+      gbase[d] = dex + hist[(int64_t)d * nblk + blockIdx.x] - ex;
+    }
+    ex += tot[j];
+    dex += dt[j];
   }
   __syncthreads();
 #pragma unroll
@@ -371,7 +395,8 @@ template <> struct RowChunk<DMT_F32> { using type = float4; static constexpr int
 #ifndef DMT_QS
 #define DMT_QS 5
 #endif
-constexpr int kQueueSlots = DMT_QS;   // finished runs a lane group parks before their rows are updated
+constexpr int kQueueSlots = DMT_QS;
+constexpr int kQueueSlotsWave = 8;  // the wave-per-tile kernel parks 8 (its slots are half as large)   // finished runs a lane group parks before their rows are updated
 
 // Each group of GL = 2^LG lanes walks one tile of kReduceTile sorted records,
 // summing the bags' gradient slices run by run (float32, record order).  Runs
@@ -429,11 +454,7 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update(
   int qn = 0;
 
   auto park = [&]() {                            // the open run is complete: queue its update
-#ifdef DMT_PROBE_NOUPDATE
-    if (cur_ok && acc.x == 12345.f) {
-#else
     if (cur_ok) {
-#endif
       q_g[qn][threadIdx.x] = acc;
       q_rowp[group][qn] = cur_rowp;
       q_stp[group][qn] = cur_stp;
@@ -456,16 +477,8 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update(
           D[u] = UD ? Dmax : q_D[group][j0 + u];
           wp[u] = (Chunk*)(q_rowp[group][j0 + u]) + gl;
           sp[u] = (float*)(q_stp[group][j0 + u]);
-#ifdef DMT_PROBE_NOSTLOAD
-          st[u] = 0.5f;
-#else
           st[u] = *sp[u];
-#endif
-#ifdef DMT_PROBE_NOROWLOAD
-          if (gl * 4 < D[u]) w[u] = Chunk{};
-#else
           if (gl * 4 < D[u]) w[u] = *wp[u];
-#endif
         }
       }
 #pragma unroll
@@ -473,7 +486,7 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update(
         if (j0 + u < qn && j0 + u < kQueueSlots) {
           const float4 g = q_g[j0 + u][threadIdx.x];
           const float ss = group_sum<LG>(g.x * g.x + g.y * g.y + g.z * g.z + g.w * g.w);
-          const float sn = st[u] + ss / (float)D[u];
+          const float sn = st[u] + ss * __builtin_amdgcn_rcpf((float)D[u]);
           const float step = lr * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(sn) + eps);
           if (gl * 4 < D[u]) {
             if constexpr (TD == DMT_F32) {
@@ -485,17 +498,10 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update(
               dmt::unpack2<TD>(w[u].x, a, b);
               dmt::unpack2<TD>(w[u].y, c, d);
               a -= step * g.x; b -= step * g.y; c -= step * g.z; d -= step * g.w;
-#ifdef DMT_PROBE_NOROWSTORE
-              if (a == 12345.f)
-#endif
               *wp[u] = make_uint2(dmt::pack2<TD>(a, b), dmt::pack2<TD>(c, d));
             }
           }
-#ifdef DMT_PROBE_NOSTSTORE
-          if (gl == 0 && sn == 12345.f) *sp[u] = sn;
-#else
           if (gl == 0) *sp[u] = sn;
-#endif
         }
       }
     }
@@ -515,12 +521,14 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update(
       if (k < total_rows && bag < nbags) {
         const uint32_t f = bag / B, b = bag - f * B;
         const DmtTableMeta& m = meta[f];
-        key_l = k;
-        D_l = m.D;
-        goff4_l = (uint32_t)(((int64_t)B * m.out_prefix + (int64_t)b * m.tower_width + m.col_off) >> 2);
         const int64_t row = (int64_t)k - m.row_base;
-        rowp_l = (unsigned long long)((const char*)m.table + row * D_l * eb);
-        stp_l = (unsigned long long)(m.state + row);
+        if (row >= 0 && row < m.rows) {            // key and bag agree on the table
+          key_l = k;
+          D_l = m.D;
+          goff4_l = (uint32_t)(((int64_t)B * m.out_prefix + (int64_t)b * m.tower_width + m.col_off) >> 2);
+          rowp_l = (unsigned long long)((const char*)m.table + row * D_l * eb);
+          stp_l = (unsigned long long)(m.state + row);
+        }
       }
     }
     // run heads of this sub-round as a bit mask, one bit per record
@@ -545,11 +553,7 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update(
         bool on = lane_on && i0 + u < cnt && go != 0xffffffffu;
         if (!UD) on = on && gl * 4 < __shfl(D_l, src);
         g[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-#ifdef DMT_PROBE_NOGRAD
-        if (on) g[u] = make_float4(go, 1.f, 2.f, 3.f);
-#else
         if (on) g[u] = grad4[(size_t)go + gl];
-#endif
       }
 #pragma unroll
       for (int u = 0; u < kReduceUnroll; ++u) {
@@ -583,6 +587,306 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update(
   drain();
 }
 
+// The same tile walk for wide rows (64 < Dmax <= 256), one WAVE per tile: the 64
+// lanes hold EPL = Dmax/64 columns each, so every per-record decision (run head,
+// tile end, queue state) is wave-uniform and lives in scalar registers: record
+// fields are fetched with v_readlane instead of ds_bpermute, branches are
+// scalar, and the two half-waves never diverge.  Same queue-and-drain scheme,
+// same partial-slot protocol, same float32 summation order as bwd_reduce_update.
+template <int EPL> struct LaneVec;
+template <> struct LaneVec<1> { using type = float; };
+template <> struct LaneVec<2> { using type = float2; };
+template <> struct LaneVec<4> { using type = float4; };
+
+template <int EPL> __device__ __forceinline__ void lv_zero(typename LaneVec<EPL>::type& a) {
+  if constexpr (EPL == 1) a = 0.f;
+  else if constexpr (EPL == 2) a = make_float2(0.f, 0.f);
+  else a = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+template <int EPL>
+__device__ __forceinline__ void lv_add(typename LaneVec<EPL>::type& a,
+                                       const typename LaneVec<EPL>::type& b) {
+  if constexpr (EPL == 1) a += b;
+  else if constexpr (EPL == 2) { a.x += b.x; a.y += b.y; }
+  else { a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w; }
+}
+template <int EPL> __device__ __forceinline__ float lv_sumsq(const typename LaneVec<EPL>::type& a) {
+  if constexpr (EPL == 1) return a * a;
+  else if constexpr (EPL == 2) return a.x * a.x + a.y * a.y;
+  else return a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+}
+
+// row[lane*EPL .. +EPL) -= step * g, in the table's element type
+template <int TD, int EPL>
+__device__ __forceinline__ void lane_row_update(void* rowp, int lane,
+                                                const typename LaneVec<EPL>::type& g, float step,
+                                                const void* loaded) {
+  if constexpr (TD == DMT_F32) {
+    using V = typename LaneVec<EPL>::type;
+    V v = *(const V*)loaded;
+    if constexpr (EPL == 1) v -= step * g;
+    else if constexpr (EPL == 2) { v.x -= step * g.x; v.y -= step * g.y; }
+    else { v.x -= step * g.x; v.y -= step * g.y; v.z -= step * g.z; v.w -= step * g.w; }
+    ((V*)rowp)[lane] = v;
+  } else if constexpr (EPL == 1) {
+    const uint16_t u = *(const uint16_t*)loaded;
+    float a = TD == DMT_F16 ? dmt::f16_bits_to_f32(u) : dmt::bf16_lo(u);
+    a -= step * g;
+    ((uint16_t*)rowp)[lane] =
+        (uint16_t)(TD == DMT_F16 ? dmt::f32_to_f16_bits(a) : dmt::f32_to_bf16_bits(a));
+  } else if constexpr (EPL == 2) {
+    float a, b;
+    dmt::unpack2<TD>(*(const uint32_t*)loaded, a, b);
+    a -= step * g.x; b -= step * g.y;
+    ((uint32_t*)rowp)[lane] = dmt::pack2<TD>(a, b);
+  } else {
+    const uint2 u = *(const uint2*)loaded;
+    float a, b, c, d;
+    dmt::unpack2<TD>(u.x, a, b);
+    dmt::unpack2<TD>(u.y, c, d);
+    a -= step * g.x; b -= step * g.y; c -= step * g.z; d -= step * g.w;
+    ((uint2*)rowp)[lane] = make_uint2(dmt::pack2<TD>(a, b), dmt::pack2<TD>(c, d));
+  }
+}
+
+template <int TD, int EPL> struct LaneChunk {            // a lane's EPL elements of a table row
+  using type = typename LaneVec<EPL>::type;
+};
+template <int EPL> struct LaneChunk<DMT_F16, EPL> {
+  using type = std::conditional_t<EPL == 1, uint16_t, std::conditional_t<EPL == 2, uint32_t, uint2>>;
+};
+template <int EPL> struct LaneChunk<DMT_BF16, EPL> {
+  using type = typename LaneChunk<DMT_F16, EPL>::type;
+};
+
+__device__ __forceinline__ unsigned long long readlane64(unsigned long long v, int l) {
+  const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)v, l);
+  const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)(v >> 32), l);
+  return ((unsigned long long)hi << 32) | lo;
+}
+
+template <int TD, int EPL, bool UD>
+__global__ __launch_bounds__(kBlock) void bwd_reduce_update_wave(
+    const DmtTableMeta* __restrict__ meta, const uint64_t* __restrict__ pk, int64_t nnz, uint32_t B,
+    uint32_t nbags, uint32_t total_rows, const float* __restrict__ grad,
+    float* __restrict__ partials, int Dmax, int64_t ntiles, int64_t blocks_per_xcd, float lr,
+    float eps) {
+  constexpr int NW = kBlock / 64;
+  constexpr int eb = TD == DMT_F32 ? 4 : 2;
+  using Vec = typename LaneVec<EPL>::type;
+  using Chunk = typename LaneChunk<TD, EPL>::type;
+  __shared__ Vec q_g[kQueueSlotsWave][kBlock];
+  __shared__ unsigned long long q_rowp[NW][kQueueSlotsWave + 1];
+  __shared__ unsigned long long q_stp[NW][kQueueSlotsWave + 1];
+  __shared__ int q_D[NW][kQueueSlotsWave + 1];
+
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const int64_t tb = (int64_t)(blockIdx.x & 7) * blocks_per_xcd + (blockIdx.x >> 3);
+  const int64_t t = tb * NW + wave;
+  if (t >= ntiles) return;
+  const bool lane_on = lane * EPL < Dmax;
+  const Vec* __restrict__ gradv = (const Vec*)grad;
+
+  const int64_t p0 = t * kReduceTile;
+  const int n = (int)min((int64_t)kReduceTile, nnz - p0);
+  const uint32_t first_key = __builtin_amdgcn_readfirstlane((uint32_t)(pk[p0] >> 32));
+  uint32_t carry = 0;
+  bool cont_prev = false;
+  if (p0 > 0) {
+    carry = __builtin_amdgcn_readfirstlane((uint32_t)(pk[p0 - 1] >> 32));
+    cont_prev = carry == first_key;
+  }
+  bool cont_next = false;
+  if (p0 + n < nnz)
+    cont_next = __builtin_amdgcn_readfirstlane((uint32_t)(pk[p0 + n - 1] >> 32)) ==
+                __builtin_amdgcn_readfirstlane((uint32_t)(pk[p0 + n] >> 32));
+  bool has_prev = p0 > 0;
+  bool run_open = cont_prev, from_left = cont_prev;
+  Vec acc;
+  lv_zero<EPL>(acc);
+  bool cur_ok = false;
+  int qn = 0;
+
+  auto store_part = [&](int64_t slot) {
+    if (lane_on) ((Vec*)(partials + slot * Dmax))[lane] = acc;
+  };
+  // the open run's row / state address sit in queue slot qn already (its head lane put
+  // them there); parking adds the gradient sum and commits the slot
+  auto park = [&]() {
+    if (cur_ok) {
+      q_g[qn][threadIdx.x] = acc;
+      ++qn;
+    }
+  };
+  auto drain = [&]() {
+    const int open_slot = qn;                      // may hold the open run's addresses
+    if constexpr (EPL == 2) {
+      // two parked rows per step: lanes 0-31 take one, lanes 32-63 the next (4 columns a lane)
+      using Chunk2 = typename RowChunk<TD>::type;
+      const int half = lane >> 5, hl = lane & 31;
+#pragma unroll
+      for (int j0 = 0; j0 < kQueueSlotsWave; j0 += 8) {
+        if (j0 >= qn) break;
+        Chunk2 w[4];
+        float st[4];
+        Chunk2* wp[4];
+        float* sp[4];
+        int D[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int j = j0 + 2 * u + half;
+          if (j < qn && j < kQueueSlotsWave) {
+            D[u] = UD ? Dmax : q_D[wave][j];
+            wp[u] = (Chunk2*)q_rowp[wave][j] + hl;
+            sp[u] = (float*)q_stp[wave][j];
+            // row and state are touched once per call: keep them from evicting gradient slices
+            st[u] = __builtin_nontemporal_load(sp[u]);
+            if (hl * 4 < D[u]) w[u] = dmt::nt_load(wp[u]);
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int j = j0 + 2 * u + half;
+          if (j < qn && j < kQueueSlotsWave) {
+            const float4 g = ((const float4*)&q_g[j][wave * 64])[hl];
+            const float ss = group_sum<5>(g.x * g.x + g.y * g.y + g.z * g.z + g.w * g.w);
+            const float sn = st[u] + ss * __builtin_amdgcn_rcpf((float)D[u]);
+            const float step = lr * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(sn) + eps);
+            if (hl * 4 < D[u]) {
+              if constexpr (TD == DMT_F32) {
+                float4 v = w[u];
+                v.x -= step * g.x; v.y -= step * g.y; v.z -= step * g.z; v.w -= step * g.w;
+                dmt::nt_store(v, wp[u]);
+              } else {
+                float a, b, c, d;
+                dmt::unpack2<TD>(w[u].x, a, b);
+                dmt::unpack2<TD>(w[u].y, c, d);
+                a -= step * g.x; b -= step * g.y; c -= step * g.z; d -= step * g.w;
+                dmt::nt_store(make_uint2(dmt::pack2<TD>(a, b), dmt::pack2<TD>(c, d)), wp[u]);
+              }
+            }
+            if (hl == 0) __builtin_nontemporal_store(sn, sp[u]);
+          }
+        }
+      }
+    } else {
+#pragma unroll
+      for (int j0 = 0; j0 < kQueueSlotsWave; j0 += 4) {
+        if (j0 >= qn) break;
+        Chunk w[4];
+        float st[4];
+        void* wp[4];
+        float* sp[4];
+        int D[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (j0 + u < qn && j0 + u < kQueueSlotsWave) {
+            D[u] = UD ? Dmax : __builtin_amdgcn_readfirstlane(q_D[wave][j0 + u]);
+            wp[u] = (void*)q_rowp[wave][j0 + u];
+            sp[u] = (float*)q_stp[wave][j0 + u];
+            st[u] = *sp[u];
+            if (lane * EPL < D[u]) w[u] = ((const Chunk*)wp[u])[lane];
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (j0 + u < qn && j0 + u < kQueueSlotsWave) {
+            const Vec g = q_g[j0 + u][threadIdx.x];
+            float ss = group_sum<5>(lv_sumsq<EPL>(g));
+            ss = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ss), 0)) +
+                 __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ss), 32));
+            const float sn = st[u] + ss * __builtin_amdgcn_rcpf((float)D[u]);
+            const float step = lr * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(sn) + eps);
+            if (lane * EPL < D[u]) lane_row_update<TD, EPL>(wp[u], lane, g, step, &w[u]);
+            if (lane == 0) *sp[u] = sn;
+          }
+        }
+      }
+    }
+    // an open run keeps its addresses: move them to the slot it will be parked in now
+    if (open_slot > 0 && open_slot < kQueueSlotsWave + 1 && run_open && !from_left && lane == 0) {
+      q_rowp[wave][0] = q_rowp[wave][open_slot];
+      q_stp[wave][0] = q_stp[wave][open_slot];
+      if (!UD) q_D[wave][0] = q_D[wave][open_slot];
+    }
+    qn = 0;
+  };
+
+  for (int sub = 0; sub < n; sub += 64) {
+    const int cnt = min(64, n - sub);
+    uint32_t key_l = total_rows, goff_l = 0xffffffffu;
+    unsigned long long rowp_l = 0, stp_l = 0;
+    int D_l = 0;
+    if (lane < cnt) {
+      const uint64_t r = pk[p0 + sub + lane];
+      const uint32_t k = (uint32_t)(r >> 32), bag = (uint32_t)r;
+      if (k < total_rows && bag < nbags) {
+        const uint32_t f = bag / B, b = bag - f * B;
+        const DmtTableMeta& m = meta[f];
+        const int64_t row = (int64_t)k - m.row_base;
+        if (row >= 0 && row < m.rows) {            // key and bag agree on the table
+          key_l = k;
+          D_l = m.D;
+          goff_l = (uint32_t)(((int64_t)B * m.out_prefix + (int64_t)b * m.tower_width + m.col_off) >> 2);
+          rowp_l = (unsigned long long)((const char*)m.table + row * D_l * eb);
+          stp_l = (unsigned long long)(m.state + row);
+        }
+      }
+    }
+    uint32_t prev = __shfl_up(key_l, 1);
+    bool head_l = lane < cnt;
+    if (lane == 0) head_l = head_l && (!has_prev || key_l != carry);
+    else head_l = head_l && key_l != prev;
+    const unsigned long long hm = __ballot(head_l);
+    carry = __builtin_amdgcn_readlane(key_l, cnt - 1);
+    has_prev = true;
+
+    for (int i0 = 0; i0 < cnt; i0 += kReduceUnroll) {
+      Vec g[kReduceUnroll];
+#pragma unroll
+      for (int u = 0; u < kReduceUnroll; ++u) {
+        lv_zero<EPL>(g[u]);
+        if (i0 + u < cnt) {
+          const uint32_t go = __builtin_amdgcn_readlane(goff_l, i0 + u);
+          bool on = lane_on && go != 0xffffffffu;
+          if (!UD) on = on && lane * EPL < __builtin_amdgcn_readlane(D_l, i0 + u);
+          if (on) g[u] = gradv[((size_t)go << 2) / EPL + lane];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kReduceUnroll; ++u) {
+        const int i = i0 + u;
+        if (i < cnt) {
+          if ((hm >> i) & 1) {                     // a run starts at this record
+            if (run_open) {
+              if (from_left) store_part(2 * t);
+              else park();
+            }
+            from_left = false;
+            run_open = true;
+            lv_zero<EPL>(acc);
+            cur_ok = __builtin_amdgcn_readlane(key_l, i) < total_rows;
+            if (lane == i) {                         // the head record's lane knows the row
+              q_rowp[wave][qn] = rowp_l;
+              q_stp[wave][qn] = stp_l;
+              if (!UD) q_D[wave][qn] = D_l;
+            }
+          }
+          lv_add<EPL>(acc, g[u]);
+        }
+      }
+      if (qn > kQueueSlotsWave - kReduceUnroll) drain();
+    }
+  }
+  if (run_open) {
+    if (from_left) store_part(2 * t);
+    else if (cont_next) { if (cur_ok) store_part(2 * t + 1); }
+    else park();
+  }
+  drain();
+}
+
 // Table that owns global row id `gid` (row_base has F + 1 ascending entries).
 __device__ __forceinline__ uint32_t table_of(const int64_t* __restrict__ row_base, int F,
                                              uint32_t gid) {
@@ -600,7 +904,6 @@ template <int TD>
 __global__ __launch_bounds__(kBlock) void bwd_fixup_update(
     const DmtTableMeta* __restrict__ meta, const int64_t* __restrict__ row_base, int F,
     const uint64_t* __restrict__ pk, int64_t nnz, uint32_t total_rows,
-    const uint32_t* __restrict__ seg_off, const uint32_t* __restrict__ tile_first,
     const float* __restrict__ partials, int Dmax, int log2_gl, int64_t ntiles, float lr, float eps) {
   const int GL = 1 << log2_gl;
   const int64_t t0 = (int64_t)blockIdx.x * (kBlock >> log2_gl) + (threadIdx.x >> log2_gl);
@@ -611,9 +914,17 @@ __global__ __launch_bounds__(kBlock) void bwd_fixup_update(
   if (k_last != (uint32_t)(pk[p1] >> 32) || k_last >= total_rows) return;
   const uint32_t k_first = (uint32_t)(pk[p0] >> 32);
   if (k_first == k_last && p0 > 0 && (uint32_t)(pk[p0 - 1] >> 32) == k_first) return;
-  const uint32_t u = tile_first[t0 + 1] - 1;      // the run that contains p1 - 1
-  const int64_t end = seg_off[u + 1];
-  const int64_t t1 = (end - 1) / kReduceTile;
+  // last tile the run reaches: the largest t with the run's key at the tile's first record
+  // (gallop first: most runs end within a tile or two)
+  int64_t t1 = t0 + 1, hi = ntiles;               // holds at t1, fails at hi
+  for (int64_t step = 1; t1 + step < hi; step <<= 1) {
+    if ((uint32_t)(pk[(t1 + step) * kReduceTile] >> 32) == k_last) t1 += step;
+    else { hi = t1 + step; break; }
+  }
+  while (hi - t1 > 1) {
+    const int64_t mid = (t1 + hi) >> 1;
+    if ((uint32_t)(pk[mid * kReduceTile] >> 32) == k_last) t1 = mid; else hi = mid;
+  }
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   const bool on = gl * 4 < Dmax;
   if (on) acc = *((const float4*)(partials + (2 * t0 + 1) * Dmax) + gl);
@@ -702,10 +1013,10 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
 
   if (nnz > 0) {
     // keys
-    { DmtScope sc_(plan, DMT_K_BWD_KEYS, s); hipLaunchKernelGGL(bwd_fill_inert, dim3((unsigned)((nnz + kBlock - 1) / kBlock)), dim3(kBlock),
-                       0, s, w.pk_a, nnz, total_rows); }
     const double mean_len = (double)nnz / (double)nbags;
-    int log2_gl = ilog2_ceil((int64_t)(mean_len + 0.5));
+    // lanes per bag: about a quarter of the mean bag length (measured best on MI355X)
+    int log2_gl = ilog2_ceil((int64_t)(mean_len + 0.5)) - 2;
+    log2_gl = dmt::env_int("DMT_KEYS_LG", log2_gl);
     log2_gl = log2_gl < 2 ? 2 : (log2_gl > 6 ? 6 : log2_gl);
     const unsigned kb_blocks = (nbags + (kBlock >> log2_gl) - 1) / (kBlock >> log2_gl);
     { DmtScope sc_(plan, DMT_K_BWD_KEYS, s); hipLaunchKernelGGL(bwd_build_keys, dim3(kb_blocks), dim3(kBlock), 0, s, plan->d_meta, indices,
@@ -713,7 +1024,7 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
                        plan->d_error); }
     // stable LSD radix sort over the bits that can be set (values 0..total_rows)
     const int key_bits = ilog2_ceil((int64_t)total_rows + 1);
-    const int passes = (key_bits + 7) / 8;
+    const int passes = (key_bits + kMaxRadixBits - 1) / kMaxRadixBits;
     const int bits_per = (key_bits + passes - 1) / passes;
     uint64_t* src = w.pk_a;
     uint64_t* dst = w.pk_b;
@@ -729,13 +1040,6 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
       uint64_t* tmp = src; src = dst; dst = tmp;
     }
     sorted = src;
-    // run heads -> segment offsets
-    { DmtScope sc_(plan, DMT_K_BWD_HEADS, s); hipLaunchKernelGGL(heads_count, dim3((unsigned)w.nblk_scan), dim3(kBlock), 0, s, sorted, nnz,
-                       w.blk_heads); }
-    { DmtScope sc_(plan, DMT_K_BWD_HEADS, s); hipLaunchKernelGGL(heads_scan, dim3(1), dim3(1024), 0, s, w.blk_heads, w.nblk_scan,
-                       w.num_unique); }
-    { DmtScope sc_(plan, DMT_K_BWD_HEADS, s); hipLaunchKernelGGL(heads_write, dim3((unsigned)w.nblk_scan), dim3(kBlock), 0, s, sorted, nnz,
-                       w.blk_heads, w.seg_off, w.tile_first); }
     // segment reduce + update, then the rows that span tiles
     int log2_glb = ilog2_ceil(plan->max_dim / 4);
     if (log2_glb < 2) log2_glb = 2;
@@ -753,24 +1057,51 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
   if (log2_glb == LG) {                                                                           \
     if (ud) DMT_BWD_LAUNCH(TD, LG, true); else DMT_BWD_LAUNCH(TD, LG, false);                     \
   }
+    const bool wave_kernel = (plan->max_dim == 128 || plan->max_dim == 256) &&
+                             dmt::env_int("DMT_BWD_WAVE", 1) != 0;
+    const int epl = plan->max_dim / 64;
+    const int64_t wblocks_per_xcd = ((w.ntiles + kBlock / 64 - 1) / (kBlock / 64) + 7) / 8;
+#define DMT_BWD_WLAUNCH(TD, EPL, UD)                                                              \
+  hipLaunchKernelGGL((bwd_reduce_update_wave<TD, EPL, UD>), dim3((unsigned)(wblocks_per_xcd * 8)), \
+                     dim3(kBlock), 0, s, plan->d_meta, sorted, nnz, (uint32_t)B, nbags,           \
+                     total_rows, grad_pooled, w.partials, plan->max_dim, w.ntiles,                \
+                     wblocks_per_xcd, lr, eps)
+#define DMT_BWD_EPL(TD, EPL)                                                                      \
+  if (epl == EPL) {                                                                               \
+    if (ud) DMT_BWD_WLAUNCH(TD, EPL, true); else DMT_BWD_WLAUNCH(TD, EPL, false);                 \
+  }
 #define DMT_BWD_CASE(TD)                                                                          \
   if (td == TD) {                                                                                 \
     {                                                                                             \
       DmtScope sc_(plan, DMT_K_BWD_REDUCE_UPDATE, s);                                             \
-      DMT_BWD_LG(TD, 2) DMT_BWD_LG(TD, 3) DMT_BWD_LG(TD, 4) DMT_BWD_LG(TD, 5) DMT_BWD_LG(TD, 6)   \
+      if (wave_kernel) {                                                                          \
+        DMT_BWD_EPL(TD, 2) DMT_BWD_EPL(TD, 4)                                                     \
+      } else {                                                                                    \
+        DMT_BWD_LG(TD, 2) DMT_BWD_LG(TD, 3) DMT_BWD_LG(TD, 4) DMT_BWD_LG(TD, 5) DMT_BWD_LG(TD, 6) \
+      }                                                                                           \
     }                                                                                             \
     { DmtScope sc_(plan, DMT_K_BWD_FIXUP, s); hipLaunchKernelGGL((bwd_fixup_update<TD>), dim3((unsigned)rblocks), dim3(kBlock), 0, s,       \
                        plan->d_meta, plan->d_row_base, plan->F, sorted, nnz, total_rows,          \
-                       w.seg_off, w.tile_first, w.partials, plan->max_dim, log2_glb, w.ntiles,    \
-                       lr, eps); }                                                                  \
+                       w.partials, plan->max_dim, log2_glb, w.ntiles, lr, eps); }                                                                  \
   }
     DMT_BWD_CASE(DMT_F32) DMT_BWD_CASE(DMT_F16) DMT_BWD_CASE(DMT_BF16)
 #undef DMT_BWD_CASE
 #undef DMT_BWD_LG
 #undef DMT_BWD_LAUNCH
+#undef DMT_BWD_EPL
+#undef DMT_BWD_WLAUNCH
   }
   if (dbg && (dbg->sorted_keys || dbg->sorted_bag || dbg->unique_keys || dbg->seg_off ||
               dbg->num_unique)) {
+    if (nnz > 0) {
+    // run heads -> segment offsets (only the parity exports need them)
+      { DmtScope sc_(plan, DMT_K_BWD_HEADS, s); hipLaunchKernelGGL(heads_count, dim3((unsigned)w.nblk_scan), dim3(kBlock), 0, s, sorted, nnz,
+                         w.blk_heads); }
+      { DmtScope sc_(plan, DMT_K_BWD_HEADS, s); hipLaunchKernelGGL(heads_scan, dim3(1), dim3(1024), 0, s, w.blk_heads, w.nblk_scan,
+                         w.num_unique); }
+      { DmtScope sc_(plan, DMT_K_BWD_HEADS, s); hipLaunchKernelGGL(heads_write, dim3((unsigned)w.nblk_scan), dim3(kBlock), 0, s, sorted, nnz,
+                         w.blk_heads, w.seg_off, w.tile_first); }
+    }
     const int64_t n = nnz + 1;
     hipLaunchKernelGGL(bwd_export, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
                        plan->d_row_base, plan->F, sorted, nnz, total_rows, w.seg_off, w.num_unique,

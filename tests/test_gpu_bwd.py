@@ -111,6 +111,14 @@ def test_imbalanced_scaled_mixed_dims():
     check_bwd(wl.scaled(wl.imbalanced(), max_rows=5000, batch=1111, num_tables=24))
 
 
+@pytest.mark.parametrize("dims", [[32, 64], [64], [32], [256]])
+def test_narrow_and_wide_rows(dims):
+    """Dims up to 64 run the lane-group kernel, 128 / 256 the wave-per-tile kernel."""
+    w = wl.scaled(wl.imbalanced(), max_rows=3000, batch=400, num_tables=12)
+    w.dims = [dims[f % len(dims)] for f in range(12)]
+    check_bwd(w)
+
+
 def test_large_scaled_bf16():
     w = wl.scaled(wl.large(), max_rows=30000, batch=130, num_tables=40)
     w.backward = True
