@@ -175,6 +175,197 @@ __global__ __launch_bounds__(kBlock, 2) void tm_gemm_mfma(const TmLaunch L) {
   }
 }
 
+// ------------------------------------------- MFMA grouped GEMM, 256 x 256 tiles
+//
+// For wide outputs (N > 128).  A 128 x 128 block tile needs 1 byte from L2 per 64
+// FLOP, which caps the matrix cores at a fraction of their rate; 256 x 256 halves
+// that.  Eight waves (two per SIMD, so one wave's LDS waits hide behind the other's
+// MFMAs) of 128 x 64 each (4 x 2 MFMA tiles, 128 accumulator registers), one block
+// per CU, two LDS stages (147 KB of the CU's 160 KB): tile k+1 goes from registers
+// to LDS and the global loads of tile k+2 are issued before the MFMAs of tile k, so
+// a whole K step of matrix work covers the memory latency and one barrier per K
+// step suffices.
+constexpr int LBM = 256, LBN = 256;
+constexpr int kBigThreads = 512;
+constexpr int kSuper = 32;                                  // tiles an XCD keeps resident (its CUs)
+constexpr int kBigTileElems = LBM * kLdsStride;            // one operand, one stage
+constexpr int kBigLdsBytes = 4 * kBigTileElems * 2;         // 2 stages x (A + B)
+
+template <int DT>
+__global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunch L) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+  // XCD-aware rasterisation.  Consecutive block ids go to different XCDs, so block b belongs
+  // to XCD b % 8 and is that XCD's (b / 8)-th block.  The launch's tiles are cut into
+  // super-tiles of up to kSuper tiles (a few tile rows x all tile columns of one group) that
+  // are dealt to the XCDs in turn: the 32 blocks resident on an XCD then share their A rows
+  // and W columns in that XCD's L2 instead of every XCD pulling every A tile over the fabric.
+  // Here L.tile_start[] counts super-tiles.
+  const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+  const int gs = (idx / kSuper) * 8 + xcd, within = idx % kSuper;
+  if (gs >= L.tile_start[L.ngroups]) return;
+  int gi = 0;
+  while (gi + 1 < L.ngroups && gs >= L.tile_start[gi + 1]) ++gi;
+  const TmGroup& G = L.g[gi];
+  const int tiles_n = (G.N + LBN - 1) / LBN, tiles_m = (G.M + LBM - 1) / LBM;
+  const int sm = tiles_n >= kSuper ? 1 : kSuper / tiles_n;       // tile rows per super-tile
+  if (within >= sm * tiles_n) return;
+  const int tm = (gs - L.tile_start[gi]) * sm + within / tiles_n, tn = within % tiles_n;
+  if (tm >= tiles_m) return;
+  const int m0 = tm * LBM, n0 = tn * LBN;
+  const int M = G.M, N = G.N, K = G.K1;           // plain GEMM only: no dot-term segment
+  const uint16_t* __restrict__ A = (const uint16_t*)G.A1;
+  const uint16_t* __restrict__ W = (const uint16_t*)G.W;
+  const int lda = G.lda1, ldw = G.ldw;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 2, wn = wave & 3;        // 2 x 4 waves of 128 x 64
+  const int srow = tid >> 3, scol = (tid & 7) * 8;
+
+  floatx16 acc[4][2];
+#pragma clang loop unroll(full)
+  for (int i = 0; i < 4; ++i)
+#pragma clang loop unroll(full)
+    for (int j = 0; j < 2; ++j)
+#pragma clang loop unroll(full)
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // element offsets of this thread's 4 + 4 chunks at k = 0 (rows past the edge are clamped
+  // to the last row and zeroed on the way to LDS)
+  uint32_t offa[4], offb[4];
+  uint32_t oka = 0, okb = 0;
+#pragma clang loop unroll(full)
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + srow + i * 64, n = n0 + srow + i * 64;
+    offa[i] = (uint32_t)min(m, M - 1) * (uint32_t)lda + scol;
+    offb[i] = (uint32_t)min(n, N - 1) * (uint32_t)ldw + scol;
+    oka |= (m < M ? 1u : 0u) << i;
+    okb |= (n < N ? 1u : 0u) << i;
+  }
+
+  uint4 ra[4], rb[4];
+  // Loads are never predicated (edge rows are clamped to a valid row, a K tail to column 0),
+  // so they stay in flight across the multiply; edge tiles zero what they must not use when
+  // the registers are written to LDS.
+  const bool interior = m0 + LBM <= M && n0 + LBN <= N && K % BK == 0;
+  auto load_tile = [&](int kt) {
+    const int k = (kt * BK + scol < K) ? kt * BK : -scol;
+#pragma clang loop unroll(full)
+    for (int i = 0; i < 4; ++i) {
+      ra[i] = *(const uint4*)(A + offa[i] + k);
+      rb[i] = *(const uint4*)(W + offb[i] + k);
+    }
+  };
+  auto store_tile = [&](int stage, int kt) {
+    uint16_t* As = lds + stage * 2 * kBigTileElems;
+    uint16_t* Bs = As + kBigTileElems;
+    if (!interior) {
+      const bool kin = kt * BK + scol < K;
+#pragma clang loop unroll(full)
+      for (int i = 0; i < 4; ++i) {
+        if (!(kin && ((oka >> i) & 1))) ra[i] = make_uint4(0, 0, 0, 0);
+        if (!(kin && ((okb >> i) & 1))) rb[i] = make_uint4(0, 0, 0, 0);
+      }
+    }
+#pragma clang loop unroll(full)
+    for (int i = 0; i < 4; ++i) {
+      *(uint4*)(As + (srow + i * 64) * kLdsStride + scol) = ra[i];
+      *(uint4*)(Bs + (srow + i * 64) * kLdsStride + scol) = rb[i];
+    }
+  };
+
+  const int nk = (K + BK - 1) / BK;
+  load_tile(0);
+  store_tile(0, 0);
+  if (nk > 1) load_tile(1);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < nk) store_tile(cur ^ 1, kt + 1);
+    if (kt + 2 < nk) load_tile(kt + 2);
+    const uint16_t* ap = lds + cur * 2 * kBigTileElems + (wm * 128 + (lane & 31)) * kLdsStride +
+                         (lane >> 5) * 8;
+    const uint16_t* bp = lds + cur * 2 * kBigTileElems + kBigTileElems +
+                         (wn * 64 + (lane & 31)) * kLdsStride + (lane >> 5) * 8;
+#pragma clang loop unroll(full)
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      uint4 a[4], b[2];
+#pragma clang loop unroll(full)
+      for (int i = 0; i < 4; ++i) a[i] = *(const uint4*)(ap + i * 32 * kLdsStride + kk * 16);
+#pragma clang loop unroll(full)
+      for (int j = 0; j < 2; ++j) b[j] = *(const uint4*)(bp + j * 32 * kLdsStride + kk * 16);
+#pragma clang loop unroll(full)
+      for (int i = 0; i < 4; ++i)
+#pragma clang loop unroll(full)
+        for (int j = 0; j < 2; ++j) acc[i][j] = mfma32<DT>(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+
+  // Epilogue through LDS, one 128-row half of the tile at a time: the waves that own the half
+  // park their float32 accumulators (a lane holds one column of 16 rows: poor for global
+  // memory), then all 512 threads walk the half in 8-column pieces, so bias, x0, x_l and the
+  // output move as 16-byte accesses.
+  const int epi = G.epi;
+  float* stage = (float*)lds;
+  constexpr int kStageStride = LBN + 8;            // 4*stride % 64 == 32: conflict-free parking
+  const bool vec_ok =
+      G.ldc % 8 == 0 && n0 + LBN <= N && (((uintptr_t)G.C | (uintptr_t)G.bias) & 15) == 0 &&
+      (epi != EPI_CROSS ||
+       (G.ldx % 8 == 0 && lda % 8 == 0 && (((uintptr_t)G.X0 | (uintptr_t)G.A1) & 15) == 0));
+#pragma clang loop unroll(full)
+  for (int h = 0; h < 2; ++h) {
+    if (wm == h) {
+#pragma clang loop unroll(full)
+      for (int j = 0; j < 2; ++j)
+#pragma clang loop unroll(full)
+        for (int i = 0; i < 4; ++i)
+#pragma clang loop unroll(full)
+          for (int v = 0; v < 16; ++v) {
+            const int r = i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+            stage[r * kStageStride + wn * 64 + j * 32 + (lane & 31)] = acc[i][j][v];
+          }
+    }
+    __syncthreads();
+    for (int c = tid; c < 128 * (LBN / 8); c += kBigThreads) {
+      const int r = c / (LBN / 8), cc = (c % (LBN / 8)) * 8;
+      const int m = m0 + h * 128 + r, n = n0 + cc;
+      if (m >= M || n >= N) continue;
+      float y[8];
+      const float4 s0 = *(const float4*)(stage + r * kStageStride + cc);
+      const float4 s1 = *(const float4*)(stage + r * kStageStride + cc + 4);
+      y[0] = s0.x; y[1] = s0.y; y[2] = s0.z; y[3] = s0.w;
+      y[4] = s1.x; y[5] = s1.y; y[6] = s1.z; y[7] = s1.w;
+      if (vec_ok) {
+        float bv[8], xv[8], lv[8];
+        dmt::decode_chunk<DT>(bv, *(const uint4*)((const uint16_t*)G.bias + n));
+#pragma clang loop unroll(full)
+        for (int q = 0; q < 8; ++q) y[q] += bv[q];
+        if (epi == EPI_BIAS_RELU) {
+#pragma clang loop unroll(full)
+          for (int q = 0; q < 8; ++q) y[q] = y[q] > 0.f ? y[q] : 0.f;
+        }
+        if (epi == EPI_CROSS) {
+          dmt::decode_chunk<DT>(xv, *(const uint4*)((const uint16_t*)G.X0 + (int64_t)m * G.ldx + n));
+          dmt::decode_chunk<DT>(lv, *(const uint4*)(A + (int64_t)m * lda + n));
+#pragma clang loop unroll(full)
+          for (int q = 0; q < 8; ++q) y[q] = xv[q] * y[q] + lv[q];
+        }
+        dmt::store_chunk<DT, 8>(G.C, (int64_t)m * G.ldc + n, y);
+      } else {
+        for (int q = 0; q < 8 && n + q < N; ++q) {
+          float z = y[q] + load_elt<DT>(G.bias, n + q);
+          if (epi == EPI_BIAS_RELU) z = z > 0.f ? z : 0.f;
+          if (epi == EPI_CROSS)
+            z = load_elt<DT>(G.X0, (int64_t)m * G.ldx + n + q) * z +
+                load_elt<DT>(G.A1, (int64_t)m * lda + n + q);
+          store_elt<DT>(G.C, (int64_t)m * G.ldc + n + q, z);
+        }
+      }
+    }
+    __syncthreads();
+  }
+}
+
 // --------------------------------------------------- plain FMA GEMM (float32)
 
 template <int DT>
@@ -367,10 +558,38 @@ void launch_groups(const dmt_plan* p, std::vector<TmGroup>& groups, hipStream_t 
     }
     L.tile_start[L.ngroups] = tiles;
     if (tiles == 0) continue;
-    if constexpr (DT == DMT_F32)
-      { DmtScope sc_(p, DMT_K_TM_GEMM, s); hipLaunchKernelGGL((tm_gemm_simple<DT>), dim3(tiles), dim3(kBlock), 0, s, L); }
-    else
-      { DmtScope sc_(p, DMT_K_TM_GEMM, s); hipLaunchKernelGGL((tm_gemm_mfma<DT>), dim3(tiles), dim3(kBlock), 0, s, L); }
+    if constexpr (DT == DMT_F32) {
+      DmtScope sc_(p, DMT_K_TM_GEMM, s);
+      hipLaunchKernelGGL((tm_gemm_simple<DT>), dim3(tiles), dim3(kBlock), 0, s, L);
+    } else {
+      // wide outputs take the 256 x 256 kernel
+      bool big = dmt::env_int("DMT_TM_BIG", 1) != 0;
+      for (int i = 0; i < L.ngroups; ++i)
+        big = big && L.g[i].N > 128 && L.g[i].N <= kSuper * LBN && L.g[i].K0 == 0 && L.g[i].K1 >= 128 &&
+              (int64_t)L.g[i].M * L.g[i].lda1 < (1LL << 31) && (int64_t)L.g[i].N * L.g[i].ldw < (1LL << 31);
+      if (big) {
+        static bool configured = false;
+        if (!configured) {
+          (void)hipFuncSetAttribute((const void*)tm_gemm_mfma_256<DT>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
+          configured = true;
+        }
+        int32_t nst = 0;                                      // super-tiles of the launch
+        for (int i = 0; i < L.ngroups; ++i) {
+          L.tile_start[i] = nst;
+          const int tn = (L.g[i].N + LBN - 1) / LBN, tm = (L.g[i].M + LBM - 1) / LBM;
+          const int sm = tn >= kSuper ? 1 : kSuper / tn;
+          nst += (tm + sm - 1) / sm;
+        }
+        L.tile_start[L.ngroups] = nst;
+        const int32_t big_tiles = (nst + 7) / 8 * 8 * kSuper;
+        DmtScope sc_(p, DMT_K_TM_GEMM, s);
+        hipLaunchKernelGGL((tm_gemm_mfma_256<DT>), dim3(big_tiles), dim3(kBigThreads), kBigLdsBytes, s, L);
+      } else {
+        DmtScope sc_(p, DMT_K_TM_GEMM, s);
+        hipLaunchKernelGGL((tm_gemm_mfma<DT>), dim3(tiles), dim3(kBlock), 0, s, L);
+      }
+    }
   }
   groups.clear();
 }
