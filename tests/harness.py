@@ -117,17 +117,39 @@ class TowerModules:
 
     def oracle(self, x_towers):
         """x_towers: float64 [B, W_t] per tower (the values the TM reads)."""
-        import oracle
-        w = self.dw.w
+        return oracle_tm(self.dw.w, self.dec, x_towers)
+
+
+def tm_device_and_decoded(w, dtype=None):
+    """(per-tower dicts of device tensors for make_tm_params, per-tower dicts of float64 arrays
+    holding exactly the encoded values) for a workload's Tower-Module weights."""
+    dtype = dtype or w.tm_dtype
+    dev_list, dec_list = [], []
+    for t, hw in enumerate(wl.tm_weights(w)):
+        enc = lambda a: wl.encode(a, dtype)
+        dev = lambda a: to_device(enc(a), dtype)
+        dd = lambda a: wl.decode(enc(a), dtype)
+        dev_list.append(dict(kind=w.tm_kind, out_dim=w.tm_out[t], w_proj=dev(hw["w_proj"]), b_proj=dev(hw["b_proj"]),
+                             w_cross=[dev(a) for a in hw["w_cross"]], b_cross=[dev(a) for a in hw["b_cross"]]))
+        dec_list.append(dict(w_proj=dd(hw["w_proj"]), b_proj=dd(hw["b_proj"]),
+                             w_cross=[dd(a) for a in hw["w_cross"]], b_cross=[dd(a) for a in hw["b_cross"]]))
+    return dev_list, dec_list
+
+
+def oracle_tm(w, dec, x_towers, towers=None):
+    """The oracle's Tower Module on float64 inputs, tower by tower."""
+    import oracle
+    if True:
         ys = []
         for t, x in enumerate(x_towers):
-            d = self.dec[t]
+            d = dec[t if towers is None else towers[t]]
             if w.tm_kind == wl.TM_LINEAR:
                 y = oracle.tm_linear(x, d["w_proj"], d["b_proj"])
             elif w.tm_kind == wl.TM_LINEAR_RELU:
                 y = oracle.tm_linear(x, d["w_proj"], d["b_proj"], relu=True)
             elif w.tm_kind == wl.TM_DOT_LINEAR:
-                y = oracle.tm_dot_linear(x, len(w.tower_tables()[t]), d["w_proj"], d["b_proj"])
+                y = oracle.tm_dot_linear(x, len(w.tower_tables()[t if towers is None else towers[t]]),
+                                         d["w_proj"], d["b_proj"])
             else:
                 y = oracle.tm_cross_linear(x, d["w_cross"], d["b_cross"], d["w_proj"], d["b_proj"])
             ys.append(y)
