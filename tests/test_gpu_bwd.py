@@ -158,3 +158,35 @@ def test_out_of_range_ids_are_skipped():
         rows = ref["key_row"][m]
         want = wl.decode(oracle.round_to(ref["new_rows"][m][:, :w.dims[f]], "f16"), "f16")
         assert_close(to_f64(dw.tables[f][torch.from_numpy(rows).cuda()]), want, 2e-2, "rows")
+
+
+def _degenerate(ids_of):
+    w = wl.scaled(wl.mid(True), max_rows=5000, batch=64, num_tables=2)
+    w.table_to_tower = [0, 0]
+    w.tm_out = [256]
+    dw = DeviceWorkload(w, with_state=True)
+    lens = np.full(2 * 64, 30, dtype=np.int64)
+    off = np.concatenate([[0], np.cumsum(lens)])
+    idx = ids_of(int(off[-1])).astype(np.int32)
+    grad = wl.grad_pooled(w)
+    dbg = run_bwd(dw, idx, off, grad, w.lr, w.eps)
+    st0 = [np.zeros(r, np.float32) for r in w.rows]
+    ref = oracle.bwd_update(dw.host_tables, w.table_dtype, st0, w.dims, w.table_to_tower, idx, off,
+                            w.batch, grad, w.lr, w.eps)
+    assert int(dbg["num_unique"].item()) == len(ref["key_row"])
+    for f in range(2):
+        m = ref["key_table"] == f
+        rows = torch.from_numpy(ref["key_row"][m]).cuda()
+        want = wl.decode(oracle.round_to(ref["new_rows"][m][:, :128], "f16"), "f16")
+        assert_close(to_f64(dw.tables[f][rows]), want, 2e-2, "rows")
+        assert_close(to_f64(dw.states[f][rows]), ref["new_state"][m], 1e-5, "state")
+
+
+def test_every_lookup_hits_the_same_row():
+    # one run per table as long as the table's whole record range: 15 reduce tiles chained
+    _degenerate(lambda n: np.full(n, 17))
+
+
+def test_every_lookup_hits_a_different_row():
+    # no duplicates at all: every run has length one
+    _degenerate(lambda n: np.arange(n) % 1920 + (np.arange(n) // 1920) * 0)

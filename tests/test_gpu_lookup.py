@@ -77,3 +77,29 @@ def test_out_of_range_id_is_reported_not_dereferenced():
                                 idx[keep], new_off, w.batch)
     for g, r in zip(dw.split_towers(got), ref):
         assert_close(g, r, 1e-5, "skip-bad")
+
+
+@pytest.mark.parametrize("dtype,dim", [("f16", 512), ("f32", 256), ("f16", 8), ("bf16", 24), ("f32", 4)])
+def test_row_width_limits(dtype, dim):
+    """Rows from one 16-byte chunk (a single lane) to the 1024-byte maximum (a whole wave),
+    and a width that is not a power of two."""
+    w = wl.scaled(wl.mid(), max_rows=400, batch=37, num_tables=4)
+    w.dims = [dim] * 4
+    w.table_dtype = dtype
+    _check(w, "f32")
+    _check(w, dtype)
+
+
+def test_one_very_long_bag_among_empty_ones():
+    w = wl.scaled(wl.mid(), max_rows=1000, batch=5, num_tables=2)
+    dw = DeviceWorkload(w, max_nnz=5000)
+    rng = np.random.default_rng(3)
+    lens = np.zeros(10, dtype=np.int64)
+    lens[3] = 3001                                   # table 0, sample 3
+    lens[9] = 1                                      # table 1, sample 4
+    off = np.concatenate([[0], np.cumsum(lens)])
+    idx = rng.integers(0, 1000, size=off[-1]).astype(np.int32)
+    got = to_f64(dw.lookup(idx, off, "f32"))
+    ref = oracle.lookup_towered(dw.host_tables, w.table_dtype, w.dims, w.table_to_tower, idx, off, w.batch)
+    for g, r in zip(dw.split_towers(got), ref):
+        assert_close(g, r, 1e-5, "long bag")

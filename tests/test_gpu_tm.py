@@ -74,3 +74,20 @@ def test_dot_linear_f32_and_f16():
         w.tm_dtype = dt
         w.pooled_dtype = dt
         check_tm(w)
+
+
+@pytest.mark.parametrize("out_dim,batch", [(100, 77), (300, 333), (257, 512)])
+def test_linear_odd_output_widths_and_ragged_batches(out_dim, batch):
+    """Output widths that are no multiple of 8 or of a tile (scalar epilogue, partial
+    column tiles) on both GEMM kernels (<= 128 columns: 128 x 128; wider: 256 x 256)."""
+    w = wl.scaled(wl.imbalanced(), max_rows=500, batch=batch, num_tables=9)
+    w.tm_out = [out_dim] * w.num_towers
+    check_tm(w)
+
+
+def test_cross_with_three_layers_and_narrow_tower():
+    w = wl.scaled(wl.large(), max_rows=300, batch=150, num_tables=3)
+    w.table_to_tower = [0, 0, 0]
+    w.tm_out = [96]
+    w.tm_cross_layers = 3
+    check_tm(w)                                       # 384-wide cross layers, 96-wide projection
