@@ -44,6 +44,7 @@ struct TmGroup {
   const void* X0;   // EPI_CROSS: [M][ldx] (x0); the x_l term is A1
   void* C;          // [M][ldc]
   int32_t lda0, K0, lda1, K1, ldw, ldc, ldx, M, N, epi;
+  int32_t nf, fdim;       // dot terms computed in-kernel: number of features and their dim
 };
 
 struct TmLaunch {
@@ -191,7 +192,10 @@ constexpr int kSuper = 32;                                  // tiles an XCD keep
 constexpr int kBigTileElems = LBM * kLdsStride;            // one operand, one stage
 constexpr int kBigLdsBytes = 4 * kBigTileElems * 2;         // 2 stages x (A + B)
 
-template <int DT>
+// DOTS: the operand's first K0 columns are the tower's pairwise dot terms, which the block
+// computes itself (Gram tiles, as in tm_dots_mfma) straight into the first LDS stage, so the
+// pooled tensor is read once and the dot terms never exist in global memory.
+template <int DT, bool DOTS>
 __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunch L) {
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
   // XCD-aware rasterisation.  Consecutive block ids go to different XCDs, so block b belongs
@@ -212,7 +216,8 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
   const int tm = (gs - L.tile_start[gi]) * sm + within / tiles_n, tn = within % tiles_n;
   if (tm >= tiles_m) return;
   const int m0 = tm * LBM, n0 = tn * LBN;
-  const int M = G.M, N = G.N, K = G.K1;           // plain GEMM only: no dot-term segment
+  const int kshift = DOTS ? G.K0 : 0;              // operand columns in front of A's own
+  const int M = G.M, N = G.N, K1 = G.K1, K = G.K1 + kshift;
   const uint16_t* __restrict__ A = (const uint16_t*)G.A1;
   const uint16_t* __restrict__ W = (const uint16_t*)G.W;
   const int lda = G.lda1, ldw = G.ldw;
@@ -246,23 +251,26 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
   // Loads are never predicated (edge rows are clamped to a valid row, a K tail to column 0),
   // so they stay in flight across the multiply; edge tiles zero what they must not use when
   // the registers are written to LDS.
-  const bool interior = m0 + LBM <= M && n0 + LBN <= N && K % BK == 0;
-  auto load_tile = [&](int kt) {
-    const int k = (kt * BK + scol < K) ? kt * BK : -scol;
+  const bool interior = !DOTS && m0 + LBM <= M && n0 + LBN <= N && K % BK == 0;
+  auto load_tile = [&](int kt) __attribute__((always_inline)) {
+    const int kw = (kt * BK + scol < K) ? kt * BK : -scol;          // W column block
+    int ka = kt * BK - kshift;                                       // A column block
+    if (ka + scol < 0 || ka + scol >= K1) ka = -scol;
 #pragma clang loop unroll(full)
     for (int i = 0; i < 4; ++i) {
-      ra[i] = *(const uint4*)(A + offa[i] + k);
-      rb[i] = *(const uint4*)(W + offb[i] + k);
+      ra[i] = *(const uint4*)(A + offa[i] + ka);
+      rb[i] = *(const uint4*)(W + offb[i] + kw);
     }
   };
-  auto store_tile = [&](int stage, int kt) {
+  auto store_tile = [&](int stage, int kt) __attribute__((always_inline)) {
     uint16_t* As = lds + stage * 2 * kBigTileElems;
     uint16_t* Bs = As + kBigTileElems;
+    const int ca = kt * BK + scol - kshift;                          // this thread's A column
     if (!interior) {
-      const bool kin = kt * BK + scol < K;
+      const bool kin = kt * BK + scol < K, ain = ca >= 0 && ca < K1;
 #pragma clang loop unroll(full)
       for (int i = 0; i < 4; ++i) {
-        if (!(kin && ((oka >> i) & 1))) ra[i] = make_uint4(0, 0, 0, 0);
+        if (!(ain && ((oka >> i) & 1))) ra[i] = make_uint4(0, 0, 0, 0);
         if (!(kin && ((okb >> i) & 1))) rb[i] = make_uint4(0, 0, 0, 0);
       }
     }
@@ -277,6 +285,42 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
   load_tile(0);
   store_tile(0, 0);
   if (nk > 1) load_tile(1);
+  if constexpr (DOTS) {
+    // pairwise dots of this block's 256 samples, written over the zeros the first tile store
+    // left in the operand's leading columns: 32 consecutive (sample, feature) rows are one
+    // 32 x 32 Gram tile; eight waves share the 256 * nf / 32 row groups
+    __syncthreads();
+    const int nf = G.nf, fd = G.fdim;
+    const int64_t nrows = (int64_t)M * nf;
+    const int ngroups = LBM * nf / 32;
+    for (int rg = wave; rg < ngroups; rg += kBigThreads / 64) {
+      const int64_t r = (int64_t)m0 * nf + rg * 32 + (lane & 31);
+      const uint16_t* xp = A + r * fd + (lane >> 5) * 8;
+      floatx16 d;
+#pragma clang loop unroll(full)
+      for (int v = 0; v < 16; ++v) d[v] = 0.f;
+      const uint16_t* xq = r < nrows ? xp : A + (lane >> 5) * 8;   // rows past the edge: row 0, zeroed
+      for (int k = 0; k < fd; k += 64) {
+        uint4 a[4];
+#pragma clang loop unroll(full)
+        for (int u = 0; u < 4; ++u) a[u] = *(const uint4*)(xq + (k + u * 16 < fd ? k + u * 16 : 0));
+#pragma clang loop unroll(full)
+        for (int u = 0; u < 4; ++u) {
+          if (!(r < nrows && k + u * 16 < fd)) a[u] = make_uint4(0, 0, 0, 0);
+          d = mfma32<DT>(a[u], a[u], d);
+        }
+      }
+      const int c = lane & 31, sc = c / nf, j = c % nf;
+      const int s_local = rg * 32 / nf + sc;
+#pragma clang loop unroll(full)
+      for (int v = 0; v < 16; ++v) {
+        const int rr = (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+        const int i = rr % nf;
+        if (rr / nf == sc && i < j)
+          store_elt<DT>(lds, s_local * kLdsStride + (i * (2 * nf - i - 1) / 2 + (j - i - 1)), d[v]);
+      }
+    }
+  }
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
@@ -541,8 +585,15 @@ dmt_status plan_tm(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, int eb
   return DMT_OK;
 }
 
+// Whether a group can go to the 256 x 256 kernel (dots: with in-kernel dot terms).
+inline bool big_ok(const TmGroup& g, bool dots) {
+  return g.N > 128 && g.N <= kSuper * LBN && g.K1 >= 128 && (dots || g.K0 == 0) &&
+         (int64_t)g.M * g.lda1 < (1LL << 31) && (int64_t)g.N * g.ldw < (1LL << 31);
+}
+
 template <int DT>
-void launch_groups(const dmt_plan* p, std::vector<TmGroup>& groups, hipStream_t s) {
+void launch_groups(const dmt_plan* p, std::vector<TmGroup>& groups, hipStream_t s,
+                   bool dots = false) {
   for (size_t first = 0; first < groups.size(); first += kMaxGroups) {
     TmLaunch L;
     L.ngroups = (int32_t)std::min<size_t>(kMaxGroups, groups.size() - first);
@@ -563,14 +614,14 @@ void launch_groups(const dmt_plan* p, std::vector<TmGroup>& groups, hipStream_t 
       hipLaunchKernelGGL((tm_gemm_simple<DT>), dim3(tiles), dim3(kBlock), 0, s, L);
     } else {
       // wide outputs take the 256 x 256 kernel
-      bool big = dmt::env_int("DMT_TM_BIG", 1) != 0;
-      for (int i = 0; i < L.ngroups; ++i)
-        big = big && L.g[i].N > 128 && L.g[i].N <= kSuper * LBN && L.g[i].K0 == 0 && L.g[i].K1 >= 128 &&
-              (int64_t)L.g[i].M * L.g[i].lda1 < (1LL << 31) && (int64_t)L.g[i].N * L.g[i].ldw < (1LL << 31);
+      bool big = dots || dmt::env_int("DMT_TM_BIG", 1) != 0;
+      for (int i = 0; i < L.ngroups; ++i) big = big && big_ok(L.g[i], dots);
       if (big) {
         static bool configured = false;
         if (!configured) {
-          (void)hipFuncSetAttribute((const void*)tm_gemm_mfma_256<DT>,
+          (void)hipFuncSetAttribute((const void*)tm_gemm_mfma_256<DT, false>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
+          (void)hipFuncSetAttribute((const void*)tm_gemm_mfma_256<DT, true>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
           configured = true;
         }
@@ -584,7 +635,12 @@ void launch_groups(const dmt_plan* p, std::vector<TmGroup>& groups, hipStream_t 
         L.tile_start[L.ngroups] = nst;
         const int32_t big_tiles = (nst + 7) / 8 * 8 * kSuper;
         DmtScope sc_(p, DMT_K_TM_GEMM, s);
-        hipLaunchKernelGGL((tm_gemm_mfma_256<DT>), dim3(big_tiles), dim3(kBigThreads), kBigLdsBytes, s, L);
+        if (dots)
+          hipLaunchKernelGGL((tm_gemm_mfma_256<DT, true>), dim3(big_tiles), dim3(kBigThreads),
+                             kBigLdsBytes, s, L);
+        else
+          hipLaunchKernelGGL((tm_gemm_mfma_256<DT, false>), dim3(big_tiles), dim3(kBigThreads),
+                             kBigLdsBytes, s, L);
       } else {
         DmtScope sc_(p, DMT_K_TM_GEMM, s);
         hipLaunchKernelGGL((tm_gemm_mfma<DT>), dim3(tiles), dim3(kBlock), 0, s, L);
@@ -604,6 +660,18 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
   for (int32_t t = 0; t < p->T; ++t) out_prefix[t + 1] = out_prefix[t] + tp[t].out_dim;
   int max_layers = 0;
 
+  // A dot-product tower whose shape fits computes its dot terms inside the projection GEMM.
+  std::vector<char> fused(p->T, 0);
+  if (DT != DMT_F32 && dmt::env_int("DMT_TM_FUSE", 1) != 0 && dmt::env_int("DMT_TM_BIG", 1) != 0)
+    for (int32_t t = 0; t < p->T; ++t) {
+      const dmt_tm_params& q = tp[t];
+      if (q.kind != DMT_TM_DOT_LINEAR) continue;
+      const int nf = p->tower_ntab[t], n = p->tower_uniform_dim[t], wt = p->tower_width[t];
+      TmGroup g{};
+      g.M = (int32_t)B; g.N = q.out_dim; g.K1 = wt; g.lda1 = wt; g.ldw = ws[t].np_pad + wt;
+      fused[t] = nf >= 2 && 32 % nf == 0 && n % 16 == 0 && ws[t].np_pad <= BK && big_ok(g, true);
+    }
+
   // stage 0: dot terms and repacked projection weights, one grouped launch per kind
   std::vector<TmAuxItem> dots_mfma, dots_simple, packs;
   std::vector<int64_t> nb_mfma, nb_simple, nb_pack;
@@ -617,7 +685,8 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
     it.O = q.out_dim; it.wt = p->tower_width[t];
     it.src = x_all + (size_t)B * p->width_prefix[t] * eb;
     it.dst = wsp + w.z_off;
-    if (DT != DMT_F32 && 32 % it.nf == 0 && it.n % 16 == 0) {
+    if (fused[t]) {
+    } else if (DT != DMT_F32 && 32 % it.nf == 0 && it.n % 16 == 0) {
       dots_mfma.push_back(it);
       nb_mfma.push_back(((B * it.nf + 31) / 32 + 3) / 4);
     } else {
@@ -682,6 +751,7 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
   }
 
   // projections of every tower
+  std::vector<TmGroup> groups_fused;
   for (int32_t t = 0; t < p->T; ++t) {
     const dmt_tm_params& q = tp[t];
     const int wt = p->tower_width[t];
@@ -701,9 +771,16 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
     g.C = y_all + (size_t)B * out_prefix[t] * eb; g.ldc = q.out_dim;
     g.M = (int32_t)B; g.N = q.out_dim;
     g.epi = q.kind == DMT_TM_LINEAR_RELU ? EPI_BIAS_RELU : EPI_BIAS;
-    groups.push_back(g);
+    if (fused[t]) {
+      g.A0 = nullptr; g.lda0 = 0;
+      g.nf = p->tower_ntab[t]; g.fdim = p->tower_uniform_dim[t];
+      groups_fused.push_back(g);
+    } else {
+      groups.push_back(g);
+    }
   }
   launch_groups<DT>(p, groups, s);
+  if constexpr (DT != DMT_F32) launch_groups<DT>(p, groups_fused, s, true);
   return hipGetLastError() == hipSuccess ? DMT_OK : DMT_EHIP;
 }
 

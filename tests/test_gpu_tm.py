@@ -76,6 +76,20 @@ def test_dot_linear_f32_and_f16():
         check_tm(w)
 
 
+def test_dot_linear_fused_and_separate_towers_in_one_call():
+    """Tower 0 (4 features x 64, 6 dots padded to 8, 300 outputs) takes the GEMM that computes
+    its dot terms in-kernel; tower 1 (8 features, 96 outputs) the separate dot kernel and the
+    128 x 128 GEMM; batch 519 leaves ragged row tiles in both."""
+    w = wl.scaled(wl.mid(), max_rows=400, batch=519, num_tables=12)
+    w.dims = [64] * 4 + [128] * 8
+    w.table_to_tower = [0] * 4 + [1] * 8
+    w.tm_out = [300, 96]
+    for dt in ("bf16", "f16"):
+        w.tm_dtype = dt
+        w.pooled_dtype = dt
+        check_tm(w)
+
+
 @pytest.mark.parametrize("out_dim,batch", [(100, 77), (300, 333), (257, 512)])
 def test_linear_odd_output_widths_and_ragged_batches(out_dim, batch):
     """Output widths that are no multiple of 8 or of a tile (scalar epilogue, partial
