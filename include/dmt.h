@@ -87,8 +87,8 @@ const char* dmt_status_str(dmt_status s);
  *                    needs at least one table.  A table's slot inside its tower
  *                    is its rank among the tower's tables by ascending id.
  *   max_batch, max_nnz  upper bounds later calls are checked against.
- * The sum of all rows must stay below 2^32 (rows are numbered globally inside
- * the backward sort).
+ * The sum of all rows must stay below 2^31 (rows are numbered globally inside
+ * the backward sort, in 31 bits of a 32-bit key).
  */
 dmt_status dmt_plan_create(dmt_plan** out, int32_t num_tables, const int64_t* rows,
                            const int32_t* dims, dmt_dtype table_dtype, int32_t num_towers,
@@ -177,7 +177,9 @@ dmt_status dmt_tower_module_fwd(const dmt_plan* plan, const dmt_tm_params* per_t
                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /* Optional outputs of the backward's integer stages, for parity checks.  Any
- * pointer may be NULL.  All dev. */
+ * pointer may be NULL.  All dev.  A lookup whose id is outside its table sorts
+ * behind its table's valid lookups, shows as key -1 in sorted_keys, starts no run
+ * (it lies inside the extent of the run before it) and is not counted. */
 typedef struct {
   int64_t* sorted_keys;  /* [nnz]  (table << 32 | row), ascending, stable           */
   int32_t* sorted_bag;   /* [nnz]  bag id f*B + b of each sorted lookup              */

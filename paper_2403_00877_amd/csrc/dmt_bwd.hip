@@ -1,18 +1,24 @@
 // dmt_tower_lookup_bwd_update: gradients to the activated rows only (paper
-// Sec. 2.2), as  key build -> stable LSD radix sort by global row id ->
-// run heads / segment offsets -> tiled segment reduce fused with the rowwise
-// Adagrad row update -> fix-up of rows whose run spans several tiles.
+// Sec. 2.2), as  key build -> stable LSD radix sort by row id inside every
+// table's records -> tiled segment reduce fused with the rowwise Adagrad row
+// update -> fix-up of rows whose run spans several tiles.
 //
 // Everything is deterministic: the sort is stable (equal rows keep ascending
 // bag order), every row's gradient is summed in a fixed order, and each row has
 // exactly one writer.  No floating-point atomics anywhere.
 //
 // Data in the workspace: 64-bit records (global_row << 32 | bag), where
-// global_row = (sum of rows of earlier tables) + row and bag = f*B + b.  Ids
-// outside their table get global_row = total_rows (sorts last, never touched).
+// global_row = (sum of rows of earlier tables) + row and bag = f*B + b.  The
+// lookups arrive grouped by table (bags are table-major), so the sort never moves
+// a record out of its table's range: sort blocks are aligned to the tables and
+// every pass ranks only the bits of the row inside the table, which takes
+// ceil(log2(largest table)) bits instead of ceil(log2(all rows)).  An id outside
+// its table gets the key  kInertBit | (global id one past the table's last row):
+// it sorts behind the table's rows, equals no row's key, and is never touched.
 // `offsets` must tile [0, nnz) (ascending, offsets[0] = 0, last = nnz): a record
 // no bag covers is never initialised; the kernels still keep every access in
 // bounds for any record contents, but the values written are then unspecified.
+#include <algorithm>
 #include <type_traits>
 
 #include "dmt_internal.h"
@@ -39,12 +45,16 @@ constexpr int kReduceTile = 128;                 // sorted records per reduce ti
 #define DMT_RU 4
 #endif
 constexpr int kReduceUnroll = DMT_RU;
+constexpr uint32_t kInertBit = 0x80000000u;      // key flag of an id outside its table
+constexpr int kScanThreads = 1024;               // block of the per-table offset scan
 
 struct BwdWs {
   uint64_t* pk_a;
   uint64_t* pk_b;
-  uint32_t* hist;         // [kMaxRadix][nblk_sort]
-  uint32_t* digit_total;  // [kMaxRadix]
+  uint32_t* hist;         // [nblk_sort][kMaxRadix]
+  uint32_t* seg_begin;    // [F + 1] first record of each table (seg_begin[F] = nnz)
+  uint32_t* seg_blk;      // [F + 1] first sort block of each table
+  uint32_t* blk_table;    // [nblk_sort] table of each sort block
   uint32_t* blk_heads;    // [nblk_scan]
   uint32_t* seg_off;      // [nnz + 1]
   uint32_t* tile_first;   // [ntiles + 1] run heads before each reduce tile
@@ -57,7 +67,7 @@ struct BwdWs {
 BwdWs carve(const dmt_plan* p, int64_t nnz, void* base) {
   BwdWs w;
   const int64_t n = nnz > 0 ? nnz : 1;
-  w.nblk_sort = (n + kSortTile - 1) / kSortTile;
+  w.nblk_sort = (n + kSortTile - 1) / kSortTile + p->F;   // every table may end in a partial block
   w.nblk_scan = (n + kScanTile - 1) / kScanTile;
   w.ntiles = (n + kReduceTile - 1) / kReduceTile;
   size_t off = 0;
@@ -69,7 +79,9 @@ BwdWs carve(const dmt_plan* p, int64_t nnz, void* base) {
   w.pk_a = (uint64_t*)take(sizeof(uint64_t) * n);
   w.pk_b = (uint64_t*)take(sizeof(uint64_t) * n);
   w.hist = (uint32_t*)take(sizeof(uint32_t) * kMaxRadix * w.nblk_sort);
-  w.digit_total = (uint32_t*)take(sizeof(uint32_t) * kMaxRadix);
+  w.seg_begin = (uint32_t*)take(sizeof(uint32_t) * (p->F + 1));
+  w.seg_blk = (uint32_t*)take(sizeof(uint32_t) * (p->F + 1));
+  w.blk_table = (uint32_t*)take(sizeof(uint32_t) * w.nblk_sort);
   w.blk_heads = (uint32_t*)take(sizeof(uint32_t) * (w.nblk_scan + 1));
   w.seg_off = (uint32_t*)take(sizeof(uint32_t) * (n + 1));
   w.tile_first = (uint32_t*)take(sizeof(uint32_t) * (w.ntiles + 1));
@@ -81,11 +93,50 @@ BwdWs carve(const dmt_plan* p, int64_t nnz, void* base) {
 
 // ------------------------------------------------------------------ key build
 
+// Where each table's records start and which sort blocks cover them.  Run by one block.
+// The starts come from the offsets of every table's first bag, made ascending and clamped to
+// [0, nnz], so that blocks stay inside the record array whatever `offsets` holds.
+__device__ void build_sort_map(const int64_t* __restrict__ offsets, uint32_t B, int F, int64_t nnz,
+                               uint32_t* __restrict__ seg_begin, uint32_t* __restrict__ seg_blk,
+                               uint32_t* __restrict__ blk_table) {
+  __shared__ uint32_t sm[kBlock / 64];
+  uint32_t rec_run = 0, blk_run = 0;
+  for (int f0 = 0; f0 < F; f0 += kBlock) {
+    const int f = f0 + (int)threadIdx.x;
+    uint32_t len = 0;
+    if (f < F) {
+      int64_t a = offsets[(int64_t)f * B], b = offsets[(int64_t)(f + 1) * B];
+      a = a < 0 ? 0 : (a > nnz ? nnz : a);
+      b = b < 0 ? 0 : (b > nnz ? nnz : b);
+      len = b > a ? (uint32_t)(b - a) : 0u;
+    }
+    uint32_t total;
+    uint32_t begin = rec_run + dmt::block_exclusive_scan<kBlock / 64>(len, sm, total);
+    rec_run += total;
+    begin = begin > (uint32_t)nnz ? (uint32_t)nnz : begin;
+    const uint32_t end = begin + len > (uint32_t)nnz ? (uint32_t)nnz : begin + len;
+    const uint32_t nb = (end - begin + kSortTile - 1) / kSortTile;
+    const uint32_t first = blk_run + dmt::block_exclusive_scan<kBlock / 64>(nb, sm, total);
+    blk_run += total;
+    if (f < F) {
+      seg_begin[f] = begin;
+      seg_blk[f] = first;
+      for (uint32_t j = 0; j < nb; ++j) blk_table[first + j] = (uint32_t)f;
+    }
+  }
+  if (threadIdx.x == 0) {
+    seg_begin[F] = rec_run > (uint32_t)nnz ? (uint32_t)nnz : rec_run;
+    seg_blk[F] = blk_run;
+  }
+}
+
 __global__ __launch_bounds__(kBlock) void bwd_build_keys(
     const DmtTableMeta* __restrict__ meta, const int32_t* __restrict__ indices,
-    const int64_t* __restrict__ offsets, uint32_t B, uint32_t nbags, int64_t nnz,
-    uint32_t total_rows, uint64_t* __restrict__ pk, int log2_gl,
+    const int64_t* __restrict__ offsets, uint32_t B, uint32_t nbags, int64_t nnz, int F,
+    uint64_t* __restrict__ pk, int log2_gl, uint32_t* __restrict__ seg_begin,
+    uint32_t* __restrict__ seg_blk, uint32_t* __restrict__ blk_table,
     unsigned long long* __restrict__ err) {
+  if (blockIdx.x == 0) build_sort_map(offsets, B, F, nnz, seg_begin, seg_blk, blk_table);
   const int GL = 1 << log2_gl;
   const uint32_t g = blockIdx.x * (kBlock >> log2_gl) + (threadIdx.x >> log2_gl);
   if (g >= nbags) return;
@@ -101,7 +152,7 @@ __global__ __launch_bounds__(kBlock) void bwd_build_keys(
     uint32_t gid = row_base + (uint32_t)idx;
     if ((uint64_t)(uint32_t)idx >= rows) {
       atomicMin(err, (unsigned long long)j);
-      gid = total_rows;
+      gid = kInertBit | (row_base + (uint32_t)rows);
     }
     pk[j] = ((uint64_t)gid << 32) | g;
   }
@@ -109,44 +160,96 @@ __global__ __launch_bounds__(kBlock) void bwd_build_keys(
 
 // ------------------------------------------------------------------ radix sort
 
-__global__ __launch_bounds__(kBlock) void radix_hist(const uint64_t* __restrict__ pk, int64_t nnz,
-                                                     int shift, int bits,
-                                                     uint32_t* __restrict__ hist, int64_t nblk) {
+// A sort block's share of its table's records, and the table's first global row id.
+struct SortBlock {
+  uint32_t base, n, row_base, valid;
+};
+__device__ __forceinline__ SortBlock sort_block(const DmtTableMeta* __restrict__ meta,
+                                                const uint32_t* __restrict__ seg_begin,
+                                                const uint32_t* __restrict__ seg_blk,
+                                                const uint32_t* __restrict__ blk_table, int F) {
+  SortBlock sb{0, 0, 0, 0};
+  if (blockIdx.x >= seg_blk[F]) return sb;
+  const uint32_t f = blk_table[blockIdx.x];
+  sb.base = seg_begin[f] + (blockIdx.x - seg_blk[f]) * (uint32_t)kSortTile;
+  const uint32_t end = seg_begin[f + 1];
+  sb.n = end - sb.base < (uint32_t)kSortTile ? end - sb.base : (uint32_t)kSortTile;
+  sb.row_base = (uint32_t)meta[f].row_base;
+  sb.valid = 1;
+  return sb;
+}
+
+// The pass's digit of a record: bits [shift, shift + bits) of the row id inside the table.
+__device__ __forceinline__ uint32_t sort_digit(uint64_t rec, uint32_t row_base, int shift,
+                                               uint32_t mask) {
+  return ((((uint32_t)(rec >> 32) & ~kInertBit) - row_base) >> shift) & mask;
+}
+
+__global__ __launch_bounds__(kBlock) void radix_hist(
+    const DmtTableMeta* __restrict__ meta, const uint64_t* __restrict__ pk, int shift, int bits,
+    uint32_t* __restrict__ hist, const uint32_t* __restrict__ seg_begin,
+    const uint32_t* __restrict__ seg_blk, const uint32_t* __restrict__ blk_table, int F) {
   __shared__ uint32_t h[kMaxRadix];
+  const SortBlock sb = sort_block(meta, seg_begin, seg_blk, blk_table, F);
+  if (!sb.valid) return;
   for (int d = threadIdx.x; d < kMaxRadix; d += kBlock) h[d] = 0;
   __syncthreads();
   const uint32_t mask = (1u << bits) - 1;
-  const int64_t base = (int64_t)blockIdx.x * kSortTile;
 #pragma unroll
   for (int i = 0; i < kSortItems; ++i) {
-    const int64_t pos = base + i * kBlock + threadIdx.x;
-    if (pos < nnz) atomicAdd(&h[(uint32_t)(pk[pos] >> (32 + shift)) & mask], 1u);
+    const uint32_t q = i * kBlock + threadIdx.x;
+    if (q < sb.n) atomicAdd(&h[sort_digit(pk[sb.base + q], sb.row_base, shift, mask)], 1u);
   }
   __syncthreads();
   for (int d = threadIdx.x; d < (1 << bits); d += kBlock)
-    hist[(int64_t)d * nblk + blockIdx.x] = h[d];
+    hist[(int64_t)blockIdx.x * kMaxRadix + d] = h[d];
 }
 
-// One block per digit: exclusive scan of that digit's per-block counts, in place.
-__global__ __launch_bounds__(kBlock) void radix_scan(uint32_t* __restrict__ hist, int64_t nblk,
-                                                     uint32_t* __restrict__ digit_total) {
-  __shared__ uint32_t sm[8];
-  uint32_t* row = hist + (int64_t)blockIdx.x * nblk;
-  uint32_t running = 0;
-  for (int64_t base = 0; base < nblk; base += kBlock) {
-    const int64_t i = base + threadIdx.x;
-    const uint32_t v = i < nblk ? row[i] : 0;
-    uint32_t total;
-    const uint32_t ex = dmt::block_exclusive_scan<kBlock / 64>(v, sm, total);
-    if (i < nblk) row[i] = running + ex;
-    running += total;
+// One block per table: turns the per-block digit counts of the table's sort blocks into the
+// position of each block's first record of each digit in the sorted output (digit-major,
+// block-minor inside the table's record range).  Thread (slice, digit) walks one slice of the
+// table's blocks.
+__global__ __launch_bounds__(kScanThreads) void radix_scan(uint32_t* __restrict__ hist, int bits,
+                                                           const uint32_t* __restrict__ seg_begin,
+                                                           const uint32_t* __restrict__ seg_blk) {
+  __shared__ uint32_t tot[kScanThreads];
+  __shared__ uint32_t dbase[kMaxRadix];
+  __shared__ uint32_t sm[kScanThreads / 64];
+  const int f = blockIdx.x;
+  const uint32_t b0 = seg_blk[f], nb = seg_blk[f + 1] - b0;
+  if (nb == 0) return;
+  const int R = 1 << bits, slices = kScanThreads >> bits;
+  const int sl = threadIdx.x >> bits, d = threadIdx.x & (R - 1);
+  const uint32_t per = (nb + slices - 1) / slices;
+  const uint32_t lo = min(nb, sl * per), hi = min(nb, lo + per);
+  uint32_t run = 0;
+  for (uint32_t b = lo; b < hi; ++b) {
+    uint32_t* p = hist + (int64_t)(b0 + b) * kMaxRadix + d;
+    const uint32_t v = *p;
+    *p = run;
+    run += v;
   }
-  if (threadIdx.x == 0) digit_total[blockIdx.x] = running;
+  tot[threadIdx.x] = run;
+  __syncthreads();
+  uint32_t before = 0, all = 0;                    // this digit: earlier slices, every slice
+  for (int q = 0; q < slices; ++q) {
+    const uint32_t t = tot[q * R + d];
+    if (q < sl) before += t;
+    all += t;
+  }
+  uint32_t total;
+  const uint32_t ex = dmt::block_exclusive_scan<kScanThreads / 64>(sl == 0 ? all : 0u, sm, total);
+  if (sl == 0) dbase[d] = ex;
+  __syncthreads();
+  const uint32_t add = seg_begin[f] + dbase[d] + before;
+  for (uint32_t b = lo; b < hi; ++b) hist[(int64_t)(b0 + b) * kMaxRadix + d] += add;
 }
 
 __global__ __launch_bounds__(kBlock) void radix_scatter(
-    const uint64_t* __restrict__ in, uint64_t* __restrict__ out, int64_t nnz, int shift, int bits,
-    const uint32_t* __restrict__ hist, const uint32_t* __restrict__ digit_total, int64_t nblk) {
+    const DmtTableMeta* __restrict__ meta, const uint64_t* __restrict__ in,
+    uint64_t* __restrict__ out, int shift, int bits, const uint32_t* __restrict__ hist,
+    const uint32_t* __restrict__ seg_begin, const uint32_t* __restrict__ seg_blk,
+    const uint32_t* __restrict__ blk_table, int F) {
   __shared__ uint64_t buf[kSortTile];
   __shared__ uint32_t cnt[kBlock / 64][kMaxRadix];
   __shared__ uint32_t tile_start[kMaxRadix];
@@ -155,11 +258,13 @@ __global__ __launch_bounds__(kBlock) void radix_scatter(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int radix = 1 << bits;
   const uint32_t mask = (uint32_t)radix - 1;
+  const SortBlock sb = sort_block(meta, seg_begin, seg_blk, blk_table, F);
+  if (!sb.valid) return;
   for (int w = 0; w < kBlock / 64; ++w)
     for (int d = tid; d < kMaxRadix; d += kBlock) cnt[w][d] = 0;
   __syncthreads();
-  const int64_t tile_base = (int64_t)blockIdx.x * kSortTile;
-  const int n_tile = (int)min((int64_t)kSortTile, nnz - tile_base);
+  const uint32_t tile_base = sb.base;
+  const int n_tile = (int)sb.n;
   volatile uint32_t* my_cnt = cnt[wave];
 
   // stable rank of every record among the records of its wave with the same digit
@@ -170,7 +275,7 @@ __global__ __launch_bounds__(kBlock) void radix_scatter(
     const int q = wave * (kSortItems * 64) + i * 64 + lane;
     const bool valid = q < n_tile;
     rec[i] = valid ? in[tile_base + q] : ~0ULL;
-    const uint32_t d = (uint32_t)(rec[i] >> (32 + shift)) & mask;
+    const uint32_t d = sort_digit(rec[i], sb.row_base, shift, mask);
     uint64_t peers = __ballot(valid);              // lanes of this wave holding the same digit
     for (int b = 0; b < bits; ++b) {
       const bool bit = (d >> b) & 1;
@@ -193,13 +298,12 @@ __global__ __launch_bounds__(kBlock) void radix_scatter(
   __syncthreads();
   // thread t owns digits t*DPT .. t*DPT+DPT-1: totals over the waves; cnt becomes each
   // wave's offset inside the digit
-  uint32_t tot[kDigitsPerThread], dt[kDigitsPerThread];
-  uint32_t tsum = 0, dsum = 0;
+  uint32_t tot[kDigitsPerThread];
+  uint32_t tsum = 0;
 #pragma unroll
   for (int j = 0; j < kDigitsPerThread; ++j) {
     const int d = tid * kDigitsPerThread + j;
     tot[j] = 0;
-    dt[j] = 0;
     if (d < radix) {
       uint32_t run = 0;
       for (int w = 0; w < kBlock / 64; ++w) {
@@ -208,38 +312,34 @@ __global__ __launch_bounds__(kBlock) void radix_scatter(
         run += c;
       }
       tot[j] = run;
-      dt[j] = digit_total[d];
     }
     tsum += tot[j];
-    dsum += dt[j];
   }
   uint32_t total;
   uint32_t ex = dmt::block_exclusive_scan<kBlock / 64>(tsum, sm, total);
-  uint32_t dex = dmt::block_exclusive_scan<kBlock / 64>(dsum, sm, total);
 #pragma unroll
   for (int j = 0; j < kDigitsPerThread; ++j) {
     const int d = tid * kDigitsPerThread + j;
     if (d < radix) {
       tile_start[d] = ex;
-      gbase[d] = dex + hist[(int64_t)d * nblk + blockIdx.x] - ex;
+      // hist holds where this block's first record of digit d goes
+      gbase[d] = hist[(int64_t)blockIdx.x * kMaxRadix + d] - ex;
     }
     ex += tot[j];
-    dex += dt[j];
   }
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < kSortItems; ++i) {
     const int q = wave * (kSortItems * 64) + i * 64 + lane;
     if (q < n_tile) {
-      const uint32_t d = (uint32_t)(rec[i] >> (32 + shift)) & mask;
+      const uint32_t d = sort_digit(rec[i], sb.row_base, shift, mask);
       buf[tile_start[d] + cnt[wave][d] + rank[i]] = rec[i];
     }
   }
   __syncthreads();
   for (int q = tid; q < n_tile; q += kBlock) {
     const uint64_t r = buf[q];
-    const uint32_t d = (uint32_t)(r >> (32 + shift)) & mask;
-    out[gbase[d] + (uint32_t)q] = r;
+    out[gbase[sort_digit(r, sb.row_base, shift, mask)] + (uint32_t)q] = r;
   }
 }
 
@@ -261,7 +361,7 @@ __device__ __forceinline__ uint32_t wave_head_ballots(const uint64_t* __restrict
     const uint32_t k = p < nnz ? (uint32_t)(pk[p] >> 32) : 0;
     uint32_t prev = __shfl_up(k, 1);
     if (lane == 0) prev = carry;
-    const bool head = p < nnz && (p == 0 || k != prev);
+    const bool head = p < nnz && (p == 0 || k != prev) && !(k & kInertBit);
     ballots[i] = __ballot(head);
     count += (uint32_t)__popcll(ballots[i]);
     carry = __shfl(k, 63);
@@ -953,9 +1053,7 @@ __global__ __launch_bounds__(kBlock) void bwd_export(
     int32_t* __restrict__ sorted_bag, int64_t* __restrict__ unique_keys,
     int64_t* __restrict__ seg_off_out, int64_t* __restrict__ num_unique) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  uint32_t U = nnz > 0 ? num_unique_in[0] : 0;
-  // the inert key (ids outside their table) sorts last and is not a row
-  if (nnz > 0 && U > 0 && (uint32_t)(pk[nnz - 1] >> 32) >= total_rows) --U;
+  const uint32_t U = nnz > 0 ? num_unique_in[0] : 0;   // inert keys were not counted as heads
   if (i == 0 && num_unique) num_unique[0] = U;
   if (i < nnz) {
     const uint32_t gid = (uint32_t)(pk[i] >> 32);
@@ -1020,10 +1118,13 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
     log2_gl = log2_gl < 2 ? 2 : (log2_gl > 6 ? 6 : log2_gl);
     const unsigned kb_blocks = (nbags + (kBlock >> log2_gl) - 1) / (kBlock >> log2_gl);
     { DmtScope sc_(plan, DMT_K_BWD_KEYS, s); hipLaunchKernelGGL(bwd_build_keys, dim3(kb_blocks), dim3(kBlock), 0, s, plan->d_meta, indices,
-                       offsets, (uint32_t)B, nbags, nnz, total_rows, w.pk_a, log2_gl,
-                       plan->d_error); }
-    // stable LSD radix sort over the bits that can be set (values 0..total_rows)
-    const int key_bits = ilog2_ceil((int64_t)total_rows + 1);
+                       offsets, (uint32_t)B, nbags, nnz, (int)plan->F, w.pk_a, log2_gl,
+                       w.seg_begin, w.seg_blk, w.blk_table, plan->d_error); }
+    // stable LSD radix sort inside every table over the bits a row id of the largest table
+    // (or its one-past-the-end inert id) can set
+    int64_t max_rows = 0;
+    for (int32_t f = 0; f < plan->F; ++f) max_rows = std::max<int64_t>(max_rows, plan->meta[f].rows);
+    const int key_bits = ilog2_ceil(max_rows + 1);
     const int passes = (key_bits + kMaxRadixBits - 1) / kMaxRadixBits;
     const int bits_per = (key_bits + passes - 1) / passes;
     uint64_t* src = w.pk_a;
@@ -1031,12 +1132,12 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
     for (int p = 0; p < passes; ++p) {
       const int shift = p * bits_per;
       const int bits = (key_bits - shift) < bits_per ? (key_bits - shift) : bits_per;
-      { DmtScope sc_(plan, DMT_K_BWD_SORT_HIST, s); hipLaunchKernelGGL(radix_hist, dim3((unsigned)w.nblk_sort), dim3(kBlock), 0, s, src, nnz,
-                         shift, bits, w.hist, w.nblk_sort); }
-      { DmtScope sc_(plan, DMT_K_BWD_SORT_SCAN, s); hipLaunchKernelGGL(radix_scan, dim3(1u << bits), dim3(kBlock), 0, s, w.hist, w.nblk_sort,
-                         w.digit_total); }
-      { DmtScope sc_(plan, DMT_K_BWD_SORT_SCATTER, s); hipLaunchKernelGGL(radix_scatter, dim3((unsigned)w.nblk_sort), dim3(kBlock), 0, s, src, dst,
-                         nnz, shift, bits, w.hist, w.digit_total, w.nblk_sort); }
+      { DmtScope sc_(plan, DMT_K_BWD_SORT_HIST, s); hipLaunchKernelGGL(radix_hist, dim3((unsigned)w.nblk_sort), dim3(kBlock), 0, s, plan->d_meta, src,
+                         shift, bits, w.hist, w.seg_begin, w.seg_blk, w.blk_table, (int)plan->F); }
+      { DmtScope sc_(plan, DMT_K_BWD_SORT_SCAN, s); hipLaunchKernelGGL(radix_scan, dim3((unsigned)plan->F), dim3(kScanThreads), 0, s, w.hist, bits,
+                         w.seg_begin, w.seg_blk); }
+      { DmtScope sc_(plan, DMT_K_BWD_SORT_SCATTER, s); hipLaunchKernelGGL(radix_scatter, dim3((unsigned)w.nblk_sort), dim3(kBlock), 0, s, plan->d_meta, src, dst,
+                         shift, bits, w.hist, w.seg_begin, w.seg_blk, w.blk_table, (int)plan->F); }
       uint64_t* tmp = src; src = dst; dst = tmp;
     }
     sorted = src;

@@ -41,7 +41,8 @@ extern "C" dmt_status dmt_plan_create(dmt_plan** out, int32_t num_tables, const 
     if (rb % 16 != 0 || rb > 1024) return DMT_ENOTSUP;
     total_rows += rows[f];
   }
-  if (total_rows >= (1LL << 32)) return DMT_ENOTSUP;
+  // the backward carries a global row id in 31 bits of its sort key (the top bit is a flag)
+  if (total_rows >= (1LL << 31)) return DMT_ENOTSUP;
 
   dmt_plan* p = new (std::nothrow) dmt_plan();
   if (!p) return DMT_ENOMEM;
