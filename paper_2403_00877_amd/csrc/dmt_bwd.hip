@@ -265,7 +265,8 @@ __global__ __launch_bounds__(kBlock) void radix_scatter(
   __syncthreads();
   const uint32_t tile_base = sb.base;
   const int n_tile = (int)sb.n;
-  volatile uint32_t* my_cnt = cnt[wave];
+  volatile __attribute__((address_space(3))) uint32_t* my_cnt =
+      (volatile __attribute__((address_space(3))) uint32_t*)cnt[wave];
 
   // stable rank of every record among the records of its wave with the same digit
   uint64_t rec[kSortItems];
@@ -442,26 +443,26 @@ __device__ __forceinline__ void apply_row_update(const DmtTableMeta* __restrict_
   float ss = g.x * g.x + g.y * g.y + g.z * g.z + g.w * g.w;
   for (int o = 1; o < GL; o <<= 1) ss += __shfl_xor(ss, o);
   float* state = meta[f].state;
-  const float st = state[row] + ss / (float)D;
+  const float st = dmt::gload(state + row) + ss / (float)D;
   const float step = lr / (sqrtf(st) + eps);
   if (gl * 4 < D) {
     if constexpr (TD == DMT_F32) {
       float4* w = (float4*)((float*)meta[f].table + (int64_t)row * D) + gl;
-      float4 v = NT ? dmt::nt_load(w) : *w;
+      float4 v = NT ? dmt::nt_load(w) : dmt::gload(w);
       v.x -= step * g.x; v.y -= step * g.y; v.z -= step * g.z; v.w -= step * g.w;
-      if (NT) dmt::nt_store(v, w); else *w = v;
+      if (NT) dmt::nt_store(v, w); else dmt::gstore(v, w);
     } else {
       uint2* w = (uint2*)((uint16_t*)meta[f].table + (int64_t)row * D) + gl;
-      const uint2 u = NT ? dmt::nt_load(w) : *w;
+      const uint2 u = NT ? dmt::nt_load(w) : dmt::gload(w);
       float a, b, c, d;
       dmt::unpack2<TD>(u.x, a, b);
       dmt::unpack2<TD>(u.y, c, d);
       a -= step * g.x; b -= step * g.y; c -= step * g.z; d -= step * g.w;
       const uint2 nu = make_uint2(dmt::pack2<TD>(a, b), dmt::pack2<TD>(c, d));
-      if (NT) dmt::nt_store(nu, w); else *w = nu;
+      if (NT) dmt::nt_store(nu, w); else dmt::gstore(nu, w);
     }
   }
-  if (gl == 0) state[row] = st;
+  if (gl == 0) dmt::gstore(st, state + row);
 }
 
 __device__ __forceinline__ void store_partial(float* __restrict__ partials, int64_t slot,
@@ -486,6 +487,15 @@ __device__ __forceinline__ float group_sum(float v) {
     v += __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), 0x401F));  // lane ^ 16
   if constexpr (LG >= 6) v += __shfl_xor(v, 32);
   return v;
+}
+
+// Orders one lane's LDS writes before other lanes' reads of them inside a wave.  The lanes of
+// a wave run in lockstep, but to the compiler they are unrelated threads: without this it may
+// move a lane's read in front of another lane's write.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // A lane's four columns of a table row.
@@ -577,8 +587,8 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update(
           D[u] = UD ? Dmax : q_D[group][j0 + u];
           wp[u] = (Chunk*)(q_rowp[group][j0 + u]) + gl;
           sp[u] = (float*)(q_stp[group][j0 + u]);
-          st[u] = *sp[u];
-          if (gl * 4 < D[u]) w[u] = *wp[u];
+          st[u] = dmt::gload(sp[u]);
+          if (gl * 4 < D[u]) w[u] = dmt::gload(wp[u]);
         }
       }
 #pragma unroll
@@ -592,16 +602,16 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update(
             if constexpr (TD == DMT_F32) {
               float4 v = w[u];
               v.x -= step * g.x; v.y -= step * g.y; v.z -= step * g.z; v.w -= step * g.w;
-              *wp[u] = v;
+              dmt::gstore(v, wp[u]);
             } else {
               float a, b, c, d;
               dmt::unpack2<TD>(w[u].x, a, b);
               dmt::unpack2<TD>(w[u].y, c, d);
               a -= step * g.x; b -= step * g.y; c -= step * g.z; d -= step * g.w;
-              *wp[u] = make_uint2(dmt::pack2<TD>(a, b), dmt::pack2<TD>(c, d));
+              dmt::gstore(make_uint2(dmt::pack2<TD>(a, b), dmt::pack2<TD>(c, d)), wp[u]);
             }
           }
-          if (gl == 0) *sp[u] = sn;
+          if (gl == 0) dmt::gstore(sn, sp[u]);
         }
       }
     }
@@ -727,25 +737,25 @@ __device__ __forceinline__ void lane_row_update(void* rowp, int lane,
     if constexpr (EPL == 1) v -= step * g;
     else if constexpr (EPL == 2) { v.x -= step * g.x; v.y -= step * g.y; }
     else { v.x -= step * g.x; v.y -= step * g.y; v.z -= step * g.z; v.w -= step * g.w; }
-    ((V*)rowp)[lane] = v;
+    dmt::gstore(v, (V*)rowp + lane);
   } else if constexpr (EPL == 1) {
     const uint16_t u = *(const uint16_t*)loaded;
     float a = TD == DMT_F16 ? dmt::f16_bits_to_f32(u) : dmt::bf16_lo(u);
     a -= step * g;
-    ((uint16_t*)rowp)[lane] =
-        (uint16_t)(TD == DMT_F16 ? dmt::f32_to_f16_bits(a) : dmt::f32_to_bf16_bits(a));
+    dmt::gstore((uint16_t)(TD == DMT_F16 ? dmt::f32_to_f16_bits(a) : dmt::f32_to_bf16_bits(a)),
+                (uint16_t*)rowp + lane);
   } else if constexpr (EPL == 2) {
     float a, b;
     dmt::unpack2<TD>(*(const uint32_t*)loaded, a, b);
     a -= step * g.x; b -= step * g.y;
-    ((uint32_t*)rowp)[lane] = dmt::pack2<TD>(a, b);
+    dmt::gstore(dmt::pack2<TD>(a, b), (uint32_t*)rowp + lane);
   } else {
     const uint2 u = *(const uint2*)loaded;
     float a, b, c, d;
     dmt::unpack2<TD>(u.x, a, b);
     dmt::unpack2<TD>(u.y, c, d);
     a -= step * g.x; b -= step * g.y; c -= step * g.z; d -= step * g.w;
-    ((uint2*)rowp)[lane] = make_uint2(dmt::pack2<TD>(a, b), dmt::pack2<TD>(c, d));
+    dmt::gstore(make_uint2(dmt::pack2<TD>(a, b), dmt::pack2<TD>(c, d)), (uint2*)rowp + lane);
   }
 }
 
@@ -821,6 +831,7 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update_wave(
   };
   auto drain = [&]() {
     const int open_slot = qn;                      // may hold the open run's addresses
+    wave_lds_sync();                               // the head lanes' addresses, the parked sums
     if constexpr (EPL == 2) {
       // two parked rows per step: lanes 0-31 take one, lanes 32-63 the next (4 columns a lane)
       using Chunk2 = typename RowChunk<TD>::type;
@@ -841,7 +852,7 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update_wave(
             wp[u] = (Chunk2*)q_rowp[wave][j] + hl;
             sp[u] = (float*)q_stp[wave][j];
             // row and state are touched once per call: keep them from evicting gradient slices
-            st[u] = __builtin_nontemporal_load(sp[u]);
+            st[u] = dmt::nt_load(sp[u]);
             if (hl * 4 < D[u]) w[u] = dmt::nt_load(wp[u]);
           }
         }
@@ -866,7 +877,7 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update_wave(
                 dmt::nt_store(make_uint2(dmt::pack2<TD>(a, b), dmt::pack2<TD>(c, d)), wp[u]);
               }
             }
-            if (hl == 0) __builtin_nontemporal_store(sn, sp[u]);
+            if (hl == 0) dmt::nt_store(sn, sp[u]);
           }
         }
       }
@@ -885,8 +896,8 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update_wave(
             D[u] = UD ? Dmax : __builtin_amdgcn_readfirstlane(q_D[wave][j0 + u]);
             wp[u] = (void*)q_rowp[wave][j0 + u];
             sp[u] = (float*)q_stp[wave][j0 + u];
-            st[u] = *sp[u];
-            if (lane * EPL < D[u]) w[u] = ((const Chunk*)wp[u])[lane];
+            st[u] = dmt::gload(sp[u]);
+            if (lane * EPL < D[u]) w[u] = dmt::gload((const Chunk*)wp[u] + lane);
           }
         }
 #pragma unroll
@@ -899,11 +910,12 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update_wave(
             const float sn = st[u] + ss * __builtin_amdgcn_rcpf((float)D[u]);
             const float step = lr * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(sn) + eps);
             if (lane * EPL < D[u]) lane_row_update<TD, EPL>(wp[u], lane, g, step, &w[u]);
-            if (lane == 0) *sp[u] = sn;
+            if (lane == 0) dmt::gstore(sn, sp[u]);
           }
         }
       }
     }
+    wave_lds_sync();                               // every lane is done reading the slots
     // an open run keeps its addresses: move them to the slot it will be parked in now
     if (open_slot > 0 && open_slot < kQueueSlotsWave + 1 && run_open && !from_left && lane == 0) {
       q_rowp[wave][0] = q_rowp[wave][open_slot];

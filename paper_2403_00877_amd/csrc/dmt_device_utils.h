@@ -99,30 +99,80 @@ typedef float dmt_f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int dmt_u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int dmt_u32x4 __attribute__((ext_vector_type(4)));
 
+// Table rows, states and the other tensors the kernels stream live in global memory.  A
+// pointer that was read from a descriptor in memory or rebuilt from an integer has lost that
+// fact and would be accessed with flat instructions (which also occupy the LDS path): these
+// casts give it back.
+#define DMT_GLOBAL __attribute__((address_space(1)))
+
 __device__ __forceinline__ float4 nt_load(const float4* p) {
-  const dmt_f32x4 v = __builtin_nontemporal_load((const dmt_f32x4*)p);
+  const dmt_f32x4 v = __builtin_nontemporal_load((const DMT_GLOBAL dmt_f32x4*)p);
   return make_float4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ void nt_store(float4 v, float4* p) {
   dmt_f32x4 t = {v.x, v.y, v.z, v.w};
-  __builtin_nontemporal_store(t, (dmt_f32x4*)p);
+  __builtin_nontemporal_store(t, (DMT_GLOBAL dmt_f32x4*)p);
 }
 __device__ __forceinline__ uint2 nt_load(const uint2* p) {
-  const dmt_u32x2 v = __builtin_nontemporal_load((const dmt_u32x2*)p);
+  const dmt_u32x2 v = __builtin_nontemporal_load((const DMT_GLOBAL dmt_u32x2*)p);
   return make_uint2(v.x, v.y);
 }
 __device__ __forceinline__ void nt_store(uint2 v, uint2* p) {
   dmt_u32x2 t = {v.x, v.y};
-  __builtin_nontemporal_store(t, (dmt_u32x2*)p);
+  __builtin_nontemporal_store(t, (DMT_GLOBAL dmt_u32x2*)p);
 }
 __device__ __forceinline__ uint4 nt_load(const uint4* p) {
-  const dmt_u32x4 v = __builtin_nontemporal_load((const dmt_u32x4*)p);
+  const dmt_u32x4 v = __builtin_nontemporal_load((const DMT_GLOBAL dmt_u32x4*)p);
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ void nt_store(uint4 v, uint4* p) {
   dmt_u32x4 t = {v.x, v.y, v.z, v.w};
-  __builtin_nontemporal_store(t, (dmt_u32x4*)p);
+  __builtin_nontemporal_store(t, (DMT_GLOBAL dmt_u32x4*)p);
 }
+
+__device__ __forceinline__ float nt_load(const float* p) {
+  return __builtin_nontemporal_load((const DMT_GLOBAL float*)p);
+}
+__device__ __forceinline__ void nt_store(float v, float* p) {
+  __builtin_nontemporal_store(v, (DMT_GLOBAL float*)p);
+}
+
+// Plain loads / stores of global memory through a pointer of unknown address space.
+typedef float dmt_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float4 gload(const float4* p) {
+  const dmt_f32x4 v = *(const DMT_GLOBAL dmt_f32x4*)p;
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void gstore(float4 v, float4* p) {
+  dmt_f32x4 t = {v.x, v.y, v.z, v.w};
+  *(DMT_GLOBAL dmt_f32x4*)p = t;
+}
+__device__ __forceinline__ float2 gload(const float2* p) {
+  const dmt_f32x2 v = *(const DMT_GLOBAL dmt_f32x2*)p;
+  return make_float2(v.x, v.y);
+}
+__device__ __forceinline__ void gstore(float2 v, float2* p) {
+  dmt_f32x2 t = {v.x, v.y};
+  *(DMT_GLOBAL dmt_f32x2*)p = t;
+}
+__device__ __forceinline__ uint4 gload(const uint4* p) {
+  const dmt_u32x4 v = *(const DMT_GLOBAL dmt_u32x4*)p;
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint2 gload(const uint2* p) {
+  const dmt_u32x2 v = *(const DMT_GLOBAL dmt_u32x2*)p;
+  return make_uint2(v.x, v.y);
+}
+__device__ __forceinline__ void gstore(uint2 v, uint2* p) {
+  dmt_u32x2 t = {v.x, v.y};
+  *(DMT_GLOBAL dmt_u32x2*)p = t;
+}
+__device__ __forceinline__ float gload(const float* p) { return *(const DMT_GLOBAL float*)p; }
+__device__ __forceinline__ void gstore(float v, float* p) { *(DMT_GLOBAL float*)p = v; }
+__device__ __forceinline__ uint32_t gload(const uint32_t* p) { return *(const DMT_GLOBAL uint32_t*)p; }
+__device__ __forceinline__ void gstore(uint32_t v, uint32_t* p) { *(DMT_GLOBAL uint32_t*)p = v; }
+__device__ __forceinline__ uint16_t gload(const uint16_t* p) { return *(const DMT_GLOBAL uint16_t*)p; }
+__device__ __forceinline__ void gstore(uint16_t v, uint16_t* p) { *(DMT_GLOBAL uint16_t*)p = v; }
 
 // Development knob: integer from the environment, `dflt` when unset.
 static inline int env_int(const char* name, int dflt) {

@@ -89,7 +89,7 @@ __global__ __launch_bounds__(kBlock) void lookup_fwd_kernel(
           const int r = __shfl(my, group_lane0 + (p & (GL - 1)));
           v[u] = make_uint4(0, 0, 0, 0);
           if (chunk_ok && p < n && r >= 0)
-            v[u] = *(const uint4*)(tab + (int64_t)r * rowbytes + chunk * 16);
+            v[u] = dmt::gload((const uint4*)(tab + (int64_t)r * rowbytes + chunk * 16));
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) dmt::accumulate_chunk<TD>(acc, v[u]);
