@@ -130,24 +130,38 @@ __device__ void build_sort_map(const int64_t* __restrict__ offsets, uint32_t B, 
   }
 }
 
+// One block takes 2^log2_bpb consecutive bags and walks their lookups id by id, so the work per
+// thread does not depend on how the bag lengths are spread (a lane group per bag leaves most lanes
+// idle when a few bags are hundreds of ids long and most hold one or two).  The bags' offsets go
+// to LDS; a thread finds the bag of its position by bisection there.
+constexpr int kKeysMaxBags = 1024;
 __global__ __launch_bounds__(kBlock) void bwd_build_keys(
     const DmtTableMeta* __restrict__ meta, const int32_t* __restrict__ indices,
     const int64_t* __restrict__ offsets, uint32_t B, uint32_t nbags, int64_t nnz, int F,
-    uint64_t* __restrict__ pk, int log2_gl, uint32_t* __restrict__ seg_begin,
+    uint64_t* __restrict__ pk, int log2_bpb, uint32_t* __restrict__ seg_begin,
     uint32_t* __restrict__ seg_blk, uint32_t* __restrict__ blk_table,
     unsigned long long* __restrict__ err) {
+  __shared__ int64_t offs[kKeysMaxBags + 1];
   if (blockIdx.x == 0) build_sort_map(offsets, B, F, nnz, seg_begin, seg_blk, blk_table);
-  const int GL = 1 << log2_gl;
-  const uint32_t g = blockIdx.x * (kBlock >> log2_gl) + (threadIdx.x >> log2_gl);
-  if (g >= nbags) return;
-  const int gl = threadIdx.x & (GL - 1);
-  const uint32_t f = g / B;
-  int64_t s = offsets[g], e = offsets[g + 1];
-  s = s < 0 ? 0 : (s > nnz ? nnz : s);
-  e = e < s ? s : (e > nnz ? nnz : e);
-  const uint64_t rows = (uint64_t)meta[f].rows;
-  const uint32_t row_base = (uint32_t)meta[f].row_base;
-  for (int64_t j = s + gl; j < e; j += GL) {
+  const uint32_t g0 = blockIdx.x << log2_bpb;
+  if (g0 >= nbags) return;
+  const int nb = (int)min((uint32_t)(1 << log2_bpb), nbags - g0);
+  for (int i = threadIdx.x; i <= nb; i += kBlock) {
+    const int64_t o = offsets[g0 + i];
+    offs[i] = o < 0 ? 0 : (o > nnz ? nnz : o);
+  }
+  __syncthreads();
+  const int64_t s = offs[0], e = offs[nb];
+  for (int64_t j = s + threadIdx.x; j < e; j += kBlock) {
+    int lo = 0, hi = nb;                           // offs[lo] <= j < offs[hi]
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (offs[mid] <= j) lo = mid; else hi = mid;
+    }
+    const uint32_t g = g0 + (uint32_t)lo;
+    const uint32_t f = g / B;
+    const uint64_t rows = (uint64_t)meta[f].rows;
+    const uint32_t row_base = (uint32_t)meta[f].row_base;
     const int32_t idx = indices[j];
     uint32_t gid = row_base + (uint32_t)idx;
     if ((uint64_t)(uint32_t)idx >= rows) {
@@ -1124,13 +1138,13 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
   if (nnz > 0) {
     // keys
     const double mean_len = (double)nnz / (double)nbags;
-    // lanes per bag: about a quarter of the mean bag length (measured best on MI355X)
-    int log2_gl = ilog2_ceil((int64_t)(mean_len + 0.5)) - 2;
-    log2_gl = dmt::env_int("DMT_KEYS_LG", log2_gl);
-    log2_gl = log2_gl < 2 ? 2 : (log2_gl > 6 ? 6 : log2_gl);
-    const unsigned kb_blocks = (nbags + (kBlock >> log2_gl) - 1) / (kBlock >> log2_gl);
+    // bags per block: about 4096 lookups' worth (a power of two, at most kKeysMaxBags)
+    int log2_bpb = ilog2_ceil((int64_t)(4096.0 / (mean_len > 1.0 ? mean_len : 1.0) + 0.5));
+    log2_bpb = dmt::env_int("DMT_KEYS_LG", log2_bpb);
+    log2_bpb = log2_bpb < 4 ? 4 : (log2_bpb > 10 ? 10 : log2_bpb);
+    const unsigned kb_blocks = (unsigned)(((int64_t)nbags + (1 << log2_bpb) - 1) >> log2_bpb);
     { DmtScope sc_(plan, DMT_K_BWD_KEYS, s); hipLaunchKernelGGL(bwd_build_keys, dim3(kb_blocks), dim3(kBlock), 0, s, plan->d_meta, indices,
-                       offsets, (uint32_t)B, nbags, nnz, (int)plan->F, w.pk_a, log2_gl,
+                       offsets, (uint32_t)B, nbags, nnz, (int)plan->F, w.pk_a, log2_bpb,
                        w.seg_begin, w.seg_blk, w.blk_table, plan->d_error); }
     // stable LSD radix sort inside every table over the bits a row id of the largest table
     // (or its one-past-the-end inert id) can set
