@@ -32,7 +32,7 @@ __global__ __launch_bounds__(kBlock) void lookup_fwd_kernel(
     const DmtTableMeta* __restrict__ meta, const int32_t* __restrict__ class_tables, int32_t D,
     const int32_t* __restrict__ indices, const int64_t* __restrict__ offsets, int64_t B,
     int64_t nnz, void* __restrict__ out, int log2_lpr, int log2_gl, int bags_per_group,
-    int32_t tiles_per_table, int32_t ntiles, int32_t tiles_per_xcd,
+    int32_t tiles_per_table, int32_t ntiles, int32_t tiles_per_xcd, int long_thr,
     unsigned long long* __restrict__ err) {
   constexpr int EPL = dmt::ChunkElems<TD>::value;
   const int bid = blockIdx.x;
@@ -45,32 +45,21 @@ __global__ __launch_bounds__(kBlock) void lookup_fwd_kernel(
   const int64_t rows = meta[f].rows;
   const int64_t out_base = B * meta[f].out_prefix + meta[f].col_off;
   const int32_t tower_width = meta[f].tower_width;
-
-  const int GL = 1 << log2_gl, LPR = 1 << log2_lpr, R = GL >> log2_lpr;
+  const int LPR = 1 << log2_lpr;
   const int lane = threadIdx.x & 63;
-  const int gl = threadIdx.x & (GL - 1);
-  const int group = threadIdx.x >> log2_gl;
-  const int ngroups = kBlock >> log2_gl;
-  const int slot = gl >> log2_lpr;
-  const int chunk = gl & (LPR - 1);
+  const int chunk = threadIdx.x & (LPR - 1);
   const bool chunk_ok = chunk * EPL < D;
-  const int group_lane0 = lane & ~(GL - 1);
   const int64_t rowbytes = (int64_t)D * dmt::EltBytes<TD>::value;
-  const int64_t b0 = (int64_t)c * ngroups * bags_per_group;
 
-  for (int i = 0; i < bags_per_group; ++i) {
-    const int64_t b = b0 + (int64_t)i * ngroups + group;
-    if (b >= B) break;
-    const int64_t bag = (int64_t)f * B + b;
-    int64_t s = offsets[bag], e = offsets[bag + 1];
-    s = s < 0 ? 0 : (s > nnz ? nnz : s);
-    e = e < s ? s : (e > nnz ? nnz : e);
-    const int len = (int)(e - s);
-
+  // The aligned group of 2^lg lanes this thread is in pools bag b (ids s .. s + len).
+  auto pool_bag = [&](int64_t b, int64_t s, int len, int lg) {
+    const int GL = 1 << lg, R = GL >> log2_lpr;
+    const int gl = threadIdx.x & (GL - 1);
+    const int slot = gl >> log2_lpr;
+    const int group_lane0 = lane & ~(GL - 1);
     float acc[EPL];
 #pragma unroll
     for (int q = 0; q < EPL; ++q) acc[q] = 0.f;
-
     for (int base = 0; base < len; base += GL) {
       const int n = min(GL, len - base);
       int my = 0;
@@ -101,13 +90,44 @@ __global__ __launch_bounds__(kBlock) void lookup_fwd_kernel(
     }
     if (slot == 0 && chunk_ok)
       dmt::store_chunk<OD, EPL>(out, out_base + b * tower_width + chunk * EPL, acc);
+  };
+
+  const int GL = 1 << log2_gl;
+  const int gl = threadIdx.x & (GL - 1);
+  const int group = threadIdx.x >> log2_gl;
+  const int ngroups = kBlock >> log2_gl;
+  const int64_t b0 = (int64_t)c * ngroups * bags_per_group;
+  for (int i = 0; i < bags_per_group; ++i) {
+    const int64_t b = b0 + (int64_t)i * ngroups + group;
+    int64_t s = 0;
+    int len = 0;
+    if (b < B) {
+      const int64_t bag = (int64_t)f * B + b;
+      int64_t e = offsets[bag + 1];
+      s = offsets[bag];
+      s = s < 0 ? 0 : (s > nnz ? nnz : s);
+      e = e < s ? s : (e > nnz ? nnz : e);
+      len = (int)(e - s);
+    }
+    // A bag much longer than the others would hold up every other bag of its wave: the groups
+    // with ordinary bags pool theirs, then the whole wave pools the long ones, one at a time,
+    // 64 / LPR rows per load instruction.
+    const bool is_long = long_thr > 0 && len > long_thr;
+    if (b < B && !is_long) pool_bag(b, s, len, log2_gl);
+    unsigned long long todo = __ballot(is_long && gl == 0);
+    while (todo) {
+      const int src = __builtin_ctzll(todo);
+      todo &= todo - 1;
+      const int64_t lb = __shfl(b, src), ls = __shfl(s, src);
+      pool_bag(lb, ls, __shfl(len, src), 6);
+    }
   }
 }
 
 template <int TD, int OD>
 void launch(const dmt_plan* p, const DmtDimClass& c, const int32_t* indices,
             const int64_t* offsets, int64_t B, int64_t nnz, void* out, int log2_lpr, int log2_gl,
-            int bpg, hipStream_t s) {
+            int bpg, int long_thr, hipStream_t s) {
   const int ngroups = kBlock >> log2_gl;
   const int64_t bags_per_block = (int64_t)ngroups * bpg;
   const int32_t tiles_per_table = (int32_t)((B + bags_per_block - 1) / bags_per_block);
@@ -115,7 +135,7 @@ void launch(const dmt_plan* p, const DmtDimClass& c, const int32_t* indices,
   const int32_t tiles_per_xcd = (ntiles + 7) / 8;
   { DmtScope sc_(p, DMT_K_LOOKUP_FWD, s); hipLaunchKernelGGL((lookup_fwd_kernel<TD, OD>), dim3(tiles_per_xcd * 8), dim3(kBlock), 0, s,
                      p->d_meta, p->d_class_tables + c.first, c.D, indices, offsets, B, nnz, out,
-                     log2_lpr, log2_gl, bpg, tiles_per_table, ntiles, tiles_per_xcd, p->d_error); }
+                     log2_lpr, log2_gl, bpg, tiles_per_table, ntiles, tiles_per_xcd, long_thr, p->d_error); }
 }
 
 int ilog2_ceil(int x) {
@@ -157,10 +177,14 @@ extern "C" dmt_status dmt_tower_lookup_fwd(const dmt_plan* plan, const int32_t* 
     const int ngroups = kBlock >> log2_gl;
     int bpg = 1;
     if (tuned_bpg > 0) bpg = tuned_bpg;
+    // bags several times longer than the mean are pooled by whole waves (0: never)
+    int long_thr = 4 * (int)(mean_len + 1.0);
+    long_thr = (long_thr < 8 ? 8 : long_thr) * r;
+    long_thr = log2_gl < 6 ? dmt::env_int("DMT_LOOKUP_LONG", long_thr) : 0;
     const int td = (int)plan->table_dtype, od = (int)out_dtype;
 #define DMT_CASE(TD, OD)                                                                      \
   if (td == TD && od == OD)                                                                   \
-    launch<TD, OD>(plan, c, indices, offsets, B, nnz, pooled_out, log2_lpr, log2_gl, bpg, s);
+    launch<TD, OD>(plan, c, indices, offsets, B, nnz, pooled_out, log2_lpr, log2_gl, bpg, long_thr, s);
     DMT_CASE(DMT_F32, DMT_F32) DMT_CASE(DMT_F32, DMT_F16) DMT_CASE(DMT_F32, DMT_BF16)
     DMT_CASE(DMT_F16, DMT_F32) DMT_CASE(DMT_F16, DMT_F16) DMT_CASE(DMT_F16, DMT_BF16)
     DMT_CASE(DMT_BF16, DMT_F32) DMT_CASE(DMT_BF16, DMT_F16) DMT_CASE(DMT_BF16, DMT_BF16)
