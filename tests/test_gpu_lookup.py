@@ -50,6 +50,15 @@ def test_group_shapes_agree(r, monkeypatch):
     _check(wl.scaled(wl.imbalanced(), max_rows=3000, batch=500, num_tables=12), "f32")
 
 
+@pytest.mark.parametrize("thr", [0, 1, 5, 1000000])
+def test_long_bag_threshold_settings_agree(thr, monkeypatch):
+    """Bags above the threshold are pooled by a whole wave, the others by their lane group:
+    every split (none, all, some, none again) gives the oracle's result."""
+    monkeypatch.setenv("DMT_LOOKUP_LONG", str(thr))
+    _check(wl.scaled(wl.imbalanced(), max_rows=3000, batch=700, num_tables=12), "f32")
+    _check(wl.scaled(wl.mid(), max_rows=3000, batch=77, num_tables=8), "bf16")
+
+
 def test_empty_bags_and_empty_batch():
     w = wl.scaled(wl.mid(), max_rows=100, batch=9, num_tables=8)
     dw = DeviceWorkload(w)
