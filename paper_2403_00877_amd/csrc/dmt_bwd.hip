@@ -520,7 +520,9 @@ template <> struct RowChunk<DMT_F32> { using type = float4; static constexpr int
 #define DMT_QS 5
 #endif
 constexpr int kQueueSlots = DMT_QS;
-constexpr int kQueueSlotsWave = 8;  // the wave-per-tile kernel parks 8 (its slots are half as large)   // finished runs a lane group parks before their rows are updated
+// finished runs parked before their rows are updated: per lane group, and per wave of the
+// wave-per-tile kernel (whose slots are half as large)
+constexpr int kQueueSlotsWave = 8;
 
 // Each group of GL = 2^LG lanes walks one tile of kReduceTile sorted records,
 // summing the bags' gradient slices run by run (float32, record order).  Runs
@@ -1107,6 +1109,71 @@ int ilog2_ceil(int64_t x) {
   return l;
 }
 
+// One launch on `s`, bracketed by the plan's timing events when that kernel family is selected.
+template <typename Kernel, typename... Args>
+void timed_launch(const dmt_plan* plan, dmt_kernel_id id, hipStream_t s, Kernel kernel,
+                  int64_t blocks, int threads, Args... args) {
+  DmtScope scope(plan, id, s);
+  hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3((unsigned)threads), 0, s, args...);
+}
+
+// What the reduce / fix-up launches share.
+struct ReduceCall {
+  const dmt_plan* plan;
+  const BwdWs* w;
+  const uint64_t* sorted;
+  int64_t nnz, B;
+  uint32_t nbags, total_rows;
+  const float* grad;
+  float lr, eps;
+  hipStream_t s;
+};
+
+template <int TD, int EPL>
+void launch_reduce_wave(const ReduceCall& c) {
+  constexpr int kWavesPerBlock = kBlock / 64;
+  const int64_t per_xcd = ((c.w->ntiles + kWavesPerBlock - 1) / kWavesPerBlock + 7) / 8;
+  auto kernel = c.plan->classes.size() == 1 ? bwd_reduce_update_wave<TD, EPL, true>
+                                            : bwd_reduce_update_wave<TD, EPL, false>;
+  timed_launch(c.plan, DMT_K_BWD_REDUCE_UPDATE, c.s, kernel, per_xcd * 8, kBlock, c.plan->d_meta,
+               c.sorted, c.nnz, (uint32_t)c.B, c.nbags, c.total_rows, c.grad, c.w->partials,
+               c.plan->max_dim, c.w->ntiles, per_xcd, c.lr, c.eps);
+}
+
+template <int TD, int LG>
+void launch_reduce_grouped(const ReduceCall& c) {
+  const int64_t blocks = (c.w->ntiles + (kBlock >> LG) - 1) / (kBlock >> LG);
+  const int64_t per_xcd = (blocks + 7) / 8;
+  auto kernel = c.plan->classes.size() == 1 ? bwd_reduce_update<TD, LG, true>
+                                            : bwd_reduce_update<TD, LG, false>;
+  timed_launch(c.plan, DMT_K_BWD_REDUCE_UPDATE, c.s, kernel, per_xcd * 8, kBlock, c.plan->d_meta,
+               c.sorted, c.nnz, (uint32_t)c.B, c.nbags, c.total_rows, c.grad, c.w->partials,
+               c.plan->max_dim, c.w->ntiles, per_xcd, c.lr, c.eps);
+}
+
+// Segment reduce + row update, then the rows whose run spans tiles.
+template <int TD>
+void launch_reduce_and_fixup(const ReduceCall& c) {
+  const int max_dim = c.plan->max_dim;
+  const int log2_gl = std::max(2, ilog2_ceil(max_dim / 4));       // lanes that hold one row
+  const bool wave_kernel = (max_dim == 128 || max_dim == 256) && dmt::env_int("DMT_BWD_WAVE", 1) != 0;
+  if (wave_kernel) {
+    if (max_dim == 128) launch_reduce_wave<TD, 2>(c); else launch_reduce_wave<TD, 4>(c);
+  } else {
+    switch (log2_gl) {
+      case 2: launch_reduce_grouped<TD, 2>(c); break;
+      case 3: launch_reduce_grouped<TD, 3>(c); break;
+      case 4: launch_reduce_grouped<TD, 4>(c); break;
+      case 5: launch_reduce_grouped<TD, 5>(c); break;
+      default: launch_reduce_grouped<TD, 6>(c); break;
+    }
+  }
+  const int64_t blocks = (c.w->ntiles + (kBlock >> log2_gl) - 1) / (kBlock >> log2_gl);
+  timed_launch(c.plan, DMT_K_BWD_FIXUP, c.s, bwd_fixup_update<TD>, blocks, kBlock, c.plan->d_meta,
+               c.plan->d_row_base, c.plan->F, c.sorted, c.nnz, c.total_rows, c.w->partials, max_dim,
+               log2_gl, c.w->ntiles, c.lr, c.eps);
+}
+
 }  // namespace
 
 extern "C" size_t dmt_bwd_workspace_bytes(const dmt_plan* plan, int64_t B, int64_t nnz) {
@@ -1136,16 +1203,16 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
   const uint64_t* sorted = w.pk_a;
 
   if (nnz > 0) {
-    // keys
+    // keys; bags per block: about 4096 lookups' worth (a power of two, at most kKeysMaxBags)
     const double mean_len = (double)nnz / (double)nbags;
-    // bags per block: about 4096 lookups' worth (a power of two, at most kKeysMaxBags)
     int log2_bpb = ilog2_ceil((int64_t)(4096.0 / (mean_len > 1.0 ? mean_len : 1.0) + 0.5));
     log2_bpb = dmt::env_int("DMT_KEYS_LG", log2_bpb);
     log2_bpb = log2_bpb < 4 ? 4 : (log2_bpb > 10 ? 10 : log2_bpb);
-    const unsigned kb_blocks = (unsigned)(((int64_t)nbags + (1 << log2_bpb) - 1) >> log2_bpb);
-    { DmtScope sc_(plan, DMT_K_BWD_KEYS, s); hipLaunchKernelGGL(bwd_build_keys, dim3(kb_blocks), dim3(kBlock), 0, s, plan->d_meta, indices,
-                       offsets, (uint32_t)B, nbags, nnz, (int)plan->F, w.pk_a, log2_bpb,
-                       w.seg_begin, w.seg_blk, w.blk_table, plan->d_error); }
+    const int64_t key_blocks = ((int64_t)nbags + (1 << log2_bpb) - 1) >> log2_bpb;
+    timed_launch(plan, DMT_K_BWD_KEYS, s, bwd_build_keys, key_blocks, kBlock, plan->d_meta, indices,
+                 offsets, (uint32_t)B, nbags, nnz, (int)plan->F, w.pk_a, log2_bpb, w.seg_begin,
+                 w.seg_blk, w.blk_table, plan->d_error);
+
     // stable LSD radix sort inside every table over the bits a row id of the largest table
     // (or its one-past-the-end inert id) can set
     int64_t max_rows = 0;
@@ -1157,77 +1224,34 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
     uint64_t* dst = w.pk_b;
     for (int p = 0; p < passes; ++p) {
       const int shift = p * bits_per;
-      const int bits = (key_bits - shift) < bits_per ? (key_bits - shift) : bits_per;
-      { DmtScope sc_(plan, DMT_K_BWD_SORT_HIST, s); hipLaunchKernelGGL(radix_hist, dim3((unsigned)w.nblk_sort), dim3(kBlock), 0, s, plan->d_meta, src,
-                         shift, bits, w.hist, w.seg_begin, w.seg_blk, w.blk_table, (int)plan->F); }
-      { DmtScope sc_(plan, DMT_K_BWD_SORT_SCAN, s); hipLaunchKernelGGL(radix_scan, dim3((unsigned)plan->F), dim3(kScanThreads), 0, s, w.hist, bits,
-                         w.seg_begin, w.seg_blk); }
-      { DmtScope sc_(plan, DMT_K_BWD_SORT_SCATTER, s); hipLaunchKernelGGL(radix_scatter, dim3((unsigned)w.nblk_sort), dim3(kBlock), 0, s, plan->d_meta, src, dst,
-                         shift, bits, w.hist, w.seg_begin, w.seg_blk, w.blk_table, (int)plan->F); }
-      uint64_t* tmp = src; src = dst; dst = tmp;
+      const int bits = std::min(bits_per, key_bits - shift);
+      timed_launch(plan, DMT_K_BWD_SORT_HIST, s, radix_hist, w.nblk_sort, kBlock, plan->d_meta, src,
+                   shift, bits, w.hist, w.seg_begin, w.seg_blk, w.blk_table, (int)plan->F);
+      timed_launch(plan, DMT_K_BWD_SORT_SCAN, s, radix_scan, plan->F, kScanThreads, w.hist, bits,
+                   w.seg_begin, w.seg_blk);
+      timed_launch(plan, DMT_K_BWD_SORT_SCATTER, s, radix_scatter, w.nblk_sort, kBlock, plan->d_meta,
+                   src, dst, shift, bits, w.hist, w.seg_begin, w.seg_blk, w.blk_table, (int)plan->F);
+      std::swap(src, dst);
     }
     sorted = src;
-    // segment reduce + update, then the rows that span tiles
-    int log2_glb = ilog2_ceil(plan->max_dim / 4);
-    if (log2_glb < 2) log2_glb = 2;
-    const int groups = kBlock >> log2_glb;
-    const int64_t rblocks = (w.ntiles + groups - 1) / groups;
-    const int64_t blocks_per_xcd = (rblocks + 7) / 8;
-    const int td = (int)plan->table_dtype;
-    const bool ud = plan->classes.size() == 1;
-#define DMT_BWD_LAUNCH(TD, LG, UD)                                                                \
-  hipLaunchKernelGGL((bwd_reduce_update<TD, LG, UD>), dim3((unsigned)(blocks_per_xcd * 8)),       \
-                     dim3(kBlock), 0, s, plan->d_meta, sorted, nnz, (uint32_t)B, nbags,           \
-                     total_rows, grad_pooled, w.partials, plan->max_dim, w.ntiles,                \
-                     blocks_per_xcd, lr, eps)
-#define DMT_BWD_LG(TD, LG)                                                                        \
-  if (log2_glb == LG) {                                                                           \
-    if (ud) DMT_BWD_LAUNCH(TD, LG, true); else DMT_BWD_LAUNCH(TD, LG, false);                     \
-  }
-    const bool wave_kernel = (plan->max_dim == 128 || plan->max_dim == 256) &&
-                             dmt::env_int("DMT_BWD_WAVE", 1) != 0;
-    const int epl = plan->max_dim / 64;
-    const int64_t wblocks_per_xcd = ((w.ntiles + kBlock / 64 - 1) / (kBlock / 64) + 7) / 8;
-#define DMT_BWD_WLAUNCH(TD, EPL, UD)                                                              \
-  hipLaunchKernelGGL((bwd_reduce_update_wave<TD, EPL, UD>), dim3((unsigned)(wblocks_per_xcd * 8)), \
-                     dim3(kBlock), 0, s, plan->d_meta, sorted, nnz, (uint32_t)B, nbags,           \
-                     total_rows, grad_pooled, w.partials, plan->max_dim, w.ntiles,                \
-                     wblocks_per_xcd, lr, eps)
-#define DMT_BWD_EPL(TD, EPL)                                                                      \
-  if (epl == EPL) {                                                                               \
-    if (ud) DMT_BWD_WLAUNCH(TD, EPL, true); else DMT_BWD_WLAUNCH(TD, EPL, false);                 \
-  }
-#define DMT_BWD_CASE(TD)                                                                          \
-  if (td == TD) {                                                                                 \
-    {                                                                                             \
-      DmtScope sc_(plan, DMT_K_BWD_REDUCE_UPDATE, s);                                             \
-      if (wave_kernel) {                                                                          \
-        DMT_BWD_EPL(TD, 2) DMT_BWD_EPL(TD, 4)                                                     \
-      } else {                                                                                    \
-        DMT_BWD_LG(TD, 2) DMT_BWD_LG(TD, 3) DMT_BWD_LG(TD, 4) DMT_BWD_LG(TD, 5) DMT_BWD_LG(TD, 6) \
-      }                                                                                           \
-    }                                                                                             \
-    { DmtScope sc_(plan, DMT_K_BWD_FIXUP, s); hipLaunchKernelGGL((bwd_fixup_update<TD>), dim3((unsigned)rblocks), dim3(kBlock), 0, s,       \
-                       plan->d_meta, plan->d_row_base, plan->F, sorted, nnz, total_rows,          \
-                       w.partials, plan->max_dim, log2_glb, w.ntiles, lr, eps); }                                                                  \
-  }
-    DMT_BWD_CASE(DMT_F32) DMT_BWD_CASE(DMT_F16) DMT_BWD_CASE(DMT_BF16)
-#undef DMT_BWD_CASE
-#undef DMT_BWD_LG
-#undef DMT_BWD_LAUNCH
-#undef DMT_BWD_EPL
-#undef DMT_BWD_WLAUNCH
+
+    const ReduceCall call{plan, &w, sorted, nnz, B, nbags, total_rows, grad_pooled, lr, eps, s};
+    switch (plan->table_dtype) {
+      case DMT_F32: launch_reduce_and_fixup<DMT_F32>(call); break;
+      case DMT_F16: launch_reduce_and_fixup<DMT_F16>(call); break;
+      default: launch_reduce_and_fixup<DMT_BF16>(call); break;
+    }
   }
   if (dbg && (dbg->sorted_keys || dbg->sorted_bag || dbg->unique_keys || dbg->seg_off ||
               dbg->num_unique)) {
     if (nnz > 0) {
-    // run heads -> segment offsets (only the parity exports need them)
-      { DmtScope sc_(plan, DMT_K_BWD_HEADS, s); hipLaunchKernelGGL(heads_count, dim3((unsigned)w.nblk_scan), dim3(kBlock), 0, s, sorted, nnz,
-                         w.blk_heads); }
-      { DmtScope sc_(plan, DMT_K_BWD_HEADS, s); hipLaunchKernelGGL(heads_scan, dim3(1), dim3(1024), 0, s, w.blk_heads, w.nblk_scan,
-                         w.num_unique); }
-      { DmtScope sc_(plan, DMT_K_BWD_HEADS, s); hipLaunchKernelGGL(heads_write, dim3((unsigned)w.nblk_scan), dim3(kBlock), 0, s, sorted, nnz,
-                         w.blk_heads, w.seg_off, w.tile_first); }
+      // run heads -> segment offsets (only the parity exports need them)
+      timed_launch(plan, DMT_K_BWD_HEADS, s, heads_count, w.nblk_scan, kBlock, sorted, nnz,
+                   w.blk_heads);
+      timed_launch(plan, DMT_K_BWD_HEADS, s, heads_scan, 1, 1024, w.blk_heads, w.nblk_scan,
+                   w.num_unique);
+      timed_launch(plan, DMT_K_BWD_HEADS, s, heads_write, w.nblk_scan, kBlock, sorted, nnz,
+                   w.blk_heads, w.seg_off, w.tile_first);
     }
     const int64_t n = nnz + 1;
     hipLaunchKernelGGL(bwd_export, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
