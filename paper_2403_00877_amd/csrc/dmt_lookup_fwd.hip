@@ -133,9 +133,11 @@ void launch(const dmt_plan* p, const DmtDimClass& c, const int32_t* indices,
   const int32_t tiles_per_table = (int32_t)((B + bags_per_block - 1) / bags_per_block);
   const int32_t ntiles = tiles_per_table * c.num_tables;
   const int32_t tiles_per_xcd = (ntiles + 7) / 8;
-  { DmtScope sc_(p, DMT_K_LOOKUP_FWD, s); hipLaunchKernelGGL((lookup_fwd_kernel<TD, OD>), dim3(tiles_per_xcd * 8), dim3(kBlock), 0, s,
+  DmtScope scope(p, DMT_K_LOOKUP_FWD, s);
+  hipLaunchKernelGGL((lookup_fwd_kernel<TD, OD>), dim3(tiles_per_xcd * 8), dim3(kBlock), 0, s,
                      p->d_meta, p->d_class_tables + c.first, c.D, indices, offsets, B, nnz, out,
-                     log2_lpr, log2_gl, bpg, tiles_per_table, ntiles, tiles_per_xcd, long_thr, p->d_error); }
+                     log2_lpr, log2_gl, bpg, tiles_per_table, ntiles, tiles_per_xcd, long_thr,
+                     p->d_error);
 }
 
 int ilog2_ceil(int x) {
