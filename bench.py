@@ -284,9 +284,9 @@ def main():
 
 def cpu_leg(dmt, wl, w, plan, tables, states, tm_host, b0, pooled, tm_out, tm_params, tm_ws, bwd_ws,
             widths):
-    """Time the CPU oracle on a bounded sample of the workload (the first two
-    towers = 16 of the 64 tables, all 8192 samples of batch 0) and check the GPU
-    step on the same inputs against it."""
+    """Time the CPU oracle on a bounded sample of the workload (batch 0 of the id
+    pool, all towers: one step's worth of lookups) and check the GPU step on the
+    same inputs against it."""
     import torch
     import oracle
 
@@ -298,7 +298,7 @@ def cpu_leg(dmt, wl, w, plan, tables, states, tm_host, b0, pooled, tm_out, tm_pa
             raise AssertionError("%s: %d of %d outside tolerance" % (what, int(bad.sum()), ref.size))
 
     B = w.batch
-    n_tow = 2
+    n_tow = w.num_towers
     tabs = [f for f in range(w.num_tables) if w.table_to_tower[f] < n_tow]
     nt = len(tabs)
     assert tabs == list(range(nt)), "sample towers must own the leading tables"
@@ -365,8 +365,8 @@ def cpu_leg(dmt, wl, w, plan, tables, states, tm_host, b0, pooled, tm_out, tm_pa
     return dict(
         baseline=dict(value=round(B / (t_cpu / frac), 1), unit="samples/s", cores=threads,
                       kind="oracle",
-                      sample="towers 0-1 (16 of 64 tables), all 8192 samples of batch 0: lookup+TM+"
-                             "bwd took %.2f s; value = batch / (time x 64/16)" % t_cpu,
+                      sample="batch 0 of the id pool, all %d tables and %d samples (one step): lookup+TM+"
+                             "bwd took %.2f s; value = batch / time" % (nt, B, t_cpu),
                       seconds=round(t_cpu, 3)),
         parity=parity)
 
