@@ -125,6 +125,17 @@ def test_large_scaled_bf16():
     check_bwd(w)
 
 
+def test_many_small_tables_some_without_lookups():
+    """300 tables (more than one pass of the sort-block map's 256-table chunks), a few rows each,
+    Poisson(0.3) bag lengths so that many tables have no lookup at all in a batch of 3."""
+    base = wl.scaled(wl.imbalanced(), max_rows=60, batch=3, num_tables=100)
+    w = wl.dataclasses.replace(
+        base, rows=[7 + (f * 13) % 50 for f in range(300)], dims=[32] * 300,
+        table_to_tower=[f // 25 for f in range(300)], tm_out=[128] * 12, len_dist="poisson",
+        len_param=0.3, len_cap=3, zipf_alpha=None)
+    check_bwd(w)
+
+
 def test_empty_batch_is_a_no_op():
     w = wl.scaled(wl.mid(True), max_rows=100, batch=9, num_tables=8)
     dw = DeviceWorkload(w, with_state=True)
