@@ -28,7 +28,7 @@ namespace {
 
 constexpr int kBlock = 256;
 #ifndef DMT_SORT_ITEMS
-#define DMT_SORT_ITEMS 16
+#define DMT_SORT_ITEMS 8
 #endif
 #ifndef DMT_RADIX_BITS
 #define DMT_RADIX_BITS 8
