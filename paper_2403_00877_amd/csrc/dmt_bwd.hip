@@ -100,6 +100,7 @@ __device__ void build_sort_map(const int64_t* __restrict__ offsets, uint32_t B, 
                                uint32_t* __restrict__ seg_begin, uint32_t* __restrict__ seg_blk,
                                uint32_t* __restrict__ blk_table) {
   __shared__ uint32_t sm[kBlock / 64];
+  __shared__ uint32_t s_first[kBlock], s_nb[kBlock];
   uint32_t rec_run = 0, blk_run = 0;
   for (int f0 = 0; f0 < F; f0 += kBlock) {
     const int f = f0 + (int)threadIdx.x;
@@ -121,8 +122,14 @@ __device__ void build_sort_map(const int64_t* __restrict__ offsets, uint32_t B, 
     if (f < F) {
       seg_begin[f] = begin;
       seg_blk[f] = first;
-      for (uint32_t j = 0; j < nb; ++j) blk_table[first + j] = (uint32_t)f;
     }
+    // the tables' block lists are written a wave per table, a block per lane
+    s_first[threadIdx.x] = first;
+    s_nb[threadIdx.x] = f < F ? nb : 0u;
+    __syncthreads();
+    for (int q = threadIdx.x >> 6; q < kBlock && f0 + q < F; q += kBlock / 64)
+      for (uint32_t j = threadIdx.x & 63; j < s_nb[q]; j += 64) blk_table[s_first[q] + j] = (uint32_t)(f0 + q);
+    __syncthreads();
   }
   if (threadIdx.x == 0) {
     seg_begin[F] = rec_run > (uint32_t)nnz ? (uint32_t)nnz : rec_run;
