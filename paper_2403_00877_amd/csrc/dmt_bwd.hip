@@ -530,6 +530,9 @@ constexpr int kQueueSlots = DMT_QS;
 // finished runs parked before their rows are updated: per lane group, and per wave of the
 // wave-per-tile kernel (whose slots are half as large)
 constexpr int kQueueSlotsWave = 8;
+constexpr int kWaveUnroll = 6;                   // gradient rows the wave-per-tile kernel requests at once
+static_assert(kReduceUnroll <= kQueueSlots && kWaveUnroll <= kQueueSlotsWave,
+              "a step of the walk parks at most as many runs as the queue holds");
 
 // Each group of GL = 2^LG lanes walks one tile of kReduceTile sorted records,
 // summing the bags' gradient slices run by run (float32, record order).  Runs
@@ -977,10 +980,10 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update_wave(
     carry = __builtin_amdgcn_readlane(key_l, cnt - 1);
     has_prev = true;
 
-    for (int i0 = 0; i0 < cnt; i0 += kReduceUnroll) {
-      Vec g[kReduceUnroll];
+    for (int i0 = 0; i0 < cnt; i0 += kWaveUnroll) {
+      Vec g[kWaveUnroll];
 #pragma unroll
-      for (int u = 0; u < kReduceUnroll; ++u) {
+      for (int u = 0; u < kWaveUnroll; ++u) {
         lv_zero<EPL>(g[u]);
         if (i0 + u < cnt) {
           const uint32_t go = __builtin_amdgcn_readlane(goff_l, i0 + u);
@@ -990,7 +993,7 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update_wave(
         }
       }
 #pragma unroll
-      for (int u = 0; u < kReduceUnroll; ++u) {
+      for (int u = 0; u < kWaveUnroll; ++u) {
         const int i = i0 + u;
         if (i < cnt) {
           if ((hm >> i) & 1) {                     // a run starts at this record
@@ -1011,7 +1014,7 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update_wave(
           lv_add<EPL>(acc, g[u]);
         }
       }
-      if (qn > kQueueSlotsWave - kReduceUnroll) drain();
+      if (qn > kQueueSlotsWave - kWaveUnroll) drain();
     }
   }
   if (run_open) {
