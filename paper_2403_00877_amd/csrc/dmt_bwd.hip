@@ -1040,7 +1040,7 @@ __device__ __forceinline__ uint32_t table_of(const int64_t* __restrict__ row_bas
 // starts adds the pieces in tile order and applies the update.
 template <int TD>
 __global__ __launch_bounds__(kBlock) void bwd_fixup_update(
-    const DmtTableMeta* __restrict__ meta, const int64_t* __restrict__ row_base, int F,
+    const DmtTableMeta* __restrict__ meta, uint32_t B, uint32_t nbags,
     const uint64_t* __restrict__ pk, int64_t nnz, uint32_t total_rows,
     const float* __restrict__ partials, int Dmax, int log2_gl, int64_t ntiles, float lr, float eps) {
   const int GL = 1 << log2_gl;
@@ -1048,8 +1048,15 @@ __global__ __launch_bounds__(kBlock) void bwd_fixup_update(
   if (t0 >= ntiles - 1) return;
   const int gl = threadIdx.x & (GL - 1);
   const int64_t p0 = t0 * kReduceTile, p1 = p0 + kReduceTile;    // p1 < nnz here
-  const uint32_t k_last = (uint32_t)(pk[p1 - 1] >> 32);
+  const uint64_t r_last = pk[p1 - 1];
+  const uint32_t k_last = (uint32_t)(r_last >> 32);
   if (k_last != (uint32_t)(pk[p1] >> 32) || k_last >= total_rows) return;
+  // the run's table follows from the bag of any of its records (no search through the row bases)
+  const uint32_t bag = (uint32_t)r_last;
+  if (bag >= nbags) return;
+  const uint32_t f = bag / B;
+  const int64_t row = (int64_t)k_last - meta[f].row_base;
+  if (row < 0 || row >= meta[f].rows) return;      // key and bag disagree: not a row to touch
   const uint32_t k_first = (uint32_t)(pk[p0] >> 32);
   if (k_first == k_last && p0 > 0 && (uint32_t)(pk[p0 - 1] >> 32) == k_first) return;
   // last tile the run reaches: the largest t with the run's key at the tile's first record
@@ -1078,8 +1085,7 @@ __global__ __launch_bounds__(kBlock) void bwd_fixup_update(
       acc.x += g[q].x; acc.y += g[q].y; acc.z += g[q].z; acc.w += g[q].w;
     }
   }
-  const uint32_t f = table_of(row_base, F, k_last);
-  apply_row_update<TD, false>(meta, f, k_last - (uint32_t)row_base[f], acc, gl, GL, lr, eps);
+  apply_row_update<TD, false>(meta, f, (uint32_t)row, acc, gl, GL, lr, eps);
 }
 
 // ------------------------------------------------------------- parity exports
@@ -1180,7 +1186,7 @@ void launch_reduce_and_fixup(const ReduceCall& c) {
   }
   const int64_t blocks = (c.w->ntiles + (kBlock >> log2_gl) - 1) / (kBlock >> log2_gl);
   timed_launch(c.plan, DMT_K_BWD_FIXUP, c.s, bwd_fixup_update<TD>, blocks, kBlock, c.plan->d_meta,
-               c.plan->d_row_base, c.plan->F, c.sorted, c.nnz, c.total_rows, c.w->partials, max_dim,
+               (uint32_t)c.B, c.nbags, c.sorted, c.nnz, c.total_rows, c.w->partials, max_dim,
                log2_gl, c.w->ntiles, c.lr, c.eps);
 }
 
