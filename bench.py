@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--batches", type=int, default=8, help="pool of pre-generated id batches")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--workload", default="backward")
+    ap.add_argument("--no-tm-bwd", action="store_true",
+                    help="skip the separate timing of the Tower Module backward")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run dmt_calibration_copy on 1 GiB three times (for rocprofv3 --pmc runs)")
     return ap.parse_args()
@@ -185,6 +187,11 @@ def main():
     full = dmt.dmt_profile_read(plan)
     dmt.dmt_profile_enable(plan, 0)
 
+    # ---- Tower Module backward, timed on its own after the step (it is not part of `value`)
+    tm_bwd = None
+    if not args.no_tm_bwd:
+        tm_bwd = time_tm_bwd(torch, dmt, wl, w, plan, tm_params, pooled, tm_out, B, args.steps)
+
     if args.calibrate:
         a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         c = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
@@ -277,9 +284,51 @@ def main():
         "other_kernels": others,
         "kernel_breakdown": kernels,
         "parity_vs_oracle_on_sample": cpu["parity"] if cpu else None,
+        "tm_backward": tm_bwd,
     }
     print(json.dumps(out), flush=True)
     return 0
+
+
+def time_tm_bwd(torch, dmt, wl, w, plan, tm_params, pooled, tm_out, B, steps):
+    """dmt_tower_module_bwd on the step's pooled / tm_out tensors and a N(0,1) output gradient:
+    ms per call, its kernels' shares, and the MFMA rate over the contractions' FLOPs (each
+    projection twice: data and weight gradient; each cross layer three times: recomputed
+    forward, data and weight gradient)."""
+    kin, tw = w.tm_in_dims(), w.tower_widths()
+    nl = w.tm_cross_layers if w.tm_kind == wl.TM_CROSS_LINEAR else 0
+    f32 = lambda *shape: torch.empty(shape, dtype=torch.float32, device="cuda")
+    grads = [dict(dw_proj=f32(o, k), db_proj=f32(o), dw_cross=[f32(d, d) for _ in range(nl)],
+                  db_cross=[f32(d) for _ in range(nl)]) for o, k, d in zip(w.tm_out, kin, tw)]
+    arr = dmt.make_tm_grads(grads)
+    ws = torch.empty(dmt.dmt_tm_bwd_workspace_bytes(plan, tm_params, B), dtype=torch.uint8, device="cuda")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7 + w.seed)
+    dy = torch.randn(B * sum(w.tm_out), generator=g, device="cuda", dtype=torch.float32)
+    dx = torch.empty(B * sum(tw), dtype=torch.float32, device="cuda")
+    run = lambda: dmt.dmt_tower_module_bwd(plan, tm_params, pooled, tm_out, B, dy, dx, arr, ws)
+    for _ in range(3):
+        run()
+    torch.cuda.synchronize()
+    n = max(3, min(steps, 20))
+    t0 = time.perf_counter()
+    for _ in range(n):
+        run()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / n
+    dmt.dmt_profile_enable(plan, (1 << dmt.DMT_K_COUNT) - 1)
+    for _ in range(n):
+        run()
+    prof = dmt.dmt_profile_read(plan)
+    dmt.dmt_profile_enable(plan, 0)
+    flops = sum(2.0 * B * (2 * o * k + 3 * nl * d * d) for o, k, d in zip(w.tm_out, kin, tw))
+    gemm_ms = prof.get("tm_bwd_gemm", (0.0, 0))[0] / n
+    return dict(ms_per_call=round(ms, 4), workspace_GB=round(ws.numel() / 1e9, 3),
+                kernels={k: dict(ms_per_call=round(v[0] / n, 4), launches_per_call=v[1] // n)
+                         for k, v in sorted(prof.items())},
+                algorithmic_flops=int(flops),
+                gemm_TFLOPs=round(flops / (gemm_ms * 1e-3) / 1e12, 1) if gemm_ms > 0 else None,
+                mfma_peak_TFLOPs=MFMA_PEAK_TFLOPS_16BIT)
 
 
 def cpu_leg(dmt, wl, w, plan, tables, states, tm_host, b0, pooled, tm_out, tm_params, tm_ws, bwd_ws,

@@ -180,6 +180,56 @@ dmt_status dmt_tower_module_fwd(const dmt_plan* plan, const dmt_tm_params* per_t
  * pointer may be NULL.  All dev.  A lookup whose id is outside its table sorts
  * behind its table's valid lookups, shows as key -1 in sorted_keys, starts no run
  * (it lies inside the extent of the run before it) and is not counted. */
+/*
+ * Parameter gradients of one tower's Tower Module, all dev float32, row-major,
+ * shaped like the parameters themselves (dw_proj [O_t][K_t] with K_t the row
+ * length of w_proj; dw_cross[l] [W_t][W_t]; the db_* vectors).  Every array is
+ * overwritten, not accumulated into.  Caller-owned.
+ */
+typedef struct {
+  float* dw_proj;
+  float* db_proj;
+  float* dw_cross[DMT_MAX_CROSS_LAYERS];
+  float* db_cross[DMT_MAX_CROSS_LAYERS];
+} dmt_tm_grads;
+
+/* Bytes of scratch dmt_tower_module_bwd needs for these towers at batch B.  Host-only. */
+size_t dmt_tm_bwd_workspace_bytes(const dmt_plan* plan, const dmt_tm_params* per_tower, int64_t B);
+
+/*
+ * Tower Module backward: the chain rule through the forms of paper Sec. 3.2 /
+ * Sec. 4 (Listings 1 and 2), from dL/d(tm_out) to dL/d(pooled) and to the
+ * gradients of every weight and bias.  grad_pooled is exactly what
+ * dmt_tower_lookup_bwd_update consumes, so the two calls chain without a copy.
+ *   linear(+ReLU)  dpre = grad_tm_out (where tm_out > 0 under ReLU);
+ *                  grad_pooled = dpre W, dW = dpre^T x, db = sum_b dpre
+ *   dot + linear   dz = dy W over z = [dot terms | x]; dW = dy^T z; the flat part
+ *                  of dz passes to x and each term (i, j) adds dz_ij x_j to dx_i
+ *                  and dz_ij x_i to dx_j
+ *   cross + linear layers taken from the last to the first with
+ *                  du_l = dx_{l+1} * x0, dx0 += dx_{l+1} * u_l, dW_l = du_l^T x_l,
+ *                  db_l = sum_b du_l, dx_l = du_l W_l + dx_{l+1};
+ *                  grad_pooled = dx_0 + dx0
+ * The forward's intermediates (dot terms, u_l, x_l) are recomputed, not kept.
+ * For DMT_BF16 / DMT_F16 every contraction runs on MFMA with float32
+ * accumulation over operands rounded once to that 16-bit type (dpre, du_l, u_l,
+ * x_l); gradients between layers and all outputs stay float32.  Bias gradients
+ * are fixed-order sums of those rounded operands, so results repeat bit for bit.
+ * DMT_F32 runs in plain float32 arithmetic.
+ *   per_tower    host [num_towers], as passed to the forward
+ *   pooled       dev, the forward's input;  tm_out dev, the forward's output
+ *                (read only by LINEAR_RELU towers, may be NULL when there are none)
+ *   grad_tm_out  dev float32, laid out like tm_out
+ *   grad_pooled  dev float32 out, tower-major like pooled, 16-byte aligned
+ *   grads        host [num_towers]; entries a tower's kind does not have are ignored
+ *   workspace    dev, at least dmt_tm_bwd_workspace_bytes, 256-byte aligned
+ */
+dmt_status dmt_tower_module_bwd(const dmt_plan* plan, const dmt_tm_params* per_tower,
+                                const void* pooled, const void* tm_out, int64_t B,
+                                const float* grad_tm_out, dmt_dtype dtype, float* grad_pooled,
+                                const dmt_tm_grads* grads, void* workspace,
+                                size_t workspace_bytes, void* stream);
+
 typedef struct {
   int64_t* sorted_keys;  /* [nnz]  (table << 32 | row), ascending, stable           */
   int32_t* sorted_bag;   /* [nnz]  bag id f*B + b of each sorted lookup              */
@@ -237,7 +287,9 @@ typedef enum {
   DMT_K_BWD_HEADS = 8,         /* run heads -> segment offsets                */
   DMT_K_BWD_REDUCE_UPDATE = 9, /* segment reduce + rowwise Adagrad            */
   DMT_K_BWD_FIXUP = 10,        /* rows whose run spans reduce tiles           */
-  DMT_K_COUNT = 11
+  DMT_K_TM_BWD_GEMM = 11,      /* Tower Module backward: grouped contractions */
+  DMT_K_TM_BWD_AUX = 12,       /* ... its elementwise / transpose / sum steps */
+  DMT_K_COUNT = 13
 } dmt_kernel_id;
 
 const char* dmt_kernel_name(int32_t kernel_id);

@@ -35,6 +35,12 @@ class dmt_tm_params(ctypes.Structure):
                 ("b_cross", ctypes.c_void_p * DMT_MAX_CROSS_LAYERS)]
 
 
+class dmt_tm_grads(ctypes.Structure):
+    _fields_ = [("dw_proj", ctypes.c_void_p), ("db_proj", ctypes.c_void_p),
+                ("dw_cross", ctypes.c_void_p * DMT_MAX_CROSS_LAYERS),
+                ("db_cross", ctypes.c_void_p * DMT_MAX_CROSS_LAYERS)]
+
+
 class dmt_bwd_debug(ctypes.Structure):
     _fields_ = [("sorted_keys", ctypes.c_void_p), ("sorted_bag", ctypes.c_void_p),
                 ("unique_keys", ctypes.c_void_p), ("seg_off", ctypes.c_void_p),
@@ -64,6 +70,9 @@ def _load() -> ctypes.CDLL:
     lib.dmt_tm_workspace_bytes.argtypes = [vp, vp, i64]
     lib.dmt_tm_workspace_bytes.restype = sz
     lib.dmt_tower_module_fwd.argtypes = [vp, vp, vp, i64, vp, ctypes.c_int, vp, sz, vp]
+    lib.dmt_tm_bwd_workspace_bytes.argtypes = [vp, vp, i64]
+    lib.dmt_tm_bwd_workspace_bytes.restype = sz
+    lib.dmt_tower_module_bwd.argtypes = [vp, vp, vp, vp, i64, vp, ctypes.c_int, vp, vp, vp, sz, vp]
     lib.dmt_bwd_workspace_bytes.argtypes = [vp, i64, i64]
     lib.dmt_bwd_workspace_bytes.restype = sz
     lib.dmt_tower_lookup_bwd_update.argtypes = [vp, vp, vp, i64, i64, vp, f32, f32, vp, sz, vp, vp]
@@ -80,11 +89,12 @@ _lib = _load()
 
 EXPORTS = ["dmt_status_str", "dmt_plan_create", "dmt_plan_destroy", "dmt_plan_layout",
            "dmt_plan_bind", "dmt_tower_lookup_fwd", "dmt_tm_workspace_bytes",
-           "dmt_tower_module_fwd", "dmt_bwd_workspace_bytes", "dmt_tower_lookup_bwd_update",
+           "dmt_tower_module_fwd", "dmt_tm_bwd_workspace_bytes", "dmt_tower_module_bwd",
+           "dmt_bwd_workspace_bytes", "dmt_tower_lookup_bwd_update",
            "dmt_last_device_error", "dmt_kernel_name", "dmt_profile_enable", "dmt_profile_read",
            "dmt_calibration_copy"]
 
-DMT_K_COUNT = 11
+DMT_K_COUNT = 13
 
 
 def library_path() -> str:
@@ -196,6 +206,34 @@ def dmt_tower_module_fwd(plan: dmt_plan, tm_params, pooled: torch.Tensor, B: int
         plan.handle, tm_params, _ptr(pooled), B, _ptr(tm_out), DTYPE_CODE[tm_out.dtype],
         _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
         _stream(stream)))
+
+
+def make_tm_grads(per_tower: Sequence[dict]):
+    """per_tower: dicts with float32 tensors dw_proj, db_proj and optionally lists
+    dw_cross / db_cross.  Returns a ctypes array."""
+    arr = (dmt_tm_grads * len(per_tower))()
+    for a, g in zip(arr, per_tower):
+        a.dw_proj = g["dw_proj"].data_ptr()
+        a.db_proj = g["db_proj"].data_ptr()
+        for l, (w, b) in enumerate(zip(g.get("dw_cross") or [], g.get("db_cross") or [])):
+            a.dw_cross[l] = w.data_ptr()
+            a.db_cross[l] = b.data_ptr()
+    return arr
+
+
+def dmt_tm_bwd_workspace_bytes(plan: dmt_plan, tm_params, B: int) -> int:
+    return int(_lib.dmt_tm_bwd_workspace_bytes(plan.handle, tm_params, B))
+
+
+def dmt_tower_module_bwd(plan: dmt_plan, tm_params, pooled: torch.Tensor,
+                         tm_out: Optional[torch.Tensor], B: int, grad_tm_out: torch.Tensor,
+                         grad_pooled: torch.Tensor, tm_grads, workspace: torch.Tensor,
+                         stream=None) -> None:
+    assert grad_tm_out.dtype == torch.float32 and grad_pooled.dtype == torch.float32
+    _check("dmt_tower_module_bwd", _lib.dmt_tower_module_bwd(
+        plan.handle, tm_params, _ptr(pooled), _ptr(tm_out), B, _ptr(grad_tm_out),
+        DTYPE_CODE[pooled.dtype], _ptr(grad_pooled), tm_grads, _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def dmt_bwd_workspace_bytes(plan: dmt_plan, B: int, nnz: int) -> int:

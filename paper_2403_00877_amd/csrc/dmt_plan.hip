@@ -192,7 +192,8 @@ extern "C" dmt_status dmt_last_device_error(const dmt_plan* plan, void* stream,
 extern "C" const char* dmt_kernel_name(int32_t id) {
   static const char* names[DMT_K_COUNT] = {
       "lookup_fwd", "tm_dots", "tm_pack_w", "tm_gemm", "bwd_build_keys", "radix_hist",
-      "radix_scan", "radix_scatter", "bwd_heads", "bwd_reduce_update", "bwd_fixup_update"};
+      "radix_scan", "radix_scatter", "bwd_heads", "bwd_reduce_update", "bwd_fixup_update",
+      "tm_bwd_gemm", "tm_bwd_aux"};
   return (id >= 0 && id < DMT_K_COUNT) ? names[id] : "?";
 }
 

@@ -1,0 +1,202 @@
+"""GPU parity of dmt_tower_module_bwd against the CPU oracle (oracle/tm_bwd.py).
+
+Both sides start from the same encoded values: the pooled block and the weights rounded to the
+compute dtype, and a float32 N(0,1) gradient of the module outputs.  The oracle differentiates
+in float64; the library rounds its contraction operands once to the compute dtype, which the
+tolerance (relative to each output's magnitude plus the array's rms) covers.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import tm_bwd
+import workloads as wl
+from harness import RTOL, DeviceWorkload, TowerModules, assert_close, to_device, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def run_bwd(dw, tm, x_dev, y_dev, dy_dev):
+    """Calls the library; returns (grad_pooled flat float64, per-tower dicts of float64 grads)."""
+    w = dw.w
+    dmt = dw.dmt
+    nan = float("nan")
+    widths = w.tower_widths()
+    grads = []
+    for t, kin in enumerate(w.tm_in_dims()):
+        L = w.tm_cross_layers if w.tm_kind == wl.TM_CROSS_LINEAR else 0
+        f = lambda *shape: torch.full(shape, nan, dtype=torch.float32, device="cuda")
+        grads.append(dict(dw_proj=f(w.tm_out[t], kin), db_proj=f(w.tm_out[t]),
+                          dw_cross=[f(widths[t], widths[t]) for _ in range(L)],
+                          db_cross=[f(widths[t]) for _ in range(L)]))
+    arr = dmt.make_tm_grads(grads)
+    nbytes = dmt.dmt_tm_bwd_workspace_bytes(dw.plan, tm.params, w.batch)
+    assert nbytes > 0
+    ws = torch.empty(nbytes // 8 + 32, dtype=torch.int64, device="cuda")
+    dx = torch.full((w.batch * sum(widths),), nan, dtype=torch.float32, device="cuda")
+    dmt.dmt_tower_module_bwd(dw.plan, tm.params, x_dev, y_dev, w.batch, dy_dev, dx, arr, ws)
+    torch.cuda.synchronize()
+    host = [dict(dw_proj=to_f64(g["dw_proj"]), db_proj=to_f64(g["db_proj"]),
+                 dw_cross=[to_f64(a) for a in g["dw_cross"]],
+                 db_cross=[to_f64(a) for a in g["db_cross"]]) for g in grads]
+    return to_f64(dx), host
+
+
+def assert_grad_close(got, ref, rtol, what):
+    """|got - ref| <= rtol (|ref| + scale) elementwise, and for the 16-bit types also
+    rms(got - ref) <= rtol / 4 * rms(ref).
+
+    Every product of a 16-bit contraction carries an independent rounding error of up to 2^-9
+    (bf16) per operand, so an output's error is a fraction of a percent of the magnitude of ITS
+    sum's terms.  For a matrix that is a sum of outer products (dW = dz^T x; dx = dz W) that
+    magnitude is the product of a row factor and a column factor, estimated here from the
+    reference as rowrms_i * colrms_j / rms; pooled sums of Zipf-length bags are heavy-tailed,
+    so single rows and columns sit far above the array's rms.  The largest error among millions
+    of outputs lies five sigma out, which the elementwise bound leaves room for; the rms bound
+    is the sharp one (a dropped term or a wrong operand moves it to order one)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    if ref.size == 0:
+        return
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    scale = rms
+    if ref.ndim == 2 and rms > 0:
+        scale = np.sqrt(np.mean(ref * ref, axis=1, keepdims=True)) * \
+            np.sqrt(np.mean(ref * ref, axis=0, keepdims=True)) / rms
+        scale = np.maximum(scale, rms)
+    err = np.abs(got - ref)
+    tol = rtol * (np.abs(ref) + scale)
+    bad = err > tol
+    if bad.any():
+        i = int(np.argmax(err - tol))
+        raise AssertionError("%s: %d of %d outside tolerance; worst at flat %d: got %r ref %r (rms %g)"
+                             % (what, int(bad.sum()), ref.size, i, got.flat[i], ref.flat[i], rms))
+    if rtol >= 1e-2:
+        e = float(np.sqrt(np.mean(err * err)))
+        assert e <= rtol / 4 * rms, "%s: rms error %g against rms %g" % (what, e, rms)
+
+
+def check_tm_bwd(w, rtol=None):
+    dw = DeviceWorkload(w)
+    tm = TowerModules(dw)
+    idx, off = wl.lookup_batch(w)
+    pooled = oracle.lookup_towered(dw.host_tables, w.table_dtype, w.dims, w.table_to_tower, idx, off, w.batch)
+    enc = [oracle.round_to(p, tm.dtype) for p in pooled]
+    x_dev = torch.cat([to_device(e, tm.dtype).reshape(-1) for e in enc])
+    x64 = [wl.decode(e, tm.dtype) for e in enc]
+    dy_all = wl.grad_tm_out(w)
+    dys, o = [], 0
+    for t in range(w.num_towers):
+        dys.append(dy_all[o:o + w.batch * w.tm_out[t]].reshape(w.batch, w.tm_out[t]).copy())
+        o += w.batch * w.tm_out[t]
+    if w.tm_kind == wl.TM_LINEAR_RELU:
+        # an output whose pre-activation is a rounding error away from zero may be on in one
+        # arithmetic and off in the other: such outputs receive no gradient in this test
+        for t in range(w.num_towers):
+            pre = oracle.tm_linear(x64[t], tm.dec[t]["w_proj"], tm.dec[t]["b_proj"])
+            dys[t][np.abs(pre) < 1e-3 * np.sqrt(np.mean(pre * pre))] = 0.0
+    dy_dev = torch.from_numpy(np.concatenate([d.reshape(-1) for d in dys])).cuda()
+    y_dev = tm.run(x_dev) if w.tm_kind == wl.TM_LINEAR_RELU else None
+    got_dx, got = run_bwd(dw, tm, x_dev, y_dev, dy_dev)
+    rtol = rtol or RTOL[tm.dtype]
+    tables = w.tower_tables()
+    for t, gdx in enumerate(dw.split_towers(got_dx, w.tower_widths())):
+        d = tm.dec[t]
+        what = "%s TM backward tower %d " % (w.name, t)
+        if w.tm_kind in (wl.TM_LINEAR, wl.TM_LINEAR_RELU):
+            dx, dW, db = tm_bwd.tm_linear_bwd(x64[t], d["w_proj"], d["b_proj"], dys[t],
+                                              relu=w.tm_kind == wl.TM_LINEAR_RELU)
+        elif w.tm_kind == wl.TM_DOT_LINEAR:
+            dx, dW, db = tm_bwd.tm_dot_linear_bwd(x64[t], len(tables[t]), d["w_proj"], d["b_proj"], dys[t])
+        else:
+            dx, dWc, dbc, dW, db = tm_bwd.tm_cross_linear_bwd(x64[t], d["w_cross"], d["b_cross"],
+                                                              d["w_proj"], d["b_proj"], dys[t])
+            for l in range(len(dWc)):
+                assert_grad_close(got[t]["dw_cross"][l], dWc[l], rtol, what + "dW_cross[%d]" % l)
+                assert_grad_close(got[t]["db_cross"][l], dbc[l], rtol, what + "db_cross[%d]" % l)
+        assert_grad_close(gdx, dx, rtol, what + "grad_pooled")
+        assert_grad_close(got[t]["dw_proj"], dW, rtol, what + "dW_proj")
+        assert_grad_close(got[t]["db_proj"], db, rtol, what + "db_proj")
+
+
+def test_tiny_linear_relu_f32():
+    check_tm_bwd(wl.tiny())
+
+
+def test_linear_bf16_and_f16_ragged():
+    # towers of unequal width, batch 777 (not a multiple of 8: padded transposed operands),
+    # output width 100 (padded gradient operand, partial column tiles)
+    w = wl.scaled(wl.imbalanced(), max_rows=2000, batch=777, num_tables=26)
+    w.tm_out = [100] * w.num_towers
+    for dt in ("f16", "bf16"):
+        w.tm_dtype = dt
+        w.pooled_dtype = dt
+        check_tm_bwd(w)
+
+
+def test_linear_relu_bf16_wide_output():
+    w = wl.scaled(wl.imbalanced(), max_rows=500, batch=333, num_tables=9)
+    w.tm_kind = wl.TM_LINEAR_RELU
+    w.tm_out = [300] * w.num_towers
+    check_tm_bwd(w)
+
+
+def test_mid_scaled_dot_linear_bf16():
+    # 2 towers x 8 features x 128: 28 dots (padded to 32) | 1024 -> 256; batch 301
+    check_tm_bwd(wl.scaled(wl.mid(), max_rows=5000, batch=301, num_tables=16))
+
+
+def test_dot_linear_odd_feature_count_f32_and_f16():
+    w = wl.scaled(wl.mid(), max_rows=500, batch=50, num_tables=6)
+    w.table_to_tower = [0, 0, 0, 1, 1, 1]
+    w.tm_out = [40, 24]
+    for dt in ("f32", "f16"):
+        w.tm_dtype = dt
+        w.pooled_dtype = dt
+        check_tm_bwd(w)
+
+
+def test_large_scaled_cross_linear_bf16():
+    # 2 towers of 16 x 128 = 2048 wide: two 2048 x 2048 cross layers, then 2048 -> 512
+    w = wl.scaled(wl.large(), max_rows=3000, batch=200)
+    sel = [f for f in range(256) if w.table_to_tower[f] in (0, 1)]
+    w.rows = [w.rows[f] for f in sel]; w.dims = [128] * 32
+    w.table_to_tower = [wl.large().table_to_tower[f] for f in sel]
+    w.tm_out = [512, 512]
+    check_tm_bwd(w, rtol=4e-2)
+
+
+def test_cross_three_layers_narrow_tower_f32_and_bf16():
+    w = wl.scaled(wl.large(), max_rows=300, batch=150, num_tables=3)
+    w.table_to_tower = [0, 0, 0]
+    w.tm_out = [96]
+    w.tm_cross_layers = 3
+    for dt, rtol in (("f32", 1e-4), ("bf16", 4e-2)):
+        w.tm_dtype = dt
+        w.pooled_dtype = dt
+        check_tm_bwd(w, rtol)
+
+
+def test_rejects_bad_arguments():
+    w = wl.tiny()
+    dw = DeviceWorkload(w)
+    tm = TowerModules(dw)
+    dmt = dw.dmt
+    x = torch.zeros(w.batch * sum(w.tower_widths()), dtype=torch.float32, device="cuda")
+    dy = torch.zeros(w.batch * sum(w.tm_out), dtype=torch.float32, device="cuda")
+    dx = torch.zeros_like(x)
+    g = [dict(dw_proj=torch.zeros(o, k, device="cuda"), db_proj=torch.zeros(o, device="cuda"))
+         for o, k in zip(w.tm_out, w.tm_in_dims())]
+    arr = dmt.make_tm_grads(g)
+    small = torch.empty(32, dtype=torch.int64, device="cuda")
+    with pytest.raises(dmt.DmtError) as e:       # workspace too small
+        dmt.dmt_tower_module_bwd(dw.plan, tm.params, x, x, w.batch, dy, dx, arr, small)
+    assert e.value.code == dmt.binding.DMT_ENOMEM
+    big = torch.empty(dmt.dmt_tm_bwd_workspace_bytes(dw.plan, tm.params, w.batch) // 8 + 32,
+                      dtype=torch.int64, device="cuda")
+    with pytest.raises(dmt.DmtError) as e:       # a ReLU tower needs the forward's output
+        dmt.dmt_tower_module_bwd(dw.plan, tm.params, x, None, w.batch, dy, dx, arr, big)
+    assert e.value.code == dmt.binding.DMT_EINVAL
+    torch.cuda.synchronize()

@@ -21,7 +21,7 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 # stream ids for numpy.random.default_rng([seed, stream, table])
-_S_ROWS, _S_DIMS, _S_LEN, _S_RANK, _S_PERM, _S_TABLE, _S_GRAD, _S_TM = range(8)
+_S_ROWS, _S_DIMS, _S_LEN, _S_RANK, _S_PERM, _S_TABLE, _S_GRAD, _S_TM, _S_GRAD_TM = range(9)
 
 F32, F16, BF16 = "f32", "f16", "bf16"
 ELT_BYTES = {F32: 4, F16: 2, BF16: 2}
@@ -336,6 +336,13 @@ def grad_pooled(w: Workload, batch_id: int = 0) -> np.ndarray:
     base, _, _ = pooled_layout(w)
     rng = np.random.default_rng([w.seed, _S_GRAD, 0, batch_id])
     return rng.standard_normal(base[-1], dtype=np.float32)
+
+
+def grad_tm_out(w: Workload, batch_id: int = 0) -> np.ndarray:
+    """N(0,1) float32 gradient w.r.t. the Tower Modules' outputs, towers one after
+    another, each [B][O_t] row-major, flat."""
+    rng = np.random.default_rng([w.seed, _S_GRAD_TM, 0, batch_id])
+    return rng.standard_normal(w.batch * sum(w.tm_out), dtype=np.float32)
 
 
 def tm_weights(w: Workload):
