@@ -16,25 +16,55 @@
 
 namespace {
 
-constexpr int kTile = 32;
+constexpr int kTile = 32;        // scalar transposes (float32 path, gradient preparation)
+constexpr int kVTile = 64;       // 16-bit transpose: 64 x 64 tiles, 8-byte accesses
+constexpr int kMaxItems = 32;
 
 template <int DT> struct EltOf { using type = uint16_t; };
 template <> struct EltOf<DMT_F32> { using type = float; };
 
+// One tower's share of a grouped launch of the small kernels below: block id ->
+// (item, block within the item), like the grouped GEMM.  The meaning of the fields is
+// each kernel's own.
+struct TmbItem {
+  const void* a;
+  const void* b;
+  const void* c;
+  void* o0;
+  void* o1;
+  int64_t n0, n1, n2;
+  int32_t i0, i1, i2, i3, i4;
+  int32_t nbx;               // blocks along the first dimension (2-D kernels) or blocks of the item
+};
+
+struct TmbLaunch {
+  int32_t n;
+  int32_t block_start[kMaxItems + 1];
+  TmbItem it[kMaxItems];
+};
+
+__device__ __forceinline__ int tmb_find(const TmbLaunch& L) {
+  int i = 0;
+  while (i + 1 < L.n && (int)blockIdx.x >= L.block_start[i + 1]) ++i;
+  return i;
+}
+
 // ---------------------------------------------------------------- small kernels
 
 // dz[b][o] = dy[b][o] (zero where ReLU was off: y[b][o] <= 0), rounded to DT, with
-// zero columns O .. Op-1; dzT[o][b] the same values transposed, zero for b in
-// [B, Bp).  Block = one 32 x 32 tile; grid.x over the batch, grid.y over outputs.
+// zero columns O .. Op-1; dzT[o][b] the same values transposed, zero for b in [B, Bp).
+// a = dy, b = y, o0 = dz, o1 = dzT, n0 = B, n1 = Bp, i0 = O, i1 = Op, i2 = relu.
 template <int DT>
-__global__ __launch_bounds__(kBlock) void tmb_prep_dy(const float* __restrict__ dy,
-                                                      const void* __restrict__ y, int relu,
-                                                      int64_t B, int O, int Op, int64_t Bp,
-                                                      void* __restrict__ dz,
-                                                      void* __restrict__ dzT) {
+__global__ __launch_bounds__(kBlock) void tmb_prep_dy(const TmbLaunch L) {
   __shared__ float tile[kTile][kTile + 1];
-  const int64_t b0 = (int64_t)blockIdx.x * kTile;
-  const int o0 = blockIdx.y * kTile;
+  const int gi = tmb_find(L);
+  const TmbItem& G = L.it[gi];
+  const int lb = blockIdx.x - L.block_start[gi];
+  const float* __restrict__ dy = (const float*)G.a;
+  const int64_t B = G.n0, Bp = G.n1;
+  const int O = G.i0, Op = G.i1, relu = G.i2;
+  const int64_t b0 = (int64_t)(lb % G.nbx) * kTile;
+  const int o0 = (lb / G.nbx) * kTile;
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
   for (int r = ty; r < kTile; r += kBlock / kTile) {
     const int64_t b = b0 + r;
@@ -42,28 +72,34 @@ __global__ __launch_bounds__(kBlock) void tmb_prep_dy(const float* __restrict__ 
     float v = 0.f;
     if (b < B && o < O) {
       v = dy[b * O + o];
-      if (relu && !(load_elt<DT>(y, b * O + o) > 0.f)) v = 0.f;
+      if (relu && !(load_elt<DT>(G.b, b * O + o) > 0.f)) v = 0.f;
     }
-    if (b < B && o < Op) store_elt<DT>(dz, b * Op + o, v);
+    if (b < B && o < Op) store_elt<DT>(G.o0, b * Op + o, v);
     tile[r][tx] = v;
   }
   __syncthreads();
   for (int r = ty; r < kTile; r += kBlock / kTile) {
     const int o = o0 + r;
     const int64_t b = b0 + tx;
-    if (o < O && b < Bp) store_elt<DT>(dzT, (int64_t)o * Bp + b, tile[tx][r]);
+    if (o < O && b < Bp) store_elt<DT>(G.o1, (int64_t)o * Bp + b, tile[tx][r]);
   }
 }
 
 // dst[c][r] = src[r][c] for r < R, 0 for R <= r < ldd; c < C.  src rows are lds
-// elements apart, dst rows ldd.  grid.x over r, grid.y over c.
+// elements apart, dst rows ldd.  a = src, o0 = dst, n0 = R, n1 = lds, n2 = ldd, i0 = C.
+// Any element type and alignment: one element per access.
 template <typename E>
-__global__ __launch_bounds__(kBlock) void tmb_transpose(const E* __restrict__ src, int64_t R,
-                                                        int C, int64_t lds, E* __restrict__ dst,
-                                                        int64_t ldd) {
+__global__ __launch_bounds__(kBlock) void tmb_transpose(const TmbLaunch L) {
   __shared__ E tile[kTile][kTile + 1];
-  const int64_t r0 = (int64_t)blockIdx.x * kTile;
-  const int c0 = blockIdx.y * kTile;
+  const int gi = tmb_find(L);
+  const TmbItem& G = L.it[gi];
+  const int lb = blockIdx.x - L.block_start[gi];
+  const E* __restrict__ src = (const E*)G.a;
+  E* __restrict__ dst = (E*)G.o0;
+  const int64_t R = G.n0, lds = G.n1, ldd = G.n2;
+  const int C = G.i0;
+  const int64_t r0 = (int64_t)(lb % G.nbx) * kTile;
+  const int c0 = (lb / G.nbx) * kTile;
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
   for (int i = ty; i < kTile; i += kBlock / kTile) {
     const int64_t r = r0 + i;
@@ -78,108 +114,260 @@ __global__ __launch_bounds__(kBlock) void tmb_transpose(const E* __restrict__ sr
   }
 }
 
+// The same for 16-bit elements with C, lds and ldd multiples of 4 and 8-byte aligned
+// bases: 64 x 64 tiles, four elements per global access.
+__global__ __launch_bounds__(kBlock) void tmb_transpose16(const TmbLaunch L) {
+  __shared__ __attribute__((aligned(8))) uint16_t tile[kVTile][kVTile + 4];
+  const int gi = tmb_find(L);
+  const TmbItem& G = L.it[gi];
+  const int lb = blockIdx.x - L.block_start[gi];
+  const uint16_t* __restrict__ src = (const uint16_t*)G.a;
+  uint16_t* __restrict__ dst = (uint16_t*)G.o0;
+  const int64_t R = G.n0, lds = G.n1, ldd = G.n2;
+  const int C = G.i0;
+  const int64_t r0 = (int64_t)(lb % G.nbx) * kVTile;
+  const int c0 = (lb / G.nbx) * kVTile;
+  const int q = threadIdx.x >> 4, v = (threadIdx.x & 15) * 4;
+#pragma unroll
+  for (int pass = 0; pass < 4; ++pass) {
+    const int i = pass * 16 + q;
+    const int64_t r = r0 + i;
+    const int c = c0 + v;
+    uint2 x = make_uint2(0, 0);
+    if (r < R && c < C) x = *(const uint2*)(src + r * lds + c);
+    *(uint2*)&tile[i][v] = x;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int pass = 0; pass < 4; ++pass) {
+    const int i = pass * 16 + q;                   // column of the source tile
+    const int c = c0 + i;
+    const int64_t r = r0 + v;
+    if (c < C && r < ldd) {
+      const uint32_t lo = tile[v][i] | ((uint32_t)tile[v + 1][i] << 16);
+      const uint32_t hi = tile[v + 2][i] | ((uint32_t)tile[v + 3][i] << 16);
+      *(uint2*)(dst + (int64_t)c * ldd + r) = make_uint2(lo, hi);
+    }
+  }
+}
+
 // out[r] = sum over c < ncols of src[r][c], float32, in a fixed order: thread t of
-// the row's block adds columns t, t + 256, ... and the 256 partial sums are folded
-// by halves.  One block per row.
+// the row's block adds columns t, t + 256, ... (16-bit types: the 8-column chunks t,
+// t + 256, ..., over the whole padded row, whose padding is zero) and the 256 partial
+// sums are folded by halves.  One block per row.  a = src, o0 = out, n0 = ld (a multiple
+// of 8 for the 16-bit types), n1 = ncols.
 template <int DT>
-__global__ __launch_bounds__(kBlock) void tmb_rowsum(const void* __restrict__ src, int64_t ld,
-                                                     int64_t ncols, float* __restrict__ out) {
+__global__ __launch_bounds__(kBlock) void tmb_rowsum(const TmbLaunch L) {
   __shared__ float part[kBlock];
-  const int64_t row = blockIdx.x;
+  const int gi = tmb_find(L);
+  const TmbItem& G = L.it[gi];
+  const int64_t row = blockIdx.x - L.block_start[gi];
+  const int64_t ld = G.n0, ncols = G.n1;
   float s = 0.f;
-  for (int64_t c = threadIdx.x; c < ncols; c += kBlock) s += load_elt<DT>(src, row * ld + c);
+  if constexpr (DT == DMT_F32) {
+    for (int64_t c = threadIdx.x; c < ncols; c += kBlock) s += load_elt<DT>(G.a, row * ld + c);
+  } else {
+    for (int64_t c = (int64_t)threadIdx.x * 8; c < ld; c += kBlock * 8) {
+      float x[8];
+      dmt::decode_chunk<DT>(x, *(const uint4*)((const uint16_t*)G.a + row * ld + c));
+#pragma unroll
+      for (int q = 0; q < 8; ++q) s += x[q];
+    }
+  }
   part[threadIdx.x] = s;
   __syncthreads();
   for (int h = kBlock / 2; h > 0; h >>= 1) {
     if ((int)threadIdx.x < h) part[threadIdx.x] += part[threadIdx.x + h];
     __syncthreads();
   }
-  if (threadIdx.x == 0) out[row] = part[0];
+  if (threadIdx.x == 0) ((float*)G.o0)[row] = part[0];
+}
+
+// Elementwise kernels over `count` = n0 elements: 8 per thread step for the 16-bit types
+// (count is then a multiple of 8), 1 for float32.  nbx = blocks of the item.
+template <int DT> struct Ew { static constexpr int V = DT == DMT_F32 ? 1 : 8; };
+
+template <int DT>
+__device__ __forceinline__ void ew_load(const void* p, int64_t e, float (&x)[Ew<DT>::V]) {
+  if constexpr (DT == DMT_F32) x[0] = ((const float*)p)[e];
+  else dmt::decode_chunk<DT>(x, *(const uint4*)((const uint16_t*)p + e));
+}
+template <int DT>
+__device__ __forceinline__ void ew_store(void* p, int64_t e, const float (&x)[Ew<DT>::V]) {
+  if constexpr (DT == DMT_F32) ((float*)p)[e] = x[0];
+  else dmt::store_chunk<DT, 8>(p, e, x);
+}
+template <int V>
+__device__ __forceinline__ void ew_load_f32(const float* p, int64_t e, float (&x)[V]) {
+  if constexpr (V == 1) x[0] = p[e];
+  else {
+    const float4 a = *(const float4*)(p + e), b = *(const float4*)(p + e + 4);
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+  }
+}
+template <int V>
+__device__ __forceinline__ void ew_store_f32(float* p, int64_t e, const float (&x)[V]) {
+  if constexpr (V == 1) p[e] = x[0];
+  else {
+    *(float4*)(p + e) = make_float4(x[0], x[1], x[2], x[3]);
+    *(float4*)(p + e + 4) = make_float4(x[4], x[5], x[6], x[7]);
+  }
 }
 
 // Dot-product tower: dx[b][i][c] = dZ[b][np_pad + i n + c]
 //                                  + sum over j != i (ascending j) of dZ[b][p(i,j)] x[b][j][c]
 // with p the row-major index of the pair {i, j}.  One thread per element of dx.
+// a = x, b = dZ, o0 = dx, n0 = B, i0 = nf, i1 = n, i2 = np_pad, i3 = ldz.
 template <int DT>
-__global__ __launch_bounds__(kBlock) void tmb_dot_bwd(const void* __restrict__ x,
-                                                      const float* __restrict__ dZ, int64_t B,
-                                                      int nf, int n, int np_pad, int ldz,
-                                                      float* __restrict__ dx) {
+__global__ __launch_bounds__(kBlock) void tmb_dot_bwd(const TmbLaunch L) {
+  const int gi = tmb_find(L);
+  const TmbItem& G = L.it[gi];
+  const int nf = G.i0, n = G.i1, np_pad = G.i2, ldz = G.i3;
   const int wt = nf * n;
-  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (e >= B * wt) return;
+  const int64_t e = (int64_t)(blockIdx.x - L.block_start[gi]) * kBlock + threadIdx.x;
+  if (e >= G.n0 * wt) return;
   const int64_t b = e / wt;
   const int r = (int)(e % wt), i = r / n, c = r % n;
-  const float* z = dZ + b * ldz;
+  const float* __restrict__ z = (const float*)G.b + b * ldz;
   float acc = z[np_pad + r];
   for (int j = 0; j < nf; ++j) {
     if (j == i) continue;
     const int lo = j < i ? j : i, hi = j < i ? i : j;
-    acc += z[lo * (2 * nf - lo - 1) / 2 + (hi - lo - 1)] * load_elt<DT>(x, b * wt + j * n + c);
+    acc += z[lo * (2 * nf - lo - 1) / 2 + (hi - lo - 1)] * load_elt<DT>(G.a, b * wt + j * n + c);
   }
-  dx[e] = acc;
+  ((float*)G.o0)[e] = acc;
 }
 
-// dw[o][k] (row length np + wt) = packed[o][k'] (row length np_pad + wt): drops the
-// padding columns between the dot terms and the flat part.
-__global__ __launch_bounds__(kBlock) void tmb_unpack_dw(const float* __restrict__ packed, int O,
-                                                        int np, int np_pad, int wt,
-                                                        float* __restrict__ dw) {
-  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+// The same for the 16-bit types with n a multiple of 8: one thread per 8 consecutive columns
+// of one feature, 16-byte accesses.
+template <int DT>
+__global__ __launch_bounds__(kBlock) void tmb_dot_bwd8(const TmbLaunch L) {
+  const int gi = tmb_find(L);
+  const TmbItem& G = L.it[gi];
+  const int nf = G.i0, n = G.i1, np_pad = G.i2, ldz = G.i3;
+  const int wt = nf * n, w8 = wt / 8;
+  const int64_t e = (int64_t)(blockIdx.x - L.block_start[gi]) * kBlock + threadIdx.x;
+  if (e >= G.n0 * w8) return;
+  const int64_t b = e / w8;
+  const int r = (int)(e % w8) * 8, i = r / n, c = r % n;
+  const float* __restrict__ z = (const float*)G.b + b * ldz;
+  const uint16_t* __restrict__ x = (const uint16_t*)G.a + b * wt + c;
+  float acc[8];
+  ew_load_f32<8>(z, np_pad + r, acc);
+  for (int j = 0; j < nf; ++j) {
+    if (j == i) continue;
+    const int lo = j < i ? j : i, hi = j < i ? i : j;
+    const float g = z[lo * (2 * nf - lo - 1) / 2 + (hi - lo - 1)];
+    float xv[8];
+    dmt::decode_chunk<DT>(xv, *(const uint4*)(x + j * n));
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc[q] += g * xv[q];
+  }
+  ew_store_f32<8>((float*)G.o0, b * wt + r, acc);
+}
+
+// dw[o][k] = sum over slices s (ascending) of part[s][o][k'], where k' = k for k < np and
+// k - np + np_pad after: adds up a split contraction's slices and drops the padding columns
+// between the dot terms and the flat part (np = np_pad = 0: plain rows).
+// a = part, o0 = dw, n0 = slice stride in floats, i0 = O, i1 = np, i2 = np_pad, i3 = wt,
+// i4 = slices.
+__global__ __launch_bounds__(kBlock) void tmb_sum_slices(const TmbLaunch L) {
+  const int gi = tmb_find(L);
+  const TmbItem& G = L.it[gi];
+  const int O = G.i0, np = G.i1, np_pad = G.i2, wt = G.i3, ns = G.i4;
+  const int64_t e = (int64_t)(blockIdx.x - L.block_start[gi]) * kBlock + threadIdx.x;
   const int kin = np + wt;
   if (e >= (int64_t)O * kin) return;
   const int o = (int)(e / kin), k = (int)(e % kin);
-  dw[e] = packed[(int64_t)o * (np_pad + wt) + (k < np ? k : k - np + np_pad)];
+  const float* __restrict__ p = (const float*)G.a + (int64_t)o * (np_pad + wt) + (k < np ? k : k - np + np_pad);
+  float s = 0.f;
+  for (int q = 0; q < ns; ++q) s += p[q * G.n0];
+  ((float*)G.o0)[e] = s;
 }
 
 // Cross layer forward, elementwise part: xn = x0 * u + xl (rounded once to DT).
+// a = x0, b = u, c = xl, o0 = xn.
 template <int DT>
-__global__ __launch_bounds__(kBlock) void tmb_cross_next(const void* __restrict__ x0,
-                                                         const void* __restrict__ u,
-                                                         const void* __restrict__ xl, int64_t count,
-                                                         void* __restrict__ xn) {
-  const int64_t stride = (int64_t)gridDim.x * kBlock;
-  for (int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x; e < count; e += stride)
-    store_elt<DT>(xn, e, load_elt<DT>(x0, e) * load_elt<DT>(u, e) + load_elt<DT>(xl, e));
-}
-
-// Cross layer backward, elementwise part: du = dxn * x0 (rounded to DT);
-// dx0 = (first ? 0 : dx0) + dxn * u.
-template <int DT>
-__global__ __launch_bounds__(kBlock) void tmb_cross_prep(const float* __restrict__ dxn,
-                                                         const void* __restrict__ x0,
-                                                         const void* __restrict__ u, int first,
-                                                         int64_t count, void* __restrict__ du,
-                                                         float* __restrict__ dx0) {
-  const int64_t stride = (int64_t)gridDim.x * kBlock;
-  for (int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x; e < count; e += stride) {
-    const float g = dxn[e];
-    store_elt<DT>(du, e, g * load_elt<DT>(x0, e));
-    const float prev = first ? 0.f : dx0[e];
-    dx0[e] = prev + g * load_elt<DT>(u, e);
+__global__ __launch_bounds__(kBlock) void tmb_cross_next(const TmbLaunch L) {
+  constexpr int V = Ew<DT>::V;
+  const int gi = tmb_find(L);
+  const TmbItem& G = L.it[gi];
+  const int64_t stride = (int64_t)G.nbx * kBlock * V;
+  for (int64_t e = ((int64_t)(blockIdx.x - L.block_start[gi]) * kBlock + threadIdx.x) * V; e < G.n0;
+       e += stride) {
+    float x0[V], u[V], xl[V];
+    ew_load<DT>(G.a, e, x0);
+    ew_load<DT>(G.b, e, u);
+    ew_load<DT>(G.c, e, xl);
+#pragma unroll
+    for (int q = 0; q < V; ++q) xl[q] = x0[q] * u[q] + xl[q];
+    ew_store<DT>(G.o0, e, xl);
   }
 }
 
-// io[e] += a[e]
-__global__ __launch_bounds__(kBlock) void tmb_add(const float* __restrict__ a, int64_t count,
-                                                  float* __restrict__ io) {
-  const int64_t stride = (int64_t)gridDim.x * kBlock;
-  for (int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x; e < count; e += stride)
-    io[e] += a[e];
+// Cross layer backward, elementwise part: du = dxn * x0 (rounded to DT);
+// dx0 = (first ? 0 : dx0) + dxn * u (+ dxn when `last`: the layer's data-gradient contraction
+// then accumulates du W_l on top, which completes dx_0 + dx0 in place).
+// a = dxn, b = x0, c = u, o0 = du, o1 = dx0, i0 = first, i1 = last.
+template <int DT>
+__global__ __launch_bounds__(kBlock) void tmb_cross_prep(const TmbLaunch L) {
+  constexpr int V = Ew<DT>::V;
+  const int gi = tmb_find(L);
+  const TmbItem& G = L.it[gi];
+  const int first = G.i0;
+  const float keep = G.i1 ? 1.f : 0.f;
+  const int64_t stride = (int64_t)G.nbx * kBlock * V;
+  for (int64_t e = ((int64_t)(blockIdx.x - L.block_start[gi]) * kBlock + threadIdx.x) * V; e < G.n0;
+       e += stride) {
+    float g[V], x0[V], u[V], acc[V];
+    ew_load_f32<V>((const float*)G.a, e, g);
+    ew_load<DT>(G.b, e, x0);
+    ew_load<DT>(G.c, e, u);
+    if (first) {
+#pragma unroll
+      for (int q = 0; q < V; ++q) acc[q] = 0.f;
+    } else {
+      ew_load_f32<V>((const float*)G.o1, e, acc);
+    }
+#pragma unroll
+    for (int q = 0; q < V; ++q) {
+      acc[q] += g[q] * u[q] + keep * g[q];
+      x0[q] *= g[q];
+    }
+    ew_store<DT>(G.o0, e, x0);
+    ew_store_f32<V>((float*)G.o1, e, acc);
+  }
 }
 
 // ----------------------------------------------------------------- host side
 
 inline int64_t up8(int64_t v) { return (v + 7) / 8 * 8; }
 
+// Slices a weight-gradient contraction (M x N outputs, K = batch) is cut into so that a
+// launch of `tiles` output tiles fills the chip: each slice at least 1024 long, a multiple
+// of 64.
+inline void choose_split(int64_t tiles_all, int64_t K, int* ksplit, int* klen) {
+  int ks = 1;
+  while (ks < 16 && tiles_all * ks < 384 && K / (ks * 2) >= 1024) ks *= 2;
+  const int forced = dmt::env_int("DMT_TMB_KSPLIT", 0);
+  if (forced > 0 && K / forced >= 128) ks = forced;
+  int len = (int)((K + ks - 1) / ks);
+  len = (len + 63) / 64 * 64;
+  *ksplit = (int)((K + len - 1) / len);
+  *klen = len;
+}
+
 struct TowerBwdWs {
   int np = 0, np_pad = 0;
   int kin = 0;                 // row length of the projection's GEMM operand (np_pad + wt for dots)
   int64_t Op = 0;
   size_t dz = 0, dzT = 0, wT = 0, zT = 0;
-  size_t p = 0, wp = 0, dZ = 0, dWp = 0;                        // dot towers
+  size_t p = 0, wp = 0, dZ = 0;                                 // dot towers
   size_t xl[DMT_MAX_CROSS_LAYERS] = {}, u[DMT_MAX_CROSS_LAYERS] = {};   // cross towers
   size_t dxn = 0, du = 0, duT = 0, wlT = 0;
+  size_t part = 0;             // weight-gradient slices (split K) / padded dW of a dot tower
+  int ksplit = 1, klen = 0;    // of the projection's weight gradient
+  int ksplit_c = 1, klen_c = 0;   // of the cross layers' weight gradients
 };
 
 dmt_status plan_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, int eb,
@@ -188,14 +376,27 @@ dmt_status plan_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, in
   auto take = [&](size_t b) { size_t o = off; off = dmt_align_up(off + b, 256); return o; };
   const int64_t Bp = up8(B);
   ws->assign(p->T, TowerBwdWs());
+  // output tiles of the weight-gradient launches (all towers together), 128 x 128 units
+  int64_t tiles_proj = 0, tiles_cross = 0;
   for (int32_t t = 0; t < p->T; ++t) {
     const dmt_tm_params& q = tp[t];
     const int64_t wt = p->tower_width[t];
-    if (q.out_dim <= 0 || !q.w_proj || !q.b_proj) return DMT_EINVAL;
+    if (q.out_dim <= 0) return DMT_EINVAL;
+    tiles_proj += ((q.out_dim + 255) / 256) * ((wt + 255) / 256);
+    if (q.kind == DMT_TM_CROSS_LINEAR) tiles_cross += ((wt + 255) / 256) * ((wt + 255) / 256);
+  }
+  for (int32_t t = 0; t < p->T; ++t) {
+    const dmt_tm_params& q = tp[t];
+    const int64_t wt = p->tower_width[t];
+    if (!q.w_proj || !q.b_proj) return DMT_EINVAL;
     if (((uintptr_t)q.w_proj & 15) && q.kind != DMT_TM_DOT_LINEAR) return DMT_EINVAL;
     TowerBwdWs& w = (*ws)[t];
     w.Op = up8(q.out_dim);
     w.kin = (int)wt;
+    if (eb == 2) {
+      choose_split(tiles_proj, Bp, &w.ksplit, &w.klen);
+      choose_split(std::max<int64_t>(tiles_cross, 1), Bp, &w.ksplit_c, &w.klen_c);
+    }
     switch (q.kind) {
       case DMT_TM_LINEAR:
       case DMT_TM_LINEAR_RELU:
@@ -209,7 +410,6 @@ dmt_status plan_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, in
         w.p = take((size_t)B * w.np_pad * eb);
         w.wp = take((size_t)q.out_dim * w.kin * eb);
         w.dZ = take((size_t)B * w.kin * 4);
-        w.dWp = take((size_t)q.out_dim * w.kin * 4);
         break;
       }
       case DMT_TM_CROSS_LINEAR:
@@ -231,22 +431,71 @@ dmt_status plan_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, in
     w.dzT = take((size_t)q.out_dim * Bp * eb);
     w.wT = take((size_t)w.kin * w.Op * eb);
     w.zT = take((size_t)w.kin * Bp * eb);
+    size_t part = 0;
+    if (w.ksplit > 1 || q.kind == DMT_TM_DOT_LINEAR)
+      part = (size_t)w.ksplit * q.out_dim * w.kin * 4;
+    if (q.kind == DMT_TM_CROSS_LINEAR && w.ksplit_c > 1)
+      part = std::max(part, (size_t)w.ksplit_c * wt * wt * 4);
+    if (part) w.part = take(part);
   }
   *bytes = off;
   return DMT_OK;
 }
 
-inline int ew_blocks(int64_t count) {
-  return (int)std::min<int64_t>((count + kBlock - 1) / kBlock, 256 * 16);
+// Items of one grouped launch of a small kernel, with each item's block count.
+struct TmbBatch {
+  std::vector<TmbItem> items;
+  std::vector<int64_t> blocks;
+  void add(const TmbItem& it, int64_t nblocks) {
+    if (nblocks <= 0) return;
+    items.push_back(it);
+    blocks.push_back(nblocks);
+  }
+};
+
+// False when an item alone exceeds the grid limit (nothing of it is launched).
+template <typename Kernel>
+bool launch_items(const dmt_plan* p, TmbBatch& batch, Kernel kernel, hipStream_t s) {
+  bool ok = true;
+  for (size_t first = 0; first < batch.items.size();) {
+    TmbLaunch L;
+    L.n = 0;
+    int64_t blocks = 0;
+    while (first < batch.items.size() && L.n < kMaxItems &&
+           blocks + batch.blocks[first] < (1LL << 30)) {
+      L.it[L.n] = batch.items[first];
+      L.block_start[L.n] = (int32_t)blocks;
+      blocks += batch.blocks[first];
+      ++L.n;
+      ++first;
+    }
+    if (L.n == 0) { ok = false; break; }
+    L.block_start[L.n] = (int32_t)blocks;
+    DmtScope sc_(p, DMT_K_TM_BWD_AUX, s);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kBlock), 0, s, L);
+  }
+  batch.items.clear();
+  batch.blocks.clear();
+  return ok;
+}
+
+inline int64_t ew_blocks(int64_t count, int vec) {
+  return std::min<int64_t>((count / vec + kBlock - 1) / kBlock, 256 * 8);
 }
 
 template <int DT>
-void transpose(const dmt_plan* p, const void* src, int64_t R, int C, int64_t lds, void* dst,
-               int64_t ldd, hipStream_t s) {
-  using E = typename EltOf<DT>::type;
-  DmtScope sc_(p, DMT_K_TM_BWD_AUX, s);
-  hipLaunchKernelGGL((tmb_transpose<E>), dim3((unsigned)((ldd + kTile - 1) / kTile), (C + kTile - 1) / kTile),
-                     dim3(kBlock), 0, s, (const E*)src, R, C, lds, (E*)dst, ldd);
+void add_transpose(TmbBatch& b, const void* src, int64_t R, int C, int64_t lds, void* dst, int64_t ldd) {
+  constexpr int tile = DT == DMT_F32 ? kTile : kVTile;
+  TmbItem it{};
+  it.a = src; it.o0 = dst; it.n0 = R; it.n1 = lds; it.n2 = ldd; it.i0 = C;
+  it.nbx = (int32_t)((ldd + tile - 1) / tile);
+  b.add(it, (int64_t)it.nbx * ((C + tile - 1) / tile));
+}
+
+template <int DT>
+bool launch_transposes(const dmt_plan* p, TmbBatch& b, hipStream_t s) {
+  if constexpr (DT == DMT_F32) return launch_items(p, b, tmb_transpose<float>, s);
+  else return launch_items(p, b, tmb_transpose16, s);
 }
 
 template <int DT>
@@ -254,6 +503,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
                       const void* pooled, const void* tm_out, int64_t B, const float* dy_all,
                       float* dx_all, const dmt_tm_grads* gr, char* wsp, hipStream_t s) {
   constexpr int eb = DT == DMT_F32 ? 4 : 2;
+  constexpr int V = Ew<DT>::V;
   const char* x_all = (const char*)pooled;
   const int64_t Bp = up8(B);
   std::vector<int64_t> out_prefix(p->T + 1, 0);
@@ -263,6 +513,8 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
   // x_l of a cross tower: l = 0 is the pooled block itself
   auto xl_of = [&](int t, int l) { return l == 0 ? x_of(t) : (const void*)(wsp + ws[t].xl[l - 1]); };
   int max_layers = 0;
+  TmbBatch batch, batch2, batch3;
+  bool ok = true;
 
   // ---- recompute what the forward did not keep: dot terms (and the repacked weights)
   std::vector<TmAuxItem> dots_mfma, dots_simple, packs;
@@ -308,17 +560,14 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
       g.C = wsp + ws[t].u[l]; g.ldc = wt;
       g.M = (int32_t)B; g.N = wt; g.epi = EPI_BIAS;
       groups.push_back(g);
+      TmbItem it{};
+      it.a = x_of(t); it.b = wsp + ws[t].u[l]; it.c = xl_of(t, l); it.o0 = wsp + ws[t].xl[l];
+      it.n0 = B * wt;
+      it.nbx = (int32_t)ew_blocks(it.n0, V);
+      batch.add(it, it.nbx);
     }
     launch_groups<DT>(p, groups, s, false, DMT_K_TM_BWD_GEMM);
-    for (int32_t t = 0; t < p->T; ++t) {
-      const dmt_tm_params& q = tp[t];
-      if (q.kind != DMT_TM_CROSS_LINEAR || l >= q.num_cross_layers) continue;
-      const int64_t count = B * p->tower_width[t];
-      DmtScope sc_(p, DMT_K_TM_BWD_AUX, s);
-      hipLaunchKernelGGL((tmb_cross_next<DT>), dim3(ew_blocks(count)), dim3(kBlock), 0, s, x_of(t),
-                         (const void*)(wsp + ws[t].u[l]), xl_of(t, l), count,
-                         (void*)(wsp + ws[t].xl[l]));
-    }
+    ok &= launch_items(p, batch, tmb_cross_next<DT>, s);
   }
 
   // ---- projection: operands, bias gradient, then both contractions for all towers
@@ -327,37 +576,38 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
     const dmt_tm_params& q = tp[t];
     const TowerBwdWs& w = ws[t];
     const int wt = p->tower_width[t], O = q.out_dim;
-    const int relu = q.kind == DMT_TM_LINEAR_RELU;
-    const float* dy = dy_all + (size_t)B * out_prefix[t];
-    const void* y = relu ? (const void*)((const char*)tm_out + (size_t)B * out_prefix[t] * eb) : nullptr;
+    const bool dot = q.kind == DMT_TM_DOT_LINEAR;
     {
-      DmtScope sc_(p, DMT_K_TM_BWD_AUX, s);
-      hipLaunchKernelGGL((tmb_prep_dy<DT>),
-                         dim3((unsigned)((Bp + kTile - 1) / kTile), (unsigned)((w.Op + kTile - 1) / kTile)),
-                         dim3(kBlock), 0, s, dy, y, relu, B, O, (int)w.Op, Bp, (void*)(wsp + w.dz),
-                         (void*)(wsp + w.dzT));
+      TmbItem it{};
+      it.a = dy_all + (size_t)B * out_prefix[t];
+      it.i2 = q.kind == DMT_TM_LINEAR_RELU;
+      it.b = it.i2 ? (const void*)((const char*)tm_out + (size_t)B * out_prefix[t] * eb) : nullptr;
+      it.o0 = wsp + w.dz; it.o1 = wsp + w.dzT;
+      it.n0 = B; it.n1 = Bp; it.i0 = O; it.i1 = (int32_t)w.Op;
+      it.nbx = (int32_t)((Bp + kTile - 1) / kTile);
+      batch.add(it, (int64_t)it.nbx * ((w.Op + kTile - 1) / kTile));
     }
     {
-      DmtScope sc_(p, DMT_K_TM_BWD_AUX, s);
-      hipLaunchKernelGGL((tmb_rowsum<DT>), dim3(O), dim3(kBlock), 0, s, (const void*)(wsp + w.dzT),
-                         Bp, B, gr[t].db_proj);
+      TmbItem it{};
+      it.a = wsp + w.dzT; it.o0 = gr[t].db_proj; it.n0 = Bp; it.n1 = B;
+      batch2.add(it, O);
     }
     // W^T [kin][Op]
-    const void* wsrc = q.kind == DMT_TM_DOT_LINEAR ? (const void*)(wsp + w.wp) : q.w_proj;
-    transpose<DT>(p, wsrc, O, w.kin, w.kin, wsp + w.wT, w.Op, s);
+    add_transpose<DT>(batch3, dot ? (const void*)(wsp + w.wp) : q.w_proj, O, w.kin, w.kin,
+                      wsp + w.wT, w.Op);
     // z^T [kin][Bp]: the projection's input, transposed
-    if (q.kind == DMT_TM_DOT_LINEAR) {
-      if (w.np_pad > 0) transpose<DT>(p, wsp + w.p, B, w.np_pad, w.np_pad, wsp + w.zT, Bp, s);
-      transpose<DT>(p, x_of(t), B, wt, wt, wsp + w.zT + (size_t)w.np_pad * Bp * eb, Bp, s);
+    if (dot) {
+      if (w.np_pad > 0) add_transpose<DT>(batch3, wsp + w.p, B, w.np_pad, w.np_pad, wsp + w.zT, Bp);
+      add_transpose<DT>(batch3, x_of(t), B, wt, wt, wsp + w.zT + (size_t)w.np_pad * Bp * eb, Bp);
     } else {
       const void* z = q.kind == DMT_TM_CROSS_LINEAR ? xl_of(t, q.num_cross_layers) : x_of(t);
-      transpose<DT>(p, z, B, wt, wt, wsp + w.zT, Bp, s);
+      add_transpose<DT>(batch3, z, B, wt, wt, wsp + w.zT, Bp);
     }
     TmGroup g{};
     g.A1 = wsp + w.dz; g.lda1 = (int32_t)w.Op; g.K1 = (int32_t)w.Op;
     g.W = wsp + w.wT; g.ldw = (int32_t)w.Op;
     g.M = (int32_t)B; g.N = w.kin; g.epi = EPI_F32;
-    if (q.kind == DMT_TM_DOT_LINEAR) { g.C = wsp + w.dZ; g.ldc = w.kin; }
+    if (dot) { g.C = wsp + w.dZ; g.ldc = w.kin; }
     else if (q.kind == DMT_TM_CROSS_LINEAR) { g.C = wsp + w.dxn; g.ldc = wt; }
     else { g.C = dx_of(t); g.ldc = wt; }
     dgrad.push_back(g);
@@ -365,79 +615,95 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
     h.A1 = wsp + w.dzT; h.lda1 = (int32_t)Bp; h.K1 = (int32_t)Bp;
     h.W = wsp + w.zT; h.ldw = (int32_t)Bp;
     h.M = O; h.N = w.kin; h.epi = EPI_F32;
-    h.C = q.kind == DMT_TM_DOT_LINEAR ? (void*)(wsp + w.dWp) : (void*)gr[t].dw_proj;
+    h.ksplit = w.ksplit; h.klen = w.klen; h.cstride = (int64_t)O * w.kin;
+    h.C = (dot || w.ksplit > 1) ? (void*)(wsp + w.part) : (void*)gr[t].dw_proj;
     h.ldc = w.kin;
     wgrad.push_back(h);
   }
+  ok &= launch_items(p, batch, tmb_prep_dy<DT>, s);
+  ok &= launch_items(p, batch2, tmb_rowsum<DT>, s);
+  ok &= launch_transposes<DT>(p, batch3, s);
   launch_groups<DT>(p, dgrad, s, false, DMT_K_TM_BWD_GEMM);
   launch_groups<DT>(p, wgrad, s, false, DMT_K_TM_BWD_GEMM);
 
-  // ---- dot towers: fold the dot terms' gradients into dx, strip dW's padding
+  // ---- weight gradients: add up the slices, strip a dot tower's padding; dot towers: fold
+  // the dot terms' gradients into dx
   for (int32_t t = 0; t < p->T; ++t) {
     const dmt_tm_params& q = tp[t];
-    if (q.kind != DMT_TM_DOT_LINEAR) continue;
     const TowerBwdWs& w = ws[t];
     const int wt = p->tower_width[t];
-    {
-      DmtScope sc_(p, DMT_K_TM_BWD_AUX, s);
-      hipLaunchKernelGGL((tmb_dot_bwd<DT>), dim3((unsigned)((B * wt + kBlock - 1) / kBlock)),
-                         dim3(kBlock), 0, s, x_of(t), (const float*)(wsp + w.dZ), B,
-                         p->tower_ntab[t], p->tower_uniform_dim[t], w.np_pad, w.kin, dx_of(t));
+    const bool dot = q.kind == DMT_TM_DOT_LINEAR;
+    if (dot || w.ksplit > 1) {
+      TmbItem it{};
+      it.a = wsp + w.part; it.o0 = gr[t].dw_proj; it.n0 = (int64_t)q.out_dim * w.kin;
+      it.i0 = q.out_dim; it.i1 = w.np; it.i2 = w.np_pad; it.i3 = wt; it.i4 = w.ksplit;
+      batch.add(it, ((int64_t)q.out_dim * (w.np + wt) + kBlock - 1) / kBlock);
     }
-    {
-      DmtScope sc_(p, DMT_K_TM_BWD_AUX, s);
-      const int64_t count = (int64_t)q.out_dim * (w.np + wt);
-      hipLaunchKernelGGL(tmb_unpack_dw, dim3((unsigned)((count + kBlock - 1) / kBlock)), dim3(kBlock),
-                         0, s, (const float*)(wsp + w.dWp), q.out_dim, w.np, w.np_pad, wt,
-                         gr[t].dw_proj);
+    if (dot) {
+      TmbItem it{};
+      it.a = x_of(t); it.b = wsp + w.dZ; it.o0 = dx_of(t); it.n0 = B;
+      it.i0 = p->tower_ntab[t]; it.i1 = p->tower_uniform_dim[t]; it.i2 = w.np_pad; it.i3 = w.kin;
+      if (DT != DMT_F32 && it.i1 % 8 == 0) batch3.add(it, (B * (wt / 8) + kBlock - 1) / kBlock);
+      else batch2.add(it, (B * wt + kBlock - 1) / kBlock);
     }
   }
+  ok &= launch_items(p, batch, tmb_sum_slices, s);
+  ok &= launch_items(p, batch2, tmb_dot_bwd<DT>, s);
+  if constexpr (DT != DMT_F32) ok &= launch_items(p, batch3, tmb_dot_bwd8<DT>, s);
 
-  // ---- cross towers: layers from the last to the first; dx0 accumulates in the output block
+  // ---- cross towers: layers from the last to the first; dx0 accumulates in the output block,
+  // where the first layer's data gradient then lands on top of it
+  TmbBatch sums;
   for (int l = max_layers - 1; l >= 0; --l) {
     for (int32_t t = 0; t < p->T; ++t) {
       const dmt_tm_params& q = tp[t];
       if (q.kind != DMT_TM_CROSS_LINEAR || l >= q.num_cross_layers) continue;
       const TowerBwdWs& w = ws[t];
       const int wt = p->tower_width[t];
-      const int64_t count = B * wt;
       {
-        DmtScope sc_(p, DMT_K_TM_BWD_AUX, s);
-        hipLaunchKernelGGL((tmb_cross_prep<DT>), dim3(ew_blocks(count)), dim3(kBlock), 0, s,
-                           (const float*)(wsp + w.dxn), x_of(t), (const void*)(wsp + w.u[l]),
-                           l == q.num_cross_layers - 1 ? 1 : 0, count, (void*)(wsp + w.du), dx_of(t));
+        TmbItem it{};
+        it.a = wsp + w.dxn; it.b = x_of(t); it.c = wsp + w.u[l]; it.o0 = wsp + w.du; it.o1 = dx_of(t);
+        it.n0 = B * wt; it.i0 = l == q.num_cross_layers - 1; it.i1 = l == 0;
+        it.nbx = (int32_t)ew_blocks(it.n0, V);
+        batch.add(it, it.nbx);
       }
-      transpose<DT>(p, wsp + w.du, B, wt, wt, wsp + w.duT, Bp, s);
+      add_transpose<DT>(batch2, wsp + w.du, B, wt, wt, wsp + w.duT, Bp);
+      add_transpose<DT>(batch2, xl_of(t, l), B, wt, wt, wsp + w.zT, Bp);
+      add_transpose<DT>(batch2, q.w_cross[l], wt, wt, wt, wsp + w.wlT, wt);
       {
-        DmtScope sc_(p, DMT_K_TM_BWD_AUX, s);
-        hipLaunchKernelGGL((tmb_rowsum<DT>), dim3(wt), dim3(kBlock), 0, s,
-                           (const void*)(wsp + w.duT), Bp, B, gr[t].db_cross[l]);
+        TmbItem it{};
+        it.a = wsp + w.duT; it.o0 = gr[t].db_cross[l]; it.n0 = Bp; it.n1 = B;
+        batch3.add(it, wt);
       }
-      transpose<DT>(p, xl_of(t, l), B, wt, wt, wsp + w.zT, Bp, s);
-      transpose<DT>(p, q.w_cross[l], wt, wt, wt, wsp + w.wlT, wt, s);
       TmGroup g{};
       g.A1 = wsp + w.du; g.lda1 = wt; g.K1 = wt;
       g.W = wsp + w.wlT; g.ldw = wt;
       g.M = (int32_t)B; g.N = wt; g.epi = EPI_F32_ADD;
-      g.C = wsp + w.dxn; g.ldc = wt;
+      g.C = l == 0 ? (void*)dx_of(t) : (void*)(wsp + w.dxn); g.ldc = wt;
       dgrad.push_back(g);
       TmGroup h{};
       h.A1 = wsp + w.duT; h.lda1 = (int32_t)Bp; h.K1 = (int32_t)Bp;
       h.W = wsp + w.zT; h.ldw = (int32_t)Bp;
       h.M = wt; h.N = wt; h.epi = EPI_F32;
-      h.C = gr[t].dw_cross[l]; h.ldc = wt;
+      h.ksplit = w.ksplit_c; h.klen = w.klen_c; h.cstride = (int64_t)wt * wt;
+      h.C = w.ksplit_c > 1 ? (void*)(wsp + w.part) : (void*)gr[t].dw_cross[l];
+      h.ldc = wt;
       wgrad.push_back(h);
+      if (w.ksplit_c > 1) {
+        TmbItem it{};
+        it.a = wsp + w.part; it.o0 = gr[t].dw_cross[l]; it.n0 = (int64_t)wt * wt;
+        it.i0 = wt; it.i1 = 0; it.i2 = 0; it.i3 = wt; it.i4 = w.ksplit_c;
+        sums.add(it, ((int64_t)wt * wt + kBlock - 1) / kBlock);
+      }
     }
+    ok &= launch_items(p, batch, tmb_cross_prep<DT>, s);
+    ok &= launch_transposes<DT>(p, batch2, s);
+    ok &= launch_items(p, batch3, tmb_rowsum<DT>, s);
     launch_groups<DT>(p, dgrad, s, false, DMT_K_TM_BWD_GEMM);
     launch_groups<DT>(p, wgrad, s, false, DMT_K_TM_BWD_GEMM);
+    ok &= launch_items(p, sums, tmb_sum_slices, s);
   }
-  for (int32_t t = 0; t < p->T; ++t) {
-    if (tp[t].kind != DMT_TM_CROSS_LINEAR) continue;
-    const int64_t count = B * p->tower_width[t];
-    DmtScope sc_(p, DMT_K_TM_BWD_AUX, s);
-    hipLaunchKernelGGL(tmb_add, dim3(ew_blocks(count)), dim3(kBlock), 0, s,
-                       (const float*)(wsp + ws[t].dxn), count, dx_of(t));
-  }
+  if (!ok) return DMT_ENOTSUP;
   return hipGetLastError() == hipSuccess ? DMT_OK : DMT_EHIP;
 }
 

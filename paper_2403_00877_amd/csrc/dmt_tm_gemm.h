@@ -39,7 +39,14 @@ struct TmGroup {
   void* C;          // [M][ldc]
   int32_t lda0, K0, lda1, K1, ldw, ldc, ldx, M, N, epi;
   int32_t nf, fdim;       // dot terms computed in-kernel: number of features and their dim
+  // Split K (EPI_F32 with K0 = 0 only): ksplit > 1 cuts the K1 columns into slices of klen
+  // (a multiple of 8); slice s is a contraction of its own whose result goes to
+  // C + s * cstride floats, and the caller adds the slices up in a fixed order.
+  int32_t ksplit, klen;
+  int64_t cstride;
 };
+
+__host__ __device__ inline int tm_slices(const TmGroup& g) { return g.ksplit > 1 ? g.ksplit : 1; }
 
 struct TmLaunch {
   int32_t ngroups;
@@ -78,13 +85,18 @@ __global__ __launch_bounds__(kBlock, 2) void tm_gemm_mfma(const TmLaunch L) {
   int gi = 0;
   while (gi + 1 < L.ngroups && (int)blockIdx.x >= L.tile_start[gi + 1]) ++gi;
   const TmGroup& G = L.g[gi];
-  const int tile = blockIdx.x - L.tile_start[gi];
+  int tile = blockIdx.x - L.tile_start[gi];
   const int tiles_n = (G.N + BN - 1) / BN;
+  const int tiles_mn = ((G.M + BM - 1) / BM) * tiles_n;
+  const int slice = tile / tiles_mn;                 // 0 unless K is split
+  tile -= slice * tiles_mn;
+  const int kofs = G.ksplit > 1 ? slice * G.klen : 0;
   const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
-  const int M = G.M, N = G.N, K0 = G.K0, K = G.K0 + G.K1;
+  const int M = G.M, N = G.N, K0 = G.K0;
+  const int K = G.K0 + (G.ksplit > 1 ? min(G.klen, G.K1 - kofs) : G.K1);
   const uint16_t* A0 = (const uint16_t*)G.A0;
-  const uint16_t* A1 = (const uint16_t*)G.A1;
-  const uint16_t* W = (const uint16_t*)G.W;
+  const uint16_t* A1 = (const uint16_t*)G.A1 + kofs;
+  const uint16_t* W = (const uint16_t*)G.W + kofs;
   const int lda0 = G.lda0, lda1 = G.lda1, ldw = G.ldw;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -161,7 +173,7 @@ __global__ __launch_bounds__(kBlock, 2) void tm_gemm_mfma(const TmLaunch L) {
         const int m = m0 + wm * 64 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
         if (m >= M) continue;
         if (epi >= EPI_F32) {
-          float* c = (float*)G.C + (int64_t)m * G.ldc + n;
+          float* c = (float*)G.C + slice * G.cstride + (int64_t)m * G.ldc + n;
           *c = epi == EPI_F32_ADD ? *c + acc[i][j][v] : acc[i][j][v];
           continue;
         }
@@ -212,13 +224,17 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
   const int tiles_n = (G.N + LBN - 1) / LBN, tiles_m = (G.M + LBM - 1) / LBM;
   const int sm = tiles_n >= kSuper ? 1 : kSuper / tiles_n;       // tile rows per super-tile
   if (within >= sm * tiles_n) return;
-  const int tm = (gs - L.tile_start[gi]) * sm + within / tiles_n, tn = within % tiles_n;
-  if (tm >= tiles_m) return;
+  // a split K multiplies the tile rows: virtual row tmv = slice * tiles_m + tm
+  const int tmv = (gs - L.tile_start[gi]) * sm + within / tiles_n, tn = within % tiles_n;
+  if (tmv >= tiles_m * tm_slices(G)) return;
+  const int slice = tmv / tiles_m, tm = tmv - slice * tiles_m;
+  const int kofs = G.ksplit > 1 ? slice * G.klen : 0;
   const int m0 = tm * LBM, n0 = tn * LBN;
   const int kshift = DOTS ? G.K0 : 0;              // operand columns in front of A's own
-  const int M = G.M, N = G.N, K1 = G.K1, K = G.K1 + kshift;
-  const uint16_t* __restrict__ A = (const uint16_t*)G.A1;
-  const uint16_t* __restrict__ W = (const uint16_t*)G.W;
+  const int M = G.M, N = G.N;
+  const int K1 = G.ksplit > 1 ? min(G.klen, G.K1 - kofs) : G.K1, K = K1 + kshift;
+  const uint16_t* __restrict__ A = (const uint16_t*)G.A1 + kofs;
+  const uint16_t* __restrict__ W = (const uint16_t*)G.W + kofs;
   const int lda = G.lda1, ldw = G.ldw;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -379,7 +395,18 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
       y[0] = s0.x; y[1] = s0.y; y[2] = s0.z; y[3] = s0.w;
       y[4] = s1.x; y[5] = s1.y; y[6] = s1.z; y[7] = s1.w;
       if (epi >= EPI_F32) {
-        float* c = (float*)G.C + (int64_t)m * G.ldc + n;
+        float* c = (float*)G.C + slice * G.cstride + (int64_t)m * G.ldc + n;
+        if (n + 8 <= N && ((uintptr_t)c & 15) == 0) {
+          float4 lo = make_float4(y[0], y[1], y[2], y[3]), hi = make_float4(y[4], y[5], y[6], y[7]);
+          if (epi == EPI_F32_ADD) {
+            const float4 p0 = *(const float4*)c, p1 = *(const float4*)(c + 4);
+            lo.x += p0.x; lo.y += p0.y; lo.z += p0.z; lo.w += p0.w;
+            hi.x += p1.x; hi.y += p1.y; hi.z += p1.z; hi.w += p1.w;
+          }
+          *(float4*)c = lo;
+          *(float4*)(c + 4) = hi;
+          continue;
+        }
         for (int q = 0; q < 8 && n + q < N; ++q) c[q] = epi == EPI_F32_ADD ? c[q] + y[q] : y[q];
         continue;
       }
@@ -566,7 +593,7 @@ void launch_groups(const dmt_plan* p, std::vector<TmGroup>& groups, hipStream_t 
       if constexpr (DT == DMT_F32)
         tiles += (int32_t)(((int64_t)g.M * g.N + kBlock - 1) / kBlock);
       else
-        tiles += ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+        tiles += ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN) * tm_slices(g);
     }
     L.tile_start[L.ngroups] = tiles;
     if (tiles == 0) continue;
@@ -589,7 +616,8 @@ void launch_groups(const dmt_plan* p, std::vector<TmGroup>& groups, hipStream_t 
         int32_t nst = 0;                                      // super-tiles of the launch
         for (int i = 0; i < L.ngroups; ++i) {
           L.tile_start[i] = nst;
-          const int tn = (L.g[i].N + LBN - 1) / LBN, tm = (L.g[i].M + LBM - 1) / LBM;
+          const int tn = (L.g[i].N + LBN - 1) / LBN;
+          const int tm = (L.g[i].M + LBM - 1) / LBM * tm_slices(L.g[i]);
           const int sm = tn >= kSuper ? 1 : kSuper / tn;
           nst += (tm + sm - 1) / sm;
         }

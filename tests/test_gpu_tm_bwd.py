@@ -200,3 +200,73 @@ def test_rejects_bad_arguments():
         dmt.dmt_tower_module_bwd(dw.plan, tm.params, x, None, w.batch, dy, dx, arr, big)
     assert e.value.code == dmt.binding.DMT_EINVAL
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("which", ["tiny_f32", "mid_bf16"])
+def test_whole_tower_step_chains_into_the_sparse_update(which):
+    """lookup -> Tower Module -> (gradient of the module outputs) -> Tower Module backward ->
+    sorted segment-reduce + rowwise Adagrad, every stage fed by the previous one on the GPU,
+    against the same chain of oracles: the sparse update receives dL/d(pooled) as the module's
+    backward produced it."""
+    if which == "tiny_f32":
+        w, rtol = wl.tiny(), 1e-4
+    else:
+        w, rtol = wl.scaled(wl.mid(True), max_rows=20000, batch=301, num_tables=16), 3e-2
+    dw = DeviceWorkload(w, with_state=True)
+    tm = TowerModules(dw)
+    dmt = dw.dmt
+    B = w.batch
+    idx, off = wl.lookup_batch(w)
+    tables0 = [t.copy() for t in dw.host_tables]
+    st0 = [np.zeros(r, dtype=np.float32) for r in w.rows]
+    # GPU chain
+    x_dev = dw.lookup(idx, off, tm.dtype)
+    y_dev = tm.run(x_dev)
+    dy = wl.grad_tm_out(w)
+    if w.tm_kind == wl.TM_LINEAR_RELU:
+        pooled = oracle.lookup_towered(tables0, w.table_dtype, w.dims, w.table_to_tower, idx, off, B)
+        o = 0
+        for t in range(w.num_towers):
+            x64 = wl.decode(oracle.round_to(pooled[t], tm.dtype), tm.dtype)
+            pre = oracle.tm_linear(x64, tm.dec[t]["w_proj"], tm.dec[t]["b_proj"])
+            near = np.abs(pre) < 1e-3 * np.sqrt(np.mean(pre * pre))
+            dy[o:o + B * w.tm_out[t]].reshape(B, -1)[near] = 0.0
+            o += B * w.tm_out[t]
+    got_dx, _ = run_bwd(dw, tm, x_dev, y_dev, torch.from_numpy(dy).cuda())
+    d_idx, d_off = torch.from_numpy(idx).cuda(), torch.from_numpy(off).cuda()
+    ws = torch.empty(max(dmt.dmt_bwd_workspace_bytes(dw.plan, B, len(idx)), 256) // 8 + 32,
+                     dtype=torch.int64, device="cuda")
+    dx_dev = torch.from_numpy(got_dx.astype(np.float32)).cuda()
+    dmt.dmt_tower_lookup_bwd_update(dw.plan, d_idx, d_off, B, dx_dev, w.lr, w.eps, ws)
+    torch.cuda.synchronize()
+    assert dmt.dmt_last_device_error(dw.plan) == -1
+    # oracle chain
+    pooled = oracle.lookup_towered(tables0, w.table_dtype, w.dims, w.table_to_tower, idx, off, B)
+    tables_of = w.tower_tables()
+    ref_dx, o = [], 0
+    for t in range(w.num_towers):
+        x64 = wl.decode(oracle.round_to(pooled[t], tm.dtype), tm.dtype)
+        d = tm.dec[t]
+        dyt = dy[o:o + B * w.tm_out[t]].reshape(B, w.tm_out[t])
+        o += B * w.tm_out[t]
+        if w.tm_kind == wl.TM_DOT_LINEAR:
+            dx = tm_bwd.tm_dot_linear_bwd(x64, len(tables_of[t]), d["w_proj"], d["b_proj"], dyt)[0]
+        else:
+            dx = tm_bwd.tm_linear_bwd(x64, d["w_proj"], d["b_proj"], dyt,
+                                      relu=w.tm_kind == wl.TM_LINEAR_RELU)[0]
+        ref_dx.append(dx.astype(np.float32).reshape(-1))
+    ref = oracle.bwd_update(tables0, w.table_dtype, st0, w.dims, w.table_to_tower, idx, off, B,
+                            np.concatenate(ref_dx), w.lr, w.eps)
+    for f in range(w.num_tables):
+        m = ref["key_table"] == f
+        rows = ref["key_row"][m]
+        if not len(rows):
+            continue
+        sel = torch.from_numpy(rows).cuda()
+        want = ref["new_rows"][m][:, :w.dims[f]]
+        if w.table_dtype != "f32":
+            want = wl.decode(oracle.round_to(want, w.table_dtype), w.table_dtype)
+        assert_close(to_f64(dw.tables[f][sel]), want, max(rtol, RTOL[w.table_dtype]),
+                     "%s chained rows of table %d" % (w.name, f))
+        assert_close(to_f64(dw.states[f][sel]), ref["new_state"][m].astype(np.float32), rtol,
+                     "%s chained state of table %d" % (w.name, f))
