@@ -18,7 +18,8 @@ import torch
 
 import oracle
 import workloads as wl
-from harness import TORCH_DT, assert_close, oracle_tm, tm_device_and_decoded, to_f64
+from oracle import tm_bwd
+from harness import TORCH_DT, assert_close, assert_grad_close, oracle_tm, tm_device_and_decoded, to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -130,7 +131,9 @@ def _compact(rows_by_table, w):
     return tabs, remap
 
 
-def test_lookup_and_tower_module_on_sampled_samples(run):
+def _sampled_pooled(run):
+    """The oracle's pooled values of the sampled samples, per tower [S][W_t], from the table rows
+    fetched before the library ran."""
     w = run.w
     F, B, S = w.num_tables, w.batch, len(run.samples)
     tabs, remap = _compact(run.fwd_rows, w)
@@ -142,7 +145,13 @@ def test_lookup_and_tower_module_on_sampled_samples(run):
             ids.append(np.searchsorted(remap[f], seg))
     s_off = np.concatenate([[0], np.cumsum(lens)])
     s_idx = np.concatenate(ids).astype(np.int32)
-    ref = oracle.lookup_towered(tabs, w.table_dtype, w.dims, w.table_to_tower, s_idx, s_off, S)
+    return oracle.lookup_towered(tabs, w.table_dtype, w.dims, w.table_to_tower, s_idx, s_off, S)
+
+
+def test_lookup_and_tower_module_on_sampled_samples(run):
+    w = run.w
+    B = w.batch
+    ref = _sampled_pooled(run)
     sel = torch.from_numpy(run.samples).cuda()
     x = [wl.decode(oracle.round_to(r, w.pooled_dtype), w.pooled_dtype) for r in ref]
     y = oracle_tm(w, run.tm_dec, x)
@@ -234,3 +243,82 @@ def test_untouched_rows_and_states_are_bit_identical(run):
     # the number of rows with a non-zero state is exactly the number of distinct rows touched
     touched = sum(int(torch.count_nonzero(s).item()) for s in run.states)
     assert touched == len(run.uk)
+
+
+def test_tower_module_backward_on_sampled_samples(run):
+    """dmt_tower_module_bwd at the full batch, in two calls.  (1) A dense N(0,1) output gradient:
+    the input gradient of a sample depends on that sample alone, so the sampled samples' rows
+    are compared with the oracle's, and every bias gradient of the projection is the plain
+    batch sum of the gradient.  (2) The same gradient kept on the sampled samples only and zero
+    elsewhere: now every weight and bias gradient is a sum over the sampled samples, which the
+    oracle recomputes in full, and all other samples' input gradients are exactly zero."""
+    w = run.w
+    dmt = run.dmt
+    B, T = w.batch, w.num_towers
+    S = len(run.samples)
+    nl = w.tm_cross_layers if w.tm_kind == wl.TM_CROSS_LINEAR else 0
+    kin, tw = w.tm_in_dims(), w.tower_widths()
+    x = [wl.decode(oracle.round_to(r, w.pooled_dtype), w.pooled_dtype) for r in _sampled_pooled(run)]
+    params = dmt.make_tm_params(run._keep)
+    f32 = lambda *shape: torch.full(shape, float("nan"), dtype=torch.float32, device="cuda")
+    grads = [dict(dw_proj=f32(o, k), db_proj=f32(o), dw_cross=[f32(d, d) for _ in range(nl)],
+                  db_cross=[f32(d) for _ in range(nl)]) for o, k, d in zip(w.tm_out, kin, tw)]
+    arr = dmt.make_tm_grads(grads)
+    ws = torch.empty(dmt.dmt_tm_bwd_workspace_bytes(run.plan, params, B), dtype=torch.uint8, device="cuda")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(991)
+    dy = torch.randn(B * sum(w.tm_out), generator=g, device="cuda", dtype=torch.float32)
+    dx = f32(B * sum(tw))
+    sel = torch.from_numpy(run.samples).cuda()
+    rtol = 4e-2 if nl else 2e-2
+    tables_of = w.tower_tables()
+
+    def oracle_bwd(t, dyt):
+        d = run.tm_dec[t]
+        if w.tm_kind == wl.TM_DOT_LINEAR:
+            r = tm_bwd.tm_dot_linear_bwd(x[t], len(tables_of[t]), d["w_proj"], d["b_proj"], dyt)
+            return r[0], [], [], r[1], r[2]
+        if w.tm_kind == wl.TM_CROSS_LINEAR:
+            return tm_bwd.tm_cross_linear_bwd(x[t], d["w_cross"], d["b_cross"], d["w_proj"], d["b_proj"], dyt)
+        r = tm_bwd.tm_linear_bwd(x[t], d["w_proj"], d["b_proj"], dyt, relu=w.tm_kind == wl.TM_LINEAR_RELU)
+        return r[0], [], [], r[1], r[2]
+
+    # (1) dense gradient
+    dmt.dmt_tower_module_bwd(run.plan, params, run.pooled, run.tm_out, B, dy, dx, arr, ws)
+    torch.cuda.synchronize()
+    pos = ypos = 0
+    for t in range(T):
+        dyt = dy[ypos:ypos + B * w.tm_out[t]].reshape(B, -1)
+        ref = oracle_bwd(t, to_f64(dyt[sel]))
+        got = to_f64(dx[pos:pos + B * tw[t]].reshape(B, -1)[sel])
+        assert_grad_close(got, ref[0], rtol, "%s dense grad_pooled tower %d" % (w.name, t))
+        assert_grad_close(to_f64(grads[t]["db_proj"]), to_f64(dyt.to(torch.float64).sum(0)), 2e-2,
+                          "%s dense db_proj tower %d" % (w.name, t))
+        pos += B * tw[t]
+        ypos += B * w.tm_out[t]
+
+    # (2) gradient on the sampled samples only
+    keep = torch.zeros(B, dtype=torch.bool, device="cuda")
+    keep[sel] = True
+    ypos = 0
+    for t in range(T):
+        dy[ypos:ypos + B * w.tm_out[t]].reshape(B, -1)[~keep] = 0.0
+        ypos += B * w.tm_out[t]
+    dx.fill_(float("nan"))
+    dmt.dmt_tower_module_bwd(run.plan, params, run.pooled, run.tm_out, B, dy, dx, arr, ws)
+    torch.cuda.synchronize()
+    pos = ypos = 0
+    for t in range(T):
+        dyt = dy[ypos:ypos + B * w.tm_out[t]].reshape(B, -1)
+        rdx, rdWc, rdbc, rdW, rdb = oracle_bwd(t, to_f64(dyt[sel]))
+        dxt = dx[pos:pos + B * tw[t]].reshape(B, -1)
+        what = "%s sparse tower %d " % (w.name, t)
+        assert_grad_close(to_f64(dxt[sel]), rdx, rtol, what + "grad_pooled")
+        assert torch.count_nonzero(dxt[~keep]).item() == 0, what + "other samples' gradients"
+        assert_grad_close(to_f64(grads[t]["dw_proj"]), rdW, rtol, what + "dW_proj")
+        assert_grad_close(to_f64(grads[t]["db_proj"]), rdb, rtol, what + "db_proj")
+        for l in range(nl):
+            assert_grad_close(to_f64(grads[t]["dw_cross"][l]), rdWc[l], rtol, what + "dW_cross[%d]" % l)
+            assert_grad_close(to_f64(grads[t]["db_cross"][l]), rdbc[l], rtol, what + "db_cross[%d]" % l)
+        pos += B * tw[t]
+        ypos += B * w.tm_out[t]

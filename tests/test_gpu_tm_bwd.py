@@ -12,7 +12,8 @@ import torch
 import oracle
 from oracle import tm_bwd
 import workloads as wl
-from harness import RTOL, DeviceWorkload, TowerModules, assert_close, to_device, to_f64
+from harness import (RTOL, DeviceWorkload, TowerModules, assert_close, assert_grad_close, to_device,
+                     to_f64)
 
 pytestmark = pytest.mark.gpu
 
@@ -41,41 +42,6 @@ def run_bwd(dw, tm, x_dev, y_dev, dy_dev):
                  dw_cross=[to_f64(a) for a in g["dw_cross"]],
                  db_cross=[to_f64(a) for a in g["db_cross"]]) for g in grads]
     return to_f64(dx), host
-
-
-def assert_grad_close(got, ref, rtol, what):
-    """|got - ref| <= rtol (|ref| + scale) elementwise, and for the 16-bit types also
-    rms(got - ref) <= rtol / 4 * rms(ref).
-
-    Every product of a 16-bit contraction carries an independent rounding error of up to 2^-9
-    (bf16) per operand, so an output's error is a fraction of a percent of the magnitude of ITS
-    sum's terms.  For a matrix that is a sum of outer products (dW = dz^T x; dx = dz W) that
-    magnitude is the product of a row factor and a column factor, estimated here from the
-    reference as rowrms_i * colrms_j / rms; pooled sums of Zipf-length bags are heavy-tailed,
-    so single rows and columns sit far above the array's rms.  The largest error among millions
-    of outputs lies five sigma out, which the elementwise bound leaves room for; the rms bound
-    is the sharp one (a dropped term or a wrong operand moves it to order one)."""
-    got = np.asarray(got, dtype=np.float64)
-    ref = np.asarray(ref, dtype=np.float64)
-    assert got.shape == ref.shape, (what, got.shape, ref.shape)
-    if ref.size == 0:
-        return
-    rms = float(np.sqrt(np.mean(ref * ref)))
-    scale = rms
-    if ref.ndim == 2 and rms > 0:
-        scale = np.sqrt(np.mean(ref * ref, axis=1, keepdims=True)) * \
-            np.sqrt(np.mean(ref * ref, axis=0, keepdims=True)) / rms
-        scale = np.maximum(scale, rms)
-    err = np.abs(got - ref)
-    tol = rtol * (np.abs(ref) + scale)
-    bad = err > tol
-    if bad.any():
-        i = int(np.argmax(err - tol))
-        raise AssertionError("%s: %d of %d outside tolerance; worst at flat %d: got %r ref %r (rms %g)"
-                             % (what, int(bad.sum()), ref.size, i, got.flat[i], ref.flat[i], rms))
-    if rtol >= 1e-2:
-        e = float(np.sqrt(np.mean(err * err)))
-        assert e <= rtol / 4 * rms, "%s: rms error %g against rms %g" % (what, e, rms)
 
 
 def check_tm_bwd(w, rtol=None):
