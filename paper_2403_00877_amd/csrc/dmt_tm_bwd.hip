@@ -12,6 +12,7 @@
 // Towers are grouped into one launch per stage like the forward's.  The
 // forward's intermediates are recomputed (dot terms, u_l = W_l x_l + b_l, x_l).
 // Bias gradients are fixed-order row sums of the transposed gradient operand.
+#define DMT_TM_TAG 1          // this file's instances of the shared GEMM kernels
 #include "dmt_tm_gemm.h"
 
 namespace {

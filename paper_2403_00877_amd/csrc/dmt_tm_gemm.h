@@ -78,7 +78,13 @@ template <int DT> __device__ __forceinline__ void store_elt(void* p, int64_t i, 
 
 // ------------------------------------------------------------- MFMA grouped GEMM
 
-template <int DT>
+// TAG (here and below) only marks the including source file in the kernel's name, so that a
+// profile tells the forward's launches from the backward's.
+#ifndef DMT_TM_TAG
+#define DMT_TM_TAG 0
+#endif
+
+template <int DT, int TAG = DMT_TM_TAG>
 __global__ __launch_bounds__(kBlock, 2) void tm_gemm_mfma(const TmLaunch L) {
   __shared__ __attribute__((aligned(16))) uint16_t As[BM * kLdsStride];
   __shared__ __attribute__((aligned(16))) uint16_t Bs[BN * kLdsStride];
@@ -206,7 +212,7 @@ constexpr int kBigLdsBytes = 4 * kBigTileElems * 2;         // 2 stages x (A + B
 // DOTS: the operand's first K0 columns are the tower's pairwise dot terms, which the block
 // computes itself (Gram tiles, as in tm_dots_mfma) straight into the first LDS stage, so the
 // pooled tensor is read once and the dot terms never exist in global memory.
-template <int DT, bool DOTS>
+template <int DT, bool DOTS, int TAG = DMT_TM_TAG>
 __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunch L) {
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
   // XCD-aware rasterisation.  Consecutive block ids go to different XCDs, so block b belongs
@@ -443,7 +449,7 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
 
 // --------------------------------------------------- plain FMA GEMM (float32)
 
-template <int DT>
+template <int DT, int TAG = DMT_TM_TAG>
 __global__ __launch_bounds__(kBlock) void tm_gemm_simple(const TmLaunch L) {
   int gi = 0;
   while (gi + 1 < L.ngroups && (int)blockIdx.x >= L.tile_start[gi + 1]) ++gi;
