@@ -168,6 +168,21 @@ def tm_dot_linear(x, nf: int, W, b, return_z: bool = False):
     return (y, z) if return_z else y
 
 
+def tm_dlrm(x, nf: int, Wp, bp, Wf, bf) -> np.ndarray:
+    """The DLRM Tower Module (paper Sec. 4, Listing 1) on x [B, nf*n] = embs (B, |F|, N) flattened:
+    o1 = the flat embeddings through one Linear(N|F| -> pD); o2 = every feature's embedding
+    through ONE shared Linear(N -> cD); result = [o1 | o2 of feature 0 | o2 of feature 1 | ...],
+    O = pD + |F| cD columns.  Wp [pD, nf*n], Wf [cD, n]."""
+    x, Wp, bp, Wf, bf = _f64(x), _f64(Wp), _f64(bp), _f64(Wf), _f64(bf)
+    B, wt = x.shape
+    n = wt // nf
+    assert nf * n == wt and Wf.shape[1] == n
+    parts = [tm_linear(x, Wp, bp)]
+    for f in range(nf):
+        parts.append(tm_linear(x[:, f * n:(f + 1) * n], Wf, bf))
+    return np.concatenate(parts, axis=1)
+
+
 def cross_layer(x0, x, W, b) -> np.ndarray:
     x0, x, W, b = _f64(x0), _f64(x), _f64(W), _f64(b)
     B, d = x.shape

@@ -71,6 +71,32 @@ def tm_dot_linear_bwd(x, nf: int, W, b, dy) -> Tuple[np.ndarray, np.ndarray, np.
     return dX.reshape(B, wt), dW, db
 
 
+def tm_dlrm_bwd(x, nf: int, Wp, bp, Wf, bf, dy):
+    """y = [x Wp^T + bp | x_0 Wf^T + bf | ... | x_{F-1} Wf^T + bf] (Listing 1; x_f the f-th
+    feature's n columns of x).  Returns (dx, dWp, dbp, dWf, dbf).
+
+    The flat part is a linear layer of its own; the shared per-feature layer receives the sum
+    over features of each feature's linear-layer gradients, and dx is the sum of both paths.
+    """
+    x, Wp, bp, Wf, bf, dy = _f64(x), _f64(Wp), _f64(bp), _f64(Wf), _f64(bf), _f64(dy)
+    B, wt = x.shape
+    n = wt // nf
+    assert nf * n == wt
+    pD, cD = Wp.shape[0], Wf.shape[0]
+    assert dy.shape == (B, pD + nf * cD)
+    dx, dWp, dbp = tm_linear_bwd(x, Wp, bp, dy[:, :pD])
+    dx = dx.copy()
+    dWf = np.zeros_like(Wf)
+    dbf = np.zeros_like(bf)
+    for f in range(nf):
+        dyf = dy[:, pD + f * cD:pD + (f + 1) * cD]
+        dxf, dW, db = tm_linear_bwd(x[:, f * n:(f + 1) * n], Wf, bf, dyf)
+        dx[:, f * n:(f + 1) * n] += dxf
+        dWf += dW
+        dbf += db
+    return dx, dWp, dbp, dWf, dbf
+
+
 def tm_cross_linear_bwd(x, Wc: Sequence, bc: Sequence, W, b, dy):
     """x_{l+1} = x0 * (W_l x_l + b_l) + x_l for every cross layer (x_0 = x0 = x), y = x_L W^T + b
     (Listing 2; the full-rank DCN-v2 layer).  Returns (dx, [dW_l], [db_l], dW, db).

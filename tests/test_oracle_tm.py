@@ -107,3 +107,24 @@ def test_output_shapes_follow_the_listings():
     y = oracle.tm_cross_linear(x, [np.zeros((nf * n, nf * n))], [np.zeros(nf * n)],
                                np.zeros((nf * D, nf * n)), np.zeros(nf * D))
     assert y.shape == (B, nf * D)
+
+
+def test_dlrm_module_by_hand_and_against_einsum():
+    # Listing 1 with |F| = 2, N = 2, pD = 1, cD = 2 on x = (1, 2 | 3, 4):
+    # o1 = 1 + 2 + 3 + 4 + 0.5; feature 0: (1 - 2, 2*1 + 1); feature 1: (3 - 4, 2*3 + 1)
+    y = oracle.tm_dlrm([[1.0, 2.0, 3.0, 4.0]], 2, [[1.0, 1.0, 1.0, 1.0]], [0.5],
+                       [[1.0, -1.0], [2.0, 0.0]], [0.0, 1.0])
+    assert y.tolist() == [[10.5, -1.0, 3.0, -1.0, 7.0]]
+    rng = np.random.default_rng(11)
+    B, F, N, pD, cD = 5, 3, 4, 6, 2
+    x = rng.normal(size=(B, F * N))
+    Wp, bp = rng.normal(size=(pD, F * N)), rng.normal(size=pD)
+    Wf, bf = rng.normal(size=(cD, N)), rng.normal(size=cD)
+    y = oracle.tm_dlrm(x, F, Wp, bp, Wf, bf)
+    assert y.shape == (B, pD + F * cD)                       # O = D (c |F| + p)
+    assert np.allclose(y[:, :pD], x @ Wp.T + bp, rtol=0, atol=1e-12)
+    o2 = np.einsum("bfn,jn->bfj", x.reshape(B, F, N), Wf) + bf
+    assert np.allclose(y[:, pD:], o2.reshape(B, F * cD), rtol=0, atol=1e-12)
+    # without the per-feature branch (c = 0) it is the plain linear module
+    y0 = oracle.tm_dlrm(x, F, Wp, bp, np.zeros((0, N)), np.zeros(0))
+    assert np.array_equal(y0, oracle.tm_linear(x, Wp, bp))

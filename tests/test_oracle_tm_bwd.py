@@ -132,3 +132,29 @@ def test_cross_zero_weights_reduce_to_a_linear_layer():
     _close(dx, lx)
     _close(dW, lW)
     _close(db, lb)
+
+
+def test_dlrm_module_against_central_differences():
+    rng = np.random.default_rng(6)
+    B, F, N, pD, cD = 4, 3, 2, 3, 2
+    x = rng.normal(size=(B, F * N))
+    Wp, bp = rng.normal(size=(pD, F * N)), rng.normal(size=pD)
+    Wf, bf = rng.normal(size=(cD, N)), rng.normal(size=cD)
+    R = rng.normal(size=(B, pD + F * cD))
+    loss = lambda: float(np.sum(oracle.tm_dlrm(x, F, Wp, bp, Wf, bf) * R))
+    dx, dWp, dbp, dWf, dbf = tm_bwd.tm_dlrm_bwd(x, F, Wp, bp, Wf, bf, R)
+    _close(dx, _numeric_grad(loss, x))
+    _close(dWp, _numeric_grad(loss, Wp))
+    _close(dbp, _numeric_grad(loss, bp))
+    _close(dWf, _numeric_grad(loss, Wf))
+    _close(dbf, _numeric_grad(loss, bf))
+
+
+def test_dlrm_module_hand_computed_shared_weights():
+    # |F| = 2, N = 1, no flat outputs worth mentioning (pD = 1 with zero weight), cD = 1:
+    # y = (b, w x0 + c, w x1 + c); dy = (0, 2, 3): dw = 2 x0 + 3 x1, dc = 5, dx = (2 w, 3 w)
+    dx, dWp, dbp, dWf, dbf = tm_bwd.tm_dlrm_bwd([[4.0, 5.0]], 2, [[0.0, 0.0]], [1.0], [[7.0]], [0.5],
+                                                [[0.0, 2.0, 3.0]])
+    assert dx.tolist() == [[14.0, 21.0]]
+    assert dWf.tolist() == [[23.0]] and dbf.tolist() == [5.0]
+    assert dWp.tolist() == [[0.0, 0.0]] and dbp.tolist() == [0.0]
