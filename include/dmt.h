@@ -63,7 +63,10 @@ typedef enum {
   DMT_TM_LINEAR = 0,       /* y = W x + b            (Listing 1 with c = 0)                      */
   DMT_TM_LINEAR_RELU = 1,  /* y = max(0, W x + b)                                                 */
   DMT_TM_DOT_LINEAR = 2,   /* z = [pairwise dots (i<j) | x], y = W z + b  (Sec. 3.2, Sec. 4)      */
-  DMT_TM_CROSS_LINEAR = 3  /* x_{l+1} = x0 * (W_l x_l + b_l) + x_l, y = W x_L + b  (Listing 2)    */
+  DMT_TM_CROSS_LINEAR = 3, /* x_{l+1} = x0 * (W_l x_l + b_l) + x_l, y = W x_L + b  (Listing 2)    */
+  DMT_TM_DLRM = 4          /* y = [W x + b | W_f x_0 + b_f | ... | W_f x_{F-1} + b_f]: the flat
+                              projection next to ONE projection shared by every feature's
+                              embedding x_f  (Listing 1 with c > 0)                                */
 } dmt_tm_kind;
 
 #define DMT_MAX_CROSS_LAYERS 4
@@ -144,12 +147,17 @@ dmt_status dmt_tower_lookup_fwd(const dmt_plan* plan, const int32_t* indices,
  *                 the W_t pooled values]; w_proj [out_dim][nf(nf-1)/2 + W_t]
  *   CROSS_LINEAR: num_cross_layers full-rank layers w_cross[l] [W_t][W_t],
  *                 b_cross[l] [W_t], then w_proj [out_dim][W_t]
+ *   DLRM        : the tower's nf tables must share one dim n.  feat_out = c D
+ *                 outputs per feature from the shared layer w_cross[0] [feat_out][n],
+ *                 b_cross[0] [feat_out]; the first out_dim - nf * feat_out (>= 1)
+ *                 outputs from w_proj [out_dim - nf * feat_out][W_t], b_proj.
+ *                 num_cross_layers is ignored.
  */
 typedef struct {
   int32_t kind;              /* dmt_tm_kind */
   int32_t out_dim;           /* O_t */
   int32_t num_cross_layers;  /* CROSS_LINEAR only, <= DMT_MAX_CROSS_LAYERS */
-  int32_t reserved;
+  int32_t feat_out;          /* DLRM only: outputs of the per-feature layer (c D) */
   const void* w_proj;
   const void* b_proj;
   const void* w_cross[DMT_MAX_CROSS_LAYERS];
@@ -183,7 +191,9 @@ dmt_status dmt_tower_module_fwd(const dmt_plan* plan, const dmt_tm_params* per_t
 /*
  * Parameter gradients of one tower's Tower Module, all dev float32, row-major,
  * shaped like the parameters themselves (dw_proj [O_t][K_t] with K_t the row
- * length of w_proj; dw_cross[l] [W_t][W_t]; the db_* vectors).  Every array is
+ * length of w_proj; dw_cross[l] [W_t][W_t]; the db_* vectors; for a DLRM tower
+ * dw_proj has the flat layer's out_dim - nf * feat_out rows and dw_cross[0] /
+ * db_cross[0] receive the shared per-feature layer's [feat_out][n] / [feat_out]).  Every array is
  * overwritten, not accumulated into.  Caller-owned.
  */
 typedef struct {
@@ -206,6 +216,9 @@ size_t dmt_tm_bwd_workspace_bytes(const dmt_plan* plan, const dmt_tm_params* per
  *   dot + linear   dz = dy W over z = [dot terms | x]; dW = dy^T z; the flat part
  *                  of dz passes to x and each term (i, j) adds dz_ij x_j to dx_i
  *                  and dz_ij x_i to dx_j
+ *   DLRM           both layers are linear layers of their own: the shared per-feature
+ *                  layer's gradients are sums over the batch and over the features,
+ *                  and grad_pooled adds both paths
  *   cross + linear layers taken from the last to the first with
  *                  du_l = dx_{l+1} * x0, dx0 += dx_{l+1} * u_l, dW_l = du_l^T x_l,
  *                  db_l = sum_b du_l, dx_l = du_l W_l + dx_{l+1};

@@ -17,19 +17,20 @@ from . import build as _build
 
 DMT_OK, DMT_EINVAL, DMT_ENOTSUP, DMT_EBOUNDS, DMT_ENOMEM, DMT_EHIP = range(6)
 DMT_F32, DMT_F16, DMT_BF16 = 0, 1, 2
-DMT_TM_LINEAR, DMT_TM_LINEAR_RELU, DMT_TM_DOT_LINEAR, DMT_TM_CROSS_LINEAR = 0, 1, 2, 3
+DMT_TM_LINEAR, DMT_TM_LINEAR_RELU, DMT_TM_DOT_LINEAR, DMT_TM_CROSS_LINEAR, DMT_TM_DLRM = 0, 1, 2, 3, 4
 DMT_MAX_CROSS_LAYERS = 4
 
 DTYPE_CODE = {"f32": DMT_F32, "f16": DMT_F16, "bf16": DMT_BF16,
               torch.float32: DMT_F32, torch.float16: DMT_F16, torch.bfloat16: DMT_BF16}
 TORCH_DTYPE = {DMT_F32: torch.float32, DMT_F16: torch.float16, DMT_BF16: torch.bfloat16}
 TM_KIND_CODE = {"linear": DMT_TM_LINEAR, "linear_relu": DMT_TM_LINEAR_RELU,
-                "dot_linear": DMT_TM_DOT_LINEAR, "cross_linear": DMT_TM_CROSS_LINEAR}
+                "dot_linear": DMT_TM_DOT_LINEAR, "cross_linear": DMT_TM_CROSS_LINEAR,
+                "dlrm": DMT_TM_DLRM}
 
 
 class dmt_tm_params(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("out_dim", ctypes.c_int32),
-                ("num_cross_layers", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("num_cross_layers", ctypes.c_int32), ("feat_out", ctypes.c_int32),
                 ("w_proj", ctypes.c_void_p), ("b_proj", ctypes.c_void_p),
                 ("w_cross", ctypes.c_void_p * DMT_MAX_CROSS_LAYERS),
                 ("b_cross", ctypes.c_void_p * DMT_MAX_CROSS_LAYERS)]
@@ -180,13 +181,15 @@ def dmt_tower_lookup_fwd(plan: dmt_plan, indices: torch.Tensor, offsets: torch.T
 
 def make_tm_params(per_tower: Sequence[dict]):
     """per_tower: dicts with kind (str), out_dim, w_proj, b_proj and optionally
-    w_cross / b_cross (lists of tensors).  Returns a ctypes array."""
+    w_cross / b_cross (lists of tensors; for kind "dlrm" the one shared per-feature layer, with
+    feat_out its output count).  Returns a ctypes array."""
     arr = (dmt_tm_params * len(per_tower))()
     for a, p in zip(arr, per_tower):
         a.kind = TM_KIND_CODE[p["kind"]]
         a.out_dim = int(p["out_dim"])
         wc = p.get("w_cross") or []
         a.num_cross_layers = len(wc)
+        a.feat_out = int(p.get("feat_out") or 0)
         a.w_proj = p["w_proj"].data_ptr()
         a.b_proj = p["b_proj"].data_ptr()
         for l, (w, b) in enumerate(zip(wc, p.get("b_cross") or [])):

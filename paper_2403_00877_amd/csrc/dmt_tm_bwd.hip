@@ -54,7 +54,11 @@ __device__ __forceinline__ int tmb_find(const TmbLaunch& L) {
 
 // dz[b][o] = dy[b][o] (zero where ReLU was off: y[b][o] <= 0), rounded to DT, with
 // zero columns O .. Op-1; dzT[o][b] the same values transposed, zero for b in [B, Bp).
-// a = dy, b = y, o0 = dz, o1 = dzT, n0 = B, n1 = Bp, i0 = O, i1 = Op, i2 = relu.
+// Row b of dy (and y) starts at element b * ldy, or, with rdiv > 0, at
+// (b / rdiv) * ldy + (b % rdiv) * ld2: rdiv rows of the gradient operand lie side by side in
+// one row of the output gradient (a per-feature layer).
+// a = dy, b = y, o0 = dz, o1 = dzT, n0 = B, n1 = Bp, n2 = ldy, i0 = O, i1 = Op, i2 = relu,
+// i3 = rdiv, i4 = ld2.
 template <int DT>
 __global__ __launch_bounds__(kBlock) void tmb_prep_dy(const TmbLaunch L) {
   __shared__ float tile[kTile][kTile + 1];
@@ -72,8 +76,9 @@ __global__ __launch_bounds__(kBlock) void tmb_prep_dy(const TmbLaunch L) {
     const int o = o0 + tx;
     float v = 0.f;
     if (b < B && o < O) {
-      v = dy[b * O + o];
-      if (relu && !(load_elt<DT>(G.b, b * O + o) > 0.f)) v = 0.f;
+      const int64_t at = (G.i3 > 0 ? (b / G.i3) * G.n2 + (b % G.i3) * G.i4 : b * G.n2) + o;
+      v = dy[at];
+      if (relu && !(load_elt<DT>(G.b, at) > 0.f)) v = 0.f;
     }
     if (b < B && o < Op) store_elt<DT>(G.o0, b * Op + o, v);
     tile[r][tx] = v;
@@ -366,6 +371,10 @@ struct TowerBwdWs {
   size_t p = 0, wp = 0, dZ = 0;                                 // dot towers
   size_t xl[DMT_MAX_CROSS_LAYERS] = {}, u[DMT_MAX_CROSS_LAYERS] = {};   // cross towers
   size_t dxn = 0, du = 0, duT = 0, wlT = 0;
+  // DLRM towers: the shared per-feature layer's operands (rows = (sample, feature))
+  int64_t Fp = 0;              // feat_out padded to 8
+  size_t dz2 = 0, dz2T = 0, w2T = 0, x2T = 0, part2 = 0;
+  int ksplit2 = 1, klen2 = 0;
   size_t part = 0;             // weight-gradient slices (split K) / padded dW of a dot tower
   int ksplit = 1, klen = 0;    // of the projection's weight gradient
   int ksplit_c = 1, klen_c = 0;   // of the cross layers' weight gradients
@@ -425,16 +434,35 @@ dmt_status plan_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, in
         w.duT = take((size_t)wt * Bp * eb);
         w.wlT = take((size_t)wt * wt * eb);
         break;
+      case DMT_TM_DLRM: {
+        const int nf = p->tower_ntab[t], n = p->tower_uniform_dim[t];
+        if (n == 0) return DMT_ENOTSUP;
+        if (q.feat_out < 1 || (int64_t)q.out_dim - (int64_t)nf * q.feat_out < 1) return DMT_EINVAL;
+        if (!q.w_cross[0] || !q.b_cross[0] || ((uintptr_t)q.w_cross[0] & 15)) return DMT_EINVAL;
+        if (B * nf >= (1LL << 31) - 8) return DMT_ENOTSUP;
+        const int64_t BFp = up8(B * nf);
+        w.Fp = up8(q.feat_out);
+        w.dz2 = take((size_t)B * nf * w.Fp * eb);
+        w.dz2T = take((size_t)q.feat_out * BFp * eb);
+        w.w2T = take((size_t)n * w.Fp * eb);
+        w.x2T = take((size_t)n * BFp * eb);
+        if (eb == 2) choose_split(p->T, BFp, &w.ksplit2, &w.klen2);
+        if (w.ksplit2 > 1) w.part2 = take((size_t)w.ksplit2 * q.feat_out * n * 4);
+        break;
+      }
       default:
         return DMT_EINVAL;
     }
+    // rows of the projection's gradient operand: all outputs, or a DLRM tower's flat outputs
+    const int64_t O1 = q.kind == DMT_TM_DLRM ? q.out_dim - p->tower_ntab[t] * q.feat_out : q.out_dim;
+    w.Op = up8(O1);
     w.dz = take((size_t)B * w.Op * eb);
-    w.dzT = take((size_t)q.out_dim * Bp * eb);
+    w.dzT = take((size_t)O1 * Bp * eb);
     w.wT = take((size_t)w.kin * w.Op * eb);
     w.zT = take((size_t)w.kin * Bp * eb);
     size_t part = 0;
     if (w.ksplit > 1 || q.kind == DMT_TM_DOT_LINEAR)
-      part = (size_t)w.ksplit * q.out_dim * w.kin * 4;
+      part = (size_t)w.ksplit * O1 * w.kin * 4;
     if (q.kind == DMT_TM_CROSS_LINEAR && w.ksplit_c > 1)
       part = std::max(part, (size_t)w.ksplit_c * wt * wt * 4);
     if (part) w.part = take(part);
@@ -572,19 +600,22 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
   }
 
   // ---- projection: operands, bias gradient, then both contractions for all towers
-  std::vector<TmGroup> dgrad, wgrad;
+  std::vector<TmGroup> dgrad, dgrad2, wgrad, wgrad2;
   for (int32_t t = 0; t < p->T; ++t) {
     const dmt_tm_params& q = tp[t];
     const TowerBwdWs& w = ws[t];
-    const int wt = p->tower_width[t], O = q.out_dim;
+    const int wt = p->tower_width[t];
     const bool dot = q.kind == DMT_TM_DOT_LINEAR;
+    const bool dlrm = q.kind == DMT_TM_DLRM;
+    // outputs of the projection: all of the tower's, or a DLRM tower's flat ones
+    const int O = dlrm ? q.out_dim - p->tower_ntab[t] * q.feat_out : q.out_dim;
     {
       TmbItem it{};
       it.a = dy_all + (size_t)B * out_prefix[t];
       it.i2 = q.kind == DMT_TM_LINEAR_RELU;
       it.b = it.i2 ? (const void*)((const char*)tm_out + (size_t)B * out_prefix[t] * eb) : nullptr;
       it.o0 = wsp + w.dz; it.o1 = wsp + w.dzT;
-      it.n0 = B; it.n1 = Bp; it.i0 = O; it.i1 = (int32_t)w.Op;
+      it.n0 = B; it.n1 = Bp; it.n2 = q.out_dim; it.i0 = O; it.i1 = (int32_t)w.Op;
       it.nbx = (int32_t)((Bp + kTile - 1) / kTile);
       batch.add(it, (int64_t)it.nbx * ((w.Op + kTile - 1) / kTile));
     }
@@ -620,12 +651,50 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
     h.C = (dot || w.ksplit > 1) ? (void*)(wsp + w.part) : (void*)gr[t].dw_proj;
     h.ldc = w.kin;
     wgrad.push_back(h);
+    if (dlrm) {
+      // the shared per-feature layer: the same steps on rows (sample, feature); its data
+      // gradient lands on top of the flat layer's (second launch below)
+      const int nf = p->tower_ntab[t], n = p->tower_uniform_dim[t], F = q.feat_out;
+      const int64_t BF = B * nf, BFp = up8(BF);
+      {
+        TmbItem it{};
+        it.a = dy_all + (size_t)B * out_prefix[t] + O;
+        it.o0 = wsp + w.dz2; it.o1 = wsp + w.dz2T;
+        it.n0 = BF; it.n1 = BFp; it.n2 = q.out_dim; it.i0 = F; it.i1 = (int32_t)w.Fp;
+        it.i3 = nf; it.i4 = F;
+        it.nbx = (int32_t)((BFp + kTile - 1) / kTile);
+        batch.add(it, (int64_t)it.nbx * ((w.Fp + kTile - 1) / kTile));
+      }
+      {
+        TmbItem it{};
+        it.a = wsp + w.dz2T; it.o0 = gr[t].db_cross[0]; it.n0 = BFp; it.n1 = BF;
+        batch2.add(it, F);
+      }
+      add_transpose<DT>(batch3, q.w_cross[0], F, n, n, wsp + w.w2T, w.Fp);
+      add_transpose<DT>(batch3, x_of(t), BF, n, n, wsp + w.x2T, BFp);
+      TmGroup g2{};
+      g2.A1 = wsp + w.dz2; g2.lda1 = (int32_t)w.Fp; g2.K1 = (int32_t)w.Fp;
+      g2.W = wsp + w.w2T; g2.ldw = (int32_t)w.Fp;
+      g2.M = (int32_t)BF; g2.N = n; g2.epi = EPI_F32_ADD;
+      g2.C = dx_of(t); g2.ldc = n;
+      dgrad2.push_back(g2);
+      TmGroup h2{};
+      h2.A1 = wsp + w.dz2T; h2.lda1 = (int32_t)BFp; h2.K1 = (int32_t)BFp;
+      h2.W = wsp + w.x2T; h2.ldw = (int32_t)BFp;
+      h2.M = F; h2.N = n; h2.epi = EPI_F32;
+      h2.ksplit = w.ksplit2; h2.klen = w.klen2; h2.cstride = (int64_t)F * n;
+      h2.C = w.ksplit2 > 1 ? (void*)(wsp + w.part2) : (void*)gr[t].dw_cross[0];
+      h2.ldc = n;
+      wgrad2.push_back(h2);
+    }
   }
   ok &= launch_items(p, batch, tmb_prep_dy<DT>, s);
   ok &= launch_items(p, batch2, tmb_rowsum<DT>, s);
   ok &= launch_transposes<DT>(p, batch3, s);
   launch_groups<DT>(p, dgrad, s, false, DMT_K_TM_BWD_GEMM);
+  launch_groups<DT>(p, dgrad2, s, false, DMT_K_TM_BWD_GEMM);
   launch_groups<DT>(p, wgrad, s, false, DMT_K_TM_BWD_GEMM);
+  launch_groups<DT>(p, wgrad2, s, false, DMT_K_TM_BWD_GEMM);
 
   // ---- weight gradients: add up the slices, strip a dot tower's padding; dot towers: fold
   // the dot terms' gradients into dx
@@ -634,11 +703,19 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
     const TowerBwdWs& w = ws[t];
     const int wt = p->tower_width[t];
     const bool dot = q.kind == DMT_TM_DOT_LINEAR;
+    const int O = q.kind == DMT_TM_DLRM ? q.out_dim - p->tower_ntab[t] * q.feat_out : q.out_dim;
     if (dot || w.ksplit > 1) {
       TmbItem it{};
-      it.a = wsp + w.part; it.o0 = gr[t].dw_proj; it.n0 = (int64_t)q.out_dim * w.kin;
-      it.i0 = q.out_dim; it.i1 = w.np; it.i2 = w.np_pad; it.i3 = wt; it.i4 = w.ksplit;
-      batch.add(it, ((int64_t)q.out_dim * (w.np + wt) + kBlock - 1) / kBlock);
+      it.a = wsp + w.part; it.o0 = gr[t].dw_proj; it.n0 = (int64_t)O * w.kin;
+      it.i0 = O; it.i1 = w.np; it.i2 = w.np_pad; it.i3 = wt; it.i4 = w.ksplit;
+      batch.add(it, ((int64_t)O * (w.np + wt) + kBlock - 1) / kBlock);
+    }
+    if (q.kind == DMT_TM_DLRM && w.ksplit2 > 1) {
+      const int n = p->tower_uniform_dim[t];
+      TmbItem it{};
+      it.a = wsp + w.part2; it.o0 = gr[t].dw_cross[0]; it.n0 = (int64_t)q.feat_out * n;
+      it.i0 = q.feat_out; it.i1 = 0; it.i2 = 0; it.i3 = n; it.i4 = w.ksplit2;
+      batch.add(it, ((int64_t)q.feat_out * n + kBlock - 1) / kBlock);
     }
     if (dot) {
       TmbItem it{};
@@ -739,6 +816,7 @@ extern "C" dmt_status dmt_tower_module_bwd(const dmt_plan* plan, const dmt_tm_pa
     if (q.kind == DMT_TM_CROSS_LINEAR)
       for (int l = 0; l < q.num_cross_layers && l < DMT_MAX_CROSS_LAYERS; ++l)
         if (!grads[t].dw_cross[l] || !grads[t].db_cross[l]) return DMT_EINVAL;
+    if (q.kind == DMT_TM_DLRM && (!grads[t].dw_cross[0] || !grads[t].db_cross[0])) return DMT_EINVAL;
   }
   std::vector<TowerBwdWs> ws;
   size_t bytes = 0;

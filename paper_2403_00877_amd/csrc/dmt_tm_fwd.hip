@@ -7,6 +7,9 @@
 //                  [z_p | x]                                      (Sec. 3.2, Sec. 4)
 //   cross + linear x_{l+1} = x0 * (W_l x_l + b_l) + x_l, then a projection
 //                                                                 (Listing 2)
+//   DLRM           the flat projection next to one projection shared by every
+//                  feature's embedding: a second contraction over the pooled block
+//                  viewed as [B * features][dim]                  (Listing 1, c > 0)
 // 16-bit types run on MFMA (v_mfma_f32_32x32x16, float32 accumulate): block tile
 // 128 x 128 x 64, four waves of 64 x 64, operands staged through padded LDS, the
 // next K tile prefetched into registers while the current one is multiplied.
@@ -60,6 +63,14 @@ dmt_status plan_tm(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, int eb
         w.x_off[0] = take((size_t)B * wt * eb);
         if (q.num_cross_layers > 1) w.x_off[1] = take((size_t)B * wt * eb);
         break;
+      case DMT_TM_DLRM: {
+        const int nf = p->tower_ntab[t];
+        if (p->tower_uniform_dim[t] == 0) return DMT_ENOTSUP;   // one shared layer needs one dim
+        if (q.feat_out < 1 || (int64_t)q.out_dim - (int64_t)nf * q.feat_out < 1) return DMT_EINVAL;
+        if (!q.w_cross[0] || !q.b_cross[0] || ((uintptr_t)q.w_cross[0] & 15)) return DMT_EINVAL;
+        if (B * nf >= (1LL << 31)) return DMT_ENOTSUP;
+        break;
+      }
       default:
         return DMT_EINVAL;
     }
@@ -143,7 +154,7 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
   }
 
   // projections of every tower
-  std::vector<TmGroup> groups_fused;
+  std::vector<TmGroup> groups_fused, groups_feat;
   for (int32_t t = 0; t < p->T; ++t) {
     const dmt_tm_params& q = tp[t];
     const int wt = p->tower_width[t];
@@ -163,6 +174,19 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
     g.C = y_all + (size_t)B * out_prefix[t] * eb; g.ldc = q.out_dim;
     g.M = (int32_t)B; g.N = q.out_dim;
     g.epi = q.kind == DMT_TM_LINEAR_RELU ? EPI_BIAS_RELU : EPI_BIAS;
+    if (q.kind == DMT_TM_DLRM) {
+      // the shared per-feature layer: rows (sample, feature) of the pooled block, whose outputs
+      // go behind the flat layer's in the sample's output row
+      const int nf = p->tower_ntab[t], n = p->tower_uniform_dim[t];
+      g.N = q.out_dim - nf * q.feat_out;
+      TmGroup h{};
+      h.A1 = x; h.lda1 = n; h.K1 = n;
+      h.W = q.w_cross[0]; h.ldw = n; h.bias = q.b_cross[0];
+      h.C = y_all + ((size_t)B * out_prefix[t] + g.N) * eb;
+      h.ldc = q.out_dim; h.rdiv = nf; h.ldc2 = q.feat_out;
+      h.M = (int32_t)(B * nf); h.N = q.feat_out; h.epi = EPI_BIAS;
+      groups_feat.push_back(h);
+    }
     if (fused[t]) {
       g.A0 = nullptr; g.lda0 = 0;
       g.nf = p->tower_ntab[t]; g.fdim = p->tower_uniform_dim[t];
@@ -172,6 +196,7 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
     }
   }
   launch_groups<DT>(p, groups, s);
+  launch_groups<DT>(p, groups_feat, s);
   if constexpr (DT != DMT_F32) launch_groups<DT>(p, groups_fused, s, true);
   return hipGetLastError() == hipSuccess ? DMT_OK : DMT_EHIP;
 }

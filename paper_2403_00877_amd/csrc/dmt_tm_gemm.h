@@ -44,7 +44,16 @@ struct TmGroup {
   // C + s * cstride floats, and the caller adds the slices up in a fixed order.
   int32_t ksplit, klen;
   int64_t cstride;
+  // Two-level output rows (128 x 128 and plain kernels only): with rdiv > 0 row m of C starts at
+  // (m / rdiv) * ldc + (m % rdiv) * ldc2, i.e. rdiv consecutive rows of the contraction share
+  // one row of the output tensor.
+  int32_t rdiv, ldc2;
 };
+
+__device__ __forceinline__ int64_t tm_crow(const TmGroup& g, int m) {
+  return g.rdiv > 0 ? (int64_t)(m / g.rdiv) * g.ldc + (int64_t)(m % g.rdiv) * g.ldc2
+                    : (int64_t)m * g.ldc;
+}
 
 __host__ __device__ inline int tm_slices(const TmGroup& g) { return g.ksplit > 1 ? g.ksplit : 1; }
 
@@ -179,7 +188,7 @@ __global__ __launch_bounds__(kBlock, 2) void tm_gemm_mfma(const TmLaunch L) {
         const int m = m0 + wm * 64 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
         if (m >= M) continue;
         if (epi >= EPI_F32) {
-          float* c = (float*)G.C + slice * G.cstride + (int64_t)m * G.ldc + n;
+          float* c = (float*)G.C + slice * G.cstride + tm_crow(G, m) + n;
           *c = epi == EPI_F32_ADD ? *c + acc[i][j][v] : acc[i][j][v];
           continue;
         }
@@ -187,7 +196,7 @@ __global__ __launch_bounds__(kBlock, 2) void tm_gemm_mfma(const TmLaunch L) {
         if (epi == EPI_BIAS_RELU) y = y > 0.f ? y : 0.f;
         if (epi == EPI_CROSS)
           y = load_elt<DT>(G.X0, (int64_t)m * G.ldx + n) * y + load_elt<DT>(G.A1, (int64_t)m * lda1 + n);
-        store_elt<DT>(G.C, (int64_t)m * G.ldc + n, y);
+        store_elt<DT>(G.C, tm_crow(G, m) + n, y);
       }
     }
   }
@@ -464,7 +473,7 @@ __global__ __launch_bounds__(kBlock) void tm_gemm_simple(const TmLaunch L) {
     s += load_elt<DT>(G.A1, (int64_t)m * G.lda1 + k) *
          load_elt<DT>(G.W, (int64_t)n * G.ldw + G.K0 + k);
   if (G.epi >= EPI_F32) {
-    float* c = (float*)G.C + (int64_t)m * G.ldc + n;
+    float* c = (float*)G.C + tm_crow(G, m) + n;
     *c = G.epi == EPI_F32_ADD ? *c + s : s;
     return;
   }
@@ -472,7 +481,7 @@ __global__ __launch_bounds__(kBlock) void tm_gemm_simple(const TmLaunch L) {
   if (G.epi == EPI_BIAS_RELU) y = y > 0.f ? y : 0.f;
   if (G.epi == EPI_CROSS)
     y = load_elt<DT>(G.X0, (int64_t)m * G.ldx + n) * y + load_elt<DT>(G.A1, (int64_t)m * G.lda1 + n);
-  store_elt<DT>(G.C, (int64_t)m * G.ldc + n, y);
+  store_elt<DT>(G.C, tm_crow(G, m) + n, y);
 }
 
 // ------------------------------------------------------------ pairwise dot terms
@@ -581,7 +590,7 @@ __global__ __launch_bounds__(kBlock) void tm_pack_w(const TmAuxLaunch L) {
 
 // Whether a group can go to the 256 x 256 kernel (dots: with in-kernel dot terms).
 inline bool big_ok(const TmGroup& g, bool dots) {
-  return g.N > 128 && g.N <= kSuper * LBN && g.K1 >= 128 && (dots || g.K0 == 0) &&
+  return g.N > 128 && g.N <= kSuper * LBN && g.K1 >= 128 && (dots || g.K0 == 0) && g.rdiv == 0 &&
          (int64_t)g.M * g.lda1 < (1LL << 31) && (int64_t)g.N * g.ldw < (1LL << 31);
 }
 

@@ -132,7 +132,8 @@ class TowerModules:
             enc = lambda a: wl.encode(a, self.dtype)
             dev = lambda a: to_device(enc(a), self.dtype)
             d = dict(kind=w.tm_kind, out_dim=w.tm_out[t], w_proj=dev(hw["w_proj"]), b_proj=dev(hw["b_proj"]),
-                     w_cross=[dev(a) for a in hw["w_cross"]], b_cross=[dev(a) for a in hw["b_cross"]])
+                     w_cross=[dev(a) for a in hw["w_cross"]], b_cross=[dev(a) for a in hw["b_cross"]],
+                     feat_out=w.tm_feat_out)
             self.keep.append(d)
             per_tower.append(d)
             dd = lambda a: wl.decode(enc(a), self.dtype)
@@ -165,7 +166,8 @@ def tm_device_and_decoded(w, dtype=None):
         dev = lambda a: to_device(enc(a), dtype)
         dd = lambda a: wl.decode(enc(a), dtype)
         dev_list.append(dict(kind=w.tm_kind, out_dim=w.tm_out[t], w_proj=dev(hw["w_proj"]), b_proj=dev(hw["b_proj"]),
-                             w_cross=[dev(a) for a in hw["w_cross"]], b_cross=[dev(a) for a in hw["b_cross"]]))
+                             w_cross=[dev(a) for a in hw["w_cross"]], b_cross=[dev(a) for a in hw["b_cross"]],
+                             feat_out=w.tm_feat_out))
         dec_list.append(dict(w_proj=dd(hw["w_proj"]), b_proj=dd(hw["b_proj"]),
                              w_cross=[dd(a) for a in hw["w_cross"]], b_cross=[dd(a) for a in hw["b_cross"]]))
     return dev_list, dec_list
@@ -185,6 +187,9 @@ def oracle_tm(w, dec, x_towers, towers=None):
             elif w.tm_kind == wl.TM_DOT_LINEAR:
                 y = oracle.tm_dot_linear(x, len(w.tower_tables()[t if towers is None else towers[t]]),
                                          d["w_proj"], d["b_proj"])
+            elif w.tm_kind == wl.TM_DLRM:
+                y = oracle.tm_dlrm(x, len(w.tower_tables()[t if towers is None else towers[t]]),
+                                   d["w_proj"], d["b_proj"], d["w_cross"][0], d["b_cross"][0])
             else:
                 y = oracle.tm_cross_linear(x, d["w_cross"], d["b_cross"], d["w_proj"], d["b_proj"])
             ys.append(y)

@@ -105,3 +105,26 @@ def test_cross_with_three_layers_and_narrow_tower():
     w.tm_out = [96]
     w.tm_cross_layers = 3
     check_tm(w)                                       # 384-wide cross layers, 96-wide projection
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16", "f32"])
+def test_dlrm_module_flat_and_shared_per_feature_projection(dt):
+    """Listing 1 with c > 0: 2 towers x 8 features x 128, flat 1024 -> 200 next to the shared
+    128 -> 24 applied to every feature (200 + 8 * 24 = 392 outputs); batch 301."""
+    w = wl.scaled(wl.mid(), max_rows=3000, batch=301, num_tables=16)
+    w.tm_kind = wl.TM_DLRM
+    w.tm_feat_out = 24
+    w.tm_out = [200 + 8 * 24] * 2
+    w.tm_dtype = dt
+    w.pooled_dtype = dt
+    check_tm(w, chained=dt == "bf16")
+
+
+def test_dlrm_module_odd_widths():
+    # 3 features per tower, 20 flat outputs, 5 per feature: nothing is a multiple of 8
+    w = wl.scaled(wl.mid(), max_rows=500, batch=77, num_tables=6)
+    w.table_to_tower = [0, 0, 0, 1, 1, 1]
+    w.tm_kind = wl.TM_DLRM
+    w.tm_feat_out = 5
+    w.tm_out = [20 + 3 * 5] * 2
+    check_tm(w)

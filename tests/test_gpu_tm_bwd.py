@@ -28,6 +28,12 @@ def run_bwd(dw, tm, x_dev, y_dev, dy_dev):
     for t, kin in enumerate(w.tm_in_dims()):
         L = w.tm_cross_layers if w.tm_kind == wl.TM_CROSS_LINEAR else 0
         f = lambda *shape: torch.full(shape, nan, dtype=torch.float32, device="cuda")
+        if w.tm_kind == wl.TM_DLRM:
+            nf = len(w.tower_tables()[t])
+            o_proj = w.tm_out[t] - nf * w.tm_feat_out
+            grads.append(dict(dw_proj=f(o_proj, kin), db_proj=f(o_proj),
+                              dw_cross=[f(w.tm_feat_out, widths[t] // nf)], db_cross=[f(w.tm_feat_out)]))
+            continue
         grads.append(dict(dw_proj=f(w.tm_out[t], kin), db_proj=f(w.tm_out[t]),
                           dw_cross=[f(widths[t], widths[t]) for _ in range(L)],
                           db_cross=[f(widths[t]) for _ in range(L)]))
@@ -76,6 +82,11 @@ def check_tm_bwd(w, rtol=None):
                                               relu=w.tm_kind == wl.TM_LINEAR_RELU)
         elif w.tm_kind == wl.TM_DOT_LINEAR:
             dx, dW, db = tm_bwd.tm_dot_linear_bwd(x64[t], len(tables[t]), d["w_proj"], d["b_proj"], dys[t])
+        elif w.tm_kind == wl.TM_DLRM:
+            dx, dW, db, dWf, dbf = tm_bwd.tm_dlrm_bwd(x64[t], len(tables[t]), d["w_proj"], d["b_proj"],
+                                                      d["w_cross"][0], d["b_cross"][0], dys[t])
+            assert_grad_close(got[t]["dw_cross"][0], dWf, rtol, what + "dW_feat")
+            assert_grad_close(got[t]["db_cross"][0], dbf, rtol, what + "db_feat")
         else:
             dx, dWc, dbc, dW, db = tm_bwd.tm_cross_linear_bwd(x64[t], d["w_cross"], d["b_cross"],
                                                               d["w_proj"], d["b_proj"], dys[t])
@@ -143,6 +154,27 @@ def test_cross_three_layers_narrow_tower_f32_and_bf16():
         w.tm_dtype = dt
         w.pooled_dtype = dt
         check_tm_bwd(w, rtol)
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16", "f32"])
+def test_dlrm_module_flat_and_shared_per_feature_projection(dt):
+    # 2 towers x 8 features x 128: flat 1024 -> 200 next to the shared 128 -> 24 (392 outputs)
+    w = wl.scaled(wl.mid(), max_rows=3000, batch=301, num_tables=16)
+    w.tm_kind = wl.TM_DLRM
+    w.tm_feat_out = 24
+    w.tm_out = [200 + 8 * 24] * 2
+    w.tm_dtype = dt
+    w.pooled_dtype = dt
+    check_tm_bwd(w)
+
+
+def test_dlrm_module_odd_widths():
+    w = wl.scaled(wl.mid(), max_rows=500, batch=77, num_tables=6)
+    w.table_to_tower = [0, 0, 0, 1, 1, 1]
+    w.tm_kind = wl.TM_DLRM
+    w.tm_feat_out = 5
+    w.tm_out = [20 + 3 * 5] * 2
+    check_tm_bwd(w)
 
 
 def test_rejects_bad_arguments():

@@ -26,8 +26,8 @@ _S_ROWS, _S_DIMS, _S_LEN, _S_RANK, _S_PERM, _S_TABLE, _S_GRAD, _S_TM, _S_GRAD_TM
 F32, F16, BF16 = "f32", "f16", "bf16"
 ELT_BYTES = {F32: 4, F16: 2, BF16: 2}
 
-TM_LINEAR, TM_LINEAR_RELU, TM_DOT_LINEAR, TM_CROSS_LINEAR = (
-    "linear", "linear_relu", "dot_linear", "cross_linear")
+TM_LINEAR, TM_LINEAR_RELU, TM_DOT_LINEAR, TM_CROSS_LINEAR, TM_DLRM = (
+    "linear", "linear_relu", "dot_linear", "cross_linear", "dlrm")
 
 
 @dataclasses.dataclass
@@ -53,6 +53,8 @@ class Workload:
     lr: float = 0.01
     eps: float = 1e-8
     table_std: float = 0.01
+    tm_feat_out: int = 0            # TM_DLRM: outputs of the shared per-feature layer (c D);
+                                    # tm_out[t] = p D + (tables of tower t) * tm_feat_out
 
     @property
     def num_tables(self) -> int:
@@ -359,10 +361,19 @@ def tm_weights(w: Workload):
             s = 1.0 / math.sqrt(d)
             wc.append(rng.uniform(-s, s, size=(d, d)).astype(np.float32))
             bc.append(rng.uniform(-s, s, size=d).astype(np.float32))
+        o_proj = w.tm_out[t]
+        if w.tm_kind == TM_DLRM:
+            # the shared per-feature layer rides in the w_cross / b_cross slot 0
+            nf = len(w.tower_tables()[t])
+            n = d // nf
+            s = 1.0 / math.sqrt(n)
+            wc.append(rng.uniform(-s, s, size=(w.tm_feat_out, n)).astype(np.float32))
+            bc.append(rng.uniform(-s, s, size=w.tm_feat_out).astype(np.float32))
+            o_proj = w.tm_out[t] - nf * w.tm_feat_out
         s = 1.0 / math.sqrt(kin)
         out.append(dict(
-            w_proj=rng.uniform(-s, s, size=(w.tm_out[t], kin)).astype(np.float32),
-            b_proj=rng.uniform(-s, s, size=w.tm_out[t]).astype(np.float32),
+            w_proj=rng.uniform(-s, s, size=(o_proj, kin)).astype(np.float32),
+            b_proj=rng.uniform(-s, s, size=o_proj).astype(np.float32),
             w_cross=wc, b_cross=bc))
     return out
 
