@@ -135,7 +135,8 @@ def main():
     tm_dev = [dict(kind=w.tm_kind, out_dim=w.tm_out[t], w_proj=dev(h["w_proj"], w.tm_dtype),
                    b_proj=dev(h["b_proj"], w.tm_dtype),
                    w_cross=[dev(a, w.tm_dtype) for a in h["w_cross"]],
-                   b_cross=[dev(a, w.tm_dtype) for a in h["b_cross"]]) for t, h in enumerate(tm_host)]
+                   b_cross=[dev(a, w.tm_dtype) for a in h["b_cross"]], feat_out=w.tm_feat_out)
+              for t, h in enumerate(tm_host)]
     if not default:
         tm_host = None
     tm_params = dmt.make_tm_params(tm_dev)
@@ -220,6 +221,9 @@ def main():
     tw = w.tower_widths()
     nl = w.tm_cross_layers if w.tm_kind == wl.TM_CROSS_LINEAR else 0
     tm_flops = sum(2.0 * B * (o * k + nl * d * d) for o, k, d in zip(w.tm_out, kin, tw))
+    if w.tm_kind == wl.TM_DLRM:      # flat layer over W_t, shared layer over one feature's dim
+        tm_flops = sum(2.0 * B * ((o - len(fs) * w.tm_feat_out) * d + w.tm_feat_out * d)
+                       for o, d, fs in zip(w.tm_out, tw, w.tower_tables()))
     tm_bytes = sum(B * (d * eo * (1 + 3 * nl) + o * eo) + (o * k + nl * d * d) * eo
                    for o, k, d in zip(w.tm_out, kin, tw))
     kernels = {}
@@ -264,6 +268,8 @@ def main():
     names = {"backward": "backward (Mid tables and lookups: lookup fwd + dot-product TM fwd + sorted "
                          "segment-reduce bwd + rowwise Adagrad)",
              "mid": "mid (lookup fwd + dot-product TM fwd)",
+             "mid_dlrm": "mid tables (lookup fwd + DLRM TM fwd: flat 1024 -> 128 next to a shared 128 -> 32 "
+                         "per feature)",
              "large": "large (lookup fwd + 2 cross layers + projection TM fwd)",
              "imbalanced": "imbalanced (lookup fwd + linear TM fwd + bwd + rowwise Adagrad)",
              "tiny": "tiny"}
@@ -300,6 +306,10 @@ def time_tm_bwd(torch, dmt, wl, w, plan, tm_params, pooled, tm_out, B, steps):
     f32 = lambda *shape: torch.empty(shape, dtype=torch.float32, device="cuda")
     grads = [dict(dw_proj=f32(o, k), db_proj=f32(o), dw_cross=[f32(d, d) for _ in range(nl)],
                   db_cross=[f32(d) for _ in range(nl)]) for o, k, d in zip(w.tm_out, kin, tw)]
+    if w.tm_kind == wl.TM_DLRM:
+        grads = [dict(dw_proj=f32(o - len(fs) * w.tm_feat_out, d), db_proj=f32(o - len(fs) * w.tm_feat_out),
+                      dw_cross=[f32(w.tm_feat_out, d // len(fs))], db_cross=[f32(w.tm_feat_out)])
+                 for o, d, fs in zip(w.tm_out, tw, w.tower_tables())]
     arr = dmt.make_tm_grads(grads)
     ws = torch.empty(dmt.dmt_tm_bwd_workspace_bytes(plan, tm_params, B), dtype=torch.uint8, device="cuda")
     g = torch.Generator(device="cuda")
@@ -322,6 +332,9 @@ def time_tm_bwd(torch, dmt, wl, w, plan, tm_params, pooled, tm_out, B, steps):
     prof = dmt.dmt_profile_read(plan)
     dmt.dmt_profile_enable(plan, 0)
     flops = sum(2.0 * B * (2 * o * k + 3 * nl * d * d) for o, k, d in zip(w.tm_out, kin, tw))
+    if w.tm_kind == wl.TM_DLRM:
+        flops = sum(4.0 * B * ((o - len(fs) * w.tm_feat_out) * d + w.tm_feat_out * d)
+                    for o, d, fs in zip(w.tm_out, tw, w.tower_tables()))
     gemm_ms = prof.get("tm_bwd_gemm", (0.0, 0))[0] / n
     return dict(ms_per_call=round(ms, 4), workspace_GB=round(ws.numel() / 1e9, 3),
                 kernels={k: dict(ms_per_call=round(v[0] / n, 4), launches_per_call=v[1] // n)

@@ -155,8 +155,19 @@ def imbalanced() -> Workload:
         tm_cross_layers=0, pooled_dtype=F16, tm_dtype=F16, backward=True)
 
 
+def mid_dlrm() -> Workload:
+    """Mid's tables and lookups under the DLRM Tower Module of Listing 1 with D = 32 (= N / 4),
+    c = 1, p = 4: per tower 8 x 32 per-feature outputs next to 128 flat ones."""
+    w = mid()
+    w.name = "mid_dlrm"
+    w.tm_kind = TM_DLRM
+    w.tm_feat_out = 32
+    w.tm_out = [4 * 32 + 8 * 32] * 8
+    return w
+
+
 def by_name(name: str) -> Workload:
-    return {"tiny": tiny, "mid": mid, "large": large,
+    return {"tiny": tiny, "mid": mid, "large": large, "mid_dlrm": mid_dlrm,
             "backward": lambda: mid(True), "imbalanced": imbalanced}[name]()
 
 
