@@ -42,7 +42,7 @@ def assert_close(got: np.ndarray, ref: np.ndarray, rtol: float, what: str = ""):
                              % (what, int(bad.sum()), ref.size, i, got.flat[i], ref.flat[i], rms))
 
 
-def assert_grad_close(got, ref, rtol, what):
+def assert_grad_close(got, ref, rtol, what, scale=None):
     """|got - ref| <= rtol (|ref| + scale) elementwise, and for the 16-bit types also
     rms(got - ref) <= rtol / 4 * rms(ref).
 
@@ -53,18 +53,25 @@ def assert_grad_close(got, ref, rtol, what):
     reference as rowrms_i * colrms_j / rms; pooled sums of Zipf-length bags are heavy-tailed,
     so single rows and columns sit far above the array's rms.  The largest error among millions
     of outputs lies five sigma out, which the elementwise bound leaves room for; the rms bound
-    is the sharp one (a dropped term or a wrong operand moves it to order one)."""
+    is the sharp one (a dropped term or a wrong operand moves it to order one).
+    `scale`, when given, is the magnitude of each output's terms themselves (sum of |term|), for
+    sums whose terms cancel (a bias gradient over a batch of one or two)."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert got.shape == ref.shape, (what, got.shape, ref.shape)
     if ref.size == 0:
         return
     rms = float(np.sqrt(np.mean(ref * ref)))
-    scale = rms
-    if ref.ndim == 2 and rms > 0:
+    rms_bound = rms
+    if scale is not None:
+        scale = np.maximum(np.asarray(scale, dtype=np.float64), rms)
+        rms_bound = float(np.sqrt(np.mean(scale * scale)))
+    elif ref.ndim == 2 and rms > 0:
         scale = np.sqrt(np.mean(ref * ref, axis=1, keepdims=True)) * \
             np.sqrt(np.mean(ref * ref, axis=0, keepdims=True)) / rms
         scale = np.maximum(scale, rms)
+    else:
+        scale = rms
     err = np.abs(got - ref)
     tol = rtol * (np.abs(ref) + scale)
     bad = err > tol
@@ -74,7 +81,7 @@ def assert_grad_close(got, ref, rtol, what):
                              % (what, int(bad.sum()), ref.size, i, got.flat[i], ref.flat[i], rms))
     if rtol >= 1e-2:
         e = float(np.sqrt(np.mean(err * err)))
-        assert e <= rtol / 4 * rms, "%s: rms error %g against rms %g" % (what, e, rms)
+        assert e <= rtol / 4 * rms_bound, "%s: rms error %g against %g" % (what, e, rms_bound)
 
 
 class DeviceWorkload:
