@@ -191,7 +191,7 @@ def main():
     # ---- Tower Module backward, timed on its own after the step (it is not part of `value`)
     tm_bwd = None
     if not args.no_tm_bwd:
-        tm_bwd = time_tm_bwd(torch, dmt, wl, w, plan, tm_params, pooled, tm_out, B, args.steps)
+        tm_bwd = time_tm_bwd(torch, dmt, wl, w, plan, tm_params, pooled, tm_out, tm_ws, B, args.steps)
 
     if args.calibrate:
         a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -296,7 +296,7 @@ def main():
     return 0
 
 
-def time_tm_bwd(torch, dmt, wl, w, plan, tm_params, pooled, tm_out, B, steps):
+def time_tm_bwd(torch, dmt, wl, w, plan, tm_params, pooled, tm_out, tm_ws, B, steps):
     """dmt_tower_module_bwd on the step's pooled / tm_out tensors and a N(0,1) output gradient:
     ms per call, its kernels' shares, and the MFMA rate over the contractions' FLOPs (each
     projection twice: data and weight gradient; each cross layer three times: recomputed
@@ -336,12 +336,33 @@ def time_tm_bwd(torch, dmt, wl, w, plan, tm_params, pooled, tm_out, B, steps):
         flops = sum(4.0 * B * ((o - len(fs) * w.tm_feat_out) * d + w.tm_feat_out * d)
                     for o, d, fs in zip(w.tm_out, tw, w.tower_tables()))
     gemm_ms = prof.get("tm_bwd_gemm", (0.0, 0))[0] / n
-    return dict(ms_per_call=round(ms, 4), workspace_GB=round(ws.numel() / 1e9, 3),
-                kernels={k: dict(ms_per_call=round(v[0] / n, 4), launches_per_call=v[1] // n)
-                         for k, v in sorted(prof.items())},
-                algorithmic_flops=int(flops),
-                gemm_TFLOPs=round(flops / (gemm_ms * 1e-3) / 1e12, 1) if gemm_ms > 0 else None,
-                mfma_peak_TFLOPs=MFMA_PEAK_TFLOPS_16BIT)
+    out = dict(ms_per_call=round(ms, 4), workspace_GB=round(ws.numel() / 1e9, 3),
+               kernels={k: dict(ms_per_call=round(v[0] / n, 4), launches_per_call=v[1] // n)
+                        for k, v in sorted(prof.items())},
+               algorithmic_flops=int(flops),
+               gemm_TFLOPs=round(flops / (gemm_ms * 1e-3) / 1e12, 1) if gemm_ms > 0 else None,
+               mfma_peak_TFLOPs=MFMA_PEAK_TFLOPS_16BIT)
+    # with the cross layers' activations kept by a training forward instead of recomputed
+    kept_bytes = dmt.dmt_tm_kept_bytes(plan, tm_params, B, w.tm_dtype)
+    if kept_bytes:
+        kept = torch.empty(kept_bytes, dtype=torch.uint8, device="cuda")
+        fwd = lambda: dmt.dmt_tower_module_fwd_keep(plan, tm_params, pooled, B, tm_out, kept, tm_ws)
+        bwd = lambda: dmt.dmt_tower_module_bwd(plan, tm_params, pooled, tm_out, B, dy, dx, arr, ws, kept=kept)
+        res = {}
+        for name, fn in (("fwd_keep", fwd), ("bwd", bwd)):
+            for _ in range(2):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(n):
+                fn()
+            torch.cuda.synchronize()
+            res[name] = (time.perf_counter() - t0) * 1e3 / n
+        out["with_kept_activations"] = dict(kept_GB=round(kept_bytes / 1e9, 3),
+                                            fwd_keep_ms_per_call=round(res["fwd_keep"], 4),
+                                            bwd_ms_per_call=round(res["bwd"], 4),
+                                            bwd_flops=int(flops - sum(2.0 * B * nl * d * d for d in tw)))
+    return out
 
 
 def cpu_leg(dmt, wl, w, plan, tables, states, tm_host, b0, pooled, tm_out, tm_params, tm_ws, bwd_ws,

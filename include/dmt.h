@@ -189,6 +189,23 @@ dmt_status dmt_tower_module_fwd(const dmt_plan* plan, const dmt_tm_params* per_t
  * behind its table's valid lookups, shows as key -1 in sorted_keys, starts no run
  * (it lies inside the extent of the run before it) and is not counted. */
 /*
+ * Training forward: dmt_tower_module_fwd that also keeps, in `kept`, what the
+ * backward would otherwise recompute: x_{l+1} and u_l = W_l x_l + b_l of every
+ * cross layer (paper Listing 2), each [B][W_t] in `dtype`.  tm_out is bit for
+ * bit that of dmt_tower_module_fwd.  Towers of the other kinds keep nothing
+ * (their backward recomputes the dot terms, which is cheaper than storing them).
+ *   kept  dev, at least dmt_tm_kept_bytes(plan, per_tower, B, dtype), 256-byte
+ *         aligned, caller-owned; pass the same buffer, unchanged, to
+ *         dmt_tower_module_bwd.  May be NULL when that size is 0.
+ */
+size_t dmt_tm_kept_bytes(const dmt_plan* plan, const dmt_tm_params* per_tower, int64_t B,
+                         dmt_dtype dtype);
+dmt_status dmt_tower_module_fwd_keep(const dmt_plan* plan, const dmt_tm_params* per_tower,
+                                     const void* pooled, int64_t B, void* tm_out, dmt_dtype dtype,
+                                     void* kept, size_t kept_bytes, void* workspace,
+                                     size_t workspace_bytes, void* stream);
+
+/*
  * Parameter gradients of one tower's Tower Module, all dev float32, row-major,
  * shaped like the parameters themselves (dw_proj [O_t][K_t] with K_t the row
  * length of w_proj; dw_cross[l] [W_t][W_t]; the db_* vectors; for a DLRM tower
@@ -223,7 +240,9 @@ size_t dmt_tm_bwd_workspace_bytes(const dmt_plan* plan, const dmt_tm_params* per
  *                  du_l = dx_{l+1} * x0, dx0 += dx_{l+1} * u_l, dW_l = du_l^T x_l,
  *                  db_l = sum_b du_l, dx_l = du_l W_l + dx_{l+1};
  *                  grad_pooled = dx_0 + dx0
- * The forward's intermediates (dot terms, u_l, x_l) are recomputed, not kept.
+ * The forward's intermediates are recomputed (dot terms; u_l and x_l of the cross
+ * layers) unless `kept` hands over what dmt_tower_module_fwd_keep stored for
+ * the same plan, towers, B and dtype.
  * For DMT_BF16 / DMT_F16 every contraction runs on MFMA with float32
  * accumulation over operands rounded once to that 16-bit type (dpre, du_l, u_l,
  * x_l); gradients between layers and all outputs stay float32.  Bias gradients
@@ -235,13 +254,15 @@ size_t dmt_tm_bwd_workspace_bytes(const dmt_plan* plan, const dmt_tm_params* per
  *   grad_tm_out  dev float32, laid out like tm_out
  *   grad_pooled  dev float32 out, tower-major like pooled, 16-byte aligned
  *   grads        host [num_towers]; entries a tower's kind does not have are ignored
- *   workspace    dev, at least dmt_tm_bwd_workspace_bytes, 256-byte aligned
+ *   kept         NULL, or dev as filled by dmt_tower_module_fwd_keep (kept_bytes its size)
+ *   workspace    dev, at least dmt_tm_bwd_workspace_bytes (which assumes kept = NULL;
+ *                less is used with it), 256-byte aligned
  */
 dmt_status dmt_tower_module_bwd(const dmt_plan* plan, const dmt_tm_params* per_tower,
                                 const void* pooled, const void* tm_out, int64_t B,
                                 const float* grad_tm_out, dmt_dtype dtype, float* grad_pooled,
-                                const dmt_tm_grads* grads, void* workspace,
-                                size_t workspace_bytes, void* stream);
+                                const dmt_tm_grads* grads, const void* kept, size_t kept_bytes,
+                                void* workspace, size_t workspace_bytes, void* stream);
 
 typedef struct {
   int64_t* sorted_keys;  /* [nnz]  (table << 32 | row), ascending, stable           */

@@ -6,6 +6,7 @@ from .binding import (  # noqa: F401
     DmtError, dmt_plan, dmt_plan_create, dmt_plan_layout, dmt_plan_bind,
     dmt_tower_lookup_fwd, make_tm_params, dmt_tm_workspace_bytes, dmt_tower_module_fwd,
     make_tm_grads, dmt_tm_bwd_workspace_bytes, dmt_tower_module_bwd,
+    dmt_tm_kept_bytes, dmt_tower_module_fwd_keep,
     dmt_bwd_workspace_bytes, dmt_tower_lookup_bwd_update, dmt_last_device_error,
     status_str, library_path, dmt_kernel_name, dmt_profile_enable, dmt_profile_read,
     DMT_K_COUNT, EXPORTS, dmt_calibration_copy)

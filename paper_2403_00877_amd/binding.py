@@ -73,7 +73,10 @@ def _load() -> ctypes.CDLL:
     lib.dmt_tower_module_fwd.argtypes = [vp, vp, vp, i64, vp, ctypes.c_int, vp, sz, vp]
     lib.dmt_tm_bwd_workspace_bytes.argtypes = [vp, vp, i64]
     lib.dmt_tm_bwd_workspace_bytes.restype = sz
-    lib.dmt_tower_module_bwd.argtypes = [vp, vp, vp, vp, i64, vp, ctypes.c_int, vp, vp, vp, sz, vp]
+    lib.dmt_tower_module_bwd.argtypes = [vp, vp, vp, vp, i64, vp, ctypes.c_int, vp, vp, vp, sz, vp, sz, vp]
+    lib.dmt_tm_kept_bytes.argtypes = [vp, vp, i64, ctypes.c_int]
+    lib.dmt_tm_kept_bytes.restype = sz
+    lib.dmt_tower_module_fwd_keep.argtypes = [vp, vp, vp, i64, vp, ctypes.c_int, vp, sz, vp, sz, vp]
     lib.dmt_bwd_workspace_bytes.argtypes = [vp, i64, i64]
     lib.dmt_bwd_workspace_bytes.restype = sz
     lib.dmt_tower_lookup_bwd_update.argtypes = [vp, vp, vp, i64, i64, vp, f32, f32, vp, sz, vp, vp]
@@ -91,6 +94,7 @@ _lib = _load()
 EXPORTS = ["dmt_status_str", "dmt_plan_create", "dmt_plan_destroy", "dmt_plan_layout",
            "dmt_plan_bind", "dmt_tower_lookup_fwd", "dmt_tm_workspace_bytes",
            "dmt_tower_module_fwd", "dmt_tm_bwd_workspace_bytes", "dmt_tower_module_bwd",
+           "dmt_tm_kept_bytes", "dmt_tower_module_fwd_keep",
            "dmt_bwd_workspace_bytes", "dmt_tower_lookup_bwd_update",
            "dmt_last_device_error", "dmt_kernel_name", "dmt_profile_enable", "dmt_profile_read",
            "dmt_calibration_copy"]
@@ -228,15 +232,31 @@ def dmt_tm_bwd_workspace_bytes(plan: dmt_plan, tm_params, B: int) -> int:
     return int(_lib.dmt_tm_bwd_workspace_bytes(plan.handle, tm_params, B))
 
 
+def _nbytes(t: Optional[torch.Tensor]) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def dmt_tm_kept_bytes(plan: dmt_plan, tm_params, B: int, dtype) -> int:
+    return int(_lib.dmt_tm_kept_bytes(plan.handle, tm_params, B, DTYPE_CODE[dtype]))
+
+
+def dmt_tower_module_fwd_keep(plan: dmt_plan, tm_params, pooled: torch.Tensor, B: int,
+                              tm_out: torch.Tensor, kept: Optional[torch.Tensor],
+                              workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    _check("dmt_tower_module_fwd_keep", _lib.dmt_tower_module_fwd_keep(
+        plan.handle, tm_params, _ptr(pooled), B, _ptr(tm_out), DTYPE_CODE[tm_out.dtype],
+        _ptr(kept), _nbytes(kept), _ptr(workspace), _nbytes(workspace), _stream(stream)))
+
+
 def dmt_tower_module_bwd(plan: dmt_plan, tm_params, pooled: torch.Tensor,
                          tm_out: Optional[torch.Tensor], B: int, grad_tm_out: torch.Tensor,
                          grad_pooled: torch.Tensor, tm_grads, workspace: torch.Tensor,
-                         stream=None) -> None:
+                         stream=None, kept: Optional[torch.Tensor] = None) -> None:
     assert grad_tm_out.dtype == torch.float32 and grad_pooled.dtype == torch.float32
     _check("dmt_tower_module_bwd", _lib.dmt_tower_module_bwd(
         plan.handle, tm_params, _ptr(pooled), _ptr(tm_out), B, _ptr(grad_tm_out),
-        DTYPE_CODE[pooled.dtype], _ptr(grad_pooled), tm_grads, _ptr(workspace),
-        workspace.numel() * workspace.element_size(), _stream(stream)))
+        DTYPE_CODE[pooled.dtype], _ptr(grad_pooled), tm_grads, _ptr(kept), _nbytes(kept),
+        _ptr(workspace), _nbytes(workspace), _stream(stream)))
 
 
 def dmt_bwd_workspace_bytes(plan: dmt_plan, B: int, nnz: int) -> int:

@@ -381,7 +381,7 @@ struct TowerBwdWs {
 };
 
 dmt_status plan_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, int eb,
-                       std::vector<TowerBwdWs>* ws, size_t* bytes) {
+                       bool have_kept, std::vector<TowerBwdWs>* ws, size_t* bytes) {
   size_t off = 0;
   auto take = [&](size_t b) { size_t o = off; off = dmt_align_up(off + b, 256); return o; };
   const int64_t Bp = up8(B);
@@ -426,6 +426,7 @@ dmt_status plan_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, in
         if (q.num_cross_layers < 1 || q.num_cross_layers > DMT_MAX_CROSS_LAYERS) return DMT_EINVAL;
         for (int l = 0; l < q.num_cross_layers; ++l) {
           if (!q.w_cross[l] || !q.b_cross[l] || ((uintptr_t)q.w_cross[l] & 15)) return DMT_EINVAL;
+          if (have_kept) continue;                  // the forward kept them
           w.xl[l] = take((size_t)B * wt * eb);      // x_{l+1}
           w.u[l] = take((size_t)B * wt * eb);
         }
@@ -530,7 +531,8 @@ bool launch_transposes(const dmt_plan* p, TmbBatch& b, hipStream_t s) {
 template <int DT>
 dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<TowerBwdWs>& ws,
                       const void* pooled, const void* tm_out, int64_t B, const float* dy_all,
-                      float* dx_all, const dmt_tm_grads* gr, char* wsp, hipStream_t s) {
+                      float* dx_all, const dmt_tm_grads* gr, const char* keptp, char* wsp,
+                      hipStream_t s) {
   constexpr int eb = DT == DMT_F32 ? 4 : 2;
   constexpr int V = Ew<DT>::V;
   const char* x_all = (const char*)pooled;
@@ -539,8 +541,17 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
   for (int32_t t = 0; t < p->T; ++t) out_prefix[t + 1] = out_prefix[t] + tp[t].out_dim;
   auto x_of = [&](int t) { return (const void*)(x_all + (size_t)B * p->width_prefix[t] * eb); };
   auto dx_of = [&](int t) { return dx_all + (size_t)B * p->width_prefix[t]; };
-  // x_l of a cross tower: l = 0 is the pooled block itself
-  auto xl_of = [&](int t, int l) { return l == 0 ? x_of(t) : (const void*)(wsp + ws[t].xl[l - 1]); };
+  // x_l and u_l of a cross tower (x_0 is the pooled block itself): kept by the forward, or
+  // recomputed below into the workspace
+  std::vector<TmKept> kept;
+  if (keptp) plan_tm_kept(p, tp, B, eb, &kept);
+  auto xl_of = [&](int t, int l) -> const void* {
+    if (l == 0) return x_of(t);
+    return keptp ? (const void*)(keptp + kept[t].x[l - 1]) : (const void*)(wsp + ws[t].xl[l - 1]);
+  };
+  auto u_of = [&](int t, int l) -> const void* {
+    return keptp ? (const void*)(keptp + kept[t].u[l]) : (const void*)(wsp + ws[t].u[l]);
+  };
   int max_layers = 0;
   TmbBatch batch, batch2, batch3;
   bool ok = true;
@@ -578,7 +589,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
 
   // ---- ... and the cross layers' u_l = x_l W_l^T + b_l, x_{l+1} = x0 * u_l + x_l
   std::vector<TmGroup> groups;
-  for (int l = 0; l < max_layers; ++l) {
+  for (int l = 0; l < max_layers && !keptp; ++l) {
     for (int32_t t = 0; t < p->T; ++t) {
       const dmt_tm_params& q = tp[t];
       if (q.kind != DMT_TM_CROSS_LINEAR || l >= q.num_cross_layers) continue;
@@ -740,7 +751,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
       const int wt = p->tower_width[t];
       {
         TmbItem it{};
-        it.a = wsp + w.dxn; it.b = x_of(t); it.c = wsp + w.u[l]; it.o0 = wsp + w.du; it.o1 = dx_of(t);
+        it.a = wsp + w.dxn; it.b = x_of(t); it.c = u_of(t, l); it.o0 = wsp + w.du; it.o1 = dx_of(t);
         it.n0 = B * wt; it.i0 = l == q.num_cross_layers - 1; it.i1 = l == 0;
         it.nbx = (int32_t)ew_blocks(it.n0, V);
         batch.add(it, it.nbx);
@@ -792,7 +803,7 @@ extern "C" size_t dmt_tm_bwd_workspace_bytes(const dmt_plan* plan, const dmt_tm_
   if (!plan || !per_tower || B <= 0) return 0;
   std::vector<TowerBwdWs> ws;
   size_t bytes = 0;
-  if (plan_tm_bwd(plan, per_tower, B, 4, &ws, &bytes) != DMT_OK) return 0;
+  if (plan_tm_bwd(plan, per_tower, B, 4, false, &ws, &bytes) != DMT_OK) return 0;
   return bytes;
 }
 
@@ -800,7 +811,8 @@ extern "C" dmt_status dmt_tower_module_bwd(const dmt_plan* plan, const dmt_tm_pa
                                            const void* pooled, const void* tm_out, int64_t B,
                                            const float* grad_tm_out, dmt_dtype dtype,
                                            float* grad_pooled, const dmt_tm_grads* grads,
-                                           void* workspace, size_t workspace_bytes, void* stream) {
+                                           const void* kept, size_t kept_bytes, void* workspace,
+                                           size_t workspace_bytes, void* stream) {
   if (!plan || !per_tower || !pooled || !grad_tm_out || !grad_pooled || !grads) return DMT_EINVAL;
   if (B <= 0 || B > plan->max_batch || B >= (1LL << 31) - 8) return DMT_EINVAL;
   if (dtype != DMT_F32 && dtype != DMT_F16 && dtype != DMT_BF16) return DMT_EINVAL;
@@ -820,7 +832,15 @@ extern "C" dmt_status dmt_tower_module_bwd(const dmt_plan* plan, const dmt_tm_pa
   }
   std::vector<TowerBwdWs> ws;
   size_t bytes = 0;
-  dmt_status st = plan_tm_bwd(plan, per_tower, B, eb, &ws, &bytes);
+  const char* keptp = nullptr;
+  if (kept) {
+    std::vector<TmKept> k;
+    const size_t need = plan_tm_kept(plan, per_tower, B, eb, &k);
+    if ((uintptr_t)kept & 255) return DMT_EINVAL;
+    if (kept_bytes < need) return DMT_ENOMEM;
+    if (need > 0) keptp = (const char*)kept;
+  }
+  dmt_status st = plan_tm_bwd(plan, per_tower, B, eb, keptp != nullptr, &ws, &bytes);
   if (st != DMT_OK) return st;
   if (!workspace || ((uintptr_t)workspace & 255)) return DMT_EINVAL;
   if (workspace_bytes < bytes) return DMT_ENOMEM;
@@ -829,12 +849,12 @@ extern "C" dmt_status dmt_tower_module_bwd(const dmt_plan* plan, const dmt_tm_pa
   switch (dtype) {
     case DMT_F32:
       return run_tm_bwd<DMT_F32>(plan, per_tower, ws, pooled, tm_out, B, grad_tm_out, grad_pooled,
-                                 grads, wsp, s);
+                                 grads, keptp, wsp, s);
     case DMT_F16:
       return run_tm_bwd<DMT_F16>(plan, per_tower, ws, pooled, tm_out, B, grad_tm_out, grad_pooled,
-                                 grads, wsp, s);
+                                 grads, keptp, wsp, s);
     default:
       return run_tm_bwd<DMT_BF16>(plan, per_tower, ws, pooled, tm_out, B, grad_tm_out, grad_pooled,
-                                  grads, wsp, s);
+                                  grads, keptp, wsp, s);
   }
 }

@@ -82,13 +82,21 @@ dmt_status plan_tm(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, int eb
 
 template <int DT>
 dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<TowerWs>& ws,
-                  const void* pooled, int64_t B, void* tm_out, char* wsp, hipStream_t s) {
+                  const void* pooled, int64_t B, void* tm_out, char* wsp, char* keptp,
+                  hipStream_t s) {
   constexpr int eb = DT == DMT_F32 ? 4 : 2;
   const char* x_all = (const char*)pooled;
   char* y_all = (char*)tm_out;
   std::vector<int64_t> out_prefix(p->T + 1, 0);
   for (int32_t t = 0; t < p->T; ++t) out_prefix[t + 1] = out_prefix[t] + tp[t].out_dim;
   int max_layers = 0;
+  // With `keptp` every cross layer's x_{l+1} and u_l go there instead of the two alternating
+  // scratch buffers (a training forward: the backward reads them).
+  std::vector<TmKept> kept;
+  if (keptp) plan_tm_kept(p, tp, B, eb, &kept);
+  auto x_layer = [&](int t, int l) -> char* {      // where x_{l+1} of tower t lives
+    return keptp ? keptp + kept[t].x[l] : wsp + ws[t].x_off[l & 1];
+  };
 
   // A dot-product tower whose shape fits computes its dot terms inside the projection GEMM.
   std::vector<char> fused(p->T, 0);
@@ -142,11 +150,12 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
       const void* x0 = x_all + (size_t)B * p->width_prefix[t] * eb;
       TmGroup g{};
       g.A0 = nullptr; g.lda0 = 0; g.K0 = 0;
-      g.A1 = l == 0 ? x0 : (const void*)(wsp + ws[t].x_off[(l - 1) & 1]);
+      g.A1 = l == 0 ? x0 : (const void*)x_layer(t, l - 1);
       g.lda1 = wt; g.K1 = wt;
       g.W = q.w_cross[l]; g.ldw = wt; g.bias = q.b_cross[l];
       g.X0 = x0; g.ldx = wt;
-      g.C = wsp + ws[t].x_off[l & 1]; g.ldc = wt;
+      g.C = x_layer(t, l); g.ldc = wt;
+      if (keptp) g.U = keptp + kept[t].u[l];
       g.M = (int32_t)B; g.N = wt; g.epi = EPI_CROSS;
       groups.push_back(g);
     }
@@ -167,7 +176,7 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
       g.A0 = wsp + ws[t].z_off; g.lda0 = ws[t].np_pad; g.K0 = ws[t].np_pad;
       g.W = wsp + ws[t].wp_off; g.ldw = ws[t].np_pad + wt;
     } else if (q.kind == DMT_TM_CROSS_LINEAR) {
-      g.A1 = wsp + ws[t].x_off[(q.num_cross_layers - 1) & 1];
+      g.A1 = x_layer(t, q.num_cross_layers - 1);
     }
     g.bias = q.b_proj;
     g.X0 = nullptr; g.ldx = 0;
@@ -213,10 +222,11 @@ extern "C" size_t dmt_tm_workspace_bytes(const dmt_plan* plan, const dmt_tm_para
   return bytes;
 }
 
-extern "C" dmt_status dmt_tower_module_fwd(const dmt_plan* plan, const dmt_tm_params* per_tower,
-                                           const void* pooled, int64_t B, void* tm_out,
-                                           dmt_dtype dtype, void* workspace,
-                                           size_t workspace_bytes, void* stream) {
+namespace {
+
+dmt_status tm_fwd_entry(const dmt_plan* plan, const dmt_tm_params* per_tower, const void* pooled,
+                        int64_t B, void* tm_out, dmt_dtype dtype, void* kept, size_t kept_bytes,
+                        bool keep, void* workspace, size_t workspace_bytes, void* stream) {
   if (!plan || !per_tower || !pooled || !tm_out) return DMT_EINVAL;
   if (B <= 0 || B > plan->max_batch || B >= (1LL << 31)) return DMT_EINVAL;
   if (dtype != DMT_F32 && dtype != DMT_F16 && dtype != DMT_BF16) return DMT_EINVAL;
@@ -232,11 +242,48 @@ extern "C" dmt_status dmt_tower_module_fwd(const dmt_plan* plan, const dmt_tm_pa
     if (!workspace || ((uintptr_t)workspace & 255)) return DMT_EINVAL;
     if (workspace_bytes < bytes) return DMT_ENOMEM;
   }
+  char* keptp = nullptr;
+  if (keep) {
+    std::vector<TmKept> k;
+    const size_t need = plan_tm_kept(plan, per_tower, B, eb, &k);
+    if (need > 0) {
+      if (!kept || ((uintptr_t)kept & 255)) return DMT_EINVAL;
+      if (kept_bytes < need) return DMT_ENOMEM;
+      keptp = (char*)kept;
+    }
+  }
   hipStream_t s = (hipStream_t)stream;
   char* wsp = (char*)workspace;
   switch (dtype) {
-    case DMT_F32: return run_tm<DMT_F32>(plan, per_tower, ws, pooled, B, tm_out, wsp, s);
-    case DMT_F16: return run_tm<DMT_F16>(plan, per_tower, ws, pooled, B, tm_out, wsp, s);
-    default: return run_tm<DMT_BF16>(plan, per_tower, ws, pooled, B, tm_out, wsp, s);
+    case DMT_F32: return run_tm<DMT_F32>(plan, per_tower, ws, pooled, B, tm_out, wsp, keptp, s);
+    case DMT_F16: return run_tm<DMT_F16>(plan, per_tower, ws, pooled, B, tm_out, wsp, keptp, s);
+    default: return run_tm<DMT_BF16>(plan, per_tower, ws, pooled, B, tm_out, wsp, keptp, s);
   }
+}
+
+}  // namespace
+
+extern "C" dmt_status dmt_tower_module_fwd(const dmt_plan* plan, const dmt_tm_params* per_tower,
+                                           const void* pooled, int64_t B, void* tm_out,
+                                           dmt_dtype dtype, void* workspace,
+                                           size_t workspace_bytes, void* stream) {
+  return tm_fwd_entry(plan, per_tower, pooled, B, tm_out, dtype, nullptr, 0, false, workspace,
+                      workspace_bytes, stream);
+}
+
+extern "C" size_t dmt_tm_kept_bytes(const dmt_plan* plan, const dmt_tm_params* per_tower,
+                                    int64_t B, dmt_dtype dtype) {
+  if (!plan || !per_tower || B <= 0) return 0;
+  std::vector<TmKept> k;
+  return plan_tm_kept(plan, per_tower, B, dmt_elt_bytes(dtype), &k);
+}
+
+extern "C" dmt_status dmt_tower_module_fwd_keep(const dmt_plan* plan,
+                                                const dmt_tm_params* per_tower,
+                                                const void* pooled, int64_t B, void* tm_out,
+                                                dmt_dtype dtype, void* kept, size_t kept_bytes,
+                                                void* workspace, size_t workspace_bytes,
+                                                void* stream) {
+  return tm_fwd_entry(plan, per_tower, pooled, B, tm_out, dtype, kept, kept_bytes, true, workspace,
+                      workspace_bytes, stream);
 }

@@ -48,6 +48,9 @@ struct TmGroup {
   // (m / rdiv) * ldc + (m % rdiv) * ldc2, i.e. rdiv consecutive rows of the contraction share
   // one row of the output tensor.
   int32_t rdiv, ldc2;
+  // EPI_CROSS only: when set, u = acc + bias (before the cross product) is also stored here,
+  // laid out like C (what the backward needs of a cross layer).
+  void* U;
 };
 
 __device__ __forceinline__ int64_t tm_crow(const TmGroup& g, int m) {
@@ -194,8 +197,10 @@ __global__ __launch_bounds__(kBlock, 2) void tm_gemm_mfma(const TmLaunch L) {
         }
         float y = acc[i][j][v] + bias;
         if (epi == EPI_BIAS_RELU) y = y > 0.f ? y : 0.f;
-        if (epi == EPI_CROSS)
+        if (epi == EPI_CROSS) {
+          if (G.U) store_elt<DT>(G.U, (int64_t)m * G.ldc + n, y);
           y = load_elt<DT>(G.X0, (int64_t)m * G.ldx + n) * y + load_elt<DT>(G.A1, (int64_t)m * lda1 + n);
+        }
         store_elt<DT>(G.C, tm_crow(G, m) + n, y);
       }
     }
@@ -383,7 +388,8 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
   float* stage = (float*)lds;
   constexpr int kStageStride = LBN + 8;            // 4*stride % 64 == 32: conflict-free parking
   const bool vec_ok =
-      G.ldc % 8 == 0 && n0 + LBN <= N && (((uintptr_t)G.C | (uintptr_t)G.bias) & 15) == 0 &&
+      G.ldc % 8 == 0 && n0 + LBN <= N &&
+      (((uintptr_t)G.C | (uintptr_t)G.bias | (uintptr_t)G.U) & 15) == 0 &&
       (epi != EPI_CROSS ||
        (G.ldx % 8 == 0 && lda % 8 == 0 && (((uintptr_t)G.X0 | (uintptr_t)G.A1) & 15) == 0));
 #pragma clang loop unroll(full)
@@ -435,6 +441,7 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
           for (int q = 0; q < 8; ++q) y[q] = y[q] > 0.f ? y[q] : 0.f;
         }
         if (epi == EPI_CROSS) {
+          if (G.U) dmt::store_chunk<DT, 8>(G.U, (int64_t)m * G.ldc + n, y);
           dmt::decode_chunk<DT>(xv, *(const uint4*)((const uint16_t*)G.X0 + (int64_t)m * G.ldx + n));
           dmt::decode_chunk<DT>(lv, *(const uint4*)(A + (int64_t)m * lda + n));
 #pragma clang loop unroll(full)
@@ -445,9 +452,11 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
         for (int q = 0; q < 8 && n + q < N; ++q) {
           float z = y[q] + load_elt<DT>(G.bias, n + q);
           if (epi == EPI_BIAS_RELU) z = z > 0.f ? z : 0.f;
-          if (epi == EPI_CROSS)
+          if (epi == EPI_CROSS) {
+            if (G.U) store_elt<DT>(G.U, (int64_t)m * G.ldc + n + q, z);
             z = load_elt<DT>(G.X0, (int64_t)m * G.ldx + n + q) * z +
                 load_elt<DT>(G.A1, (int64_t)m * lda + n + q);
+          }
           store_elt<DT>(G.C, (int64_t)m * G.ldc + n + q, z);
         }
       }
@@ -479,8 +488,10 @@ __global__ __launch_bounds__(kBlock) void tm_gemm_simple(const TmLaunch L) {
   }
   float y = s + load_elt<DT>(G.bias, n);
   if (G.epi == EPI_BIAS_RELU) y = y > 0.f ? y : 0.f;
-  if (G.epi == EPI_CROSS)
+  if (G.epi == EPI_CROSS) {
+    if (G.U) store_elt<DT>(G.U, (int64_t)m * G.ldc + n, y);
     y = load_elt<DT>(G.X0, (int64_t)m * G.ldx + n) * y + load_elt<DT>(G.A1, (int64_t)m * G.lda1 + n);
+  }
   store_elt<DT>(G.C, tm_crow(G, m) + n, y);
 }
 
@@ -586,6 +597,28 @@ __global__ __launch_bounds__(kBlock) void tm_pack_w(const TmAuxLaunch L) {
   } else {
     ((uint16_t*)G.dst)[e] = (k >= np && k < np_pad) ? (uint16_t)0 : ((const uint16_t*)G.src)[src];
   }
+}
+
+// What a training forward keeps for the backward: for every cross layer l of a cross tower,
+// x_{l+1} and u_l = W_l x_l + b_l, each [B][W_t] in the compute type.  Offsets in bytes from a
+// 256-byte-aligned base; towers of other kinds keep nothing (their backward recomputes).
+struct TmKept {
+  size_t x[DMT_MAX_CROSS_LAYERS] = {}, u[DMT_MAX_CROSS_LAYERS] = {};
+};
+
+inline size_t plan_tm_kept(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, int eb,
+                           std::vector<TmKept>* kept) {
+  size_t off = 0;
+  kept->assign(p->T, TmKept());
+  for (int32_t t = 0; t < p->T; ++t) {
+    if (tp[t].kind != DMT_TM_CROSS_LINEAR) continue;
+    const size_t bytes = dmt_align_up((size_t)B * p->tower_width[t] * eb, 256);
+    for (int l = 0; l < tp[t].num_cross_layers && l < DMT_MAX_CROSS_LAYERS; ++l) {
+      (*kept)[t].x[l] = off; off += bytes;
+      (*kept)[t].u[l] = off; off += bytes;
+    }
+  }
+  return off;
 }
 
 // Whether a group can go to the 256 x 256 kernel (dots: with in-kernel dot terms).

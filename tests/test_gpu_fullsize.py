@@ -305,7 +305,18 @@ def test_tower_module_backward_on_sampled_samples(run):
         dy[ypos:ypos + B * w.tm_out[t]].reshape(B, -1)[~keep] = 0.0
         ypos += B * w.tm_out[t]
     dx.fill_(float("nan"))
-    dmt.dmt_tower_module_bwd(run.plan, params, run.pooled, run.tm_out, B, dy, dx, arr, ws)
+    # this time on what a training forward kept (cross towers; nothing for the other kinds)
+    kept = None
+    kept_bytes = dmt.dmt_tm_kept_bytes(run.plan, params, B, w.tm_dtype)
+    if kept_bytes:
+        kept = torch.empty(kept_bytes, dtype=torch.uint8, device="cuda")
+        fws = torch.empty(max(dmt.dmt_tm_workspace_bytes(run.plan, params, B), 256), dtype=torch.uint8, device="cuda")
+        y2 = torch.empty_like(run.tm_out)
+        dmt.dmt_tower_module_fwd_keep(run.plan, params, run.pooled, B, y2, kept, fws)
+        torch.cuda.synchronize()
+        assert torch.equal(y2.view(torch.int16), run.tm_out.view(torch.int16))
+        del fws, y2
+    dmt.dmt_tower_module_bwd(run.plan, params, run.pooled, run.tm_out, B, dy, dx, arr, ws, kept=kept)
     torch.cuda.synchronize()
     pos = ypos = 0
     for t in range(T):

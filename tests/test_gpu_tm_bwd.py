@@ -18,7 +18,7 @@ from harness import (RTOL, DeviceWorkload, TowerModules, assert_close, assert_gr
 pytestmark = pytest.mark.gpu
 
 
-def run_bwd(dw, tm, x_dev, y_dev, dy_dev):
+def run_bwd(dw, tm, x_dev, y_dev, dy_dev, kept=None):
     """Calls the library; returns (grad_pooled flat float64, per-tower dicts of float64 grads)."""
     w = dw.w
     dmt = dw.dmt
@@ -42,7 +42,7 @@ def run_bwd(dw, tm, x_dev, y_dev, dy_dev):
     assert nbytes > 0
     ws = torch.empty(nbytes // 8 + 32, dtype=torch.int64, device="cuda")
     dx = torch.full((w.batch * sum(widths),), nan, dtype=torch.float32, device="cuda")
-    dmt.dmt_tower_module_bwd(dw.plan, tm.params, x_dev, y_dev, w.batch, dy_dev, dx, arr, ws)
+    dmt.dmt_tower_module_bwd(dw.plan, tm.params, x_dev, y_dev, w.batch, dy_dev, dx, arr, ws, kept=kept)
     torch.cuda.synchronize()
     host = [dict(dw_proj=to_f64(g["dw_proj"]), db_proj=to_f64(g["db_proj"]),
                  dw_cross=[to_f64(a) for a in g["dw_cross"]],
@@ -50,7 +50,21 @@ def run_bwd(dw, tm, x_dev, y_dev, dy_dev):
     return to_f64(dx), host
 
 
-def check_tm_bwd(w, rtol=None):
+def forward_keep(dw, tm, x_dev):
+    """dmt_tower_module_fwd_keep; checks its output against the plain forward's, bit for bit."""
+    w, dmt = dw.w, dw.dmt
+    nbytes = dmt.dmt_tm_kept_bytes(dw.plan, tm.params, w.batch, tm.dtype)
+    kept = torch.full((nbytes // 2 + 128,), -1, dtype=torch.int16, device="cuda") if nbytes else None
+    y = torch.full((w.batch * sum(tm.out_widths),), float("nan"), dtype=x_dev.dtype, device="cuda")
+    dmt.dmt_tower_module_fwd_keep(dw.plan, tm.params, x_dev, w.batch, y, kept, tm.workspace)
+    torch.cuda.synchronize()
+    plain = tm.run(x_dev)
+    bits = torch.int32 if y.dtype == torch.float32 else torch.int16
+    assert torch.equal(y.view(bits), plain.view(bits))
+    return kept
+
+
+def check_tm_bwd(w, rtol=None, keep=False):
     dw = DeviceWorkload(w)
     tm = TowerModules(dw)
     idx, off = wl.lookup_batch(w)
@@ -71,7 +85,8 @@ def check_tm_bwd(w, rtol=None):
             dys[t][np.abs(pre) < 1e-3 * np.sqrt(np.mean(pre * pre))] = 0.0
     dy_dev = torch.from_numpy(np.concatenate([d.reshape(-1) for d in dys])).cuda()
     y_dev = tm.run(x_dev) if w.tm_kind == wl.TM_LINEAR_RELU else None
-    got_dx, got = run_bwd(dw, tm, x_dev, y_dev, dy_dev)
+    kept = forward_keep(dw, tm, x_dev) if keep else None
+    got_dx, got = run_bwd(dw, tm, x_dev, y_dev, dy_dev, kept)
     rtol = rtol or RTOL[tm.dtype]
     tables = w.tower_tables()
     for t, gdx in enumerate(dw.split_towers(got_dx, w.tower_widths())):
@@ -148,7 +163,10 @@ def test_large_scaled_cross_linear_bf16():
     check_tm_bwd(w, rtol=4e-2)
 
 
-def test_cross_three_layers_narrow_tower_f32_and_bf16():
+@pytest.mark.parametrize("keep", [False, True])
+def test_cross_three_layers_narrow_tower_f32_and_bf16(keep):
+    """keep: the cross layers' u_l and x_l come from dmt_tower_module_fwd_keep instead of being
+    recomputed by the backward."""
     w = wl.scaled(wl.large(), max_rows=300, batch=150, num_tables=3)
     w.table_to_tower = [0, 0, 0]
     w.tm_out = [96]
@@ -156,7 +174,19 @@ def test_cross_three_layers_narrow_tower_f32_and_bf16():
     for dt, rtol in (("f32", 1e-4), ("bf16", 4e-2)):
         w.tm_dtype = dt
         w.pooled_dtype = dt
-        check_tm_bwd(w, rtol)
+        check_tm_bwd(w, rtol, keep=keep)
+
+
+def test_kept_activations_wide_cross_tower_and_towers_that_keep_nothing():
+    # two 2048-wide towers (256 x 256 GEMM path), 2 layers; then a dot tower, whose forward keeps
+    # nothing: the backward must behave exactly as without
+    w = wl.scaled(wl.large(), max_rows=3000, batch=200)
+    sel = [f for f in range(256) if w.table_to_tower[f] in (0, 1)]
+    w.rows = [w.rows[f] for f in sel]; w.dims = [128] * 32
+    w.table_to_tower = [wl.large().table_to_tower[f] for f in sel]
+    w.tm_out = [512, 512]
+    check_tm_bwd(w, rtol=4e-2, keep=True)
+    check_tm_bwd(wl.scaled(wl.mid(), max_rows=5000, batch=301, num_tables=16), keep=True)
 
 
 @pytest.mark.parametrize("dt", ["bf16", "f16", "f32"])
