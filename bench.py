@@ -192,6 +192,9 @@ def main():
     tm_bwd = None
     if not args.no_tm_bwd:
         tm_bwd = time_tm_bwd(torch, dmt, wl, w, plan, tm_params, pooled, tm_out, tm_ws, B, args.steps)
+        if w.backward:
+            tm_bwd["whole_tower_step"] = time_whole_step(torch, dmt, wl, w, plan, tm_params, pooled, tm_out,
+                                                         tm_ws, bwd_ws, batches, B, args.steps)
 
     if args.calibrate:
         a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -363,6 +366,50 @@ def time_tm_bwd(torch, dmt, wl, w, plan, tm_params, pooled, tm_out, tm_ws, B, st
                                             bwd_ms_per_call=round(res["bwd"], 4),
                                             bwd_flops=int(flops - sum(2.0 * B * nl * d * d for d in tw)))
     return out
+
+
+def time_whole_step(torch, dmt, wl, w, plan, tm_params, pooled, tm_out, tm_ws, bwd_ws, batches, B, steps):
+    """One GPU's whole tower step with the real gradient chain: lookup -> Tower Module (training
+    forward) -> Tower Module backward on a fixed N(0,1) gradient of the module outputs -> sorted
+    segment-reduce + rowwise Adagrad fed by the module's dL/d(pooled).  Timed after everything
+    else; not part of `value`."""
+    kin, tw = w.tm_in_dims(), w.tower_widths()
+    nl = w.tm_cross_layers if w.tm_kind == wl.TM_CROSS_LINEAR else 0
+    f32 = lambda *shape: torch.empty(shape, dtype=torch.float32, device="cuda")
+    if w.tm_kind == wl.TM_DLRM:
+        grads = [dict(dw_proj=f32(o - len(fs) * w.tm_feat_out, d), db_proj=f32(o - len(fs) * w.tm_feat_out),
+                      dw_cross=[f32(w.tm_feat_out, d // len(fs))], db_cross=[f32(w.tm_feat_out)])
+                 for o, d, fs in zip(w.tm_out, tw, w.tower_tables())]
+    else:
+        grads = [dict(dw_proj=f32(o, k), db_proj=f32(o), dw_cross=[f32(d, d) for _ in range(nl)],
+                      db_cross=[f32(d) for _ in range(nl)]) for o, k, d in zip(w.tm_out, kin, tw)]
+    arr = dmt.make_tm_grads(grads)
+    ws = torch.empty(dmt.dmt_tm_bwd_workspace_bytes(plan, tm_params, B), dtype=torch.uint8, device="cuda")
+    kept_bytes = dmt.dmt_tm_kept_bytes(plan, tm_params, B, w.tm_dtype)
+    kept = torch.empty(kept_bytes, dtype=torch.uint8, device="cuda") if kept_bytes else None
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11 + w.seed)
+    dy = torch.randn(B * sum(w.tm_out), generator=g, device="cuda", dtype=torch.float32)
+    dx = torch.empty(B * sum(tw), dtype=torch.float32, device="cuda")
+
+    def step(i):
+        b = batches[i % len(batches)]
+        dmt.dmt_tower_lookup_fwd(plan, b["idx"], b["off"], B, pooled)
+        dmt.dmt_tower_module_fwd_keep(plan, tm_params, pooled, B, tm_out, kept, tm_ws)
+        dmt.dmt_tower_module_bwd(plan, tm_params, pooled, tm_out, B, dy, dx, arr, ws, kept=kept)
+        dmt.dmt_tower_lookup_bwd_update(plan, b["idx"], b["off"], B, dx, w.lr, w.eps, bwd_ws)
+
+    for i in range(3):
+        step(i)
+    torch.cuda.synchronize()
+    n = max(3, min(steps, 40))
+    t0 = time.perf_counter()
+    for i in range(n):
+        step(3 + i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / n
+    assert dmt.dmt_last_device_error(plan) == -1
+    return dict(ms_per_step=round(ms, 4), samples_per_s=round(B / (ms * 1e-3), 1), steps=n)
 
 
 def cpu_leg(dmt, wl, w, plan, tables, states, tm_host, b0, pooled, tm_out, tm_params, tm_ws, bwd_ws,
