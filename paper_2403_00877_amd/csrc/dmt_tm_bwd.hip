@@ -349,12 +349,27 @@ __global__ __launch_bounds__(kBlock) void tmb_cross_prep(const TmbLaunch L) {
 
 inline int64_t up8(int64_t v) { return (v + 7) / 8 * 8; }
 
+// Row length (elements of eb bytes) of a transposed operand whose rows hold `count` batch
+// entries: a multiple of 8, and never a multiple of 1 KB in bytes.  With a power-of-two
+// row pitch the 256 rows a GEMM block reads in one K step all fall on the same memory channels;
+// 128 bytes of (zero) padding spread them.
+inline int64_t ld_batch(int64_t count, int eb) {
+  int64_t ld = up8(count);
+  if ((ld * eb) % 1024 == 0) ld += 128 / eb;
+  return ld;
+}
+
 // Slices a weight-gradient contraction (M x N outputs, K = batch) is cut into so that a
-// launch of `tiles` output tiles fills the chip: each slice at least 1024 long, a multiple
+// launch of `tiles_all` output tiles (all towers) fills the 256 CUs once, as nearly as it can
+// without a second, mostly empty round of blocks: each slice at least 1024 long, a multiple
 // of 64.
 inline void choose_split(int64_t tiles_all, int64_t K, int* ksplit, int* klen) {
-  int ks = 1;
-  while (ks < 16 && tiles_all * ks < 384 && K / (ks * 2) >= 1024) ks *= 2;
+  int ks = (int)std::max<int64_t>(1, std::min<int64_t>(16, 256 / std::max<int64_t>(tiles_all, 1)));
+  while (ks > 1 && K / ks < 1024) --ks;
+  // A long batch with few tiles (narrow outputs: the contraction is bound by memory latency,
+  // one block per CU) measured faster in slices of about 4096 spread over several rounds
+  // (Imbalanced: 0.54 against 0.73 ms) than in one round of very long slices.
+  if (tiles_all < 256 && K / ks > 4096) ks = (int)std::min<int64_t>(16, (K + 4095) / 4096);
   const int forced = dmt::env_int("DMT_TMB_KSPLIT", 0);
   if (forced > 0 && K / forced >= 128) ks = forced;
   int len = (int)((K + ks - 1) / ks);
@@ -384,7 +399,7 @@ dmt_status plan_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, in
                        bool have_kept, std::vector<TowerBwdWs>* ws, size_t* bytes) {
   size_t off = 0;
   auto take = [&](size_t b) { size_t o = off; off = dmt_align_up(off + b, 256); return o; };
-  const int64_t Bp = up8(B);
+  const int64_t Bp = ld_batch(B, eb);
   ws->assign(p->T, TowerBwdWs());
   // output tiles of the weight-gradient launches (all towers together), 128 x 128 units
   int64_t tiles_proj = 0, tiles_cross = 0;
@@ -392,7 +407,12 @@ dmt_status plan_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, in
     const dmt_tm_params& q = tp[t];
     const int64_t wt = p->tower_width[t];
     if (q.out_dim <= 0) return DMT_EINVAL;
-    tiles_proj += ((q.out_dim + 255) / 256) * ((wt + 255) / 256);
+    int64_t kin = wt;                                 // columns of the projection's weight gradient
+    if (q.kind == DMT_TM_DOT_LINEAR) {
+      const int64_t nf = p->tower_ntab[t];
+      kin += (nf * (nf - 1) / 2 + 7) / 8 * 8;
+    }
+    tiles_proj += ((q.out_dim + 255) / 256) * ((kin + 255) / 256);
     if (q.kind == DMT_TM_CROSS_LINEAR) tiles_cross += ((wt + 255) / 256) * ((wt + 255) / 256);
   }
   for (int32_t t = 0; t < p->T; ++t) {
@@ -440,8 +460,8 @@ dmt_status plan_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, in
         if (n == 0) return DMT_ENOTSUP;
         if (q.feat_out < 1 || (int64_t)q.out_dim - (int64_t)nf * q.feat_out < 1) return DMT_EINVAL;
         if (!q.w_cross[0] || !q.b_cross[0] || ((uintptr_t)q.w_cross[0] & 15)) return DMT_EINVAL;
-        if (B * nf >= (1LL << 31) - 8) return DMT_ENOTSUP;
-        const int64_t BFp = up8(B * nf);
+        if (B * nf >= (1LL << 31) - 128) return DMT_ENOTSUP;
+        const int64_t BFp = ld_batch(B * nf, eb);
         w.Fp = up8(q.feat_out);
         w.dz2 = take((size_t)B * nf * w.Fp * eb);
         w.dz2T = take((size_t)q.feat_out * BFp * eb);
@@ -536,7 +556,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
   constexpr int eb = DT == DMT_F32 ? 4 : 2;
   constexpr int V = Ew<DT>::V;
   const char* x_all = (const char*)pooled;
-  const int64_t Bp = up8(B);
+  const int64_t Bp = ld_batch(B, eb);
   std::vector<int64_t> out_prefix(p->T + 1, 0);
   for (int32_t t = 0; t < p->T; ++t) out_prefix[t + 1] = out_prefix[t] + tp[t].out_dim;
   auto x_of = [&](int t) { return (const void*)(x_all + (size_t)B * p->width_prefix[t] * eb); };
@@ -666,7 +686,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
       // the shared per-feature layer: the same steps on rows (sample, feature); its data
       // gradient lands on top of the flat layer's (second launch below)
       const int nf = p->tower_ntab[t], n = p->tower_uniform_dim[t], F = q.feat_out;
-      const int64_t BF = B * nf, BFp = up8(BF);
+      const int64_t BF = B * nf, BFp = ld_batch(BF, eb);
       {
         TmbItem it{};
         it.a = dy_all + (size_t)B * out_prefix[t] + O;
@@ -814,7 +834,7 @@ extern "C" dmt_status dmt_tower_module_bwd(const dmt_plan* plan, const dmt_tm_pa
                                            const void* kept, size_t kept_bytes, void* workspace,
                                            size_t workspace_bytes, void* stream) {
   if (!plan || !per_tower || !pooled || !grad_tm_out || !grad_pooled || !grads) return DMT_EINVAL;
-  if (B <= 0 || B > plan->max_batch || B >= (1LL << 31) - 8) return DMT_EINVAL;
+  if (B <= 0 || B > plan->max_batch || B >= (1LL << 31) - 128) return DMT_EINVAL;
   if (dtype != DMT_F32 && dtype != DMT_F16 && dtype != DMT_BF16) return DMT_EINVAL;
   if (((uintptr_t)pooled & 15) || ((uintptr_t)tm_out & 15) || ((uintptr_t)grad_pooled & 15) ||
       ((uintptr_t)grad_tm_out & 3))
