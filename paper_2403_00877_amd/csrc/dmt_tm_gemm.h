@@ -96,7 +96,9 @@ template <int DT> __device__ __forceinline__ void store_elt(void* p, int64_t i, 
 #define DMT_TM_TAG 0
 #endif
 
-template <int DT, int TAG = DMT_TM_TAG>
+// KEEPU: the cross epilogue also stores u (TmGroup::U).  An instance of its own, because the
+// second store in the fully unrolled epilogue costs the bf16 kernel 40 registers and spills.
+template <int DT, bool KEEPU = false, int TAG = DMT_TM_TAG>
 __global__ __launch_bounds__(kBlock, 2) void tm_gemm_mfma(const TmLaunch L) {
   __shared__ __attribute__((aligned(16))) uint16_t As[BM * kLdsStride];
   __shared__ __attribute__((aligned(16))) uint16_t Bs[BN * kLdsStride];
@@ -198,7 +200,9 @@ __global__ __launch_bounds__(kBlock, 2) void tm_gemm_mfma(const TmLaunch L) {
         float y = acc[i][j][v] + bias;
         if (epi == EPI_BIAS_RELU) y = y > 0.f ? y : 0.f;
         if (epi == EPI_CROSS) {
-          if (G.U) store_elt<DT>(G.U, (int64_t)m * G.ldc + n, y);
+          if constexpr (KEEPU) {
+            if (G.U) store_elt<DT>(G.U, (int64_t)m * G.ldc + n, y);
+          }
           y = load_elt<DT>(G.X0, (int64_t)m * G.ldx + n) * y + load_elt<DT>(G.A1, (int64_t)m * lda1 + n);
         }
         store_elt<DT>(G.C, tm_crow(G, m) + n, y);
@@ -679,8 +683,13 @@ void launch_groups(const dmt_plan* p, std::vector<TmGroup>& groups, hipStream_t 
           hipLaunchKernelGGL((tm_gemm_mfma_256<DT, false>), dim3(big_tiles), dim3(kBigThreads),
                              kBigLdsBytes, s, L);
       } else {
+        bool keepu = false;
+        for (int i = 0; i < L.ngroups; ++i) keepu = keepu || L.g[i].U != nullptr;
         DmtScope sc_(p, kid, s);
-        hipLaunchKernelGGL((tm_gemm_mfma<DT>), dim3(tiles), dim3(kBlock), 0, s, L);
+        if (keepu)
+          hipLaunchKernelGGL((tm_gemm_mfma<DT, true>), dim3(tiles), dim3(kBlock), 0, s, L);
+        else
+          hipLaunchKernelGGL((tm_gemm_mfma<DT, false>), dim3(tiles), dim3(kBlock), 0, s, L);
       }
     }
   }
