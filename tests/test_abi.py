@@ -105,6 +105,66 @@ def test_hot_calls_validate_before_launching():
     assert tm(p.handle, arr, fake, 4, fake, 2, ws, 16, None) == binding.DMT_ENOMEM      # workspace too small
 
 
+def test_tower_module_backward_and_keep_validate_on_the_host():
+    """dmt_tower_module_bwd / _fwd_keep: sizes are host arithmetic, bad arguments come back as
+    codes before anything is launched."""
+    lib = ctypes.CDLL(dmt.library_path())
+    vp, i64, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
+    # two towers of two 8-wide tables each, batch up to 4
+    p = dmt.dmt_plan_create([5, 5, 5, 5], [8, 8, 8, 8], "f16", 2, [0, 0, 1, 1], 4, 64)
+    arr = (dmt.binding.dmt_tm_params * 2)()
+    for a in arr:
+        a.kind, a.out_dim, a.w_proj, a.b_proj = binding.DMT_TM_CROSS_LINEAR, 8, 4096, 4096
+        a.num_cross_layers = 2
+        for l in range(2):
+            a.w_cross[l] = a.b_cross[l] = 4096
+    # kept: per tower and layer x_{l+1} and u_l, each B * 16 f16 values rounded up to 256 bytes
+    assert dmt.dmt_tm_kept_bytes(p, arr, 4, "f16") == 2 * 2 * 2 * 256
+    assert dmt.dmt_tm_kept_bytes(p, arr, 4, "f32") == 2 * 2 * 2 * 256
+    assert dmt.dmt_tm_kept_bytes(p, arr, 3, "bf16") == 2 * 2 * 2 * 256
+    need = dmt.dmt_tm_bwd_workspace_bytes(p, arr, 4)
+    assert need > 0 and dmt.dmt_tm_bwd_workspace_bytes(p, arr, 2) <= need
+    for a in arr:
+        a.kind = binding.DMT_TM_DOT_LINEAR
+    assert dmt.dmt_tm_kept_bytes(p, arr, 4, "f16") == 0          # dot towers keep nothing
+    grads = (dmt.binding.dmt_tm_grads * 2)()
+    bwd = lib.dmt_tower_module_bwd
+    bwd.argtypes = [vp, vp, vp, vp, i64, vp, ctypes.c_int, vp, vp, vp, sz, vp, sz, vp]
+    fake = vp(4096)
+    args = lambda **kw: [kw.get("plan", p.handle), arr, kw.get("pooled", fake), fake, kw.get("B", 4), fake, 1,
+                         kw.get("dx", fake), grads, kw.get("kept", None), kw.get("kept_bytes", 0),
+                         kw.get("ws", fake), kw.get("ws_bytes", 1 << 30), None]
+    assert bwd(*args()) == binding.DMT_EINVAL                     # gradient outputs not given
+    for g in grads:
+        g.dw_proj = g.db_proj = 4096
+    assert bwd(*args(plan=None)) == binding.DMT_EINVAL
+    assert bwd(*args(pooled=None)) == binding.DMT_EINVAL
+    assert bwd(*args(B=5)) == binding.DMT_EINVAL                  # B > max_batch
+    assert bwd(*args(dx=vp(4100))) == binding.DMT_EINVAL          # misaligned output
+    assert bwd(*args(ws=vp(4100))) == binding.DMT_EINVAL          # misaligned workspace
+    assert bwd(*args(ws_bytes=64)) == binding.DMT_ENOMEM
+    for a in arr:
+        a.kind = binding.DMT_TM_CROSS_LINEAR
+    assert bwd(*args()) == binding.DMT_EINVAL                     # cross gradients not given
+    for g in grads:
+        for l in range(2):
+            g.dw_cross[l] = g.db_cross[l] = 4096
+    assert bwd(*args(kept=fake, kept_bytes=64)) == binding.DMT_ENOMEM
+    assert bwd(*args(kept=vp(4100), kept_bytes=1 << 20)) == binding.DMT_EINVAL
+    keep = lib.dmt_tower_module_fwd_keep
+    keep.argtypes = [vp, vp, vp, i64, vp, ctypes.c_int, vp, sz, vp, sz, vp]
+    assert keep(p.handle, arr, fake, 4, fake, 1, None, 0, fake, 1 << 20, None) == binding.DMT_EINVAL
+    assert keep(p.handle, arr, fake, 4, fake, 1, fake, 64, fake, 1 << 20, None) == binding.DMT_ENOMEM
+    # a DLRM tower needs at least one flat output beside its per-feature ones
+    for a in arr:
+        a.kind, a.feat_out, a.out_dim = binding.DMT_TM_DLRM, 4, 8      # 2 features * 4 = all 8 outputs
+    assert bwd(*args()) == binding.DMT_EINVAL
+    assert dmt.dmt_tm_bwd_workspace_bytes(p, arr, 4) == 0
+    for a in arr:
+        a.out_dim = 9
+    assert dmt.dmt_tm_bwd_workspace_bytes(p, arr, 4) > 0
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys
