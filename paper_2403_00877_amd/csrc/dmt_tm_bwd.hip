@@ -91,6 +91,57 @@ __global__ __launch_bounds__(kBlock) void tmb_prep_dy(const TmbLaunch L) {
   }
 }
 
+// The same for the 16-bit types when O, ldy (and ld2) are multiples of 4 and dy is 16-byte
+// aligned: 64 x 64 tiles, 16-byte reads of the gradient, 8-byte writes of both outputs.
+template <int DT>
+__global__ __launch_bounds__(kBlock) void tmb_prep_dy16(const TmbLaunch L) {
+  __shared__ __attribute__((aligned(8))) uint16_t tile[kVTile][kVTile + 4];
+  const int gi = tmb_find(L);
+  const TmbItem& G = L.it[gi];
+  const int lb = blockIdx.x - L.block_start[gi];
+  const float* __restrict__ dy = (const float*)G.a;
+  const uint16_t* __restrict__ y = (const uint16_t*)G.b;
+  uint16_t* __restrict__ dz = (uint16_t*)G.o0;
+  uint16_t* __restrict__ dzT = (uint16_t*)G.o1;
+  const int64_t B = G.n0, Bp = G.n1;
+  const int O = G.i0, Op = G.i1, relu = G.i2;
+  const int64_t b0 = (int64_t)(lb % G.nbx) * kVTile;
+  const int o0 = (lb / G.nbx) * kVTile;
+  const int q = threadIdx.x >> 4, v = (threadIdx.x & 15) * 4;
+#pragma unroll
+  for (int pass = 0; pass < 4; ++pass) {
+    const int i = pass * 16 + q;
+    const int64_t b = b0 + i;
+    const int o = o0 + v;
+    float g[4] = {0.f, 0.f, 0.f, 0.f};
+    if (b < B && o < O) {
+      const int64_t at = (G.i3 > 0 ? (b / G.i3) * G.n2 + (b % G.i3) * G.i4 : b * G.n2) + o;
+      const float4 t = *(const float4*)(dy + at);
+      g[0] = t.x; g[1] = t.y; g[2] = t.z; g[3] = t.w;
+      if (relu) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (!(load_elt<DT>(y, at + e) > 0.f)) g[e] = 0.f;
+      }
+    }
+    const uint2 packed = make_uint2(dmt::pack2<DT>(g[0], g[1]), dmt::pack2<DT>(g[2], g[3]));
+    if (b < B && o < Op) *(uint2*)(dz + b * Op + o) = packed;
+    *(uint2*)&tile[i][v] = packed;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int pass = 0; pass < 4; ++pass) {
+    const int i = pass * 16 + q;                   // output column of the tile
+    const int o = o0 + i;
+    const int64_t b = b0 + v;
+    if (o < O && b < Bp) {
+      const uint32_t lo = tile[v][i] | ((uint32_t)tile[v + 1][i] << 16);
+      const uint32_t hi = tile[v + 2][i] | ((uint32_t)tile[v + 3][i] << 16);
+      *(uint2*)(dzT + (int64_t)o * Bp + b) = make_uint2(lo, hi);
+    }
+  }
+}
+
 // dst[c][r] = src[r][c] for r < R, 0 for R <= r < ldd; c < C.  src rows are lds
 // elements apart, dst rows ldd.  a = src, o0 = dst, n0 = R, n1 = lds, n2 = ldd, i0 = C.
 // Any element type and alignment: one element per access.
@@ -542,6 +593,17 @@ void add_transpose(TmbBatch& b, const void* src, int64_t R, int C, int64_t lds, 
   b.add(it, (int64_t)it.nbx * ((C + tile - 1) / tile));
 }
 
+// Queues a gradient-preparation item (all fields but nbx set) on the 16-byte kernel when its
+// shape and alignment allow, else on the one-element kernel.
+template <int DT>
+void add_prep(TmbBatch& scalar, TmbBatch& vec, TmbItem it) {
+  const bool v = DT != DMT_F32 && it.i0 % 4 == 0 && it.n2 % 4 == 0 && (it.i3 == 0 || it.i4 % 4 == 0) &&
+                 ((uintptr_t)it.a & 15) == 0;
+  const int tile = v ? kVTile : kTile;
+  it.nbx = (int32_t)((it.n1 + tile - 1) / tile);
+  (v ? vec : scalar).add(it, (int64_t)it.nbx * ((it.i1 + tile - 1) / tile));
+}
+
 template <int DT>
 bool launch_transposes(const dmt_plan* p, TmbBatch& b, hipStream_t s) {
   if constexpr (DT == DMT_F32) return launch_items(p, b, tmb_transpose<float>, s);
@@ -573,7 +635,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
     return keptp ? (const void*)(keptp + kept[t].u[l]) : (const void*)(wsp + ws[t].u[l]);
   };
   int max_layers = 0;
-  TmbBatch batch, batch2, batch3;
+  TmbBatch batch, batch2, batch3, prep16;
   bool ok = true;
 
   // ---- recompute what the forward did not keep: dot terms (and the repacked weights)
@@ -647,8 +709,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
       it.b = it.i2 ? (const void*)((const char*)tm_out + (size_t)B * out_prefix[t] * eb) : nullptr;
       it.o0 = wsp + w.dz; it.o1 = wsp + w.dzT;
       it.n0 = B; it.n1 = Bp; it.n2 = q.out_dim; it.i0 = O; it.i1 = (int32_t)w.Op;
-      it.nbx = (int32_t)((Bp + kTile - 1) / kTile);
-      batch.add(it, (int64_t)it.nbx * ((w.Op + kTile - 1) / kTile));
+      add_prep<DT>(batch, prep16, it);
     }
     {
       TmbItem it{};
@@ -693,8 +754,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
         it.o0 = wsp + w.dz2; it.o1 = wsp + w.dz2T;
         it.n0 = BF; it.n1 = BFp; it.n2 = q.out_dim; it.i0 = F; it.i1 = (int32_t)w.Fp;
         it.i3 = nf; it.i4 = F;
-        it.nbx = (int32_t)((BFp + kTile - 1) / kTile);
-        batch.add(it, (int64_t)it.nbx * ((w.Fp + kTile - 1) / kTile));
+        add_prep<DT>(batch, prep16, it);
       }
       {
         TmbItem it{};
@@ -720,6 +780,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
     }
   }
   ok &= launch_items(p, batch, tmb_prep_dy<DT>, s);
+  if constexpr (DT != DMT_F32) ok &= launch_items(p, prep16, tmb_prep_dy16<DT>, s);
   ok &= launch_items(p, batch2, tmb_rowsum<DT>, s);
   ok &= launch_transposes<DT>(p, batch3, s);
   launch_groups<DT>(p, dgrad, s, false, DMT_K_TM_BWD_GEMM);
