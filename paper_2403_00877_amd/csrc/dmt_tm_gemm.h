@@ -625,9 +625,11 @@ inline size_t plan_tm_kept(const dmt_plan* p, const dmt_tm_params* tp, int64_t B
   return off;
 }
 
-// Whether a group can go to the 256 x 256 kernel (dots: with in-kernel dot terms).
+// Whether a group can go to the 256 x 256 kernel (dots: with in-kernel dot terms).  At most 128
+// rows or columns (a weight gradient with few outputs) would leave half of every tile empty.
 inline bool big_ok(const TmGroup& g, bool dots) {
-  return g.N > 128 && g.N <= kSuper * LBN && g.K1 >= 128 && (dots || g.K0 == 0) && g.rdiv == 0 &&
+  return g.N > 128 && g.M > 128 && g.N <= kSuper * LBN && g.K1 >= 128 && (dots || g.K0 == 0) &&
+         g.rdiv == 0 &&
          (int64_t)g.M * g.lda1 < (1LL << 31) && (int64_t)g.N * g.ldw < (1LL << 31);
 }
 
