@@ -396,8 +396,33 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
       (((uintptr_t)G.C | (uintptr_t)G.bias | (uintptr_t)G.U) & 15) == 0 &&
       (epi != EPI_CROSS ||
        (G.ldx % 8 == 0 && lda % 8 == 0 && (((uintptr_t)G.X0 | (uintptr_t)G.A1) & 15) == 0));
+  // The two epilogues that read global memory (cross: x0 and x_l; accumulate: C itself) request
+  // all of a half's operands before the accumulators are parked: with one block per CU nothing
+  // else hides that latency, and a thread's eight chunks one after another cost eight of them.
+  constexpr int kChunks = 128 * (LBN / 8) / kBigThreads;
+  // (byte offsets from the operand's base fit 32 bits: one register per address instead of two)
+  const bool fast_cross = epi == EPI_CROSS && vec_ok && (int64_t)M * G.ldx < (1LL << 31);
+  const bool fast_add = epi == EPI_F32_ADD && n0 + LBN <= N && G.ldc % 4 == 0 &&
+                        (int64_t)M * G.ldc < (1LL << 30) &&
+                        (((uintptr_t)((float*)G.C + slice * G.cstride)) & 15) == 0;
+  const char* const pre_a = fast_cross ? (const char*)G.X0 : (const char*)((float*)G.C + slice * G.cstride);
+  const char* const pre_b = fast_cross ? (const char*)A : pre_a + 16;
+  const uint32_t pre_lda = fast_cross ? (uint32_t)G.ldx * 2u : (uint32_t)G.ldc * 4u;   // row pitch, bytes
+  const uint32_t pre_ldb = fast_cross ? (uint32_t)lda * 2u : pre_lda;
+  const uint32_t pre_col = fast_cross ? 2u : 4u;                                        // bytes per column
 #pragma clang loop unroll(full)
   for (int h = 0; h < 2; ++h) {
+    uint4 pa[kChunks], pb[kChunks];
+    if (fast_cross || fast_add) {
+#pragma clang loop unroll(full)
+      for (int u = 0; u < kChunks; ++u) {
+        const int c = tid + u * kBigThreads;
+        const int r = c / (LBN / 8), cc = (c % (LBN / 8)) * 8;
+        const uint32_t m = (uint32_t)min(m0 + h * 128 + r, M - 1), n = (uint32_t)(n0 + cc);
+        pa[u] = *(const uint4*)(pre_a + (m * pre_lda + n * pre_col));
+        pb[u] = *(const uint4*)(pre_b + (m * pre_ldb + n * pre_col));
+      }
+    }
     if (wm == h) {
 #pragma clang loop unroll(full)
       for (int j = 0; j < 2; ++j)
@@ -410,6 +435,39 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
           }
     }
     __syncthreads();
+    if (fast_cross || fast_add) {
+#pragma clang loop unroll(full)
+      for (int u = 0; u < kChunks; ++u) {
+        const int c = tid + u * kBigThreads;
+        const int r = c / (LBN / 8), cc = (c % (LBN / 8)) * 8;
+        const int m = m0 + h * 128 + r, n = n0 + cc;
+        if (m >= M) continue;
+        float y[8];
+        const float4 s0 = *(const float4*)(stage + r * kStageStride + cc);
+        const float4 s1 = *(const float4*)(stage + r * kStageStride + cc + 4);
+        y[0] = s0.x; y[1] = s0.y; y[2] = s0.z; y[3] = s0.w;
+        y[4] = s1.x; y[5] = s1.y; y[6] = s1.z; y[7] = s1.w;
+        if (fast_add) {
+          float* c0 = (float*)G.C + slice * G.cstride + (int64_t)m * G.ldc + n;
+          const float4 p0 = __builtin_bit_cast(float4, pa[u]), p1 = __builtin_bit_cast(float4, pb[u]);
+          *(float4*)c0 = make_float4(y[0] + p0.x, y[1] + p0.y, y[2] + p0.z, y[3] + p0.w);
+          *(float4*)(c0 + 4) = make_float4(y[4] + p1.x, y[5] + p1.y, y[6] + p1.z, y[7] + p1.w);
+        } else {
+          float bv[8], xv[8], lv[8];
+          dmt::decode_chunk<DT>(bv, *(const uint4*)((const uint16_t*)G.bias + n));
+#pragma clang loop unroll(full)
+          for (int q = 0; q < 8; ++q) y[q] += bv[q];
+          if (G.U) dmt::store_chunk<DT, 8>(G.U, (int64_t)m * G.ldc + n, y);
+          dmt::decode_chunk<DT>(xv, pa[u]);
+          dmt::decode_chunk<DT>(lv, pb[u]);
+#pragma clang loop unroll(full)
+          for (int q = 0; q < 8; ++q) y[q] = xv[q] * y[q] + lv[q];
+          dmt::store_chunk<DT, 8>(G.C, (int64_t)m * G.ldc + n, y);
+        }
+      }
+      __syncthreads();
+      continue;
+    }
     for (int c = tid; c < 128 * (LBN / 8); c += kBigThreads) {
       const int r = c / (LBN / 8), cc = (c % (LBN / 8)) * 8;
       const int m = m0 + h * 128 + r, n = n0 + cc;
