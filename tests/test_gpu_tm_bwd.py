@@ -228,6 +228,27 @@ def test_degenerate_sizes(kind, dt):
     check_tm_bwd(w, rtol=(4e-2 if kind == "cross_linear" else 2e-2) if dt != "f32" else 1e-4)
 
 
+@pytest.mark.parametrize("D", [64, 32, 16, 8])
+def test_compression_ratios_of_the_cross_module(D):
+    """The DCN Tower Module at the output widths of the paper's compression study (Table 5):
+    O = |F| D for D = 64 ... 8 with |F| = 4 features of N = 128, i.e. CR = D / N from 1/2 down to
+    1/16; forward (training variant) and backward."""
+    w = wl.scaled(wl.large(), max_rows=300, batch=97, num_tables=4)
+    w.table_to_tower = [0, 0, 0, 0]
+    w.dims = [128] * 4
+    w.tm_out = [4 * D]
+    w.tm_cross_layers = 2
+    dw = DeviceWorkload(w)
+    tm = TowerModules(dw)
+    idx, off = wl.lookup_batch(w)
+    pooled = oracle.lookup_towered(dw.host_tables, w.table_dtype, w.dims, w.table_to_tower, idx, off, w.batch)
+    enc = oracle.round_to(pooled[0], tm.dtype)
+    y = to_f64(tm.run(to_device(enc, tm.dtype).reshape(-1))).reshape(w.batch, 4 * D)
+    ref = tm.oracle([wl.decode(enc, tm.dtype)])[0]
+    assert_close(y, wl.decode(oracle.round_to(ref, tm.dtype), tm.dtype), RTOL[tm.dtype], "cross module, D = %d" % D)
+    check_tm_bwd(w, rtol=4e-2, keep=True)
+
+
 def test_rejects_bad_arguments():
     w = wl.tiny()
     dw = DeviceWorkload(w)
