@@ -10,8 +10,13 @@
 // The operands that exist only in the other orientation (W^T, dz^T, x^T) are
 // written by an LDS-tiled transpose into 16-byte-aligned, zero-padded rows.
 // Towers are grouped into one launch per stage like the forward's.  The
-// forward's intermediates are recomputed (dot terms, u_l = W_l x_l + b_l, x_l).
+// forward's intermediates are recomputed (dot terms; u_l = W_l x_l + b_l and x_l of
+// the cross layers unless the caller hands over what a training forward kept).
+// A weight gradient has few output tiles and a long K (the batch): K is cut into
+// slices that are contractions of their own and summed in slice order.
 // Bias gradients are fixed-order row sums of the transposed gradient operand.
+// The DLRM module's shared per-feature layer is the same machinery on rows
+// (sample, feature) of the pooled block.
 #define DMT_TM_TAG 1          // this file's instances of the shared GEMM kernels
 #include "dmt_tm_gemm.h"
 
@@ -142,8 +147,10 @@ __global__ __launch_bounds__(kBlock) void tmb_prep_dy16(const TmbLaunch L) {
   }
 }
 
-// dst[c][r] = src[r][c] for r < R, 0 for R <= r < ldd; c < C.  src rows are lds
-// elements apart, dst rows ldd.  a = src, o0 = dst, n0 = R, n1 = lds, n2 = ldd, i0 = C.
+// dst[c][r] = src[r][c] for r < R, 0 for R <= r < fill; c < C.  src rows are lds
+// elements apart, dst rows ldd; fill = i1, or ldd when that is 0 (a narrower fill writes
+// one column block of a wider matrix).
+// a = src, o0 = dst, n0 = R, n1 = lds, n2 = ldd, i0 = C, i1 = fill.
 // Any element type and alignment: one element per access.
 template <typename E>
 __global__ __launch_bounds__(kBlock) void tmb_transpose(const TmbLaunch L) {
@@ -153,7 +160,7 @@ __global__ __launch_bounds__(kBlock) void tmb_transpose(const TmbLaunch L) {
   const int lb = blockIdx.x - L.block_start[gi];
   const E* __restrict__ src = (const E*)G.a;
   E* __restrict__ dst = (E*)G.o0;
-  const int64_t R = G.n0, lds = G.n1, ldd = G.n2;
+  const int64_t R = G.n0, lds = G.n1, ldd = G.n2, fill = G.i1 > 0 ? G.i1 : G.n2;
   const int C = G.i0;
   const int64_t r0 = (int64_t)(lb % G.nbx) * kTile;
   const int c0 = (lb / G.nbx) * kTile;
@@ -167,7 +174,7 @@ __global__ __launch_bounds__(kBlock) void tmb_transpose(const TmbLaunch L) {
   for (int i = ty; i < kTile; i += kBlock / kTile) {
     const int c = c0 + i;
     const int64_t r = r0 + tx;
-    if (c < C && r < ldd) dst[(int64_t)c * ldd + r] = tile[tx][i];
+    if (c < C && r < fill) dst[(int64_t)c * ldd + r] = tile[tx][i];
   }
 }
 
@@ -180,7 +187,7 @@ __global__ __launch_bounds__(kBlock) void tmb_transpose16(const TmbLaunch L) {
   const int lb = blockIdx.x - L.block_start[gi];
   const uint16_t* __restrict__ src = (const uint16_t*)G.a;
   uint16_t* __restrict__ dst = (uint16_t*)G.o0;
-  const int64_t R = G.n0, lds = G.n1, ldd = G.n2;
+  const int64_t R = G.n0, lds = G.n1, ldd = G.n2, fill = G.i1 > 0 ? G.i1 : G.n2;
   const int C = G.i0;
   const int64_t r0 = (int64_t)(lb % G.nbx) * kVTile;
   const int c0 = (lb / G.nbx) * kVTile;
@@ -200,7 +207,7 @@ __global__ __launch_bounds__(kBlock) void tmb_transpose16(const TmbLaunch L) {
     const int i = pass * 16 + q;                   // column of the source tile
     const int c = c0 + i;
     const int64_t r = r0 + v;
-    if (c < C && r < ldd) {
+    if (c < C && r < fill) {
       const uint32_t lo = tile[v][i] | ((uint32_t)tile[v + 1][i] << 16);
       const uint32_t hi = tile[v + 2][i] | ((uint32_t)tile[v + 3][i] << 16);
       *(uint2*)(dst + (int64_t)c * ldd + r) = make_uint2(lo, hi);
@@ -439,7 +446,7 @@ struct TowerBwdWs {
   size_t dxn = 0, du = 0, duT = 0, wlT = 0;
   // DLRM towers: the shared per-feature layer's operands (rows = (sample, feature))
   int64_t Fp = 0;              // feat_out padded to 8
-  size_t dz2 = 0, dz2T = 0, w2T = 0, x2T = 0, part2 = 0;
+  size_t dz2 = 0, dz2T = 0, wcomb = 0, x2T = 0, part2 = 0;
   int ksplit2 = 1, klen2 = 0;
   size_t part = 0;             // weight-gradient slices (split K) / padded dW of a dot tower
   int ksplit = 1, klen = 0;    // of the projection's weight gradient
@@ -516,7 +523,9 @@ dmt_status plan_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, in
         w.Fp = up8(q.feat_out);
         w.dz2 = take((size_t)B * nf * w.Fp * eb);
         w.dz2T = take((size_t)q.feat_out * BFp * eb);
-        w.w2T = take((size_t)n * w.Fp * eb);
+        // row f n + c: column f n + c of the flat layer's weights, then column c of the shared
+        // layer's: what the data gradient of feature f's slice of the pooled block contracts with
+        w.wcomb = take((size_t)wt * (up8(q.out_dim - nf * q.feat_out) + w.Fp) * eb);
         w.x2T = take((size_t)n * BFp * eb);
         if (eb == 2) choose_split(p->T, BFp, &w.ksplit2, &w.klen2);
         if (w.ksplit2 > 1) w.part2 = take((size_t)w.ksplit2 * q.feat_out * n * 4);
@@ -585,11 +594,12 @@ inline int64_t ew_blocks(int64_t count, int vec) {
 }
 
 template <int DT>
-void add_transpose(TmbBatch& b, const void* src, int64_t R, int C, int64_t lds, void* dst, int64_t ldd) {
+void add_transpose(TmbBatch& b, const void* src, int64_t R, int C, int64_t lds, void* dst, int64_t ldd,
+                   int fill = 0) {
   constexpr int tile = DT == DMT_F32 ? kTile : kVTile;
   TmbItem it{};
-  it.a = src; it.o0 = dst; it.n0 = R; it.n1 = lds; it.n2 = ldd; it.i0 = C;
-  it.nbx = (int32_t)((ldd + tile - 1) / tile);
+  it.a = src; it.o0 = dst; it.n0 = R; it.n1 = lds; it.n2 = ldd; it.i0 = C; it.i1 = fill;
+  it.nbx = (int32_t)(((fill > 0 ? fill : ldd) + tile - 1) / tile);
   b.add(it, (int64_t)it.nbx * ((C + tile - 1) / tile));
 }
 
@@ -716,9 +726,10 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
       it.a = wsp + w.dzT; it.o0 = gr[t].db_proj; it.n0 = Bp; it.n1 = B;
       batch2.add(it, O);
     }
-    // W^T [kin][Op]
-    add_transpose<DT>(batch3, dot ? (const void*)(wsp + w.wp) : q.w_proj, O, w.kin, w.kin,
-                      wsp + w.wT, w.Op);
+    // W^T [kin][Op] (a DLRM tower's goes into its combined weights below)
+    if (!dlrm)
+      add_transpose<DT>(batch3, dot ? (const void*)(wsp + w.wp) : q.w_proj, O, w.kin, w.kin,
+                        wsp + w.wT, w.Op);
     // z^T [kin][Bp]: the projection's input, transposed
     if (dot) {
       if (w.np_pad > 0) add_transpose<DT>(batch3, wsp + w.p, B, w.np_pad, w.np_pad, wsp + w.zT, Bp);
@@ -734,7 +745,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
     if (dot) { g.C = wsp + w.dZ; g.ldc = w.kin; }
     else if (q.kind == DMT_TM_CROSS_LINEAR) { g.C = wsp + w.dxn; g.ldc = wt; }
     else { g.C = dx_of(t); g.ldc = wt; }
-    dgrad.push_back(g);
+    if (!dlrm) dgrad.push_back(g);
     TmGroup h{};
     h.A1 = wsp + w.dzT; h.lda1 = (int32_t)Bp; h.K1 = (int32_t)Bp;
     h.W = wsp + w.zT; h.ldw = (int32_t)Bp;
@@ -744,8 +755,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
     h.ldc = w.kin;
     wgrad.push_back(h);
     if (dlrm) {
-      // the shared per-feature layer: the same steps on rows (sample, feature); its data
-      // gradient lands on top of the flat layer's (second launch below)
+      // the shared per-feature layer: the same steps on rows (sample, feature)
       const int nf = p->tower_ntab[t], n = p->tower_uniform_dim[t], F = q.feat_out;
       const int64_t BF = B * nf, BFp = ld_batch(BF, eb);
       {
@@ -761,14 +771,23 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
         it.a = wsp + w.dz2T; it.o0 = gr[t].db_cross[0]; it.n0 = BFp; it.n1 = BF;
         batch2.add(it, F);
       }
-      add_transpose<DT>(batch3, q.w_cross[0], F, n, n, wsp + w.w2T, w.Fp);
       add_transpose<DT>(batch3, x_of(t), BF, n, n, wsp + w.x2T, BFp);
-      TmGroup g2{};
-      g2.A1 = wsp + w.dz2; g2.lda1 = (int32_t)w.Fp; g2.K1 = (int32_t)w.Fp;
-      g2.W = wsp + w.w2T; g2.ldw = (int32_t)w.Fp;
-      g2.M = (int32_t)BF; g2.N = n; g2.epi = EPI_F32_ADD;
-      g2.C = dx_of(t); g2.ldc = n;
-      dgrad2.push_back(g2);
+      // data gradient, both layers in one contraction per feature f: the pooled block's columns
+      // f n .. f n + n - 1 receive [dz1 | dz2 of feature f] . [W1^T rows f n .. | W_f^T], so
+      // grad_pooled is written once; the combined weights are rows of Op + Fp columns
+      const int kc = (int)(w.Op + w.Fp);
+      add_transpose<DT>(batch3, q.w_proj, O, wt, wt, wsp + w.wcomb, kc, (int)w.Op);
+      for (int f = 0; f < nf; ++f) {
+        add_transpose<DT>(batch3, q.w_cross[0], F, n, n,
+                          wsp + w.wcomb + ((size_t)f * n * kc + w.Op) * eb, kc, (int)w.Fp);
+        TmGroup g2{};
+        g2.A0 = wsp + w.dz; g2.lda0 = (int32_t)w.Op; g2.K0 = (int32_t)w.Op;
+        g2.A1 = wsp + w.dz2 + (size_t)f * w.Fp * eb; g2.lda1 = (int32_t)(nf * w.Fp); g2.K1 = (int32_t)w.Fp;
+        g2.W = wsp + w.wcomb + (size_t)f * n * kc * eb; g2.ldw = kc;
+        g2.M = (int32_t)B; g2.N = n; g2.epi = EPI_F32;
+        g2.C = dx_of(t) + (size_t)f * n; g2.ldc = wt;
+        dgrad2.push_back(g2);
+      }
       TmGroup h2{};
       h2.A1 = wsp + w.dz2T; h2.lda1 = (int32_t)BFp; h2.K1 = (int32_t)BFp;
       h2.W = wsp + w.x2T; h2.ldw = (int32_t)BFp;
