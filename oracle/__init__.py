@@ -201,6 +201,20 @@ def tm_cross_linear(x, Wc, bc, W, b) -> np.ndarray:
     return tm_linear(xl, W, b)
 
 
+def tm_cross_lowrank_linear(x, Vc, Uc, bc, W, b) -> np.ndarray:
+    """The DCN Tower Module (paper Sec. 4, Listing 2) with low-rank cross layers, the DCN-v2
+    form whose d x d matrix is the product of a d x r and an r x d factor:
+    x_{l+1} = x0 * (U_l (V_l x_l) + b_l) + x_l with V_l [r, d], U_l [d, r]; then Linear."""
+    x0 = _f64(x)
+    xl = x0
+    for Vl, Ul, bl in zip(Vc, Uc, bc):
+        Vl, Ul, bl = _f64(Vl), _f64(Ul), _f64(bl)
+        t = tm_linear(xl, Vl, np.zeros(Vl.shape[0]))
+        u = tm_linear(t, Ul, bl)
+        xl = x0 * u + xl
+    return tm_linear(xl, W, b)
+
+
 def sort_keys(F: int, B: int, indices, offsets):
     """Stable sort of all lookups by (table, row).  Returns int64 arrays
     (sorted_table, sorted_row, sorted_pos)."""

@@ -129,3 +129,45 @@ def tm_cross_linear_bwd(x, Wc: Sequence, bc: Sequence, W, b, dy):
         dbc[l] = du.sum(axis=0)
         dxl = du @ Wc[l] + dxl
     return dxl + dx0, dWc, dbc, dW, db
+
+
+def tm_cross_lowrank_linear_bwd(x, Vc: Sequence, Uc: Sequence, bc: Sequence, W, b, dy):
+    """x_{l+1} = x0 * (U_l (V_l x_l) + b_l) + x_l, y = x_L W^T + b (Listing 2 with the low-rank
+    DCN-v2 layer).  Returns (dx, [dV_l], [dU_l], [db_l], dW, db).
+
+    With t_l = V_l x_l and u_l = U_l t_l + b_l, going down from l = L-1:
+      du_l = dx_{l+1} * x0;  dx0 += dx_{l+1} * u_l;  dU_l = du_l^T t_l;  db_l = sum_b du_l;
+      dt_l = du_l U_l;  dV_l = dt_l^T x_l;  dx_l = dt_l V_l + dx_{l+1};
+    and dx = dx_0 + dx0.
+    """
+    x0 = _f64(x)
+    Vc = [_f64(v) for v in Vc]
+    Uc = [_f64(u) for u in Uc]
+    bc = [_f64(v) for v in bc]
+    W, b, dy = _f64(W), _f64(b), _f64(dy)
+    xs: List[np.ndarray] = [x0]
+    ts: List[np.ndarray] = []
+    us: List[np.ndarray] = []
+    for Vl, Ul, bl in zip(Vc, Uc, bc):
+        t = xs[-1] @ Vl.T
+        u = t @ Ul.T + bl
+        ts.append(t)
+        us.append(u)
+        xs.append(x0 * u + xs[-1])
+    dxl = dy @ W
+    dW = dy.T @ xs[-1]
+    db = dy.sum(axis=0)
+    dx0 = np.zeros_like(x0)
+    L = len(Vc)
+    dVc: List[np.ndarray] = [None] * L
+    dUc: List[np.ndarray] = [None] * L
+    dbc: List[np.ndarray] = [None] * L
+    for l in range(L - 1, -1, -1):
+        du = dxl * x0
+        dx0 += dxl * us[l]
+        dUc[l] = du.T @ ts[l]
+        dbc[l] = du.sum(axis=0)
+        dt = du @ Uc[l]
+        dVc[l] = dt.T @ xs[l]
+        dxl = dt @ Vc[l] + dxl
+    return dxl + dx0, dVc, dUc, dbc, dW, db

@@ -128,3 +128,20 @@ def test_dlrm_module_by_hand_and_against_einsum():
     # without the per-feature branch (c = 0) it is the plain linear module
     y0 = oracle.tm_dlrm(x, F, Wp, bp, np.zeros((0, N)), np.zeros(0))
     assert np.array_equal(y0, oracle.tm_linear(x, Wp, bp))
+
+
+def test_lowrank_cross_module_equals_the_full_rank_one_with_the_product_matrix():
+    # U (V x) = (U V) x: the low-rank module is the full-rank module with W_l = U_l V_l
+    rng = np.random.default_rng(12)
+    B, d, r, O = 6, 5, 2, 3
+    x = rng.normal(size=(B, d))
+    Vc = [0.4 * rng.normal(size=(r, d)) for _ in range(2)]
+    Uc = [0.4 * rng.normal(size=(d, r)) for _ in range(2)]
+    bc = [rng.normal(size=d) for _ in range(2)]
+    W, b = rng.normal(size=(O, d)), rng.normal(size=O)
+    y = oracle.tm_cross_lowrank_linear(x, Vc, Uc, bc, W, b)
+    full = oracle.tm_cross_linear(x, [U @ V for U, V in zip(Uc, Vc)], bc, W, b)
+    assert np.allclose(y, full, rtol=0, atol=1e-12)
+    # scalar by hand: d = r = 1, x = 2, v = 3, u = 0.5, c = 1: x1 = 2 * (0.5 * 3 * 2 + 1) + 2 = 10; y = 5 * 10
+    y = oracle.tm_cross_lowrank_linear([[2.0]], [[[3.0]]], [[[0.5]]], [[1.0]], [[5.0]], [0.0])
+    assert y.tolist() == [[50.0]]

@@ -158,3 +158,45 @@ def test_dlrm_module_hand_computed_shared_weights():
     assert dx.tolist() == [[14.0, 21.0]]
     assert dWf.tolist() == [[23.0]] and dbf.tolist() == [5.0]
     assert dWp.tolist() == [[0.0, 0.0]] and dbp.tolist() == [0.0]
+
+
+@pytest.mark.parametrize("layers", [1, 2])
+def test_lowrank_cross_against_central_differences(layers):
+    rng = np.random.default_rng(7)
+    B, d, r, O = 3, 5, 2, 2
+    x = rng.normal(size=(B, d))
+    Vc = [0.4 * rng.normal(size=(r, d)) for _ in range(layers)]
+    Uc = [0.4 * rng.normal(size=(d, r)) for _ in range(layers)]
+    bc = [rng.normal(size=d) for _ in range(layers)]
+    W, b = rng.normal(size=(O, d)), rng.normal(size=O)
+    R = rng.normal(size=(B, O))
+    loss = lambda: float(np.sum(oracle.tm_cross_lowrank_linear(x, Vc, Uc, bc, W, b) * R))
+    dx, dVc, dUc, dbc, dW, db = tm_bwd.tm_cross_lowrank_linear_bwd(x, Vc, Uc, bc, W, b, R)
+    _close(dx, _numeric_grad(loss, x), 1e-6)
+    for l in range(layers):
+        _close(dVc[l], _numeric_grad(loss, Vc[l]), 1e-6)
+        _close(dUc[l], _numeric_grad(loss, Uc[l]), 1e-6)
+        _close(dbc[l], _numeric_grad(loss, bc[l]), 1e-6)
+    _close(dW, _numeric_grad(loss, W), 1e-6)
+    _close(db, _numeric_grad(loss, b), 1e-6)
+
+
+def test_lowrank_cross_against_the_full_rank_backward():
+    # with W_l = U_l V_l the input, bias and projection gradients are those of the full-rank
+    # module, and dW_l of the full-rank module factors as dU_l = dW_l V_l^T, dV_l = U_l^T dW_l
+    rng = np.random.default_rng(8)
+    B, d, r, O = 4, 4, 2, 3
+    x = rng.normal(size=(B, d))
+    Vc = [0.4 * rng.normal(size=(r, d)) for _ in range(2)]
+    Uc = [0.4 * rng.normal(size=(d, r)) for _ in range(2)]
+    bc = [rng.normal(size=d) for _ in range(2)]
+    W, b, dy = rng.normal(size=(O, d)), rng.normal(size=O), rng.normal(size=(B, O))
+    dx, dVc, dUc, dbc, dW, db = tm_bwd.tm_cross_lowrank_linear_bwd(x, Vc, Uc, bc, W, b, dy)
+    fx, fWc, fbc, fW, fb = tm_bwd.tm_cross_linear_bwd(x, [U @ V for U, V in zip(Uc, Vc)], bc, W, b, dy)
+    _close(dx, fx)
+    _close(dW, fW)
+    _close(db, fb)
+    for l in range(2):
+        _close(dbc[l], fbc[l])
+        _close(dUc[l], fWc[l] @ Vc[l].T)
+        _close(dVc[l], Uc[l].T @ fWc[l])
