@@ -84,7 +84,7 @@ def main():
     eo = wl.ELT_BYTES[w.pooled_dtype]
     tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
     default = w.name == "backward"
-    on_device = w.name in ("large", "imbalanced")        # id streams too large for numpy
+    on_device = w.name in ("large", "large_lowrank", "imbalanced")   # id streams too large for numpy
     nb = args.batches if default else min(args.batches, 2)
 
     t0 = time.time()
@@ -223,10 +223,7 @@ def main():
     kin = w.tm_in_dims()
     tw = w.tower_widths()
     nl = w.tm_cross_layers if w.tm_kind == wl.TM_CROSS_LINEAR else 0
-    tm_flops = sum(2.0 * B * (o * k + nl * d * d) for o, k, d in zip(w.tm_out, kin, tw))
-    if w.tm_kind == wl.TM_DLRM:      # flat layer over W_t, shared layer over one feature's dim
-        tm_flops = sum(2.0 * B * ((o - len(fs) * w.tm_feat_out) * d + w.tm_feat_out * d)
-                       for o, d, fs in zip(w.tm_out, tw, w.tower_tables()))
+    tm_fwd_flops = tm_flops(wl, w, B)[0]
     tm_bytes = sum(B * (d * eo * (1 + 3 * nl) + o * eo) + (o * k + nl * d * d) * eo
                    for o, k, d in zip(w.tm_out, kin, tw))
     kernels = {}
@@ -248,11 +245,11 @@ def main():
                         frac=round(g / HBM_PEAK_GBS, 4), traffic=None,
                         ms_per_launch=round(per_step / launches, 4), launches_per_step=launches,
                         algorithmic_bytes=int(bytes_of[name]))
-        tf = tm_flops / (per_step * 1e-3) / 1e12
+        tf = tm_fwd_flops / (per_step * 1e-3) / 1e12
         return dict(kernel=name, bound="mfma", achieved=round(tf, 2), peak=MFMA_PEAK_TFLOPS_16BIT,
                     unit="TFLOP/s", frac=round(tf / MFMA_PEAK_TFLOPS_16BIT, 4), traffic=None,
                     ms_per_launch=round(per_step / launches, 4), launches_per_step=launches,
-                    algorithmic_flops=int(tm_flops),
+                    algorithmic_flops=int(tm_fwd_flops),
                     achieved_GBs=round(tm_bytes / (per_step * 1e-3) / 1e9, 1))
 
     dom = max(prof.items(), key=lambda kv: kv[1][0])[0]
@@ -274,6 +271,7 @@ def main():
              "mid_dlrm": "mid tables (lookup fwd + DLRM TM fwd: flat 1024 -> 128 next to a shared 128 -> 32 "
                          "per feature)",
              "large": "large (lookup fwd + 2 cross layers + projection TM fwd)",
+             "large_lowrank": "large tables (lookup fwd + 2 low-rank (r = 512) cross layers + projection TM fwd)",
              "imbalanced": "imbalanced (lookup fwd + linear TM fwd + bwd + rowwise Adagrad)",
              "tiny": "tiny"}
     out = {
@@ -299,20 +297,57 @@ def main():
     return 0
 
 
+def tm_grad_buffers(torch, wl, w):
+    """Float32 device buffers for every parameter gradient of the workload's Tower Modules."""
+    kin, tw = w.tm_in_dims(), w.tower_widths()
+    f32 = lambda *shape: torch.empty(shape, dtype=torch.float32, device="cuda")
+    out = []
+    for o, k, d, fs in zip(w.tm_out, kin, tw, w.tower_tables()):
+        if w.tm_kind == wl.TM_DLRM:
+            po = o - len(fs) * w.tm_feat_out
+            out.append(dict(dw_proj=f32(po, d), db_proj=f32(po), dw_cross=[f32(w.tm_feat_out, d // len(fs))],
+                            db_cross=[f32(w.tm_feat_out)]))
+        elif w.tm_kind == wl.TM_CROSS_LOWRANK_LINEAR:
+            r = w.tm_feat_out
+            out.append(dict(dw_proj=f32(o, k), db_proj=f32(o),
+                            dw_cross=[f32(*sh) for _ in range(w.tm_cross_layers) for sh in ((r, d), (d, r))],
+                            db_cross=[f32(d) for _ in range(w.tm_cross_layers)]))
+        else:
+            nl = w.tm_cross_layers if w.tm_kind == wl.TM_CROSS_LINEAR else 0
+            out.append(dict(dw_proj=f32(o, k), db_proj=f32(o), dw_cross=[f32(d, d) for _ in range(nl)],
+                            db_cross=[f32(d) for _ in range(nl)]))
+    return out
+
+
+def tm_flops(wl, w, B):
+    """(forward, backward with recomputation, backward on kept activations) FLOPs of the Tower
+    Modules' contractions: a projection counts once forward and twice backward (data and weight
+    gradient); a full-rank cross layer d^2 forward, 2 d^2 backward plus d^2 recomputed; a low-rank
+    one 2 d r forward (t and u), 4 d r backward plus t recomputed always and u unless kept."""
+    kin, tw = w.tm_in_dims(), w.tower_widths()
+    fwd = bwd = kept = 0.0
+    for o, k, d, fs in zip(w.tm_out, kin, tw, w.tower_tables()):
+        proj, cf, cb, ck = o * k, 0, 0, 0
+        if w.tm_kind == wl.TM_DLRM:
+            proj = (o - len(fs) * w.tm_feat_out) * d + w.tm_feat_out * d
+        elif w.tm_kind == wl.TM_CROSS_LINEAR:
+            cf, cb, ck = d * d, 3 * d * d, 2 * d * d
+        elif w.tm_kind == wl.TM_CROSS_LOWRANK_LINEAR:
+            dr = d * w.tm_feat_out
+            cf, cb, ck = 2 * dr, 6 * dr, 5 * dr
+        fwd += 2.0 * B * (proj + w.tm_cross_layers * cf)
+        bwd += 2.0 * B * (2 * proj + w.tm_cross_layers * cb)
+        kept += 2.0 * B * (2 * proj + w.tm_cross_layers * ck)
+    return fwd, bwd, kept
+
+
 def time_tm_bwd(torch, dmt, wl, w, plan, tm_params, pooled, tm_out, tm_ws, B, steps):
     """dmt_tower_module_bwd on the step's pooled / tm_out tensors and a N(0,1) output gradient:
     ms per call, its kernels' shares, and the MFMA rate over the contractions' FLOPs (each
     projection twice: data and weight gradient; each cross layer three times: recomputed
     forward, data and weight gradient)."""
-    kin, tw = w.tm_in_dims(), w.tower_widths()
-    nl = w.tm_cross_layers if w.tm_kind == wl.TM_CROSS_LINEAR else 0
-    f32 = lambda *shape: torch.empty(shape, dtype=torch.float32, device="cuda")
-    grads = [dict(dw_proj=f32(o, k), db_proj=f32(o), dw_cross=[f32(d, d) for _ in range(nl)],
-                  db_cross=[f32(d) for _ in range(nl)]) for o, k, d in zip(w.tm_out, kin, tw)]
-    if w.tm_kind == wl.TM_DLRM:
-        grads = [dict(dw_proj=f32(o - len(fs) * w.tm_feat_out, d), db_proj=f32(o - len(fs) * w.tm_feat_out),
-                      dw_cross=[f32(w.tm_feat_out, d // len(fs))], db_cross=[f32(w.tm_feat_out)])
-                 for o, d, fs in zip(w.tm_out, tw, w.tower_tables())]
+    tw = w.tower_widths()
+    grads = tm_grad_buffers(torch, wl, w)
     arr = dmt.make_tm_grads(grads)
     ws = torch.empty(dmt.dmt_tm_bwd_workspace_bytes(plan, tm_params, B), dtype=torch.uint8, device="cuda")
     g = torch.Generator(device="cuda")
@@ -334,10 +369,7 @@ def time_tm_bwd(torch, dmt, wl, w, plan, tm_params, pooled, tm_out, tm_ws, B, st
         run()
     prof = dmt.dmt_profile_read(plan)
     dmt.dmt_profile_enable(plan, 0)
-    flops = sum(2.0 * B * (2 * o * k + 3 * nl * d * d) for o, k, d in zip(w.tm_out, kin, tw))
-    if w.tm_kind == wl.TM_DLRM:
-        flops = sum(4.0 * B * ((o - len(fs) * w.tm_feat_out) * d + w.tm_feat_out * d)
-                    for o, d, fs in zip(w.tm_out, tw, w.tower_tables()))
+    _, flops, flops_kept = tm_flops(wl, w, B)
     gemm_ms = prof.get("tm_bwd_gemm", (0.0, 0))[0] / n
     out = dict(ms_per_call=round(ms, 4), workspace_GB=round(ws.numel() / 1e9, 3),
                kernels={k: dict(ms_per_call=round(v[0] / n, 4), launches_per_call=v[1] // n)
@@ -364,7 +396,7 @@ def time_tm_bwd(torch, dmt, wl, w, plan, tm_params, pooled, tm_out, tm_ws, B, st
         out["with_kept_activations"] = dict(kept_GB=round(kept_bytes / 1e9, 3),
                                             fwd_keep_ms_per_call=round(res["fwd_keep"], 4),
                                             bwd_ms_per_call=round(res["bwd"], 4),
-                                            bwd_flops=int(flops - sum(2.0 * B * nl * d * d for d in tw)))
+                                            bwd_flops=int(flops_kept))
     return out
 
 
@@ -373,16 +405,8 @@ def time_whole_step(torch, dmt, wl, w, plan, tm_params, pooled, tm_out, tm_ws, b
     forward) -> Tower Module backward on a fixed N(0,1) gradient of the module outputs -> sorted
     segment-reduce + rowwise Adagrad fed by the module's dL/d(pooled).  Timed after everything
     else; not part of `value`."""
-    kin, tw = w.tm_in_dims(), w.tower_widths()
-    nl = w.tm_cross_layers if w.tm_kind == wl.TM_CROSS_LINEAR else 0
-    f32 = lambda *shape: torch.empty(shape, dtype=torch.float32, device="cuda")
-    if w.tm_kind == wl.TM_DLRM:
-        grads = [dict(dw_proj=f32(o - len(fs) * w.tm_feat_out, d), db_proj=f32(o - len(fs) * w.tm_feat_out),
-                      dw_cross=[f32(w.tm_feat_out, d // len(fs))], db_cross=[f32(w.tm_feat_out)])
-                 for o, d, fs in zip(w.tm_out, tw, w.tower_tables())]
-    else:
-        grads = [dict(dw_proj=f32(o, k), db_proj=f32(o), dw_cross=[f32(d, d) for _ in range(nl)],
-                      db_cross=[f32(d) for _ in range(nl)]) for o, k, d in zip(w.tm_out, kin, tw)]
+    tw = w.tower_widths()
+    grads = tm_grad_buffers(torch, wl, w)
     arr = dmt.make_tm_grads(grads)
     ws = torch.empty(dmt.dmt_tm_bwd_workspace_bytes(plan, tm_params, B), dtype=torch.uint8, device="cuda")
     kept_bytes = dmt.dmt_tm_kept_bytes(plan, tm_params, B, w.tm_dtype)

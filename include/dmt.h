@@ -64,9 +64,11 @@ typedef enum {
   DMT_TM_LINEAR_RELU = 1,  /* y = max(0, W x + b)                                                 */
   DMT_TM_DOT_LINEAR = 2,   /* z = [pairwise dots (i<j) | x], y = W z + b  (Sec. 3.2, Sec. 4)      */
   DMT_TM_CROSS_LINEAR = 3, /* x_{l+1} = x0 * (W_l x_l + b_l) + x_l, y = W x_L + b  (Listing 2)    */
-  DMT_TM_DLRM = 4          /* y = [W x + b | W_f x_0 + b_f | ... | W_f x_{F-1} + b_f]: the flat
+  DMT_TM_DLRM = 4,         /* y = [W x + b | W_f x_0 + b_f | ... | W_f x_{F-1} + b_f]: the flat
                               projection next to ONE projection shared by every feature's
                               embedding x_f  (Listing 1 with c > 0)                                */
+  DMT_TM_CROSS_LOWRANK_LINEAR = 5 /* x_{l+1} = x0 * (U_l (V_l x_l) + b_l) + x_l, y = W x_L + b:
+                              Listing 2 with DCN-v2's low-rank cross layer                         */
 } dmt_tm_kind;
 
 #define DMT_MAX_CROSS_LAYERS 4
@@ -152,12 +154,17 @@ dmt_status dmt_tower_lookup_fwd(const dmt_plan* plan, const int32_t* indices,
  *                 b_cross[0] [feat_out]; the first out_dim - nf * feat_out (>= 1)
  *                 outputs from w_proj [out_dim - nf * feat_out][W_t], b_proj.
  *                 num_cross_layers is ignored.
+ *   CROSS_LOWRANK_LINEAR: num_cross_layers <= DMT_MAX_CROSS_LAYERS / 2 layers of rank
+ *                 feat_out = r (a multiple of 8 for the 16-bit types): w_cross[2 l] = V_l
+ *                 [r][W_t], w_cross[2 l + 1] = U_l [W_t][r], b_cross[l] [W_t]; then
+ *                 w_proj [out_dim][W_t]
  */
 typedef struct {
   int32_t kind;              /* dmt_tm_kind */
   int32_t out_dim;           /* O_t */
   int32_t num_cross_layers;  /* CROSS_LINEAR only, <= DMT_MAX_CROSS_LAYERS */
-  int32_t feat_out;          /* DLRM only: outputs of the per-feature layer (c D) */
+  int32_t feat_out;          /* DLRM: outputs of the per-feature layer (c D);
+                                CROSS_LOWRANK_LINEAR: the rank r */
   const void* w_proj;
   const void* b_proj;
   const void* w_cross[DMT_MAX_CROSS_LAYERS];
@@ -191,7 +198,7 @@ dmt_status dmt_tower_module_fwd(const dmt_plan* plan, const dmt_tm_params* per_t
 /*
  * Training forward: dmt_tower_module_fwd that also keeps, in `kept`, what the
  * backward would otherwise recompute: x_{l+1} and u_l = W_l x_l + b_l of every
- * cross layer (paper Listing 2), each [B][W_t] in `dtype`.  tm_out is bit for
+ * cross layer, full-rank or low-rank (paper Listing 2), each [B][W_t] in `dtype`.  tm_out is bit for
  * bit that of dmt_tower_module_fwd.  Towers of the other kinds keep nothing
  * (their backward recomputes the dot terms, which is cheaper than storing them).
  *   kept  dev, at least dmt_tm_kept_bytes(plan, per_tower, B, dtype), 256-byte
@@ -210,7 +217,8 @@ dmt_status dmt_tower_module_fwd_keep(const dmt_plan* plan, const dmt_tm_params* 
  * shaped like the parameters themselves (dw_proj [O_t][K_t] with K_t the row
  * length of w_proj; dw_cross[l] [W_t][W_t]; the db_* vectors; for a DLRM tower
  * dw_proj has the flat layer's out_dim - nf * feat_out rows and dw_cross[0] /
- * db_cross[0] receive the shared per-feature layer's [feat_out][n] / [feat_out]).  Every array is
+ * db_cross[0] receive the shared per-feature layer's [feat_out][n] / [feat_out];
+ * for a low-rank cross tower dw_cross[2 l] / dw_cross[2 l + 1] are dV_l / dU_l).  Every array is
  * overwritten, not accumulated into.  Caller-owned.
  */
 typedef struct {
@@ -240,6 +248,8 @@ size_t dmt_tm_bwd_workspace_bytes(const dmt_plan* plan, const dmt_tm_params* per
  *                  du_l = dx_{l+1} * x0, dx0 += dx_{l+1} * u_l, dW_l = du_l^T x_l,
  *                  db_l = sum_b du_l, dx_l = du_l W_l + dx_{l+1};
  *                  grad_pooled = dx_0 + dx0
+ *   low-rank cross the same with t_l = V_l x_l, u_l = U_l t_l + b_l: dU_l = du_l^T t_l,
+ *                  dt_l = du_l U_l, dV_l = dt_l^T x_l, dx_l = dt_l V_l + dx_{l+1}
  * The forward's intermediates are recomputed (dot terms; u_l and x_l of the cross
  * layers) unless `kept` hands over what dmt_tower_module_fwd_keep stored for
  * the same plan, towers, B and dtype.

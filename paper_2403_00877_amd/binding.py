@@ -18,6 +18,7 @@ from . import build as _build
 DMT_OK, DMT_EINVAL, DMT_ENOTSUP, DMT_EBOUNDS, DMT_ENOMEM, DMT_EHIP = range(6)
 DMT_F32, DMT_F16, DMT_BF16 = 0, 1, 2
 DMT_TM_LINEAR, DMT_TM_LINEAR_RELU, DMT_TM_DOT_LINEAR, DMT_TM_CROSS_LINEAR, DMT_TM_DLRM = 0, 1, 2, 3, 4
+DMT_TM_CROSS_LOWRANK_LINEAR = 5
 DMT_MAX_CROSS_LAYERS = 4
 
 DTYPE_CODE = {"f32": DMT_F32, "f16": DMT_F16, "bf16": DMT_BF16,
@@ -25,7 +26,7 @@ DTYPE_CODE = {"f32": DMT_F32, "f16": DMT_F16, "bf16": DMT_BF16,
 TORCH_DTYPE = {DMT_F32: torch.float32, DMT_F16: torch.float16, DMT_BF16: torch.bfloat16}
 TM_KIND_CODE = {"linear": DMT_TM_LINEAR, "linear_relu": DMT_TM_LINEAR_RELU,
                 "dot_linear": DMT_TM_DOT_LINEAR, "cross_linear": DMT_TM_CROSS_LINEAR,
-                "dlrm": DMT_TM_DLRM}
+                "dlrm": DMT_TM_DLRM, "cross_lowrank_linear": DMT_TM_CROSS_LOWRANK_LINEAR}
 
 
 class dmt_tm_params(ctypes.Structure):
@@ -193,11 +194,14 @@ def make_tm_params(per_tower: Sequence[dict]):
         a.out_dim = int(p["out_dim"])
         wc = p.get("w_cross") or []
         a.num_cross_layers = len(wc)
+        if a.kind == DMT_TM_CROSS_LOWRANK_LINEAR:       # w_cross = [V_0, U_0, V_1, U_1, ...]
+            a.num_cross_layers = len(wc) // 2
         a.feat_out = int(p.get("feat_out") or 0)
         a.w_proj = p["w_proj"].data_ptr()
         a.b_proj = p["b_proj"].data_ptr()
-        for l, (w, b) in enumerate(zip(wc, p.get("b_cross") or [])):
+        for l, w in enumerate(wc):
             a.w_cross[l] = w.data_ptr()
+        for l, b in enumerate(p.get("b_cross") or []):
             a.b_cross[l] = b.data_ptr()
     return arr
 
@@ -222,8 +226,9 @@ def make_tm_grads(per_tower: Sequence[dict]):
     for a, g in zip(arr, per_tower):
         a.dw_proj = g["dw_proj"].data_ptr()
         a.db_proj = g["db_proj"].data_ptr()
-        for l, (w, b) in enumerate(zip(g.get("dw_cross") or [], g.get("db_cross") or [])):
+        for l, w in enumerate(g.get("dw_cross") or []):
             a.dw_cross[l] = w.data_ptr()
+        for l, b in enumerate(g.get("db_cross") or []):
             a.db_cross[l] = b.data_ptr()
     return arr
 

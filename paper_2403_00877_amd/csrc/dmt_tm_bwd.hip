@@ -407,6 +407,10 @@ __global__ __launch_bounds__(kBlock) void tmb_cross_prep(const TmbLaunch L) {
 
 inline int64_t up8(int64_t v) { return (v + 7) / 8 * 8; }
 
+inline bool is_cross(const dmt_tm_params& q) {
+  return q.kind == DMT_TM_CROSS_LINEAR || q.kind == DMT_TM_CROSS_LOWRANK_LINEAR;
+}
+
 // Row length (elements of eb bytes) of a transposed operand whose rows hold `count` batch
 // entries: a multiple of 8, and never a multiple of 1 KB in bytes.  With a power-of-two
 // row pitch the 256 rows a GEMM block reads in one K step all fall on the same memory channels;
@@ -444,6 +448,11 @@ struct TowerBwdWs {
   size_t p = 0, wp = 0, dZ = 0;                                 // dot towers
   size_t xl[DMT_MAX_CROSS_LAYERS] = {}, u[DMT_MAX_CROSS_LAYERS] = {};   // cross towers
   size_t dxn = 0, du = 0, duT = 0, wlT = 0;
+  // low-rank cross towers: t_l = V_l x_l per layer; per-layer scratch t^T, U_l^T, V_l^T,
+  // dt (float32), dt rounded and its transpose; rp = rank padded to 8
+  size_t tl[DMT_MAX_CROSS_LAYERS] = {};
+  size_t tT = 0, uT = 0, vT = 0, dtf = 0, dtq = 0, dtT = 0;
+  int rp = 0;
   // DLRM towers: the shared per-feature layer's operands (rows = (sample, feature))
   int64_t Fp = 0;              // feat_out padded to 8
   size_t dz2 = 0, dz2T = 0, wcomb = 0, x2T = 0, part2 = 0;
@@ -472,6 +481,7 @@ dmt_status plan_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, in
     }
     tiles_proj += ((q.out_dim + 255) / 256) * ((kin + 255) / 256);
     if (q.kind == DMT_TM_CROSS_LINEAR) tiles_cross += ((wt + 255) / 256) * ((wt + 255) / 256);
+    if (q.kind == DMT_TM_CROSS_LOWRANK_LINEAR) tiles_cross += ((wt + 255) / 256) * ((q.feat_out + 255) / 256);
   }
   for (int32_t t = 0; t < p->T; ++t) {
     const dmt_tm_params& q = tp[t];
@@ -513,6 +523,32 @@ dmt_status plan_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, in
         w.duT = take((size_t)wt * Bp * eb);
         w.wlT = take((size_t)wt * wt * eb);
         break;
+      case DMT_TM_CROSS_LOWRANK_LINEAR: {
+        const int L = q.num_cross_layers, r = q.feat_out;
+        if (L < 1 || 2 * L > DMT_MAX_CROSS_LAYERS || r < 1) return DMT_EINVAL;
+        if (eb == 2 && r % 8 != 0) return DMT_ENOTSUP;
+        for (int l = 0; l < L; ++l)
+          if (!q.w_cross[2 * l] || !q.w_cross[2 * l + 1] || !q.b_cross[l] ||
+              (((uintptr_t)q.w_cross[2 * l] | (uintptr_t)q.w_cross[2 * l + 1]) & 15))
+            return DMT_EINVAL;
+        w.rp = (int)up8(r);
+        for (int l = 0; l < L; ++l) {
+          w.tl[l] = take((size_t)B * r * eb);
+          if (have_kept) continue;
+          w.xl[l] = take((size_t)B * wt * eb);
+          w.u[l] = take((size_t)B * wt * eb);
+        }
+        w.dxn = take((size_t)B * wt * 4);
+        w.du = take((size_t)B * wt * eb);
+        w.duT = take((size_t)wt * Bp * eb);
+        w.tT = take((size_t)r * Bp * eb);
+        w.uT = take((size_t)r * wt * eb);
+        w.vT = take((size_t)wt * w.rp * eb);
+        w.dtf = take((size_t)B * r * 4);
+        w.dtq = take((size_t)B * w.rp * eb);
+        w.dtT = take((size_t)r * Bp * eb);
+        break;
+      }
       case DMT_TM_DLRM: {
         const int nf = p->tower_ntab[t], n = p->tower_uniform_dim[t];
         if (n == 0) return DMT_ENOTSUP;
@@ -546,6 +582,8 @@ dmt_status plan_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, in
       part = (size_t)w.ksplit * O1 * w.kin * 4;
     if (q.kind == DMT_TM_CROSS_LINEAR && w.ksplit_c > 1)
       part = std::max(part, (size_t)w.ksplit_c * wt * wt * 4);
+    if (q.kind == DMT_TM_CROSS_LOWRANK_LINEAR && w.ksplit_c > 1)
+      part = std::max(part, (size_t)w.ksplit_c * wt * q.feat_out * 4);
     if (part) w.part = take(part);
   }
   *bytes = off;
@@ -653,7 +691,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
   std::vector<int64_t> nb_mfma, nb_simple, nb_pack;
   for (int32_t t = 0; t < p->T; ++t) {
     const dmt_tm_params& q = tp[t];
-    if (q.kind == DMT_TM_CROSS_LINEAR) max_layers = std::max(max_layers, q.num_cross_layers);
+    if (is_cross(q)) max_layers = std::max(max_layers, q.num_cross_layers);
     if (q.kind != DMT_TM_DOT_LINEAR) continue;
     const TowerBwdWs& w = ws[t];
     TmAuxItem it{};
@@ -679,16 +717,30 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
   launch_aux<DT>(p, B, dots_simple, nb_simple, 1, s);
   launch_aux<DT>(p, B, packs, nb_pack, 2, s);
 
-  // ---- ... and the cross layers' u_l = x_l W_l^T + b_l, x_{l+1} = x0 * u_l + x_l
-  std::vector<TmGroup> groups;
-  for (int l = 0; l < max_layers && !keptp; ++l) {
+  // ---- ... and the cross layers' u_l = x_l W_l^T + b_l, x_{l+1} = x0 * u_l + x_l (low-rank
+  // layers: t_l = x_l V_l^T, which the backward needs whether or not the rest was kept, then
+  // u_l = t_l U_l^T + b_l)
+  std::vector<TmGroup> groups, groups_t;
+  for (int l = 0; l < max_layers; ++l) {
     for (int32_t t = 0; t < p->T; ++t) {
       const dmt_tm_params& q = tp[t];
-      if (q.kind != DMT_TM_CROSS_LINEAR || l >= q.num_cross_layers) continue;
+      if (!is_cross(q) || l >= q.num_cross_layers) continue;
       const int wt = p->tower_width[t];
       TmGroup g{};
       g.A1 = xl_of(t, l); g.lda1 = wt; g.K1 = wt;
       g.W = q.w_cross[l]; g.ldw = wt; g.bias = q.b_cross[l];
+      if (q.kind == DMT_TM_CROSS_LOWRANK_LINEAR) {
+        const int r = q.feat_out;
+        TmGroup h{};
+        h.A1 = xl_of(t, l); h.lda1 = wt; h.K1 = wt;
+        h.W = q.w_cross[2 * l]; h.ldw = wt; h.bias = nullptr;
+        h.C = wsp + ws[t].tl[l]; h.ldc = r;
+        h.M = (int32_t)B; h.N = r; h.epi = EPI_BIAS;
+        groups_t.push_back(h);
+        g.A1 = wsp + ws[t].tl[l]; g.lda1 = r; g.K1 = r;
+        g.W = q.w_cross[2 * l + 1]; g.ldw = r;
+      }
+      if (keptp) continue;
       g.C = wsp + ws[t].u[l]; g.ldc = wt;
       g.M = (int32_t)B; g.N = wt; g.epi = EPI_BIAS;
       groups.push_back(g);
@@ -698,6 +750,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
       it.nbx = (int32_t)ew_blocks(it.n0, V);
       batch.add(it, it.nbx);
     }
+    launch_groups<DT>(p, groups_t, s, false, DMT_K_TM_BWD_GEMM);
     launch_groups<DT>(p, groups, s, false, DMT_K_TM_BWD_GEMM);
     ok &= launch_items(p, batch, tmb_cross_next<DT>, s);
   }
@@ -735,7 +788,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
       if (w.np_pad > 0) add_transpose<DT>(batch3, wsp + w.p, B, w.np_pad, w.np_pad, wsp + w.zT, Bp);
       add_transpose<DT>(batch3, x_of(t), B, wt, wt, wsp + w.zT + (size_t)w.np_pad * Bp * eb, Bp);
     } else {
-      const void* z = q.kind == DMT_TM_CROSS_LINEAR ? xl_of(t, q.num_cross_layers) : x_of(t);
+      const void* z = is_cross(q) ? xl_of(t, q.num_cross_layers) : x_of(t);
       add_transpose<DT>(batch3, z, B, wt, wt, wsp + w.zT, Bp);
     }
     TmGroup g{};
@@ -743,7 +796,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
     g.W = wsp + w.wT; g.ldw = (int32_t)w.Op;
     g.M = (int32_t)B; g.N = w.kin; g.epi = EPI_F32;
     if (dot) { g.C = wsp + w.dZ; g.ldc = w.kin; }
-    else if (q.kind == DMT_TM_CROSS_LINEAR) { g.C = wsp + w.dxn; g.ldc = wt; }
+    else if (is_cross(q)) { g.C = wsp + w.dxn; g.ldc = wt; }
     else { g.C = dx_of(t); g.ldc = wt; }
     if (!dlrm) dgrad.push_back(g);
     TmGroup h{};
@@ -842,11 +895,11 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
 
   // ---- cross towers: layers from the last to the first; dx0 accumulates in the output block,
   // where the first layer's data gradient then lands on top of it
-  TmbBatch sums;
+  TmbBatch sums, sums2, prep_dt, prep_dt16;
   for (int l = max_layers - 1; l >= 0; --l) {
     for (int32_t t = 0; t < p->T; ++t) {
       const dmt_tm_params& q = tp[t];
-      if (q.kind != DMT_TM_CROSS_LINEAR || l >= q.num_cross_layers) continue;
+      if (!is_cross(q) || l >= q.num_cross_layers) continue;
       const TowerBwdWs& w = ws[t];
       const int wt = p->tower_width[t];
       {
@@ -858,12 +911,67 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
       }
       add_transpose<DT>(batch2, wsp + w.du, B, wt, wt, wsp + w.duT, Bp);
       add_transpose<DT>(batch2, xl_of(t, l), B, wt, wt, wsp + w.zT, Bp);
-      add_transpose<DT>(batch2, q.w_cross[l], wt, wt, wt, wsp + w.wlT, wt);
       {
         TmbItem it{};
         it.a = wsp + w.duT; it.o0 = gr[t].db_cross[l]; it.n0 = Bp; it.n1 = B;
         batch3.add(it, wt);
       }
+      if (q.kind == DMT_TM_CROSS_LOWRANK_LINEAR) {
+        // stage 1: dt = du U_l (float32) and dU_l = du^T t_l; stage 2, once dt is rounded and
+        // transposed: dx_l = dt V_l + dx_{l+1} and dV_l = dt^T x_l
+        const int r = q.feat_out;
+        add_transpose<DT>(batch2, wsp + w.tl[l], B, r, r, wsp + w.tT, Bp);
+        add_transpose<DT>(batch2, q.w_cross[2 * l + 1], wt, r, r, wsp + w.uT, wt);     // U_l^T [r][wt]
+        add_transpose<DT>(batch2, q.w_cross[2 * l], r, wt, wt, wsp + w.vT, w.rp);      // V_l^T [wt][rp]
+        TmGroup g1{};
+        g1.A1 = wsp + w.du; g1.lda1 = wt; g1.K1 = wt;
+        g1.W = wsp + w.uT; g1.ldw = wt;
+        g1.M = (int32_t)B; g1.N = r; g1.epi = EPI_F32;
+        g1.C = wsp + w.dtf; g1.ldc = r;
+        dgrad.push_back(g1);
+        TmGroup h1{};
+        h1.A1 = wsp + w.duT; h1.lda1 = (int32_t)Bp; h1.K1 = (int32_t)Bp;
+        h1.W = wsp + w.tT; h1.ldw = (int32_t)Bp;
+        h1.M = wt; h1.N = r; h1.epi = EPI_F32;
+        h1.ksplit = w.ksplit_c; h1.klen = w.klen_c; h1.cstride = (int64_t)wt * r;
+        h1.C = w.ksplit_c > 1 ? (void*)(wsp + w.part) : (void*)gr[t].dw_cross[2 * l + 1];
+        h1.ldc = r;
+        wgrad.push_back(h1);
+        if (w.ksplit_c > 1) {
+          TmbItem it{};
+          it.a = wsp + w.part; it.o0 = gr[t].dw_cross[2 * l + 1]; it.n0 = (int64_t)wt * r;
+          it.i0 = wt; it.i1 = 0; it.i2 = 0; it.i3 = r; it.i4 = w.ksplit_c;
+          sums.add(it, ((int64_t)wt * r + kBlock - 1) / kBlock);
+        }
+        {
+          TmbItem it{};
+          it.a = wsp + w.dtf; it.o0 = wsp + w.dtq; it.o1 = wsp + w.dtT;
+          it.n0 = B; it.n1 = Bp; it.n2 = r; it.i0 = r; it.i1 = w.rp;
+          add_prep<DT>(prep_dt, prep_dt16, it);
+        }
+        TmGroup g2{};
+        g2.A1 = wsp + w.dtq; g2.lda1 = w.rp; g2.K1 = w.rp;
+        g2.W = wsp + w.vT; g2.ldw = w.rp;
+        g2.M = (int32_t)B; g2.N = wt; g2.epi = EPI_F32_ADD;
+        g2.C = l == 0 ? (void*)dx_of(t) : (void*)(wsp + w.dxn); g2.ldc = wt;
+        dgrad2.push_back(g2);
+        TmGroup h2{};
+        h2.A1 = wsp + w.dtT; h2.lda1 = (int32_t)Bp; h2.K1 = (int32_t)Bp;
+        h2.W = wsp + w.zT; h2.ldw = (int32_t)Bp;
+        h2.M = r; h2.N = wt; h2.epi = EPI_F32;
+        h2.ksplit = w.ksplit_c; h2.klen = w.klen_c; h2.cstride = (int64_t)r * wt;
+        h2.C = w.ksplit_c > 1 ? (void*)(wsp + w.part) : (void*)gr[t].dw_cross[2 * l];
+        h2.ldc = wt;
+        wgrad2.push_back(h2);
+        if (w.ksplit_c > 1) {
+          TmbItem it{};
+          it.a = wsp + w.part; it.o0 = gr[t].dw_cross[2 * l]; it.n0 = (int64_t)r * wt;
+          it.i0 = r; it.i1 = 0; it.i2 = 0; it.i3 = wt; it.i4 = w.ksplit_c;
+          sums2.add(it, ((int64_t)r * wt + kBlock - 1) / kBlock);
+        }
+        continue;
+      }
+      add_transpose<DT>(batch2, q.w_cross[l], wt, wt, wt, wsp + w.wlT, wt);
       TmGroup g{};
       g.A1 = wsp + w.du; g.lda1 = wt; g.K1 = wt;
       g.W = wsp + w.wlT; g.ldw = wt;
@@ -891,6 +999,12 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
     launch_groups<DT>(p, dgrad, s, false, DMT_K_TM_BWD_GEMM);
     launch_groups<DT>(p, wgrad, s, false, DMT_K_TM_BWD_GEMM);
     ok &= launch_items(p, sums, tmb_sum_slices, s);
+    // low-rank towers, stage 2 (the slices' buffer is free again after the sums above)
+    ok &= launch_items(p, prep_dt, tmb_prep_dy<DT>, s);
+    if constexpr (DT != DMT_F32) ok &= launch_items(p, prep_dt16, tmb_prep_dy16<DT>, s);
+    launch_groups<DT>(p, dgrad2, s, false, DMT_K_TM_BWD_GEMM);
+    launch_groups<DT>(p, wgrad2, s, false, DMT_K_TM_BWD_GEMM);
+    ok &= launch_items(p, sums2, tmb_sum_slices, s);
   }
   if (!ok) return DMT_ENOTSUP;
   return hipGetLastError() == hipSuccess ? DMT_OK : DMT_EHIP;
@@ -929,6 +1043,10 @@ extern "C" dmt_status dmt_tower_module_bwd(const dmt_plan* plan, const dmt_tm_pa
       for (int l = 0; l < q.num_cross_layers && l < DMT_MAX_CROSS_LAYERS; ++l)
         if (!grads[t].dw_cross[l] || !grads[t].db_cross[l]) return DMT_EINVAL;
     if (q.kind == DMT_TM_DLRM && (!grads[t].dw_cross[0] || !grads[t].db_cross[0])) return DMT_EINVAL;
+    if (q.kind == DMT_TM_CROSS_LOWRANK_LINEAR)
+      for (int l = 0; l < q.num_cross_layers && 2 * l + 1 < DMT_MAX_CROSS_LAYERS; ++l)
+        if (!grads[t].dw_cross[2 * l] || !grads[t].dw_cross[2 * l + 1] || !grads[t].db_cross[l])
+          return DMT_EINVAL;
   }
   std::vector<TowerBwdWs> ws;
   size_t bytes = 0;

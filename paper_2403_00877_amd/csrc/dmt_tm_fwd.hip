@@ -27,6 +27,7 @@ namespace {
 
 struct TowerWs {
   size_t z_off = 0, wp_off = 0, x_off[2] = {0, 0};
+  size_t t_off = 0;            // low-rank cross layers: t = V_l x_l, [B][r]
   int np = 0, np_pad = 0;
 };
 
@@ -63,6 +64,19 @@ dmt_status plan_tm(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, int eb
         w.x_off[0] = take((size_t)B * wt * eb);
         if (q.num_cross_layers > 1) w.x_off[1] = take((size_t)B * wt * eb);
         break;
+      case DMT_TM_CROSS_LOWRANK_LINEAR: {
+        const int L = q.num_cross_layers, r = q.feat_out;
+        if (L < 1 || 2 * L > DMT_MAX_CROSS_LAYERS || r < 1) return DMT_EINVAL;
+        if (eb == 2 && r % 8 != 0) return DMT_ENOTSUP;           // t is a K operand: 16-byte pieces
+        for (int l = 0; l < L; ++l)
+          if (!q.w_cross[2 * l] || !q.w_cross[2 * l + 1] || !q.b_cross[l] ||
+              (((uintptr_t)q.w_cross[2 * l] | (uintptr_t)q.w_cross[2 * l + 1]) & 15))
+            return DMT_EINVAL;
+        w.x_off[0] = take((size_t)B * wt * eb);
+        if (L > 1) w.x_off[1] = take((size_t)B * wt * eb);
+        w.t_off = take((size_t)B * r * eb);
+        break;
+      }
       case DMT_TM_DLRM: {
         const int nf = p->tower_ntab[t];
         if (p->tower_uniform_dim[t] == 0) return DMT_ENOTSUP;   // one shared layer needs one dim
@@ -115,7 +129,8 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
   std::vector<int64_t> nb_mfma, nb_simple, nb_pack;
   for (int32_t t = 0; t < p->T; ++t) {
     const dmt_tm_params& q = tp[t];
-    if (q.kind == DMT_TM_CROSS_LINEAR) max_layers = std::max(max_layers, q.num_cross_layers);
+    if (q.kind == DMT_TM_CROSS_LINEAR || q.kind == DMT_TM_CROSS_LOWRANK_LINEAR)
+      max_layers = std::max(max_layers, q.num_cross_layers);
     if (q.kind != DMT_TM_DOT_LINEAR) continue;
     const TowerWs& w = ws[t];
     TmAuxItem it{};
@@ -140,25 +155,39 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
   launch_aux<DT>(p, B, dots_simple, nb_simple, 1, s);
   launch_aux<DT>(p, B, packs, nb_pack, 2, s);
 
-  // cross layers, one grouped launch per layer index
-  std::vector<TmGroup> groups;
+  // cross layers, one grouped launch per layer index (low-rank layers: t = V_l x_l first)
+  std::vector<TmGroup> groups, groups_t;
   for (int l = 0; l < max_layers; ++l) {
     for (int32_t t = 0; t < p->T; ++t) {
       const dmt_tm_params& q = tp[t];
-      if (q.kind != DMT_TM_CROSS_LINEAR || l >= q.num_cross_layers) continue;
+      const bool low = q.kind == DMT_TM_CROSS_LOWRANK_LINEAR;
+      if ((q.kind != DMT_TM_CROSS_LINEAR && !low) || l >= q.num_cross_layers) continue;
       const int wt = p->tower_width[t];
       const void* x0 = x_all + (size_t)B * p->width_prefix[t] * eb;
+      const void* xl = l == 0 ? x0 : (const void*)x_layer(t, l - 1);
       TmGroup g{};
       g.A0 = nullptr; g.lda0 = 0; g.K0 = 0;
-      g.A1 = l == 0 ? x0 : (const void*)x_layer(t, l - 1);
-      g.lda1 = wt; g.K1 = wt;
+      g.A1 = xl; g.lda1 = wt; g.K1 = wt;
       g.W = q.w_cross[l]; g.ldw = wt; g.bias = q.b_cross[l];
+      if (low) {
+        const int r = q.feat_out;
+        TmGroup h{};
+        h.A1 = xl; h.lda1 = wt; h.K1 = wt;
+        h.W = q.w_cross[2 * l]; h.ldw = wt; h.bias = nullptr;
+        h.C = wsp + ws[t].t_off; h.ldc = r;
+        h.M = (int32_t)B; h.N = r; h.epi = EPI_BIAS;
+        groups_t.push_back(h);
+        g.A1 = wsp + ws[t].t_off; g.lda1 = r; g.K1 = r;
+        g.W = q.w_cross[2 * l + 1]; g.ldw = r;
+        g.XL = xl; g.ldxl = wt;
+      }
       g.X0 = x0; g.ldx = wt;
       g.C = x_layer(t, l); g.ldc = wt;
       if (keptp) g.U = keptp + kept[t].u[l];
       g.M = (int32_t)B; g.N = wt; g.epi = EPI_CROSS;
       groups.push_back(g);
     }
+    launch_groups<DT>(p, groups_t, s);
     launch_groups<DT>(p, groups, s);
   }
 
@@ -175,7 +204,7 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
     if (q.kind == DMT_TM_DOT_LINEAR) {
       g.A0 = wsp + ws[t].z_off; g.lda0 = ws[t].np_pad; g.K0 = ws[t].np_pad;
       g.W = wsp + ws[t].wp_off; g.ldw = ws[t].np_pad + wt;
-    } else if (q.kind == DMT_TM_CROSS_LINEAR) {
+    } else if (q.kind == DMT_TM_CROSS_LINEAR || q.kind == DMT_TM_CROSS_LOWRANK_LINEAR) {
       g.A1 = x_layer(t, q.num_cross_layers - 1);
     }
     g.bias = q.b_proj;

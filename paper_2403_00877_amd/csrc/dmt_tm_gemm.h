@@ -51,7 +51,15 @@ struct TmGroup {
   // EPI_CROSS only: when set, u = acc + bias (before the cross product) is also stored here,
   // laid out like C (what the backward needs of a cross layer).
   void* U;
+  // EPI_CROSS: the x_l term, [M][ldxl]; NULL when it is the operand A1 itself (a full-rank
+  // layer).  A low-rank layer contracts t = V x_l instead, and adds x_l from here.
+  const void* XL;
+  int32_t ldxl;
 };
+
+// bias may be NULL (no bias)
+__device__ __forceinline__ const void* tm_xl(const TmGroup& g) { return g.XL ? g.XL : g.A1; }
+__device__ __forceinline__ int tm_ldxl(const TmGroup& g) { return g.XL ? g.ldxl : g.lda1; }
 
 __device__ __forceinline__ int64_t tm_crow(const TmGroup& g, int m) {
   return g.rdiv > 0 ? (int64_t)(m / g.rdiv) * g.ldc + (int64_t)(m % g.rdiv) * g.ldc2
@@ -185,7 +193,7 @@ __global__ __launch_bounds__(kBlock, 2) void tm_gemm_mfma(const TmLaunch L) {
   for (int j = 0; j < 2; ++j) {
     const int n = n0 + wn * 64 + j * 32 + (lane & 31);
     if (n >= N) continue;
-    const float bias = epi >= EPI_F32 ? 0.f : load_elt<DT>(G.bias, n);
+    const float bias = (epi >= EPI_F32 || !G.bias) ? 0.f : load_elt<DT>(G.bias, n);
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
 #pragma unroll
@@ -203,7 +211,8 @@ __global__ __launch_bounds__(kBlock, 2) void tm_gemm_mfma(const TmLaunch L) {
           if constexpr (KEEPU) {
             if (G.U) store_elt<DT>(G.U, (int64_t)m * G.ldc + n, y);
           }
-          y = load_elt<DT>(G.X0, (int64_t)m * G.ldx + n) * y + load_elt<DT>(G.A1, (int64_t)m * lda1 + n);
+          y = load_elt<DT>(G.X0, (int64_t)m * G.ldx + n) * y +
+              load_elt<DT>(tm_xl(G), (int64_t)m * tm_ldxl(G) + n);
         }
         store_elt<DT>(G.C, tm_crow(G, m) + n, y);
       }
@@ -395,20 +404,23 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
       G.ldc % 8 == 0 && n0 + LBN <= N &&
       (((uintptr_t)G.C | (uintptr_t)G.bias | (uintptr_t)G.U) & 15) == 0 &&
       (epi != EPI_CROSS ||
-       (G.ldx % 8 == 0 && lda % 8 == 0 && (((uintptr_t)G.X0 | (uintptr_t)G.A1) & 15) == 0));
+       (G.ldx % 8 == 0 && tm_ldxl(G) % 8 == 0 && (((uintptr_t)G.X0 | (uintptr_t)tm_xl(G)) & 15) == 0));
+  const uint16_t* __restrict__ XLp = (const uint16_t*)tm_xl(G);
+  const int ldxl = tm_ldxl(G);
   // The two epilogues that read global memory (cross: x0 and x_l; accumulate: C itself) request
   // all of a half's operands before the accumulators are parked: with one block per CU nothing
   // else hides that latency, and a thread's eight chunks one after another cost eight of them.
   constexpr int kChunks = 128 * (LBN / 8) / kBigThreads;
   // (byte offsets from the operand's base fit 32 bits: one register per address instead of two)
-  const bool fast_cross = epi == EPI_CROSS && vec_ok && (int64_t)M * G.ldx < (1LL << 31);
+  const bool fast_cross = epi == EPI_CROSS && vec_ok && (int64_t)M * G.ldx < (1LL << 31) &&
+                          (int64_t)M * ldxl < (1LL << 31);
   const bool fast_add = epi == EPI_F32_ADD && n0 + LBN <= N && G.ldc % 4 == 0 &&
                         (int64_t)M * G.ldc < (1LL << 30) &&
                         (((uintptr_t)((float*)G.C + slice * G.cstride)) & 15) == 0;
   const char* const pre_a = fast_cross ? (const char*)G.X0 : (const char*)((float*)G.C + slice * G.cstride);
-  const char* const pre_b = fast_cross ? (const char*)A : pre_a + 16;
+  const char* const pre_b = fast_cross ? (const char*)XLp : pre_a + 16;
   const uint32_t pre_lda = fast_cross ? (uint32_t)G.ldx * 2u : (uint32_t)G.ldc * 4u;   // row pitch, bytes
-  const uint32_t pre_ldb = fast_cross ? (uint32_t)lda * 2u : pre_lda;
+  const uint32_t pre_ldb = fast_cross ? (uint32_t)ldxl * 2u : pre_lda;
   const uint32_t pre_col = fast_cross ? 2u : 4u;                                        // bytes per column
 #pragma clang loop unroll(full)
   for (int h = 0; h < 2; ++h) {
@@ -454,9 +466,11 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
           *(float4*)(c0 + 4) = make_float4(y[4] + p1.x, y[5] + p1.y, y[6] + p1.z, y[7] + p1.w);
         } else {
           float bv[8], xv[8], lv[8];
-          dmt::decode_chunk<DT>(bv, *(const uint4*)((const uint16_t*)G.bias + n));
+          if (G.bias) {
+            dmt::decode_chunk<DT>(bv, *(const uint4*)((const uint16_t*)G.bias + n));
 #pragma clang loop unroll(full)
-          for (int q = 0; q < 8; ++q) y[q] += bv[q];
+            for (int q = 0; q < 8; ++q) y[q] += bv[q];
+          }
           if (G.U) dmt::store_chunk<DT, 8>(G.U, (int64_t)m * G.ldc + n, y);
           dmt::decode_chunk<DT>(xv, pa[u]);
           dmt::decode_chunk<DT>(lv, pb[u]);
@@ -495,9 +509,11 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
       }
       if (vec_ok) {
         float bv[8], xv[8], lv[8];
-        dmt::decode_chunk<DT>(bv, *(const uint4*)((const uint16_t*)G.bias + n));
+        if (G.bias) {
+          dmt::decode_chunk<DT>(bv, *(const uint4*)((const uint16_t*)G.bias + n));
 #pragma clang loop unroll(full)
-        for (int q = 0; q < 8; ++q) y[q] += bv[q];
+          for (int q = 0; q < 8; ++q) y[q] += bv[q];
+        }
         if (epi == EPI_BIAS_RELU) {
 #pragma clang loop unroll(full)
           for (int q = 0; q < 8; ++q) y[q] = y[q] > 0.f ? y[q] : 0.f;
@@ -505,19 +521,19 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
         if (epi == EPI_CROSS) {
           if (G.U) dmt::store_chunk<DT, 8>(G.U, (int64_t)m * G.ldc + n, y);
           dmt::decode_chunk<DT>(xv, *(const uint4*)((const uint16_t*)G.X0 + (int64_t)m * G.ldx + n));
-          dmt::decode_chunk<DT>(lv, *(const uint4*)(A + (int64_t)m * lda + n));
+          dmt::decode_chunk<DT>(lv, *(const uint4*)(XLp + (int64_t)m * ldxl + n));
 #pragma clang loop unroll(full)
           for (int q = 0; q < 8; ++q) y[q] = xv[q] * y[q] + lv[q];
         }
         dmt::store_chunk<DT, 8>(G.C, (int64_t)m * G.ldc + n, y);
       } else {
         for (int q = 0; q < 8 && n + q < N; ++q) {
-          float z = y[q] + load_elt<DT>(G.bias, n + q);
+          float z = y[q] + (G.bias ? load_elt<DT>(G.bias, n + q) : 0.f);
           if (epi == EPI_BIAS_RELU) z = z > 0.f ? z : 0.f;
           if (epi == EPI_CROSS) {
             if (G.U) store_elt<DT>(G.U, (int64_t)m * G.ldc + n + q, z);
             z = load_elt<DT>(G.X0, (int64_t)m * G.ldx + n + q) * z +
-                load_elt<DT>(G.A1, (int64_t)m * lda + n + q);
+                load_elt<DT>(XLp, (int64_t)m * ldxl + n + q);
           }
           store_elt<DT>(G.C, (int64_t)m * G.ldc + n + q, z);
         }
@@ -548,11 +564,12 @@ __global__ __launch_bounds__(kBlock) void tm_gemm_simple(const TmLaunch L) {
     *c = G.epi == EPI_F32_ADD ? *c + s : s;
     return;
   }
-  float y = s + load_elt<DT>(G.bias, n);
+  float y = s + (G.bias ? load_elt<DT>(G.bias, n) : 0.f);
   if (G.epi == EPI_BIAS_RELU) y = y > 0.f ? y : 0.f;
   if (G.epi == EPI_CROSS) {
     if (G.U) store_elt<DT>(G.U, (int64_t)m * G.ldc + n, y);
-    y = load_elt<DT>(G.X0, (int64_t)m * G.ldx + n) * y + load_elt<DT>(G.A1, (int64_t)m * G.lda1 + n);
+    y = load_elt<DT>(G.X0, (int64_t)m * G.ldx + n) * y +
+        load_elt<DT>(tm_xl(G), (int64_t)m * tm_ldxl(G) + n);
   }
   store_elt<DT>(G.C, tm_crow(G, m) + n, y);
 }
@@ -661,8 +678,8 @@ __global__ __launch_bounds__(kBlock) void tm_pack_w(const TmAuxLaunch L) {
   }
 }
 
-// What a training forward keeps for the backward: for every cross layer l of a cross tower,
-// x_{l+1} and u_l = W_l x_l + b_l, each [B][W_t] in the compute type.  Offsets in bytes from a
+// What a training forward keeps for the backward: for every cross layer l of a cross tower
+// (full-rank or low-rank), x_{l+1} and u_l = W_l x_l + b_l, each [B][W_t] in the compute type.  Offsets in bytes from a
 // 256-byte-aligned base; towers of other kinds keep nothing (their backward recomputes).
 struct TmKept {
   size_t x[DMT_MAX_CROSS_LAYERS] = {}, u[DMT_MAX_CROSS_LAYERS] = {};
@@ -673,7 +690,7 @@ inline size_t plan_tm_kept(const dmt_plan* p, const dmt_tm_params* tp, int64_t B
   size_t off = 0;
   kept->assign(p->T, TmKept());
   for (int32_t t = 0; t < p->T; ++t) {
-    if (tp[t].kind != DMT_TM_CROSS_LINEAR) continue;
+    if (tp[t].kind != DMT_TM_CROSS_LINEAR && tp[t].kind != DMT_TM_CROSS_LOWRANK_LINEAR) continue;
     const size_t bytes = dmt_align_up((size_t)B * p->tower_width[t] * eb, 256);
     for (int l = 0; l < tp[t].num_cross_layers && l < DMT_MAX_CROSS_LAYERS; ++l) {
       (*kept)[t].x[l] = off; off += bytes;

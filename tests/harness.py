@@ -194,6 +194,9 @@ def oracle_tm(w, dec, x_towers, towers=None):
             elif w.tm_kind == wl.TM_DOT_LINEAR:
                 y = oracle.tm_dot_linear(x, len(w.tower_tables()[t if towers is None else towers[t]]),
                                          d["w_proj"], d["b_proj"])
+            elif w.tm_kind == wl.TM_CROSS_LOWRANK_LINEAR:
+                y = oracle.tm_cross_lowrank_linear(x, d["w_cross"][0::2], d["w_cross"][1::2], d["b_cross"],
+                                                   d["w_proj"], d["b_proj"])
             elif w.tm_kind == wl.TM_DLRM:
                 y = oracle.tm_dlrm(x, len(w.tower_tables()[t if towers is None else towers[t]]),
                                    d["w_proj"], d["b_proj"], d["w_cross"][0], d["b_cross"][0])

@@ -128,3 +128,18 @@ def test_dlrm_module_odd_widths():
     w.tm_feat_out = 5
     w.tm_out = [20 + 3 * 5] * 2
     check_tm(w)
+
+
+@pytest.mark.parametrize("dt,rank", [("bf16", 64), ("bf16", 256), ("f16", 32), ("f32", 5)])
+def test_lowrank_cross_module(dt, rank):
+    """Two low-rank DCN-v2 cross layers on 512-wide towers (rank 256 takes the 256 x 256 GEMM for
+    the second contraction, the smaller ranks the 128 x 128 one), then 512 -> 96; batch 150."""
+    w = wl.scaled(wl.large(), max_rows=300, batch=150, num_tables=8)
+    w.table_to_tower = [0, 0, 0, 0, 1, 1, 1, 1]
+    w.tm_out = [96, 96]
+    w.tm_kind = wl.TM_CROSS_LOWRANK_LINEAR
+    w.tm_cross_layers = 2
+    w.tm_feat_out = rank
+    w.tm_dtype = dt
+    w.pooled_dtype = dt
+    check_tm(w, chained=dt == "bf16" and rank == 64)

@@ -34,6 +34,12 @@ def run_bwd(dw, tm, x_dev, y_dev, dy_dev, kept=None):
             grads.append(dict(dw_proj=f(o_proj, kin), db_proj=f(o_proj),
                               dw_cross=[f(w.tm_feat_out, widths[t] // nf)], db_cross=[f(w.tm_feat_out)]))
             continue
+        if w.tm_kind == wl.TM_CROSS_LOWRANK_LINEAR:
+            r, d = w.tm_feat_out, widths[t]
+            grads.append(dict(dw_proj=f(w.tm_out[t], kin), db_proj=f(w.tm_out[t]),
+                              dw_cross=[f(*shape) for _ in range(w.tm_cross_layers) for shape in ((r, d), (d, r))],
+                              db_cross=[f(d) for _ in range(w.tm_cross_layers)]))
+            continue
         grads.append(dict(dw_proj=f(w.tm_out[t], kin), db_proj=f(w.tm_out[t]),
                           dw_cross=[f(widths[t], widths[t]) for _ in range(L)],
                           db_cross=[f(widths[t]) for _ in range(L)]))
@@ -97,6 +103,13 @@ def check_tm_bwd(w, rtol=None, keep=False):
                                               relu=w.tm_kind == wl.TM_LINEAR_RELU)
         elif w.tm_kind == wl.TM_DOT_LINEAR:
             dx, dW, db = tm_bwd.tm_dot_linear_bwd(x64[t], len(tables[t]), d["w_proj"], d["b_proj"], dys[t])
+        elif w.tm_kind == wl.TM_CROSS_LOWRANK_LINEAR:
+            dx, dVc, dUc, dbc, dW, db = tm_bwd.tm_cross_lowrank_linear_bwd(
+                x64[t], d["w_cross"][0::2], d["w_cross"][1::2], d["b_cross"], d["w_proj"], d["b_proj"], dys[t])
+            for l in range(len(dVc)):
+                assert_grad_close(got[t]["dw_cross"][2 * l], dVc[l], rtol, what + "dV[%d]" % l)
+                assert_grad_close(got[t]["dw_cross"][2 * l + 1], dUc[l], rtol, what + "dU[%d]" % l)
+                assert_grad_close(got[t]["db_cross"][l], dbc[l], rtol, what + "db_cross[%d]" % l)
         elif w.tm_kind == wl.TM_DLRM:
             dx, dW, db, dWf, dbf = tm_bwd.tm_dlrm_bwd(x64[t], len(tables[t]), d["w_proj"], d["b_proj"],
                                                       d["w_cross"][0], d["b_cross"][0], dys[t])
@@ -247,6 +260,22 @@ def test_compression_ratios_of_the_cross_module(D):
     ref = tm.oracle([wl.decode(enc, tm.dtype)])[0]
     assert_close(y, wl.decode(oracle.round_to(ref, tm.dtype), tm.dtype), RTOL[tm.dtype], "cross module, D = %d" % D)
     check_tm_bwd(w, rtol=4e-2, keep=True)
+
+
+@pytest.mark.parametrize("keep", [False, True])
+@pytest.mark.parametrize("dt,rank", [("bf16", 64), ("bf16", 256), ("f16", 32), ("f32", 5)])
+def test_lowrank_cross_module(dt, rank, keep):
+    """Two low-rank DCN-v2 cross layers on 512-wide towers, then 512 -> 96; batch 150; with the
+    backward recomputing u_l and x_l, and on what the training forward kept."""
+    w = wl.scaled(wl.large(), max_rows=300, batch=150, num_tables=8)
+    w.table_to_tower = [0, 0, 0, 0, 1, 1, 1, 1]
+    w.tm_out = [96, 96]
+    w.tm_kind = wl.TM_CROSS_LOWRANK_LINEAR
+    w.tm_cross_layers = 2
+    w.tm_feat_out = rank
+    w.tm_dtype = dt
+    w.pooled_dtype = dt
+    check_tm_bwd(w, rtol=1e-4 if dt == "f32" else 4e-2, keep=keep)
 
 
 def test_rejects_bad_arguments():

@@ -26,8 +26,8 @@ _S_ROWS, _S_DIMS, _S_LEN, _S_RANK, _S_PERM, _S_TABLE, _S_GRAD, _S_TM, _S_GRAD_TM
 F32, F16, BF16 = "f32", "f16", "bf16"
 ELT_BYTES = {F32: 4, F16: 2, BF16: 2}
 
-TM_LINEAR, TM_LINEAR_RELU, TM_DOT_LINEAR, TM_CROSS_LINEAR, TM_DLRM = (
-    "linear", "linear_relu", "dot_linear", "cross_linear", "dlrm")
+TM_LINEAR, TM_LINEAR_RELU, TM_DOT_LINEAR, TM_CROSS_LINEAR, TM_DLRM, TM_CROSS_LOWRANK_LINEAR = (
+    "linear", "linear_relu", "dot_linear", "cross_linear", "dlrm", "cross_lowrank_linear")
 
 
 @dataclasses.dataclass
@@ -54,7 +54,8 @@ class Workload:
     eps: float = 1e-8
     table_std: float = 0.01
     tm_feat_out: int = 0            # TM_DLRM: outputs of the shared per-feature layer (c D);
-                                    # tm_out[t] = p D + (tables of tower t) * tm_feat_out
+                                    # tm_out[t] = p D + (tables of tower t) * tm_feat_out.
+                                    # TM_CROSS_LOWRANK_LINEAR: the rank r of its cross layers
 
     @property
     def num_tables(self) -> int:
@@ -166,8 +167,19 @@ def mid_dlrm() -> Workload:
     return w
 
 
+def large_lowrank() -> Workload:
+    """Large's tables and lookups under the DCN Tower Module with low-rank cross layers of rank
+    512 (a quarter of the tower width)."""
+    w = large()
+    w.name = "large_lowrank"
+    w.tm_kind = TM_CROSS_LOWRANK_LINEAR
+    w.tm_feat_out = 512
+    return w
+
+
 def by_name(name: str) -> Workload:
     return {"tiny": tiny, "mid": mid, "large": large, "mid_dlrm": mid_dlrm,
+            "large_lowrank": large_lowrank,
             "backward": lambda: mid(True), "imbalanced": imbalanced}[name]()
 
 
@@ -371,6 +383,14 @@ def tm_weights(w: Workload):
         for _ in range(w.tm_cross_layers if w.tm_kind == TM_CROSS_LINEAR else 0):
             s = 1.0 / math.sqrt(d)
             wc.append(rng.uniform(-s, s, size=(d, d)).astype(np.float32))
+            bc.append(rng.uniform(-s, s, size=d).astype(np.float32))
+        for _ in range(w.tm_cross_layers if w.tm_kind == TM_CROSS_LOWRANK_LINEAR else 0):
+            # w_cross = [V_0 [r, d], U_0 [d, r], V_1, U_1, ...]; the product U V is scaled like a
+            # full-rank layer's matrix
+            r = w.tm_feat_out
+            s = 1.0 / math.sqrt(d)
+            wc.append(rng.uniform(-s, s, size=(r, d)).astype(np.float32) * math.sqrt(3.0))
+            wc.append(rng.uniform(-1, 1, size=(d, r)).astype(np.float32) / math.sqrt(r))
             bc.append(rng.uniform(-s, s, size=d).astype(np.float32))
         o_proj = w.tm_out[t]
         if w.tm_kind == TM_DLRM:
