@@ -349,26 +349,6 @@ __global__ __launch_bounds__(kBlock) void tmb_sum_slices(const TmbLaunch L) {
   ((float*)G.o0)[e] = s;
 }
 
-// Cross layer forward, elementwise part: xn = x0 * u + xl (rounded once to DT).
-// a = x0, b = u, c = xl, o0 = xn.
-template <int DT>
-__global__ __launch_bounds__(kBlock) void tmb_cross_next(const TmbLaunch L) {
-  constexpr int V = Ew<DT>::V;
-  const int gi = tmb_find(L);
-  const TmbItem& G = L.it[gi];
-  const int64_t stride = (int64_t)G.nbx * kBlock * V;
-  for (int64_t e = ((int64_t)(blockIdx.x - L.block_start[gi]) * kBlock + threadIdx.x) * V; e < G.n0;
-       e += stride) {
-    float x0[V], u[V], xl[V];
-    ew_load<DT>(G.a, e, x0);
-    ew_load<DT>(G.b, e, u);
-    ew_load<DT>(G.c, e, xl);
-#pragma unroll
-    for (int q = 0; q < V; ++q) xl[q] = x0[q] * u[q] + xl[q];
-    ew_store<DT>(G.o0, e, xl);
-  }
-}
-
 // Cross layer backward, elementwise part: du = dxn * x0 (rounded to DT);
 // dx0 = (first ? 0 : dx0) + dxn * u (+ dxn when `last`: the layer's data-gradient contraction
 // then accumulates du W_l on top, which completes dx_0 + dx0 in place).
@@ -717,9 +697,9 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
   launch_aux<DT>(p, B, dots_simple, nb_simple, 1, s);
   launch_aux<DT>(p, B, packs, nb_pack, 2, s);
 
-  // ---- ... and the cross layers' u_l = x_l W_l^T + b_l, x_{l+1} = x0 * u_l + x_l (low-rank
-  // layers: t_l = x_l V_l^T, which the backward needs whether or not the rest was kept, then
-  // u_l = t_l U_l^T + b_l)
+  // ---- ... and the cross layers' u_l = x_l W_l^T + b_l, x_{l+1} = x0 * u_l + x_l, both from one
+  // contraction as in the training forward (low-rank layers: t_l = x_l V_l^T first, which the
+  // backward needs whether or not the rest was kept, then u_l = t_l U_l^T + b_l)
   std::vector<TmGroup> groups, groups_t;
   for (int l = 0; l < max_layers; ++l) {
     for (int32_t t = 0; t < p->T; ++t) {
@@ -739,20 +719,18 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
         groups_t.push_back(h);
         g.A1 = wsp + ws[t].tl[l]; g.lda1 = r; g.K1 = r;
         g.W = q.w_cross[2 * l + 1]; g.ldw = r;
+        g.XL = xl_of(t, l); g.ldxl = wt;
       }
       if (keptp) continue;
-      g.C = wsp + ws[t].u[l]; g.ldc = wt;
-      g.M = (int32_t)B; g.N = wt; g.epi = EPI_BIAS;
+      // exactly the training forward's contraction: x_{l+1} from the cross epilogue, u_l on the side
+      g.X0 = x_of(t); g.ldx = wt;
+      g.C = wsp + ws[t].xl[l]; g.ldc = wt;
+      g.U = wsp + ws[t].u[l];
+      g.M = (int32_t)B; g.N = wt; g.epi = EPI_CROSS;
       groups.push_back(g);
-      TmbItem it{};
-      it.a = x_of(t); it.b = wsp + ws[t].u[l]; it.c = xl_of(t, l); it.o0 = wsp + ws[t].xl[l];
-      it.n0 = B * wt;
-      it.nbx = (int32_t)ew_blocks(it.n0, V);
-      batch.add(it, it.nbx);
     }
     launch_groups<DT>(p, groups_t, s, false, DMT_K_TM_BWD_GEMM);
     launch_groups<DT>(p, groups, s, false, DMT_K_TM_BWD_GEMM);
-    ok &= launch_items(p, batch, tmb_cross_next<DT>, s);
   }
 
   // ---- projection: operands, bias gradient, then both contractions for all towers
