@@ -162,7 +162,8 @@ dmt_status dmt_tower_lookup_fwd(const dmt_plan* plan, const int32_t* indices,
 typedef struct {
   int32_t kind;              /* dmt_tm_kind */
   int32_t out_dim;           /* O_t */
-  int32_t num_cross_layers;  /* CROSS_LINEAR only, <= DMT_MAX_CROSS_LAYERS */
+  int32_t num_cross_layers;  /* CROSS_LINEAR (<= DMT_MAX_CROSS_LAYERS) and
+                                CROSS_LOWRANK_LINEAR (half as many) only */
   int32_t feat_out;          /* DLRM: outputs of the per-feature layer (c D);
                                 CROSS_LOWRANK_LINEAR: the rank r */
   const void* w_proj;
@@ -191,15 +192,12 @@ dmt_status dmt_tower_module_fwd(const dmt_plan* plan, const dmt_tm_params* per_t
                                 const void* pooled, int64_t B, void* tm_out, dmt_dtype dtype,
                                 void* workspace, size_t workspace_bytes, void* stream);
 
-/* Optional outputs of the backward's integer stages, for parity checks.  Any
- * pointer may be NULL.  All dev.  A lookup whose id is outside its table sorts
- * behind its table's valid lookups, shows as key -1 in sorted_keys, starts no run
- * (it lies inside the extent of the run before it) and is not counted. */
 /*
  * Training forward: dmt_tower_module_fwd that also keeps, in `kept`, what the
  * backward would otherwise recompute: x_{l+1} and u_l = W_l x_l + b_l of every
- * cross layer, full-rank or low-rank (paper Listing 2), each [B][W_t] in `dtype`.  tm_out is bit for
- * bit that of dmt_tower_module_fwd.  Towers of the other kinds keep nothing
+ * cross layer, full-rank or low-rank (paper Listing 2), each [B][W_t] in
+ * `dtype`.  tm_out is bit for bit that of dmt_tower_module_fwd.  Towers of the
+ * other kinds keep nothing
  * (their backward recomputes the dot terms, which is cheaper than storing them).
  *   kept  dev, at least dmt_tm_kept_bytes(plan, per_tower, B, dtype), 256-byte
  *         aligned, caller-owned; pass the same buffer, unchanged, to
@@ -218,8 +216,8 @@ dmt_status dmt_tower_module_fwd_keep(const dmt_plan* plan, const dmt_tm_params* 
  * length of w_proj; dw_cross[l] [W_t][W_t]; the db_* vectors; for a DLRM tower
  * dw_proj has the flat layer's out_dim - nf * feat_out rows and dw_cross[0] /
  * db_cross[0] receive the shared per-feature layer's [feat_out][n] / [feat_out];
- * for a low-rank cross tower dw_cross[2 l] / dw_cross[2 l + 1] are dV_l / dU_l).  Every array is
- * overwritten, not accumulated into.  Caller-owned.
+ * for a low-rank cross tower dw_cross[2 l] / dw_cross[2 l + 1] are dV_l / dU_l).
+ * Every array is overwritten, not accumulated into.  Caller-owned.
  */
 typedef struct {
   float* dw_proj;
@@ -274,6 +272,10 @@ dmt_status dmt_tower_module_bwd(const dmt_plan* plan, const dmt_tm_params* per_t
                                 const dmt_tm_grads* grads, const void* kept, size_t kept_bytes,
                                 void* workspace, size_t workspace_bytes, void* stream);
 
+/* Optional outputs of the backward's integer stages, for parity checks.  Any
+ * pointer may be NULL.  All dev.  A lookup whose id is outside its table sorts
+ * behind its table's valid lookups, shows as key -1 in sorted_keys, starts no run
+ * (it lies inside the extent of the run before it) and is not counted. */
 typedef struct {
   int64_t* sorted_keys;  /* [nnz]  (table << 32 | row), ascending, stable           */
   int32_t* sorted_bag;   /* [nnz]  bag id f*B + b of each sorted lookup              */
