@@ -12,6 +12,10 @@
  *                                Sec. 2.2): stable sort by row id, segment
  *                                reduce, one deterministic rowwise-Adagrad
  *                                write per row
+ * and, between the last two in a training step,
+ *   dmt_tower_module_fwd_keep    the same forward, keeping what its backward needs
+ *   dmt_tower_module_bwd         the Tower Module's backward, whose dL/d(pooled)
+ *                                is what dmt_tower_lookup_bwd_update consumes
  *
  * Conventions
  *  - C linkage, no exceptions cross the boundary; every call returns dmt_status.
@@ -19,7 +23,7 @@
  *    tensors); "host" pointers are ordinary host memory, read during the call
  *    only.  The library owns nothing but the plan object and the small device
  *    tables dmt_plan_bind creates.
- *  - The three dmt_tower_* calls validate on the host first (null pointers,
+ *  - The dmt_tower_* calls validate on the host first (null pointers,
  *    sizes against the plan, supported dtypes / widths) and return
  *    DMT_EINVAL / DMT_ENOTSUP without launching anything; then they enqueue
  *    kernels on `stream` (a hipStream_t, NULL = default stream) and return
