@@ -278,6 +278,55 @@ def test_lowrank_cross_module(dt, rank, keep):
     check_tm_bwd(w, rtol=1e-4 if dt == "f32" else 4e-2, keep=keep)
 
 
+def _random_tower_config(seed):
+    """A seeded, arbitrary small configuration: two towers of 1-5 features each, any module
+    kind, ragged batch and output widths, every dtype (table dims a multiple of 8 so that the
+    16-bit types accept them)."""
+    rng = np.random.default_rng(1000 + seed)
+    kinds = [wl.TM_LINEAR, wl.TM_LINEAR_RELU, wl.TM_DOT_LINEAR, wl.TM_CROSS_LINEAR, wl.TM_DLRM,
+             wl.TM_CROSS_LOWRANK_LINEAR]
+    kind = kinds[seed % len(kinds)]
+    dt = ["bf16", "f16", "f32"][(seed // len(kinds)) % 3]
+    nfs = [int(rng.integers(1, 6)), int(rng.integers(1, 6))]
+    dims = [int(rng.choice([8, 16, 32, 64, 128])), int(rng.choice([8, 16, 32, 64, 128]))]
+    w = wl.scaled(wl.mid(), max_rows=200, batch=int(rng.integers(1, 700)), num_tables=sum(nfs))
+    w.table_to_tower = [0] * nfs[0] + [1] * nfs[1]
+    w.dims = [dims[0]] * nfs[0] + [dims[1]] * nfs[1]
+    w.tm_kind = kind
+    w.tm_dtype = w.pooled_dtype = dt
+    w.tm_cross_layers = int(rng.integers(1, 3)) if kind in (wl.TM_CROSS_LINEAR, wl.TM_CROSS_LOWRANK_LINEAR) else 0
+    w.tm_out = [int(rng.integers(1, 300)), int(rng.integers(1, 300))]
+    if kind == wl.TM_DLRM:
+        w.tm_feat_out = int(rng.integers(1, 40))
+        w.tm_out = [int(rng.integers(1, 200)) + nf * w.tm_feat_out for nf in nfs]
+    if kind == wl.TM_CROSS_LOWRANK_LINEAR:
+        w.tm_feat_out = int(rng.integers(1, 12)) * 8 if dt != "f32" else int(rng.integers(1, 70))
+    return w
+
+
+@pytest.mark.parametrize("seed", range(36))
+def test_random_small_configurations(seed):
+    """Forward (plain and training variant, bit-identical) and backward of arbitrary small towers
+    against the oracle: odd widths, one-sample batches, single-feature towers, every kind and
+    dtype; what the hand-picked cases above do not happen to hit."""
+    w = _random_tower_config(seed)
+    dw = DeviceWorkload(w)
+    tm = TowerModules(dw)
+    idx, off = wl.lookup_batch(w)
+    pooled = oracle.lookup_towered(dw.host_tables, w.table_dtype, w.dims, w.table_to_tower, idx, off, w.batch)
+    enc = [oracle.round_to(p, tm.dtype) for p in pooled]
+    x_dev = torch.cat([to_device(e, tm.dtype).reshape(-1) for e in enc])
+    got = to_f64(tm.run(x_dev))
+    ref = tm.oracle([wl.decode(e, tm.dtype) for e in enc])
+    deep = w.tm_cross_layers > 0
+    ftol = (1e-4 if deep else 1e-5) if tm.dtype == "f32" else (4e-2 if deep else 2e-2)
+    for t, (g, r) in enumerate(zip(dw.split_towers(got, tm.out_widths), ref)):
+        if tm.dtype != "f32":
+            r = wl.decode(oracle.round_to(r, tm.dtype), tm.dtype)
+        assert_close(g, r, ftol, "seed %d %s forward tower %d" % (seed, w.tm_kind, t))
+    check_tm_bwd(w, rtol=ftol, keep=True)
+
+
 def test_rejects_bad_arguments():
     w = wl.tiny()
     dw = DeviceWorkload(w)
