@@ -38,6 +38,7 @@ struct TmbItem {
   const void* c;
   void* o0;
   void* o1;
+  void* o2;
   int64_t n0, n1, n2;
   int32_t i0, i1, i2, i3, i4;
   int32_t nbx;               // blocks along the first dimension (2-D kernels) or blocks of the item
@@ -380,6 +381,66 @@ __global__ __launch_bounds__(kBlock) void tmb_cross_prep(const TmbLaunch L) {
     }
     ew_store<DT>(G.o0, e, x0);
     ew_store_f32<V>((float*)G.o1, e, acc);
+  }
+}
+
+// The same for the 16-bit types, writing du^T as well (the weight gradient's operand), so that du
+// is not read back by a transpose: 64 x 64 tiles of the [B][W] tensors, 16-byte reads of dxn and
+// dx0, 8-byte accesses of the 16-bit tensors.  W is a multiple of 8.
+// a = dxn, b = x0, c = u, o0 = du, o1 = dx0, o2 = du^T [W][Bp], n0 = B, n1 = Bp, i0 = first,
+// i1 = last, i2 = W; nbx = tiles along the batch.
+template <int DT>
+__global__ __launch_bounds__(kBlock) void tmb_cross_prep_t(const TmbLaunch L) {
+  __shared__ __attribute__((aligned(8))) uint16_t tile[kVTile][kVTile + 4];
+  const int gi = tmb_find(L);
+  const TmbItem& G = L.it[gi];
+  const int lb = blockIdx.x - L.block_start[gi];
+  const float* __restrict__ dxn = (const float*)G.a;
+  const uint16_t* __restrict__ x0 = (const uint16_t*)G.b;
+  const uint16_t* __restrict__ u = (const uint16_t*)G.c;
+  uint16_t* __restrict__ du = (uint16_t*)G.o0;
+  float* __restrict__ dx0 = (float*)G.o1;
+  uint16_t* __restrict__ duT = (uint16_t*)G.o2;
+  const int64_t B = G.n0, Bp = G.n1;
+  const int W = G.i2, first = G.i0;
+  const float keep = G.i1 ? 1.f : 0.f;
+  const int64_t b0 = (int64_t)(lb % G.nbx) * kVTile;
+  const int c0 = (lb / G.nbx) * kVTile;
+  const int q = threadIdx.x >> 4, v = (threadIdx.x & 15) * 4;
+#pragma unroll
+  for (int pass = 0; pass < 4; ++pass) {
+    const int i = pass * 16 + q;
+    const int64_t b = b0 + i;
+    const int c = c0 + v;
+    uint2 packed = make_uint2(0, 0);
+    if (b < B && c < W) {
+      const int64_t at = b * W + c;
+      const float4 g = *(const float4*)(dxn + at);
+      const uint2 xr = *(const uint2*)(x0 + at), ur = *(const uint2*)(u + at);
+      float xa, xb, xc, xd, ua, ub, uc, ud;
+      dmt::unpack2<DT>(xr.x, xa, xb); dmt::unpack2<DT>(xr.y, xc, xd);
+      dmt::unpack2<DT>(ur.x, ua, ub); dmt::unpack2<DT>(ur.y, uc, ud);
+      float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (!first) acc = *(const float4*)(dx0 + at);
+      acc.x += g.x * ua + keep * g.x; acc.y += g.y * ub + keep * g.y;
+      acc.z += g.z * uc + keep * g.z; acc.w += g.w * ud + keep * g.w;
+      *(float4*)(dx0 + at) = acc;
+      packed = make_uint2(dmt::pack2<DT>(g.x * xa, g.y * xb), dmt::pack2<DT>(g.z * xc, g.w * xd));
+      *(uint2*)(du + at) = packed;
+    }
+    *(uint2*)&tile[i][v] = packed;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int pass = 0; pass < 4; ++pass) {
+    const int i = pass * 16 + q;                   // column of the tile
+    const int c = c0 + i;
+    const int64_t b = b0 + v;
+    if (c < W && b < Bp) {
+      const uint32_t lo = tile[v][i] | ((uint32_t)tile[v + 1][i] << 16);
+      const uint32_t hi = tile[v + 2][i] | ((uint32_t)tile[v + 3][i] << 16);
+      *(uint2*)(duT + (int64_t)c * Bp + b) = make_uint2(lo, hi);
+    }
   }
 }
 
@@ -873,7 +934,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
 
   // ---- cross towers: layers from the last to the first; dx0 accumulates in the output block,
   // where the first layer's data gradient then lands on top of it
-  TmbBatch sums, sums2, prep_dt, prep_dt16;
+  TmbBatch sums, sums2, prep_dt, prep_dt16, prep_t;
   for (int l = max_layers - 1; l >= 0; --l) {
     for (int32_t t = 0; t < p->T; ++t) {
       const dmt_tm_params& q = tp[t];
@@ -883,11 +944,18 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
       {
         TmbItem it{};
         it.a = wsp + w.dxn; it.b = x_of(t); it.c = u_of(t, l); it.o0 = wsp + w.du; it.o1 = dx_of(t);
-        it.n0 = B * wt; it.i0 = l == q.num_cross_layers - 1; it.i1 = l == 0;
-        it.nbx = (int32_t)ew_blocks(it.n0, V);
-        batch.add(it, it.nbx);
+        it.i0 = l == q.num_cross_layers - 1; it.i1 = l == 0;
+        if constexpr (DT == DMT_F32) {
+          it.n0 = B * wt;
+          it.nbx = (int32_t)ew_blocks(it.n0, V);
+          batch.add(it, it.nbx);
+          add_transpose<DT>(batch2, wsp + w.du, B, wt, wt, wsp + w.duT, Bp);
+        } else {                                     // du and du^T from one pass
+          it.o2 = wsp + w.duT; it.n0 = B; it.n1 = Bp; it.i2 = wt;
+          it.nbx = (int32_t)((Bp + kVTile - 1) / kVTile);
+          prep_t.add(it, (int64_t)it.nbx * ((wt + kVTile - 1) / kVTile));
+        }
       }
-      add_transpose<DT>(batch2, wsp + w.du, B, wt, wt, wsp + w.duT, Bp);
       add_transpose<DT>(batch2, xl_of(t, l), B, wt, wt, wsp + w.zT, Bp);
       {
         TmbItem it{};
@@ -972,6 +1040,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
       }
     }
     ok &= launch_items(p, batch, tmb_cross_prep<DT>, s);
+    if constexpr (DT != DMT_F32) ok &= launch_items(p, prep_t, tmb_cross_prep_t<DT>, s);
     ok &= launch_transposes<DT>(p, batch2, s);
     ok &= launch_items(p, batch3, tmb_rowsum<DT>, s);
     launch_groups<DT>(p, dgrad, s, false, DMT_K_TM_BWD_GEMM);
