@@ -1062,10 +1062,12 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
 extern "C" size_t dmt_tm_bwd_workspace_bytes(const dmt_plan* plan, const dmt_tm_params* per_tower,
                                              int64_t B) {
   if (!plan || !per_tower || B <= 0) return 0;
+  // enough for every dtype: the 16-bit layouts have smaller operands but may split K
   std::vector<TowerBwdWs> ws;
-  size_t bytes = 0;
-  if (plan_tm_bwd(plan, per_tower, B, 4, false, &ws, &bytes) != DMT_OK) return 0;
-  return bytes;
+  size_t b4 = 0, b2 = 0;
+  if (plan_tm_bwd(plan, per_tower, B, 4, false, &ws, &b4) != DMT_OK) return 0;
+  if (plan_tm_bwd(plan, per_tower, B, 2, false, &ws, &b2) != DMT_OK) b2 = 0;   // e.g. a rank no multiple of 8
+  return std::max(b4, b2);
 }
 
 extern "C" dmt_status dmt_tower_module_bwd(const dmt_plan* plan, const dmt_tm_params* per_tower,
