@@ -433,7 +433,27 @@ def time_whole_step(torch, dmt, wl, w, plan, tm_params, pooled, tm_out, tm_ws, b
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / n
     assert dmt.dmt_last_device_error(plan) == -1
-    return dict(ms_per_step=round(ms, 4), samples_per_s=round(B / (ms * 1e-3), 1), steps=n)
+    out = dict(ms_per_step=round(ms, 4), samples_per_s=round(B / (ms * 1e-3), 1), steps=n)
+    # the same steps as HIP graphs, one captured per id batch of the pool and replayed in turn
+    # (the calls only enqueue kernels, so they capture as they are)
+    side = torch.cuda.Stream()
+    graphs = []
+    for i in range(len(batches)):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            step(i)
+        graphs.append(g)
+    for i in range(3):
+        graphs[i % len(graphs)].replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(n):
+        graphs[(3 + i) % len(graphs)].replay()
+    torch.cuda.synchronize()
+    gms = (time.perf_counter() - t0) * 1e3 / n
+    assert dmt.dmt_last_device_error(plan) == -1
+    out["hip_graph_ms_per_step"] = round(gms, 4)
+    return out
 
 
 def cpu_leg(dmt, wl, w, plan, tables, states, tm_host, b0, pooled, tm_out, tm_params, tm_ws, bwd_ws,
