@@ -313,6 +313,64 @@ dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const int32_t* indi
                                        const dmt_bwd_debug* dbg);
 
 /*
+ * Tower Partitioner (paper Sec. 3.3): a balanced feature -> tower map learned from the
+ * embeddings a model produces.  Three calls, one per stage; the caller moves the small
+ * |F| x |F| matrix from the device to the host between the first and the second.
+ *
+ * Stage 1, on the device.  interaction[i][j] = | mean over the batch of the cosine between the
+ * pooled embeddings of features i and j | (the cosine kernel on normalised embeddings, the
+ * batch form mean(R R^T, dim = 0), then the absolute value).  A zero embedding has no
+ * direction and counts as cosine 0.
+ *   plan          any bound plan whose tables all have the same dim N, N % 8 == 0, N <= 512
+ *                 (else DMT_ENOTSUP); typically one tower holding every table
+ *   pooled        dev, the tower-major tensor dmt_tower_lookup_fwd wrote for this plan and B
+ *   interaction   dev out, float32 [F][F] in table order, exactly symmetric
+ *   workspace     dev, at least dmt_tp_workspace_bytes(plan, B), 16-byte aligned
+ * The normalised values enter the contraction as float16 and accumulate in float32: an
+ * entry differs from the exact value by at most 2^-10.
+ */
+size_t dmt_tp_workspace_bytes(const dmt_plan* plan, int64_t B);
+
+dmt_status dmt_tp_interaction(const dmt_plan* plan, const void* pooled, int64_t B,
+                              dmt_dtype pooled_dtype, float* interaction, void* workspace,
+                              size_t workspace_bytes, void* stream);
+
+typedef enum {
+  DMT_TP_DIVERSE = 0,   /* D = I: features that differ share a tower    */
+  DMT_TP_COHERENT = 1   /* D = 1 - I: features that agree share a tower */
+} dmt_tp_strategy;
+
+/*
+ * Stage 2, on the host, float64.  D = f(I) by `strategy`, then coordinates x_i in R^n that
+ * minimise  sum over i, over j < i, of (||x_i - x_j||_2 - D(i, j))^2  by `steps` iterations of
+ * Adam (beta1 0.9, beta2 0.999, epsilon 1e-8, bias-corrected) with step size lr from x0.
+ * Only the entries of `interaction` below the diagonal are read.
+ *   interaction   host, float32 [F][F]
+ *   x0, x         host, float64 [F][n]: start (the method's random draw, supplied by the
+ *                 caller) and result; may be the same buffer
+ *   stress        host out or NULL: the objective at x
+ */
+dmt_status dmt_tp_embed(const float* interaction, int32_t F, dmt_tp_strategy strategy, int32_t n,
+                        int32_t steps, double lr, const double* x0, double* x, double* stress);
+
+/*
+ * Stage 3, on the host, float64.  Constrained K-means (Bradley, Bennett and Demiriz 2000) of
+ * the F points x into T groups: the assignment step is the minimum-cost assignment under
+ * bounds on the group sizes, the update step moves every centre to its group's mean; it stops
+ * when an assignment repeats, or after max_iter assignment steps.  The bounds make the
+ * largest group at most `ratio` times the smallest: every group holds at least
+ * smin = min(ceil(F / (T - 1 + ratio)), floor(F / T)) and at most
+ * max(floor(ratio * smin), ceil(F / T)) points (ratio 1: sizes floor(F / T) and ceil(F / T)).
+ *   centres0        host, float64 [T][n], the start centres (supplied by the caller)
+ *   table_to_tower  host out, int32 [F]: group of each feature, usable as dmt_plan_create's map
+ *   centres         host out [T][n] or NULL;  iterations  host out or NULL
+ * DMT_EINVAL unless 1 <= T <= F, ratio >= 1, max_iter >= 1.
+ */
+dmt_status dmt_tp_kmeans(const double* x, int32_t F, int32_t n, int32_t T, double ratio,
+                         const double* centres0, int32_t max_iter, int32_t* table_to_tower,
+                         double* centres, int32_t* iterations);
+
+/*
  * Synchronise `stream` and report whether any kernel since the last call saw an
  * id outside its table: DMT_EBOUNDS with *bad_position = smallest offending
  * position in `indices`, else DMT_OK with *bad_position = -1.  Clears the record.
@@ -339,7 +397,9 @@ typedef enum {
   DMT_K_BWD_FIXUP = 10,        /* rows whose run spans reduce tiles           */
   DMT_K_TM_BWD_GEMM = 11,      /* Tower Module backward: grouped contractions */
   DMT_K_TM_BWD_AUX = 12,       /* ... its elementwise / transpose / sum steps */
-  DMT_K_COUNT = 13
+  DMT_K_TP_GRAM = 13,          /* Tower Partitioner: normalise + Gram tiles   */
+  DMT_K_TP_FINISH = 14,        /* ... slice sum, mean, absolute value         */
+  DMT_K_COUNT = 15
 } dmt_kernel_id;
 
 const char* dmt_kernel_name(int32_t kernel_id);

@@ -87,6 +87,12 @@ def _load() -> ctypes.CDLL:
     lib.dmt_profile_enable.argtypes = [vp, ctypes.c_uint32]
     lib.dmt_profile_read.argtypes = [vp, vp, vp, vp]
     lib.dmt_calibration_copy.argtypes = [vp, vp, sz, vp]
+    f64 = ctypes.c_double
+    lib.dmt_tp_workspace_bytes.argtypes = [vp, i64]
+    lib.dmt_tp_workspace_bytes.restype = sz
+    lib.dmt_tp_interaction.argtypes = [vp, vp, i64, ctypes.c_int, vp, vp, sz, vp]
+    lib.dmt_tp_embed.argtypes = [vp, i32, ctypes.c_int, i32, i32, f64, vp, vp, ctypes.POINTER(f64)]
+    lib.dmt_tp_kmeans.argtypes = [vp, i32, i32, i32, f64, vp, i32, vp, vp, ctypes.POINTER(i32)]
     return lib
 
 
@@ -98,9 +104,11 @@ EXPORTS = ["dmt_status_str", "dmt_plan_create", "dmt_plan_destroy", "dmt_plan_la
            "dmt_tm_kept_bytes", "dmt_tower_module_fwd_keep",
            "dmt_bwd_workspace_bytes", "dmt_tower_lookup_bwd_update",
            "dmt_last_device_error", "dmt_kernel_name", "dmt_profile_enable", "dmt_profile_read",
-           "dmt_calibration_copy"]
+           "dmt_calibration_copy", "dmt_tp_workspace_bytes", "dmt_tp_interaction",
+           "dmt_tp_embed", "dmt_tp_kmeans"]
 
-DMT_K_COUNT = 13
+DMT_K_COUNT = 15
+TP_STRATEGY_CODE = {"diverse": 0, "coherent": 1}
 
 
 def library_path() -> str:
@@ -311,3 +319,52 @@ def dmt_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> N
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() >= nbytes
     _check("dmt_calibration_copy", _lib.dmt_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)))
+
+
+def dmt_tp_workspace_bytes(plan: dmt_plan, B: int) -> int:
+    return int(_lib.dmt_tp_workspace_bytes(plan.handle, B))
+
+
+def dmt_tp_interaction(plan: dmt_plan, pooled: torch.Tensor, B: int, interaction: torch.Tensor,
+                       workspace: torch.Tensor, stream=None) -> None:
+    assert interaction.dtype == torch.float32
+    assert interaction.numel() >= plan.num_tables * plan.num_tables
+    _check("dmt_tp_interaction", _lib.dmt_tp_interaction(
+        plan.handle, _ptr(pooled), B, DTYPE_CODE[pooled.dtype], _ptr(interaction),
+        _ptr(workspace), _nbytes(workspace), _stream(stream)))
+
+
+def _host(a, dtype):
+    import numpy as np
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def dmt_tp_embed(interaction, strategy: str, n: int, steps: int, lr: float, x0):
+    """Host arrays in, (coordinates float64 [F][n], stress) out."""
+    import numpy as np
+    I = _host(interaction, np.float32)
+    x0 = _host(x0, np.float64)
+    F = I.shape[0]
+    assert I.shape == (F, F) and x0.shape == (F, n)
+    x = np.empty_like(x0)
+    stress = ctypes.c_double(0.0)
+    _check("dmt_tp_embed", _lib.dmt_tp_embed(
+        I.ctypes.data, F, TP_STRATEGY_CODE[strategy], n, steps, lr, x0.ctypes.data, x.ctypes.data,
+        ctypes.byref(stress)))
+    return x, float(stress.value)
+
+
+def dmt_tp_kmeans(x, T: int, ratio: float, centres0, max_iter: int = 100):
+    """Host arrays in, (table_to_tower int32 [F], centres float64 [T][n], iterations) out."""
+    import numpy as np
+    x = _host(x, np.float64)
+    c0 = _host(centres0, np.float64)
+    F, n = x.shape
+    assert c0.shape == (T, n)
+    labels = np.empty(F, dtype=np.int32)
+    centres = np.empty_like(c0)
+    it = ctypes.c_int32(0)
+    _check("dmt_tp_kmeans", _lib.dmt_tp_kmeans(
+        x.ctypes.data, F, n, T, ratio, c0.ctypes.data, max_iter, labels.ctypes.data,
+        centres.ctypes.data, ctypes.byref(it)))
+    return labels, centres, int(it.value)

@@ -193,7 +193,7 @@ extern "C" const char* dmt_kernel_name(int32_t id) {
   static const char* names[DMT_K_COUNT] = {
       "lookup_fwd", "tm_dots", "tm_pack_w", "tm_gemm", "bwd_build_keys", "radix_hist",
       "radix_scan", "radix_scatter", "bwd_heads", "bwd_reduce_update", "bwd_fixup_update",
-      "tm_bwd_gemm", "tm_bwd_aux"};
+      "tm_bwd_gemm", "tm_bwd_aux", "tp_gram", "tp_finish"};
   return (id >= 0 && id < DMT_K_COUNT) ? names[id] : "?";
 }
 

@@ -1,0 +1,182 @@
+"""GPU parity of the Tower Partitioner's device stage (dmt_tp_interaction) against the CPU
+oracle, and the three stages chained."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2403_00877_amd as dmt
+import workloads as wl
+from harness import DeviceWorkload, to_device
+from oracle import tp
+
+pytestmark = pytest.mark.gpu
+
+# The normalised values enter the contraction as float16 (unit roundoff u = 2^-11): a product of
+# two of them is off by at most (2u + u^2) |x y|, and sum |x_k y_k| <= 1 for unit vectors, so every
+# cosine, and with it every entry of the batch mean, is within 2^-10 of the exact value (the
+# float32 accumulation adds ~1e-7 per term).  The errors are independent across elements and
+# samples, so the typical error is far smaller: bounded here by 1e-4 rms.
+ATOL = 2.0 ** -10
+RMS = 1e-4
+
+
+def _workload(F, N, T, B, dtype, sizes=None):
+    """F tables of dim N on T towers (round-robin unless `sizes` gives the tower sizes)."""
+    if sizes is None:
+        t2t = [f % T for f in range(F)]
+    else:
+        t2t = [t for t, k in enumerate(sizes) for _ in range(k)]
+    return dataclasses.replace(wl.tiny(), name="tp", rows=[4] * F, dims=[N] * F, table_dtype=dtype,
+                               table_to_tower=t2t, batch=B, pooled_dtype=dtype,
+                               tm_out=[8] * (max(t2t) + 1))
+
+
+def _tower_major(w, R_enc):
+    """(B, F, N) encoded values -> the flat tower-major tensor [T][B][W_t] of the plan."""
+    base, widths, col = wl.pooled_layout(w)
+    flat = np.zeros(base[-1], dtype=R_enc.dtype)
+    for f in range(w.num_tables):
+        t = w.table_to_tower[f]
+        view = flat[base[t]:base[t + 1]].reshape(w.batch, widths[t])
+        view[:, col[f]:col[f] + w.dims[f]] = R_enc[:, f, :]
+    return flat
+
+
+def _interaction(dw, pooled_dev):
+    F = dw.w.num_tables
+    ws = torch.empty(max(16, dmt.dmt_tp_workspace_bytes(dw.plan, dw.w.batch)), dtype=torch.uint8,
+                     device="cuda")
+    out = torch.full((F, F), float("nan"), dtype=torch.float32, device="cuda")
+    dmt.dmt_tp_interaction(dw.plan, pooled_dev, dw.w.batch, out, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def _check(I, ref, what):
+    assert np.isfinite(I).all(), what
+    np.testing.assert_array_equal(I, I.T, err_msg=what + ": not symmetric")
+    err = np.abs(I.astype(np.float64) - ref)
+    assert err.max() <= ATOL, "%s: worst error %g" % (what, err.max())
+    assert np.sqrt(np.mean(err * err)) <= RMS, "%s: rms error %g" % (what, np.sqrt(np.mean(err * err)))
+
+
+@pytest.mark.parametrize("F,N,B,T,dtype,sizes", [
+    (5, 8, 37, 1, "f32", None),
+    (64, 128, 300, 1, "bf16", None),          # one full tile, Mid's feature shape
+    (70, 64, 129, 3, "f16", [30, 5, 35]),     # ragged second tile, towers of unequal width
+    (130, 32, 50, 2, "bf16", None),           # three tiles: six tile pairs
+    (16, 16, 1, 1, "f32", None),              # a batch of one
+    (8, 256, 20, 1, "f32", None),              # the widest float32 rows a plan takes
+    (4, 512, 9, 2, "bf16", None),             # the widest 16-bit rows
+    (12, 24, 33, 1, "bf16", None),            # N not a multiple of the MFMA's K step
+    (64, 128, 2500, 8, "f16", None),          # more samples than batch slices
+])
+def test_interaction_matches_the_oracle(F, N, B, T, dtype, sizes):
+    w = _workload(F, N, T, B, dtype, sizes)
+    dw = DeviceWorkload(w)
+    R = wl.tp_embeddings(7, B, F, N, groups=max(1, F // 4))
+    enc = wl.encode(R.astype(np.float32), dtype)
+    I = _interaction(dw, to_device(_tower_major(w, enc), dtype))
+    ref = tp.tp_interaction(wl.decode(enc, dtype))
+    _check(I, ref, "F=%d N=%d B=%d %s" % (F, N, B, dtype))
+    np.testing.assert_allclose(np.diag(I), 1.0, atol=ATOL)
+
+
+def test_zero_embeddings_count_as_cosine_zero_and_signs_cancel():
+    F, N, B = 6, 16, 8
+    w = _workload(F, N, 2, B, "f32")
+    dw = DeviceWorkload(w)
+    R = wl.tp_embeddings(8, B, F, N, groups=3)
+    R[::2, 1, :] = 0.0                      # feature 1 has an empty bag in every other sample
+    R[:, 4, :] = R[:, 0, :]                 # feature 4 agrees with feature 0 in half of the batch
+    R[B // 2:, 4, :] *= -1.0                # ... and opposes it in the other half
+    R[:, 5, :] = 0.0                        # feature 5 never has an embedding
+    enc = R.astype(np.float32)
+    I = _interaction(dw, to_device(_tower_major(w, enc), "f32"))
+    ref = tp.tp_interaction(enc)
+    _check(I, ref, "zero rows")
+    assert I[1, 1] == pytest.approx(0.5, abs=ATOL) and I[5].max() == 0.0
+    assert I[0, 4] <= ATOL and I[0, 0] == pytest.approx(1.0, abs=ATOL)
+
+
+def test_interaction_of_the_device_lookup_output():
+    # lookup -> interaction on the device against oracle lookup -> oracle interaction
+    w = wl.scaled(wl.mid(), max_rows=5000, batch=257, num_tables=24)
+    dw = DeviceWorkload(w)
+    idx, off = wl.lookup_batch(w)
+    pooled_dev = dw.lookup(idx, off, "bf16")
+    I = _interaction(dw, pooled_dev)
+    pooled = oracle.lookup_towered(dw.host_tables, w.table_dtype, w.dims, w.table_to_tower, idx, off,
+                                   w.batch)
+    R = np.zeros((w.batch, w.num_tables, 128))
+    _, _, col = wl.pooled_layout(w)
+    for f in range(w.num_tables):
+        R[:, f, :] = pooled[w.table_to_tower[f]][:, col[f]:col[f] + 128]
+    # the device pools in float32 and rounds to bf16 once; the oracle works on the exact sums
+    ref = tp.tp_interaction(R)
+    err = np.abs(I - ref)
+    assert err.max() <= ATOL + 2.0 ** -8 and np.sqrt(np.mean(err * err)) <= 3e-4
+
+
+def test_partition_chain_recovers_planted_groups_and_matches_the_oracle():
+    G, per, N, B = 8, 8, 64, 512
+    F = G * per
+    w = _workload(F, N, 1, B, "bf16")
+    dw = DeviceWorkload(w)
+    R = wl.tp_embeddings(9, B, F, N, groups=G)
+    enc = wl.encode(R.astype(np.float32), "bf16")
+    I = _interaction(dw, to_device(_tower_major(w, enc), "bf16"))
+    x0, start = wl.tp_start(9, F, 2, G)
+    group = np.arange(F) % G
+    start = np.array([int(np.nonzero(group == g)[0][0]) for g in range(G)])
+    x, stress = dmt.dmt_tp_embed(I, "coherent", 2, 2000, 0.02, x0)
+    labels, centres, it = dmt.dmt_tp_kmeans(x, G, 1.0, x[start])
+    for h in range(G):
+        assert len(set(group[labels == h])) == 1, (h, group[labels == h])
+    assert sorted(np.bincount(labels)) == [per] * G
+    # the oracle on the same (decoded) embeddings and the same draws lands on the same partition
+    res = tp.tp_partition(wl.decode(enc, "bf16"), G, "coherent", x0, start, 2000, 0.02)
+    np.testing.assert_array_equal(labels, res["labels"])
+    # the labels are usable as a plan's table -> tower map
+    plan = dmt.dmt_plan_create(w.rows, w.dims, w.table_dtype, G, [int(t) for t in labels], B,
+                               F * B * w.len_cap)
+    assert plan.num_towers == G
+
+
+def test_interaction_rejects_what_it_cannot_run():
+    w = _workload(6, 16, 2, 10, "f32")
+    dw = DeviceWorkload(w)
+    F = 6
+    pooled = torch.zeros(10 * 6 * 16, dtype=torch.float32, device="cuda")
+    out = torch.zeros(F, F, dtype=torch.float32, device="cuda")
+    need = dmt.dmt_tp_workspace_bytes(dw.plan, 10)
+    assert need >= 64 * 64 * 4
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    dmt.dmt_tp_interaction(dw.plan, pooled, 10, out, ws)
+    with pytest.raises(dmt.DmtError) as e:
+        dmt.dmt_tp_interaction(dw.plan, pooled, 10, out, ws[:need - 16])
+    assert e.value.code == 4                 # workspace too small
+    with pytest.raises(dmt.DmtError) as e:
+        dmt.dmt_tp_interaction(dw.plan, pooled, 11, out, ws)
+    assert e.value.code == 1                 # beyond the plan's batch
+    raw = dmt.binding._lib.dmt_tp_interaction
+    assert raw(dw.plan.handle, None, 10, 0, out.data_ptr(), ws.data_ptr(), need, None) == 1
+    assert raw(dw.plan.handle, pooled.data_ptr(), 10, 0, None, ws.data_ptr(), need, None) == 1
+    assert raw(dw.plan.handle, pooled.data_ptr(), 10, 7, out.data_ptr(), ws.data_ptr(), need, None) == 1
+    assert raw(dw.plan.handle, pooled.data_ptr() + 4, 10, 0, out.data_ptr(), ws.data_ptr(), need, None) == 1
+    # tables of different dims have no cosine between them
+    wm = dataclasses.replace(w, dims=[16, 16, 32, 16, 16, 16])
+    dwm = DeviceWorkload(wm)
+    assert dmt.dmt_tp_workspace_bytes(dwm.plan, 10) == 0
+    with pytest.raises(dmt.DmtError) as e:
+        dmt.dmt_tp_interaction(dwm.plan, pooled, 10, out, ws)
+    assert e.value.code == 2
+    # dims that do not split into 16-byte chunks
+    wo = dataclasses.replace(w, dims=[12] * 6)
+    with pytest.raises(dmt.DmtError) as e:
+        dmt.dmt_tp_interaction(DeviceWorkload(wo).plan, pooled, 10, out, ws)
+    assert e.value.code == 2
+    torch.cuda.synchronize()

@@ -183,6 +183,23 @@ def by_name(name: str) -> Workload:
             "backward": lambda: mid(True), "imbalanced": imbalanced}[name]()
 
 
+def tp_embeddings(seed: int, B: int, F: int, N: int, groups: int, noise: float = 0.3) -> np.ndarray:
+    """Synthetic pooled embeddings (B, F, N), float64, for the Tower Partitioner: feature f belongs
+    to the planted group f % groups; per sample every group draws one N(0, 1) direction that its
+    features share, and every feature adds independent N(0, noise^2) on top.  Stands in for the
+    embeddings of a trained model (features that interact move together)."""
+    rng = np.random.default_rng([seed, 0x7470])
+    base = rng.standard_normal((B, groups, N))
+    return base[:, np.arange(F) % groups, :] + noise * rng.standard_normal((B, F, N))
+
+
+def tp_start(seed: int, F: int, n: int, T: int):
+    """The Tower Partitioner's random draws: start coordinates N(0, 1) of shape (F, n) and the T
+    distinct features whose embedded coordinates serve as start centres."""
+    rng = np.random.default_rng([seed, 0x7471])
+    return rng.standard_normal((F, n)), np.sort(rng.choice(F, T, replace=False))
+
+
 def scaled(w: Workload, *, max_rows: Optional[int] = None,
            batch: Optional[int] = None, num_tables: Optional[int] = None,
            name: Optional[str] = None) -> Workload:
