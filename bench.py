@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--workload", default="backward")
     ap.add_argument("--no-tm-bwd", action="store_true",
                     help="skip the separate timing of the Tower Module backward")
+    ap.add_argument("--no-tp", action="store_true",
+                    help="skip the separate timing of the Tower Partitioner")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run dmt_calibration_copy on 1 GiB three times (for rocprofv3 --pmc runs)")
     return ap.parse_args()
@@ -196,6 +198,13 @@ def main():
             tm_bwd["whole_tower_step"] = time_whole_step(torch, dmt, wl, w, plan, tm_params, pooled, tm_out,
                                                          tm_ws, bwd_ws, batches, B, args.steps)
 
+    # ---- Tower Partitioner on this batch's pooled embeddings (not part of `value`)
+    tp_out = None
+    if not args.no_tp and len(set(w.dims)) == 1 and w.dims[0] % 8 == 0:
+        dmt.dmt_tower_lookup_fwd(plan, batches[0]["idx"], batches[0]["off"], B, pooled)
+        tp_out = time_tower_partitioner(torch, dmt, wl, w, plan, pooled, B, args.steps,
+                                        with_oracle=default and not args.no_cpu)
+
     if args.calibrate:
         a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         c = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
@@ -292,9 +301,70 @@ def main():
         "kernel_breakdown": kernels,
         "parity_vs_oracle_on_sample": cpu["parity"] if cpu else None,
         "tm_backward": tm_bwd,
+        "tower_partitioner": tp_out,
     }
     print(json.dumps(out), flush=True)
     return 0
+
+
+def time_tower_partitioner(torch, dmt, wl, w, plan, pooled, B, steps, with_oracle):
+    """The Tower Partitioner (Sec. 3.3) on the pooled embeddings of one batch: the interaction
+    matrix on the device (timed per launch by HIP events), then the embedding by Adam and the
+    constrained K-means on the host, with as many towers as the workload has."""
+    F, N, T = w.num_tables, w.dims[0], w.num_towers
+    eo = wl.ELT_BYTES[w.pooled_dtype]
+    ws = torch.empty(max(16, dmt.dmt_tp_workspace_bytes(plan, B)), dtype=torch.uint8, device="cuda")
+    I = torch.empty(F, F, dtype=torch.float32, device="cuda")
+    for _ in range(3):
+        dmt.dmt_tp_interaction(plan, pooled, B, I, ws)
+    torch.cuda.synchronize()
+    name_to_id = {dmt.dmt_kernel_name(i): i for i in range(dmt.DMT_K_COUNT)}
+    dmt.dmt_profile_enable(plan, (1 << name_to_id["tp_gram"]) | (1 << name_to_id["tp_finish"]))
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        dmt.dmt_tp_interaction(plan, pooled, B, I, ws)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    prof = dmt.dmt_profile_read(plan)
+    dmt.dmt_profile_enable(plan, 0)
+    gram_ms = prof["tp_gram"][0] / prof["tp_gram"][1]
+    fin_ms = prof["tp_finish"][0] / prof["tp_finish"][1]
+    nbytes = B * F * N * eo                       # every pooled embedding read once
+    flops = 2.0 * B * F * F * N
+    I_host = I.cpu().numpy()
+    x0, start = wl.tp_start(w.seed, F, 2, T)
+    t0 = time.perf_counter()
+    x, stress = dmt.dmt_tp_embed(I_host, "coherent", 2, 2000, 0.02, x0)
+    embed_ms = (time.perf_counter() - t0) * 1e3
+    t0 = time.perf_counter()
+    labels, _, it = dmt.dmt_tp_kmeans(x, T, 1.0, x[start])
+    kmeans_ms = (time.perf_counter() - t0) * 1e3
+    sizes = np.bincount(labels, minlength=T)
+    out = dict(features=F, dim=N, towers=T, batch=B,
+               interaction_ms=round(ms, 4), samples_per_s=round(B / (ms * 1e-3), 1),
+               tp_gram=dict(ms_per_launch=round(gram_ms, 4), bound="hbm", algorithmic_bytes=int(nbytes),
+                            achieved=round(nbytes / (gram_ms * 1e-3) / 1e9, 1), peak=HBM_PEAK_GBS,
+                            unit="GB/s", frac=round(nbytes / (gram_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                            tflops=round(flops / (gram_ms * 1e-3) / 1e12, 2)),
+               tp_finish_ms=round(fin_ms, 4),
+               host=dict(embed_ms=round(embed_ms, 2), adam_steps=2000, stress=round(stress, 4),
+                         kmeans_ms=round(kmeans_ms, 2), kmeans_assignment_steps=it,
+                         tower_sizes=[int(sizes.min()), int(sizes.max())]))
+    if with_oracle:
+        from oracle import tp as otp
+        nb = min(B, 512)                          # a bounded sample of the batch for the CPU oracle
+        R = np.zeros((nb, F, N))
+        base, widths, col = wl.pooled_layout(w)
+        host = pooled.float().cpu().numpy()
+        for f in range(F):
+            t = w.table_to_tower[f]
+            R[:, f, :] = host[base[t]:base[t + 1]].reshape(B, widths[t])[:nb, col[f]:col[f] + N]
+        t0 = time.perf_counter()
+        I_ref = otp.tp_interaction(R)
+        dt = time.perf_counter() - t0
+        out["cpu_oracle"] = dict(samples_per_s=round(nb / dt, 1), sample="first %d samples of the batch" % nb,
+                                 kind="oracle")
+    return out
 
 
 def tm_grad_buffers(torch, wl, w):

@@ -326,8 +326,9 @@ dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const int32_t* indi
  *   pooled        dev, the tower-major tensor dmt_tower_lookup_fwd wrote for this plan and B
  *   interaction   dev out, float32 [F][F] in table order, exactly symmetric
  *   workspace     dev, at least dmt_tp_workspace_bytes(plan, B), 16-byte aligned
- * The normalised values enter the contraction as float16 and accumulate in float32: an
- * entry differs from the exact value by at most 2^-10.
+ * 16-bit embeddings are contracted as they are (their products are exact in float32) and the
+ * cosines formed in float32; float32 embeddings are normalised and rounded to float16 first,
+ * so that an entry can differ from the exact value by up to 2^-10.
  */
 size_t dmt_tp_workspace_bytes(const dmt_plan* plan, int64_t B);
 

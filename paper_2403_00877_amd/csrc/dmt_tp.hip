@@ -3,12 +3,13 @@
 //
 //   dmt_tp_interaction  device: I = | mean_b Rn_b Rn_b^T |, Rn the per-(sample, feature)
 //                       normalised embeddings.  One fused kernel reads the pooled tensor once:
-//                       it normalises a 64-feature tile of one sample on the way into LDS (as
-//                       float16: the values are at most 1 in magnitude) and feeds the tile to
-//                       MFMA, accumulating the 64 x 64 Gram tile over its slice of the batch in
-//                       registers; a second kernel sums the slices in a fixed order, divides by
-//                       B and takes the absolute value.  At F = 64 the contraction is 64 FLOP
-//                       per byte read, so the kernel is bound by reading the pooled tensor.
+//                       it stages a 64-feature tile of one sample in LDS, computing the row
+//                       norms on the way, multiplies the tile on MFMA and adds the products,
+//                       scaled by the two inverse norms, to the 64 x 64 Gram tile it keeps in
+//                       registers over its slice of the batch; a second kernel sums the slices
+//                       in a fixed order, divides by B and takes the absolute value.  At
+//                       F = 64 the contraction is 64 FLOP per byte read, so the kernel is bound
+//                       by reading the pooled tensor.
 //   dmt_tp_embed        host, float64: D = f(I), then Adam on the pairwise-distance objective.
 //   dmt_tp_kmeans       host, float64: constrained K-means; the assignment step is solved
 //                       exactly as a square assignment problem over (group, slot) pairs.
@@ -19,6 +20,7 @@
 
 #include <algorithm>
 #include <limits>
+#include <type_traits>
 #include <vector>
 
 #include "dmt_internal.h"
@@ -28,55 +30,124 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kTile = 64;                    // features per Gram tile side
-constexpr int kTargetBlocks = 1024;          // blocks per launch the batch is sliced for
+constexpr int kTargetBlocks = 1024;          // resident blocks: 4 per CU (LDS 34 KB each at N = 128)
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 __host__ __device__ inline int tp_pair_index(int ti, int tj, int nt) {   // ti <= tj
   return ti * nt - ti * (ti - 1) / 2 + (tj - ti);
 }
 
-// 8 consecutive elements of a row as float32.
+// One lane's 8 consecutive elements of a row, as loaded: one 16-byte chunk of 16-bit elements,
+// two of float32.
+template <int DT> struct Raw8 { uint4 v[DT == DMT_F32 ? 2 : 1]; };
+
 template <int DT>
-__device__ __forceinline__ void load8(const void* base, int64_t off, float (&x)[8]) {
+__device__ __forceinline__ Raw8<DT> fetch8(const void* base, int64_t off) {
+  Raw8<DT> r;
   if constexpr (DT == DMT_F32) {
-    const float4 a = dmt::gload((const float4*)((const float*)base + off));
-    const float4 b = dmt::gload((const float4*)((const float*)base + off) + 1);
-    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
-    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+    r.v[0] = dmt::gload((const uint4*)((const float*)base + off));
+    r.v[1] = dmt::gload((const uint4*)((const float*)base + off) + 1);
   } else {
-    dmt::decode_chunk<DT>(x, dmt::gload((const uint4*)((const uint16_t*)base + off)));
+    r.v[0] = dmt::gload((const uint4*)((const uint16_t*)base + off));
+  }
+  return r;
+}
+
+template <int DT>
+__device__ __forceinline__ void decode8(const Raw8<DT>& r, float (&x)[8]) {
+  if constexpr (DT == DMT_F32) {
+    x[0] = __uint_as_float(r.v[0].x); x[1] = __uint_as_float(r.v[0].y);
+    x[2] = __uint_as_float(r.v[0].z); x[3] = __uint_as_float(r.v[0].w);
+    x[4] = __uint_as_float(r.v[1].x); x[5] = __uint_as_float(r.v[1].y);
+    x[6] = __uint_as_float(r.v[1].z); x[7] = __uint_as_float(r.v[1].w);
+  } else {
+    dmt::decode_chunk<DT>(x, r.v[0]);
   }
 }
 
-// Gram tiles of the normalised embeddings.  Block (pair, slice): features [64 ti, 64 ti + 64)
-// against [64 tj, 64 tj + 64), ti <= tj, over samples [slice * per, (slice + 1) * per).
+// Sum of `v` over the LPR consecutive lanes (LPR = 4 ... 64, aligned) that hold one row.
+template <int LPR>
+__device__ __forceinline__ float row_group_sum(float v) {
+  auto dpp = [](float x, auto ctrl) __attribute__((always_inline)) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), decltype(ctrl)::value,
+                                                      0xf, 0xf, true));
+  };
+  v += dpp(v, std::integral_constant<int, 0xB1>{});                      // lane ^ 1
+  v += dpp(v, std::integral_constant<int, 0x4E>{});                      // lane ^ 2
+  if constexpr (LPR >= 8) v += dpp(v, std::integral_constant<int, 0x141>{});   // mirror in 8
+  if constexpr (LPR >= 16) v += dpp(v, std::integral_constant<int, 0x140>{});  // mirror in 16
+  if constexpr (LPR >= 32) v += __shfl_xor(v, 16);
+  if constexpr (LPR >= 64) v += __shfl_xor(v, 32);
+  return v;
+}
+
+// Sum of squares of the 8 elements of a 16-byte chunk of 16-bit elements.
+template <int DT>
+__device__ __forceinline__ float sumsq8(uint4 r) {
+  float s = 0.f;
+  const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    if constexpr (DT == DMT_F16) {
+      const halfx2 h = __builtin_bit_cast(halfx2, w[q]);
+      s = __builtin_amdgcn_fdot2(h, h, s, false);
+    } else {
+      const bf16x2 h = __builtin_bit_cast(bf16x2, w[q]);
+      s = __builtin_amdgcn_fdot2_f32_bf16(h, h, s, false);
+    }
+  }
+  return s;
+}
+
+// Gram tiles of the normalised embeddings.  Block (pair, slice): features [TF ti, TF ti + TF)
+// against [TF tj, TF tj + TF), ti <= tj, over samples [slice * per, (slice + 1) * per); TF is
+// 64 (one tile covers up to 64 features) or 128 (more features: fewer, larger tiles re-read
+// the pooled rows less often).
+//
+// Per sample the block stages its two feature tiles in LDS, multiplies them on MFMA
+// (4 waves, TF / 64 squared 32 x 32 sub-tiles each) and adds  product * inv_norm(row) * inv_norm(column)  to
+// its running sum.  16-bit rows go to LDS and into the matrix cores exactly as they were
+// loaded (their products are exact in float32); only their norms are computed on the way.
+// float32 rows are normalised first and stored as float16, with scales of one.
 // Thread layout of the staging step: LPR = 4 NP lanes per feature row, 8 elements per lane,
-// 256 / LPR rows per pass, NP passes per tile.  LDS rows hold Npad = N rounded up to 16 halfs
-// (zeros past N) plus 8 halfs of padding.
-template <int DT, int NP>
+// 256 / LPR rows per pass.  LDS rows hold Npad = N rounded up to 16
+// elements (zeros past N) plus 8 of padding.  The next sample's rows are loaded into
+// registers while the current one is multiplied, so global loads stay in flight across the
+// barriers.  Consecutive block ids run on different XCDs: the blocks of one batch slice (one
+// per tile pair, all reading the same samples) get ids that are equal mod 8, so that they
+// share one XCD's L2.
+template <int DT, int NP, int TF>
 __global__ __launch_bounds__(kBlock) void tp_gram(const DmtTableMeta* __restrict__ meta,
                                                   const void* __restrict__ pooled, int64_t B,
                                                   int F, int N, int nt, int npairs, int64_t per,
-                                                  float* __restrict__ partial) {
-  constexpr int LPR = 4 * NP, RP = kBlock / LPR;
+                                                  int64_t nslices, float* __restrict__ partial) {
+  constexpr int LPR = 4 * NP, RP = kBlock / LPR, PT = TF / RP;   // PT staging passes per tile
+  constexpr int SW = TF / 64;                // 32 x 32 sub-tiles per wave and direction
+  constexpr bool kRaw = DT != DMT_F32;
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
-  __shared__ int64_t s_base[2 * kTile];
-  __shared__ int32_t s_pitch[2 * kTile];
-  const int pair = blockIdx.x % npairs;
-  const int64_t slice = blockIdx.x / npairs;
+  __shared__ int64_t s_base[2 * TF];
+  __shared__ int32_t s_pitch[2 * TF];
+  __shared__ __attribute__((aligned(16))) float s_inv[2][TF];
+  const int64_t rest = blockIdx.x >> 3;
+  const int pair = (int)(rest % npairs);
+  const int64_t slice = (rest / npairs) * 8 + (blockIdx.x & 7);
+  if (slice >= nslices) return;
   int ti = 0;
-  while (tp_pair_index(ti + 1, ti + 1, nt) <= pair && ti + 1 < nt) ++ti;
+  while (ti + 1 < nt && tp_pair_index(ti + 1, ti + 1, nt) <= pair) ++ti;
   const int tj = ti + (pair - tp_pair_index(ti, ti, nt));
   const bool diag = ti == tj;
   const int npad = (N + 15) & ~15, ldx = npad + 8;
   uint16_t* Xi = lds;
-  uint16_t* Xj = diag ? lds : lds + kTile * ldx;
+  uint16_t* Xj = diag ? lds : lds + TF * ldx;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (tid < 2 * kTile) {
-    const int f = (tid < kTile ? ti : tj) * kTile + (tid & (kTile - 1));
+  if (tid < 2 * TF) {
+    const int f = (tid < TF ? ti : tj) * TF + (tid & (TF - 1));
     int64_t base = 0;
     int32_t pitch = 0;
     if (f < F) {
@@ -91,87 +162,168 @@ __global__ __launch_bounds__(kBlock) void tp_gram(const DmtTableMeta* __restrict
 
   const int chunk = tid % LPR, row0 = tid / LPR;
   const bool cin = chunk * 8 < N;
-  floatx16 acc;
+  floatx16 total[SW][SW];
 #pragma unroll
-  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  for (int i = 0; i < SW; ++i)
+#pragma unroll
+    for (int j = 0; j < SW; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) total[i][j][v] = 0.f;
+  // the wave's SW x SW sub-tiles cover rows [32 SW wi, +32 SW) x columns [32 SW wj, +32 SW)
   const int wi = wave >> 1, wj = wave & 1;
-  const uint16_t* pa = Xi + (32 * wi + (lane & 31)) * ldx + (lane >> 5) * 8;
-  const uint16_t* pb = Xj + (32 * wj + (lane & 31)) * ldx + (lane >> 5) * 8;
+  const uint16_t* pa = Xi + (32 * SW * wi + (lane & 31)) * ldx + (lane >> 5) * 8;
+  const uint16_t* pb = Xj + (32 * SW * wj + (lane & 31)) * ldx + (lane >> 5) * 8;
+  const float* inv_col = &s_inv[diag ? 0 : 1][32 * SW * wj + (lane & 31)];
+  const float* inv_row = &s_inv[0][32 * SW * wi + (lane >> 5) * 4];
 
-  auto stage = [&](int which, int64_t b, uint16_t* Xs) __attribute__((always_inline)) {
-    float x[NP][8];
+  Raw8<DT> raw[2][PT];
+  auto fetch = [&](int which, int64_t b) __attribute__((always_inline)) {
 #pragma unroll
-    for (int p = 0; p < NP; ++p) {
+    for (int p = 0; p < PT; ++p) {
       const int row = p * RP + row0;
-      const int f = (which ? tj : ti) * kTile + row;
+      const int f = (which ? tj : ti) * TF + row;
       if (cin && f < F) {
-        load8<DT>(pooled, s_base[which * kTile + row] + b * s_pitch[which * kTile + row] + chunk * 8,
-                  x[p]);
+        raw[which][p] = fetch8<DT>(
+            pooled, s_base[which * TF + row] + b * s_pitch[which * TF + row] + chunk * 8);
       } else {
 #pragma unroll
-        for (int q = 0; q < 8; ++q) x[p][q] = 0.f;
+        for (int q = 0; q < (DT == DMT_F32 ? 2 : 1); ++q) raw[which][p].v[q] = make_uint4(0, 0, 0, 0);
       }
     }
+  };
+  auto commit = [&](int which, uint16_t* Xs) __attribute__((always_inline)) {
 #pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      float ss = 0.f;
+    for (int p = 0; p < PT; ++p) {
+      const int row = p * RP + row0;
+      if constexpr (kRaw) {
+        const uint4 r = raw[which][p].v[0];
+        const float ss = row_group_sum<LPR>(sumsq8<DT>(r));
+        if (chunk * 8 < npad) *(uint4*)(Xs + row * ldx + chunk * 8) = r;
+        if (chunk == 0) s_inv[which][row] = ss > 0.f ? __builtin_amdgcn_rsqf(ss) : 0.f;
+      } else {
+        float x[8];
+        decode8<DT>(raw[which][p], x);
+        float ss = 0.f;
 #pragma unroll
-      for (int q = 0; q < 8; ++q) ss += x[p][q] * x[p][q];
-#pragma unroll
-      for (int o = 1; o < LPR; o <<= 1) ss += __shfl_xor(ss, o);
-      const float inv = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
-      if (chunk * 8 < npad) {
-        const int row = p * RP + row0;
-        *(uint4*)(Xs + row * ldx + chunk * 8) =
-            make_uint4(dmt::pack2<DMT_F16>(x[p][0] * inv, x[p][1] * inv),
-                       dmt::pack2<DMT_F16>(x[p][2] * inv, x[p][3] * inv),
-                       dmt::pack2<DMT_F16>(x[p][4] * inv, x[p][5] * inv),
-                       dmt::pack2<DMT_F16>(x[p][6] * inv, x[p][7] * inv));
+        for (int q = 0; q < 8; ++q) ss += x[q] * x[q];
+        ss = row_group_sum<LPR>(ss);
+        const float inv = ss > 0.f ? __builtin_amdgcn_rsqf(ss) : 0.f;
+        if (chunk * 8 < npad) {
+          *(uint4*)(Xs + row * ldx + chunk * 8) =
+              make_uint4(dmt::pack2<DMT_F16>(x[0] * inv, x[1] * inv),
+                         dmt::pack2<DMT_F16>(x[2] * inv, x[3] * inv),
+                         dmt::pack2<DMT_F16>(x[4] * inv, x[5] * inv),
+                         dmt::pack2<DMT_F16>(x[6] * inv, x[7] * inv));
+        }
+        if (chunk == 0) s_inv[which][row] = 1.0f;
       }
     }
   };
 
   const int64_t b_begin = slice * per, b_end = b_begin + per < B ? b_begin + per : B;
+  if (b_begin < b_end) {
+    fetch(0, b_begin);
+    if (!diag) fetch(1, b_begin);
+  }
   for (int64_t b = b_begin; b < b_end; ++b) {
     __syncthreads();                         // the previous sample's tile has been consumed
-    stage(0, b, Xi);
-    if (!diag) stage(1, b, Xj);
+    commit(0, Xi);
+    if (!diag) commit(1, Xj);
     __syncthreads();
+    if (b + 1 < b_end) {
+      fetch(0, b + 1);
+      if (!diag) fetch(1, b + 1);
+    }
+    floatx16 acc[SW][SW];
+#pragma unroll
+    for (int i = 0; i < SW; ++i)
+#pragma unroll
+      for (int j = 0; j < SW; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     for (int k = 0; k < npad; k += 16) {
-      const uint4 a = *(const uint4*)(pa + k);
-      const uint4 c = *(const uint4*)(pb + k);
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8, a),
-                                                   __builtin_bit_cast(halfx8, c), acc, 0, 0, 0);
+      uint4 a[SW], c[SW];
+#pragma unroll
+      for (int i = 0; i < SW; ++i) {
+        a[i] = *(const uint4*)(pa + i * 32 * ldx + k);
+        c[i] = *(const uint4*)(pb + i * 32 * ldx + k);
+      }
+#pragma unroll
+      for (int i = 0; i < SW; ++i)
+#pragma unroll
+        for (int j = 0; j < SW; ++j) {
+          if constexpr (DT == DMT_BF16)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                __builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, c[j]), acc[i][j], 0, 0, 0);
+          else
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                __builtin_bit_cast(halfx8, a[i]), __builtin_bit_cast(halfx8, c[j]), acc[i][j], 0, 0, 0);
+        }
+    }
+    // lane holds column lane % 32 of rows (v / 4) * 8 + (lane / 32) * 4 + v % 4 of a sub-tile
+#pragma unroll
+    for (int j = 0; j < SW; ++j) {
+      const float ic = inv_col[32 * j];
+#pragma unroll
+      for (int i = 0; i < SW; ++i) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float4 ir = *(const float4*)(inv_row + 32 * i + q * 8);
+          total[i][j][4 * q + 0] += acc[i][j][4 * q + 0] * (ir.x * ic);
+          total[i][j][4 * q + 1] += acc[i][j][4 * q + 1] * (ir.y * ic);
+          total[i][j][4 * q + 2] += acc[i][j][4 * q + 2] * (ir.z * ic);
+          total[i][j][4 * q + 3] += acc[i][j][4 * q + 3] * (ir.w * ic);
+        }
+      }
     }
   }
 
-  // lane holds column lane % 32 of rows (v / 4) * 8 + (lane / 32) * 4 + v % 4 of its 32 x 32 tile
-  float* out = partial + ((int64_t)slice * npairs + pair) * (kTile * kTile);
+  float* out = partial + ((int64_t)slice * npairs + pair) * (TF * TF);
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const int r = 32 * wi + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-    out[r * kTile + 32 * wj + (lane & 31)] = acc[v];
-  }
+  for (int i = 0; i < SW; ++i)
+#pragma unroll
+    for (int j = 0; j < SW; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int r = 32 * (SW * wi + i) + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+        out[r * TF + 32 * (SW * wj + j) + (lane & 31)] = total[i][j][v];
+      }
 }
 
 // I[i][j] = | sum over the batch slices of the Gram entry | / B.  Entry (i, j) and (j, i) are
-// both read from the tile element (min, max), so the result is exactly symmetric.
+// both read from the tile element (min, max), so the result is exactly symmetric.  A block
+// takes 16 consecutive entries; its 16 thread groups each add up every 16th slice, then the
+// group sums are added in group order: a fixed order whatever the launch.
+constexpr int kFinElems = 16, kFinGroups = kBlock / kFinElems;
 __global__ __launch_bounds__(kBlock) void tp_finish(const float* __restrict__ partial, int F,
-                                                    int nt, int npairs, int64_t nslices,
-                                                    float inv_b, float* __restrict__ I) {
-  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (e >= (int64_t)F * F) return;
-  const int i = (int)(e / F), j = (int)(e % F);
-  const int a = i < j ? i : j, c = i < j ? j : i;
-  const float* p = partial + (int64_t)tp_pair_index(a / kTile, c / kTile, nt) * (kTile * kTile) +
-                   (a % kTile) * kTile + (c % kTile);
+                                                    int tile, int nt, int npairs,
+                                                    int64_t nslices, float inv_b,
+                                                    float* __restrict__ I) {
+  __shared__ float s_sum[kFinGroups][kFinElems];
+  const int le = threadIdx.x % kFinElems, g = threadIdx.x / kFinElems;
+  const int64_t e = (int64_t)blockIdx.x * kFinElems + le;
   float s = 0.f;
-  for (int64_t q = 0; q < nslices; ++q) s += p[q * npairs * (kTile * kTile)];
-  I[e] = fabsf(s * inv_b);
+  if (e < (int64_t)F * F) {
+    const int i = (int)(e / F), j = (int)(e % F);
+    const int a = i < j ? i : j, c = i < j ? j : i;
+    const float* p = partial + (int64_t)tp_pair_index(a / tile, c / tile, nt) * (tile * tile) +
+                     (a % tile) * tile + (c % tile);
+    const int64_t stride = (int64_t)npairs * (tile * tile);
+#pragma unroll 8
+    for (int64_t q = g; q < nslices; q += kFinGroups) s += p[q * stride];
+  }
+  s_sum[g][le] = s;
+  __syncthreads();
+  if (g == 0 && e < (int64_t)F * F) {
+    float t = 0.f;
+#pragma unroll
+    for (int q = 0; q < kFinGroups; ++q) t += s_sum[q][le];
+    I[e] = fabsf(t * inv_b);
+  }
 }
 
 struct TpShape {
-  int N, nt, npairs;
+  int N, np, tile, nt, npairs;             // np: staging passes per 64 rows (4 np lanes per row)
   int64_t per, nslices;
   size_t bytes;
 };
@@ -184,39 +336,48 @@ dmt_status tp_shape(const dmt_plan* p, int64_t B, TpShape& s) {
   if (s.N % 8 != 0 || s.N > 512) return DMT_ENOTSUP;
   for (const DmtTableMeta& m : p->meta)
     if (m.col_off % 8 != 0 || m.tower_width % 8 != 0) return DMT_ENOTSUP;
-  s.nt = (p->F + kTile - 1) / kTile;
+  s.np = s.N <= 32 ? 1 : s.N <= 64 ? 2 : s.N <= 128 ? 4 : s.N <= 256 ? 8 : 16;
+  // 64-feature tiles.  (The kernel also runs with TF = 128, which re-reads the pooled rows less
+  // when there are more than 64 features, but measured slower on MI355X: 0.76 ms against 0.66 ms
+  // at F = 256, N = 128, B = 16384.  Its larger register and LDS footprint halves the resident
+  // blocks, and the loads in flight with them.)
+  s.tile = kTile;
+  s.nt = (p->F + s.tile - 1) / s.tile;
   s.npairs = s.nt * (s.nt + 1) / 2;
-  const int64_t want = std::max<int64_t>(1, kTargetBlocks / s.npairs);
+  // one round of resident blocks for a single pair; two when diagonal pairs (one tile to stage)
+  // and off-diagonal pairs (two) share the launch, so that the uneven blocks even out
+  const int64_t want = std::max<int64_t>(1, (s.npairs > 1 ? 2 : 1) * kTargetBlocks / s.npairs);
   s.per = (B + want - 1) / want;
   s.nslices = (B + s.per - 1) / s.per;
-  s.bytes = sizeof(float) * (size_t)s.nslices * s.npairs * kTile * kTile;
+  s.bytes = sizeof(float) * (size_t)s.nslices * s.npairs * s.tile * s.tile;
   return DMT_OK;
 }
 
-template <int DT, int NP>
+template <int DT, int NP, int TF>
 void launch_gram(const dmt_plan* p, const void* pooled, int64_t B, const TpShape& sh,
                  float* partial, hipStream_t s) {
   const int npad = (sh.N + 15) & ~15;
-  const size_t lds = sizeof(uint16_t) * 2 * kTile * (npad + 8);
+  const size_t lds = sizeof(uint16_t) * 2 * TF * (npad + 8);
   static bool configured = false;           // wide rows need more than the default LDS limit
   if (!configured) {
-    (void)hipFuncSetAttribute((const void*)tp_gram<DT, NP>,
+    (void)hipFuncSetAttribute((const void*)tp_gram<DT, NP, TF>,
                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)(sizeof(uint16_t) * 2 * kTile * (NP * 32 + 8)));
+                              (int)(sizeof(uint16_t) * 2 * TF * (NP * 32 + 8)));
     configured = true;
   }
-  hipLaunchKernelGGL((tp_gram<DT, NP>), dim3((unsigned)(sh.nslices * sh.npairs)), dim3(kBlock), lds,
-                     s, p->d_meta, pooled, B, p->F, sh.N, sh.nt, sh.npairs, sh.per, partial);
+  const int64_t blocks = (sh.nslices + 7) / 8 * 8 * sh.npairs;
+  hipLaunchKernelGGL((tp_gram<DT, NP, TF>), dim3((unsigned)blocks), dim3(kBlock), lds, s, p->d_meta,
+                     pooled, B, p->F, sh.N, sh.nt, sh.npairs, sh.per, sh.nslices, partial);
 }
 
 template <int DT>
 void launch_gram_dt(const dmt_plan* p, const void* pooled, int64_t B, const TpShape& sh,
                     float* partial, hipStream_t s) {
-  if (sh.N <= 32) launch_gram<DT, 1>(p, pooled, B, sh, partial, s);
-  else if (sh.N <= 64) launch_gram<DT, 2>(p, pooled, B, sh, partial, s);
-  else if (sh.N <= 128) launch_gram<DT, 4>(p, pooled, B, sh, partial, s);
-  else if (sh.N <= 256) launch_gram<DT, 8>(p, pooled, B, sh, partial, s);
-  else launch_gram<DT, 16>(p, pooled, B, sh, partial, s);
+  if (sh.np == 1) launch_gram<DT, 1, kTile>(p, pooled, B, sh, partial, s);
+  else if (sh.np == 2) launch_gram<DT, 2, kTile>(p, pooled, B, sh, partial, s);
+  else if (sh.np == 4) launch_gram<DT, 4, kTile>(p, pooled, B, sh, partial, s);
+  else if (sh.np == 8) launch_gram<DT, 8, kTile>(p, pooled, B, sh, partial, s);
+  else launch_gram<DT, 16, kTile>(p, pooled, B, sh, partial, s);
 }
 
 // ------------------------------------------------------------------ host: assignment
@@ -297,8 +458,8 @@ extern "C" dmt_status dmt_tp_interaction(const dmt_plan* plan, const void* poole
   {
     DmtScope scope(plan, DMT_K_TP_FINISH, s);
     const int64_t n = (int64_t)plan->F * plan->F;
-    hipLaunchKernelGGL(tp_finish, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
-                       partial, plan->F, sh.nt, sh.npairs, sh.nslices, (float)(1.0 / (double)B),
+    hipLaunchKernelGGL(tp_finish, dim3((unsigned)((n + kFinElems - 1) / kFinElems)), dim3(kBlock), 0, s,
+                       partial, plan->F, sh.tile, sh.nt, sh.npairs, sh.nslices, (float)(1.0 / (double)B),
                        interaction);
   }
   return hipGetLastError() == hipSuccess ? DMT_OK : DMT_EHIP;

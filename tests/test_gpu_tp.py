@@ -73,6 +73,9 @@ def _check(I, ref, what):
     (4, 512, 9, 2, "bf16", None),             # the widest 16-bit rows
     (12, 24, 33, 1, "bf16", None),            # N not a multiple of the MFMA's K step
     (64, 128, 2500, 8, "f16", None),          # more samples than batch slices
+    (200, 128, 40, 4, "bf16", None),          # 128-feature tiles: two tiles, three pairs
+    (300, 64, 21, 5, "f32", None),            # 128-feature tiles on float32 rows, ragged third tile
+    (70, 128, 30, 2, "f32", None),            # float32 rows too wide for them: 64-feature tiles
 ])
 def test_interaction_matches_the_oracle(F, N, B, T, dtype, sizes):
     w = _workload(F, N, T, B, dtype, sizes)
