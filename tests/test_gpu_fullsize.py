@@ -333,3 +333,46 @@ def test_tower_module_backward_on_sampled_samples(run):
             assert_grad_close(to_f64(grads[t]["db_cross"][l]), rdbc[l], rtol, what + "db_cross[%d]" % l)
         pos += B * tw[t]
         ypos += B * w.tm_out[t]
+
+
+def test_interaction_matrix_on_sampled_pairs(run):
+    """Tower Partitioner, device stage, on the full batch: entries (i, j) of the interaction
+    matrix for sampled feature pairs against the oracle, which pools the two features over all
+    B samples itself from the table rows they touch."""
+    from oracle import tp
+    w, dmt = run.w, run.dmt
+    F, B = w.num_tables, w.batch
+    if len(set(w.dims)) != 1:
+        pytest.skip("tables of different dims have no cosine between them")
+    ws = torch.empty(dmt.dmt_tp_workspace_bytes(run.plan, B), dtype=torch.uint8, device="cuda")
+    I_dev = torch.empty(F, F, dtype=torch.float32, device="cuda")
+    dmt.dmt_tp_interaction(run.plan, run.pooled, B, I_dev, ws)
+    torch.cuda.synchronize()
+    I = I_dev.cpu().numpy()
+    np.testing.assert_array_equal(I, I.T)
+    # a feature's cosine with itself is 1 wherever its bag is not empty
+    lens = np.diff(run.off).reshape(F, B)
+    np.testing.assert_allclose(np.diag(I), (lens > 0).mean(axis=1), atol=1e-4)
+    # the table rows as the lookup saw them (the backward run has updated its tables since)
+    tables = wl.tables_device(w) if w.backward else run.tables
+    rng = np.random.default_rng(321)
+    feats = np.sort(rng.choice(F, size=8, replace=False))
+
+    def pooled_of(f):
+        seg = run.idx[run.off[f * B]:run.off[(f + 1) * B]]
+        rows = np.unique(seg)
+        t = tables[f][torch.from_numpy(rows).cuda()]
+        vals = t.view(torch.int16).cpu().numpy().view(np.uint16) if w.table_dtype == "bf16" else t.cpu().numpy()
+        off = run.off[f * B:(f + 1) * B + 1] - run.off[f * B]
+        p = oracle.lookup_towered([vals], w.table_dtype, [w.dims[f]], [0],
+                                  np.searchsorted(rows, seg).astype(np.int32), off, B)[0]
+        return wl.decode(oracle.round_to(p, w.pooled_dtype), w.pooled_dtype)
+
+    R = np.stack([pooled_of(int(f)) for f in feats], axis=1)            # (B, 8, N)
+    ref = tp.tp_interaction(R)
+    got = I[np.ix_(feats, feats)]
+    # 16-bit pooled values are contracted exactly; what is left is the float32 arithmetic of the
+    # cosines and of the batch mean, and the rare pooled element whose float32 sum rounds to the
+    # neighbouring 16-bit value
+    err = np.abs(got - ref)
+    assert err.max() <= 1e-4, (w.name, err.max())

@@ -21,6 +21,10 @@ pytestmark = pytest.mark.gpu
 # samples, so the typical error is far smaller: bounded here by 1e-4 rms.
 ATOL = 2.0 ** -10
 RMS = 1e-4
+# 16-bit embeddings are contracted as they are: their products are exact in float32, and what is
+# left is float32 rounding in the sums, the norms and the batch mean.
+ATOL16 = 2e-5
+RMS16 = 5e-6
 
 
 def _workload(F, N, T, B, dtype, sizes=None):
@@ -55,12 +59,13 @@ def _interaction(dw, pooled_dev):
     return out.cpu().numpy()
 
 
-def _check(I, ref, what):
+def _check(I, ref, what, dtype="f32"):
+    atol, rms = (ATOL, RMS) if dtype == "f32" else (ATOL16, RMS16)
     assert np.isfinite(I).all(), what
     np.testing.assert_array_equal(I, I.T, err_msg=what + ": not symmetric")
     err = np.abs(I.astype(np.float64) - ref)
-    assert err.max() <= ATOL, "%s: worst error %g" % (what, err.max())
-    assert np.sqrt(np.mean(err * err)) <= RMS, "%s: rms error %g" % (what, np.sqrt(np.mean(err * err)))
+    assert err.max() <= atol, "%s: worst error %g" % (what, err.max())
+    assert np.sqrt(np.mean(err * err)) <= rms, "%s: rms error %g" % (what, np.sqrt(np.mean(err * err)))
 
 
 @pytest.mark.parametrize("F,N,B,T,dtype,sizes", [
@@ -84,7 +89,7 @@ def test_interaction_matches_the_oracle(F, N, B, T, dtype, sizes):
     enc = wl.encode(R.astype(np.float32), dtype)
     I = _interaction(dw, to_device(_tower_major(w, enc), dtype))
     ref = tp.tp_interaction(wl.decode(enc, dtype))
-    _check(I, ref, "F=%d N=%d B=%d %s" % (F, N, B, dtype))
+    _check(I, ref, "F=%d N=%d B=%d %s" % (F, N, B, dtype), dtype)
     np.testing.assert_allclose(np.diag(I), 1.0, atol=ATOL)
 
 
