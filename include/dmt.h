@@ -16,6 +16,12 @@
  *   dmt_tower_module_fwd_keep    the same forward, keeping what its backward needs
  *   dmt_tower_module_bwd         the Tower Module's backward, whose dL/d(pooled)
  *                                is what dmt_tower_lookup_bwd_update consumes
+ * Beside the step, the Tower Partitioner that decides which table goes to which
+ * tower (paper Sec. 3.3):
+ *   dmt_tp_interaction           feature interaction matrix of a batch of pooled
+ *                                embeddings (device)
+ *   dmt_tp_embed, dmt_tp_kmeans  distance embedding by Adam and constrained
+ *                                K-means (host; they touch |F| x |F| numbers)
  *
  * Conventions
  *  - C linkage, no exceptions cross the boundary; every call returns dmt_status.
