@@ -30,6 +30,7 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kTile = 64;                    // features per Gram tile side
+constexpr int kWideBlocks = 256;             // tp_gram_wide: one block per CU
 constexpr int kTargetBlocks = 1024;          // resident blocks: 4 per CU (LDS 34 KB each at N = 128)
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -290,6 +291,150 @@ __global__ __launch_bounds__(kBlock) void tp_gram(const DmtTableMeta* __restrict
       }
 }
 
+// The same contraction for 65 ... 256 features of dim N <= 128: one block of 16 waves stages ALL
+// features of a sample (up to 256 rows, 68 KB of LDS at N = 128), so the pooled tensor is read
+// exactly once, and its waves share out the 32 x 32 sub-tiles of the upper triangle of the
+// Gram matrix (at most 36, three per wave).  A sub-tile (r, c), r <= c, is stored like a tile
+// pair of 32-feature tiles, which is what tp_finish reads.  One block per CU; block = batch slice.
+constexpr int kWideThreads = 1024, kWideRows = 256, kWideSub = 3;
+template <int DT, int NP>
+__global__ __launch_bounds__(kWideThreads) void tp_gram_wide(
+    const DmtTableMeta* __restrict__ meta, const void* __restrict__ pooled, int64_t B, int F, int N,
+    int gt, int nsub, int64_t per, float* __restrict__ partial) {
+  constexpr int LPR = 4 * NP, RP = kWideThreads / LPR;     // NP passes cover the 256 rows
+  constexpr bool kRaw = DT != DMT_F32;
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+  __shared__ int64_t s_base[kWideRows];
+  __shared__ int32_t s_pitch[kWideRows];
+  __shared__ __attribute__((aligned(16))) float s_inv[kWideRows];
+  __shared__ uint8_t s_r[36], s_c[36];
+  const int npad = (N + 15) & ~15, ldx = npad + 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid < kWideRows) {
+    int64_t base = 0;
+    int32_t pitch = 0;
+    if (tid < F) {
+      const DmtTableMeta m = meta[tid];
+      base = m.out_prefix * B + m.col_off;
+      pitch = m.tower_width;
+    }
+    s_base[tid] = base;
+    s_pitch[tid] = pitch;
+  }
+  if (tid < nsub) {
+    int r = 0;
+    while (r + 1 < gt && tp_pair_index(r + 1, r + 1, gt) <= tid) ++r;
+    s_r[tid] = (uint8_t)r;
+    s_c[tid] = (uint8_t)(r + (tid - tp_pair_index(r, r, gt)));
+  }
+  __syncthreads();
+
+  const int chunk = tid % LPR, row0 = tid / LPR;
+  const bool cin = chunk * 8 < N;
+  floatx16 total[kWideSub];
+  int oa[kWideSub], ob[kWideSub], ir_off[kWideSub], ic_off[kWideSub];   // LDS element offsets
+#pragma unroll
+  for (int q = 0; q < kWideSub; ++q) {
+    const int sub = wave + 16 * q;
+    const int r = sub < nsub ? s_r[sub] : 0, c = sub < nsub ? s_c[sub] : 0;
+    oa[q] = (32 * r + (lane & 31)) * ldx + (lane >> 5) * 8;
+    ob[q] = (32 * c + (lane & 31)) * ldx + (lane >> 5) * 8;
+    ir_off[q] = 32 * r + (lane >> 5) * 4;
+    ic_off[q] = 32 * c + (lane & 31);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) total[q][v] = 0.f;
+  }
+
+  Raw8<DT> raw[NP];
+  auto fetch = [&](int64_t b) __attribute__((always_inline)) {
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      const int row = p * RP + row0;
+      if (cin && row < F) {
+        raw[p] = fetch8<DT>(pooled, s_base[row] + b * s_pitch[row] + chunk * 8);
+      } else {
+#pragma unroll
+        for (int q = 0; q < (DT == DMT_F32 ? 2 : 1); ++q) raw[p].v[q] = make_uint4(0, 0, 0, 0);
+      }
+    }
+  };
+  auto commit = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      const int row = p * RP + row0;
+      if constexpr (kRaw) {
+        const uint4 r = raw[p].v[0];
+        const float ss = row_group_sum<LPR>(sumsq8<DT>(r));
+        if (chunk * 8 < npad) *(uint4*)(lds + row * ldx + chunk * 8) = r;
+        if (chunk == 0) s_inv[row] = ss > 0.f ? __builtin_amdgcn_rsqf(ss) : 0.f;
+      } else {
+        float x[8];
+        decode8<DT>(raw[p], x);
+        float ss = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) ss += x[q] * x[q];
+        ss = row_group_sum<LPR>(ss);
+        const float inv = ss > 0.f ? __builtin_amdgcn_rsqf(ss) : 0.f;
+        if (chunk * 8 < npad) {
+          *(uint4*)(lds + row * ldx + chunk * 8) =
+              make_uint4(dmt::pack2<DMT_F16>(x[0] * inv, x[1] * inv),
+                         dmt::pack2<DMT_F16>(x[2] * inv, x[3] * inv),
+                         dmt::pack2<DMT_F16>(x[4] * inv, x[5] * inv),
+                         dmt::pack2<DMT_F16>(x[6] * inv, x[7] * inv));
+        }
+        if (chunk == 0) s_inv[row] = 1.0f;
+      }
+    }
+  };
+
+  const int64_t b_begin = blockIdx.x * per, b_end = b_begin + per < B ? b_begin + per : B;
+  if (b_begin < b_end) fetch(b_begin);
+  for (int64_t b = b_begin; b < b_end; ++b) {
+    __syncthreads();                         // the previous sample's rows have been consumed
+    commit();
+    __syncthreads();
+    if (b + 1 < b_end) fetch(b + 1);
+#pragma unroll
+    for (int q = 0; q < kWideSub; ++q) {
+      if (wave + 16 * q < nsub) {            // uniform over the wave
+        floatx16 acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+        for (int k = 0; k < npad; k += 16) {
+          const uint4 a = *(const uint4*)(lds + oa[q] + k);
+          const uint4 c = *(const uint4*)(lds + ob[q] + k);
+          if constexpr (DT == DMT_BF16)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                          __builtin_bit_cast(bf16x8, c), acc, 0, 0, 0);
+          else
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8, a),
+                                                         __builtin_bit_cast(halfx8, c), acc, 0, 0, 0);
+        }
+        const float ic = s_inv[ic_off[q]];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float4 ir = *(const float4*)(s_inv + ir_off[q] + j * 8);
+          total[q][4 * j + 0] += acc[4 * j + 0] * (ir.x * ic);
+          total[q][4 * j + 1] += acc[4 * j + 1] * (ir.y * ic);
+          total[q][4 * j + 2] += acc[4 * j + 2] * (ir.z * ic);
+          total[q][4 * j + 3] += acc[4 * j + 3] * (ir.w * ic);
+        }
+      }
+    }
+  }
+
+#pragma unroll
+  for (int q = 0; q < kWideSub; ++q) {
+    const int sub = wave + 16 * q;
+    if (sub < nsub) {
+      float* out = partial + ((int64_t)blockIdx.x * nsub + sub) * (32 * 32);
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        out[((v >> 2) * 8 + (lane >> 5) * 4 + (v & 3)) * 32 + (lane & 31)] = total[q][v];
+    }
+  }
+}
+
 // I[i][j] = | sum over the batch slices of the Gram entry | / B.  Entry (i, j) and (j, i) are
 // both read from the tile element (min, max), so the result is exactly symmetric.  A block
 // takes 16 consecutive entries; its 16 thread groups each add up every 16th slice, then the
@@ -324,31 +469,44 @@ __global__ __launch_bounds__(kBlock) void tp_finish(const float* __restrict__ pa
 
 struct TpShape {
   int N, np, tile, nt, npairs;             // np: staging passes per 64 rows (4 np lanes per row)
+  bool wide;                               // tp_gram_wide: all features in one block
   int64_t per, nslices;
   size_t bytes;
 };
 
 // Every table must have the same embedding dim (the cosine kernel pairs any two features), a
-// multiple of 8 up to 512, so that rows split into aligned 8-element chunks.
-dmt_status tp_shape(const dmt_plan* p, int64_t B, TpShape& s) {
+// multiple of 8 up to 512, so that rows split into aligned 8-element chunks.  `rows16`: the
+// pooled tensor holds 16-bit elements (float32 rows take the tile-pair kernel: staged, they
+// need more registers than a 16-wave block has).
+dmt_status tp_shape(const dmt_plan* p, int64_t B, bool rows16, TpShape& s) {
   if (p->classes.size() != 1) return DMT_ENOTSUP;
   s.N = p->classes[0].D;
   if (s.N % 8 != 0 || s.N > 512) return DMT_ENOTSUP;
   for (const DmtTableMeta& m : p->meta)
     if (m.col_off % 8 != 0 || m.tower_width % 8 != 0) return DMT_ENOTSUP;
   s.np = s.N <= 32 ? 1 : s.N <= 64 ? 2 : s.N <= 128 ? 4 : s.N <= 256 ? 8 : 16;
-  // 64-feature tiles.  (The kernel also runs with TF = 128, which re-reads the pooled rows less
-  // when there are more than 64 features, but measured slower on MI355X: 0.76 ms against 0.66 ms
-  // at F = 256, N = 128, B = 16384.  Its larger register and LDS footprint halves the resident
-  // blocks, and the loads in flight with them.)
-  s.tile = kTile;
-  s.nt = (p->F + s.tile - 1) / s.tile;
-  s.npairs = s.nt * (s.nt + 1) / 2;
-  // one round of resident blocks for a single pair; two when diagonal pairs (one tile to stage)
-  // and off-diagonal pairs (two) share the launch, so that the uneven blocks even out
-  const int64_t want = std::max<int64_t>(1, (s.npairs > 1 ? 2 : 1) * kTargetBlocks / s.npairs);
-  s.per = (B + want - 1) / want;
-  s.nslices = (B + s.per - 1) / s.per;
+  if (rows16 && p->F > kTile && p->F <= kWideRows && s.np <= 4) {
+    // one block per CU stages all features of a sample; "tiles" are its 32 x 32 sub-tiles
+    s.wide = true;
+    s.tile = 32;
+    s.nt = (p->F + 31) / 32;
+    s.npairs = s.nt * (s.nt + 1) / 2;
+    s.per = (B + kWideBlocks - 1) / kWideBlocks;
+    s.nslices = (B + s.per - 1) / s.per;
+  } else {
+    // tile pairs of 64 features.  (tp_gram also runs with TF = 128, which re-reads the pooled
+    // rows less, but measured slower on MI355X: its larger register and LDS footprint halves
+    // the resident blocks, and the loads in flight with them.)
+    s.wide = false;
+    s.tile = kTile;
+    s.nt = (p->F + s.tile - 1) / s.tile;
+    s.npairs = s.nt * (s.nt + 1) / 2;
+    // one round of resident blocks for a single pair; two when diagonal pairs (one tile to
+    // stage) and off-diagonal pairs (two) share the launch, so that the uneven blocks even out
+    const int64_t want = std::max<int64_t>(1, (s.npairs > 1 ? 2 : 1) * kTargetBlocks / s.npairs);
+    s.per = (B + want - 1) / want;
+    s.nslices = (B + s.per - 1) / s.per;
+  }
   s.bytes = sizeof(float) * (size_t)s.nslices * s.npairs * s.tile * s.tile;
   return DMT_OK;
 }
@@ -370,9 +528,33 @@ void launch_gram(const dmt_plan* p, const void* pooled, int64_t B, const TpShape
                      pooled, B, p->F, sh.N, sh.nt, sh.npairs, sh.per, sh.nslices, partial);
 }
 
+template <int DT, int NP>
+void launch_gram_wide(const dmt_plan* p, const void* pooled, int64_t B, const TpShape& sh,
+                      float* partial, hipStream_t s) {
+  const int npad = (sh.N + 15) & ~15;
+  const size_t lds = sizeof(uint16_t) * kWideRows * (npad + 8);
+  static bool configured = false;
+  if (!configured) {
+    (void)hipFuncSetAttribute((const void*)tp_gram_wide<DT, NP>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)(sizeof(uint16_t) * kWideRows * (NP * 32 + 8)));
+    configured = true;
+  }
+  hipLaunchKernelGGL((tp_gram_wide<DT, NP>), dim3((unsigned)sh.nslices), dim3(kWideThreads), lds, s,
+                     p->d_meta, pooled, B, p->F, sh.N, sh.nt, sh.npairs, sh.per, partial);
+}
+
 template <int DT>
 void launch_gram_dt(const dmt_plan* p, const void* pooled, int64_t B, const TpShape& sh,
                     float* partial, hipStream_t s) {
+  if constexpr (DT != DMT_F32) {
+    if (sh.wide) {
+      if (sh.np == 1) launch_gram_wide<DT, 1>(p, pooled, B, sh, partial, s);
+      else if (sh.np == 2) launch_gram_wide<DT, 2>(p, pooled, B, sh, partial, s);
+      else launch_gram_wide<DT, 4>(p, pooled, B, sh, partial, s);
+      return;
+    }
+  }
   if (sh.np == 1) launch_gram<DT, 1, kTile>(p, pooled, B, sh, partial, s);
   else if (sh.np == 2) launch_gram<DT, 2, kTile>(p, pooled, B, sh, partial, s);
   else if (sh.np == 4) launch_gram<DT, 4, kTile>(p, pooled, B, sh, partial, s);
@@ -429,9 +611,10 @@ void size_bounds(int F, int T, double R, int& smin, int& smax) {
 }  // namespace
 
 extern "C" size_t dmt_tp_workspace_bytes(const dmt_plan* plan, int64_t B) {
-  TpShape sh;
-  if (!plan || B <= 0 || tp_shape(plan, B, sh) != DMT_OK) return 0;
-  return sh.bytes;
+  TpShape a, b;                             // enough for a pooled tensor of any dtype
+  if (!plan || B <= 0 || tp_shape(plan, B, true, a) != DMT_OK || tp_shape(plan, B, false, b) != DMT_OK)
+    return 0;
+  return std::max(a.bytes, b.bytes);
 }
 
 extern "C" dmt_status dmt_tp_interaction(const dmt_plan* plan, const void* pooled, int64_t B,
@@ -444,7 +627,7 @@ extern "C" dmt_status dmt_tp_interaction(const dmt_plan* plan, const void* poole
   if (((uintptr_t)pooled & 15) || ((uintptr_t)workspace & 15) || ((uintptr_t)interaction & 3))
     return DMT_EINVAL;
   TpShape sh;
-  const dmt_status st = tp_shape(plan, B, sh);
+  const dmt_status st = tp_shape(plan, B, pooled_dtype != DMT_F32, sh);
   if (st != DMT_OK) return st;
   if (workspace_bytes < sh.bytes) return DMT_ENOMEM;
   hipStream_t s = (hipStream_t)stream;

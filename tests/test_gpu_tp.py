@@ -78,9 +78,11 @@ def _check(I, ref, what, dtype="f32"):
     (4, 512, 9, 2, "bf16", None),             # the widest 16-bit rows
     (12, 24, 33, 1, "bf16", None),            # N not a multiple of the MFMA's K step
     (64, 128, 2500, 8, "f16", None),          # more samples than batch slices
-    (200, 128, 40, 4, "bf16", None),          # 128-feature tiles: two tiles, three pairs
-    (300, 64, 21, 5, "f32", None),            # 128-feature tiles on float32 rows, ragged third tile
-    (70, 128, 30, 2, "f32", None),            # float32 rows too wide for them: 64-feature tiles
+    (200, 128, 40, 4, "bf16", None),          # 65 ... 256 16-bit features: one block stages them all
+    (256, 128, 300, 16, "bf16", None),        # ... all 36 sub-tiles, Large's feature shape
+    (65, 8, 19, 1, "f16", None),              # ... one row into the third 32-row group
+    (300, 64, 21, 5, "bf16", None),           # more than 256 features: tile pairs again
+    (70, 128, 30, 2, "f32", None),            # float32 rows: tile pairs, ragged second tile
 ])
 def test_interaction_matches_the_oracle(F, N, B, T, dtype, sizes):
     w = _workload(F, N, T, B, dtype, sizes)
