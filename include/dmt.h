@@ -371,7 +371,8 @@ dmt_status dmt_tp_embed(const float* interaction, int32_t F, dmt_tp_strategy str
  *   centres0        host, float64 [T][n], the start centres (supplied by the caller)
  *   table_to_tower  host out, int32 [F]: group of each feature, usable as dmt_plan_create's map
  *   centres         host out [T][n] or NULL;  iterations  host out or NULL
- * DMT_EINVAL unless 1 <= T <= F, ratio >= 1, max_iter >= 1.
+ * DMT_EINVAL unless 1 <= T <= F, ratio >= 1, max_iter >= 1; DMT_ENOTSUP when T times the
+ * upper size bound exceeds 4096 (the assignment step is cubic in it).
  */
 dmt_status dmt_tp_kmeans(const double* x, int32_t F, int32_t n, int32_t T, double ratio,
                          const double* centres0, int32_t max_iter, int32_t* table_to_tower,

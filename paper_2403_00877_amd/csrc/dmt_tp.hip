@@ -717,7 +717,7 @@ extern "C" dmt_status dmt_tp_kmeans(const double* x, int32_t F, int32_t n, int32
   int smin, smax;
   size_bounds(F, T, ratio, smin, smax);
   const int ns = T * smax;                  // slots = rows of the square problem
-  if ((int64_t)ns * ns > ((int64_t)1 << 26)) return DMT_ENOTSUP;
+  if (ns > 4096) return DMT_ENOTSUP;         // the O(ns^3) assignment is meant for |F| in the hundreds
   std::vector<double> C(centres0, centres0 + (size_t)T * n), d2((size_t)F * T), cost((size_t)ns * ns);
   std::vector<int> col, labels(F, -1), now(F), count(T);
   int it = 0;
