@@ -9,7 +9,9 @@
 //                       registers over its slice of the batch; a second kernel sums the slices
 //                       in a fixed order, divides by B and takes the absolute value.  At
 //                       F = 64 the contraction is 64 FLOP per byte read, so the kernel is bound
-//                       by reading the pooled tensor.
+//                       by reading the pooled tensor.  With 65 ... 256 features a 16-wave block
+//                       stages all of them, so that the tensor is still read only once
+//                       (tp_gram_wide); beyond that, pairs of 64-feature tiles.
 //   dmt_tp_embed        host, float64: D = f(I), then Adam on the pairwise-distance objective.
 //   dmt_tp_kmeans       host, float64: constrained K-means; the assignment step is solved
 //                       exactly as a square assignment problem over (group, slot) pairs.
