@@ -1,0 +1,73 @@
+"""Pins of the SPTT shuffle oracle (oracle/sptt.py; paper Sec. 3.1.1): the paper's example, hand
+cases on labelled blocks, and the whole transform on a simulated cluster against the definition
+of the lookup it must not change."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import sptt
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def test_peer_order_of_the_papers_example():
+    rows = [[int(x) for x in l.split()] for l in open(os.path.join(GOLD, "peer_order_example.txt"))
+            if l.strip() and not l.startswith("#")]
+    for G, L, *order in rows:
+        assert sptt.peer_order(G, L) == order
+    assert sptt.peer_order(4, 2) == [0, 2, 1, 3]
+
+
+def test_peer_order_groups_peers_by_host():
+    for G, L in ((8, 4), (8, 2), (16, 8), (6, 3), (5, 1), (4, 4)):
+        T = G // L
+        order = sptt.peer_order(G, L)
+        assert sorted(order) == list(range(G))
+        for l in range(L):
+            group = order[l * T:(l + 1) * T]
+            assert group == sptt.peers(l, G, L)              # one peer group, ascending host
+            assert [g // L for g in group] == list(range(T))
+    # the key as printed, (g % T, g // L), does not do that once T != L
+    printed = sorted(range(8), key=lambda g: (g % 2, g // 4))
+    assert printed[:2] != sptt.peers(0, 8, 4)
+    with pytest.raises(ValueError):
+        sptt.peer_order(6, 4)
+
+
+def test_peer_permute_and_shuffle_on_labelled_blocks():
+    # block (f, g) holds the value 10 f + g
+    F, G, L = 2, 4, 2
+    x = (10 * np.arange(F)[:, None] + np.arange(G)[None, :]).astype(np.float64)[:, :, None]
+    y = sptt.peer_permute(x, L)
+    assert y[:, :, 0].tolist() == [[0, 2, 1, 3], [10, 12, 11, 13]]
+    z = (10 * np.arange(3)[:, None] + np.arange(2)[None, :]).astype(np.float64)[:, :, None]   # (features, peers)
+    s = sptt.shuffle(z)
+    assert s.shape == (2, 3, 1)
+    assert s[:, :, 0].tolist() == [[0, 10, 20], [1, 11, 21]]
+    assert s.reshape(-1).tolist() == [0, 10, 20, 1, 11, 21]      # flattened (peers x features)
+
+
+@pytest.mark.parametrize("T,L,per_tower", [(2, 2, [1, 1]), (2, 2, [2, 2]), (2, 4, [5, 4]), (3, 2, [2, 3, 1]),
+                                           (4, 1, [2, 2, 2, 2]), (1, 4, [6])])
+def test_the_transform_keeps_the_lookup(T, L, per_tower):
+    """After steps a-f every GPU holds, per tower, the pooled embeddings of that tower's features
+    for its own samples: exactly what the plain lookup gives."""
+    rng = np.random.default_rng(T * 10 + L)
+    B_l, N = 3, 4
+    G = T * L
+    F = sum(per_tower)
+    ids = list(rng.permutation(F))                  # towers own arbitrary table ids
+    tower_tables, k = [], 0
+    for n in per_tower:
+        tower_tables.append([int(f) for f in ids[k:k + n]])
+        k += n
+    truth = rng.normal(size=(F, G * B_l, N))        # pooled embedding of table f for every global sample
+    out = sptt.simulate(lambda f, lo, hi: truth[f, lo:hi], tower_tables, L, B_l)
+    assert len(out) == G
+    for g in range(G):
+        for t in range(T):
+            got = out[g][t]
+            assert got.shape == (per_tower[t], B_l, N)
+            for i, f in enumerate(tower_tables[t]):
+                np.testing.assert_array_equal(got[i], truth[f, g * B_l:(g + 1) * B_l])
