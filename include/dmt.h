@@ -379,6 +379,30 @@ dmt_status dmt_tp_kmeans(const double* x, int32_t F, int32_t n, int32_t T, doubl
                          double* centres, int32_t* iterations);
 
 /*
+ * SPTT's data-shuffle steps inside one GPU's memory (paper Sec. 3.1.1, steps c and e), in
+ * their explicit form.  (The training step above does not need them: dmt_tower_lookup_fwd
+ * already stores in the layout they lead to.  They serve a deployment in which step d's
+ * intra-host exchange runs between them.)  G ranks, L per host, T = G / L hosts.  A block is
+ * `block_bytes` contiguous bytes (a multiple of 16): the embeddings of one feature for one
+ * rank's samples.  `in` and `out` are dev, 16-byte aligned, distinct buffers of equal size.
+ *
+ * Peer order: all ranks sorted by (g % L, g / L), so that peers (ranks with equal g % L) are
+ * adjacent and ordered by host; G = 4, L = 2 gives (0, 2, 1, 3).  (The walk-through prints the
+ * key (g % T, g / L), which equals this one in its example, T = L = 2, and fails to bring
+ * peers together otherwise.)  order: host out [G], order[k] = rank at position k.
+ */
+dmt_status dmt_sptt_peer_order(int32_t G, int32_t L, int32_t* order);
+
+/* Step c, peer permute: in [features][G][block] in rank order -> out[f][k] = in[f][order[k]]. */
+dmt_status dmt_sptt_peer_permute(const void* in, void* out, int64_t features, int32_t G, int32_t L,
+                                 int64_t block_bytes, void* stream);
+
+/* Step e: in [features][peers][block] -> out [peers][features][block], i.e. the 2-D arrangement
+ * (features, peers) transposed and flattened as (peers x features). */
+dmt_status dmt_sptt_shuffle(const void* in, void* out, int64_t features, int64_t peers,
+                            int64_t block_bytes, void* stream);
+
+/*
  * Synchronise `stream` and report whether any kernel since the last call saw an
  * id outside its table: DMT_EBOUNDS with *bad_position = smallest offending
  * position in `indices`, else DMT_OK with *bad_position = -1.  Clears the record.

@@ -93,6 +93,9 @@ def _load() -> ctypes.CDLL:
     lib.dmt_tp_interaction.argtypes = [vp, vp, i64, ctypes.c_int, vp, vp, sz, vp]
     lib.dmt_tp_embed.argtypes = [vp, i32, ctypes.c_int, i32, i32, f64, vp, vp, ctypes.POINTER(f64)]
     lib.dmt_tp_kmeans.argtypes = [vp, i32, i32, i32, f64, vp, i32, vp, vp, ctypes.POINTER(i32)]
+    lib.dmt_sptt_peer_order.argtypes = [i32, i32, vp]
+    lib.dmt_sptt_peer_permute.argtypes = [vp, vp, i64, i32, i32, i64, vp]
+    lib.dmt_sptt_shuffle.argtypes = [vp, vp, i64, i64, i64, vp]
     return lib
 
 
@@ -105,7 +108,8 @@ EXPORTS = ["dmt_status_str", "dmt_plan_create", "dmt_plan_destroy", "dmt_plan_la
            "dmt_bwd_workspace_bytes", "dmt_tower_lookup_bwd_update",
            "dmt_last_device_error", "dmt_kernel_name", "dmt_profile_enable", "dmt_profile_read",
            "dmt_calibration_copy", "dmt_tp_workspace_bytes", "dmt_tp_interaction",
-           "dmt_tp_embed", "dmt_tp_kmeans"]
+           "dmt_tp_embed", "dmt_tp_kmeans", "dmt_sptt_peer_order", "dmt_sptt_peer_permute",
+           "dmt_sptt_shuffle"]
 
 DMT_K_COUNT = 15
 TP_STRATEGY_CODE = {"diverse": 0, "coherent": 1}
@@ -368,3 +372,23 @@ def dmt_tp_kmeans(x, T: int, ratio: float, centres0, max_iter: int = 100):
         x.ctypes.data, F, n, T, ratio, c0.ctypes.data, max_iter, labels.ctypes.data,
         centres.ctypes.data, ctypes.byref(it)))
     return labels, centres, int(it.value)
+
+
+def dmt_sptt_peer_order(G: int, L: int) -> List[int]:
+    order = (ctypes.c_int32 * max(G, 1))()
+    _check("dmt_sptt_peer_order", _lib.dmt_sptt_peer_order(G, L, order))
+    return list(order)
+
+
+def dmt_sptt_peer_permute(inp: torch.Tensor, out: torch.Tensor, features: int, G: int, L: int,
+                          block_bytes: int, stream=None) -> None:
+    assert _nbytes(inp) >= features * G * block_bytes and _nbytes(out) >= features * G * block_bytes
+    _check("dmt_sptt_peer_permute", _lib.dmt_sptt_peer_permute(
+        _ptr(inp), _ptr(out), features, G, L, block_bytes, _stream(stream)))
+
+
+def dmt_sptt_shuffle(inp: torch.Tensor, out: torch.Tensor, features: int, peers: int,
+                     block_bytes: int, stream=None) -> None:
+    assert _nbytes(inp) >= features * peers * block_bytes and _nbytes(out) >= features * peers * block_bytes
+    _check("dmt_sptt_shuffle", _lib.dmt_sptt_shuffle(
+        _ptr(inp), _ptr(out), features, peers, block_bytes, _stream(stream)))

@@ -171,3 +171,13 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
                        capture_output=True, text=True)
     assert r.returncode != 0 and "ONE GPU" in r.stderr
+
+
+def test_sptt_peer_order_matches_the_papers_example_and_the_oracle():
+    from oracle import sptt
+    assert dmt.dmt_sptt_peer_order(4, 2) == [0, 2, 1, 3]          # Sec. 3.1.1's example
+    for G, L in ((8, 4), (8, 2), (16, 8), (6, 3), (5, 1), (4, 4), (1, 1)):
+        assert dmt.dmt_sptt_peer_order(G, L) == sptt.peer_order(G, L)
+    order = (ctypes.c_int32 * 8)()
+    raw = dmt.binding._lib.dmt_sptt_peer_order
+    assert raw(8, 3, order) == 1 and raw(0, 1, order) == 1 and raw(8, 0, order) == 1 and raw(8, 2, None) == 1
