@@ -205,6 +205,9 @@ def main():
         tp_out = time_tower_partitioner(torch, dmt, wl, w, plan, pooled, B, args.steps,
                                         with_oracle=default and not args.no_cpu)
 
+    # ---- SPTT's explicit shuffle steps on a buffer the size of the pooled tensor (not part of `value`)
+    sptt_out = None if args.no_tp else time_sptt_shuffles(torch, dmt, pooled, F, args.steps)
+
     if args.calibrate:
         a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         c = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
@@ -302,9 +305,38 @@ def main():
         "parity_vs_oracle_on_sample": cpu["parity"] if cpu else None,
         "tm_backward": tm_bwd,
         "tower_partitioner": tp_out,
+        "sptt_shuffle_steps": sptt_out,
     }
     print(json.dumps(out), flush=True)
     return 0
+
+
+def time_sptt_shuffles(torch, dmt, pooled, F, steps, G=8, L=4):
+    """Steps c and e of Sec. 3.1.1 in their explicit form, on a buffer of the pooled tensor's size
+    read as [features][G ranks][block] resp. [features][peers][block]: pure data movement, timed by
+    events on the launch stream against the HBM peak (bytes read + bytes written)."""
+    nbytes = pooled.numel() * pooled.element_size()
+    if nbytes % (F * G * 16) != 0:
+        return None
+    block = nbytes // (F * G)
+    src = pooled.view(torch.uint8)
+    dst = torch.empty_like(src)
+    out = dict(features=F, ranks=G, per_host=L, block_bytes=block, bytes_moved=2 * nbytes)
+    for name, call in (("peer_permute", lambda: dmt.dmt_sptt_peer_permute(src, dst, F, G, L, block)),
+                       ("shuffle", lambda: dmt.dmt_sptt_shuffle(src, dst, F, G, block))):
+        for _ in range(3):
+            call()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(steps):
+            call()
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / steps
+        g = 2 * nbytes / (ms * 1e-3) / 1e9
+        out[name] = dict(ms=round(ms, 4), bound="hbm", achieved=round(g, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                         frac=round(g / HBM_PEAK_GBS, 4))
+    return out
 
 
 def time_tower_partitioner(torch, dmt, wl, w, plan, pooled, B, steps, with_oracle):
