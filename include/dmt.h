@@ -22,6 +22,8 @@
  *                                embeddings (device)
  *   dmt_tp_embed, dmt_tp_kmeans  distance embedding by Adam and constrained
  *                                K-means (host; they touch |F| x |F| numbers)
+ * and SPTT's data-shuffle steps c and e in explicit form (paper Sec. 3.1.1):
+ *   dmt_sptt_peer_permute, dmt_sptt_shuffle   block transposes in device memory
  *
  * Conventions
  *  - C linkage, no exceptions cross the boundary; every call returns dmt_status.

@@ -49,14 +49,20 @@ __host__ __device__ inline int tp_pair_index(int ti, int tj, int nt) {   // ti <
 // two of float32.
 template <int DT> struct Raw8 { uint4 v[DT == DMT_F32 ? 2 : 1]; };
 
-template <int DT>
+// NT: the tensor is larger than the caches and read once (nontemporal loads keep it from
+// sweeping them); a tensor the lookup has just written is better taken from the caches.
+template <int DT, bool NT>
 __device__ __forceinline__ Raw8<DT> fetch8(const void* base, int64_t off) {
   Raw8<DT> r;
+  auto ld = [](const uint4* p) __attribute__((always_inline)) {
+    if constexpr (NT) return dmt::nt_load(p);
+    else return dmt::gload(p);
+  };
   if constexpr (DT == DMT_F32) {
-    r.v[0] = dmt::gload((const uint4*)((const float*)base + off));
-    r.v[1] = dmt::gload((const uint4*)((const float*)base + off) + 1);
+    r.v[0] = ld((const uint4*)((const float*)base + off));
+    r.v[1] = ld((const uint4*)((const float*)base + off) + 1);
   } else {
-    r.v[0] = dmt::gload((const uint4*)((const uint16_t*)base + off));
+    r.v[0] = ld((const uint4*)((const uint16_t*)base + off));
   }
   return r;
 }
@@ -186,7 +192,7 @@ __global__ __launch_bounds__(kBlock) void tp_gram(const DmtTableMeta* __restrict
       const int row = p * RP + row0;
       const int f = (which ? tj : ti) * TF + row;
       if (cin && f < F) {
-        raw[which][p] = fetch8<DT>(
+        raw[which][p] = fetch8<DT, false>(
             pooled, s_base[which * TF + row] + b * s_pitch[which * TF + row] + chunk * 8);
       } else {
 #pragma unroll
@@ -353,7 +359,7 @@ __global__ __launch_bounds__(kWideThreads) void tp_gram_wide(
     for (int p = 0; p < NP; ++p) {
       const int row = p * RP + row0;
       if (cin && row < F) {
-        raw[p] = fetch8<DT>(pooled, s_base[row] + b * s_pitch[row] + chunk * 8);
+        raw[p] = fetch8<DT, true>(pooled, s_base[row] + b * s_pitch[row] + chunk * 8);
       } else {
 #pragma unroll
         for (int q = 0; q < (DT == DMT_F32 ? 2 : 1); ++q) raw[p].v[q] = make_uint4(0, 0, 0, 0);
