@@ -24,6 +24,7 @@ def _blocks(rng, shape, dtype):
     (2, 8, 1, 7, 8, np.uint16),        # one GPU per host: peer order = rank order
     (2, 8, 8, 7, 8, np.uint16),        # one host: peer order = rank order as well
     (1, 2, 2, 4097, 128, np.uint16),   # blocks longer than one workgroup pass, ragged tail
+    (64, 8, 4, 1024, 128, np.uint16),  # the size bench.py times: Mid's pooled tensor, 134 MB
 ])
 def test_peer_permute_matches_the_oracle(F, G, L, Bl, N, dtype):
     rng = np.random.default_rng(F * 100 + G)
@@ -40,7 +41,8 @@ def test_peer_permute_matches_the_oracle(F, G, L, Bl, N, dtype):
 
 @pytest.mark.parametrize("F,P,Bl,N,dtype", [(1, 1, 2, 8, np.uint16), (8, 2, 129, 128, np.uint16),
                                             (16, 16, 33, 64, np.uint16), (3, 5, 1, 4, np.float32),
-                                            (2, 3, 2049, 128, np.float32)])
+                                            (2, 3, 2049, 128, np.float32),
+                                            (64, 8, 1024, 128, np.uint16)])      # 134 MB, as bench.py times it
 def test_shuffle_matches_the_oracle(F, P, Bl, N, dtype):
     rng = np.random.default_rng(F * 100 + P)
     z = _blocks(rng, (F, P, Bl, N), dtype)
