@@ -70,6 +70,8 @@ def _check(I, ref, what, dtype="f32"):
 
 @pytest.mark.parametrize("F,N,B,T,dtype,sizes", [
     (5, 8, 37, 1, "f32", None),
+    (1, 16, 5, 1, "f32", None),               # a single feature: I = [[1]]
+    (2, 8, 3, 2, "bf16", None),               # one feature per tower, the narrowest rows
     (64, 128, 300, 1, "bf16", None),          # one full tile, Mid's feature shape
     (70, 64, 129, 3, "f16", [30, 5, 35]),     # ragged second tile, towers of unequal width
     (130, 32, 50, 2, "bf16", None),           # three tiles: six tile pairs
