@@ -22,6 +22,7 @@
 
 #include <algorithm>
 #include <limits>
+#include <new>
 #include <type_traits>
 #include <vector>
 
@@ -656,9 +657,9 @@ extern "C" dmt_status dmt_tp_interaction(const dmt_plan* plan, const void* poole
   return hipGetLastError() == hipSuccess ? DMT_OK : DMT_EHIP;
 }
 
-extern "C" dmt_status dmt_tp_embed(const float* interaction, int32_t F, dmt_tp_strategy strategy,
-                                   int32_t n, int32_t steps, double lr, const double* x0,
-                                   double* x, double* stress) {
+static dmt_status tp_embed(const float* interaction, int32_t F, dmt_tp_strategy strategy,
+                           int32_t n, int32_t steps, double lr, const double* x0, double* x,
+                           double* stress) {
   if (!interaction || !x0 || !x || F <= 0 || n <= 0 || steps < 0 || !(lr > 0.0)) return DMT_EINVAL;
   if (strategy != DMT_TP_DIVERSE && strategy != DMT_TP_COHERENT) return DMT_EINVAL;
   const double beta1 = 0.9, beta2 = 0.999, eps = 1e-8;
@@ -716,10 +717,20 @@ extern "C" dmt_status dmt_tp_embed(const float* interaction, int32_t F, dmt_tp_s
   return DMT_OK;
 }
 
-extern "C" dmt_status dmt_tp_kmeans(const double* x, int32_t F, int32_t n, int32_t T,
-                                    double ratio, const double* centres0, int32_t max_iter,
-                                    int32_t* table_to_tower, double* centres,
-                                    int32_t* iterations) {
+// No exception crosses the C boundary: a failed host allocation is reported as DMT_ENOMEM.
+extern "C" dmt_status dmt_tp_embed(const float* interaction, int32_t F, dmt_tp_strategy strategy,
+                                   int32_t n, int32_t steps, double lr, const double* x0,
+                                   double* x, double* stress) {
+  try {
+    return tp_embed(interaction, F, strategy, n, steps, lr, x0, x, stress);
+  } catch (const std::bad_alloc&) {
+    return DMT_ENOMEM;
+  }
+}
+
+static dmt_status tp_kmeans(const double* x, int32_t F, int32_t n, int32_t T, double ratio,
+                            const double* centres0, int32_t max_iter, int32_t* table_to_tower,
+                            double* centres, int32_t* iterations) {
   if (!x || !centres0 || !table_to_tower || F <= 0 || n <= 0 || T <= 0 || T > F) return DMT_EINVAL;
   if (!(ratio >= 1.0) || max_iter <= 0) return DMT_EINVAL;
   int smin, smax;
@@ -767,4 +778,15 @@ extern "C" dmt_status dmt_tp_kmeans(const double* x, int32_t F, int32_t n, int32
   if (centres) std::copy(C.begin(), C.end(), centres);
   if (iterations) *iterations = it;
   return DMT_OK;
+}
+
+extern "C" dmt_status dmt_tp_kmeans(const double* x, int32_t F, int32_t n, int32_t T,
+                                    double ratio, const double* centres0, int32_t max_iter,
+                                    int32_t* table_to_tower, double* centres,
+                                    int32_t* iterations) {
+  try {
+    return tp_kmeans(x, F, n, T, ratio, centres0, max_iter, table_to_tower, centres, iterations);
+  } catch (const std::bad_alloc&) {
+    return DMT_ENOMEM;
+  }
 }
