@@ -106,3 +106,24 @@ def simulate(pooled_of, tower_tables: Sequence[Sequence[int]], L: int, B_l: int)
         t, l = divmod(r, L)
         out.append([shuffled[src_host * L + l][t] for src_host in range(T)])
     return out
+
+
+# ------------------------------------------------------------------ row-wise sharded tables
+
+def row_shard_lookups(indices, offsets, F: int, B: int, row_begin: Sequence[int],
+                      rows: Sequence[int]):
+    """The lookups of a batch that fall into one row-wise shard (Sec. 3.1.3: a table too large
+    for one GPU is split by rows inside its tower; every shard pools the rows it holds and step d
+    becomes a ReduceScatter that adds the partial pools).
+
+    The shard holds rows [row_begin[f], row_begin[f] + rows[f]) of table f.  Returns the jagged
+    batch restricted to those rows, ids renumbered from the shard's first row: (indices, offsets)
+    in the same feature-major layout, the order inside every bag kept."""
+    indices = np.asarray(indices, dtype=np.int64)
+    offsets = np.asarray(offsets, dtype=np.int64)
+    table_of = np.repeat(np.arange(F), np.diff(offsets[::B]))
+    lo = np.asarray(row_begin, dtype=np.int64)[table_of]
+    hi = lo + np.asarray(rows, dtype=np.int64)[table_of]
+    keep = (indices >= lo) & (indices < hi)
+    kept_before = np.concatenate([[0], np.cumsum(keep)])
+    return (indices - lo)[keep].astype(np.int32), kept_before[offsets]

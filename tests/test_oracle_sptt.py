@@ -71,3 +71,45 @@ def test_the_transform_keeps_the_lookup(T, L, per_tower):
             assert got.shape == (per_tower[t], B_l, N)
             for i, f in enumerate(tower_tables[t]):
                 np.testing.assert_array_equal(got[i], truth[f, g * B_l:(g + 1) * B_l])
+
+
+# ------------------------------------------------------------------ row-wise shards (Sec. 3.1.3)
+
+def test_row_shard_lookups_hand_case():
+    # one table, B = 3 bags: [0 5 9] [] [4 5 5 1]; the shard holds rows 4 .. 7
+    idx = np.array([0, 5, 9, 4, 5, 5, 1], dtype=np.int32)
+    off = np.array([0, 3, 3, 7], dtype=np.int64)
+    s_idx, s_off = sptt.row_shard_lookups(idx, off, 1, 3, [4], [4])
+    assert s_idx.tolist() == [1, 0, 1, 1] and s_off.tolist() == [0, 1, 1, 4]
+    # a shard that holds everything changes nothing; one that holds nothing leaves empty bags
+    a_idx, a_off = sptt.row_shard_lookups(idx, off, 1, 3, [0], [10])
+    assert a_idx.tolist() == idx.tolist() and a_off.tolist() == off.tolist()
+    n_idx, n_off = sptt.row_shard_lookups(idx, off, 1, 3, [10], [5])
+    assert len(n_idx) == 0 and n_off.tolist() == [0, 0, 0, 0]
+
+
+def test_partial_pools_of_the_shards_add_up_to_the_lookup():
+    import oracle
+    rng = np.random.default_rng(3)
+    F, B, D = 3, 6, 4
+    rows = [11, 7, 20]
+    tables = [rng.integers(-8, 8, size=(r, D)).astype(np.float32) for r in rows]   # exact sums
+    lens = rng.integers(0, 5, size=F * B)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    idx = np.concatenate([rng.integers(0, rows[f], size=int(lens[f * B:(f + 1) * B].sum()))
+                          for f in range(F)]).astype(np.int32)
+    t2t = [0, 1, 0]
+    full = oracle.lookup_towered(tables, "f32", [D] * F, t2t, idx, off, B)
+    cuts = [[0, 4, 11], [0, 7, 7], [0, 1, 20]]          # two shards per table, one of them empty
+    total = [np.zeros_like(t) for t in full]
+    for s in range(2):
+        lo = [cuts[f][s] for f in range(F)]
+        n = [cuts[f][s + 1] - cuts[f][s] for f in range(F)]
+        shard_tables = [tables[f][lo[f]:lo[f] + n[f]] if n[f] else np.zeros((1, D), np.float32)
+                        for f in range(F)]
+        s_idx, s_off = sptt.row_shard_lookups(idx, off, F, B, lo, n)
+        part = oracle.lookup_towered(shard_tables, "f32", [D] * F, t2t, s_idx, s_off, B)
+        for t in range(2):
+            total[t] += part[t]
+    for t in range(2):
+        np.testing.assert_array_equal(total[t], full[t])
