@@ -138,6 +138,21 @@ dmt_status dmt_plan_layout(const dmt_plan* plan, int64_t B, int64_t* tower_base,
 dmt_status dmt_plan_bind(dmt_plan* plan, const void* const* tables, float* const* adagrad_state);
 
 /*
+ * Row-wise shards (paper Sec. 3.1.3: a table too large for one GPU is split by rows inside
+ * its tower, and step d becomes a ReduceScatter that adds the shards' partial pools).  After
+ * this call table f of the plan stands for rows [row_begin[f], row_begin[f] + rows[f]) of a
+ * larger table: `indices` keep carrying ids of the whole table, ids outside the local rows
+ * belong to other shards and are skipped without being reported, dmt_tower_lookup_fwd writes
+ * the PARTIAL pool of the local rows (the caller's reduction over the shards gives the pooled
+ * embedding), and dmt_tower_lookup_bwd_update updates the local rows only, each exactly as
+ * the unsharded table's row would be.
+ *   row_begin   host [num_tables], >= 0, row_begin[f] + rows[f] <= 2^31
+ * May be called before or after dmt_plan_bind (it synchronises then); not while kernels of
+ * this plan are in flight.
+ */
+dmt_status dmt_plan_set_row_shards(dmt_plan* plan, const int64_t* row_begin);
+
+/*
  * Tower-local pooled lookup, forward (paper Sec. 2.2 step b with the layout of
  * Sec. 3.1.1 steps c-e fused into the store).
  *   pooled_out[tower_base[t] + b*W_t + col_off[f] + d]

@@ -23,8 +23,12 @@ With G = 8, L = 4, T = 2 the printed key has ties and does not bring peers
 together; (g % L, g // L) does, and gives the printed order (0, 2, 1, 3) for the
 example.  That key is used here.
 
+`row_shard_lookups` covers the row-wise sharded variant of Sec. 3.1.3: the part
+of a batch's lookups one row shard of the tables serves.
+
 Pinned in tests/test_oracle_sptt.py against the paper's example, hand-labelled
-blocks, and the end-to-end simulation against the definition of the lookup.
+blocks, the end-to-end simulation against the definition of the lookup, and
+(row shards) a hand case and partial pools that add up to the lookup.
 """
 from __future__ import annotations
 
@@ -70,7 +74,6 @@ def simulate(pooled_of, tower_tables: Sequence[Sequence[int]], L: int, B_l: int)
     """
     T = len(tower_tables)
     G = T * L
-    owner = {}                                       # table -> (host, local index)
     local_tables = [[] for _ in range(G)]
     for t, fs in enumerate(tower_tables):
         for i, f in enumerate(fs):

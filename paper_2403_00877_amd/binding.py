@@ -93,6 +93,7 @@ def _load() -> ctypes.CDLL:
     lib.dmt_tp_interaction.argtypes = [vp, vp, i64, ctypes.c_int, vp, vp, sz, vp]
     lib.dmt_tp_embed.argtypes = [vp, i32, ctypes.c_int, i32, i32, f64, vp, vp, ctypes.POINTER(f64)]
     lib.dmt_tp_kmeans.argtypes = [vp, i32, i32, i32, f64, vp, i32, vp, vp, ctypes.POINTER(i32)]
+    lib.dmt_plan_set_row_shards.argtypes = [vp, vp]
     lib.dmt_sptt_peer_order.argtypes = [i32, i32, vp]
     lib.dmt_sptt_peer_permute.argtypes = [vp, vp, i64, i32, i32, i64, vp]
     lib.dmt_sptt_shuffle.argtypes = [vp, vp, i64, i64, i64, vp]
@@ -109,7 +110,7 @@ EXPORTS = ["dmt_status_str", "dmt_plan_create", "dmt_plan_destroy", "dmt_plan_la
            "dmt_last_device_error", "dmt_kernel_name", "dmt_profile_enable", "dmt_profile_read",
            "dmt_calibration_copy", "dmt_tp_workspace_bytes", "dmt_tp_interaction",
            "dmt_tp_embed", "dmt_tp_kmeans", "dmt_sptt_peer_order", "dmt_sptt_peer_permute",
-           "dmt_sptt_shuffle"]
+           "dmt_sptt_shuffle", "dmt_plan_set_row_shards"]
 
 DMT_K_COUNT = 15
 TP_STRATEGY_CODE = {"diverse": 0, "coherent": 1}
@@ -392,3 +393,9 @@ def dmt_sptt_shuffle(inp: torch.Tensor, out: torch.Tensor, features: int, peers:
     assert _nbytes(inp) >= features * peers * block_bytes and _nbytes(out) >= features * peers * block_bytes
     _check("dmt_sptt_shuffle", _lib.dmt_sptt_shuffle(
         _ptr(inp), _ptr(out), features, peers, block_bytes, _stream(stream)))
+
+
+def dmt_plan_set_row_shards(plan: dmt_plan, row_begin: Sequence[int]) -> None:
+    assert len(row_begin) == plan.num_tables
+    arr = (ctypes.c_int64 * plan.num_tables)(*[int(r) for r in row_begin])
+    _check("dmt_plan_set_row_shards", _lib.dmt_plan_set_row_shards(plan.handle, arr))

@@ -169,10 +169,11 @@ __global__ __launch_bounds__(kBlock) void bwd_build_keys(
     const uint32_t f = g / B;
     const uint64_t rows = (uint64_t)meta[f].rows;
     const uint32_t row_base = (uint32_t)meta[f].row_base;
-    const int32_t idx = indices[j];
-    uint32_t gid = row_base + (uint32_t)idx;
-    if ((uint64_t)(uint32_t)idx >= rows) {
-      atomicMin(err, (unsigned long long)j);
+    // a row-wise shard gives the ids of other shards the inert key silently (err is null then)
+    const int64_t local = (int64_t)indices[j] - meta[f].row_begin;
+    uint32_t gid = row_base + (uint32_t)local;
+    if ((uint64_t)local >= rows) {
+      if (err) atomicMin(err, (unsigned long long)j);
       gid = kInertBit | (row_base + (uint32_t)rows);
     }
     pk[j] = ((uint64_t)gid << 32) | g;
@@ -1227,7 +1228,7 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
     const int64_t key_blocks = ((int64_t)nbags + (1 << log2_bpb) - 1) >> log2_bpb;
     timed_launch(plan, DMT_K_BWD_KEYS, s, bwd_build_keys, key_blocks, kBlock, plan->d_meta, indices,
                  offsets, (uint32_t)B, nbags, nnz, (int)plan->F, w.pk_a, log2_bpb, w.seg_begin,
-                 w.seg_blk, w.blk_table, plan->d_error);
+                 w.seg_blk, w.blk_table, plan->row_shards ? nullptr : plan->d_error);
 
     // stable LSD radix sort inside every table over the bits a row id of the largest table
     // (or its one-past-the-end inert id) can set

@@ -19,6 +19,7 @@ struct DmtTableMeta {
   const void* table;     // row-major [rows][D]
   float* state;          // [rows] or null
   int64_t rows;
+  int64_t row_begin;     // id of the table's first local row (0 unless the table is a row-wise shard)
   int64_t row_base;      // global id of row 0 (prefix sum of rows over tables)
   int64_t out_prefix;    // sum of W_t' over towers before this table's tower; x B = tower base
   int32_t D;
@@ -59,6 +60,7 @@ struct dmt_plan {
   // device side (created by dmt_plan_bind)
   bool bound = false;
   bool has_state = false;
+  bool row_shards = false;                 // ids outside a table's rows belong to other shards
   DmtTableMeta* d_meta = nullptr;          // [F]
   int32_t* d_class_tables = nullptr;       // [F]
   int64_t* d_row_base = nullptr;           // [F+1]

@@ -42,7 +42,7 @@ __global__ __launch_bounds__(kBlock) void lookup_fwd_kernel(
   const int c = tile - k * tiles_per_table;
   const int f = class_tables[k];
   const char* __restrict__ tab = (const char*)meta[f].table;
-  const int64_t rows = meta[f].rows;
+  const int64_t rows = meta[f].rows, row_begin = meta[f].row_begin;
   const int64_t out_base = B * meta[f].out_prefix + meta[f].col_off;
   const int32_t tower_width = meta[f].tower_width;
   const int LPR = 1 << log2_lpr;
@@ -64,9 +64,11 @@ __global__ __launch_bounds__(kBlock) void lookup_fwd_kernel(
       const int n = min(GL, len - base);
       int my = 0;
       if (gl < n) {
-        my = indices[s + base + gl];
-        if ((unsigned)my >= (unsigned long long)rows) {
-          atomicMin(err, (unsigned long long)(s + base + gl));
+        // a row-wise shard skips the ids of other shards silently (err is null then)
+        const int64_t local = (int64_t)indices[s + base + gl] - row_begin;
+        my = (int)local;
+        if ((unsigned long long)local >= (unsigned long long)rows) {
+          if (err) atomicMin(err, (unsigned long long)(s + base + gl));
           my = -1;
         }
       }
@@ -137,7 +139,7 @@ void launch(const dmt_plan* p, const DmtDimClass& c, const int32_t* indices,
   hipLaunchKernelGGL((lookup_fwd_kernel<TD, OD>), dim3(tiles_per_xcd * 8), dim3(kBlock), 0, s,
                      p->d_meta, p->d_class_tables + c.first, c.D, indices, offsets, B, nnz, out,
                      log2_lpr, log2_gl, bpg, tiles_per_table, ntiles, tiles_per_xcd, long_thr,
-                     p->d_error);
+                     p->row_shards ? nullptr : p->d_error);
 }
 
 int ilog2_ceil(int x) {

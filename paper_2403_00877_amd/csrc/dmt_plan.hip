@@ -65,6 +65,7 @@ extern "C" dmt_status dmt_plan_create(dmt_plan** out, int32_t num_tables, const 
     m.table = nullptr;
     m.state = nullptr;
     m.rows = rows[f];
+    m.row_begin = 0;
     m.row_base = rb;
     rb += rows[f];
     m.D = dims[f];
@@ -169,6 +170,19 @@ extern "C" dmt_status dmt_plan_bind(dmt_plan* plan, const void* const* tables,
                         hipMemcpyHostToDevice));
   DMT_HIP_TRY(hipMemcpy(plan->d_error, &none, sizeof(none), hipMemcpyHostToDevice));
   plan->bound = true;
+  return DMT_OK;
+}
+
+extern "C" dmt_status dmt_plan_set_row_shards(dmt_plan* plan, const int64_t* row_begin) {
+  if (!plan || !row_begin) return DMT_EINVAL;
+  // a local row is addressed as id - row_begin, which must stay within an int32 id
+  for (int32_t f = 0; f < plan->F; ++f)
+    if (row_begin[f] < 0 || row_begin[f] + plan->meta[f].rows > (1LL << 31)) return DMT_EINVAL;
+  for (int32_t f = 0; f < plan->F; ++f) plan->meta[f].row_begin = row_begin[f];
+  plan->row_shards = true;
+  if (plan->bound)
+    DMT_HIP_TRY(hipMemcpy(plan->d_meta, plan->meta.data(), sizeof(DmtTableMeta) * plan->F,
+                          hipMemcpyHostToDevice));
   return DMT_OK;
 }
 
