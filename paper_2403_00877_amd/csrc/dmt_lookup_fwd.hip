@@ -136,7 +136,11 @@ void launch(const dmt_plan* p, const DmtDimClass& c, const int32_t* indices,
   const int32_t ntiles = tiles_per_table * c.num_tables;
   const int32_t tiles_per_xcd = (ntiles + 7) / 8;
   DmtScope scope(p, DMT_K_LOOKUP_FWD, s);
-  hipLaunchKernelGGL((lookup_fwd_kernel<TD, OD>), dim3(tiles_per_xcd * 8), dim3(kBlock), 0, s,
+  // Development knob: reserve unused LDS per block, to time the gather at the occupancy a kernel
+  // that also holds a Tower Module tile in LDS would leave it.
+  const int idle_lds = dmt::env_int("DMT_LOOKUP_IDLE_LDS", 0);
+  hipLaunchKernelGGL((lookup_fwd_kernel<TD, OD>), dim3(tiles_per_xcd * 8), dim3(kBlock),
+                     idle_lds > 0 && idle_lds <= 65536 ? idle_lds : 0, s,
                      p->d_meta, p->d_class_tables + c.first, c.D, indices, offsets, B, nnz, out,
                      log2_lpr, log2_gl, bpg, tiles_per_table, ntiles, tiles_per_xcd, long_thr,
                      p->row_shards ? nullptr : p->d_error);
