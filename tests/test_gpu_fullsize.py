@@ -1,4 +1,4 @@
-"""Parity at the benchmark's full sizes, in the launch configurations bench.py
+"""Parity at the benchmark configurations' full sizes, in the launch configurations bench.py
 times: the Backward workload (= Mid tables and lookups, 64 x 1M x 128 fp16,
 B = 8192; the benchmark's own step), Imbalanced (128 mixed-width tables,
 B = 65536, forward + backward) and Large (256 bf16 tables, ~97 GB, B = 16384,
