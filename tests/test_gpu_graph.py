@@ -87,3 +87,46 @@ def test_captured_step_replays_like_eager_steps(which):
             bits = {2: torch.int16, 4: torch.int32}[a.element_size()]
             assert torch.equal(a.view(bits), b.view(bits)), "replay %d differs from %d eager steps" % (n, n + 1)
     assert graphed["dw"].dmt.dmt_last_device_error(graphed["dw"].plan) == -1
+
+
+def test_partitioner_and_shuffle_calls_capture_too():
+    """dmt_tp_interaction and the SPTT shuffle steps also only enqueue kernels: captured after one
+    eager call each, every replay on fresh pooled values gives the eager result bit for bit."""
+    import paper_2403_00877_amd as dmt
+    w = wl.scaled(wl.mid(), max_rows=3000, batch=256, num_tables=16)
+    dw = DeviceWorkload(w)
+    F, B = w.num_tables, w.batch
+    n = B * sum(w.tower_widths())
+    pooled = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    I = torch.zeros(F, F, dtype=torch.float32, device="cuda")
+    ws = torch.empty(dmt.dmt_tp_workspace_bytes(dw.plan, B), dtype=torch.uint8, device="cuda")
+    src = pooled.view(torch.uint8)
+    permuted, shuffled = torch.zeros_like(src), torch.zeros_like(src)
+    block = src.numel() // (F * 8)
+
+    def calls():
+        dmt.dmt_tp_interaction(dw.plan, pooled, B, I, ws)
+        dmt.dmt_sptt_peer_permute(src, permuted, F, 8, 4, block)
+        dmt.dmt_sptt_shuffle(src, shuffled, F, 8, block)
+
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3)
+    pooled.copy_(torch.randn(n, generator=g, device="cuda"))
+    calls()                                          # eager warm-up
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.graph(graph, stream=side):
+        calls()
+    for _ in range(3):
+        pooled.copy_(torch.randn(n, generator=g, device="cuda"))   # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (I.clone(), permuted.clone(), shuffled.clone())
+        I.zero_(); permuted.zero_(); shuffled.zero_()
+        calls()
+        torch.cuda.synchronize()
+        for a, b in zip(got, (I, permuted, shuffled)):
+            assert torch.equal(a, b)
+        assert float(I.diagonal().min()) > 0.99
