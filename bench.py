@@ -258,11 +258,18 @@ def main():
                         ms_per_launch=round(per_step / launches, 4), launches_per_step=launches,
                         algorithmic_bytes=int(bytes_of[name]))
         tf = tm_fwd_flops / (per_step * 1e-3) / 1e12
+        g = tm_bytes / (per_step * 1e-3) / 1e9
+        # the Tower Module's contraction is bound by whichever roof its FLOP per byte puts lower
+        if tm_fwd_flops / tm_bytes < MFMA_PEAK_TFLOPS_16BIT * 1e12 / (HBM_PEAK_GBS * 1e9):
+            return dict(kernel=name, bound="hbm", achieved=round(g, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=round(g / HBM_PEAK_GBS, 4), traffic=None,
+                        ms_per_launch=round(per_step / launches, 4), launches_per_step=launches,
+                        algorithmic_bytes=int(tm_bytes), algorithmic_flops=int(tm_fwd_flops),
+                        achieved_TFLOPs=round(tf, 2))
         return dict(kernel=name, bound="mfma", achieved=round(tf, 2), peak=MFMA_PEAK_TFLOPS_16BIT,
                     unit="TFLOP/s", frac=round(tf / MFMA_PEAK_TFLOPS_16BIT, 4), traffic=None,
                     ms_per_launch=round(per_step / launches, 4), launches_per_step=launches,
-                    algorithmic_flops=int(tm_fwd_flops),
-                    achieved_GBs=round(tm_bytes / (per_step * 1e-3) / 1e9, 1))
+                    algorithmic_flops=int(tm_fwd_flops), achieved_GBs=round(g, 1))
 
     dom = max(prof.items(), key=lambda kv: kv[1][0])[0]
     roofline = describe(dom)
