@@ -180,9 +180,9 @@ __global__ __launch_bounds__(kBlock) void tmb_transpose(const TmbLaunch L) {
 }
 
 // The same for 16-bit elements with C, lds and ldd multiples of 4 and 8-byte aligned
-// bases: 64 x 64 tiles, four elements per global access.
+// bases: 64 x 64 tiles, four (or, alignment permitting, eight) elements per global access.
 __global__ __launch_bounds__(kBlock) void tmb_transpose16(const TmbLaunch L) {
-  __shared__ __attribute__((aligned(8))) uint16_t tile[kVTile][kVTile + 4];
+  __shared__ __attribute__((aligned(16))) uint16_t tile[kVTile][kVTile + 8];
   const int gi = tmb_find(L);
   const TmbItem& G = L.it[gi];
   const int lb = blockIdx.x - L.block_start[gi];
@@ -192,6 +192,37 @@ __global__ __launch_bounds__(kBlock) void tmb_transpose16(const TmbLaunch L) {
   const int C = G.i0;
   const int64_t r0 = (int64_t)(lb % G.nbx) * kVTile;
   const int c0 = (lb / G.nbx) * kVTile;
+  // 16-byte global accesses where every row of both matrices splits into aligned 8-element
+  // chunks (the same for the whole item, so the branch is uniform)
+  const bool wide = C % 8 == 0 && lds % 8 == 0 && ldd % 8 == 0 && fill % 8 == 0 &&
+                    (((uintptr_t)src | (uintptr_t)dst) & 15) == 0;
+  if (wide) {
+    const int q = threadIdx.x >> 3, v = (threadIdx.x & 7) * 8;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      const int i = pass * 32 + q;
+      const int64_t r = r0 + i;
+      const int c = c0 + v;
+      uint4 x = make_uint4(0, 0, 0, 0);
+      if (r < R && c < C) x = *(const uint4*)(src + r * lds + c);
+      *(uint4*)&tile[i][v] = x;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      const int i = pass * 32 + q;                 // column of the source tile
+      const int c = c0 + i;
+      const int64_t r = r0 + v;
+      if (c < C && r < fill) {
+        uint32_t w[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+          w[k] = tile[v + 2 * k][i] | ((uint32_t)tile[v + 2 * k + 1][i] << 16);
+        *(uint4*)(dst + (int64_t)c * ldd + r) = make_uint4(w[0], w[1], w[2], w[3]);
+      }
+    }
+    return;
+  }
   const int q = threadIdx.x >> 4, v = (threadIdx.x & 15) * 4;
 #pragma unroll
   for (int pass = 0; pass < 4; ++pass) {
