@@ -758,6 +758,9 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
   TmbBatch batch, batch2, batch3, prep16;
   bool ok = true;
 
+  auto z_of = [&](int t) -> const char* {           // dot terms: kept by the forward, or recomputed
+    return keptp && kept[t].has_z ? keptp + kept[t].z : (const char*)(wsp + ws[t].p);
+  };
   // ---- recompute what the forward did not keep: dot terms (and the repacked weights)
   std::vector<TmAuxItem> dots_mfma, dots_simple, packs;
   std::vector<int64_t> nb_mfma, nb_simple, nb_pack;
@@ -771,7 +774,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
     it.O = q.out_dim; it.wt = p->tower_width[t];
     it.src = x_of(t);
     it.dst = wsp + w.p;
-    if (w.np_pad > 0) {
+    if (w.np_pad > 0 && !(keptp && kept[t].has_z)) {
       if (DT != DMT_F32 && 32 % it.nf == 0 && it.n % 16 == 0) {
         dots_mfma.push_back(it);
         nb_mfma.push_back(((B * it.nf + 31) / 32 + 3) / 4);
@@ -855,7 +858,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
                         wsp + w.wT, w.Op);
     // z^T [kin][Bp]: the projection's input, transposed
     if (dot) {
-      if (w.np_pad > 0) add_transpose<DT>(batch3, wsp + w.p, B, w.np_pad, w.np_pad, wsp + w.zT, Bp);
+      if (w.np_pad > 0) add_transpose<DT>(batch3, z_of(t), B, w.np_pad, w.np_pad, wsp + w.zT, Bp);
       add_transpose<DT>(batch3, x_of(t), B, wt, wt, wsp + w.zT + (size_t)w.np_pad * Bp * eb, Bp);
     } else {
       const void* z = is_cross(q) ? xl_of(t, q.num_cross_layers) : x_of(t);

@@ -112,6 +112,11 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
     return keptp ? keptp + kept[t].x[l] : wsp + ws[t].x_off[l & 1];
   };
 
+  // the dot terms of a dot-product tower: kept for the backward, else scratch
+  auto z_of = [&](int t) -> char* {
+    return keptp && kept[t].has_z ? keptp + kept[t].z : wsp + ws[t].z_off;
+  };
+
   // A dot-product tower whose shape fits computes its dot terms inside the projection GEMM.
   std::vector<char> fused(p->T, 0);
   if (DT != DMT_F32 && dmt::env_int("DMT_TM_FUSE", 1) != 0 && dmt::env_int("DMT_TM_BIG", 1) != 0)
@@ -137,7 +142,7 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
     it.nf = p->tower_ntab[t]; it.n = p->tower_uniform_dim[t]; it.np = w.np; it.np_pad = w.np_pad;
     it.O = q.out_dim; it.wt = p->tower_width[t];
     it.src = x_all + (size_t)B * p->width_prefix[t] * eb;
-    it.dst = wsp + w.z_off;
+    it.dst = z_of(t);
     if (fused[t]) {
     } else if (DT != DMT_F32 && 32 % it.nf == 0 && it.n % 16 == 0) {
       dots_mfma.push_back(it);
@@ -202,7 +207,7 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
     g.A1 = x; g.lda1 = wt; g.K1 = wt;
     g.W = q.w_proj; g.ldw = wt;
     if (q.kind == DMT_TM_DOT_LINEAR) {
-      g.A0 = wsp + ws[t].z_off; g.lda0 = ws[t].np_pad; g.K0 = ws[t].np_pad;
+      g.A0 = z_of(t); g.lda0 = ws[t].np_pad; g.K0 = ws[t].np_pad;
       g.W = wsp + ws[t].wp_off; g.ldw = ws[t].np_pad + wt;
     } else if (q.kind == DMT_TM_CROSS_LINEAR || q.kind == DMT_TM_CROSS_LOWRANK_LINEAR) {
       g.A1 = x_layer(t, q.num_cross_layers - 1);
@@ -226,6 +231,7 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
       groups_feat.push_back(h);
     }
     if (fused[t]) {
+      if (keptp && kept[t].has_z) g.U = z_of(t);
       g.A0 = nullptr; g.lda0 = 0;
       g.nf = p->tower_ntab[t]; g.fdim = p->tower_uniform_dim[t];
       groups_fused.push_back(g);

@@ -48,8 +48,9 @@ struct TmGroup {
   // (m / rdiv) * ldc + (m % rdiv) * ldc2, i.e. rdiv consecutive rows of the contraction share
   // one row of the output tensor.
   int32_t rdiv, ldc2;
-  // EPI_CROSS only: when set, u = acc + bias (before the cross product) is also stored here,
-  // laid out like C (what the backward needs of a cross layer).
+  // EPI_CROSS: when set, u = acc + bias (before the cross product) is also stored here, laid
+  // out like C (what the backward needs of a cross layer).  A group whose dot terms are computed
+  // in-kernel: when set, they are also stored here as [M][K0], zeros in the padding columns.
   void* U;
   // EPI_CROSS: the x_l term, [M][ldxl]; NULL when it is the operand A1 itself (a full-rank
   // layer).  A low-rank layer contracts t = V x_l instead, and adds x_l from here.
@@ -239,7 +240,7 @@ constexpr int kBigLdsBytes = 4 * kBigTileElems * 2;         // 2 stages x (A + B
 // DOTS: the operand's first K0 columns are the tower's pairwise dot terms, which the block
 // computes itself (Gram tiles, as in tm_dots_mfma) straight into the first LDS stage, so the
 // pooled tensor is read once and the dot terms never exist in global memory.
-template <int DT, bool DOTS, int TAG = DMT_TM_TAG>
+template <int DT, bool DOTS, int TAG = DMT_TM_TAG, bool KEEPZ = false>
 __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunch L) {
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
   // XCD-aware rasterisation.  Consecutive block ids go to different XCDs, so block b belongs
@@ -364,8 +365,21 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
       for (int v = 0; v < 16; ++v) {
         const int rr = (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
         const int i = rr % nf;
-        if (rr / nf == sc && i < j)
-          store_elt<DT>(lds, s_local * kLdsStride + (i * (2 * nf - i - 1) / 2 + (j - i - 1)), d[v]);
+        if (rr / nf == sc && i < j) {
+          const int term = i * (2 * nf - i - 1) / 2 + (j - i - 1);
+          store_elt<DT>(lds, s_local * kLdsStride + term, d[v]);
+          if constexpr (KEEPZ)
+            if (G.U && m0 + s_local < M) store_elt<DT>(G.U, (int64_t)(m0 + s_local) * G.K0 + term, d[v]);
+        }
+      }
+      if constexpr (KEEPZ) {
+        // zeros behind the terms of the row group's samples
+        const int np = nf * (nf - 1) / 2, npad = G.K0 - np, spg = 32 / nf;
+        if (G.U)
+          for (int e = lane; e < spg * npad; e += 64) {
+            const int row = m0 + rg * spg + e / npad;
+            if (row < M) store_elt<DT>(G.U, (int64_t)row * G.K0 + np + e % npad, 0.f);
+          }
       }
     }
   }
@@ -631,9 +645,11 @@ __global__ __launch_bounds__(kBlock) void tm_dots_mfma(const TmAuxLaunch L) {
     if (rr / nf == sc && i < j && s0 + sc < B)
       store_elt<DT>(z, (s0 + sc) * np_pad + (i * (2 * nf - i - 1) / 2 + (j - i - 1)), acc[v]);
   }
+  // zeros behind the terms of the row group's samples (2 features: 16 samples x 7 columns, more
+  // than one per lane)
   const int npad = np_pad - np;
-  if (lane < spg * npad) {
-    const int s = lane / npad, q = lane % npad;
+  for (int e = lane; e < spg * npad; e += 64) {
+    const int s = e / npad, q = e % npad;
     if (s0 + s < B) store_elt<DT>(z, (s0 + s) * np_pad + np + q, 0.f);
   }
 }
@@ -679,10 +695,14 @@ __global__ __launch_bounds__(kBlock) void tm_pack_w(const TmAuxLaunch L) {
 }
 
 // What a training forward keeps for the backward: for every cross layer l of a cross tower
-// (full-rank or low-rank), x_{l+1} and u_l = W_l x_l + b_l, each [B][W_t] in the compute type.  Offsets in bytes from a
-// 256-byte-aligned base; towers of other kinds keep nothing (their backward recomputes).
+// (full-rank or low-rank), x_{l+1} and u_l = W_l x_l + b_l, each [B][W_t] in the compute type;
+// for a dot-product tower its dot terms, [B][np_pad] (np_pad = the F (F - 1) / 2 terms rounded
+// up to 8, zeros behind them).  Offsets in bytes from a 256-byte-aligned base; towers of other
+// kinds keep nothing (their backward needs only the pooled values).
 struct TmKept {
   size_t x[DMT_MAX_CROSS_LAYERS] = {}, u[DMT_MAX_CROSS_LAYERS] = {};
+  size_t z = 0;
+  bool has_z = false;
 };
 
 inline size_t plan_tm_kept(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, int eb,
@@ -690,6 +710,15 @@ inline size_t plan_tm_kept(const dmt_plan* p, const dmt_tm_params* tp, int64_t B
   size_t off = 0;
   kept->assign(p->T, TmKept());
   for (int32_t t = 0; t < p->T; ++t) {
+    if (tp[t].kind == DMT_TM_DOT_LINEAR) {
+      const int nf = p->tower_ntab[t], np_pad = (nf * (nf - 1) / 2 + 7) / 8 * 8;
+      if (np_pad > 0) {
+        (*kept)[t].z = off;
+        (*kept)[t].has_z = true;
+        off += dmt_align_up((size_t)B * np_pad * eb, 256);
+      }
+      continue;
+    }
     if (tp[t].kind != DMT_TM_CROSS_LINEAR && tp[t].kind != DMT_TM_CROSS_LOWRANK_LINEAR) continue;
     const size_t bytes = dmt_align_up((size_t)B * p->tower_width[t] * eb, 256);
     for (int l = 0; l < tp[t].num_cross_layers && l < DMT_MAX_CROSS_LAYERS; ++l) {
@@ -740,6 +769,8 @@ void launch_groups(const dmt_plan* p, std::vector<TmGroup>& groups, hipStream_t 
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
           (void)hipFuncSetAttribute((const void*)tm_gemm_mfma_256<DT, true>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
+          (void)hipFuncSetAttribute((const void*)tm_gemm_mfma_256<DT, true, DMT_TM_TAG, true>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
           configured = true;
         }
         int32_t nst = 0;                                      // super-tiles of the launch
@@ -753,7 +784,12 @@ void launch_groups(const dmt_plan* p, std::vector<TmGroup>& groups, hipStream_t 
         L.tile_start[L.ngroups] = nst;
         const int32_t big_tiles = (nst + 7) / 8 * 8 * kSuper;
         DmtScope sc_(p, kid, s);
-        if (dots)
+        bool keepz = false;                   // a training forward keeps the dot terms
+        for (int i = 0; i < L.ngroups; ++i) keepz = keepz || (dots && L.g[i].U != nullptr);
+        if (keepz)
+          hipLaunchKernelGGL((tm_gemm_mfma_256<DT, true, DMT_TM_TAG, true>), dim3(big_tiles),
+                             dim3(kBigThreads), kBigLdsBytes, s, L);
+        else if (dots)
           hipLaunchKernelGGL((tm_gemm_mfma_256<DT, true>), dim3(big_tiles), dim3(kBigThreads),
                              kBigLdsBytes, s, L);
         else

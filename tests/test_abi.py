@@ -126,7 +126,13 @@ def test_tower_module_backward_and_keep_validate_on_the_host():
     assert need > 0 and dmt.dmt_tm_bwd_workspace_bytes(p, arr, 2) <= need
     for a in arr:
         a.kind = binding.DMT_TM_DOT_LINEAR
-    assert dmt.dmt_tm_kept_bytes(p, arr, 4, "f16") == 0          # dot towers keep nothing
+    # dot towers keep their dot terms: 1 term padded to 8 per sample, rounded up to 256 bytes
+    assert dmt.dmt_tm_kept_bytes(p, arr, 4, "f16") == 2 * 256
+    for a in arr:
+        a.kind = binding.DMT_TM_LINEAR
+    assert dmt.dmt_tm_kept_bytes(p, arr, 4, "f16") == 0          # linear towers keep nothing
+    for a in arr:
+        a.kind = binding.DMT_TM_DOT_LINEAR
     grads = (dmt.binding.dmt_tm_grads * 2)()
     bwd = lib.dmt_tower_module_bwd
     bwd.argtypes = [vp, vp, vp, vp, i64, vp, ctypes.c_int, vp, vp, vp, sz, vp, sz, vp]

@@ -305,7 +305,7 @@ def test_tower_module_backward_on_sampled_samples(run):
         dy[ypos:ypos + B * w.tm_out[t]].reshape(B, -1)[~keep] = 0.0
         ypos += B * w.tm_out[t]
     dx.fill_(float("nan"))
-    # this time on what a training forward kept (cross towers; nothing for the other kinds)
+    # this time on what a training forward kept (cross towers: u_l and x_l; dot towers: the dot terms)
     kept = None
     kept_bytes = dmt.dmt_tm_kept_bytes(run.plan, params, B, w.tm_dtype)
     if kept_bytes:

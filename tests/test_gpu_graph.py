@@ -34,6 +34,8 @@ def _make(w):
                                (torch.float16 if tm.dtype == "f16" else torch.float32), device="cuda")
     st["y"] = torch.zeros(B * sum(w.tm_out), dtype=st["pooled"].dtype, device="cuda")
     st["dx"] = torch.zeros(B * sum(widths), dtype=torch.float32, device="cuda")
+    nk = dmt.dmt_tm_kept_bytes(dw.plan, tm.params, B, tm.dtype)
+    st["kept"] = torch.empty(nk, dtype=torch.uint8, device="cuda") if nk else None
     st["ws_bwd"] = torch.empty(dmt.dmt_tm_bwd_workspace_bytes(dw.plan, tm.params, B), dtype=torch.uint8, device="cuda")
     st["ws_upd"] = torch.empty(max(dmt.dmt_bwd_workspace_bytes(dw.plan, B, len(idx)), 256), dtype=torch.uint8,
                                device="cuda")
@@ -44,9 +46,9 @@ def _step(st):
     dw, tm, B = st["dw"], st["tm"], st["B"]
     dmt, w = dw.dmt, dw.w
     dmt.dmt_tower_lookup_fwd(dw.plan, st["idx"], st["off"], B, st["pooled"])
-    dmt.dmt_tower_module_fwd_keep(dw.plan, tm.params, st["pooled"], B, st["y"], None, tm.workspace)
+    dmt.dmt_tower_module_fwd_keep(dw.plan, tm.params, st["pooled"], B, st["y"], st["kept"], tm.workspace)
     dmt.dmt_tower_module_bwd(dw.plan, tm.params, st["pooled"], st["y"], B, st["dy"], st["dx"], st["arr"],
-                             st["ws_bwd"])
+                             st["ws_bwd"], kept=st["kept"])
     dmt.dmt_tower_lookup_bwd_update(dw.plan, st["idx"], st["off"], B, st["dx"], w.lr, w.eps, st["ws_upd"])
 
 

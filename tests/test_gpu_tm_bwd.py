@@ -190,9 +190,9 @@ def test_cross_three_layers_narrow_tower_f32_and_bf16(keep):
         check_tm_bwd(w, rtol, keep=keep)
 
 
-def test_kept_activations_wide_cross_tower_and_towers_that_keep_nothing():
-    # two 2048-wide towers (256 x 256 GEMM path), 2 layers; then a dot tower, whose forward keeps
-    # nothing: the backward must behave exactly as without
+def test_kept_activations_wide_cross_tower_and_dot_towers():
+    # two 2048-wide towers (256 x 256 GEMM path), 2 layers; then dot towers, whose training forward
+    # keeps the dot terms it computes inside the projection kernel
     w = wl.scaled(wl.large(), max_rows=3000, batch=200)
     sel = [f for f in range(256) if w.table_to_tower[f] in (0, 1)]
     w.rows = [w.rows[f] for f in sel]; w.dims = [128] * 32
@@ -200,6 +200,24 @@ def test_kept_activations_wide_cross_tower_and_towers_that_keep_nothing():
     w.tm_out = [512, 512]
     check_tm_bwd(w, rtol=4e-2, keep=True)
     check_tm_bwd(wl.scaled(wl.mid(), max_rows=5000, batch=301, num_tables=16), keep=True)
+
+
+@pytest.mark.parametrize("dt,fuse", [("f32", "1"), ("f16", "1"), ("bf16", "0")])
+def test_kept_dot_terms_on_every_dot_path(dt, fuse, monkeypatch):
+    """The dot terms a training forward keeps, from the one-thread-per-term kernel (float32), the
+    fused projection kernel, and the separate Gram-tile kernel (fusion switched off); 5 features
+    per tower leave padding columns behind the 10 terms."""
+    monkeypatch.setenv("DMT_TM_FUSE", fuse)
+    w = wl.scaled(wl.mid(), max_rows=3000, batch=257, num_tables=16)
+    w.tm_dtype = dt
+    w.pooled_dtype = dt
+    check_tm_bwd(w, rtol=1e-4 if dt == "f32" else 4e-2, keep=True)
+    w5 = wl.scaled(wl.mid(), max_rows=3000, batch=130, num_tables=10)
+    w5.table_to_tower = [0] * 5 + [1] * 5
+    w5.tm_out = [256, 256]
+    w5.tm_dtype = dt
+    w5.pooled_dtype = dt
+    check_tm_bwd(w5, rtol=1e-4 if dt == "f32" else 4e-2, keep=True)
 
 
 @pytest.mark.parametrize("dt", ["bf16", "f16", "f32"])
