@@ -224,7 +224,8 @@ dmt_status dmt_tower_module_fwd(const dmt_plan* plan, const dmt_tm_params* per_t
  * backward would otherwise recompute: x_{l+1} and u_l = W_l x_l + b_l of every
  * cross layer, full-rank or low-rank (paper Listing 2), each [B][W_t] in
  * `dtype`; the pairwise dot terms of a dot-product tower, [B][F_t (F_t - 1) / 2
- * rounded up to 8] in `dtype`.  tm_out is bit for bit that of
+ * rounded up to 8] in `dtype`, and its projection weights repacked to match
+ * (so the weights must not change between this call and the backward).  tm_out is bit for bit that of
  * dmt_tower_module_fwd.  Towers of the other kinds keep nothing (their backward
  * needs only the pooled values).
  *   kept  dev, at least dmt_tm_kept_bytes(plan, per_tower, B, dtype), 256-byte

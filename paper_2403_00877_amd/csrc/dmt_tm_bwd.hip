@@ -761,6 +761,9 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
   auto z_of = [&](int t) -> const char* {           // dot terms: kept by the forward, or recomputed
     return keptp && kept[t].has_z ? keptp + kept[t].z : (const char*)(wsp + ws[t].p);
   };
+  auto wp_of = [&](int t) -> const char* {          // ... and the repacked projection weights
+    return keptp && kept[t].has_z ? keptp + kept[t].wp : (const char*)(wsp + ws[t].wp);
+  };
   // ---- recompute what the forward did not keep: dot terms (and the repacked weights)
   std::vector<TmAuxItem> dots_mfma, dots_simple, packs;
   std::vector<int64_t> nb_mfma, nb_simple, nb_pack;
@@ -783,6 +786,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
         nb_simple.push_back((B * w.np_pad + kBlock - 1) / kBlock);
       }
     }
+    if (keptp && kept[t].has_z) continue;
     it.src = q.w_proj;
     it.dst = wsp + w.wp;
     packs.push_back(it);
@@ -854,7 +858,7 @@ dmt_status run_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, const std::vec
     }
     // W^T [kin][Op] (a DLRM tower's goes into its combined weights below)
     if (!dlrm)
-      add_transpose<DT>(batch3, dot ? (const void*)(wsp + w.wp) : q.w_proj, O, w.kin, w.kin,
+      add_transpose<DT>(batch3, dot ? (const void*)wp_of(t) : q.w_proj, O, w.kin, w.kin,
                         wsp + w.wT, w.Op);
     // z^T [kin][Bp]: the projection's input, transposed
     if (dot) {

@@ -117,6 +117,10 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
     return keptp && kept[t].has_z ? keptp + kept[t].z : wsp + ws[t].z_off;
   };
 
+  auto wp_of = [&](int t) -> char* {                // ... and its repacked projection weights
+    return keptp && kept[t].has_z ? keptp + kept[t].wp : wsp + ws[t].wp_off;
+  };
+
   // A dot-product tower whose shape fits computes its dot terms inside the projection GEMM.
   std::vector<char> fused(p->T, 0);
   if (DT != DMT_F32 && dmt::env_int("DMT_TM_FUSE", 1) != 0 && dmt::env_int("DMT_TM_BIG", 1) != 0)
@@ -152,7 +156,7 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
       nb_simple.push_back((B * w.np_pad + kBlock - 1) / kBlock);
     }
     it.src = q.w_proj;
-    it.dst = wsp + w.wp_off;
+    it.dst = wp_of(t);
     packs.push_back(it);
     nb_pack.push_back(((int64_t)q.out_dim * (w.np_pad + it.wt) + kBlock - 1) / kBlock);
   }
@@ -208,7 +212,7 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
     g.W = q.w_proj; g.ldw = wt;
     if (q.kind == DMT_TM_DOT_LINEAR) {
       g.A0 = z_of(t); g.lda0 = ws[t].np_pad; g.K0 = ws[t].np_pad;
-      g.W = wsp + ws[t].wp_off; g.ldw = ws[t].np_pad + wt;
+      g.W = wp_of(t); g.ldw = ws[t].np_pad + wt;
     } else if (q.kind == DMT_TM_CROSS_LINEAR || q.kind == DMT_TM_CROSS_LOWRANK_LINEAR) {
       g.A1 = x_layer(t, q.num_cross_layers - 1);
     }

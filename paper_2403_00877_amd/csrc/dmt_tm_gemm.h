@@ -697,11 +697,12 @@ __global__ __launch_bounds__(kBlock) void tm_pack_w(const TmAuxLaunch L) {
 // What a training forward keeps for the backward: for every cross layer l of a cross tower
 // (full-rank or low-rank), x_{l+1} and u_l = W_l x_l + b_l, each [B][W_t] in the compute type;
 // for a dot-product tower its dot terms, [B][np_pad] (np_pad = the F (F - 1) / 2 terms rounded
-// up to 8, zeros behind them).  Offsets in bytes from a 256-byte-aligned base; towers of other
+// up to 8, zeros behind them), and its projection weights with zero columns inserted to match,
+// [O][np_pad + W_t].  Offsets in bytes from a 256-byte-aligned base; towers of other
 // kinds keep nothing (their backward needs only the pooled values).
 struct TmKept {
   size_t x[DMT_MAX_CROSS_LAYERS] = {}, u[DMT_MAX_CROSS_LAYERS] = {};
-  size_t z = 0;
+  size_t z = 0, wp = 0;      // dot tower: dot terms, and the projection weights as repacked for them
   bool has_z = false;
 };
 
@@ -716,6 +717,8 @@ inline size_t plan_tm_kept(const dmt_plan* p, const dmt_tm_params* tp, int64_t B
         (*kept)[t].z = off;
         (*kept)[t].has_z = true;
         off += dmt_align_up((size_t)B * np_pad * eb, 256);
+        (*kept)[t].wp = off;
+        off += dmt_align_up((size_t)tp[t].out_dim * (np_pad + p->tower_width[t]) * eb, 256);
       }
       continue;
     }

@@ -126,8 +126,9 @@ def test_tower_module_backward_and_keep_validate_on_the_host():
     assert need > 0 and dmt.dmt_tm_bwd_workspace_bytes(p, arr, 2) <= need
     for a in arr:
         a.kind = binding.DMT_TM_DOT_LINEAR
-    # dot towers keep their dot terms: 1 term padded to 8 per sample, rounded up to 256 bytes
-    assert dmt.dmt_tm_kept_bytes(p, arr, 4, "f16") == 2 * 256
+    # dot towers keep their dot terms (1 term padded to 8 per sample) and the repacked weights
+    # ([8][8 + 16] f16 = 384 bytes), each rounded up to 256 bytes
+    assert dmt.dmt_tm_kept_bytes(p, arr, 4, "f16") == 2 * (256 + 512)
     for a in arr:
         a.kind = binding.DMT_TM_LINEAR
     assert dmt.dmt_tm_kept_bytes(p, arr, 4, "f16") == 0          # linear towers keep nothing
