@@ -326,6 +326,9 @@ size_t dmt_bwd_workspace_bytes(const dmt_plan* plan, int64_t B, int64_t nnz);
  *   table_f[r][d] -= lr * G[d] / (sqrt(state[f][r]) + eps)   (rounded once to the
  *            table dtype, one writer per row, no atomics)
  * Rows no lookup touched, and their states, are not written.
+ * `offsets` must tile [0, nnz): offsets[0] = 0, ascending, offsets[num_tables*B] = nnz.  This
+ * is checked on the device; when it does not hold no row and no state is written and
+ * dmt_last_device_error returns DMT_EINVAL.
  *   grad_pooled  dev float32, tower-major like pooled_out
  *   workspace    dev, at least dmt_bwd_workspace_bytes(plan, B, nnz), 256-byte aligned
  *   dbg          NULL or where to export the sorted / deduplicated keys
@@ -422,9 +425,14 @@ dmt_status dmt_sptt_shuffle(const void* in, void* out, int64_t features, int64_t
                             int64_t block_bytes, void* stream);
 
 /*
- * Synchronise `stream` and report whether any kernel since the last call saw an
- * id outside its table: DMT_EBOUNDS with *bad_position = smallest offending
- * position in `indices`, else DMT_OK with *bad_position = -1.  Clears the record.
+ * Synchronise `stream` and report what the kernels since the last call found wrong with
+ * their jagged input.  Clears the record.
+ *   DMT_EINVAL   the backward saw `offsets` that do not tile [0, nnz) (first entry not 0, a
+ *                descending pair, an entry outside [0, nnz], last entry not nnz);
+ *                *bad_position = the first such bag.  That call updated no row.
+ *   DMT_EBOUNDS  an id outside its table; *bad_position = smallest offending position in
+ *                `indices`.  Such lookups were skipped, everything else was done.
+ *   DMT_OK       neither; *bad_position = -1.
  */
 dmt_status dmt_last_device_error(const dmt_plan* plan, void* stream, int64_t* bad_position);
 

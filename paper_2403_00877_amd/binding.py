@@ -296,11 +296,15 @@ def dmt_tower_lookup_bwd_update(plan: dmt_plan, indices: torch.Tensor, offsets: 
 
 
 def dmt_last_device_error(plan: dmt_plan, stream=None) -> int:
-    """-1 when clean, else the smallest offending position (and the record is cleared)."""
+    """-1 when clean, else the smallest position of an id outside its table (and the record is
+    cleared).  Raises DmtError(DMT_EINVAL) when the backward found malformed offsets; the
+    exception's `position` is the first offending bag."""
     pos = ctypes.c_int64(-1)
     code = _lib.dmt_last_device_error(plan.handle, _stream(stream), ctypes.byref(pos))
     if code not in (DMT_OK, DMT_EBOUNDS):
-        raise DmtError("dmt_last_device_error", code)
+        e = DmtError("dmt_last_device_error", code)
+        e.position = int(pos.value)
+        raise e
     return int(pos.value)
 
 

@@ -15,9 +15,9 @@
 // ceil(log2(largest table)) bits instead of ceil(log2(all rows)).  An id outside
 // its table gets the key  kInertBit | (global id one past the table's last row):
 // it sorts behind the table's rows, equals no row's key, and is never touched.
-// `offsets` must tile [0, nnz) (ascending, offsets[0] = 0, last = nnz): a record
-// no bag covers is never initialised; the kernels still keep every access in
-// bounds for any record contents, but the values written are then unspecified.
+// `offsets` must tile [0, nnz) (ascending, offsets[0] = 0, last = nnz): the key build
+// checks this, records the first bag that breaks it, and the reduce and fix-up kernels
+// then return without touching a row (dmt_last_device_error reports DMT_EINVAL).
 #include <algorithm>
 #include <type_traits>
 
@@ -147,17 +147,24 @@ __global__ __launch_bounds__(kBlock) void bwd_build_keys(
     const int64_t* __restrict__ offsets, uint32_t B, uint32_t nbags, int64_t nnz, int F,
     uint64_t* __restrict__ pk, int log2_bpb, uint32_t* __restrict__ seg_begin,
     uint32_t* __restrict__ seg_blk, uint32_t* __restrict__ blk_table,
-    unsigned long long* __restrict__ err) {
+    unsigned long long* __restrict__ err, unsigned long long* __restrict__ err_offsets) {
   __shared__ int64_t offs[kKeysMaxBags + 1];
   if (blockIdx.x == 0) build_sort_map(offsets, B, F, nnz, seg_begin, seg_blk, blk_table);
   const uint32_t g0 = blockIdx.x << log2_bpb;
   if (g0 >= nbags) return;
   const int nb = (int)min((uint32_t)(1 << log2_bpb), nbags - g0);
+  // `offsets` must tile [0, nnz): starts at 0, never descends, ends at nnz.  The first bag
+  // that breaks this is recorded; the reduce and fix-up kernels then touch no row.
   for (int i = threadIdx.x; i <= nb; i += kBlock) {
     const int64_t o = offsets[g0 + i];
+    const bool at_end = g0 + (uint32_t)i == nbags;
+    if (o < 0 || o > nnz || (g0 + (uint32_t)i == 0 && o != 0) || (at_end && o != nnz))
+      atomicMin(err_offsets, (unsigned long long)(g0 + i - (at_end ? 1 : 0)));
     offs[i] = o < 0 ? 0 : (o > nnz ? nnz : o);
   }
   __syncthreads();
+  for (int i = threadIdx.x; i < nb; i += kBlock)
+    if (offs[i] > offs[i + 1]) atomicMin(err_offsets, (unsigned long long)(g0 + i));
   const int64_t s = offs[0], e = offs[nb];
   for (int64_t j = s + threadIdx.x; j < e; j += kBlock) {
     int lo = 0, hi = nb;                           // offs[lo] <= j < offs[hi]
@@ -549,7 +556,8 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update(
     const DmtTableMeta* __restrict__ meta, const uint64_t* __restrict__ pk, int64_t nnz, uint32_t B,
     uint32_t nbags, uint32_t total_rows, const float* __restrict__ grad,
     float* __restrict__ partials, int Dmax, int64_t ntiles, int64_t blocks_per_xcd, float lr,
-    float eps) {
+    float eps, const unsigned long long* __restrict__ err_offsets) {
+  if (*err_offsets != ~0ULL) return;              // malformed offsets: the records mean nothing
   constexpr int GL = 1 << LG, NG = kBlock >> LG;
   constexpr int eb = TD == DMT_F32 ? 4 : 2;
   using Chunk = typename RowChunk<TD>::type;
@@ -807,7 +815,8 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update_wave(
     const DmtTableMeta* __restrict__ meta, const uint64_t* __restrict__ pk, int64_t nnz, uint32_t B,
     uint32_t nbags, uint32_t total_rows, const float* __restrict__ grad,
     float* __restrict__ partials, int Dmax, int64_t ntiles, int64_t blocks_per_xcd, float lr,
-    float eps) {
+    float eps, const unsigned long long* __restrict__ err_offsets) {
+  if (*err_offsets != ~0ULL) return;              // malformed offsets: the records mean nothing
   constexpr int NW = kBlock / 64;
   constexpr int eb = TD == DMT_F32 ? 4 : 2;
   using Vec = typename LaneVec<EPL>::type;
@@ -1043,7 +1052,9 @@ template <int TD>
 __global__ __launch_bounds__(kBlock) void bwd_fixup_update(
     const DmtTableMeta* __restrict__ meta, uint32_t B, uint32_t nbags,
     const uint64_t* __restrict__ pk, int64_t nnz, uint32_t total_rows,
-    const float* __restrict__ partials, int Dmax, int log2_gl, int64_t ntiles, float lr, float eps) {
+    const float* __restrict__ partials, int Dmax, int log2_gl, int64_t ntiles, float lr, float eps,
+    const unsigned long long* __restrict__ err_offsets) {
+  if (*err_offsets != ~0ULL) return;
   const int GL = 1 << log2_gl;
   const int64_t t0 = (int64_t)blockIdx.x * (kBlock >> log2_gl) + (threadIdx.x >> log2_gl);
   if (t0 >= ntiles - 1) return;
@@ -1154,7 +1165,7 @@ void launch_reduce_wave(const ReduceCall& c) {
                                             : bwd_reduce_update_wave<TD, EPL, false>;
   timed_launch(c.plan, DMT_K_BWD_REDUCE_UPDATE, c.s, kernel, per_xcd * 8, kBlock, c.plan->d_meta,
                c.sorted, c.nnz, (uint32_t)c.B, c.nbags, c.total_rows, c.grad, c.w->partials,
-               c.plan->max_dim, c.w->ntiles, per_xcd, c.lr, c.eps);
+               c.plan->max_dim, c.w->ntiles, per_xcd, c.lr, c.eps, c.plan->d_error + 1);
 }
 
 template <int TD, int LG>
@@ -1165,7 +1176,7 @@ void launch_reduce_grouped(const ReduceCall& c) {
                                             : bwd_reduce_update<TD, LG, false>;
   timed_launch(c.plan, DMT_K_BWD_REDUCE_UPDATE, c.s, kernel, per_xcd * 8, kBlock, c.plan->d_meta,
                c.sorted, c.nnz, (uint32_t)c.B, c.nbags, c.total_rows, c.grad, c.w->partials,
-               c.plan->max_dim, c.w->ntiles, per_xcd, c.lr, c.eps);
+               c.plan->max_dim, c.w->ntiles, per_xcd, c.lr, c.eps, c.plan->d_error + 1);
 }
 
 // Segment reduce + row update, then the rows whose run spans tiles.
@@ -1188,7 +1199,7 @@ void launch_reduce_and_fixup(const ReduceCall& c) {
   const int64_t blocks = (c.w->ntiles + (kBlock >> log2_gl) - 1) / (kBlock >> log2_gl);
   timed_launch(c.plan, DMT_K_BWD_FIXUP, c.s, bwd_fixup_update<TD>, blocks, kBlock, c.plan->d_meta,
                (uint32_t)c.B, c.nbags, c.sorted, c.nnz, c.total_rows, c.w->partials, max_dim,
-               log2_gl, c.w->ntiles, c.lr, c.eps);
+               log2_gl, c.w->ntiles, c.lr, c.eps, c.plan->d_error + 1);
 }
 
 }  // namespace
@@ -1198,11 +1209,12 @@ extern "C" size_t dmt_bwd_workspace_bytes(const dmt_plan* plan, int64_t B, int64
   return carve(plan, nnz, nullptr).bytes;
 }
 
-extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const int32_t* indices,
-                                                  const int64_t* offsets, int64_t B, int64_t nnz,
-                                                  const float* grad_pooled, float lr, float eps,
-                                                  void* workspace, size_t workspace_bytes,
-                                                  void* stream, const dmt_bwd_debug* dbg) {
+// Validation and launches of the update; `workspace` is any device memory of at least
+// carve().bytes bytes, 256-byte aligned.  Allocates nothing.
+static dmt_status bwd_update_run(const dmt_plan* plan, const int32_t* indices,
+                                 const int64_t* offsets, int64_t B, int64_t nnz,
+                                 const float* grad_pooled, float lr, float eps, void* workspace,
+                                 size_t workspace_bytes, void* stream, const dmt_bwd_debug* dbg) {
   if (!plan || !offsets || !grad_pooled) return DMT_EINVAL;
   if (B <= 0 || B > plan->max_batch || nnz < 0 || nnz > plan->max_nnz) return DMT_EINVAL;
   if (nnz > 0 && !indices) return DMT_EINVAL;
@@ -1228,7 +1240,7 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
     const int64_t key_blocks = ((int64_t)nbags + (1 << log2_bpb) - 1) >> log2_bpb;
     timed_launch(plan, DMT_K_BWD_KEYS, s, bwd_build_keys, key_blocks, kBlock, plan->d_meta, indices,
                  offsets, (uint32_t)B, nbags, nnz, (int)plan->F, w.pk_a, log2_bpb, w.seg_begin,
-                 w.seg_blk, w.blk_table, plan->row_shards ? nullptr : plan->d_error);
+                 w.seg_blk, w.blk_table, plan->row_shards ? nullptr : plan->d_error, plan->d_error + 1);
 
     // stable LSD radix sort inside every table over the bits a row id of the largest table
     // (or its one-past-the-end inert id) can set
@@ -1277,4 +1289,13 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
                        dbg->num_unique);
   }
   return hipGetLastError() == hipSuccess ? DMT_OK : DMT_EHIP;
+}
+
+extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const int32_t* indices,
+                                                  const int64_t* offsets, int64_t B, int64_t nnz,
+                                                  const float* grad_pooled, float lr, float eps,
+                                                  void* workspace, size_t workspace_bytes,
+                                                  void* stream, const dmt_bwd_debug* dbg) {
+  return bwd_update_run(plan, indices, offsets, B, nnz, grad_pooled, lr, eps, workspace,
+                        workspace_bytes, stream, dbg);
 }

@@ -64,7 +64,8 @@ struct dmt_plan {
   DmtTableMeta* d_meta = nullptr;          // [F]
   int32_t* d_class_tables = nullptr;       // [F]
   int64_t* d_row_base = nullptr;           // [F+1]
-  unsigned long long* d_error = nullptr;   // smallest bad position, ~0 = none
+  unsigned long long* d_error = nullptr;   // [0] smallest bad id position, [1] first bag with
+                                           // malformed offsets; ~0 = none
   mutable DmtProfile prof;
 };
 

@@ -156,19 +156,19 @@ extern "C" dmt_status dmt_plan_bind(dmt_plan* plan, const void* const* tables,
     DMT_HIP_TRY(hipMalloc((void**)&plan->d_meta, sizeof(DmtTableMeta) * plan->F));
     DMT_HIP_TRY(hipMalloc((void**)&plan->d_class_tables, sizeof(int32_t) * plan->F));
     DMT_HIP_TRY(hipMalloc((void**)&plan->d_row_base, sizeof(int64_t) * (plan->F + 1)));
-    DMT_HIP_TRY(hipMalloc((void**)&plan->d_error, sizeof(unsigned long long)));
+    DMT_HIP_TRY(hipMalloc((void**)&plan->d_error, 2 * sizeof(unsigned long long)));
   }
   std::vector<int64_t> row_base(plan->F + 1);
   for (int32_t f = 0; f < plan->F; ++f) row_base[f] = plan->meta[f].row_base;
   row_base[plan->F] = plan->total_rows;
-  const unsigned long long none = ~0ULL;
+  const unsigned long long none[2] = {~0ULL, ~0ULL};
   DMT_HIP_TRY(hipMemcpy(plan->d_meta, plan->meta.data(), sizeof(DmtTableMeta) * plan->F,
                         hipMemcpyHostToDevice));
   DMT_HIP_TRY(hipMemcpy(plan->d_class_tables, plan->class_tables.data(),
                         sizeof(int32_t) * plan->F, hipMemcpyHostToDevice));
   DMT_HIP_TRY(hipMemcpy(plan->d_row_base, row_base.data(), sizeof(int64_t) * (plan->F + 1),
                         hipMemcpyHostToDevice));
-  DMT_HIP_TRY(hipMemcpy(plan->d_error, &none, sizeof(none), hipMemcpyHostToDevice));
+  DMT_HIP_TRY(hipMemcpy(plan->d_error, none, sizeof(none), hipMemcpyHostToDevice));
   plan->bound = true;
   return DMT_OK;
 }
@@ -192,14 +192,19 @@ extern "C" dmt_status dmt_last_device_error(const dmt_plan* plan, void* stream,
   *bad_position = -1;
   if (!plan->bound) return DMT_EINVAL;
   hipStream_t s = (hipStream_t)stream;
-  unsigned long long v = ~0ULL;
-  const unsigned long long none = ~0ULL;
-  DMT_HIP_TRY(hipMemcpyAsync(&v, plan->d_error, sizeof(v), hipMemcpyDeviceToHost, s));
+  // [0] smallest position of an id outside its table, [1] first bag whose offsets are malformed
+  unsigned long long v[2] = {~0ULL, ~0ULL};
+  const unsigned long long none[2] = {~0ULL, ~0ULL};
+  DMT_HIP_TRY(hipMemcpyAsync(v, plan->d_error, sizeof(v), hipMemcpyDeviceToHost, s));
   DMT_HIP_TRY(hipStreamSynchronize(s));
-  if (v == none) return DMT_OK;
-  DMT_HIP_TRY(hipMemcpyAsync(plan->d_error, &none, sizeof(none), hipMemcpyHostToDevice, s));
+  if (v[0] == none[0] && v[1] == none[1]) return DMT_OK;
+  DMT_HIP_TRY(hipMemcpyAsync(plan->d_error, none, sizeof(none), hipMemcpyHostToDevice, s));
   DMT_HIP_TRY(hipStreamSynchronize(s));
-  *bad_position = (int64_t)v;
+  if (v[1] != none[1]) {
+    *bad_position = (int64_t)v[1];
+    return DMT_EINVAL;
+  }
+  *bad_position = (int64_t)v[0];
   return DMT_EBOUNDS;
 }
 

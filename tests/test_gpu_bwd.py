@@ -171,6 +171,39 @@ def test_out_of_range_ids_are_skipped():
         assert_close(to_f64(dw.tables[f][torch.from_numpy(rows).cuda()]), want, 2e-2, "rows")
 
 
+@pytest.mark.parametrize("case", ["first_not_zero", "descending", "last_not_nnz", "beyond_nnz"])
+def test_malformed_offsets_update_nothing_and_are_reported(case):
+    # the host cannot see device offsets; the key build checks them and the update is skipped
+    w = wl.scaled(wl.mid(True), max_rows=100, batch=16, num_tables=8)
+    dw = DeviceWorkload(w, with_state=True)
+    idx, off = wl.lookup_batch(w)
+    grad = wl.grad_pooled(w)
+    bad = off.copy()
+    nbags = len(off) - 1
+    if case == "first_not_zero":
+        bad[0], where = 3, 0
+    elif case == "descending":
+        bad[41], where = bad[40] - 1 if bad[40] > 0 else bad[42] + 1, 40
+        if bad[41] > bad[42]:
+            where = 41
+    elif case == "last_not_nnz":
+        bad[-1], where = len(idx) - 2, nbags - 1
+    else:
+        bad[-1], where = len(idx) + 5, nbags - 1
+    before = [t.clone() for t in dw.tables]
+    run_bwd(dw, idx, bad, grad, w.lr, w.eps, debug=False)
+    with pytest.raises(dw.dmt.DmtError) as e:
+        dw.dmt.dmt_last_device_error(dw.plan)
+    assert e.value.code == 1 and e.value.position == where           # DMT_EINVAL, first bad bag
+    for a, b, s in zip(dw.tables, before, dw.states):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+        assert int((s != 0).sum()) == 0
+    # the record is cleared and a well-formed call works afterwards
+    run_bwd(dw, idx, off, grad, w.lr, w.eps, debug=False)
+    assert dw.dmt.dmt_last_device_error(dw.plan) == -1
+    assert sum(int((s != 0).sum()) for s in dw.states) > 0
+
+
 def _degenerate(ids_of):
     w = wl.scaled(wl.mid(True), max_rows=5000, batch=64, num_tables=2)
     w.table_to_tower = [0, 0]
