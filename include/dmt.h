@@ -341,6 +341,28 @@ dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const int32_t* indi
                                        const dmt_bwd_debug* dbg);
 
 /*
+ * dmt_tower_lookup_bwd_update for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving / training loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels and bit-identical table and state updates,
+ * but the scratch memory is an array of DMT_BWD_NOALLOC_SCRATCH_BYTES bytes inside the library
+ * (one copy on every GPU the library runs on, held until the process ends) and there are no
+ * parity exports.  The call allocates nothing on host or device; the first call on a device
+ * looks up the array's address there.
+ *   DMT_ENOMEM  dmt_bwd_workspace_bytes(plan, B, nnz) exceeds the array (about 28 bytes per
+ *               lookup at dim 128: roughly 1.1 million lookups); nothing is launched
+ * All calls on one GPU share that GPU's array, whatever their plan or stream: calls that
+ * overlap in time on one GPU race and must be ordered by the caller.  The array keeps the
+ * previous call's contents; no kernel of the update reads scratch it has not written in the
+ * same call, so nothing needs clearing between calls.
+ */
+#define DMT_BWD_NOALLOC_SCRATCH_BYTES (32u << 20)
+size_t dmt_bwd_noalloc_scratch_bytes(void);
+dmt_status dmt_tower_lookup_bwd_update_noalloc(const dmt_plan* plan, const int32_t* indices,
+                                               const int64_t* offsets, int64_t B, int64_t nnz,
+                                               const float* grad_pooled, float lr, float eps,
+                                               void* stream);
+
+/*
  * Tower Partitioner (paper Sec. 3.3): a balanced feature -> tower map learned from the
  * embeddings a model produces.  Three calls, one per stage; the caller moves the small
  * |F| x |F| matrix from the device to the host between the first and the second.

@@ -81,6 +81,9 @@ def _load() -> ctypes.CDLL:
     lib.dmt_bwd_workspace_bytes.argtypes = [vp, i64, i64]
     lib.dmt_bwd_workspace_bytes.restype = sz
     lib.dmt_tower_lookup_bwd_update.argtypes = [vp, vp, vp, i64, i64, vp, f32, f32, vp, sz, vp, vp]
+    lib.dmt_bwd_noalloc_scratch_bytes.argtypes = []
+    lib.dmt_bwd_noalloc_scratch_bytes.restype = sz
+    lib.dmt_tower_lookup_bwd_update_noalloc.argtypes = [vp, vp, vp, i64, i64, vp, f32, f32, vp]
     lib.dmt_last_device_error.argtypes = [vp, vp, ctypes.POINTER(i64)]
     lib.dmt_kernel_name.restype = ctypes.c_char_p
     lib.dmt_kernel_name.argtypes = [i32]
@@ -110,7 +113,8 @@ EXPORTS = ["dmt_status_str", "dmt_plan_create", "dmt_plan_destroy", "dmt_plan_la
            "dmt_last_device_error", "dmt_kernel_name", "dmt_profile_enable", "dmt_profile_read",
            "dmt_calibration_copy", "dmt_tp_workspace_bytes", "dmt_tp_interaction",
            "dmt_tp_embed", "dmt_tp_kmeans", "dmt_sptt_peer_order", "dmt_sptt_peer_permute",
-           "dmt_sptt_shuffle", "dmt_plan_set_row_shards"]
+           "dmt_sptt_shuffle", "dmt_plan_set_row_shards", "dmt_bwd_noalloc_scratch_bytes",
+           "dmt_tower_lookup_bwd_update_noalloc"]
 
 DMT_K_COUNT = 15
 TP_STRATEGY_CODE = {"diverse": 0, "coherent": 1}
@@ -293,6 +297,18 @@ def dmt_tower_lookup_bwd_update(plan: dmt_plan, indices: torch.Tensor, offsets: 
     _check("dmt_tower_lookup_bwd_update", _lib.dmt_tower_lookup_bwd_update(
         plan.handle, _ptr(indices), _ptr(offsets), B, indices.numel(), _ptr(grad_pooled),
         lr, eps, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream), dbg))
+
+
+def dmt_bwd_noalloc_scratch_bytes() -> int:
+    return int(_lib.dmt_bwd_noalloc_scratch_bytes())
+
+
+def dmt_tower_lookup_bwd_update_noalloc(plan: dmt_plan, indices: torch.Tensor, offsets: torch.Tensor,
+                                        B: int, grad_pooled: torch.Tensor, lr: float, eps: float,
+                                        stream=None) -> None:
+    _check("dmt_tower_lookup_bwd_update_noalloc", _lib.dmt_tower_lookup_bwd_update_noalloc(
+        plan.handle, _ptr(indices), _ptr(offsets), B, indices.numel(), _ptr(grad_pooled),
+        lr, eps, _stream(stream)))
 
 
 def dmt_last_device_error(plan: dmt_plan, stream=None) -> int:

@@ -19,6 +19,7 @@
 // checks this, records the first bag that breaks it, and the reduce and fix-up kernels
 // then return without touching a row (dmt_last_device_error reports DMT_EINVAL).
 #include <algorithm>
+#include <mutex>
 #include <type_traits>
 
 #include "dmt_internal.h"
@@ -1298,4 +1299,45 @@ extern "C" dmt_status dmt_tower_lookup_bwd_update(const dmt_plan* plan, const in
                                                   void* stream, const dmt_bwd_debug* dbg) {
   return bwd_update_run(plan, indices, offsets, B, nnz, grad_pooled, lr, eps, workspace,
                         workspace_bytes, stream, dbg);
+}
+
+// ------------------------------------------- the update on the library's own scratch memory
+
+// Scratch of dmt_tower_lookup_bwd_update_noalloc: one array per GPU the library runs on, held
+// until the process ends.  Host code never uses the array's name as an address: it asks the
+// runtime for the array's device address once per device and passes that pointer on.
+static __device__ __align__(256) unsigned char scratch[DMT_BWD_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each device, once resolved
+}  // namespace
+
+extern "C" size_t dmt_bwd_noalloc_scratch_bytes(void) { return DMT_BWD_NOALLOC_SCRATCH_BYTES; }
+
+extern "C" dmt_status dmt_tower_lookup_bwd_update_noalloc(const dmt_plan* plan,
+                                                          const int32_t* indices,
+                                                          const int64_t* offsets, int64_t B,
+                                                          int64_t nnz, const float* grad_pooled,
+                                                          float lr, float eps, void* stream) {
+  if (!plan || B <= 0 || nnz < 0) return DMT_EINVAL;
+  // the size check comes first: nothing is resolved or launched for a call that cannot fit
+  if (carve(plan, nnz, nullptr).bytes > (size_t)DMT_BWD_NOALLOC_SCRATCH_BYTES) return DMT_ENOMEM;
+  int dev = -1;
+  DMT_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return DMT_ENOTSUP;
+  void* ptr = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+      void* p = nullptr;
+      DMT_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+      if (!p) return DMT_EHIP;
+      g_scratch_ptr[dev] = p;
+    }
+    ptr = g_scratch_ptr[dev];
+  }
+  return bwd_update_run(plan, indices, offsets, B, nnz, grad_pooled, lr, eps, ptr,
+                        (size_t)DMT_BWD_NOALLOC_SCRATCH_BYTES, stream, nullptr);
 }
