@@ -1036,6 +1036,251 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update_wave(
   drain();
 }
 
+// The tile walk for rows of at most 128 columns, built to spend as few instructions per sorted
+// record as the hardware allows and to keep a wave's row updates off its critical path.
+//  * One wave per tile of kReduceTile records.  A tile is cut into chunks of up to 64
+//    consecutive records of ONE table, one record per lane (two chunks, more only where the
+//    tile straddles a table boundary), so everything a table decides (row width, gradient
+//    base, row and state base) sits in scalar registers.
+//  * Each lane reads one record and the record after it; "my key differs from the next one"
+//    is one ballot, the mask of run TAILS.  Nothing else about runs is ever computed.
+//  * The walk proper is, per record: one v_readlane (its gradient offset), one buffer load of
+//    the slice (two columns per lane), two adds, one scalar bit test.  kLeanBatch slices are
+//    requested together.
+//  * At a tail the sum is parked in a ring of 8 LDS slots, and the lane number of the tail
+//    record is packed into a scalar register.  Row updates come off the ring four at a time,
+//    ONE instruction for four rows (16 lanes a row, 8 columns a lane), in two halves: at a
+//    batch boundary the rows and states of the four oldest parked runs are REQUESTED (the
+//    row's key comes from the tail record's lane by ds_bpermute, the addresses from the
+//    chunk's scalars); the walk goes on, and at the next boundary the update is computed and
+//    stored.  The requests are older than the next batch's slices and the memory counter
+//    retires in order, so the wave waits once for both instead of once for each.
+//  * Same partial-slot protocol and the same float32 summation order as the other walks.
+constexpr int kLeanQueue = 8;
+constexpr int kLeanGroup = 4;                    // rows updated by one instruction
+constexpr int kLeanBatch = 8;                    // gradient slices requested together
+static_assert(kLeanBatch <= kLeanQueue && 64 % kLeanBatch == 0,
+              "every record of a batch may end a run, and all of them must fit the emptied ring");
+
+template <int TD>
+__global__ __launch_bounds__(kBlock) void bwd_reduce_update_lean(
+    const DmtTableMeta* __restrict__ meta, const uint64_t* __restrict__ pk, int64_t nnz, uint32_t B,
+    uint32_t bag_mul, uint32_t bag_shift, uint32_t F, const float* __restrict__ grad,
+    float* __restrict__ partials, int Dmax, int64_t ntiles, int64_t blocks_per_xcd, float lr,
+    float eps, const unsigned long long* __restrict__ err_offsets) {
+  if (*err_offsets != ~0ULL) return;              // malformed offsets: the records mean nothing
+  constexpr int NW = kBlock / 64;
+  constexpr int eb = TD == DMT_F32 ? 4 : 2;
+  using Chunk = std::conditional_t<TD == DMT_F32, float4, uint4>;
+  constexpr int NC = TD == DMT_F32 ? 2 : 1;
+  __shared__ float q_g[NW][kLeanQueue][128];
+
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const int64_t tb = (int64_t)(blockIdx.x & 7) * blocks_per_xcd + (blockIdx.x >> 3);
+  const int64_t t = tb * NW + wave;
+  if (t >= ntiles) return;
+  const int64_t p0 = t * kReduceTile;
+  const int n = (int)min((int64_t)kReduceTile, nnz - p0);
+  const int qd = lane >> 4, ql = lane & 15;        // row updates: quarter-wave qd, 8 columns from 8 ql
+  float* const qbase = &q_g[wave][0][0];
+
+  uint32_t from_left = 0;                          // the open run began in an earlier tile
+  if (p0 > 0)
+    from_left = __builtin_amdgcn_readfirstlane((uint32_t)(pk[p0 - 1] >> 32)) ==
+                __builtin_amdgcn_readfirstlane((uint32_t)(pk[p0] >> 32));
+  bool open_end = false;                           // the last record's run goes on in the next tile
+  int last_D = 0;
+  float2 acc = make_float2(0.f, 0.f);
+  // the ring: runs parked, runs whose row and state are requested, runs updated (P >= I >= C,
+  // P - C <= 8, I - C <= 4); run e lives in slot e & 7, byte e & 7 of qcodes is 4 x the lane
+  // of its tail record
+  uint32_t P = 0, I = 0, C = 0;
+  uint64_t qcodes = 0;
+
+  for (int pos = 0; pos < n;) {
+    const int nrem = n - pos;
+    const int64_t idx = p0 + pos + lane;
+    uint64_t rec = ~0ULL;
+    if (lane < nrem) rec = __builtin_nontemporal_load(pk + idx);
+    const uint32_t key_l = (uint32_t)(rec >> 32), bag_l = (uint32_t)rec;
+    // the key after each record: the next lane's, and for the last of the (up to) 64 records
+    // read here the key of the record behind them, one scalar load
+    const int nread = min(nrem, 64);
+    const int64_t behind = p0 + pos + nread;
+    uint32_t key_behind = ~key_l;                  // differs: the last record of all ends its run
+    if (behind < nnz) key_behind = __builtin_amdgcn_readfirstlane((uint32_t)(pk[behind] >> 32));
+    const uint32_t down = (uint32_t)__shfl_down((int)key_l, 1);
+    const uint32_t next_key_l = lane == nread - 1 ? key_behind : down;
+    const uint32_t f_l = B == 1 ? bag_l : (__umulhi(bag_l, bag_mul) >> bag_shift);   // bag / B
+    const uint32_t f = __builtin_amdgcn_readfirstlane(f_l);
+    const int cnt = __popcll(__ballot(lane < nrem && f_l == f));   // records sorted by table: a prefix
+    if (f >= F) {                                  // not a record the key build wrote
+      acc = make_float2(0.f, 0.f);
+      from_left = 0;
+      open_end = false;
+      pos += cnt;
+      continue;
+    }
+    const DmtTableMeta& m = meta[f];
+    const int D = m.D;
+    const uint32_t row_base = (uint32_t)m.row_base, rows = (uint32_t)m.rows;
+    const char* const table = (const char*)m.table;
+    float* const state = m.state;
+    const uint32_t rowbytes = (uint32_t)D * eb;
+    const char* const gbase = (const char*)(grad + (int64_t)B * m.out_prefix + m.col_off);
+    const uint32_t tw4 = (uint32_t)m.tower_width * 4u;
+    // (lanes past the chunk name sample 0's slice: every readlane below yields a valid offset)
+    const uint32_t boff_l = lane < cnt ? (bag_l - f * B) * tw4 : 0u;
+    const bool in_l = lane < cnt && (key_l - row_base) < rows;     // a row of this table
+    const bool tail_l = in_l && next_key_l != key_l;
+    const uint64_t tm = __ballot(tail_l);
+    const bool last_in = (__ballot(in_l) >> (cnt - 1)) & 1;
+    const bool lane_on = lane * 2 < D;
+    // lanes past the row's width read the row's first columns instead (every load stays
+    // unconditional and in bounds) and park zeros
+    const uint32_t lane_off = lane_on ? (uint32_t)lane * 8u : 0u;
+    const bool col_on = ql * 8 < D, col_hi = ql * 8 + 4 < D;
+    const float inv_D = __builtin_amdgcn_rcpf((float)D);
+
+    // rows and states requested for runs C .. I - 1, one run per quarter-wave
+    Chunk pw[NC];
+    float pst = 0.f;
+    uint32_t prow = 0;
+    // Requests the row and the state of runs I .. I + g - 1 (g <= 4).  No load is conditional:
+    // a quarter-wave with no run, and lanes past the row's width, read row 0 / the row's
+    // first columns.
+    auto request = [&](uint32_t g) {
+      const uint32_t slot = (I + qd) & 7u;
+      const uint32_t code = (uint32_t)(qcodes >> (slot * 8)) & 0xffu;
+      const uint32_t k = (uint32_t)__builtin_amdgcn_ds_bpermute((int)code, (int)key_l);
+      prow = (uint32_t)qd < g ? k - row_base : 0u;
+      const char* wp = table + (uint64_t)prow * rowbytes + (col_on ? ql * (8 * eb) : 0);
+      pst = dmt::nt_load(state + prow);
+      if constexpr (TD == DMT_F32) {
+        pw[0] = dmt::nt_load((const float4*)wp);
+        pw[1] = dmt::nt_load((const float4*)wp + (col_hi ? 1 : 0));
+      } else {
+        pw[0] = dmt::nt_load((const uint4*)wp);
+      }
+      I += g;
+    };
+    // Updates the rows requested last: runs C .. I - 1.
+    auto update = [&]() {
+      const bool on = (uint32_t)qd < I - C;
+      wave_lds_sync();                             // the parked sums
+      const float4* gq = (const float4*)(qbase + ((C + qd) & 7u) * 128 + ql * 8);
+      const float4 g0 = gq[0], g1 = gq[1];
+      float ss = g0.x * g0.x + g0.y * g0.y + g0.z * g0.z + g0.w * g0.w + g1.x * g1.x +
+                 g1.y * g1.y + g1.z * g1.z + g1.w * g1.w;
+      ss = group_sum<4>(ss);
+      const float sn = pst + ss * inv_D;
+      const float step = lr * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(sn) + eps);
+      char* wp = (char*)table + (uint64_t)prow * rowbytes + (col_on ? ql * (8 * eb) : 0);
+      if constexpr (TD == DMT_F32) {
+        float4 v = pw[0];
+        v.x -= step * g0.x; v.y -= step * g0.y; v.z -= step * g0.z; v.w -= step * g0.w;
+        if (on && col_on) dmt::nt_store(v, (float4*)wp);
+        v = pw[1];
+        v.x -= step * g1.x; v.y -= step * g1.y; v.z -= step * g1.z; v.w -= step * g1.w;
+        if (on && col_hi) dmt::nt_store(v, (float4*)wp + 1);
+      } else {
+        float a, b, c, d;
+        uint4 o;
+        dmt::unpack2<TD>(pw[0].x, a, b);
+        dmt::unpack2<TD>(pw[0].y, c, d);
+        a -= step * g0.x; b -= step * g0.y; c -= step * g0.z; d -= step * g0.w;
+        o.x = dmt::pack2<TD>(a, b);
+        o.y = dmt::pack2<TD>(c, d);
+        dmt::unpack2<TD>(pw[0].z, a, b);
+        dmt::unpack2<TD>(pw[0].w, c, d);
+        a -= step * g1.x; b -= step * g1.y; c -= step * g1.z; d -= step * g1.w;
+        o.z = dmt::pack2<TD>(a, b);
+        o.w = dmt::pack2<TD>(c, d);
+        if (on && col_on) dmt::nt_store(o, (uint4*)wp);
+      }
+      if (on && ql == 0) dmt::nt_store(sn, state + prow);
+      wave_lds_sync();                             // every lane is done reading the slots
+      C = I;
+    };
+    // the run that ends at record i of this chunk is complete
+    auto close_run = [&](int i) {
+      const float2 a = lane_on ? acc : make_float2(0.f, 0.f);
+      if (from_left != 0) {
+        if (lane * 2 < Dmax) ((float2*)(partials + 2 * t * Dmax))[lane] = a;
+        from_left = 0;
+      } else {
+        const uint32_t sh = (P & 7u) * 8u;
+        ((float2*)(qbase + (sh << 4)))[lane] = a;
+        qcodes = (qcodes & ~(0xffULL << sh)) | ((uint64_t)(uint32_t)(i * 4) << sh);
+        ++P;
+      }
+      acc = make_float2(0.f, 0.f);
+    };
+    // This lane's two columns of record i's gradient, as a buffer load: the table's column
+    // block is the buffer, the lane's column offset the vector offset and the record's row
+    // offset the scalar offset, so a record costs no address arithmetic beyond its v_readlane
+    // (and a read past the block would return zeros instead of faulting).
+    const __amdgpu_buffer_rsrc_t gbuf = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)gbase, 0, (int)((B - 1) * tw4 + (uint32_t)D * 4u), 0x00020000);
+    auto slice = [&](int i) {
+      const uint32_t bo = __builtin_amdgcn_readlane(boff_l, i);
+      const dmt::dmt_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(gbuf, (int)lane_off, (int)bo, 0);
+      return make_float2(__uint_as_float(v.x), __uint_as_float(v.y));
+    };
+
+    // Parked runs name lanes of this chunk's key_l and live on its scalars, so the ring is
+    // empty when the chunk is left.
+    for (int i0 = 0;; i0 += kLeanBatch) {
+      const bool more = i0 < cnt;
+      const uint32_t tails = (uint32_t)(tm >> (i0 & 63)) & ((1u << kLeanBatch) - 1);
+      // what was requested at the last boundary has had a batch's time to arrive
+      if (I != C) update();
+      // room for this batch's tails (seldom short), or everything out at the chunk's end
+      while (more ? P - C + __popc(tails) > (uint32_t)kLeanQueue : P != C) {
+        request(min(P - I, (uint32_t)kLeanGroup));
+        update();
+      }
+      if (!more) break;
+      if (P - I >= (uint32_t)kLeanGroup) request(kLeanGroup);
+      float2 g[kLeanBatch];
+      if (i0 + kLeanBatch <= cnt) {
+#pragma unroll
+        for (int u = 0; u < kLeanBatch; ++u) g[u] = slice(i0 + u);
+#pragma unroll
+        for (int u = 0; u < kLeanBatch; ++u) {
+          acc.x += g[u].x;
+          acc.y += g[u].y;
+          if ((tails >> u) & 1) close_run(i0 + u);
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < kLeanBatch; ++u) g[u] = slice((i0 + u) & 63);
+#pragma unroll
+        for (int u = 0; u < kLeanBatch; ++u) {
+          if (i0 + u < cnt) {
+            acc.x += g[u].x;
+            acc.y += g[u].y;
+            if ((tails >> u) & 1) close_run(i0 + u);
+          }
+        }
+      }
+    }
+    open_end = last_in && !((tm >> (cnt - 1)) & 1);
+    last_D = D;
+    if (!last_in) {                                // ids outside the table end its records: nothing to carry
+      acc = make_float2(0.f, 0.f);
+      from_left = 0;
+    }
+    pos += cnt;
+  }
+  // (the last chunk's table decides which lanes hold columns; the others hold what they read
+  // in place of them and store zeros)
+  if (open_end && lane * 2 < Dmax)
+    ((float2*)(partials + (2 * t + (from_left ? 0 : 1)) * Dmax))[lane] =
+        lane * 2 < last_D ? acc : make_float2(0.f, 0.f);
+}
+
 // Table that owns global row id `gid` (row_base has F + 1 ascending entries).
 __device__ __forceinline__ uint32_t table_of(const int64_t* __restrict__ row_base, int F,
                                              uint32_t gid) {
@@ -1169,6 +1414,29 @@ void launch_reduce_wave(const ReduceCall& c) {
                c.plan->max_dim, c.w->ntiles, per_xcd, c.lr, c.eps, c.plan->d_error + 1);
 }
 
+// bag / B for bag < 2^31 as (bag * mul) >> (32 + shift); B = 1 is handled by the kernel.
+void bag_divider(uint32_t B, uint32_t& mul, uint32_t& shift) {
+  uint32_t l = 0;
+  while ((1ull << l) < B) ++l;
+  mul = 0;
+  shift = 0;
+  if (B <= 1) return;
+  mul = (uint32_t)(((1ull << (31 + l)) + B - 1) / B);
+  shift = l - 1;
+}
+
+template <int TD>
+void launch_reduce_lean(const ReduceCall& c) {
+  constexpr int kWavesPerBlock = kBlock / 64;
+  const int64_t per_xcd = ((c.w->ntiles + kWavesPerBlock - 1) / kWavesPerBlock + 7) / 8;
+  uint32_t mul, shift;
+  bag_divider((uint32_t)c.B, mul, shift);
+  timed_launch(c.plan, DMT_K_BWD_REDUCE_UPDATE, c.s, bwd_reduce_update_lean<TD>, per_xcd * 8, kBlock,
+               c.plan->d_meta, c.sorted, c.nnz, (uint32_t)c.B, mul, shift, (uint32_t)c.plan->F, c.grad,
+               c.w->partials, c.plan->max_dim, c.w->ntiles, per_xcd, c.lr, c.eps,
+               c.plan->d_error + 1);
+}
+
 template <int TD, int LG>
 void launch_reduce_grouped(const ReduceCall& c) {
   const int64_t blocks = (c.w->ntiles + (kBlock >> LG) - 1) / (kBlock >> LG);
@@ -1185,8 +1453,14 @@ template <int TD>
 void launch_reduce_and_fixup(const ReduceCall& c) {
   const int max_dim = c.plan->max_dim;
   const int log2_gl = std::max(2, ilog2_ceil(max_dim / 4));       // lanes that hold one row
-  const bool wave_kernel = (max_dim == 128 || max_dim == 256) && dmt::env_int("DMT_BWD_WAVE", 1) != 0;
-  if (wave_kernel) {
+  const bool wave_kernel = (max_dim == 128 || max_dim == 256) && c.plan->sw.bwd_kernel != 2;
+  // the lean walk addresses a gradient slice by a 32-bit byte offset inside its tower's block
+  int64_t widest = 0;
+  for (int32_t t = 0; t < c.plan->T; ++t) widest = std::max<int64_t>(widest, c.plan->tower_width[t]);
+  const bool lean = max_dim <= 128 && c.B * widest * 4 < (1LL << 32) && c.plan->sw.bwd_kernel == 0;
+  if (lean) {
+    launch_reduce_lean<TD>(c);
+  } else if (wave_kernel) {
     if (max_dim == 128) launch_reduce_wave<TD, 2>(c); else launch_reduce_wave<TD, 4>(c);
   } else {
     switch (log2_gl) {
@@ -1236,7 +1510,7 @@ static dmt_status bwd_update_run(const dmt_plan* plan, const int32_t* indices,
     // keys; bags per block: about 4096 lookups' worth (a power of two, at most kKeysMaxBags)
     const double mean_len = (double)nnz / (double)nbags;
     int log2_bpb = ilog2_ceil((int64_t)(4096.0 / (mean_len > 1.0 ? mean_len : 1.0) + 0.5));
-    log2_bpb = dmt::env_int("DMT_KEYS_LG", log2_bpb);
+    if (plan->sw.keys_lg >= 0) log2_bpb = plan->sw.keys_lg;
     log2_bpb = log2_bpb < 4 ? 4 : (log2_bpb > 10 ? 10 : log2_bpb);
     const int64_t key_blocks = ((int64_t)nbags + (1 << log2_bpb) - 1) >> log2_bpb;
     timed_launch(plan, DMT_K_BWD_KEYS, s, bwd_build_keys, key_blocks, kBlock, plan->d_meta, indices,

@@ -5,7 +5,6 @@
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-#include <stdlib.h>
 
 #include "dmt.h"
 
@@ -173,12 +172,6 @@ __device__ __forceinline__ uint32_t gload(const uint32_t* p) { return *(const DM
 __device__ __forceinline__ void gstore(uint32_t v, uint32_t* p) { *(DMT_GLOBAL uint32_t*)p = v; }
 __device__ __forceinline__ uint16_t gload(const uint16_t* p) { return *(const DMT_GLOBAL uint16_t*)p; }
 __device__ __forceinline__ void gstore(uint16_t v, uint16_t* p) { *(DMT_GLOBAL uint16_t*)p = v; }
-
-// Development knob: integer from the environment, `dflt` when unset.
-static inline int env_int(const char* name, int dflt) {
-  const char* v = getenv(name);
-  return (v && *v) ? atoi(v) : dflt;
-}
 
 }  // namespace dmt
 

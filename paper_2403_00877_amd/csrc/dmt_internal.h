@@ -43,7 +43,21 @@ struct DmtProfile {
   std::vector<hipEvent_t> pool;
 };
 
+// Kernel-choice switches, read from the environment ONCE, when the plan is created (tests reach
+// both variants of a choice, sweeps need no rebuild); 0 / -1 = the library's own choice.
+struct DmtSwitches {
+  int tm_big = 1;        // DMT_TM_BIG=0: every contraction on the 128 x 128 kernel
+  int tm_fuse = 1;       // DMT_TM_FUSE=0: dot terms by their own kernel, not inside the projection
+  int tmb_ksplit = 0;    // DMT_TMB_KSPLIT=n: slices of every weight gradient
+  int bwd_kernel = 0;    // DMT_BWD_KERNEL=1 / 2: the wave-per-tile / lane-group segment reduce
+  int keys_lg = -1;      // DMT_KEYS_LG=l: 2^l bags per key-build block
+  int lookup_r = 0;      // DMT_LOOKUP_R=r: row slots per bag
+  int lookup_bpg = 0;    // DMT_LOOKUP_BPG=n: bags a lane group pools in turn
+  int lookup_long = -1;  // DMT_LOOKUP_LONG=n: bags longer than n ids go to whole waves (0: never)
+};
+
 struct dmt_plan {
+  DmtSwitches sw;
   int32_t F = 0, T = 0;
   dmt_dtype table_dtype = DMT_F32;
   int64_t max_batch = 0, max_nnz = 0;

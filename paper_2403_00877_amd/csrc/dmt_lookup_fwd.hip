@@ -136,11 +136,7 @@ void launch(const dmt_plan* p, const DmtDimClass& c, const int32_t* indices,
   const int32_t ntiles = tiles_per_table * c.num_tables;
   const int32_t tiles_per_xcd = (ntiles + 7) / 8;
   DmtScope scope(p, DMT_K_LOOKUP_FWD, s);
-  // Development knob: reserve unused LDS per block, to time the gather at the occupancy a kernel
-  // that also holds a Tower Module tile in LDS would leave it.
-  const int idle_lds = dmt::env_int("DMT_LOOKUP_IDLE_LDS", 0);
-  hipLaunchKernelGGL((lookup_fwd_kernel<TD, OD>), dim3(tiles_per_xcd * 8), dim3(kBlock),
-                     idle_lds > 0 && idle_lds <= 65536 ? idle_lds : 0, s,
+  hipLaunchKernelGGL((lookup_fwd_kernel<TD, OD>), dim3(tiles_per_xcd * 8), dim3(kBlock), 0, s,
                      p->d_meta, p->d_class_tables + c.first, c.D, indices, offsets, B, nnz, out,
                      log2_lpr, log2_gl, bpg, tiles_per_table, ntiles, tiles_per_xcd, long_thr,
                      p->row_shards ? nullptr : p->d_error);
@@ -166,8 +162,7 @@ extern "C" dmt_status dmt_tower_lookup_fwd(const dmt_plan* plan, const int32_t* 
   hipStream_t s = (hipStream_t)stream;
   const int eb = dmt_elt_bytes(plan->table_dtype);
   const double mean_len = (double)nnz / ((double)plan->F * (double)B);
-  const int tuned_r = dmt::env_int("DMT_LOOKUP_R", 0);
-  const int tuned_bpg = dmt::env_int("DMT_LOOKUP_BPG", 0);
+  const int tuned_r = plan->sw.lookup_r, tuned_bpg = plan->sw.lookup_bpg;
 
   for (const DmtDimClass& c : plan->classes) {
     const int log2_lpr = ilog2_ceil(c.D * eb / 16);
@@ -191,7 +186,8 @@ extern "C" dmt_status dmt_tower_lookup_fwd(const dmt_plan* plan, const int32_t* 
     // bags several times longer than the mean are pooled by whole waves (0: never)
     int long_thr = 4 * (int)(mean_len + 1.0);
     long_thr = (long_thr < 8 ? 8 : long_thr) * r;
-    long_thr = log2_gl < 6 ? dmt::env_int("DMT_LOOKUP_LONG", long_thr) : 0;
+    if (plan->sw.lookup_long >= 0) long_thr = plan->sw.lookup_long;
+    if (log2_gl >= 6) long_thr = 0;
     const int td = (int)plan->table_dtype, od = (int)out_dtype;
 #define DMT_CASE(TD, OD)                                                                      \
   if (td == TD && od == OD)                                                                   \

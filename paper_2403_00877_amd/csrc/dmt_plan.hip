@@ -1,6 +1,8 @@
 // Plan object: the static description of tables and towers (paper Sec. 2.1,
 // Sec. 3.1), the tower-major layout arithmetic, and the device-side lookup
 // tables the kernels index.
+#include <stdlib.h>
+
 #include <algorithm>
 #include <new>
 
@@ -46,6 +48,18 @@ extern "C" dmt_status dmt_plan_create(dmt_plan** out, int32_t num_tables, const 
 
   dmt_plan* p = new (std::nothrow) dmt_plan();
   if (!p) return DMT_ENOMEM;
+  auto env = [](const char* name, int dflt) {
+    const char* v = getenv(name);
+    return (v && *v) ? atoi(v) : dflt;
+  };
+  p->sw.tm_big = env("DMT_TM_BIG", 1);
+  p->sw.tm_fuse = env("DMT_TM_FUSE", 1);
+  p->sw.tmb_ksplit = env("DMT_TMB_KSPLIT", 0);
+  p->sw.bwd_kernel = env("DMT_BWD_KERNEL", 0);
+  p->sw.keys_lg = env("DMT_KEYS_LG", -1);
+  p->sw.lookup_r = env("DMT_LOOKUP_R", 0);
+  p->sw.lookup_bpg = env("DMT_LOOKUP_BPG", 0);
+  p->sw.lookup_long = env("DMT_LOOKUP_LONG", -1);
   p->F = num_tables;
   p->T = num_towers;
   p->table_dtype = table_dtype;

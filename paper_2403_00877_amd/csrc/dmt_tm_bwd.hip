@@ -497,14 +497,14 @@ inline int64_t ld_batch(int64_t count, int eb) {
 // launch of `tiles_all` output tiles (all towers) fills the 256 CUs once, as nearly as it can
 // without a second, mostly empty round of blocks: each slice at least 1024 long, a multiple
 // of 64.
-inline void choose_split(int64_t tiles_all, int64_t K, int* ksplit, int* klen) {
+inline void choose_split(const dmt_plan* p, int64_t tiles_all, int64_t K, int* ksplit, int* klen) {
   int ks = (int)std::max<int64_t>(1, std::min<int64_t>(16, 256 / std::max<int64_t>(tiles_all, 1)));
   while (ks > 1 && K / ks < 1024) --ks;
   // A long batch with few tiles (narrow outputs: the contraction is bound by memory latency,
   // one block per CU) measured faster in slices of about 4096 spread over several rounds
   // (Imbalanced: 0.54 against 0.73 ms) than in one round of very long slices.
   if (tiles_all < 256 && K / ks > 4096) ks = (int)std::min<int64_t>(16, (K + 4095) / 4096);
-  const int forced = dmt::env_int("DMT_TMB_KSPLIT", 0);
+  const int forced = p->sw.tmb_ksplit;
   if (forced > 0 && K / forced >= 128) ks = forced;
   int len = (int)((K + ks - 1) / ks);
   len = (len + 63) / 64 * 64;
@@ -564,8 +564,8 @@ dmt_status plan_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, in
     w.Op = up8(q.out_dim);
     w.kin = (int)wt;
     if (eb == 2) {
-      choose_split(tiles_proj, Bp, &w.ksplit, &w.klen);
-      choose_split(std::max<int64_t>(tiles_cross, 1), Bp, &w.ksplit_c, &w.klen_c);
+      choose_split(p, tiles_proj, Bp, &w.ksplit, &w.klen);
+      choose_split(p, std::max<int64_t>(tiles_cross, 1), Bp, &w.ksplit_c, &w.klen_c);
     }
     switch (q.kind) {
       case DMT_TM_LINEAR:
@@ -635,7 +635,7 @@ dmt_status plan_tm_bwd(const dmt_plan* p, const dmt_tm_params* tp, int64_t B, in
         // layer's: what the data gradient of feature f's slice of the pooled block contracts with
         w.wcomb = take((size_t)wt * (up8(q.out_dim - nf * q.feat_out) + w.Fp) * eb);
         w.x2T = take((size_t)n * BFp * eb);
-        if (eb == 2) choose_split(p->T, BFp, &w.ksplit2, &w.klen2);
+        if (eb == 2) choose_split(p, p->T, BFp, &w.ksplit2, &w.klen2);
         if (w.ksplit2 > 1) w.part2 = take((size_t)w.ksplit2 * q.feat_out * n * 4);
         break;
       }

@@ -123,7 +123,7 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
 
   // A dot-product tower whose shape fits computes its dot terms inside the projection GEMM.
   std::vector<char> fused(p->T, 0);
-  if (DT != DMT_F32 && dmt::env_int("DMT_TM_FUSE", 1) != 0 && dmt::env_int("DMT_TM_BIG", 1) != 0)
+  if (DT != DMT_F32 && p->sw.tm_fuse != 0 && p->sw.tm_big != 0)
     for (int32_t t = 0; t < p->T; ++t) {
       const dmt_tm_params& q = tp[t];
       if (q.kind != DMT_TM_DOT_LINEAR) continue;

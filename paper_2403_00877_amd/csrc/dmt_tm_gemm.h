@@ -763,7 +763,7 @@ void launch_groups(const dmt_plan* p, std::vector<TmGroup>& groups, hipStream_t 
       hipLaunchKernelGGL((tm_gemm_simple<DT>), dim3(tiles), dim3(kBlock), 0, s, L);
     } else {
       // wide outputs take the 256 x 256 kernel
-      bool big = dots || dmt::env_int("DMT_TM_BIG", 1) != 0;
+      bool big = dots || p->sw.tm_big != 0;
       for (int i = 0; i < L.ngroups; ++i) big = big && big_ok(L.g[i], dots);
       if (big) {
         static bool configured = false;

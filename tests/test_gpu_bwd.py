@@ -102,6 +102,15 @@ def test_mid_scaled_and_repeatable():
         assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("kernel", ["1", "2"])
+def test_the_other_segment_reduce_kernels(kernel, monkeypatch):
+    # rows of at most 128 columns take the lean walk; the wave-per-tile and lane-group walks
+    # (wider rows) are reached here through the plan's switch
+    monkeypatch.setenv("DMT_BWD_KERNEL", kernel)
+    check_bwd(wl.scaled(wl.mid(True), max_rows=3000, batch=300, num_tables=12))
+    check_bwd(wl.scaled(wl.imbalanced(), max_rows=2000, batch=400, num_tables=20))
+
+
 def test_hot_rows_span_many_tiles():
     # 200 rows only: every row is hit thousands of times, runs cross many reduce tiles
     check_bwd(wl.scaled(wl.mid(True), max_rows=200, batch=512, num_tables=8))
@@ -113,7 +122,7 @@ def test_imbalanced_scaled_mixed_dims():
 
 @pytest.mark.parametrize("dims", [[32, 64], [64], [32], [256]])
 def test_narrow_and_wide_rows(dims):
-    """Dims up to 64 run the lane-group kernel, 128 / 256 the wave-per-tile kernel."""
+    """Dims up to 128 run the lean walk, 256 the wave-per-tile kernel."""
     w = wl.scaled(wl.imbalanced(), max_rows=3000, batch=400, num_tables=12)
     w.dims = [dims[f % len(dims)] for f in range(12)]
     check_bwd(w)
