@@ -7,16 +7,26 @@ on the "Mid" tables and lookups (64 fp16 tables x 1M rows x D=128, 8 towers of
 8, batch 8192, Poisson(20) bags, Zipf 1.05 ids; dot-product Tower Module to 256
 on bf16 MFMA), with the "Backward" configuration's sorted / segment-reduced
 gradient and in-place rowwise Adagrad.  Inputs are resident in HBM before the
-timed region.  Prints ONE JSON line.
+timed region.  Prints ONE JSON line; the same line carries, as `other_workloads`,
+the Imbalanced step and the Large forward timed the same way.
+
+The bytes that cross the L2 <-> fabric boundary per kernel are counted in this
+run: before this process touches the GPU it runs itself twice per workload under
+`rocprofv3 --pmc` (FETCH_SIZE, then WRITE_SIZE), a few steps plus a copy kernel of
+known size that calibrates the counters.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--batches N] [--no-cpu]
+                    [--no-traffic] [--no-others] [--workload NAME]
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import shutil
+import subprocess
 import sys
+import tempfile
 import time
 
 import numpy as np
@@ -24,13 +34,15 @@ import numpy as np
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS_16BIT = 2500.0
 RTILE = 128          # sorted records per reduce tile in the backward kernel (for byte accounting)
+ROOT = os.path.dirname(os.path.abspath(__file__))
+OTHERS = ("imbalanced", "large")
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=40)
-    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--batches", type=int, default=8, help="pool of pre-generated id batches")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--workload", default="backward")
@@ -38,8 +50,14 @@ def parse():
                     help="skip the separate timing of the Tower Module backward")
     ap.add_argument("--no-tp", action="store_true",
                     help="skip the separate timing of the Tower Partitioner")
+    ap.add_argument("--no-traffic", action="store_true",
+                    help="do not count L2 <-> fabric bytes under rocprofv3 (the committed summary "
+                         "under profiles/ is quoted instead, and named as the source)")
+    ap.add_argument("--no-others", action="store_true",
+                    help="time only the named workload, not Imbalanced and Large beside it")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run dmt_calibration_copy on 1 GiB three times (for rocprofv3 --pmc runs)")
+    ap.add_argument("--traffic-child", action="store_true", help=argparse.SUPPRESS)
     return ap.parse_args()
 
 
@@ -69,25 +87,172 @@ def batch_accounting(torch, w, idx, off):
                 partial_slots=int(crossing.sum().item()) + span)
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
-              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
-        return 2
+# --------------------------------------------------------------------------------------------
+# L2 <-> fabric bytes per kernel, counted under rocprofv3 in child runs of this same file
+# --------------------------------------------------------------------------------------------
+
+# kernel (as the profiler names it) -> the family dmt_kernel_name() reports
+FAMILIES = (("lookup_fwd_kernel", "lookup_fwd"), ("bwd_reduce_update", "bwd_reduce_update"),
+            ("bwd_fixup_update", "bwd_fixup_update"), ("bwd_build_keys", "bwd_build_keys"),
+            ("radix_hist", "radix_hist"), ("radix_scan", "radix_scan"), ("radix_scatter", "radix_scatter"),
+            ("tm_gemm", "tm_gemm"), ("tm_pack_w", "tm_pack_w"), ("tm_dots", "tm_dots"),
+            ("dmt_copy_kernel", "copy"))
+KERNEL_REGEX = "lookup_fwd|bwd_|radix_|tm_|dmt_copy"
+CHILD_STEPS = 3
+COPY_BYTES = 1 << 30
+
+
+def traffic_child(args):
+    """What runs under rocprofv3: CHILD_STEPS steps of the workload, then three copies of 1 GiB by
+    dmt_copy_kernel (whose traffic is known exactly)."""
+    import torch
+    ctx = setup(args, args.workload, nb=2)
+    for i in range(CHILD_STEPS):
+        ctx["step"](i)
+    dmt = ctx["dmt"]
+    a = torch.empty(COPY_BYTES, dtype=torch.uint8, device="cuda")
+    c = torch.ones(COPY_BYTES, dtype=torch.uint8, device="cuda")
+    for _ in range(3):
+        dmt.dmt_calibration_copy(a, c)
+    torch.cuda.synchronize()
+    return 0
+
+
+def read_counter_db(path):
+    """{family: [sum of the counter over the family's dispatches, dispatches]} from a rocprofv3
+    results database."""
+    import sqlite3
+    con = sqlite3.connect(path)
+    cur = con.execute("select * from counters_collection limit 1")
+    cols = [d[0] for d in cur.description]
+    ni = cols.index("kernel_name") if "kernel_name" in cols else cols.index("name")
+    vi = cols.index("value")
+    out = {}
+    for r in con.execute("select * from counters_collection"):
+        for pat, fam in FAMILIES:
+            if pat in r[ni]:
+                e = out.setdefault(fam, [0.0, 0])
+                e[0] += float(r[vi])
+                e[1] += 1
+                break
+    con.close()
+    return out
+
+
+def collect_traffic(names):
+    """FETCH_SIZE and WRITE_SIZE (KiB per dispatch, L2 <-> fabric, so Infinity-Cache hits count)
+    of every kernel family of the named workloads, from two rocprofv3 --pmc runs each of this
+    file with --traffic-child; scaled by what the same counter reads for dmt_copy_kernel on
+    1 GiB.  Runs BEFORE this process initialises the GPU.  {workload: {...} or {"error": ...}}."""
+    exe = shutil.which("rocprofv3") or "/opt/rocm/bin/rocprofv3"
+    res = {}
+    if not os.path.exists(exe):
+        return {n: {"error": "rocprofv3 not found"} for n in names}
+    for name in names:
+        fam = {}
+        scale = {}
+        err = None
+        for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+            tmp = tempfile.mkdtemp(prefix="dmt_pmc_", dir="/tmp")
+            # (counters only on this library's kernels: the profiler has crashed while counting
+            # on the generators that draw the Large workload's ids)
+            cmd = [exe, "--pmc", counter, "--kernel-include-regex", KERNEL_REGEX, "-d", tmp, "-o", "p",
+                   "--", sys.executable,
+                   os.path.join(ROOT, "bench.py"), "--traffic-child", "--workload", name]
+            env = dict(os.environ, TMPDIR="/tmp")
+            t0 = time.time()
+            try:
+                r = subprocess.run(cmd, cwd="/tmp", env=env, stdout=subprocess.DEVNULL,
+                                   stderr=subprocess.PIPE, timeout=240)
+                if r.returncode != 0:
+                    err = "%s run exited with %d: %s" % (counter, r.returncode, r.stderr.decode()[-200:])
+                else:
+                    dbs = [os.path.join(d, f) for d, _, fs in os.walk(tmp) for f in fs
+                           if f.endswith("_results.db")]
+                    if not dbs:
+                        err = "%s run left no results database" % counter
+                    else:
+                        got = read_counter_db(dbs[0])
+                        if "copy" not in got or got["copy"][0] <= 0:
+                            err = "%s run has no calibration kernel" % counter
+                        else:
+                            scale[counter] = (COPY_BYTES / 1024.0) / (got["copy"][0] / got["copy"][1])
+                            for k, (tot, n) in got.items():
+                                fam.setdefault(k, {})[counter] = (tot, n)
+            except Exception as e:                       # a missing profiler must not cost the bench line
+                err = "%s run failed: %r" % (counter, e)
+            finally:
+                shutil.rmtree(tmp, ignore_errors=True)
+            log("[bench] rocprofv3 --pmc %s on %s: %.1fs%s" %
+                (counter, name, time.time() - t0, "" if err is None else " (" + err + ")"))
+            if err:
+                break
+        if err:
+            res[name] = {"error": err}
+            continue
+        per = {}
+        for k, v in fam.items():
+            if k == "copy" or "FETCH_SIZE" not in v or "WRITE_SIZE" not in v:
+                continue
+            rd = v["FETCH_SIZE"][0] * scale["FETCH_SIZE"] * 1024.0 / CHILD_STEPS
+            wr = v["WRITE_SIZE"][0] * scale["WRITE_SIZE"] * 1024.0 / CHILD_STEPS
+            per[k] = dict(read_bytes=int(rd), write_bytes=int(wr), bytes=int(rd + wr),
+                          launches_per_step=v["FETCH_SIZE"][1] // CHILD_STEPS)
+        res[name] = dict(per_step=per,
+                         source="rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE child runs of this command "
+                                "(%d steps each), scaled by dmt_copy_kernel on 1 GiB (factors %.3f / %.3f)"
+                                % (CHILD_STEPS, scale["FETCH_SIZE"], scale["WRITE_SIZE"]))
+    return res
+
+
+def committed_traffic(name):
+    """The committed summary of an earlier counter run of this command, when this run counted
+    nothing itself."""
+    tfile = os.path.join(ROOT, "profiles", "bench_%s_hbm_traffic.json" % name)
+    if not os.path.exists(tfile):
+        return None
+    tj = json.load(open(tfile))
+    per = {k: dict(bytes=int(v["bytes"]), launches_per_step=int(v.get("launches_per_step", 1)))
+           for k, v in tj.get("per_step", tj.get("per_launch", {})).items()}
+    return dict(per_step=per, source="committed: " + tj.get("source", tfile))
+
+
+# --------------------------------------------------------------------------------------------
+# one workload: set-up, timed steps, byte accounting
+# --------------------------------------------------------------------------------------------
+
+DTYPE_TEXT = {
+    "backward": "f16 tables, bf16 pooled values and Tower Module on MFMA, f32 accumulation, gradients and state",
+    "mid": "f16 tables, bf16 pooled values and Tower Module on MFMA, f32 accumulation",
+    "mid_dlrm": "f16 tables, bf16 pooled values and Tower Module on MFMA, f32 accumulation",
+    "large": "bf16 tables, pooled values and Tower Module on MFMA, f32 accumulation",
+    "large_lowrank": "bf16 tables, pooled values and Tower Module on MFMA, f32 accumulation",
+    "imbalanced": "f16 tables, pooled values and Tower Module on MFMA, f32 accumulation, gradients and state",
+    "tiny": "f32",
+}
+NAMES = {"backward": "backward (Mid tables and lookups: lookup fwd + dot-product TM fwd + sorted "
+                     "segment-reduce bwd + rowwise Adagrad)",
+         "mid": "mid (lookup fwd + dot-product TM fwd)",
+         "mid_dlrm": "mid tables (lookup fwd + DLRM TM fwd: flat 1024 -> 128 next to a shared 128 -> 32 "
+                     "per feature)",
+         "large": "large (lookup fwd + 2 cross layers + projection TM fwd)",
+         "large_lowrank": "large tables (lookup fwd + 2 low-rank (r = 512) cross layers + projection TM fwd)",
+         "imbalanced": "imbalanced (lookup fwd + linear TM fwd + bwd + rowwise Adagrad)",
+         "tiny": "tiny"}
+
+
+def setup(args, wname, nb):
+    """Tables, id batches, plan, Tower Module weights and buffers of a workload, all resident on
+    the device; `step(i)` enqueues one pass of the hot path on batch i of the pool."""
     import torch
     import paper_2403_00877_amd as dmt
     import workloads as wl
 
     torch.cuda.set_device(0)
-    w = wl.by_name(args.workload)
+    w = wl.by_name(wname)
     F, B, T = w.num_tables, w.batch, w.num_towers
-    eb = wl.ELT_BYTES[w.table_dtype]
-    eo = wl.ELT_BYTES[w.pooled_dtype]
     tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
-    default = w.name == "backward"
     on_device = w.name in ("large", "large_lowrank", "imbalanced")   # id streams too large for numpy
-    nb = args.batches if default else min(args.batches, 2)
 
     t0 = time.time()
     tables = wl.tables_device(w)
@@ -119,11 +284,9 @@ def main():
                 if i == 0:
                     host = (idx, off, hg)
         batches.append(dict(idx=d_idx, off=d_off, grad=grad, host=host,
-                            acct=batch_accounting(torch, w, d_idx, d_off)))
-    a0 = batches[0]["acct"]
-    log("[bench] %d batches generated in %.1fs; nnz %d, unique rows %d (%.0f%% duplicates)" %
-        (len(batches), time.time() - t0, a0["nnz"], a0["U"], 100 * (1 - a0["U"] / max(a0["nnz"], 1))))
-    max_nnz = max(b["acct"]["nnz"] for b in batches)
+                            acct=None if args.traffic_child else batch_accounting(torch, w, d_idx, d_off)))
+    log("[bench] %d batches generated in %.1fs" % (len(batches), time.time() - t0))
+    max_nnz = max(b["idx"].numel() for b in batches)
 
     plan = dmt.dmt_plan_create(w.rows, w.dims, w.table_dtype, T, w.table_to_tower, B, max_nnz)
     dmt.dmt_plan_bind(plan, tables, states)
@@ -139,8 +302,6 @@ def main():
                    w_cross=[dev(a, w.tm_dtype) for a in h["w_cross"]],
                    b_cross=[dev(a, w.tm_dtype) for a in h["b_cross"]], feat_out=w.tm_feat_out)
               for t, h in enumerate(tm_host)]
-    if not default:
-        tm_host = None
     tm_params = dmt.make_tm_params(tm_dev)
     tm_ws = torch.empty(max(dmt.dmt_tm_workspace_bytes(plan, tm_params, B), 256), dtype=torch.uint8,
                         device="cuda")
@@ -158,29 +319,57 @@ def main():
         if w.backward:
             dmt.dmt_tower_lookup_bwd_update(plan, b["idx"], b["off"], B, b["grad"], w.lr, w.eps, bwd_ws)
 
+    return dict(torch=torch, dmt=dmt, wl=wl, w=w, tables=tables, states=states, batches=batches, plan=plan,
+                widths=widths, tm_host=tm_host, tm_dev=tm_dev, tm_params=tm_params, tm_ws=tm_ws,
+                bwd_ws=bwd_ws, pooled=pooled, tm_out=tm_out, step=step)
+
+
+def run_workload(args, wname, traffic, primary):
+    """Times `wname` and returns its result object: the whole bench line for the primary
+    workload, the same fields without the side measurements for the others."""
+    default = wname == "backward"
+    nb = args.batches if default else min(args.batches, 2)
+    ctx = setup(args, wname, nb)
+    torch, dmt, wl, w = ctx["torch"], ctx["dmt"], ctx["wl"], ctx["w"]
+    plan, batches, step = ctx["plan"], ctx["batches"], ctx["step"]
+    tables, states, pooled, tm_out = ctx["tables"], ctx["states"], ctx["pooled"], ctx["tm_out"]
+    tm_params, tm_ws, bwd_ws, widths = ctx["tm_params"], ctx["tm_ws"], ctx["bwd_ws"], ctx["widths"]
+    F, B, T = w.num_tables, w.batch, w.num_towers
+    eb = wl.ELT_BYTES[w.table_dtype]
+    eo = wl.ELT_BYTES[w.pooled_dtype]
+    a0 = batches[0]["acct"]
+    log("[bench] %s: nnz %d, unique rows %d (%.0f%% duplicates)" %
+        (w.name, a0["nnz"], a0["U"], 100 * (1 - a0["U"] / max(a0["nnz"], 1))))
+
     # ---- CPU oracle leg: baseline timing + a live parity check on the same inputs
     cpu = None
-    if default and not args.no_cpu:
-        cpu = cpu_leg(dmt, wl, w, plan, tables, states, tm_host, batches[0], pooled, tm_out, tm_params,
+    if primary and default and not args.no_cpu:
+        cpu = cpu_leg(dmt, wl, w, plan, tables, states, ctx["tm_host"], batches[0], pooled, tm_out, tm_params,
                       tm_ws, bwd_ws, widths)
         for s in states:                      # restart the optimizer state for the timed run
             s.zero_()
 
-    # ---- timed region
+    # ---- timed region: exactly args.steps steps between two synchronisations; an event pair
+    # around every step (on the stream the kernels are launched on) gives the spread
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
     timed = ["lookup_fwd", "tm_gemm", "radix_scatter", "bwd_reduce_update"]
     name_to_id = {dmt.dmt_kernel_name(i): i for i in range(dmt.DMT_K_COUNT)}
     dmt.dmt_profile_enable(plan, sum(1 << name_to_id[n] for n in timed))
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
+        ev[i][0].record()
         step(args.warmup + i)
+        ev[i][1].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     prof = dmt.dmt_profile_read(plan)
     ms_per_step = elapsed * 1e3 / args.steps
+    per_step_ms = np.array([a.elapsed_time(b) for a, b in ev])
     assert dmt.dmt_last_device_error(plan) == -1
 
     # ---- per-kernel breakdown (outside the timed region, every family timed)
@@ -192,7 +381,7 @@ def main():
 
     # ---- Tower Module backward, timed on its own after the step (it is not part of `value`)
     tm_bwd = None
-    if not args.no_tm_bwd:
+    if primary and not args.no_tm_bwd:
         tm_bwd = time_tm_bwd(torch, dmt, wl, w, plan, tm_params, pooled, tm_out, tm_ws, B, args.steps)
         if w.backward:
             tm_bwd["whole_tower_step"] = time_whole_step(torch, dmt, wl, w, plan, tm_params, pooled, tm_out,
@@ -200,13 +389,13 @@ def main():
 
     # ---- Tower Partitioner on this batch's pooled embeddings (not part of `value`)
     tp_out = None
-    if not args.no_tp and len(set(w.dims)) == 1 and w.dims[0] % 8 == 0:
+    if primary and not args.no_tp and len(set(w.dims)) == 1 and w.dims[0] % 8 == 0:
         dmt.dmt_tower_lookup_fwd(plan, batches[0]["idx"], batches[0]["off"], B, pooled)
         tp_out = time_tower_partitioner(torch, dmt, wl, w, plan, pooled, B, args.steps,
                                         with_oracle=default and not args.no_cpu)
 
     # ---- SPTT's explicit shuffle steps on a buffer the size of the pooled tensor (not part of `value`)
-    sptt_out = None if args.no_tp else time_sptt_shuffles(torch, dmt, pooled, F, args.steps)
+    sptt_out = None if (args.no_tp or not primary) else time_sptt_shuffles(torch, dmt, pooled, F, args.steps)
 
     if args.calibrate:
         a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -215,14 +404,17 @@ def main():
             dmt.dmt_calibration_copy(a, c)
         torch.cuda.synchronize()
 
-    # ---- algorithmic bytes per step, averaged over the batches the timed steps used
+    # ---- bytes per step, averaged over the batches the timed steps used.  Three figures per
+    # gather / scatter kernel: LOGICAL (every lookup's row or gradient slice counted, whether a
+    # cache served it or not), COMPULSORY (each distinct row and each gradient slice once) and
+    # MEASURED (the L2 <-> fabric counters).
     used = [batches[(args.warmup + i) % nb]["acct"] for i in range(args.steps)]
     mean = lambda k: np.mean([u[k] for u in used], axis=0)
     nnz, U, span, pslots = float(mean("nnz")), float(mean("U")), float(mean("span")), float(mean("partial_slots"))
     nnz_f, U_f = mean("nnz_f"), mean("U_f")
     Df = np.array(w.dims, dtype=np.float64)
     Dmax = float(Df.max())
-    bytes_of = {
+    logical = {
         # per lookup: row + id; per bag: offset + pooled store
         "lookup_fwd": float((nnz_f * (Df * eb + 4) + B * (8 + Df * eo)).sum()),
         # per lookup: sorted record + gradient slice; per row finished in-tile: row read + write and
@@ -230,6 +422,14 @@ def main():
         "bwd_reduce_update": float((nnz_f * (8 + Df * 4) + U_f * (2 * Df * eb + 8)).sum()
                                    - span * (2 * Dmax * eb + 8) + pslots * Dmax * 4),
         # one radix pass: records read and written
+        "radix_scatter": nnz * 16,
+    }
+    compulsory = {
+        # each distinct row once; ids, offsets and the pooled store as they are
+        "lookup_fwd": float((U_f * Df * eb + nnz_f * 4 + B * (8 + Df * eo)).sum()),
+        # each bag's gradient slice once, every sorted record once, each distinct row read and
+        # written once with its state
+        "bwd_reduce_update": float((B * Df * 4 + nnz_f * 8 + U_f * (2 * Df * eb + 8)).sum()),
         "radix_scatter": nnz * 16,
     }
     kin = w.tm_in_dims()
@@ -242,78 +442,119 @@ def main():
     for name, (ms, n) in sorted(full.items()):
         kernels[name] = dict(ms_per_launch=round(ms / n, 4), launches_per_step=n // nb,
                              ms_per_step=round(ms / nb, 4))
+    if traffic is None or "per_step" not in traffic:
+        if traffic is not None:
+            log("[bench] no traffic counted for %s: %s" % (wname, traffic.get("error")))
+        traffic = committed_traffic(wname)
+    measured = traffic["per_step"] if traffic else {}
 
     def describe(name):
         """Roofline entry of one kernel family from the timed region (all its launches of a step
-        taken together)."""
+        taken together).  For the kernels bound by memory `achieved` and `frac` are the MEASURED
+        rate when the counters are there (never the logical one: a cache-served byte is no HBM
+        byte), else the compulsory rate."""
         ms, n = prof[name]
         per_step = ms / args.steps
         launches = n // args.steps
-        if name in bytes_of:
-            g = bytes_of[name] / (per_step * 1e-3) / 1e9
-            if name == "radix_scatter":
-                g *= launches                   # bytes_of is per pass
-            return dict(kernel=name, bound="hbm", achieved=round(g, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                        frac=round(g / HBM_PEAK_GBS, 4), traffic=None,
+        sec = per_step * 1e-3
+        mt = measured.get(name, {}).get("bytes")
+        if name in logical:
+            mult = launches if name == "radix_scatter" else 1      # its byte figures are per pass
+            lg, cp = logical[name] * mult / sec / 1e9, compulsory[name] * mult / sec / 1e9
+            mg = mt / sec / 1e9 if mt else None
+            ach = mg if mg is not None else cp
+            return dict(kernel=name, bound="hbm", achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=round(ach / HBM_PEAK_GBS, 4),
+                        achieved_is="measured L2<->fabric bytes / time" if mg is not None
+                        else "compulsory bytes / time (no counters in this run)",
+                        traffic=int(mt) if mt else None,
+                        logical_GBs=round(lg, 1), compulsory_GBs=round(cp, 1),
+                        measured_GBs=round(mg, 1) if mg is not None else None,
+                        traffic_over_compulsory=round(mt / (compulsory[name] * mult), 3) if mt else None,
                         ms_per_launch=round(per_step / launches, 4), launches_per_step=launches,
-                        algorithmic_bytes=int(bytes_of[name]))
-        tf = tm_fwd_flops / (per_step * 1e-3) / 1e12
-        g = tm_bytes / (per_step * 1e-3) / 1e9
+                        logical_bytes=int(logical[name] * mult), compulsory_bytes=int(compulsory[name] * mult))
+        tf = tm_fwd_flops / sec / 1e12
+        g = tm_bytes / sec / 1e9
+        mg = mt / sec / 1e9 if mt else None
         # the Tower Module's contraction is bound by whichever roof its FLOP per byte puts lower
         if tm_fwd_flops / tm_bytes < MFMA_PEAK_TFLOPS_16BIT * 1e12 / (HBM_PEAK_GBS * 1e9):
-            return dict(kernel=name, bound="hbm", achieved=round(g, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                        frac=round(g / HBM_PEAK_GBS, 4), traffic=None,
+            ach = mg if mg is not None else g
+            return dict(kernel=name, bound="hbm", achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=round(ach / HBM_PEAK_GBS, 4),
+                        achieved_is="measured L2<->fabric bytes / time" if mg is not None
+                        else "algorithmic bytes / time (no counters in this run)",
+                        traffic=int(mt) if mt else None, algorithmic_GBs=round(g, 1),
+                        measured_GBs=round(mg, 1) if mg is not None else None,
+                        traffic_over_algorithmic=round(mt / tm_bytes, 3) if mt else None,
                         ms_per_launch=round(per_step / launches, 4), launches_per_step=launches,
                         algorithmic_bytes=int(tm_bytes), algorithmic_flops=int(tm_fwd_flops),
                         achieved_TFLOPs=round(tf, 2))
         return dict(kernel=name, bound="mfma", achieved=round(tf, 2), peak=MFMA_PEAK_TFLOPS_16BIT,
-                    unit="TFLOP/s", frac=round(tf / MFMA_PEAK_TFLOPS_16BIT, 4), traffic=None,
+                    unit="TFLOP/s", frac=round(tf / MFMA_PEAK_TFLOPS_16BIT, 4),
+                    traffic=int(mt) if mt else None,
                     ms_per_launch=round(per_step / launches, 4), launches_per_step=launches,
-                    algorithmic_flops=int(tm_fwd_flops), achieved_GBs=round(g, 1))
+                    algorithmic_flops=int(tm_fwd_flops), algorithmic_GBs=round(g, 1))
 
     dom = max(prof.items(), key=lambda kv: kv[1][0])[0]
     roofline = describe(dom)
-    # L2<->fabric bytes per launch cannot be counted in this process: they come from the separate
-    # rocprofv3 --pmc runs of this same command whose summary is committed under profiles/
-    tfile = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
-                         "bench_%s_hbm_traffic.json" % w.name)
-    if os.path.exists(tfile):
-        tj = json.load(open(tfile))
-        if dom in tj.get("per_launch", {}):
-            roofline["traffic"] = tj["per_launch"][dom]["bytes"]
-            roofline["traffic_source"] = tj["source"]
+    if traffic:
+        roofline["traffic_source"] = traffic["source"]
     others = {n: describe(n) for n in timed if n in prof and n != dom}
 
-    names = {"backward": "backward (Mid tables and lookups: lookup fwd + dot-product TM fwd + sorted "
-                         "segment-reduce bwd + rowwise Adagrad)",
-             "mid": "mid (lookup fwd + dot-product TM fwd)",
-             "mid_dlrm": "mid tables (lookup fwd + DLRM TM fwd: flat 1024 -> 128 next to a shared 128 -> 32 "
-                         "per feature)",
-             "large": "large (lookup fwd + 2 cross layers + projection TM fwd)",
-             "large_lowrank": "large tables (lookup fwd + 2 low-rank (r = 512) cross layers + projection TM fwd)",
-             "imbalanced": "imbalanced (lookup fwd + linear TM fwd + bwd + rowwise Adagrad)",
-             "tiny": "tiny"}
     out = {
         "metric": "tower lookup+TM samples/sec; achieved HBM GB/s and % of peak (fwd, bwd)",
         "value": round(B / (ms_per_step * 1e-3), 1),
         "unit": "samples/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_median": round(float(np.median(per_step_ms)), 4),
+        "ms_per_step_p10": round(float(np.percentile(per_step_ms, 10)), 4),
+        "ms_per_step_p90": round(float(np.percentile(per_step_ms, 90)), 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": names[w.name], "tables": F, "rows": [min(w.rows), max(w.rows)],
+        "dtype": DTYPE_TEXT[w.name], "data": "synthetic",
+        "config": {"workload": NAMES[w.name], "tables": F, "rows": [min(w.rows), max(w.rows)],
                    "dims": sorted(set(w.dims)), "table_dtype": w.table_dtype, "towers": T, "batch": B,
                    "mean_nnz": int(nnz), "mean_unique_rows": int(U),
                    "duplicate_fraction": round(1 - U / max(nnz, 1.0), 3), "id_batches": nb},
         "roofline": roofline,
-        "cpu_baseline": cpu["baseline"] if cpu else None,
         "other_kernels": others,
         "kernel_breakdown": kernels,
-        "parity_vs_oracle_on_sample": cpu["parity"] if cpu else None,
-        "tm_backward": tm_bwd,
-        "tower_partitioner": tp_out,
-        "sptt_shuffle_steps": sptt_out,
     }
+    if primary:
+        out.update({
+            "cpu_baseline": cpu["baseline"] if cpu else None,
+            "parity_vs_oracle_on_sample": cpu["parity"] if cpu else None,
+            "tm_backward": tm_bwd,
+            "tower_partitioner": tp_out,
+            "sptt_shuffle_steps": sptt_out,
+        })
+    else:
+        for k in ("metric", "n_gpus", "higher_is_better", "scaling", "vs_baseline", "data"):
+            out.pop(k)
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+    if args.traffic_child:
+        return traffic_child(args)
+    with_others = args.workload == "backward" and not args.no_others
+    names = [args.workload] + (list(OTHERS) if with_others else [])
+    # the counter runs come first: children of a process that has not touched the GPU yet
+    traffic = {} if args.no_traffic else collect_traffic(names)
+    out = run_workload(args, args.workload, traffic.get(args.workload), primary=True)
+    if with_others:
+        import gc
+        import torch
+        out["other_workloads"] = {}
+        for n in OTHERS:
+            gc.collect()
+            torch.cuda.empty_cache()
+            out["other_workloads"][n] = run_workload(args, n, traffic.get(n), primary=False)
     print(json.dumps(out), flush=True)
     return 0
 
@@ -613,6 +854,21 @@ def cpu_leg(dmt, wl, w, plan, tables, states, tm_host, b0, pooled, tm_out, tm_pa
     frac = nt / w.num_tables
     log("[bench] oracle on %d/%d tables, %d threads: lookup %.2fs, TM %.2fs, bwd %.2fs" %
         (nt, w.num_tables, threads, t1 - t0, t2 - t1, t3 - t2))
+    # the same oracle on ONE thread, on the first tower only (its share of the step)
+    nt1 = len(w.tower_tables()[0])
+    oracle.set_threads(1)
+    t4 = time.perf_counter()
+    o1 = oracle.lookup_towered(host_tables[:nt1], w.table_dtype, s_dims[:nt1], s_t2t[:nt1],
+                               s_idx[:s_off[nt1 * B]], s_off[:nt1 * B + 1], B)
+    x1 = wl.decode(oracle.round_to(o1[0], w.pooled_dtype), w.pooled_dtype)
+    oracle.tm_dot_linear(x1, nt1, dec[0]["w"], dec[0]["b"])
+    oracle.bwd_update(host_tables[:nt1], w.table_dtype, [np.zeros(w.rows[f], dtype=np.float32) for f in range(nt1)],
+                      s_dims[:nt1], s_t2t[:nt1], s_idx[:s_off[nt1 * B]], s_off[:nt1 * B + 1], B,
+                      s_grad[:B * widths[0]], w.lr, w.eps)
+    t_one = time.perf_counter() - t4
+    oracle.set_threads(threads)
+    frac1 = nt1 / w.num_tables
+    log("[bench] oracle on %d/%d tables, 1 thread: %.2fs" % (nt1, w.num_tables, t_one))
 
     # the same step on the GPU, from the same starting tables
     dmt.dmt_tower_lookup_fwd(plan, b0["idx"], b0["off"], B, pooled)
@@ -650,7 +906,11 @@ def cpu_leg(dmt, wl, w, plan, tables, states, tm_host, b0, pooled, tm_out, tm_pa
                       kind="oracle",
                       sample="batch 0 of the id pool, all %d tables and %d samples (one step): lookup+TM+"
                              "bwd took %.2f s; value = batch / time" % (nt, B, t_cpu),
-                      seconds=round(t_cpu, 3)),
+                      seconds=round(t_cpu, 3),
+                      single_thread=dict(value=round(B / (t_one / frac1), 1), unit="samples/s", cores=1,
+                                         sample="the first tower's %d tables, all %d samples: %.2f s; value = "
+                                                "batch / (time x %d towers)" % (nt1, B, t_one, w.num_towers),
+                                         seconds=round(t_one, 3))),
         parity=parity)
 
 
