@@ -35,8 +35,10 @@
  *    sizes against the plan, supported dtypes / widths) and return
  *    DMT_EINVAL / DMT_ENOTSUP without launching anything; then they enqueue
  *    kernels on `stream` (a hipStream_t, NULL = default stream) and return
- *    without synchronising or allocating.  Scratch memory is the caller's
- *    `workspace`, sized by the dmt_*_workspace_bytes functions.
+ *    without synchronising and without allocating device memory.  Scratch
+ *    memory is the caller's `workspace`, sized by the dmt_*_workspace_bytes
+ *    functions.  (The Tower Module calls build short descriptor lists on the
+ *    host; if that allocation fails they return DMT_ENOMEM.)
  *  - Ids out of range [0, rows_f) are never dereferenced: the kernels skip them
  *    and record the smallest offending position; dmt_last_device_error
  *    synchronises the stream and reports it as DMT_EBOUNDS.
@@ -69,6 +71,9 @@ typedef enum {
   DMT_EHIP = 5      /* a HIP runtime call failed                                */
 } dmt_status;
 
+/* Element types.  Across the boundary a type (like every other enumeration here) travels as
+ * an int32_t holding one of these values, so that a value outside the list is an argument the
+ * call can reject (DMT_EINVAL) instead of an invalid enum object. */
 typedef enum { DMT_F32 = 0, DMT_F16 = 1, DMT_BF16 = 2 } dmt_dtype;
 
 typedef enum {
@@ -90,7 +95,7 @@ typedef enum {
 typedef struct dmt_plan dmt_plan; /* opaque, library-owned */
 
 /* Human-readable name of a status code (static string). */
-const char* dmt_status_str(dmt_status s);
+const char* dmt_status_str(int32_t status);
 
 /*
  * Describe the model's sparse side (paper Sec. 2.1: one table per sparse
@@ -108,7 +113,7 @@ const char* dmt_status_str(dmt_status s);
  * the backward sort, in 31 bits of a 32-bit key).
  */
 dmt_status dmt_plan_create(dmt_plan** out, int32_t num_tables, const int64_t* rows,
-                           const int32_t* dims, dmt_dtype table_dtype, int32_t num_towers,
+                           const int32_t* dims, int32_t table_dtype, int32_t num_towers,
                            const int32_t* table_to_tower, int64_t max_batch, int64_t max_nnz);
 
 void dmt_plan_destroy(dmt_plan* plan);
@@ -164,7 +169,7 @@ dmt_status dmt_plan_set_row_shards(dmt_plan* plan, const int64_t* row_begin);
  */
 dmt_status dmt_tower_lookup_fwd(const dmt_plan* plan, const int32_t* indices,
                                 const int64_t* offsets, int64_t B, int64_t nnz,
-                                void* pooled_out, dmt_dtype out_dtype, void* stream);
+                                void* pooled_out, int32_t out_dtype, void* stream);
 
 /*
  * Per-tower Tower-Module parameters (paper Sec. 4).  All weights are dev
@@ -216,7 +221,7 @@ size_t dmt_tm_workspace_bytes(const dmt_plan* plan, const dmt_tm_params* per_tow
  *              NULL when that is 0)
  */
 dmt_status dmt_tower_module_fwd(const dmt_plan* plan, const dmt_tm_params* per_tower,
-                                const void* pooled, int64_t B, void* tm_out, dmt_dtype dtype,
+                                const void* pooled, int64_t B, void* tm_out, int32_t dtype,
                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
@@ -233,9 +238,9 @@ dmt_status dmt_tower_module_fwd(const dmt_plan* plan, const dmt_tm_params* per_t
  *         dmt_tower_module_bwd.  May be NULL when that size is 0.
  */
 size_t dmt_tm_kept_bytes(const dmt_plan* plan, const dmt_tm_params* per_tower, int64_t B,
-                         dmt_dtype dtype);
+                         int32_t dtype);
 dmt_status dmt_tower_module_fwd_keep(const dmt_plan* plan, const dmt_tm_params* per_tower,
-                                     const void* pooled, int64_t B, void* tm_out, dmt_dtype dtype,
+                                     const void* pooled, int64_t B, void* tm_out, int32_t dtype,
                                      void* kept, size_t kept_bytes, void* workspace,
                                      size_t workspace_bytes, void* stream);
 
@@ -297,7 +302,7 @@ size_t dmt_tm_bwd_workspace_bytes(const dmt_plan* plan, const dmt_tm_params* per
  */
 dmt_status dmt_tower_module_bwd(const dmt_plan* plan, const dmt_tm_params* per_tower,
                                 const void* pooled, const void* tm_out, int64_t B,
-                                const float* grad_tm_out, dmt_dtype dtype, float* grad_pooled,
+                                const float* grad_tm_out, int32_t dtype, float* grad_pooled,
                                 const dmt_tm_grads* grads, const void* kept, size_t kept_bytes,
                                 void* workspace, size_t workspace_bytes, void* stream);
 
@@ -383,7 +388,7 @@ dmt_status dmt_tower_lookup_bwd_update_noalloc(const dmt_plan* plan, const int32
 size_t dmt_tp_workspace_bytes(const dmt_plan* plan, int64_t B);
 
 dmt_status dmt_tp_interaction(const dmt_plan* plan, const void* pooled, int64_t B,
-                              dmt_dtype pooled_dtype, float* interaction, void* workspace,
+                              int32_t pooled_dtype, float* interaction, void* workspace,
                               size_t workspace_bytes, void* stream);
 
 typedef enum {
@@ -401,7 +406,7 @@ typedef enum {
  *                 caller) and result; may be the same buffer
  *   stress        host out or NULL: the objective at x
  */
-dmt_status dmt_tp_embed(const float* interaction, int32_t F, dmt_tp_strategy strategy, int32_t n,
+dmt_status dmt_tp_embed(const float* interaction, int32_t F, int32_t strategy, int32_t n,
                         int32_t steps, double lr, const double* x0, double* x, double* stress);
 
 /*

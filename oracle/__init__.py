@@ -22,7 +22,10 @@ DT = {"f32": 0, "f16": 1, "bf16": 2}
 
 
 def build(force: bool = False) -> str:
-    """Compile the C oracle with gcc (-O2, OpenMP)."""
+    """Compile the C oracle with gcc (-O2, OpenMP).  DMT_ORACLE_LIB names a library built
+    elsewhere from the same source instead (the sanitizer test's -fsanitize build)."""
+    if os.environ.get("DMT_ORACLE_LIB"):
+        return os.environ["DMT_ORACLE_LIB"]
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp%d" % os.getpid()
         subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",

@@ -56,7 +56,12 @@ class DmtError(RuntimeError):
 
 
 def _load() -> ctypes.CDLL:
-    if not os.path.exists(_build.LIB):
+    if _build.is_stale():
+        # missing, or built from other sources than the tree holds: results would describe code
+        # that is no longer there
+        import sys
+        print("[dmt] %s is missing or stale: building it from the sources in the tree" % _build.LIB,
+              file=sys.stderr, flush=True)
         _build.build()          # raises if hipcc is missing or the build fails
     lib = ctypes.CDLL(_build.LIB)
     vp, i32, i64, f32, sz = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float,

@@ -45,6 +45,8 @@ def build(verbose: bool = False, jobs: int = None) -> str:
             print(" ".join(cmd), flush=True)
         subprocess.check_call(cmd)
         os.replace(tmp, LIB)
+        with open(STAMP, "w") as f:
+            f.write(source_digest() + "\n")
     finally:
         for o in objs:
             if os.path.exists(o):
@@ -52,12 +54,29 @@ def build(verbose: bool = False, jobs: int = None) -> str:
     return LIB
 
 
+def source_digest() -> str:
+    """SHA-256 over everything the library is built from (sources, headers, flags)."""
+    import hashlib
+    h = hashlib.sha256()
+    deps = sources() + sorted(glob.glob(os.path.join(CSRC, "*.h"))) + [os.path.join(ROOT, "include", "dmt.h")]
+    for d in deps:
+        h.update(os.path.basename(d).encode())
+        with open(d, "rb") as f:
+            h.update(f.read())
+    h.update(" ".join(FLAGS[:-4]).encode())          # (not the include paths, which name this checkout)
+    return h.hexdigest()
+
+
+STAMP = LIB + ".stamp"
+
+
 def is_stale() -> bool:
-    if not os.path.exists(LIB):
+    """True when libdmt.so is missing or was not built from the sources in the tree (by content,
+    not by file time: a copied tree keeps no trustworthy times)."""
+    if not os.path.exists(LIB) or not os.path.exists(STAMP):
         return True
-    t = os.path.getmtime(LIB)
-    deps = sources() + glob.glob(os.path.join(CSRC, "*.h")) + [os.path.join(ROOT, "include", "dmt.h")]
-    return any(os.path.getmtime(d) > t for d in deps)
+    with open(STAMP) as f:
+        return f.read().strip() != source_digest()
 
 
 if __name__ == "__main__":

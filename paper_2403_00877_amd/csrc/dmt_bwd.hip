@@ -75,7 +75,7 @@ BwdWs carve(const dmt_plan* p, int64_t nnz, void* base) {
   auto take = [&](size_t bytes) {
     size_t o = off;
     off = dmt_align_up(off + bytes, 256);
-    return (char*)base + o;
+    return (char*)((uintptr_t)base + o);          // (base is null when only the size is wanted)
   };
   w.pk_a = (uint64_t*)take(sizeof(uint64_t) * n);
   w.pk_b = (uint64_t*)take(sizeof(uint64_t) * n);

@@ -14,6 +14,28 @@
     if (e_ != hipSuccess) return DMT_EHIP;    \
   } while (0)
 
+// No exception crosses the C boundary: an entry point whose host side allocates (std::vector)
+// runs its body through one of these.
+#include <new>
+template <typename Body>
+static inline dmt_status dmt_guard(Body body) {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    return DMT_ENOMEM;
+  } catch (...) {
+    return DMT_EINVAL;
+  }
+}
+template <typename Body>
+static inline size_t dmt_guard_size(Body body) {
+  try {
+    return body();
+  } catch (...) {
+    return 0;
+  }
+}
+
 // Per-table record the kernels read (device copy lives in the plan).
 struct DmtTableMeta {
   const void* table;     // row-major [rows][D]

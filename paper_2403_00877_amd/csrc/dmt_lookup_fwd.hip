@@ -152,7 +152,7 @@ int ilog2_ceil(int x) {
 
 extern "C" dmt_status dmt_tower_lookup_fwd(const dmt_plan* plan, const int32_t* indices,
                                            const int64_t* offsets, int64_t B, int64_t nnz,
-                                           void* pooled_out, dmt_dtype out_dtype, void* stream) {
+                                           void* pooled_out, int32_t out_dtype, void* stream) {
   if (!plan || !offsets || !pooled_out) return DMT_EINVAL;
   if (B <= 0 || B > plan->max_batch || nnz < 0 || nnz > plan->max_nnz) return DMT_EINVAL;
   if (nnz > 0 && !indices) return DMT_EINVAL;

@@ -8,8 +8,8 @@
 
 #include "dmt_internal.h"
 
-extern "C" const char* dmt_status_str(dmt_status s) {
-  switch (s) {
+extern "C" const char* dmt_status_str(int32_t status) {
+  switch (status) {
     case DMT_OK: return "DMT_OK";
     case DMT_EINVAL: return "DMT_EINVAL";
     case DMT_ENOTSUP: return "DMT_ENOTSUP";
@@ -21,7 +21,7 @@ extern "C" const char* dmt_status_str(dmt_status s) {
 }
 
 extern "C" dmt_status dmt_plan_create(dmt_plan** out, int32_t num_tables, const int64_t* rows,
-                                      const int32_t* dims, dmt_dtype table_dtype,
+                                      const int32_t* dims, int32_t table_dtype_code,
                                       int32_t num_towers, const int32_t* table_to_tower,
                                       int64_t max_batch, int64_t max_nnz) {
   if (!out) return DMT_EINVAL;
@@ -30,7 +30,9 @@ extern "C" dmt_status dmt_plan_create(dmt_plan** out, int32_t num_tables, const 
   if (num_tables <= 0 || num_tables > DMT_MAX_TABLES) return DMT_EINVAL;
   if (num_towers <= 0 || num_towers > DMT_MAX_TOWERS || num_towers > num_tables) return DMT_EINVAL;
   if (max_batch <= 0 || max_nnz < 0) return DMT_EINVAL;
-  if (table_dtype != DMT_F32 && table_dtype != DMT_F16 && table_dtype != DMT_BF16) return DMT_EINVAL;
+  if (table_dtype_code != DMT_F32 && table_dtype_code != DMT_F16 && table_dtype_code != DMT_BF16)
+    return DMT_EINVAL;
+  const dmt_dtype table_dtype = (dmt_dtype)table_dtype_code;
   // bag ids f*B + b and lookup positions are carried in 32 bits by the backward
   if ((int64_t)num_tables * max_batch >= (1LL << 31) || max_nnz >= (1LL << 31)) return DMT_ENOTSUP;
   const int eb = dmt_elt_bytes(table_dtype);
@@ -46,8 +48,13 @@ extern "C" dmt_status dmt_plan_create(dmt_plan** out, int32_t num_tables, const 
   // the backward carries a global row id in 31 bits of its sort key (the top bit is a flag)
   if (total_rows >= (1LL << 31)) return DMT_ENOTSUP;
 
+  return dmt_guard([&]() -> dmt_status {
   dmt_plan* p = new (std::nothrow) dmt_plan();
   if (!p) return DMT_ENOMEM;
+  struct Drop {                                   // frees the plan unless it is handed over
+    dmt_plan* p;
+    ~Drop() { delete p; }
+  } drop{p};
   auto env = [](const char* name, int dflt) {
     const char* v = getenv(name);
     return (v && *v) ? atoi(v) : dflt;
@@ -96,7 +103,7 @@ extern "C" dmt_status dmt_plan_create(dmt_plan** out, int32_t num_tables, const 
     p->max_dim = std::max(p->max_dim, dims[f]);
   }
   for (int32_t t = 0; t < num_towers; ++t) {
-    if (p->tower_ntab[t] == 0) { delete p; return DMT_EINVAL; }
+    if (p->tower_ntab[t] == 0) return DMT_EINVAL;
     p->width_prefix[t + 1] = p->width_prefix[t] + p->tower_width[t];
   }
   for (int32_t f = 0; f < num_tables; ++f) {
@@ -116,8 +123,10 @@ extern "C" dmt_status dmt_plan_create(dmt_plan** out, int32_t num_tables, const 
     c.num_tables = (int32_t)p->class_tables.size() - c.first;
     p->classes.push_back(c);
   }
+  drop.p = nullptr;
   *out = p;
   return DMT_OK;
+  });
 }
 
 static void release_device(dmt_plan* p) {
@@ -172,7 +181,12 @@ extern "C" dmt_status dmt_plan_bind(dmt_plan* plan, const void* const* tables,
     DMT_HIP_TRY(hipMalloc((void**)&plan->d_row_base, sizeof(int64_t) * (plan->F + 1)));
     DMT_HIP_TRY(hipMalloc((void**)&plan->d_error, 2 * sizeof(unsigned long long)));
   }
-  std::vector<int64_t> row_base(plan->F + 1);
+  std::vector<int64_t> row_base;
+  try {
+    row_base.resize(plan->F + 1);
+  } catch (...) {
+    return DMT_ENOMEM;
+  }
   for (int32_t f = 0; f < plan->F; ++f) row_base[f] = plan->meta[f].row_base;
   row_base[plan->F] = plan->total_rows;
   const unsigned long long none[2] = {~0ULL, ~0ULL};

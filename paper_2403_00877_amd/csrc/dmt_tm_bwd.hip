@@ -1101,22 +1101,25 @@ extern "C" size_t dmt_tm_bwd_workspace_bytes(const dmt_plan* plan, const dmt_tm_
                                              int64_t B) {
   if (!plan || !per_tower || B <= 0) return 0;
   // enough for every dtype: the 16-bit layouts have smaller operands but may split K
-  std::vector<TowerBwdWs> ws;
-  size_t b4 = 0, b2 = 0;
-  if (plan_tm_bwd(plan, per_tower, B, 4, false, &ws, &b4) != DMT_OK) return 0;
-  if (plan_tm_bwd(plan, per_tower, B, 2, false, &ws, &b2) != DMT_OK) b2 = 0;   // e.g. a rank no multiple of 8
-  return std::max(b4, b2);
+  return dmt_guard_size([&]() -> size_t {
+    std::vector<TowerBwdWs> ws;
+    size_t b4 = 0, b2 = 0;
+    if (plan_tm_bwd(plan, per_tower, B, 4, false, &ws, &b4) != DMT_OK) return 0;
+    if (plan_tm_bwd(plan, per_tower, B, 2, false, &ws, &b2) != DMT_OK) b2 = 0;   // e.g. a rank no multiple of 8
+    return std::max(b4, b2);
+  });
 }
 
 extern "C" dmt_status dmt_tower_module_bwd(const dmt_plan* plan, const dmt_tm_params* per_tower,
                                            const void* pooled, const void* tm_out, int64_t B,
-                                           const float* grad_tm_out, dmt_dtype dtype,
+                                           const float* grad_tm_out, int32_t dtype_code,
                                            float* grad_pooled, const dmt_tm_grads* grads,
                                            const void* kept, size_t kept_bytes, void* workspace,
                                            size_t workspace_bytes, void* stream) {
   if (!plan || !per_tower || !pooled || !grad_tm_out || !grad_pooled || !grads) return DMT_EINVAL;
   if (B <= 0 || B > plan->max_batch || B >= (1LL << 31) - 128) return DMT_EINVAL;
-  if (dtype != DMT_F32 && dtype != DMT_F16 && dtype != DMT_BF16) return DMT_EINVAL;
+  if (dtype_code != DMT_F32 && dtype_code != DMT_F16 && dtype_code != DMT_BF16) return DMT_EINVAL;
+  const dmt_dtype dtype = (dmt_dtype)dtype_code;
   if (((uintptr_t)pooled & 15) || ((uintptr_t)tm_out & 15) || ((uintptr_t)grad_pooled & 15) ||
       ((uintptr_t)grad_tm_out & 3))
     return DMT_EINVAL;
@@ -1135,6 +1138,7 @@ extern "C" dmt_status dmt_tower_module_bwd(const dmt_plan* plan, const dmt_tm_pa
         if (!grads[t].dw_cross[2 * l] || !grads[t].dw_cross[2 * l + 1] || !grads[t].db_cross[l])
           return DMT_EINVAL;
   }
+  return dmt_guard([&]() -> dmt_status {
   std::vector<TowerBwdWs> ws;
   size_t bytes = 0;
   const char* keptp = nullptr;
@@ -1162,4 +1166,5 @@ extern "C" dmt_status dmt_tower_module_bwd(const dmt_plan* plan, const dmt_tm_pa
       return run_tm_bwd<DMT_BF16>(plan, per_tower, ws, pooled, tm_out, B, grad_tm_out, grad_pooled,
                                   grads, keptp, wsp, s);
   }
+  });
 }

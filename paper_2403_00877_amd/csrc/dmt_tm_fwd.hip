@@ -254,21 +254,24 @@ dmt_status run_tm(const dmt_plan* p, const dmt_tm_params* tp, const std::vector<
 extern "C" size_t dmt_tm_workspace_bytes(const dmt_plan* plan, const dmt_tm_params* per_tower,
                                          int64_t B) {
   if (!plan || !per_tower || B <= 0) return 0;
-  std::vector<TowerWs> ws;
-  size_t bytes = 0;
-  // sized for the wider element type so one figure serves every dtype
-  if (plan_tm(plan, per_tower, B, 4, &ws, &bytes) != DMT_OK) return 0;
-  return bytes;
+  return dmt_guard_size([&]() -> size_t {
+    std::vector<TowerWs> ws;
+    size_t bytes = 0;
+    // sized for the wider element type so one figure serves every dtype
+    if (plan_tm(plan, per_tower, B, 4, &ws, &bytes) != DMT_OK) return 0;
+    return bytes;
+  });
 }
 
 namespace {
 
 dmt_status tm_fwd_entry(const dmt_plan* plan, const dmt_tm_params* per_tower, const void* pooled,
-                        int64_t B, void* tm_out, dmt_dtype dtype, void* kept, size_t kept_bytes,
+                        int64_t B, void* tm_out, int32_t dtype_code, void* kept, size_t kept_bytes,
                         bool keep, void* workspace, size_t workspace_bytes, void* stream) {
   if (!plan || !per_tower || !pooled || !tm_out) return DMT_EINVAL;
   if (B <= 0 || B > plan->max_batch || B >= (1LL << 31)) return DMT_EINVAL;
-  if (dtype != DMT_F32 && dtype != DMT_F16 && dtype != DMT_BF16) return DMT_EINVAL;
+  if (dtype_code != DMT_F32 && dtype_code != DMT_F16 && dtype_code != DMT_BF16) return DMT_EINVAL;
+  const dmt_dtype dtype = (dmt_dtype)dtype_code;
   if (((uintptr_t)pooled & 15) || ((uintptr_t)tm_out & 15)) return DMT_EINVAL;
   const int eb = dmt_elt_bytes(dtype);
   for (int32_t t = 0; t < plan->T; ++t)
@@ -304,25 +307,32 @@ dmt_status tm_fwd_entry(const dmt_plan* plan, const dmt_tm_params* per_tower, co
 
 extern "C" dmt_status dmt_tower_module_fwd(const dmt_plan* plan, const dmt_tm_params* per_tower,
                                            const void* pooled, int64_t B, void* tm_out,
-                                           dmt_dtype dtype, void* workspace,
+                                           int32_t dtype, void* workspace,
                                            size_t workspace_bytes, void* stream) {
-  return tm_fwd_entry(plan, per_tower, pooled, B, tm_out, dtype, nullptr, 0, false, workspace,
-                      workspace_bytes, stream);
+  return dmt_guard([&] {
+    return tm_fwd_entry(plan, per_tower, pooled, B, tm_out, dtype, nullptr, 0, false, workspace,
+                        workspace_bytes, stream);
+  });
 }
 
 extern "C" size_t dmt_tm_kept_bytes(const dmt_plan* plan, const dmt_tm_params* per_tower,
-                                    int64_t B, dmt_dtype dtype) {
+                                    int64_t B, int32_t dtype) {
   if (!plan || !per_tower || B <= 0) return 0;
-  std::vector<TmKept> k;
-  return plan_tm_kept(plan, per_tower, B, dmt_elt_bytes(dtype), &k);
+  if (dtype != DMT_F32 && dtype != DMT_F16 && dtype != DMT_BF16) return 0;
+  return dmt_guard_size([&]() -> size_t {
+    std::vector<TmKept> k;
+    return plan_tm_kept(plan, per_tower, B, dmt_elt_bytes((dmt_dtype)dtype), &k);
+  });
 }
 
 extern "C" dmt_status dmt_tower_module_fwd_keep(const dmt_plan* plan,
                                                 const dmt_tm_params* per_tower,
                                                 const void* pooled, int64_t B, void* tm_out,
-                                                dmt_dtype dtype, void* kept, size_t kept_bytes,
+                                                int32_t dtype, void* kept, size_t kept_bytes,
                                                 void* workspace, size_t workspace_bytes,
                                                 void* stream) {
-  return tm_fwd_entry(plan, per_tower, pooled, B, tm_out, dtype, kept, kept_bytes, true, workspace,
-                      workspace_bytes, stream);
+  return dmt_guard([&] {
+    return tm_fwd_entry(plan, per_tower, pooled, B, tm_out, dtype, kept, kept_bytes, true, workspace,
+                        workspace_bytes, stream);
+  });
 }

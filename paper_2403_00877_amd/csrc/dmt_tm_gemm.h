@@ -105,8 +105,9 @@ template <int DT> __device__ __forceinline__ void store_elt(void* p, int64_t i, 
 #define DMT_TM_TAG 0
 #endif
 
-// KEEPU: the cross epilogue also stores u (TmGroup::U).  An instance of its own, because the
-// second store in the fully unrolled epilogue costs the bf16 kernel 40 registers and spills.
+// KEEPU: the cross epilogue also stores u (TmGroup::U), in a pass of its own over the
+// accumulators: a second store inside the fully unrolled epilogue cost the bf16 kernel 40
+// registers and made it spill.
 template <int DT, bool KEEPU = false, int TAG = DMT_TM_TAG>
 __global__ __launch_bounds__(kBlock, 2) void tm_gemm_mfma(const TmLaunch L) {
   __shared__ __attribute__((aligned(16))) uint16_t As[BM * kLdsStride];
@@ -190,6 +191,23 @@ __global__ __launch_bounds__(kBlock, 2) void tm_gemm_mfma(const TmLaunch L) {
 
   // epilogue: lane holds column n = lane % 32 of rows (v/4)*8 + (lane/32)*4 + v%4
   const int epi = G.epi;
+  if constexpr (KEEPU) {
+    if (epi == EPI_CROSS && G.U) {
+      for (int j = 0; j < 2; ++j) {
+        const int n = n0 + wn * 64 + j * 32 + (lane & 31);
+        if (n >= N) continue;
+        const float bias = G.bias ? load_elt<DT>(G.bias, n) : 0.f;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int m = m0 + wm * 64 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+            if (m < M) store_elt<DT>(G.U, (int64_t)m * G.ldc + n, acc[i][j][v] + bias);
+          }
+        }
+      }
+    }
+  }
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const int n = n0 + wn * 64 + j * 32 + (lane & 31);
@@ -209,9 +227,6 @@ __global__ __launch_bounds__(kBlock, 2) void tm_gemm_mfma(const TmLaunch L) {
         float y = acc[i][j][v] + bias;
         if (epi == EPI_BIAS_RELU) y = y > 0.f ? y : 0.f;
         if (epi == EPI_CROSS) {
-          if constexpr (KEEPU) {
-            if (G.U) store_elt<DT>(G.U, (int64_t)m * G.ldc + n, y);
-          }
           y = load_elt<DT>(G.X0, (int64_t)m * G.ldx + n) * y +
               load_elt<DT>(tm_xl(G), (int64_t)m * tm_ldxl(G) + n);
         }

@@ -627,7 +627,7 @@ extern "C" size_t dmt_tp_workspace_bytes(const dmt_plan* plan, int64_t B) {
 }
 
 extern "C" dmt_status dmt_tp_interaction(const dmt_plan* plan, const void* pooled, int64_t B,
-                                         dmt_dtype pooled_dtype, float* interaction,
+                                         int32_t pooled_dtype, float* interaction,
                                          void* workspace, size_t workspace_bytes, void* stream) {
   if (!plan || !pooled || !interaction || !workspace) return DMT_EINVAL;
   if (B <= 0 || B > plan->max_batch || !plan->bound) return DMT_EINVAL;
@@ -657,7 +657,7 @@ extern "C" dmt_status dmt_tp_interaction(const dmt_plan* plan, const void* poole
   return hipGetLastError() == hipSuccess ? DMT_OK : DMT_EHIP;
 }
 
-static dmt_status tp_embed(const float* interaction, int32_t F, dmt_tp_strategy strategy,
+static dmt_status tp_embed(const float* interaction, int32_t F, int32_t strategy,
                            int32_t n, int32_t steps, double lr, const double* x0, double* x,
                            double* stress) {
   if (!interaction || !x0 || !x || F <= 0 || n <= 0 || steps < 0 || !(lr > 0.0)) return DMT_EINVAL;
@@ -718,7 +718,7 @@ static dmt_status tp_embed(const float* interaction, int32_t F, dmt_tp_strategy 
 }
 
 // No exception crosses the C boundary: a failed host allocation is reported as DMT_ENOMEM.
-extern "C" dmt_status dmt_tp_embed(const float* interaction, int32_t F, dmt_tp_strategy strategy,
+extern "C" dmt_status dmt_tp_embed(const float* interaction, int32_t F, int32_t strategy,
                                    int32_t n, int32_t steps, double lr, const double* x0,
                                    double* x, double* stress) {
   try {

@@ -13,12 +13,8 @@ from concurrent.futures import ThreadPoolExecutor
 
 from paper_2403_00877_amd import build as hip_build
 
-# kernels that are allowed to spill, with the reason
-ALLOWED = {
-    # bf16 instance of the u-storing cross epilogue: used only by a training forward of cross
-    # towers at most 128 wide (wider towers take the 256 x 256 kernel, which does not spill)
-    r"tm_gemm_mfmaILi2ELb1E",
-}
+# kernels that are allowed to spill, with the reason (none)
+ALLOWED = set()
 
 
 def _resources(src):
