@@ -23,7 +23,8 @@ With G = 8, L = 4, T = 2 the printed key has ties and does not bring peers
 together; (g % L, g // L) does, and gives the printed order (0, 2, 1, 3) for the
 example.  That key is used here.
 
-`row_shard_lookups` covers the row-wise sharded variant of Sec. 3.1.3: the part
+`peer_permute_ids` is step c moved in front of step b (Sec. 3.1.3): the permute acts on the
+jagged sparse inputs.  `row_shard_lookups` covers the row-wise sharded variant of Sec. 3.1.3: the part
 of a batch's lookups one row shard of the tables serves.
 
 Pinned in tests/test_oracle_sptt.py against the paper's example, hand-labelled
@@ -109,6 +110,29 @@ def simulate(pooled_of, tower_tables: Sequence[Sequence[int]], L: int, B_l: int)
         t, l = divmod(r, L)
         out.append([shuffled[src_host * L + l][t] for src_host in range(T)])
     return out
+
+
+def peer_permute_ids(indices, offsets, features: int, G: int, L: int, B_l: int):
+    """Steps b and c swapped (Sec. 3.1.3: the shuffle may act on the sparse inputs instead of
+    the embeddings, whichever is smaller).  `indices` / `offsets` hold, feature-major, the bags
+    of `features` local features for the samples of all G ranks in rank order (bag (f, g, b) of
+    feature f, rank g, sample b is number (f G + g) B_l + b).  Returns the same jagged batch with
+    every feature's G blocks of B_l bags in peer order, so that a lookup on it yields what step
+    c would have made of the lookup on the input."""
+    indices = np.asarray(indices)
+    offsets = np.asarray(offsets, dtype=np.int64)
+    order = peer_order(G, L)
+    out_idx, lens = [], []
+    for f in range(features):
+        for g in order:
+            first = (f * G + g) * B_l
+            lo, hi = offsets[first], offsets[first + B_l]
+            out_idx.append(indices[lo:hi])
+            lens.append(np.diff(offsets[first:first + B_l + 1]))
+    new_idx = np.concatenate(out_idx) if out_idx else indices[:0]
+    new_off = np.concatenate([[0], np.cumsum(np.concatenate(lens))]).astype(np.int64) if lens \
+        else np.zeros(1, np.int64)
+    return new_idx.astype(indices.dtype), new_off
 
 
 # ------------------------------------------------------------------ row-wise sharded tables

@@ -113,3 +113,49 @@ def test_partial_pools_of_the_shards_add_up_to_the_lookup():
             total[t] += part[t]
     for t in range(2):
         np.testing.assert_array_equal(total[t], full[t])
+
+
+def test_peer_permute_ids_hand_case():
+    # one feature, G = 4 ranks, L = 2 per host, one sample per rank; bags of ranks 0..3 hold
+    # [10], [20, 21], [40], [30, 31, 32]; peer order is (0, 2, 1, 3)
+    idx = np.array([10, 20, 21, 40, 30, 31, 32], dtype=np.int32)
+    off = np.array([0, 1, 3, 4, 7], dtype=np.int64)
+    new_idx, new_off = sptt.peer_permute_ids(idx, off, 1, 4, 2, 1)
+    assert new_idx.tolist() == [10, 40, 20, 21, 30, 31, 32]
+    assert new_off.tolist() == [0, 1, 2, 4, 7]
+    # two samples per rank, an empty bag: rank blocks [[1], [2, 3]], [[], [4]], [[5, 6], []], [[7], [8]]
+    idx = np.arange(1, 9, dtype=np.int32)
+    off = np.array([0, 1, 3, 3, 4, 6, 6, 7, 8], dtype=np.int64)
+    new_idx, new_off = sptt.peer_permute_ids(idx, off, 1, 4, 2, 2)
+    assert new_idx.tolist() == [1, 2, 3, 5, 6, 4, 7, 8]
+    assert new_off.tolist() == [0, 1, 3, 5, 5, 5, 6, 7, 8]
+    # two features: every feature's blocks are permuted inside the feature's own range
+    idx2 = np.concatenate([idx, idx + 100]).astype(np.int32)
+    off2 = np.concatenate([off, off[1:] + 8])
+    new_idx2, new_off2 = sptt.peer_permute_ids(idx2, off2, 2, 4, 2, 2)
+    assert new_idx2.tolist() == new_idx.tolist() + (new_idx + 100).tolist()
+    assert new_off2.tolist() == new_off.tolist() + (new_off[1:] + 8).tolist()
+
+
+@pytest.mark.parametrize("G,L,Bl", [(4, 2, 3), (8, 4, 2), (6, 3, 5), (2, 2, 4), (3, 1, 2)])
+def test_lookup_on_permuted_ids_is_the_permuted_lookup(G, L, Bl):
+    """Swapping steps b and c does not change what step c hands to step d: the pooled embeddings
+    of a lookup on the permuted ids are, block for block, the peer permute of the pooled
+    embeddings of the lookup on the ids as they arrived."""
+    import oracle
+    rng = np.random.default_rng(G * 100 + L)
+    F, N, rows = 3, 4, 50
+    B = G * Bl
+    lens = rng.integers(0, 5, size=F * B)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    idx = rng.integers(0, rows, size=int(off[-1])).astype(np.int32)
+    tables = [rng.standard_normal((rows, N)).astype(np.float32) for _ in range(F)]
+    t2t = [0] * F
+
+    def pooled(i, o):                    # (F, G, Bl, N): tower-major [B][F N] -> per feature blocks
+        out = oracle.lookup_towered(tables, "f32", [N] * F, t2t, i, o, B)[0]
+        return np.ascontiguousarray(out.reshape(B, F, N).transpose(1, 0, 2)).reshape(F, G, Bl, N)
+
+    new_idx, new_off = sptt.peer_permute_ids(idx, off, F, G, L, Bl)
+    assert np.array_equal(np.sort(new_idx), np.sort(idx)) and new_off[-1] == off[-1]
+    assert np.array_equal(pooled(new_idx, new_off), sptt.peer_permute(pooled(idx, off), L))
