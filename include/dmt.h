@@ -446,6 +446,24 @@ dmt_status dmt_sptt_peer_order(int32_t G, int32_t L, int32_t* order);
 dmt_status dmt_sptt_peer_permute(const void* in, void* out, int64_t features, int32_t G, int32_t L,
                                  int64_t block_bytes, void* stream);
 
+/*
+ * Step c moved in front of step b (paper Sec. 3.1.3: steps b and c may be swapped so that the
+ * shuffle acts on the smaller object): the peer permute on the sparse inputs.  `indices` /
+ * `offsets` are a jagged batch as everywhere in this library, for `features` local features and
+ * B = G * B_l samples, the samples of rank g being bags g * B_l .. (g + 1) * B_l - 1 of every
+ * feature.  The output is the same batch with every feature's G blocks of B_l bags in peer
+ * order (out block k of a feature = in block order[k]); a lookup on it yields, block for block,
+ * what dmt_sptt_peer_permute makes of the lookup on the input.
+ *   indices dev int32 [nnz], offsets dev int64 [features * G * B_l + 1] (tiling [0, nnz));
+ *   out_indices / out_offsets dev, same sizes, distinct from the inputs
+ * DMT_ENOTSUP for G > 1024 or features * G > 65535.  Offsets outside [0, nnz] are clamped: the
+ * copies stay in bounds whatever they hold.
+ */
+dmt_status dmt_sptt_peer_permute_ids(const int32_t* indices, const int64_t* offsets,
+                                     int64_t features, int32_t G, int32_t L, int64_t B_l,
+                                     int64_t nnz, int32_t* out_indices, int64_t* out_offsets,
+                                     void* stream);
+
 /* Step e: in [features][peers][block] -> out [peers][features][block], i.e. the 2-D arrangement
  * (features, peers) transposed and flattened as (peers x features). */
 dmt_status dmt_sptt_shuffle(const void* in, void* out, int64_t features, int64_t peers,

@@ -12,4 +12,4 @@ from .binding import (  # noqa: F401
     DMT_K_COUNT, EXPORTS, dmt_calibration_copy,
     dmt_tp_workspace_bytes, dmt_tp_interaction, dmt_tp_embed, dmt_tp_kmeans,
     dmt_sptt_peer_order, dmt_sptt_peer_permute, dmt_sptt_shuffle, dmt_plan_set_row_shards,
-    dmt_bwd_noalloc_scratch_bytes, dmt_tower_lookup_bwd_update_noalloc)
+    dmt_bwd_noalloc_scratch_bytes, dmt_tower_lookup_bwd_update_noalloc, dmt_sptt_peer_permute_ids)

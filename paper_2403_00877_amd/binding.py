@@ -105,6 +105,7 @@ def _load() -> ctypes.CDLL:
     lib.dmt_sptt_peer_order.argtypes = [i32, i32, vp]
     lib.dmt_sptt_peer_permute.argtypes = [vp, vp, i64, i32, i32, i64, vp]
     lib.dmt_sptt_shuffle.argtypes = [vp, vp, i64, i64, i64, vp]
+    lib.dmt_sptt_peer_permute_ids.argtypes = [vp, vp, i64, i32, i32, i64, i64, vp, vp, vp]
     return lib
 
 
@@ -119,7 +120,7 @@ EXPORTS = ["dmt_status_str", "dmt_plan_create", "dmt_plan_destroy", "dmt_plan_la
            "dmt_calibration_copy", "dmt_tp_workspace_bytes", "dmt_tp_interaction",
            "dmt_tp_embed", "dmt_tp_kmeans", "dmt_sptt_peer_order", "dmt_sptt_peer_permute",
            "dmt_sptt_shuffle", "dmt_plan_set_row_shards", "dmt_bwd_noalloc_scratch_bytes",
-           "dmt_tower_lookup_bwd_update_noalloc"]
+           "dmt_tower_lookup_bwd_update_noalloc", "dmt_sptt_peer_permute_ids"]
 
 DMT_K_COUNT = 15
 TP_STRATEGY_CODE = {"diverse": 0, "coherent": 1}
@@ -418,6 +419,18 @@ def dmt_sptt_shuffle(inp: torch.Tensor, out: torch.Tensor, features: int, peers:
     assert _nbytes(inp) >= features * peers * block_bytes and _nbytes(out) >= features * peers * block_bytes
     _check("dmt_sptt_shuffle", _lib.dmt_sptt_shuffle(
         _ptr(inp), _ptr(out), features, peers, block_bytes, _stream(stream)))
+
+
+def dmt_sptt_peer_permute_ids(indices: torch.Tensor, offsets: torch.Tensor, features: int, G: int,
+                              L: int, B_l: int, out_indices: torch.Tensor, out_offsets: torch.Tensor,
+                              stream=None) -> None:
+    assert indices.dtype == torch.int32 and offsets.dtype == torch.int64
+    assert out_indices.dtype == torch.int32 and out_offsets.dtype == torch.int64
+    assert offsets.numel() == features * G * B_l + 1 and out_offsets.numel() >= offsets.numel()
+    assert out_indices.numel() >= indices.numel()
+    _check("dmt_sptt_peer_permute_ids", _lib.dmt_sptt_peer_permute_ids(
+        _ptr(indices), _ptr(offsets), features, G, L, B_l, indices.numel(), _ptr(out_indices),
+        _ptr(out_offsets), _stream(stream)))
 
 
 def dmt_plan_set_row_shards(plan: dmt_plan, row_begin: Sequence[int]) -> None:

@@ -125,3 +125,74 @@ def test_shuffle_steps_reject_bad_arguments():
     assert raw_s(pa, pb, 2, 0, 64, None) == 1 and raw_s(pa, pb, 2, 4, 0, None) == 1
     assert raw_s(pa, pb, 1 << 21, 4, 64, None) == 2           # beyond the supported block count
     torch.cuda.synchronize()
+
+
+def _jagged(rng, nbags, max_len, rows, empty=0.2):
+    lens = rng.integers(0, max_len + 1, size=nbags)
+    lens[rng.random(nbags) < empty] = 0
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    return rng.integers(0, rows, size=int(off[-1])).astype(np.int32), off
+
+
+@pytest.mark.parametrize("F,G,L,Bl,max_len", [
+    (1, 4, 2, 1, 3),          # the paper's example: 4 GPUs, 2 per host
+    (3, 8, 4, 5, 7), (2, 6, 3, 33, 40), (5, 8, 1, 4, 2), (5, 8, 8, 4, 2),
+    (8, 8, 4, 1024, 40),      # Mid's feature shape: 8192 samples over 8 ranks, ~20 ids per bag
+    (2, 16, 4, 300, 900),     # blocks of ids that span many workgroup passes
+    (4, 4, 2, 6, 0),          # no ids at all
+])
+def test_peer_permute_of_the_sparse_inputs_matches_the_oracle(F, G, L, Bl, max_len):
+    """Steps b and c swapped (Sec. 3.1.3): the permute on ids, bit for bit."""
+    rng = np.random.default_rng(F * 1000 + G * 10 + L)
+    idx, off = _jagged(rng, F * G * Bl, max_len, 1 << 20)
+    d_idx, d_off = torch.from_numpy(idx).cuda(), torch.from_numpy(off).cuda()
+    o_idx = torch.full((max(len(idx), 1),), -7, dtype=torch.int32, device="cuda")
+    o_off = torch.full((len(off),), -7, dtype=torch.int64, device="cuda")
+    dmt.dmt_sptt_peer_permute_ids(d_idx, d_off, F, G, L, Bl, o_idx[:len(idx)], o_off)
+    torch.cuda.synchronize()
+    want_idx, want_off = sptt.peer_permute_ids(idx, off, F, G, L, Bl)
+    np.testing.assert_array_equal(o_off.cpu().numpy(), want_off)
+    np.testing.assert_array_equal(o_idx[:len(idx)].cpu().numpy(), want_idx)
+
+
+def test_lookup_on_permuted_ids_is_the_permuted_lookup_on_the_device():
+    """b and c swapped against b then c, both on the device: same bits."""
+    import workloads as wl
+    from harness import DeviceWorkload
+    G, L = 8, 4
+    w = wl.scaled(wl.mid(), max_rows=5000, batch=G * 37, num_tables=8)
+    w.pooled_dtype = "f32"
+    w.table_to_tower = [0] * 8
+    w.tm_out = [256]
+    dw = DeviceWorkload(w)
+    F, B, N = 8, w.batch, 128
+    Bl = B // G
+    idx, off = wl.lookup_batch(w)
+    d_idx, d_off = torch.from_numpy(idx).cuda(), torch.from_numpy(off).cuda()
+    p_idx, p_off = torch.empty_like(d_idx), torch.empty_like(d_off)
+    dmt.dmt_sptt_peer_permute_ids(d_idx, d_off, F, G, L, Bl, p_idx, p_off)
+    torch.cuda.synchronize()
+    swapped = dw.lookup(p_idx.cpu().numpy(), p_off.cpu().numpy())        # [B][F][N], samples in peer order
+    plain = dw.lookup(idx, off)
+    # step c on the plain lookup, per feature: (F, G, Bl * N) blocks
+    blocks = plain.view(B, F, N).permute(1, 0, 2).contiguous().view(-1)
+    out = torch.empty_like(blocks)
+    dmt.dmt_sptt_peer_permute(blocks.view(torch.uint8), out.view(torch.uint8), F, G, L, Bl * N * 4)
+    torch.cuda.synchronize()
+    want = out.view(F, B, N).permute(1, 0, 2).contiguous().view(-1)
+    assert torch.equal(swapped.view(torch.int32), want.view(torch.int32))
+
+
+def test_peer_permute_of_ids_rejects_bad_arguments():
+    raw = dmt.binding._lib.dmt_sptt_peer_permute_ids
+    i = torch.zeros(64, dtype=torch.int32, device="cuda")
+    o = torch.zeros(4 * 2 + 1, dtype=torch.int64, device="cuda")
+    i2, o2 = torch.zeros_like(i), torch.zeros_like(o)
+    a = (i.data_ptr(), o.data_ptr())
+    assert raw(*a, 1, 4, 2, 2, 0, i2.data_ptr(), o2.data_ptr(), None) == 0
+    assert raw(*a, 1, 4, 3, 2, 0, i2.data_ptr(), o2.data_ptr(), None) == 1       # L does not divide G
+    assert raw(*a, 1, 4, 2, 2, 0, i2.data_ptr(), o.data_ptr(), None) == 1        # offsets in place
+    assert raw(*a, 1, 4, 2, 2, 8, i.data_ptr(), o2.data_ptr(), None) == 1        # ids in place
+    assert raw(None, o.data_ptr(), 1, 4, 2, 2, 8, i2.data_ptr(), o2.data_ptr(), None) == 1
+    assert raw(*a, 1, 2048, 2, 2, 0, i2.data_ptr(), o2.data_ptr(), None) == 2    # more ranks than supported
+    torch.cuda.synchronize()
