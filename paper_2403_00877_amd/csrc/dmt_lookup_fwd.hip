@@ -22,6 +22,7 @@
 namespace {
 
 constexpr int kBlock = 256;
+constexpr int kStagedBags = 2048;  // most bags of one block whose offsets are staged in LDS
 #ifndef DMT_LOOKUP_UNROLL
 #define DMT_LOOKUP_UNROLL 4
 #endif
@@ -33,7 +34,7 @@ __global__ __launch_bounds__(kBlock) void lookup_fwd_kernel(
     const int32_t* __restrict__ indices, const int64_t* __restrict__ offsets, int64_t B,
     int64_t nnz, void* __restrict__ out, int log2_lpr, int log2_gl, int bags_per_group,
     int32_t tiles_per_table, int32_t ntiles, int32_t tiles_per_xcd, int long_thr,
-    unsigned long long* __restrict__ err) {
+    int stage_offsets, unsigned long long* __restrict__ err) {
   constexpr int EPL = dmt::ChunkElems<TD>::value;
   const int bid = blockIdx.x;
   const int tile = (bid & 7) * tiles_per_xcd + (bid >> 3);
@@ -99,16 +100,36 @@ __global__ __launch_bounds__(kBlock) void lookup_fwd_kernel(
   const int group = threadIdx.x >> log2_gl;
   const int ngroups = kBlock >> log2_gl;
   const int64_t b0 = (int64_t)c * ngroups * bags_per_group;
+  // A block's bags are consecutive.  When every lane group pools several of them, their
+  // offsets come in with one coalesced read through LDS, so that a group's next bag starts
+  // at its ids; with one bag per group the direct read is the shorter path.
+  __shared__ int64_t s_off[kStagedBags + 1];
+  const bool staged = stage_offsets != 0;
+  if (staged) {
+    const int nb_blk = (int)min((int64_t)ngroups * bags_per_group, B - b0);
+    for (int j = threadIdx.x; j <= nb_blk; j += kBlock) {
+      const int64_t o = offsets[(int64_t)f * B + b0 + j];
+      s_off[j] = o < 0 ? 0 : (o > nnz ? nnz : o);
+    }
+    __syncthreads();
+  }
   for (int i = 0; i < bags_per_group; ++i) {
     const int64_t b = b0 + (int64_t)i * ngroups + group;
     int64_t s = 0;
     int len = 0;
     if (b < B) {
-      const int64_t bag = (int64_t)f * B + b;
-      int64_t e = offsets[bag + 1];
-      s = offsets[bag];
-      s = s < 0 ? 0 : (s > nnz ? nnz : s);
-      e = e < s ? s : (e > nnz ? nnz : e);
+      int64_t e;
+      if (staged) {
+        s = s_off[b - b0];
+        e = s_off[b - b0 + 1];
+      } else {
+        const int64_t bag = (int64_t)f * B + b;
+        e = offsets[bag + 1];
+        s = offsets[bag];
+        s = s < 0 ? 0 : (s > nnz ? nnz : s);
+        e = e > nnz ? nnz : e;
+      }
+      e = e < s ? s : e;
       len = (int)(e - s);
     }
     // A bag much longer than the others would hold up every other bag of its wave: the groups
@@ -135,11 +156,12 @@ void launch(const dmt_plan* p, const DmtDimClass& c, const int32_t* indices,
   const int32_t tiles_per_table = (int32_t)((B + bags_per_block - 1) / bags_per_block);
   const int32_t ntiles = tiles_per_table * c.num_tables;
   const int32_t tiles_per_xcd = (ntiles + 7) / 8;
+  const int stage_offsets = bpg > 1 && bags_per_block <= kStagedBags;
   DmtScope scope(p, DMT_K_LOOKUP_FWD, s);
   hipLaunchKernelGGL((lookup_fwd_kernel<TD, OD>), dim3(tiles_per_xcd * 8), dim3(kBlock), 0, s,
                      p->d_meta, p->d_class_tables + c.first, c.D, indices, offsets, B, nnz, out,
                      log2_lpr, log2_gl, bpg, tiles_per_table, ntiles, tiles_per_xcd, long_thr,
-                     p->row_shards ? nullptr : p->d_error);
+                     stage_offsets, p->row_shards ? nullptr : p->d_error);
 }
 
 int ilog2_ceil(int x) {
