@@ -57,6 +57,9 @@ def parse():
                     help="time only the named workload, not Imbalanced and Large beside it")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run dmt_calibration_copy on 1 GiB three times (for rocprofv3 --pmc runs)")
+    ap.add_argument("--traffic-out", default=None, metavar="DIR",
+                    help="also write the counted bytes per kernel as bench_<workload>_hbm_traffic.txt "
+                         "and .json into DIR (the form kept under profiles/)")
     ap.add_argument("--traffic-child", action="store_true", help=argparse.SUPPRESS)
     return ap.parse_args()
 
@@ -139,7 +142,42 @@ def read_counter_db(path):
     return out
 
 
-def collect_traffic(names):
+def write_traffic_summary(outdir, name, cmds, scale, fam, per, source):
+    """The text and JSON summaries of one workload's counter runs, in the form profiles/ keeps."""
+    os.makedirs(outdir, exist_ok=True)
+    base = os.path.join(outdir, "bench_%s_hbm_traffic" % name)
+    with open(base + ".txt", "w") as f:
+        f.write("L2 <-> memory-fabric bytes per kernel family on the %s workload, MI355X\n" % name)
+        f.write("written by: python3 bench.py --traffic-out DIR, which ran (from /tmp, TMPDIR=/tmp):\n")
+        for c in cmds:
+            f.write("  " + c + "\n")
+        f.write("(each child run: %d steps of the path, then dmt_copy_kernel on 1 GiB three times)\n" % CHILD_STEPS)
+        f.write("calibration: the copy reads and writes 1048576 KiB; FETCH_SIZE scale %.4f, WRITE_SIZE scale %.4f\n"
+                % (scale["FETCH_SIZE"], scale["WRITE_SIZE"]))
+        f.write("the counters sit between L2 and the fabric: an Infinity-Cache hit counts like an HBM access\n\n")
+        f.write("%-20s %10s %15s %15s %12s %12s %12s\n" % ("kernel family", "dispatches", "FETCH_raw_avg",
+                                                          "WRITE_raw_avg", "read_MB/step", "write_MB/step", "MB/step"))
+        for k in sorted(fam):
+            v = fam[k]
+            if "FETCH_SIZE" not in v or "WRITE_SIZE" not in v:
+                continue
+            fa = v["FETCH_SIZE"][0] / v["FETCH_SIZE"][1]
+            wa = v["WRITE_SIZE"][0] / v["WRITE_SIZE"][1]
+            if k == "copy":
+                f.write("%-20s %10d %15.1f %15.1f %12s %12s %12s\n" % (k, v["FETCH_SIZE"][1], fa, wa, "-", "-", "-"))
+            else:
+                e = per[k]
+                f.write("%-20s %10d %15.1f %15.1f %12.1f %12.1f %12.1f\n" %
+                        (k, v["FETCH_SIZE"][1], fa, wa, e["read_bytes"] / 1e6, e["write_bytes"] / 1e6,
+                         e["bytes"] / 1e6))
+    with open(base + ".json", "w") as f:
+        json.dump(dict(workload=name, source="profiles/bench_%s_hbm_traffic.txt (%s)" % (name, source),
+                       fetch_scale=round(scale["FETCH_SIZE"], 4), write_scale=round(scale["WRITE_SIZE"], 4),
+                       per_step=per), f, indent=1)
+        f.write("\n")
+
+
+def collect_traffic(names, outdir=None):
     """FETCH_SIZE and WRITE_SIZE (KiB per dispatch, L2 <-> fabric, so Infinity-Cache hits count)
     of every kernel family of the named workloads, from two rocprofv3 --pmc runs each of this
     file with --traffic-child; scaled by what the same counter reads for dmt_copy_kernel on
@@ -152,6 +190,7 @@ def collect_traffic(names):
         fam = {}
         scale = {}
         err = None
+        cmds = []
         for counter in ("FETCH_SIZE", "WRITE_SIZE"):
             tmp = tempfile.mkdtemp(prefix="dmt_pmc_", dir="/tmp")
             # (counters only on this library's kernels: the profiler has crashed while counting
@@ -160,6 +199,7 @@ def collect_traffic(names):
                    "--", sys.executable,
                    os.path.join(ROOT, "bench.py"), "--traffic-child", "--workload", name]
             env = dict(os.environ, TMPDIR="/tmp")
+            cmds.append(" ".join(cmd[:4] + ["'%s'" % cmd[4], "-d", "<tmp>"] + cmd[7:9] + ["--", "python3", "bench.py"] + cmd[12:]))
             t0 = time.time()
             try:
                 r = subprocess.run(cmd, cwd="/tmp", env=env, stdout=subprocess.DEVNULL,
@@ -202,6 +242,8 @@ def collect_traffic(names):
                          source="rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE child runs of this command "
                                 "(%d steps each), scaled by dmt_copy_kernel on 1 GiB (factors %.3f / %.3f)"
                                 % (CHILD_STEPS, scale["FETCH_SIZE"], scale["WRITE_SIZE"]))
+        if outdir:
+            write_traffic_summary(outdir, name, cmds, scale, fam, per, res[name]["source"])
     return res
 
 
@@ -545,7 +587,7 @@ def main():
     with_others = args.workload == "backward" and not args.no_others
     names = [args.workload] + (list(OTHERS) if with_others else [])
     # the counter runs come first: children of a process that has not touched the GPU yet
-    traffic = {} if args.no_traffic else collect_traffic(names)
+    traffic = {} if args.no_traffic else collect_traffic(names, args.traffic_out)
     out = run_workload(args, args.workload, traffic.get(args.workload), primary=True)
     if with_others:
         import gc
