@@ -24,6 +24,7 @@ import argparse
 import json
 import os
 import shutil
+import signal
 import subprocess
 import sys
 import tempfile
@@ -202,10 +203,18 @@ def collect_traffic(names, outdir=None):
             cmds.append(" ".join(cmd[:4] + ["'%s'" % cmd[4], "-d", "<tmp>"] + cmd[7:9] + ["--", "python3", "bench.py"] + cmd[12:]))
             t0 = time.time()
             try:
-                r = subprocess.run(cmd, cwd="/tmp", env=env, stdout=subprocess.DEVNULL,
-                                   stderr=subprocess.PIPE, timeout=240)
-                if r.returncode != 0:
-                    err = "%s run exited with %d: %s" % (counter, r.returncode, r.stderr.decode()[-200:])
+                # the profiler and the child under it form a process group of their own, so that a
+                # time-out ends both and nothing outlives this function
+                pr = subprocess.Popen(cmd, cwd="/tmp", env=env, stdout=subprocess.DEVNULL,
+                                      stderr=subprocess.PIPE, start_new_session=True)
+                try:
+                    _, stderr = pr.communicate(timeout=240)
+                except subprocess.TimeoutExpired:
+                    os.killpg(pr.pid, signal.SIGKILL)
+                    pr.communicate()
+                    raise
+                if pr.returncode != 0:
+                    err = "%s run exited with %d: %s" % (counter, pr.returncode, stderr.decode()[-200:])
                 else:
                     dbs = [os.path.join(d, f) for d, _, fs in os.walk(tmp) for f in fs
                            if f.endswith("_results.db")]
