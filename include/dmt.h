@@ -24,6 +24,11 @@
  *                                K-means (host; they touch |F| x |F| numbers)
  * and SPTT's data-shuffle steps c and e in explicit form (paper Sec. 3.1.1):
  *   dmt_sptt_peer_permute, dmt_sptt_shuffle   block transposes in device memory
+ *   dmt_sptt_peer_permute_ids    step c moved in front of step b (paper Sec.
+ *                                3.1.3): the same permute on the jagged ids
+ * For callers that can neither allocate nor hand over a workspace:
+ *   dmt_tower_lookup_bwd_update_noalloc   the update on a scratch array that
+ *                                lives inside the library
  *
  * Conventions
  *  - C linkage, no exceptions cross the boundary; every call returns dmt_status.
@@ -41,7 +46,11 @@
  *    host; if that allocation fails they return DMT_ENOMEM.)
  *  - Ids out of range [0, rows_f) are never dereferenced: the kernels skip them
  *    and record the smallest offending position; dmt_last_device_error
- *    synchronises the stream and reports it as DMT_EBOUNDS.
+ *    synchronises the stream and reports it as DMT_EBOUNDS.  Offsets that do
+ *    not tile [0, nnz) make the update touch no row at all; the same call
+ *    reports them as DMT_EINVAL with the first offending bag.
+ *  - Enumerations are passed by value as int32_t, so that a value outside the
+ *    enumeration reaches the library's own check.
  *  - Jagged input is feature-major CSR: bag (f, b) of table f and sample b owns
  *    indices[offsets[f*B + b] .. offsets[f*B + b + 1]); offsets has
  *    num_tables*B + 1 entries, offsets[0] = 0, offsets[num_tables*B] = nnz.
