@@ -61,6 +61,10 @@ def parse():
     ap.add_argument("--traffic-out", default=None, metavar="DIR",
                     help="also write the counted bytes per kernel as bench_<workload>_hbm_traffic.txt "
                          "and .json into DIR (the form kept under profiles/)")
+    ap.add_argument("--chunk-sweep", action="store_true",
+                    help="instead of the step: lookup -> Tower Module run over the batch in 1, 2, 4 ... "
+                         "chunks (each chunk a batch of its own), to see whether a pooled block that "
+                         "stays in the caches between the two calls pays for the smaller launches")
     ap.add_argument("--traffic-child", action="store_true", help=argparse.SUPPRESS)
     return ap.parse_args()
 
@@ -585,6 +589,83 @@ def run_workload(args, wname, traffic, primary):
     return out
 
 
+def chunk_sweep(args):
+    """Lookup -> Tower Module over the whole batch as k chunks of B / k samples, k = 1, 2, 4 ...:
+    the existing entry points called on batch slices (a chunk's pooled block is B / k rows of
+    every tower, written by the lookup and read back by the Tower Module right after).  One JSON
+    line; the time is per WHOLE batch, so k = 1 is the ordinary forward."""
+    import torch
+    import paper_2403_00877_amd as dmt
+    import workloads as wl
+    name = args.workload
+    w0 = wl.by_name(name)
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+    tables = wl.tables_device(w0)
+
+    def dev(a, dt):
+        t = torch.from_numpy(wl.encode(a, dt))
+        return (t.view(torch.int16).view(torch.bfloat16) if dt == "bf16" else t).cuda()
+
+    tm_dev = [dict(kind=w0.tm_kind, out_dim=w0.tm_out[t], w_proj=dev(h["w_proj"], w0.tm_dtype),
+                   b_proj=dev(h["b_proj"], w0.tm_dtype), w_cross=[dev(a, w0.tm_dtype) for a in h["w_cross"]],
+                   b_cross=[dev(a, w0.tm_dtype) for a in h["b_cross"]], feat_out=w0.tm_feat_out)
+              for t, h in enumerate(wl.tm_weights(w0))]
+    on_device = w0.name in ("large", "large_lowrank", "imbalanced")
+    rows = []
+    k = 1
+    while k <= 64 and w0.batch // k >= 256:
+        w = wl.by_name(name)
+        w.batch = B = w0.batch // k
+        chunks = []
+        for i in range(k):                      # k different chunks, ids drawn per chunk
+            if on_device:
+                d_idx, d_off = wl.lookup_batch_device(w, i)
+            else:
+                idx, off = wl.lookup_batch(w, i)
+                d_idx, d_off = torch.from_numpy(idx).cuda(), torch.from_numpy(off).cuda()
+            chunks.append((d_idx, d_off))
+        max_nnz = max(c[0].numel() for c in chunks)
+        plan = dmt.dmt_plan_create(w.rows, w.dims, w.table_dtype, w.num_towers, w.table_to_tower, B, max_nnz)
+        dmt.dmt_plan_bind(plan, tables, None)
+        base, _, _ = dmt.dmt_plan_layout(plan, B)
+        tm_params = dmt.make_tm_params(tm_dev)
+        tm_ws = torch.empty(max(dmt.dmt_tm_workspace_bytes(plan, tm_params, B), 256), dtype=torch.uint8,
+                            device="cuda")
+        pooled = [torch.empty(base[-1], dtype=tdt[w.pooled_dtype], device="cuda") for _ in range(min(k, 2))]
+        tm_out = torch.empty(B * sum(w.tm_out), dtype=tdt[w.tm_dtype], device="cuda")
+
+        def whole():
+            for i, (d_idx, d_off) in enumerate(chunks):
+                p = pooled[i % len(pooled)]
+                dmt.dmt_tower_lookup_fwd(plan, d_idx, d_off, B, p)
+                dmt.dmt_tower_module_fwd(plan, tm_params, p, B, tm_out, tm_ws)
+
+        for _ in range(3):
+            whole()
+        torch.cuda.synchronize()
+        n = max(5, min(args.steps, 20))
+        t0 = time.perf_counter()
+        for _ in range(n):
+            whole()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / n
+        dmt.dmt_profile_enable(plan, (1 << dmt.DMT_K_COUNT) - 1)
+        for _ in range(5):
+            whole()
+        prof = dmt.dmt_profile_read(plan)
+        dmt.dmt_profile_enable(plan, 0)
+        rows.append(dict(chunks=k, samples_per_chunk=B,
+                         pooled_MB_per_chunk=round(pooled[0].numel() * pooled[0].element_size() / 1e6, 1),
+                         ms_per_whole_batch=round(ms, 4),
+                         kernel_ms_per_whole_batch={kk: round(v[0] / 5, 4) for kk, v in prof.items()}))
+        log("[bench] %s in %d chunks: %.3f ms per whole batch" % (name, k, ms))
+        del plan
+        k *= 2
+    print(json.dumps({"chunk_sweep": {"workload": name, "what": "lookup_fwd -> tower_module_fwd per chunk, "
+                                      "ms per whole batch", "rows": rows}}), flush=True)
+    return 0
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -593,6 +674,8 @@ def main():
         return 2
     if args.traffic_child:
         return traffic_child(args)
+    if args.chunk_sweep:
+        return chunk_sweep(args)
     with_others = args.workload == "backward" and not args.no_others
     names = [args.workload] + (list(OTHERS) if with_others else [])
     # the counter runs come first: children of a process that has not touched the GPU yet
