@@ -70,6 +70,7 @@ struct DmtProfile {
 struct DmtSwitches {
   int tm_big = 1;        // DMT_TM_BIG=0: every contraction on the 128 x 128 kernel
   int tm_fuse = 1;       // DMT_TM_FUSE=0: dot terms by their own kernel, not inside the projection
+  int tm_direct = 1;     // DMT_TM_DIRECT=0: interior launches of the 256 x 256 kernel stage through registers too
   int tmb_ksplit = 0;    // DMT_TMB_KSPLIT=n: slices of every weight gradient
   int bwd_kernel = 0;    // DMT_BWD_KERNEL=1 / 2: the wave-per-tile / lane-group segment reduce
   int keys_lg = -1;      // DMT_KEYS_LG=l: 2^l bags per key-build block

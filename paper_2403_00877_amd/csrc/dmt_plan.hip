@@ -61,6 +61,7 @@ extern "C" dmt_status dmt_plan_create(dmt_plan** out, int32_t num_tables, const 
   };
   p->sw.tm_big = env("DMT_TM_BIG", 1);
   p->sw.tm_fuse = env("DMT_TM_FUSE", 1);
+  p->sw.tm_direct = env("DMT_TM_DIRECT", 1);
   p->sw.tmb_ksplit = env("DMT_TMB_KSPLIT", 0);
   p->sw.bwd_kernel = env("DMT_BWD_KERNEL", 0);
   p->sw.keys_lg = env("DMT_KEYS_LG", -1);

@@ -255,8 +255,21 @@ constexpr int kBigLdsBytes = 4 * kBigTileElems * 2;         // 2 stages x (A + B
 // DOTS: the operand's first K0 columns are the tower's pairwise dot terms, which the block
 // computes itself (Gram tiles, as in tm_dots_mfma) straight into the first LDS stage, so the
 // pooled tensor is read once and the dot terms never exist in global memory.
-template <int DT, bool DOTS, int TAG = DMT_TM_TAG, bool KEEPZ = false>
+//
+// DIRECT (launches whose tiles are all interior: M and N multiples of 256, K of 64, no dot
+// terms): the operand tiles go from global memory straight into LDS (global_load_lds_dwordx4:
+// a wave's 64 lanes fill 1 KB of consecutive LDS, 16 bytes a lane), so the K loop has no
+// register stage and no LDS stores.  LDS rows are then 128 bytes with no padding; each lane
+// fetches the 16-byte column chunk (slot ^ row % 8) of its row, which puts the eight chunks
+// of eight consecutive rows into eight different bank groups, and the fragment reads apply
+// the same exclusive-or: conflict-free without padding.  The tile of step k + 1 is requested
+// at the start of step k into the other stage; every wave waits for its own requests before
+// the barrier that ends the step.  (The requests are written as inline assembly: told about
+// them, the compiler would make every LDS read of the current tile wait for the next tile's
+// requests, since it cannot tell the two stages apart.)
+template <int DT, bool DOTS, int TAG = DMT_TM_TAG, bool KEEPZ = false, bool DIRECT = false>
 __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunch L) {
+  static_assert(!(DIRECT && DOTS), "in-kernel dot terms are written into a padded first stage");
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
   // XCD-aware rasterisation.  Consecutive block ids go to different XCDs, so block b belongs
   // to XCD b % 8 and is that XCD's (b / 8)-th block.  The launch's tiles are cut into
@@ -346,6 +359,61 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
   };
 
   const int nk = (K + BK - 1) / BK;
+  if constexpr (DIRECT) {
+    constexpr int kStageEl = 2 * LBM * BK;         // one stage: A then W, 128-byte rows
+    // instruction j of wave w fills LDS rows (j * 8 + w) * 8 .. + 7 of an operand; lane l holds
+    // slot l % 8 of row l / 8 there and fetches column chunk (l % 8) ^ (l / 8) of that row
+    const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) uint16_t*)lds;
+    const int chunk = (lane & 7) ^ (lane >> 3);
+    uint32_t va[4], vb[4];                         // byte offsets of this lane's chunks at k = 0
+#pragma clang loop unroll(full)
+    for (int j = 0; j < 4; ++j) {
+      const int r = (j * 8 + wave) * 8 + (lane >> 3);
+      va[j] = ((uint32_t)(m0 + r) * (uint32_t)lda + chunk * 8) * 2u;
+      vb[j] = ((uint32_t)(n0 + r) * (uint32_t)ldw + chunk * 8) * 2u;
+    }
+    auto request_tile = [&](int stage, int kt) __attribute__((always_inline)) {
+      const uint16_t* ak = A + kt * BK;
+      const uint16_t* wk = W + kt * BK;
+#pragma clang loop unroll(full)
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t da = __builtin_amdgcn_readfirstlane(
+            lds0 + (uint32_t)(stage * kStageEl * 2 + (j * 8 + wave) * 1024));
+        const uint32_t db = da + LBM * BK * 2;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :: "s"(da), "v"(va[j]), "s"(ak) : "memory");
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :: "s"(db), "v"(vb[j]), "s"(wk) : "memory");
+      }
+    };
+    // fragment reads: row (lane % 32) of a 32-row block, chunk 2 kk + lane / 32, swizzled
+    int sw[BK / 16];
+#pragma clang loop unroll(full)
+    for (int kk = 0; kk < BK / 16; ++kk) sw[kk] = (((kk * 2 + (lane >> 5)) ^ (lane & 7)) * 8);
+    request_tile(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0f70);            // vmcnt(0): this wave's requests have landed
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+      const int cur = kt & 1;
+      if (kt + 1 < nk) request_tile(cur ^ 1, kt + 1);
+      const uint16_t* ap = lds + cur * kStageEl + (wm * 128 + (lane & 31)) * BK;
+      const uint16_t* bp = lds + cur * kStageEl + LBM * BK + (wn * 64 + (lane & 31)) * BK;
+#pragma clang loop unroll(full)
+      for (int kk = 0; kk < BK / 16; ++kk) {
+        uint4 a[4], b[2];
+#pragma clang loop unroll(full)
+        for (int i = 0; i < 4; ++i) a[i] = *(const uint4*)(ap + i * 32 * BK + sw[kk]);
+#pragma clang loop unroll(full)
+        for (int j = 0; j < 2; ++j) b[j] = *(const uint4*)(bp + j * 32 * BK + sw[kk]);
+#pragma clang loop unroll(full)
+        for (int i = 0; i < 4; ++i)
+#pragma clang loop unroll(full)
+          for (int j = 0; j < 2; ++j) acc[i][j] = mfma32<DT>(a[i], b[j], acc[i][j]);
+      }
+      __builtin_amdgcn_s_waitcnt(0x0f70);
+      __syncthreads();
+    }
+  } else {
   load_tile(0);
   store_tile(0, 0);
   if (nk > 1) load_tile(1);
@@ -420,6 +488,7 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
         for (int j = 0; j < 2; ++j) acc[i][j] = mfma32<DT>(a[i], b[j], acc[i][j]);
     }
     __syncthreads();
+  }
   }
 
   // Epilogue through LDS, one 128-row half of the tile at a time: the waves that own the half
@@ -789,6 +858,8 @@ void launch_groups(const dmt_plan* p, std::vector<TmGroup>& groups, hipStream_t 
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
           (void)hipFuncSetAttribute((const void*)tm_gemm_mfma_256<DT, true, DMT_TM_TAG, true>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
+          (void)hipFuncSetAttribute((const void*)tm_gemm_mfma_256<DT, false, DMT_TM_TAG, false, true>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
           configured = true;
         }
         int32_t nst = 0;                                      // super-tiles of the launch
@@ -802,6 +873,15 @@ void launch_groups(const dmt_plan* p, std::vector<TmGroup>& groups, hipStream_t 
         L.tile_start[L.ngroups] = nst;
         const int32_t big_tiles = (nst + 7) / 8 * 8 * kSuper;
         DmtScope sc_(p, kid, s);
+        // every tile interior and every operand row 16-byte aligned: tiles go straight to LDS
+        bool direct = !dots && p->sw.tm_direct != 0;
+        for (int i = 0; i < L.ngroups; ++i) {
+          const TmGroup& g = L.g[i];
+          const int kk = g.ksplit > 1 ? g.klen : g.K1;
+          direct = direct && g.M % LBM == 0 && g.N % LBN == 0 && kk % BK == 0 && g.K1 % BK == 0 &&
+                   g.lda1 % 8 == 0 && g.ldw % 8 == 0 &&
+                   (((uintptr_t)g.A1 | (uintptr_t)g.W) & 15) == 0;
+        }
         bool keepz = false;                   // a training forward keeps the dot terms
         for (int i = 0; i < L.ngroups; ++i) keepz = keepz || (dots && L.g[i].U != nullptr);
         if (keepz)
@@ -810,6 +890,9 @@ void launch_groups(const dmt_plan* p, std::vector<TmGroup>& groups, hipStream_t 
         else if (dots)
           hipLaunchKernelGGL((tm_gemm_mfma_256<DT, true>), dim3(big_tiles), dim3(kBigThreads),
                              kBigLdsBytes, s, L);
+        else if (direct)
+          hipLaunchKernelGGL((tm_gemm_mfma_256<DT, false, DMT_TM_TAG, false, true>), dim3(big_tiles),
+                             dim3(kBigThreads), kBigLdsBytes, s, L);
         else
           hipLaunchKernelGGL((tm_gemm_mfma_256<DT, false>), dim3(big_tiles), dim3(kBigThreads),
                              kBigLdsBytes, s, L);

@@ -55,6 +55,23 @@ def test_large_scaled_cross_linear_bf16():
     check_tm(w, chained=True)
 
 
+@pytest.mark.parametrize("direct", ["1", "0"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_cross_linear_on_interior_tiles(direct, dtype, monkeypatch):
+    """A batch and widths that are multiples of the 256 x 256 tile: such launches load their
+    operand tiles straight into LDS (DMT_TM_DIRECT=0 keeps the register-staged loop); two 1024
+    x 1024 cross layers and a 1024 -> 256 projection on two towers, B = 512."""
+    monkeypatch.setenv("DMT_TM_DIRECT", direct)
+    w = wl.scaled(wl.large(), max_rows=3000, batch=512)
+    sel = [f for f in range(256) if w.table_to_tower[f] in (0, 1)][:16]
+    w.rows = [w.rows[f] for f in sel]
+    w.dims = [128] * 16
+    w.table_to_tower = [f // 8 for f in range(16)]
+    w.tm_out = [256, 256]
+    w.table_dtype = w.pooled_dtype = w.tm_dtype = dtype
+    check_tm(w, chained=True)
+
+
 def test_imbalanced_scaled_linear_f16():
     # towers of unequal width (mixed 32/64/128 dims), Linear -> 128
     check_tm(wl.scaled(wl.imbalanced(), max_rows=2000, batch=777, num_tables=26), chained=True)
