@@ -1306,17 +1306,19 @@ __global__ __launch_bounds__(kBlock) void bwd_fixup_update(
   if (t0 >= ntiles - 1) return;
   const int gl = threadIdx.x & (GL - 1);
   const int64_t p0 = t0 * kReduceTile, p1 = p0 + kReduceTile;    // p1 < nnz here
-  const uint64_t r_last = pk[p1 - 1];
+  // (the four records the decisions below look at are requested together: their latencies
+  // would otherwise follow one another in every group)
+  const uint64_t r_last = pk[p1 - 1], r_next = pk[p1], r_first = pk[p0], r_before = pk[p0 > 0 ? p0 - 1 : 0];
   const uint32_t k_last = (uint32_t)(r_last >> 32);
-  if (k_last != (uint32_t)(pk[p1] >> 32) || k_last >= total_rows) return;
+  if (k_last != (uint32_t)(r_next >> 32) || k_last >= total_rows) return;
   // the run's table follows from the bag of any of its records (no search through the row bases)
   const uint32_t bag = (uint32_t)r_last;
   if (bag >= nbags) return;
   const uint32_t f = bag / B;
   const int64_t row = (int64_t)k_last - meta[f].row_base;
   if (row < 0 || row >= meta[f].rows) return;      // key and bag disagree: not a row to touch
-  const uint32_t k_first = (uint32_t)(pk[p0] >> 32);
-  if (k_first == k_last && p0 > 0 && (uint32_t)(pk[p0 - 1] >> 32) == k_first) return;
+  const uint32_t k_first = (uint32_t)(r_first >> 32);
+  if (k_first == k_last && p0 > 0 && (uint32_t)(r_before >> 32) == k_first) return;
   // last tile the run reaches: the largest t with the run's key at the tile's first record
   // (gallop first: most runs end within a tile or two)
   int64_t t1 = t0 + 1, hi = ntiles;               // holds at t1, fails at hi
