@@ -48,6 +48,7 @@ constexpr int kReduceTile = 128;                 // sorted records per reduce ti
 constexpr int kReduceUnroll = DMT_RU;
 constexpr uint32_t kInertBit = 0x80000000u;      // key flag of an id outside its table
 constexpr int kScanThreads = 1024;               // block of the per-table offset scan
+constexpr int kScanBatch = 16;                   // sort blocks whose counts it reads together
 
 struct BwdWs {
   uint64_t* pk_a;
@@ -252,12 +253,19 @@ __global__ __launch_bounds__(kScanThreads) void radix_scan(uint32_t* __restrict_
   const int sl = threadIdx.x >> bits, d = threadIdx.x & (R - 1);
   const uint32_t per = (nb + slices - 1) / slices;
   const uint32_t lo = min(nb, sl * per), hi = min(nb, lo + per);
+  // (counts are read sixteen blocks at a time: one by one, every read would wait for the store
+  // before it, which the compiler must assume may touch the same word)
   uint32_t run = 0;
-  for (uint32_t b = lo; b < hi; ++b) {
-    uint32_t* p = hist + (int64_t)(b0 + b) * kMaxRadix + d;
-    const uint32_t v = *p;
-    *p = run;
-    run += v;
+  for (uint32_t b = lo; b < hi; b += kScanBatch) {
+    uint32_t v[kScanBatch];
+#pragma unroll
+    for (int q = 0; q < kScanBatch; ++q)
+      v[q] = b + q < hi ? hist[(int64_t)(b0 + b + q) * kMaxRadix + d] : 0u;
+#pragma unroll
+    for (int q = 0; q < kScanBatch; ++q) {
+      if (b + q < hi) hist[(int64_t)(b0 + b + q) * kMaxRadix + d] = run;
+      run += v[q];
+    }
   }
   tot[threadIdx.x] = run;
   __syncthreads();
@@ -272,7 +280,15 @@ __global__ __launch_bounds__(kScanThreads) void radix_scan(uint32_t* __restrict_
   if (sl == 0) dbase[d] = ex;
   __syncthreads();
   const uint32_t add = seg_begin[f] + dbase[d] + before;
-  for (uint32_t b = lo; b < hi; ++b) hist[(int64_t)(b0 + b) * kMaxRadix + d] += add;
+  for (uint32_t b = lo; b < hi; b += kScanBatch) {
+    uint32_t v[kScanBatch];
+#pragma unroll
+    for (int q = 0; q < kScanBatch; ++q)
+      v[q] = b + q < hi ? hist[(int64_t)(b0 + b + q) * kMaxRadix + d] : 0u;
+#pragma unroll
+    for (int q = 0; q < kScanBatch; ++q)
+      if (b + q < hi) hist[(int64_t)(b0 + b + q) * kMaxRadix + d] = v[q] + add;
+  }
 }
 
 __global__ __launch_bounds__(kBlock) void radix_scatter(
