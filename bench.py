@@ -65,6 +65,10 @@ def parse():
                     help="instead of the step: lookup -> Tower Module run over the batch in 1, 2, 4 ... "
                          "chunks (each chunk a batch of its own), to see whether a pooled block that "
                          "stays in the caches between the two calls pays for the smaller launches")
+    ap.add_argument("--gather-rates", action="store_true",
+                    help="instead of the step: the rate of plain random row reads on this machine "
+                         "(dmt_calibration_gather) from tables that fit the L2, the Infinity Cache, "
+                         "or neither")
     ap.add_argument("--traffic-child", action="store_true", help=argparse.SUPPRESS)
     return ap.parse_args()
 
@@ -666,6 +670,42 @@ def chunk_sweep(args):
     return 0
 
 
+def gather_rates(args):
+    """What rows at random addresses reach on this machine, with a kernel that does nothing else:
+    uniform random ids, 64-, 256- and 512-byte rows, tables of 2 MiB (inside one XCD's L2), 64 MiB
+    (inside the Infinity Cache), 1 GiB and 16 GiB.  One JSON line."""
+    import torch
+    import paper_2403_00877_amd as dmt
+    n = 1 << 25
+    out = torch.empty(dmt.binding.DMT_CALIBRATION_GATHER_BLOCKS * 256 * 16, dtype=torch.uint8, device="cuda")
+    rows_out = []
+    for table_bytes in (2 << 20, 64 << 20, 1 << 30, 16 << 30):
+        table = torch.zeros(table_bytes, dtype=torch.uint8, device="cuda")
+        for row_bytes in (64, 256, 512):
+            g = torch.Generator(device="cuda")
+            g.manual_seed(table_bytes // row_bytes)
+            ids = torch.randint(0, table_bytes // row_bytes, (n,), generator=g, device="cuda", dtype=torch.int32)
+            for _ in range(3):
+                dmt.dmt_calibration_gather(table, row_bytes, ids, out)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 10
+            a.record()
+            for _ in range(reps):
+                dmt.dmt_calibration_gather(table, row_bytes, ids, out)
+            b.record()
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b) / reps
+            rows_out.append(dict(table_MiB=table_bytes >> 20, row_bytes=row_bytes, rows_gathered=n,
+                                 ms=round(ms, 4), row_GBs=round(n * row_bytes / ms / 1e6, 1),
+                                 rows_per_us=round(n / ms / 1e3, 1)))
+            log("[bench] gather: table %6d MiB, %3d-byte rows: %.3f ms, %.0f GB/s" %
+                (table_bytes >> 20, row_bytes, ms, n * row_bytes / ms / 1e6))
+        del table
+    print(json.dumps({"gather_rates": {"what": "dmt_calibration_gather, uniform random ids, 2^25 rows per launch",
+                                       "rows": rows_out}}), flush=True)
+    return 0
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -676,6 +716,8 @@ def main():
         return traffic_child(args)
     if args.chunk_sweep:
         return chunk_sweep(args)
+    if args.gather_rates:
+        return gather_rates(args)
     with_others = args.workload == "backward" and not args.no_others
     names = [args.workload] + (list(OTHERS) if with_others else [])
     # the counter runs come first: children of a process that has not touched the GPU yet

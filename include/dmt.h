@@ -533,6 +533,21 @@ dmt_status dmt_profile_read(dmt_plan* plan, void* stream, double* total_ms, int6
  */
 dmt_status dmt_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
 
+/*
+ * Plain gather of n rows of `row_bytes` bytes (a power of two, 16 ... 1024) by id from a
+ * row-major table of `rows` rows, by a kernel named dmt_gather_kernel that does nothing else
+ * (eight row reads in flight per wave).  It exists so that the rate of the lookup and update
+ * kernels, whose traffic is rows at random addresses, can be set against what such reads reach
+ * on the machine at hand, from a table that fits the L2, the Infinity Cache, or neither.
+ *   table dev [rows][row_bytes], 16-byte aligned; ids dev int32 [n] (an id outside [0, rows)
+ *   reads row 0); out dev, DMT_CALIBRATION_GATHER_BLOCKS * 256 * 16 bytes, 16-byte aligned (one
+ *   folded word per thread, written so that the reads cannot be optimised away).
+ * Traffic: n * row_bytes bytes of rows and 4 n bytes of ids read.
+ */
+#define DMT_CALIBRATION_GATHER_BLOCKS 2048
+dmt_status dmt_calibration_gather(const void* table, int64_t rows, int32_t row_bytes,
+                                  const int32_t* ids, int64_t n, void* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -95,6 +95,7 @@ def _load() -> ctypes.CDLL:
     lib.dmt_profile_enable.argtypes = [vp, ctypes.c_uint32]
     lib.dmt_profile_read.argtypes = [vp, vp, vp, vp]
     lib.dmt_calibration_copy.argtypes = [vp, vp, sz, vp]
+    lib.dmt_calibration_gather.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int64, vp, vp]
     f64 = ctypes.c_double
     lib.dmt_tp_workspace_bytes.argtypes = [vp, i64]
     lib.dmt_tp_workspace_bytes.restype = sz
@@ -117,7 +118,7 @@ EXPORTS = ["dmt_status_str", "dmt_plan_create", "dmt_plan_destroy", "dmt_plan_la
            "dmt_tm_kept_bytes", "dmt_tower_module_fwd_keep",
            "dmt_bwd_workspace_bytes", "dmt_tower_lookup_bwd_update",
            "dmt_last_device_error", "dmt_kernel_name", "dmt_profile_enable", "dmt_profile_read",
-           "dmt_calibration_copy", "dmt_tp_workspace_bytes", "dmt_tp_interaction",
+           "dmt_calibration_copy", "dmt_calibration_gather", "dmt_tp_workspace_bytes", "dmt_tp_interaction",
            "dmt_tp_embed", "dmt_tp_kmeans", "dmt_sptt_peer_order", "dmt_sptt_peer_permute",
            "dmt_sptt_shuffle", "dmt_plan_set_row_shards", "dmt_bwd_noalloc_scratch_bytes",
            "dmt_tower_lookup_bwd_update_noalloc", "dmt_sptt_peer_permute_ids"]
@@ -350,6 +351,18 @@ def dmt_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> N
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() >= nbytes
     _check("dmt_calibration_copy", _lib.dmt_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)))
+
+
+DMT_CALIBRATION_GATHER_BLOCKS = 2048
+
+
+def dmt_calibration_gather(table: torch.Tensor, row_bytes: int, ids: torch.Tensor, out: torch.Tensor,
+                           stream=None) -> None:
+    """table: any dtype, rows of row_bytes bytes; ids int32; out: at least 2048 * 256 * 16 bytes."""
+    rows = table.numel() * table.element_size() // row_bytes
+    assert out.numel() * out.element_size() >= DMT_CALIBRATION_GATHER_BLOCKS * 256 * 16
+    _check("dmt_calibration_gather", _lib.dmt_calibration_gather(
+        _ptr(table), rows, row_bytes, _ptr(ids), ids.numel(), _ptr(out), _stream(stream)))
 
 
 def dmt_tp_workspace_bytes(plan: dmt_plan, B: int) -> int:

@@ -279,6 +279,53 @@ __global__ __launch_bounds__(256) void dmt_copy_kernel(uint4* __restrict__ dst,
     dst[i] = src[i];
 }
 
+// Rows of `row_bytes` bytes (16 << log2_lpr) gathered by id, 64 >> log2_lpr rows per wave
+// instruction and eight instructions in flight per wave, nothing else: what random row reads
+// reach on the machine at hand.  Every lane folds what it read into one word and stores it at
+// the end, so that the loads cannot be dropped.
+__global__ __launch_bounds__(256) void dmt_gather_kernel(const char* __restrict__ table, int64_t rows,
+                                                         int log2_lpr, const int32_t* __restrict__ ids,
+                                                         int64_t n, uint4* __restrict__ out) {
+  constexpr int kInFlight = 8;
+  const int lane = threadIdx.x & 63;
+  const int rpi = 64 >> log2_lpr;                             // rows per instruction
+  const int sub = lane >> log2_lpr, chunk = lane & ((1 << log2_lpr) - 1);
+  const int64_t wave = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
+  const int64_t nwaves = ((int64_t)gridDim.x * 256) >> 6;
+  const int64_t per_step = (int64_t)rpi * kInFlight;
+  uint4 acc = make_uint4(0, 0, 0, 0);
+  for (int64_t base = wave * per_step; base < n; base += nwaves * per_step) {
+    uint4 v[kInFlight];
+#pragma unroll
+    for (int u = 0; u < kInFlight; ++u) {
+      const int64_t i = base + (int64_t)u * rpi + sub;
+      int64_t r = i < n ? (int64_t)ids[i] : 0;
+      r = (uint64_t)r < (uint64_t)rows ? r : 0;               // an id outside the table reads row 0
+      v[u] = make_uint4(0, 0, 0, 0);
+      if (i < n) v[u] = *(const uint4*)(table + ((r << log2_lpr) + chunk) * 16);
+    }
+#pragma unroll
+    for (int u = 0; u < kInFlight; ++u) {
+      acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w;
+    }
+  }
+  out[(size_t)blockIdx.x * 256 + threadIdx.x] = acc;
+}
+
+extern "C" dmt_status dmt_calibration_gather(const void* table, int64_t rows, int32_t row_bytes,
+                                             const int32_t* ids, int64_t n, void* out,
+                                             void* stream) {
+  if (!table || !ids || !out || rows <= 0 || n < 0 || ((uintptr_t)table & 15) || ((uintptr_t)out & 15))
+    return DMT_EINVAL;
+  int log2_lpr = 0;
+  while ((16 << log2_lpr) < row_bytes) ++log2_lpr;
+  if (row_bytes < 16 || row_bytes > 1024 || (16 << log2_lpr) != row_bytes) return DMT_EINVAL;
+  if (n == 0) return DMT_OK;
+  hipLaunchKernelGGL(dmt_gather_kernel, dim3(DMT_CALIBRATION_GATHER_BLOCKS), dim3(256), 0,
+                     (hipStream_t)stream, (const char*)table, rows, log2_lpr, ids, n, (uint4*)out);
+  return hipGetLastError() == hipSuccess ? DMT_OK : DMT_EHIP;
+}
+
 extern "C" dmt_status dmt_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
   if (!dst || !src || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15))
     return DMT_EINVAL;
