@@ -1,6 +1,6 @@
 """Parity at the benchmark configurations' full sizes, in the launch configurations bench.py
-times: the Backward workload (= Mid tables and lookups, 64 x 1M x 128 fp16,
-B = 8192; the benchmark's own step), Imbalanced (128 mixed-width tables,
+times: Mid under its own seed (forward only), the Backward workload (= Mid tables and
+lookups, 64 x 1M x 128 fp16, B = 8192; the benchmark's own step), Imbalanced (128 mixed-width tables,
 B = 65536, forward + backward) and Large (256 bf16 tables, ~97 GB, B = 16384,
 forward + two cross layers + projection).
 
@@ -106,7 +106,8 @@ class FullRun:
         return t.cpu().numpy()
 
 
-RUNS = {"backward": dict(n_samples=96, n_rows=1500, device_ids=False),
+RUNS = {"mid": dict(n_samples=48, n_rows=0, device_ids=False),
+        "backward": dict(n_samples=96, n_rows=1500, device_ids=False),
         "imbalanced": dict(n_samples=64, n_rows=1500, device_ids=True),
         "large": dict(n_samples=24, n_rows=0, device_ids=True)}
 
