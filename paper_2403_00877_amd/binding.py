@@ -8,7 +8,6 @@ fallback: if the library cannot be loaded the import of this module raises.
 from __future__ import annotations
 
 import ctypes
-import os
 from typing import List, Optional, Sequence
 
 import torch

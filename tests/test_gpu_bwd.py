@@ -5,7 +5,7 @@ import torch
 
 import oracle
 import workloads as wl
-from harness import RTOL, DeviceWorkload, assert_close, to_device, to_f64
+from harness import RTOL, DeviceWorkload, assert_close, to_f64
 
 pytestmark = pytest.mark.gpu
 

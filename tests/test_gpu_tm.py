@@ -1,5 +1,4 @@
 """GPU parity of dmt_tower_module_fwd against the CPU oracle."""
-import numpy as np
 import pytest
 import torch
 

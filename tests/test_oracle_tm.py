@@ -3,7 +3,6 @@ inputs, closed forms and special cases; shapes from the paper's Sec. 4."""
 import os
 
 import numpy as np
-import pytest
 
 import oracle
 

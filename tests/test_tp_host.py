@@ -1,6 +1,5 @@
 """Host stages of the Tower Partitioner (paper Sec. 3.3) through the C ABI against the oracle:
 distance + Adam embedding, constrained K-means.  They run on the host, so no GPU is needed."""
-import ctypes
 
 import numpy as np
 import pytest
