@@ -730,7 +730,11 @@ def main():
         for n in OTHERS:
             gc.collect()
             torch.cuda.empty_cache()
-            out["other_workloads"][n] = run_workload(args, n, traffic.get(n), primary=False)
+            try:                                   # the default line must not hang on a side workload
+                out["other_workloads"][n] = run_workload(args, n, traffic.get(n), primary=False)
+            except Exception as e:
+                log("[bench] %s failed: %r" % (n, e))
+                out["other_workloads"][n] = {"error": repr(e)}
     print(json.dumps(out), flush=True)
     return 0
 
