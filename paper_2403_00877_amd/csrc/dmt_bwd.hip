@@ -712,8 +712,10 @@ __global__ __launch_bounds__(kBlock) void bwd_reduce_update(
       for (int u = 0; u < kReduceUnroll; ++u) {
         const int src = lane0 + ((i0 + u) & (GL - 1));
         const uint32_t go = __shfl(goff4_l, src);
-        bool on = lane_on && i0 + u < cnt && go != 0xffffffffu;
-        if (!UD) on = on && gl * 4 < __shfl(D_l, src);
+        // (every lane takes part in the exchange: a lane that is off would hand out nothing,
+        // and the lanes past the widest row hold records like any other)
+        const int D_src = UD ? Dmax : __shfl(D_l, src);
+        const bool on = lane_on && i0 + u < cnt && go != 0xffffffffu && gl * 4 < D_src;
         g[u] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (on) g[u] = grad4[(size_t)go + gl];
       }

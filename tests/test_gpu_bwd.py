@@ -128,6 +128,16 @@ def test_narrow_and_wide_rows(dims):
     check_bwd(w)
 
 
+@pytest.mark.parametrize("widest", [136, 160, 200, 248])
+def test_widest_row_between_128_and_256_columns(widest):
+    """Mixed widths whose widest row is neither 128 nor 256 columns take the lane-group walk with
+    64-lane groups of which only widest / 4 lanes hold columns; the records of the other lanes
+    count like any other (they once did not: their gradients were dropped)."""
+    w = wl.scaled(wl.imbalanced(), max_rows=700, batch=150, num_tables=9)
+    w.dims = [widest, 64, 16, 128, widest, 32, 8, 96, 24]
+    check_bwd(w)
+
+
 def test_large_scaled_bf16():
     w = wl.scaled(wl.large(), max_rows=30000, batch=130, num_tables=40)
     w.backward = True
