@@ -44,3 +44,66 @@ def test_random_configuration(seed):
     w = random_workload(seed)
     check_lookup(w)
     check_bwd(w)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_configuration_with_ids_outside_their_tables(seed):
+    """About one lookup in fifty names a row its table does not have (negative, or past the
+    end): the lookup and the update must behave exactly as if those lookups were not there,
+    and report the first of them."""
+    import torch
+    import oracle
+    from harness import RTOL, DeviceWorkload, assert_close, to_f64
+    from test_gpu_bwd import run_bwd
+
+    w = random_workload(500 + seed)
+    rng = np.random.default_rng([78, seed])
+    idx, off = wl.lookup_batch(w, 0)
+    if len(idx) == 0:
+        pytest.skip("no lookups drawn")
+    F, B = w.num_tables, w.batch
+    lens = np.diff(off)
+    bag_of = np.repeat(np.arange(F * B), lens)
+    nbad = max(1, len(idx) // 50)
+    bad_pos = np.sort(rng.choice(len(idx), size=nbad, replace=False))
+    bad = idx.copy()
+    rows_of = np.asarray(w.rows)[bag_of[bad_pos] // B]
+    bad[bad_pos] = np.where(rng.random(nbad) < 0.5, rows_of + rng.integers(0, 5, nbad),
+                            -1 - rng.integers(0, 5, nbad)).astype(np.int32)
+    keep = np.ones(len(idx), bool)
+    keep[bad_pos] = False
+    clean_idx = np.ascontiguousarray(idx[keep])
+    clean_off = np.concatenate([[0], np.cumsum(np.bincount(bag_of[keep], minlength=F * B))]).astype(np.int64)
+
+    dw = DeviceWorkload(w, with_state=True)
+    got = to_f64(dw.lookup(bad, off, "f32"))
+    assert dw.dmt.dmt_last_device_error(dw.plan) == int(bad_pos[0])
+    ref = oracle.lookup_towered(dw.host_tables, w.table_dtype, w.dims, w.table_to_tower, clean_idx,
+                                clean_off, B)
+    for t, (g, r) in enumerate(zip(dw.split_towers(got), ref)):
+        assert_close(g, r, 1e-5, "lookup tower %d" % t)
+
+    grad = wl.grad_pooled(w, 0)
+    before = [t.clone() for t in dw.tables]
+    run_bwd(dw, bad, off, grad, w.lr, w.eps, debug=False)
+    assert dw.dmt.dmt_last_device_error(dw.plan) == int(bad_pos[0])
+    st0 = [np.zeros(r, np.float32) for r in w.rows]
+    want = oracle.bwd_update(dw.host_tables, w.table_dtype, st0, w.dims, w.table_to_tower, clean_idx,
+                             clean_off, B, grad, w.lr, w.eps)
+    for f in range(F):
+        m = want["key_table"] == f
+        rows = want["key_row"][m]
+        D = w.dims[f]
+        new_rows = want["new_rows"][m][:, :D]
+        if w.table_dtype != "f32":
+            new_rows = wl.decode(oracle.round_to(new_rows, w.table_dtype), w.table_dtype)
+        sel = torch.from_numpy(rows).cuda()
+        assert_close(to_f64(dw.tables[f][sel]), new_rows, RTOL[w.table_dtype], "rows of table %d" % f)
+        assert_close(to_f64(dw.states[f][sel]), want["new_state"][m].astype(np.float32), 1e-5,
+                     "state of table %d" % f)
+        untouched = np.ones(w.rows[f], bool)
+        untouched[rows] = False
+        u = torch.from_numpy(np.nonzero(untouched)[0]).cuda()
+        bits = torch.int16 if w.table_dtype != "f32" else torch.int32
+        assert torch.equal(dw.tables[f][u].view(bits), before[f][u].view(bits))
+        assert torch.count_nonzero(dw.states[f][u]).item() == 0
