@@ -345,6 +345,52 @@ def test_random_small_configurations(seed):
     check_tm_bwd(w, rtol=ftol, keep=True)
 
 
+def _random_medium_config(seed):
+    """Larger arbitrary towers: 2-16 features of 32-128 columns, batches and widths that are
+    sometimes whole multiples of the 256 x 256 tile (the contraction then loads its operand
+    tiles straight into LDS) and sometimes ragged."""
+    rng = np.random.default_rng(5000 + seed)
+    kinds = [wl.TM_LINEAR_RELU, wl.TM_DOT_LINEAR, wl.TM_CROSS_LINEAR, wl.TM_DLRM, wl.TM_CROSS_LOWRANK_LINEAR]
+    kind = kinds[seed % len(kinds)]
+    dt = ["bf16", "f16"][(seed // len(kinds)) % 2]
+    nfs = [int(rng.choice([2, 4, 8, 16])), int(rng.integers(2, 13))]
+    dims = [int(rng.choice([64, 128])), int(rng.choice([32, 64, 128]))]
+    batch = int(rng.choice([256, 512, 768, 1024])) if rng.random() < 0.5 else int(rng.integers(200, 1500))
+    w = wl.scaled(wl.mid(), max_rows=300, batch=batch, num_tables=sum(nfs))
+    w.table_to_tower = [0] * nfs[0] + [1] * nfs[1]
+    w.dims = [dims[0]] * nfs[0] + [dims[1]] * nfs[1]
+    w.tm_kind = kind
+    w.tm_dtype = w.pooled_dtype = dt
+    w.tm_cross_layers = int(rng.integers(1, 3)) if kind in (wl.TM_CROSS_LINEAR, wl.TM_CROSS_LOWRANK_LINEAR) else 0
+    w.tm_out = [int(rng.choice([256, 512])) if rng.random() < 0.5 else int(rng.integers(100, 600)) for _ in nfs]
+    if kind == wl.TM_DLRM:
+        w.tm_feat_out = int(rng.integers(1, 5)) * 8
+        w.tm_out = [int(rng.integers(100, 400)) + nf * w.tm_feat_out for nf in nfs]
+    if kind == wl.TM_CROSS_LOWRANK_LINEAR:
+        w.tm_feat_out = int(rng.choice([64, 128, 256]))
+    return w
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_random_medium_configurations(seed):
+    """Forward and backward of arbitrary towers wide and long enough for the 256 x 256 kernel,
+    the in-kernel dot terms, split-K weight gradients and the straight-to-LDS operand loads."""
+    w = _random_medium_config(seed)
+    dw = DeviceWorkload(w)
+    tm = TowerModules(dw)
+    idx, off = wl.lookup_batch(w)
+    pooled = oracle.lookup_towered(dw.host_tables, w.table_dtype, w.dims, w.table_to_tower, idx, off, w.batch)
+    enc = [oracle.round_to(p, tm.dtype) for p in pooled]
+    x_dev = torch.cat([to_device(e, tm.dtype).reshape(-1) for e in enc])
+    got = to_f64(tm.run(x_dev))
+    ref = tm.oracle([wl.decode(e, tm.dtype) for e in enc])
+    ftol = 4e-2 if w.tm_cross_layers > 0 else 2e-2
+    for t, (g, r) in enumerate(zip(dw.split_towers(got, tm.out_widths), ref)):
+        r = wl.decode(oracle.round_to(r, tm.dtype), tm.dtype)
+        assert_close(g, r, ftol, "seed %d %s forward tower %d" % (seed, w.tm_kind, t))
+    check_tm_bwd(w, rtol=ftol, keep=bool(seed & 1))
+
+
 def test_rejects_bad_arguments():
     w = wl.tiny()
     dw = DeviceWorkload(w)
