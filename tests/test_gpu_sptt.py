@@ -196,3 +196,36 @@ def test_peer_permute_of_ids_rejects_bad_arguments():
     assert raw(None, o.data_ptr(), 1, 4, 2, 2, 8, i2.data_ptr(), o2.data_ptr(), None) == 1
     assert raw(*a, 1, 2048, 2, 2, 0, i2.data_ptr(), o2.data_ptr(), None) == 2    # more ranks than supported
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_of_all_three_shuffles(seed):
+    """Seeded arbitrary feature / rank / block counts through the block permute (step c), the
+    block transpose (step e) and the permute on ids (steps b and c swapped), bit for bit."""
+    rng = np.random.default_rng([91, seed])
+    F = int(rng.integers(1, 20))
+    L = int(rng.choice([1, 2, 3, 4, 8]))
+    G = L * int(rng.integers(1, 9))
+    Bl = int(np.exp(rng.uniform(0, np.log(600))))
+    N = int(rng.choice([4, 8, 16, 32, 128]))
+    z = rng.integers(0, 2**31, size=(F, G, Bl, N), dtype=np.int64).astype(np.uint32)
+    d_in = torch.from_numpy(z.view(np.uint8).reshape(-1)).cuda()
+    d_out = torch.zeros_like(d_in)
+    dmt.dmt_sptt_peer_permute(d_in, d_out, F, G, L, Bl * N * 4)
+    torch.cuda.synchronize()
+    order = sptt.peer_order(G, L)
+    np.testing.assert_array_equal(d_out.cpu().numpy().view(np.uint32).reshape(F, G, Bl, N), z[:, order])
+    d_out.zero_()
+    dmt.dmt_sptt_shuffle(d_in, d_out, F, G, Bl * N * 4)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(d_out.cpu().numpy().view(np.uint32).reshape(G, F, Bl, N),
+                                  z.transpose(1, 0, 2, 3))
+    idx, off = _jagged(rng, F * G * Bl, int(rng.choice([0, 2, 9, 60])), 1 << 20, empty=float(rng.random()) * 0.8)
+    d_idx, d_off = torch.from_numpy(idx).cuda(), torch.from_numpy(off).cuda()
+    o_idx = torch.full((max(len(idx), 1),), -7, dtype=torch.int32, device="cuda")
+    o_off = torch.full((len(off),), -7, dtype=torch.int64, device="cuda")
+    dmt.dmt_sptt_peer_permute_ids(d_idx, d_off, F, G, L, Bl, o_idx[:len(idx)], o_off)
+    torch.cuda.synchronize()
+    want_idx, want_off = sptt.peer_permute_ids(idx, off, F, G, L, Bl)
+    np.testing.assert_array_equal(o_off.cpu().numpy(), want_off)
+    np.testing.assert_array_equal(o_idx[:len(idx)].cpu().numpy(), want_idx)
