@@ -107,3 +107,12 @@ def test_random_configuration_with_ids_outside_their_tables(seed):
         bits = torch.int16 if w.table_dtype != "f32" else torch.int32
         assert torch.equal(dw.tables[f][u].view(bits), before[f][u].view(bits))
         assert torch.count_nonzero(dw.states[f][u]).item() == 0
+
+
+@pytest.mark.parametrize("kernel", ["1", "2"])
+@pytest.mark.parametrize("seed", range(100, 120))
+def test_random_configuration_on_the_other_segment_reduce_kernels(seed, kernel, monkeypatch):
+    """The same arbitrary configurations with the plan's switch set to the wave-per-tile walk
+    (taken where the widest row has 128 or 256 columns) and to the lane-group walk."""
+    monkeypatch.setenv("DMT_BWD_KERNEL", kernel)
+    check_bwd(random_workload(seed))
