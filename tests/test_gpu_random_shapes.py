@@ -116,3 +116,18 @@ def test_random_configuration_on_the_other_segment_reduce_kernels(seed, kernel, 
     (taken where the widest row has 128 or 256 columns) and to the lane-group walk."""
     monkeypatch.setenv("DMT_BWD_KERNEL", kernel)
     check_bwd(random_workload(seed))
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_configuration_with_many_rows(seed):
+    """Tables of up to 400 000 rows: ids need 17 to 19 bits, so the sort takes three passes, and
+    most lookups hit rows of their own."""
+    rng = np.random.default_rng([79, seed])
+    w = random_workload(300 + seed)
+    F = min(w.num_tables, 5)
+    w = dataclasses.replace(
+        w, rows=[int(np.exp(rng.uniform(np.log(70000), np.log(400000)))) for _ in range(F)],
+        dims=[min(d, 64) for d in w.dims[:F]], table_to_tower=[0] * F, tm_out=[128],
+        batch=int(rng.integers(200, 900)))
+    check_lookup(w)
+    check_bwd(w)
