@@ -97,6 +97,25 @@ def test_interaction_matches_the_oracle(F, N, B, T, dtype, sizes):
     np.testing.assert_allclose(np.diag(I), 1.0, atol=ATOL)
 
 
+@pytest.mark.parametrize("seed", range(20))
+def test_interaction_on_random_shapes(seed):
+    """Seeded arbitrary feature counts, widths, batches, tower counts and dtypes."""
+    rng = np.random.default_rng([93, seed])
+    dtype = ["bf16", "f16", "f32"][seed % 3]
+    F = int(np.exp(rng.uniform(0, np.log(320))))
+    N = int(rng.choice([8, 16, 24, 32, 64, 128, 256] if dtype == "f32" else [8, 16, 24, 32, 64, 128, 256, 512]))
+    if F * N > 40000:
+        N = 32
+    B = int(np.exp(rng.uniform(0, np.log(1500))))
+    T = int(rng.integers(1, min(F, 6) + 1))
+    w = _workload(F, N, T, B, dtype)
+    dw = DeviceWorkload(w)
+    R = wl.tp_embeddings(100 + seed, B, F, N, groups=max(1, F // 3))
+    enc = wl.encode(R.astype(np.float32), dtype)
+    I = _interaction(dw, to_device(_tower_major(w, enc), dtype))
+    _check(I, tp.tp_interaction(wl.decode(enc, dtype)), "seed %d F=%d N=%d B=%d T=%d %s" % (seed, F, N, B, T, dtype), dtype)
+
+
 def test_zero_embeddings_count_as_cosine_zero_and_signs_cancel():
     F, N, B = 6, 16, 8
     w = _workload(F, N, 2, B, "f32")
