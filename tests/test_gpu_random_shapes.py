@@ -131,3 +131,14 @@ def test_random_configuration_with_many_rows(seed):
         batch=int(rng.integers(200, 900)))
     check_lookup(w)
     check_bwd(w)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_configuration_with_random_lookup_switches(seed, monkeypatch):
+    """The lookup's launch shape (row slots per bag, bags a lane group pools in turn, the
+    threshold from which a bag goes to a whole wave) set at random instead of derived."""
+    rng = np.random.default_rng([80, seed])
+    monkeypatch.setenv("DMT_LOOKUP_R", str(int(rng.choice([0, 1, 2, 4, 8]))))
+    monkeypatch.setenv("DMT_LOOKUP_BPG", str(int(rng.choice([0, 1, 2, 3, 8, 16, 64]))))
+    monkeypatch.setenv("DMT_LOOKUP_LONG", str(int(rng.choice([-1, 0, 1, 5, 60]))))
+    check_lookup(random_workload(700 + seed))
