@@ -391,6 +391,16 @@ def test_random_medium_configurations(seed):
     check_tm_bwd(w, rtol=ftol, keep=bool(seed & 1))
 
 
+@pytest.mark.parametrize("switch", ["DMT_TM_BIG=0", "DMT_TM_FUSE=0", "DMT_TMB_KSPLIT=3", "DMT_TM_DIRECT=0"])
+@pytest.mark.parametrize("seed", range(10))
+def test_random_medium_configurations_on_the_other_kernel_choices(seed, switch, monkeypatch):
+    """The same towers with one of the plan's kernel choices turned the other way."""
+    name, value = switch.split("=")
+    monkeypatch.setenv(name, value)
+    w = _random_medium_config(seed)
+    check_tm_bwd(w, rtol=4e-2 if w.tm_cross_layers > 0 else 2e-2, keep=bool(seed & 1))
+
+
 def test_rejects_bad_arguments():
     w = wl.tiny()
     dw = DeviceWorkload(w)
