@@ -66,3 +66,28 @@ def test_noalloc_rejects_what_does_not_fit():
     with pytest.raises(dmt.DmtError) as e:
         dmt.dmt_tower_lookup_bwd_update_noalloc(dw.plan, idx, off, w.batch, grad, w.lr, w.eps)
     assert e.value.code == 4                        # DMT_ENOMEM
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_noalloc_on_random_configurations(seed):
+    """Arbitrary table sets: the scratch-array entry point and the workspace one leave the same
+    bits, whichever segment-reduce kernel the widths select."""
+    from test_gpu_random_shapes import random_workload
+    w = random_workload(900 + seed)
+    ref = DeviceWorkload(w, with_state=True)
+    new = DeviceWorkload(w, with_state=True)
+    dmt = ref.dmt
+    idx, off, grad = _inputs(w, 0)
+    nbytes = dmt.dmt_bwd_workspace_bytes(ref.plan, w.batch, len(idx))
+    if nbytes > dmt.dmt_bwd_noalloc_scratch_bytes():
+        pytest.skip("does not fit the scratch array")
+    d_idx, d_off = torch.from_numpy(idx).cuda(), torch.from_numpy(off).cuda()
+    d_grad = torch.from_numpy(grad).cuda()
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+    dmt.dmt_tower_lookup_bwd_update(ref.plan, d_idx, d_off, w.batch, d_grad, w.lr, w.eps, ws)
+    dmt.dmt_tower_lookup_bwd_update_noalloc(new.plan, d_idx, d_off, w.batch, d_grad, w.lr, w.eps)
+    torch.cuda.synchronize()
+    assert dmt.dmt_last_device_error(ref.plan) == -1 and dmt.dmt_last_device_error(new.plan) == -1
+    for f in range(w.num_tables):
+        assert torch.equal(_bits(ref.tables[f]), _bits(new.tables[f])), f
+        assert torch.equal(ref.states[f], new.states[f]), f
