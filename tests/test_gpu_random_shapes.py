@@ -142,3 +142,14 @@ def test_random_configuration_with_random_lookup_switches(seed, monkeypatch):
     monkeypatch.setenv("DMT_LOOKUP_BPG", str(int(rng.choice([0, 1, 2, 3, 8, 16, 64]))))
     monkeypatch.setenv("DMT_LOOKUP_LONG", str(int(rng.choice([-1, 0, 1, 5, 60]))))
     check_lookup(random_workload(700 + seed))
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_configuration_with_few_rows_and_many_lookups(seed):
+    """Tables of 1 to 60 rows under batches of up to 3000 samples: every row's run spans many
+    reduce tiles, so most of the work goes through the partial sums and the fix-up."""
+    rng = np.random.default_rng([81, seed])
+    w = random_workload(1200 + seed)
+    w = dataclasses.replace(w, rows=[int(np.exp(rng.uniform(0, np.log(60)))) for _ in w.rows],
+                            batch=int(rng.integers(500, 3000)), len_cap=max(w.len_cap, 40))
+    check_bwd(w)
