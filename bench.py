@@ -428,6 +428,18 @@ def run_workload(args, wname, traffic, primary):
     elapsed = time.perf_counter() - t0
     prof = dmt.dmt_profile_read(plan)
     ms_per_step = elapsed * 1e3 / args.steps
+    # the spread is reported over at least 50 steps: when fewer were asked for, more steps follow
+    # the timed region (they do not enter `value`), each with its own event pair
+    extra = max(0, 50 - args.steps)
+    ev += [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(extra)]
+    for i in range(args.steps, args.steps + extra):
+        ev[i][0].record()
+        step(args.warmup + i)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    if extra:
+        dmt.dmt_profile_read(plan)                  # (their kernel timings are dropped)
     per_step_ms = np.array([a.elapsed_time(b) for a, b in ev])
     assert dmt.dmt_last_device_error(plan) == -1
 
@@ -569,6 +581,7 @@ def run_workload(args, wname, traffic, primary):
         "ms_per_step_median": round(float(np.median(per_step_ms)), 4),
         "ms_per_step_p10": round(float(np.percentile(per_step_ms, 10)), 4),
         "ms_per_step_p90": round(float(np.percentile(per_step_ms, 90)), 4),
+        "ms_per_step_samples": int(len(per_step_ms)),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": DTYPE_TEXT[w.name], "data": "synthetic",
         "config": {"workload": NAMES[w.name], "tables": F, "rows": [min(w.rows), max(w.rows)],
