@@ -46,8 +46,11 @@ def test_partial_pools_match_the_oracle_and_add_up(name, nshards):
     w = {"tiny": wl.tiny(),
          "mid": wl.scaled(wl.mid(), max_rows=3000, batch=203, num_tables=16),
          "imbalanced": wl.scaled(wl.imbalanced(), max_rows=2000, batch=333, num_tables=12)}[name]
+    _check_partial_pools(w, nshards, np.random.default_rng(5), name)
+
+
+def _check_partial_pools(w, nshards, rng, name):
     F, B = w.num_tables, w.batch
-    rng = np.random.default_rng(5)
     host = wl.tables_host(w)
     idx, off = wl.lookup_batch(w)
     d_idx, d_off = torch.from_numpy(idx).cuda(), torch.from_numpy(off).cuda()
@@ -79,8 +82,23 @@ def test_partial_pools_match_the_oracle_and_add_up(name, nshards):
 def test_sharded_update_is_the_unsharded_update_row_by_row(name, nshards):
     w = {"tiny": wl.tiny(),
          "mid": wl.scaled(wl.mid(True), max_rows=4000, batch=203, num_tables=16)}[name]
+    _check_sharded_update(w, nshards, np.random.default_rng(6), name)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_configurations_in_random_shards(seed):
+    """Arbitrary table sets cut into 2 to 4 uneven row shards (some empty)."""
+    from test_gpu_random_shapes import random_workload
+    w = random_workload(1500 + seed)
+    if len(wl.lookup_batch(w)[0]) == 0:
+        pytest.skip("no lookups drawn")
+    nshards = 2 + seed % 3
+    _check_partial_pools(w, nshards, np.random.default_rng([7, seed]), w.name)
+    _check_sharded_update(w, nshards, np.random.default_rng([8, seed]), w.name)
+
+
+def _check_sharded_update(w, nshards, rng, name):
     F, B = w.num_tables, w.batch
-    rng = np.random.default_rng(6)
     host = wl.tables_host(w)
     idx, off = wl.lookup_batch(w)
     grad = wl.grad_pooled(w)
