@@ -68,8 +68,10 @@ def test_random_configuration_with_ids_outside_their_tables(seed):
     bad_pos = np.sort(rng.choice(len(idx), size=nbad, replace=False))
     bad = idx.copy()
     rows_of = np.asarray(w.rows)[bag_of[bad_pos] // B]
-    bad[bad_pos] = np.where(rng.random(nbad) < 0.5, rows_of + rng.integers(0, 5, nbad),
-                            -1 - rng.integers(0, 5, nbad)).astype(np.int32)
+    kind = rng.integers(0, 4, nbad)                  # just past the end, just below zero, the extremes
+    bad[bad_pos] = np.select([kind == 0, kind == 1, kind == 2],
+                             [rows_of + rng.integers(0, 5, nbad), -1 - rng.integers(0, 5, nbad),
+                              np.full(nbad, 2**31 - 1)], np.full(nbad, -2**31)).astype(np.int32)
     keep = np.ones(len(idx), bool)
     keep[bad_pos] = False
     clean_idx = np.ascontiguousarray(idx[keep])
