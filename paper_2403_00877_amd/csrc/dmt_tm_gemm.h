@@ -245,7 +245,9 @@ __global__ __launch_bounds__(kBlock, 2) void tm_gemm_mfma(const TmLaunch L) {
 // per CU, two LDS stages (147 KB of the CU's 160 KB): tile k+1 goes from registers
 // to LDS and the global loads of tile k+2 are issued before the MFMAs of tile k, so
 // a whole K step of matrix work covers the memory latency and one barrier per K
-// step suffices.
+// step suffices.  The MFMAs take the W fragment as their first operand, so the accumulators
+// hold the tile transposed: a lane owns one row and four consecutive columns per register
+// quad, which the epilogue parks in LDS with 16-byte stores.
 constexpr int LBM = 256, LBN = 256;
 constexpr int kBigThreads = 512;
 constexpr int kSuper = 32;                                  // tiles an XCD keeps resident (its CUs)
@@ -260,12 +262,15 @@ constexpr int kBigLdsBytes = 4 * kBigTileElems * 2;         // 2 stages x (A + B
 // terms): the operand tiles go from global memory straight into LDS (global_load_lds_dwordx4:
 // a wave's 64 lanes fill 1 KB of consecutive LDS, 16 bytes a lane), so the K loop has no
 // register stage and no LDS stores.  LDS rows are then 128 bytes with no padding; each lane
-// fetches the 16-byte column chunk (slot ^ row % 8) of its row, which puts the eight chunks
-// of eight consecutive rows into eight different bank groups, and the fragment reads apply
-// the same exclusive-or: conflict-free without padding.  The tile of step k + 1 is requested
-// at the start of step k into the other stage; every wave waits for its own requests before
-// the barrier that ends the step.  (The requests are written as inline assembly: told about
-// them, the compiler would make every LDS read of the current tile wait for the next tile's
+// fetches the 16-byte column chunk (slot ^ (row / 2) % 8) of its row and the fragment reads
+// apply the same exclusive-or.  A ds_read_b128 serves 16 lanes at a time from 64 banks; the
+// 16 rows they read then fall on 16 different 16-byte bank groups (rows 2 r and 2 r + 1 lie in
+// the two halves of one 256-byte bank row and share a slot, the eight pairs differ in it):
+// conflict-free without padding (with slot ^ row % 8, rows r and r + 8 collide and half the
+// LDS cycles are conflict cycles).  Tile kt + 2 is requested into the stage tile kt is being
+// read from, behind the barrier inside step kt; every wave waits for its own requests before
+// the next step's barrier.  (The requests are written as inline assembly: told about them,
+// the compiler would make every LDS read of the current tile wait for the next tile's
 // requests, since it cannot tell the two stages apart.)
 template <int DT, bool DOTS, int TAG = DMT_TM_TAG, bool KEEPZ = false, bool DIRECT = false>
 __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunch L) {
@@ -362,9 +367,10 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
   if constexpr (DIRECT) {
     constexpr int kStageEl = 2 * LBM * BK;         // one stage: A then W, 128-byte rows
     // instruction j of wave w fills LDS rows (j * 8 + w) * 8 .. + 7 of an operand; lane l holds
-    // slot l % 8 of row l / 8 there and fetches column chunk (l % 8) ^ (l / 8) of that row
+    // slot l % 8 of row r = (j * 8 + w) * 8 + l / 8 there and fetches column chunk
+    // (l % 8) ^ ((r / 2) % 8) of that row, (r / 2) % 8 being (w % 2) * 4 + l / 16
     const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) uint16_t*)lds;
-    const int chunk = (lane & 7) ^ (lane >> 3);
+    const int chunk = (lane & 7) ^ (((wave & 1) << 2) | (lane >> 4));
     uint32_t va[4], vb[4];                         // byte offsets of this lane's chunks at k = 0
 #pragma clang loop unroll(full)
     for (int j = 0; j < 4; ++j) {
@@ -386,32 +392,58 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
                      :: "s"(db), "v"(vb[j]), "s"(wk) : "memory");
       }
     };
-    // fragment reads: row (lane % 32) of a 32-row block, chunk 2 kk + lane / 32, swizzled
+    // fragment reads: row (lane % 32) of a 32-row block, chunk 2 kk + lane / 32, in slot
+    // chunk ^ ((lane % 32) / 2) % 8
     int sw[BK / 16];
 #pragma clang loop unroll(full)
-    for (int kk = 0; kk < BK / 16; ++kk) sw[kk] = (((kk * 2 + (lane >> 5)) ^ (lane & 7)) * 8);
+    for (int kk = 0; kk < BK / 16; ++kk)
+      sw[kk] = (((kk * 2 + (lane >> 5)) ^ ((lane >> 1) & 7)) * 8);
+    // Fragments are double-buffered in registers: the six reads of K slice kk + 1 are issued
+    // before the eight MFMAs of slice kk, so LDS latency hides behind matrix work of the same
+    // wave.  The barrier of a K step sits in front of its last slice's MFMAs: behind it come
+    // the requests for tile kt + 2 (every wave has read the whole current stage by then) and
+    // the first reads of tile kt + 1, and the last slice's MFMAs cover both.
+    uint4 fa[2][4], fb[2][2];
+    auto read_frag = [&](int buf, int stage, int kk) __attribute__((always_inline)) {
+      const uint16_t* ap = lds + stage * kStageEl + (wm * 128 + (lane & 31)) * BK + sw[kk];
+      const uint16_t* bp = lds + stage * kStageEl + LBM * BK + (wn * 64 + (lane & 31)) * BK + sw[kk];
+#pragma clang loop unroll(full)
+      for (int i = 0; i < 4; ++i) fa[buf][i] = *(const uint4*)(ap + i * 32 * BK);
+#pragma clang loop unroll(full)
+      for (int j = 0; j < 2; ++j) fb[buf][j] = *(const uint4*)(bp + j * 32 * BK);
+    };
     request_tile(0, 0);
     __builtin_amdgcn_s_waitcnt(0x0f70);            // vmcnt(0): this wave's requests have landed
     __syncthreads();
+    if (nk > 1) request_tile(1, 1);
+    read_frag(0, 0, 0);
     for (int kt = 0; kt < nk; ++kt) {
       const int cur = kt & 1;
-      if (kt + 1 < nk) request_tile(cur ^ 1, kt + 1);
-      const uint16_t* ap = lds + cur * kStageEl + (wm * 128 + (lane & 31)) * BK;
-      const uint16_t* bp = lds + cur * kStageEl + LBM * BK + (wn * 64 + (lane & 31)) * BK;
 #pragma clang loop unroll(full)
       for (int kk = 0; kk < BK / 16; ++kk) {
-        uint4 a[4], b[2];
-#pragma clang loop unroll(full)
-        for (int i = 0; i < 4; ++i) a[i] = *(const uint4*)(ap + i * 32 * BK + sw[kk]);
-#pragma clang loop unroll(full)
-        for (int j = 0; j < 2; ++j) b[j] = *(const uint4*)(bp + j * 32 * BK + sw[kk]);
+        if (kk + 1 < BK / 16) {
+          read_frag((kk + 1) & 1, cur, kk + 1);
+        } else {
+          __builtin_amdgcn_s_waitcnt(0x0f70);
+          __syncthreads();
+          if (kt + 2 < nk) request_tile(cur, kt + 2);
+          if (kt + 1 < nk) read_frag(0, cur ^ 1, 0);
+        }
 #pragma clang loop unroll(full)
         for (int i = 0; i < 4; ++i)
 #pragma clang loop unroll(full)
-          for (int j = 0; j < 2; ++j) acc[i][j] = mfma32<DT>(a[i], b[j], acc[i][j]);
+          for (int j = 0; j < 2; ++j) acc[i][j] = mfma32<DT>(fb[kk & 1][j], fa[kk & 1][i], acc[i][j]);
+        // one LDS read, one MFMA, ...: left alone, the scheduler puts each read right in front
+        // of the MFMA that needs it, to save registers
+        if (kk + 1 < BK / 16) {
+#pragma clang loop unroll(full)
+          for (int q = 0; q < 6; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          }
+          __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        }
       }
-      __builtin_amdgcn_s_waitcnt(0x0f70);
-      __syncthreads();
     }
   } else {
   load_tile(0);
@@ -485,19 +517,18 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
 #pragma clang loop unroll(full)
       for (int i = 0; i < 4; ++i)
 #pragma clang loop unroll(full)
-        for (int j = 0; j < 2; ++j) acc[i][j] = mfma32<DT>(a[i], b[j], acc[i][j]);
+        for (int j = 0; j < 2; ++j) acc[i][j] = mfma32<DT>(b[j], a[i], acc[i][j]);
     }
     __syncthreads();
   }
   }
-
   // Epilogue through LDS, one 128-row half of the tile at a time: the waves that own the half
-  // park their float32 accumulators (a lane holds one column of 16 rows: poor for global
-  // memory), then all 512 threads walk the half in 8-column pieces, so bias, x0, x_l and the
-  // output move as 16-byte accesses.
+  // park their float32 accumulators (a lane holds four consecutive columns of one row per
+  // register quad: too narrow for global memory), then all 512 threads walk the half in
+  // 8-column pieces, so bias, x0, x_l and the output move as 16-byte accesses.
   const int epi = G.epi;
   float* stage = (float*)lds;
-  constexpr int kStageStride = LBN + 8;            // 4*stride % 64 == 32: conflict-free parking
+  constexpr int kStageStride = LBN + 4;            // rows 4 banks apart: 16 lanes' float4 stores spread over all 64
   const bool vec_ok =
       G.ldc % 8 == 0 && n0 + LBN <= N &&
       (((uintptr_t)G.C | (uintptr_t)G.bias | (uintptr_t)G.U) & 15) == 0 &&
@@ -511,10 +542,16 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
   constexpr int kChunks = 128 * (LBN / 8) / kBigThreads;
   // (byte offsets from the operand's base fit 32 bits: one register per address instead of two)
   const bool fast_cross = epi == EPI_CROSS && vec_ok && (int64_t)M * G.ldx < (1LL << 31) &&
-                          (int64_t)M * ldxl < (1LL << 31);
+                          (int64_t)M * ldxl < (1LL << 31) && (int64_t)M * G.ldc < (1LL << 31);
   const bool fast_add = epi == EPI_F32_ADD && n0 + LBN <= N && G.ldc % 4 == 0 &&
                         (int64_t)M * G.ldc < (1LL << 30) &&
                         (((uintptr_t)((float*)G.C + slice * G.cstride)) & 15) == 0;
+  // bias / bias + ReLU / plain float32 tiles walk the same unrolled loop (nothing to prefetch)
+  const bool fast_plain = vec_ok && epi <= EPI_BIAS_RELU && (int64_t)M * G.ldc < (1LL << 31);
+  const bool fast_f32 = epi == EPI_F32 && n0 + LBN <= N && G.ldc % 4 == 0 &&
+                        (int64_t)M * G.ldc < (1LL << 30) &&
+                        (((uintptr_t)((float*)G.C + slice * G.cstride)) & 15) == 0;
+  const bool fast = fast_cross || fast_add || fast_plain || fast_f32;
   const char* const pre_a = fast_cross ? (const char*)G.X0 : (const char*)((float*)G.C + slice * G.cstride);
   const char* const pre_b = fast_cross ? (const char*)XLp : pre_a + 16;
   const uint32_t pre_lda = fast_cross ? (uint32_t)G.ldx * 2u : (uint32_t)G.ldc * 4u;   // row pitch, bytes
@@ -539,42 +576,57 @@ __global__ __launch_bounds__(kBigThreads, 1) void tm_gemm_mfma_256(const TmLaunc
 #pragma clang loop unroll(full)
         for (int i = 0; i < 4; ++i)
 #pragma clang loop unroll(full)
-          for (int v = 0; v < 16; ++v) {
-            const int r = i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-            stage[r * kStageStride + wn * 64 + j * 32 + (lane & 31)] = acc[i][j][v];
-          }
+          for (int g = 0; g < 4; ++g)
+            *(float4*)(stage + (i * 32 + (lane & 31)) * kStageStride + wn * 64 + j * 32 + g * 8 + (lane >> 5) * 4) =
+                make_float4(acc[i][j][g * 4], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]);
     }
     __syncthreads();
-    if (fast_cross || fast_add) {
+    if (fast) {
+      // chunk u of half h is row h * 128 + u * 16 + tid / 32 of the tile, the thread's own 8
+      // columns: one 32-bit byte offset from C (and U), advanced by a uniform step
+      const int r0 = tid / (LBN / 8), cc = (tid % (LBN / 8)) * 8;
+      const uint32_t esz = epi >= EPI_F32 ? 4u : 2u;
+      char* const cbase = epi >= EPI_F32 ? (char*)((float*)G.C + slice * G.cstride) : (char*)G.C;
+      const uint32_t ostep = 16u * (uint32_t)G.ldc * esz;
+      uint32_t off = ((uint32_t)(m0 + h * 128 + r0) * (uint32_t)G.ldc + (uint32_t)(n0 + cc)) * esz;
+      // a thread's chunks all lie in one 8-column piece of the tile: one bias load serves them
+      uint4 bias_raw = make_uint4(0, 0, 0, 0);
+      if ((fast_cross || fast_plain) && G.bias) bias_raw = *(const uint4*)((const uint16_t*)G.bias + n0 + cc);
 #pragma clang loop unroll(full)
-      for (int u = 0; u < kChunks; ++u) {
-        const int c = tid + u * kBigThreads;
-        const int r = c / (LBN / 8), cc = (c % (LBN / 8)) * 8;
-        const int m = m0 + h * 128 + r, n = n0 + cc;
-        if (m >= M) continue;
+      for (int u = 0; u < kChunks; ++u, off += ostep) {
+        const int r = r0 + u * 16;
+        if (m0 + h * 128 + r >= M) continue;
         float y[8];
         const float4 s0 = *(const float4*)(stage + r * kStageStride + cc);
         const float4 s1 = *(const float4*)(stage + r * kStageStride + cc + 4);
         y[0] = s0.x; y[1] = s0.y; y[2] = s0.z; y[3] = s0.w;
         y[4] = s1.x; y[5] = s1.y; y[6] = s1.z; y[7] = s1.w;
         if (fast_add) {
-          float* c0 = (float*)G.C + slice * G.cstride + (int64_t)m * G.ldc + n;
           const float4 p0 = __builtin_bit_cast(float4, pa[u]), p1 = __builtin_bit_cast(float4, pb[u]);
-          *(float4*)c0 = make_float4(y[0] + p0.x, y[1] + p0.y, y[2] + p0.z, y[3] + p0.w);
-          *(float4*)(c0 + 4) = make_float4(y[4] + p1.x, y[5] + p1.y, y[6] + p1.z, y[7] + p1.w);
+          *(float4*)(cbase + off) = make_float4(y[0] + p0.x, y[1] + p0.y, y[2] + p0.z, y[3] + p0.w);
+          *(float4*)(cbase + off + 16) = make_float4(y[4] + p1.x, y[5] + p1.y, y[6] + p1.z, y[7] + p1.w);
+        } else if (fast_f32) {
+          *(float4*)(cbase + off) = s0;
+          *(float4*)(cbase + off + 16) = s1;
         } else {
-          float bv[8], xv[8], lv[8];
-          if (G.bias) {
-            dmt::decode_chunk<DT>(bv, *(const uint4*)((const uint16_t*)G.bias + n));
+          float bv[8];
+          dmt::decode_chunk<DT>(bv, bias_raw);
 #pragma clang loop unroll(full)
-            for (int q = 0; q < 8; ++q) y[q] += bv[q];
+          for (int q = 0; q < 8; ++q) y[q] += bv[q];
+          if (fast_plain) {
+            if (epi == EPI_BIAS_RELU) {
+#pragma clang loop unroll(full)
+              for (int q = 0; q < 8; ++q) y[q] = y[q] > 0.f ? y[q] : 0.f;
+            }
+          } else {
+            float xv[8], lv[8];
+            if (G.U) dmt::store_chunk<DT, 8>((char*)G.U + off, 0, y);
+            dmt::decode_chunk<DT>(xv, pa[u]);
+            dmt::decode_chunk<DT>(lv, pb[u]);
+#pragma clang loop unroll(full)
+            for (int q = 0; q < 8; ++q) y[q] = xv[q] * y[q] + lv[q];
           }
-          if (G.U) dmt::store_chunk<DT, 8>(G.U, (int64_t)m * G.ldc + n, y);
-          dmt::decode_chunk<DT>(xv, pa[u]);
-          dmt::decode_chunk<DT>(lv, pb[u]);
-#pragma clang loop unroll(full)
-          for (int q = 0; q < 8; ++q) y[q] = xv[q] * y[q] + lv[q];
-          dmt::store_chunk<DT, 8>(G.C, (int64_t)m * G.ldc + n, y);
+          dmt::store_chunk<DT, 8>(cbase + off, 0, y);
         }
       }
       __syncthreads();
@@ -878,7 +930,7 @@ void launch_groups(const dmt_plan* p, std::vector<TmGroup>& groups, hipStream_t 
         for (int i = 0; i < L.ngroups; ++i) {
           const TmGroup& g = L.g[i];
           const int kk = g.ksplit > 1 ? g.klen : g.K1;
-          direct = direct && g.M % LBM == 0 && g.N % LBN == 0 && kk % BK == 0 && g.K1 % BK == 0 &&
+          direct = direct && g.M % LBM == 0 && g.N % LBN == 0 && kk >= BK && kk % BK == 0 && g.K1 % BK == 0 &&
                    g.lda1 % 8 == 0 && g.ldw % 8 == 0 &&
                    (((uintptr_t)g.A1 | (uintptr_t)g.W) & 15) == 0;
         }
