@@ -205,7 +205,9 @@ __global__ __launch_bounds__(kBlock) void tmb_transpose16(const TmbLaunch L) {
       const int c = c0 + v;
       uint4 x = make_uint4(0, 0, 0, 0);
       if (r < R && c < C) x = *(const uint4*)(src + r * lds + c);
-      *(uint4*)&tile[i][v] = x;
+      // chunk j of row i sits in slot j ^ (i / 8) % 8: the eight rows 8 apart that one read
+      // instruction below touches then fall on eight different 16-byte bank groups
+      *(uint4*)&tile[i][v ^ (i & 56)] = x;
     }
     __syncthreads();
 #pragma unroll
@@ -217,7 +219,7 @@ __global__ __launch_bounds__(kBlock) void tmb_transpose16(const TmbLaunch L) {
         uint32_t w[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k)
-          w[k] = tile[v + 2 * k][i] | ((uint32_t)tile[v + 2 * k + 1][i] << 16);
+          w[k] = tile[v + 2 * k][i ^ v] | ((uint32_t)tile[v + 2 * k + 1][i ^ v] << 16);
         *(uint4*)(dst + (int64_t)c * ldd + r) = make_uint4(w[0], w[1], w[2], w[3]);
       }
     }
