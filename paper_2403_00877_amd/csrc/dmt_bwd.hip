@@ -1080,14 +1080,21 @@ constexpr int kLeanBatch = 8;                    // gradient slices requested to
 static_assert(kLeanBatch <= kLeanQueue && 64 % kLeanBatch == 0,
               "every record of a batch may end a run, and all of them must fit the emptied ring");
 
+// One wave per block: the waves of a block share nothing, and a block's slots are only handed
+// on when its slowest wave is done.  Tile times spread widely (per-tile timestamps on Mid:
+// 27 us at the 10th percentile, 73 at the 90th), so with four waves a block a third of the
+// wave slots sat waiting for a sibling.  Filling them makes every tile slower instead (mean
+// 48 -> 55 us: the gathers, not the number of waves, bound the kernel) and the launch 1 %
+// faster.
+constexpr int kLeanBlock = 64;
 template <int TD>
-__global__ __launch_bounds__(kBlock) void bwd_reduce_update_lean(
+__global__ __launch_bounds__(kLeanBlock) void bwd_reduce_update_lean(
     const DmtTableMeta* __restrict__ meta, const uint64_t* __restrict__ pk, int64_t nnz, uint32_t B,
     uint32_t bag_mul, uint32_t bag_shift, uint32_t F, const float* __restrict__ grad,
     float* __restrict__ partials, int Dmax, int64_t ntiles, int64_t blocks_per_xcd, float lr,
     float eps, const unsigned long long* __restrict__ err_offsets) {
   if (*err_offsets != ~0ULL) return;              // malformed offsets: the records mean nothing
-  constexpr int NW = kBlock / 64;
+  constexpr int NW = kLeanBlock / 64;
   constexpr int eb = TD == DMT_F32 ? 4 : 2;
   using Chunk = std::conditional_t<TD == DMT_F32, float4, uint4>;
   constexpr int NC = TD == DMT_F32 ? 2 : 1;
@@ -1447,11 +1454,11 @@ void bag_divider(uint32_t B, uint32_t& mul, uint32_t& shift) {
 
 template <int TD>
 void launch_reduce_lean(const ReduceCall& c) {
-  constexpr int kWavesPerBlock = kBlock / 64;
+  constexpr int kWavesPerBlock = kLeanBlock / 64;
   const int64_t per_xcd = ((c.w->ntiles + kWavesPerBlock - 1) / kWavesPerBlock + 7) / 8;
   uint32_t mul, shift;
   bag_divider((uint32_t)c.B, mul, shift);
-  timed_launch(c.plan, DMT_K_BWD_REDUCE_UPDATE, c.s, bwd_reduce_update_lean<TD>, per_xcd * 8, kBlock,
+  timed_launch(c.plan, DMT_K_BWD_REDUCE_UPDATE, c.s, bwd_reduce_update_lean<TD>, per_xcd * 8, kLeanBlock,
                c.plan->d_meta, c.sorted, c.nnz, (uint32_t)c.B, mul, shift, (uint32_t)c.plan->F, c.grad,
                c.w->partials, c.plan->max_dim, c.w->ntiles, per_xcd, c.lr, c.eps,
                c.plan->d_error + 1);
