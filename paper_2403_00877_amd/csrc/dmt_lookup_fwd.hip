@@ -21,8 +21,11 @@
 
 namespace {
 
-constexpr int kBlock = 256;
-constexpr int kStagedBags = 2048;  // most bags of one block whose offsets are staged in LDS
+// One wave per block: a block's lane groups share nothing but the staged offsets, and with
+// several waves a block its wave slots are only handed on when the wave with the longest bags
+// is done (measured against 256 threads: Mid and Large 2.5 - 3 % shorter, Imbalanced 3 - 4 %).
+constexpr int kBlock = 64;
+constexpr int kStagedBags = kBlock * 8;  // most bags of one block whose offsets are staged in LDS
 #ifndef DMT_LOOKUP_UNROLL
 #define DMT_LOOKUP_UNROLL 4
 #endif
