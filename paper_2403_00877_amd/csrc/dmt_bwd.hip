@@ -1319,15 +1319,18 @@ __device__ __forceinline__ uint32_t table_of(const int64_t* __restrict__ row_bas
 
 // Rows whose run crosses tile boundaries: the group of the tile where the run
 // starts adds the pieces in tile order and applies the update.
+// one wave per block: groups are independent, and the group at the head of a long run works
+// far longer than its neighbours (50.7 -> 47.4 us on Mid)
+constexpr int kFixBlock = 64;
 template <int TD>
-__global__ __launch_bounds__(kBlock) void bwd_fixup_update(
+__global__ __launch_bounds__(kFixBlock) void bwd_fixup_update(
     const DmtTableMeta* __restrict__ meta, uint32_t B, uint32_t nbags,
     const uint64_t* __restrict__ pk, int64_t nnz, uint32_t total_rows,
     const float* __restrict__ partials, int Dmax, int log2_gl, int64_t ntiles, float lr, float eps,
     const unsigned long long* __restrict__ err_offsets) {
   if (*err_offsets != ~0ULL) return;
   const int GL = 1 << log2_gl;
-  const int64_t t0 = (int64_t)blockIdx.x * (kBlock >> log2_gl) + (threadIdx.x >> log2_gl);
+  const int64_t t0 = (int64_t)blockIdx.x * (kFixBlock >> log2_gl) + (threadIdx.x >> log2_gl);
   if (t0 >= ntiles - 1) return;
   const int gl = threadIdx.x & (GL - 1);
   const int64_t p0 = t0 * kReduceTile, p1 = p0 + kReduceTile;    // p1 < nnz here
@@ -1375,13 +1378,13 @@ __global__ __launch_bounds__(kBlock) void bwd_fixup_update(
 
 // ------------------------------------------------------------- parity exports
 
-__global__ __launch_bounds__(kBlock) void bwd_export(
+__global__ __launch_bounds__(kFixBlock) void bwd_export(
     const int64_t* __restrict__ row_base, int F, const uint64_t* __restrict__ pk, int64_t nnz,
     uint32_t total_rows, const uint32_t* __restrict__ seg_off,
     const uint32_t* __restrict__ num_unique_in, int64_t* __restrict__ sorted_keys,
     int32_t* __restrict__ sorted_bag, int64_t* __restrict__ unique_keys,
     int64_t* __restrict__ seg_off_out, int64_t* __restrict__ num_unique) {
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int64_t i = (int64_t)blockIdx.x * kFixBlock + threadIdx.x;
   const uint32_t U = nnz > 0 ? num_unique_in[0] : 0;   // inert keys were not counted as heads
   if (i == 0 && num_unique) num_unique[0] = U;
   if (i < nnz) {
@@ -1498,8 +1501,8 @@ void launch_reduce_and_fixup(const ReduceCall& c) {
       default: launch_reduce_grouped<TD, 6>(c); break;
     }
   }
-  const int64_t blocks = (c.w->ntiles + (kBlock >> log2_gl) - 1) / (kBlock >> log2_gl);
-  timed_launch(c.plan, DMT_K_BWD_FIXUP, c.s, bwd_fixup_update<TD>, blocks, kBlock, c.plan->d_meta,
+  const int64_t blocks = (c.w->ntiles + (kFixBlock >> log2_gl) - 1) / (kFixBlock >> log2_gl);
+  timed_launch(c.plan, DMT_K_BWD_FIXUP, c.s, bwd_fixup_update<TD>, blocks, kFixBlock, c.plan->d_meta,
                (uint32_t)c.B, c.nbags, c.sorted, c.nnz, c.total_rows, c.w->partials, max_dim,
                log2_gl, c.w->ntiles, c.lr, c.eps, c.plan->d_error + 1);
 }
