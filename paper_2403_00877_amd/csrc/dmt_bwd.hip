@@ -1378,13 +1378,13 @@ __global__ __launch_bounds__(kFixBlock) void bwd_fixup_update(
 
 // ------------------------------------------------------------- parity exports
 
-__global__ __launch_bounds__(kFixBlock) void bwd_export(
+__global__ __launch_bounds__(kBlock) void bwd_export(
     const int64_t* __restrict__ row_base, int F, const uint64_t* __restrict__ pk, int64_t nnz,
     uint32_t total_rows, const uint32_t* __restrict__ seg_off,
     const uint32_t* __restrict__ num_unique_in, int64_t* __restrict__ sorted_keys,
     int32_t* __restrict__ sorted_bag, int64_t* __restrict__ unique_keys,
     int64_t* __restrict__ seg_off_out, int64_t* __restrict__ num_unique) {
-  const int64_t i = (int64_t)blockIdx.x * kFixBlock + threadIdx.x;
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   const uint32_t U = nnz > 0 ? num_unique_in[0] : 0;   // inert keys were not counted as heads
   if (i == 0 && num_unique) num_unique[0] = U;
   if (i < nnz) {
